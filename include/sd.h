@@ -1,0 +1,178 @@
+/*
+ * sd.h -- C ABI of the MI355X draft-generation library for SuffixDecoding
+ * (arxiv 2411.04975).
+ *
+ * The library keeps two suffix indexes in device memory -- a GLOBAL one over
+ * previously generated outputs and a PER-REQUEST one over each in-flight
+ * request's prompt + output (Section 3, "Suffix Tree Construction") -- and,
+ * for a batch of requests, produces one speculation tree per request
+ * (Algorithm 1, GenerateCandidateTree) plus the greedy acceptance walk over a
+ * verified tree (Section 2, "Speculative Decoding", step 2).
+ *
+ * Conventions
+ *  - Every pointer named d_* is a DEVICE pointer owned by the caller (for
+ *    example the storage of a torch tensor).  The library reads or writes it
+ *    only through work enqueued on `hip_stream` by that call and never frees
+ *    it.  Pointers without the prefix are host pointers.
+ *  - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *    sd_index_build, sd_index_append, sd_speculate and sd_accept only ENQUEUE
+ *    work; they do not synchronise the device.  sd_create, sd_destroy and
+ *    sd_get_stats synchronise.
+ *  - Errors the host can see (bad arguments, sizes beyond the configured
+ *    capacity) return a code at once and enqueue nothing.  Conditions only the
+ *    device can see (a token outside [0, vocab), a slot id out of range, a
+ *    context that would outgrow max_ctx_tokens) raise a sticky device flag; the
+ *    offending sequence is skipped, and the flag is reported by sd_get_stats.
+ *  - One sd_ctx belongs to one device; calls on one sd_ctx must not overlap.
+ *  - Tokens are int32 in [0, vocab).  Sequence i of a (tokens, offsets) pair
+ *    is tokens[offsets[i] .. offsets[i+1]).
+ *
+ * Readings of points the paper leaves open are part of this contract:
+ *  - Depth bound D: the indexes hold every suffix cut to its first D tokens, so
+ *    a path of D tokens has no continuation.  Requires 1 <= P < D.
+ *  - Suffixes never run across a document (global) or past the end of the
+ *    context (request).  COUNT is the number of occurrences by position.
+ *  - C(N) = COUNT(N) / COUNT(PARENT(N)); D(N) is the product of C along the
+ *    path from the matched node, computed in binary64 as
+ *    parent_score * ((double)count_child / (double)count_parent).
+ *  - The frontier of ExpandSpeculationTree is every not-yet-added child of any
+ *    node already in the tree; ties go to the lower token id, then to the
+ *    lower parent index.  A candidate scoring below min_score is never added.
+ *  - The matched node N_p is not a draft node: sizes and SCORE count draft
+ *    nodes only, at most floor(alpha * p) of them.
+ *  - Between candidate trees a strictly greater SCORE wins, scanning the
+ *    global index for p = 1..P first and the per-request index after it.
+ */
+#ifndef SD_H
+#define SD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sd_ctx sd_ctx; /* opaque; owns all index and scratch memory */
+
+typedef enum {
+    SD_OK = 0,
+    SD_ERR_INVALID_ARG = 1,
+    SD_ERR_OOM = 2,
+    SD_ERR_HIP = 3,
+    SD_ERR_CAPACITY = 4,
+    SD_ERR_STATE = 5
+} sd_status;
+
+/* Limits checked by sd_create: 1 <= P < D <= 255, P <= 64, alpha > 0,
+ * 1 <= floor(alpha*P) <= 256, 0 <= min_score <= 1, 1 <= vocab <= 2^24,
+ * max_batch_slots >= 1, max_ctx_tokens >= 1, 0 <= max_global_tokens (documents
+ * included, each document costs one extra position) < 2^31 - 4096. */
+typedef struct {
+    int32_t vocab;
+    int32_t D;               /* depth bound of both indexes                         */
+    int32_t P;               /* longest pattern tried (Algorithm 1, "max pattern size") */
+    double alpha;            /* MAX_SPEC = alpha * p (Section 3, "Adaptive Speculation Lengths") */
+    double min_score;        /* per-node cut-off on D(N)                            */
+    int32_t max_batch_slots; /* request slots 0 .. max_batch_slots-1                */
+    int32_t max_ctx_tokens;  /* per slot, growth by sd_index_append included        */
+    int64_t max_global_tokens;
+    int32_t device;          /* HIP device ordinal                                  */
+} sd_config;
+
+typedef enum { SD_SCOPE_GLOBAL = 0, SD_SCOPE_REQUESTS = 1 } sd_scope;
+
+/* Speculation trees of a batch, all arrays caller-allocated on the device.
+ * Request b owns entries [b*max_nodes, (b+1)*max_nodes) of the per-node arrays.
+ * Draft node j of a request has token d_tokens[j], parent d_parents[j] (an
+ * earlier node index, or -1 for a child of the matched node) and score
+ * d_scores[j] = D(N); nodes appear in the order the greedy expansion added them.
+ * Entries past d_n_nodes[b] are written as -1 / -1 / 0.0 so whole buffers can
+ * be compared.  d_match_len[b] is the winning pattern length p (0 if none),
+ * d_source[b] is 0 (global index), 1 (per-request index) or -1 (no tree),
+ * d_tree_score[b] is SCORE = sum of node scores in node order (0.0 if none). */
+typedef struct {
+    int32_t *d_n_nodes;   /* [batch]             */
+    int32_t *d_tokens;    /* [batch * max_nodes] */
+    int32_t *d_parents;   /* [batch * max_nodes] */
+    int32_t *d_match_len; /* [batch]             */
+    int32_t *d_source;    /* [batch]             */
+    double *d_scores;     /* [batch * max_nodes] */
+    double *d_tree_score; /* [batch]             */
+    int32_t max_nodes;    /* >= floor(alpha * P) */
+} sd_trees;
+
+typedef struct {
+    int64_t global_tokens;     /* tokens in the global index                    */
+    int64_t global_docs;
+    int32_t err_bad_token;     /* sticky: a token outside [0, vocab) was seen   */
+    int32_t err_bad_slot;      /* sticky: a slot id outside the configured range */
+    int32_t err_ctx_overflow;  /* sticky: a context would exceed max_ctx_tokens */
+    int32_t reserved;
+    int64_t index_bytes;       /* device bytes held by the global index         */
+    int64_t scratch_bytes;     /* device bytes of scratch held by the context   */
+} sd_stats;
+
+/* Validate the configuration, select `device`, allocate index capacity and
+ * scratch.  On failure *out is NULL. */
+sd_status sd_create(const sd_config *cfg, sd_ctx **out);
+void sd_destroy(sd_ctx *ctx);
+/* Text of the last host-side error of this context (owned by the context). */
+const char *sd_last_error(const sd_ctx *ctx);
+
+/* Build an index (Section 3, "Suffix Tree Construction").
+ * SD_SCOPE_GLOBAL: the n_seq sequences are the documents of the corpus of
+ *   previous outputs; the global index is replaced.  d_slot_ids is ignored.
+ *   n_seq may be 0 (empty index).  Total tokens + n_seq must not exceed
+ *   max_global_tokens (SD_ERR_CAPACITY).  `n_tokens` is the total token count
+ *   (= offsets[n_seq], passed by the host so that no device read is needed).
+ * SD_SCOPE_REQUESTS: sequence i becomes the whole context x_{1:t} of slot
+ *   d_slot_ids[i], replacing what the slot held; other slots are untouched.
+ *   Slot ids in one call must be distinct.
+ * d_seq_offsets is int64[n_seq + 1] on the device. */
+sd_status sd_index_build(sd_ctx *ctx, sd_scope scope, const int32_t *d_slot_ids,
+                         const int32_t *d_tokens, const int64_t *d_seq_offsets, int32_t n_seq,
+                         int64_t n_tokens, void *hip_stream);
+
+/* Extend the contexts of n_slots distinct slots: slot d_slot_ids[i] receives
+ * d_new_tokens[d_new_offsets[i] .. d_new_offsets[i+1]) (int32 offsets, device).
+ * Afterwards the per-request index equals the one a fresh build over the longer
+ * context would give (the online update of Section 3). */
+sd_status sd_index_append(sd_ctx *ctx, const int32_t *d_slot_ids, const int32_t *d_new_tokens,
+                          const int32_t *d_new_offsets, int32_t n_slots, void *hip_stream);
+
+/* GenerateCandidateTree (Algorithm 1) for `batch` requests: request b uses the
+ * current context of slot d_slot_ids[b].  For every pattern length p = 1..P
+ * and both indexes it matches the last p context tokens (MatchPattern), grows
+ * a tree of at most floor(alpha*p) nodes greedily by D(N)
+ * (ExpandSpeculationTree) and keeps the tree with the highest SCORE.
+ * batch <= max_batch_slots; out.max_nodes >= floor(alpha*P). */
+sd_status sd_speculate(sd_ctx *ctx, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
+                       void *hip_stream);
+
+/* Greedy verification walk (Section 2, "accepting tokens up to the first
+ * discrepancy"; Section 4.1, simulated verifier).  d_target_tokens is
+ * int32[batch * (max_nodes + 1)]: entry 0 of a request is the target model's
+ * token after the context (at the tree root), entry 1+j its token after draft
+ * node j.  From the root, the child whose token equals the target at the
+ * current node is accepted and becomes the current node, until no child does.
+ * d_accept_len[b] = number of accepted nodes, d_accept_path[b*max_nodes ..]
+ * their indices in order (rest -1), d_bonus[b] = the target token at the last
+ * accepted node (the token the target model contributes itself). */
+sd_status sd_accept(sd_ctx *ctx, sd_trees trees, int32_t batch, const int32_t *d_target_tokens,
+                    int32_t *d_accept_len, int32_t *d_accept_path, int32_t *d_bonus,
+                    void *hip_stream);
+
+/* Synchronises the device and copies counters and sticky flags to the host. */
+sd_status sd_get_stats(sd_ctx *ctx, sd_stats *host_out);
+
+/* Test hook: synchronises, then copies the global index to host buffers:
+ * the laid-out text (documents back to back, -1 after each) and the suffix
+ * array over it, `*n_positions` entries each (tokens + documents).  Returns
+ * SD_ERR_CAPACITY if `cap` entries are too few (only *n_positions is set). */
+sd_status sd_debug_read_global(sd_ctx *ctx, int32_t *h_text, int32_t *h_sa, int64_t cap,
+                               int64_t *n_positions);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SD_H */

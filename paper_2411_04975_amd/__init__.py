@@ -1,0 +1,10 @@
+"""MI355X-native draft generation for SuffixDecoding (arxiv 2411.04975).
+
+The work is done by hand-written HIP kernels behind the C ABI declared in
+include/sd.h; this package is a thin ctypes binding with the same call names.
+There is no CPU fallback: importing the binding without the built shared
+object raises.
+"""
+from .binding import (SD_SCOPE_GLOBAL, SD_SCOPE_REQUESTS, SdError, Trees, lib_path,  # noqa: F401
+                      sd_accept, sd_create, sd_debug_read_global, sd_destroy, sd_get_stats, sd_index_append,
+                      sd_index_build, sd_speculate)

@@ -1,0 +1,247 @@
+// Index construction (Section 3, "Suffix Tree Construction").
+//
+// Global index: instead of a pointer tree the library keeps a suffix array.  The documents
+// are laid out in one text with an end marker after each; all positions are sorted by the
+// suffix that starts there, compared on at least its first D tokens, with the end marker
+// below every token.  A path w of the depth-bounded suffix tree then is the contiguous range
+// of suffixes that start with w: COUNT(w) is the width of the range, its children are the
+// runs of equal token at offset |w| inside it, and suffixes that stop at w sit first in it.
+//
+// The sort is prefix doubling: positions are first ordered by their leading two tokens, then
+// each round orders them by the pair (rank of the first h tokens, rank of the next h tokens),
+// which doubles the compared length until it reaches D.  Ranks are group numbers of the
+// previous round, so every round is one radix sort of 2*ceil(log2 N) bit keys.
+//
+// Per-request index: the contexts are kept as plain token rows (one per slot) followed by end
+// markers; occurrences are found by scanning the row at speculation time, so building is a
+// copy and appending writes the new tokens behind the old ones.
+#include "sd_internal.h"
+
+namespace {
+
+constexpr int TB = 256;
+
+// text[i + doc(i)] = tokens[i]: document j is shifted right by j to make room for one end
+// marker after each earlier document.
+__global__ __launch_bounds__(TB) void k_layout_text(const int32_t *__restrict__ tokens,
+                                                    const int64_t *__restrict__ offs, int32_t n_seq,
+                                                    int64_t n_tokens, int32_t *__restrict__ text,
+                                                    int32_t vocab, int32_t *err) {
+    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (i >= n_tokens) return;
+    // largest j with offs[j] <= i
+    int32_t lo = 0, hi = n_seq;  // answer in [lo, hi)
+    while (hi - lo > 1) {
+        int32_t mid = (lo + hi) >> 1;
+        if (offs[mid] <= i) lo = mid; else hi = mid;
+    }
+    int32_t t = tokens[i];
+    if (t < 0 || t >= vocab) {
+        atomicOr(&err[SD_DEVERR_TOKEN], 1);
+        t = 0;
+    }
+    text[i + lo] = t;
+}
+
+__global__ __launch_bounds__(TB) void k_layout_marks(const int64_t *__restrict__ offs, int32_t n_seq,
+                                                     int64_t N, int32_t *__restrict__ text) {
+    int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (j < n_seq) text[offs[j + 1] + j] = SD_END_TOKEN;
+    if (j < SD_TEXT_PAD) text[N + j] = SD_END_TOKEN;
+}
+
+__global__ __launch_bounds__(TB) void k_init_keys(const int32_t *__restrict__ text, int64_t N,
+                                                  int tok_bits, uint64_t *__restrict__ keys,
+                                                  uint32_t *__restrict__ vals) {
+    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (i >= N) return;
+    uint64_t a = (uint64_t)(text[i] + 1), b = (uint64_t)(text[i + 1] + 1);
+    keys[i] = (a << tok_bits) | b;
+    vals[i] = (uint32_t)i;
+}
+
+__global__ __launch_bounds__(TB) void k_group_flags(const uint64_t *__restrict__ keys, int64_t N,
+                                                    uint32_t *__restrict__ flags) {
+    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (i >= N) return;
+    flags[i] = (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
+}
+
+__global__ __launch_bounds__(TB) void k_assign_rank(const uint32_t *__restrict__ sa,
+                                                    const uint32_t *__restrict__ gid, int64_t N,
+                                                    uint32_t *__restrict__ rank) {
+    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (i >= N) return;
+    rank[sa[i]] = gid[i];
+}
+
+__global__ __launch_bounds__(TB) void k_round_keys(const uint32_t *__restrict__ sa,
+                                                   const uint32_t *__restrict__ rank, int64_t N,
+                                                   int64_t h, int rank_bits,
+                                                   uint64_t *__restrict__ keys) {
+    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (i >= N) return;
+    int64_t p = sa[i];
+    uint64_t r1 = rank[p];
+    uint64_t r2 = (p + h < N) ? rank[p + h] : 0u;
+    keys[i] = (r1 << rank_bits) | r2;
+}
+
+__global__ __launch_bounds__(TB) void k_copy_sa(const uint32_t *__restrict__ vals, int64_t N,
+                                                int32_t *__restrict__ sa) {
+    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (i < N) sa[i] = (int32_t)vals[i];
+}
+
+// bucket[c] = first index whose suffix starts with token code (token + 1) >= c
+__global__ __launch_bounds__(TB) void k_bucket(const int32_t *__restrict__ text,
+                                               const int32_t *__restrict__ sa, int64_t N,
+                                               int32_t vocab, int32_t *__restrict__ bucket) {
+    int64_t c = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (c > (int64_t)vocab + 1) return;
+    int64_t lo = 0, hi = N;
+    while (lo < hi) {
+        int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)text[sa[mid]] + 1 < c) lo = mid + 1; else hi = mid;
+    }
+    bucket[c] = (int32_t)lo;
+}
+
+__global__ __launch_bounds__(TB) void k_fill_i32(int32_t *p, int64_t n, int32_t v) {
+    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// one workgroup per sequence: copy it into its slot row and close the row with end markers
+__global__ __launch_bounds__(TB) void k_req_build(const int32_t *__restrict__ slot_ids,
+                                                  const int32_t *__restrict__ tokens,
+                                                  const int64_t *__restrict__ offs,
+                                                  int32_t *__restrict__ r_text,
+                                                  int32_t *__restrict__ r_len, int64_t stride,
+                                                  int32_t max_ctx, int32_t max_slots, int32_t vocab,
+                                                  int32_t *err) {
+    const int s = blockIdx.x;
+    const int32_t slot = slot_ids[s];
+    if (slot < 0 || slot >= max_slots) {
+        if (threadIdx.x == 0) atomicOr(&err[SD_DEVERR_SLOT], 1);
+        return;
+    }
+    const int64_t b = offs[s], len = offs[s + 1] - b;
+    if (len < 0 || len > max_ctx) {
+        if (threadIdx.x == 0) atomicOr(&err[SD_DEVERR_CTX], 1);
+        return;
+    }
+    int32_t *row = r_text + (int64_t)slot * stride;
+    for (int64_t i = threadIdx.x; i < stride; i += TB) {
+        int32_t t = SD_END_TOKEN;
+        if (i < len) {
+            t = tokens[b + i];
+            if (t < 0 || t >= vocab) {
+                atomicOr(&err[SD_DEVERR_TOKEN], 1);
+                t = 0;
+            }
+        }
+        row[i] = t;
+    }
+    if (threadIdx.x == 0) r_len[slot] = (int32_t)len;
+}
+
+__global__ __launch_bounds__(64) void k_req_append(const int32_t *__restrict__ slot_ids,
+                                                   const int32_t *__restrict__ new_tokens,
+                                                   const int32_t *__restrict__ new_offs,
+                                                   int32_t *__restrict__ r_text,
+                                                   int32_t *__restrict__ r_len, int64_t stride,
+                                                   int32_t max_ctx, int32_t max_slots, int32_t vocab,
+                                                   int32_t *err) {
+    const int s = blockIdx.x;
+    const int32_t slot = slot_ids[s];
+    if (slot < 0 || slot >= max_slots) {
+        if (threadIdx.x == 0) atomicOr(&err[SD_DEVERR_SLOT], 1);
+        return;
+    }
+    const int32_t b = new_offs[s], k = new_offs[s + 1] - b;
+    const int32_t old = r_len[slot];
+    if (k < 0 || (int64_t)old + k > max_ctx) {
+        if (threadIdx.x == 0) atomicOr(&err[SD_DEVERR_CTX], 1);
+        return;
+    }
+    int32_t *row = r_text + (int64_t)slot * stride;
+    for (int32_t i = threadIdx.x; i < k; i += 64) {
+        int32_t t = new_tokens[b + i];
+        if (t < 0 || t >= vocab) {
+            atomicOr(&err[SD_DEVERR_TOKEN], 1);
+            t = 0;
+        }
+        row[old + i] = t;
+    }
+    __syncthreads();  // every lane has read `old` before it changes
+    if (threadIdx.x == 0) r_len[slot] = old + k;
+}
+
+inline unsigned nblk(int64_t n) { return (unsigned)((n + TB - 1) / TB); }
+
+}  // namespace
+
+sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
+                               int32_t n_seq, int64_t n_tokens, hipStream_t st) {
+    const int64_t N = n_tokens + n_seq;
+    const int32_t vocab = c->cfg.vocab;
+    c->g_N = N;
+    c->g_tokens = n_tokens;
+    c->g_docs = n_seq;
+    if (n_tokens > 0)
+        hipLaunchKernelGGL(k_layout_text, dim3(nblk(n_tokens)), dim3(TB), 0, st, d_tokens, d_offsets,
+                           n_seq, n_tokens, c->g_text, vocab, c->d_err);
+    {
+        int64_t m = n_seq > SD_TEXT_PAD ? n_seq : SD_TEXT_PAD;
+        hipLaunchKernelGGL(k_layout_marks, dim3(nblk(m)), dim3(TB), 0, st, d_offsets, n_seq, N,
+                           c->g_text);
+    }
+    if (N > 0) {
+        const int tok_bits = sd_bits_for((uint64_t)vocab);  // codes 0..vocab
+        hipLaunchKernelGGL(k_init_keys, dim3(nblk(N)), dim3(TB), 0, st, c->g_text, N, tok_bits,
+                           c->b_keys[0], c->b_vals[0]);
+        int cur = sd_sort_pairs(c, N, 2 * tok_bits, 0, st);
+        const int rank_bits = sd_bits_for((uint64_t)N);  // ranks 0..N
+        int64_t h = 2;
+        for (;;) {
+            hipLaunchKernelGGL(k_group_flags, dim3(nblk(N)), dim3(TB), 0, st, c->b_keys[cur], N,
+                               c->b_flags);
+            sd_scan_inclusive_u32(c, c->b_flags, N, st);
+            hipLaunchKernelGGL(k_assign_rank, dim3(nblk(N)), dim3(TB), 0, st, c->b_vals[cur],
+                               c->b_flags, N, c->b_rank);
+            if (h >= c->cfg.D) break;
+            hipLaunchKernelGGL(k_round_keys, dim3(nblk(N)), dim3(TB), 0, st, c->b_vals[cur],
+                               c->b_rank, N, h, rank_bits, c->b_keys[cur]);
+            cur = sd_sort_pairs(c, N, 2 * rank_bits, cur, st);
+            h *= 2;
+        }
+        hipLaunchKernelGGL(k_copy_sa, dim3(nblk(N)), dim3(TB), 0, st, c->b_vals[cur], N, c->g_sa);
+    }
+    hipLaunchKernelGGL(k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, st, c->g_text, c->g_sa,
+                       N, vocab, c->g_bucket);
+    return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+sd_status sd_build_requests_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_tokens,
+                                 const int64_t *d_offsets, int32_t n_seq, hipStream_t st) {
+    if (n_seq == 0) return SD_OK;
+    hipLaunchKernelGGL(k_req_build, dim3((unsigned)n_seq), dim3(TB), 0, st, d_slot_ids, d_tokens,
+                       d_offsets, c->r_text, c->r_len, c->r_stride, c->cfg.max_ctx_tokens,
+                       c->cfg.max_batch_slots, c->cfg.vocab, c->d_err);
+    return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+sd_status sd_append_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_new_tokens,
+                         const int32_t *d_new_offsets, int32_t n_slots, hipStream_t st) {
+    if (n_slots == 0) return SD_OK;
+    hipLaunchKernelGGL(k_req_append, dim3((unsigned)n_slots), dim3(64), 0, st, d_slot_ids,
+                       d_new_tokens, d_new_offsets, c->r_text, c->r_len, c->r_stride,
+                       c->cfg.max_ctx_tokens, c->cfg.max_batch_slots, c->cfg.vocab, c->d_err);
+    return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+// used by sd_create to put every slot row into the "empty context" state
+void sd_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t st) {
+    if (n > 0) hipLaunchKernelGGL(k_fill_i32, dim3(nblk(n)), dim3(TB), 0, st, p, n, v);
+}

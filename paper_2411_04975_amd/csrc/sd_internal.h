@@ -1,0 +1,85 @@
+// Internal declarations shared by the HIP translation units of the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+
+#include "../../include/sd.h"
+
+#define SD_WAVE 64
+#define SD_TEXT_PAD 512      // sentinel tokens kept after the last real position of a text
+#define SD_END_TOKEN (-1)    // sentinel: sorts below every token and never matches one
+
+// sticky device-side error flags (indices into sd_ctx::d_err)
+enum { SD_DEVERR_TOKEN = 0, SD_DEVERR_SLOT = 1, SD_DEVERR_CTX = 2, SD_DEVERR_N = 4 };
+
+struct sd_ctx {
+    sd_config cfg;
+    int max_nodes;           // floor(alpha * P)
+    std::string last_error;
+
+    // ---- global index -------------------------------------------------
+    // g_text: documents laid out back to back, one SD_END_TOKEN after each, then padding.
+    // g_sa:   positions of g_text (sentinel positions included, they sort first) ordered by
+    //         the suffix starting there, compared on at least its first D tokens.
+    // g_bucket[c] (c = token + 1, 0 for the sentinel): first g_sa index whose suffix starts
+    //         with a token code >= c; g_bucket[vocab + 1] = g_N.
+    int32_t *g_text = nullptr;
+    int32_t *g_sa = nullptr;
+    int32_t *g_bucket = nullptr;
+    int64_t g_cap = 0;       // capacity in positions (tokens + documents)
+    int64_t g_N = 0;         // positions in use
+    int64_t g_tokens = 0, g_docs = 0;
+
+    // build scratch (sized for g_cap)
+    uint64_t *b_keys[2] = {nullptr, nullptr};
+    uint32_t *b_vals[2] = {nullptr, nullptr};
+    uint32_t *b_rank = nullptr;
+    uint32_t *b_flags = nullptr;     // group-start flags / their scan
+    uint32_t *b_hist = nullptr;      // per-tile digit histograms
+    uint32_t *b_partials = nullptr;  // scan partial sums
+    int64_t b_hist_cap = 0, b_partials_cap = 0;
+
+    // ---- per-request contexts -----------------------------------------
+    int32_t *r_text = nullptr;       // [max_batch_slots][r_stride], SD_END_TOKEN after the context
+    int32_t *r_len = nullptr;        // [max_batch_slots]
+    int64_t r_stride = 0;
+
+    // ---- speculate scratch (sized for max_batch_slots requests) -------
+    int2 *s_occ = nullptr;           // [B][max_ctx]: (end position e, common-suffix length L)
+    int32_t *s_occ_n = nullptr;      // [B]
+    int32_t *s_cntL = nullptr;       // [B][P+1]: occurrences with L >= p
+    int32_t *s_unit_sa = nullptr;    // [B][P][max_ctx]: per-(request,p) suffix lists
+    int32_t *s_unit_n = nullptr;     // [B][2P] nodes of each unit tree
+    double *s_unit_score = nullptr;  // [B][2P]
+    int32_t *s_unit_tok = nullptr;   // [B][2P][max_nodes]
+    int32_t *s_unit_par = nullptr;
+    double *s_unit_sc = nullptr;
+
+    int32_t *d_err = nullptr;        // [SD_DEVERR_N]
+    int64_t index_bytes = 0, scratch_bytes = 0;
+};
+
+// ---- launchers implemented in the other translation units ---------------
+// radix sort of (key, value) pairs on bits [0, nbits); result ends in keys[out_idx]/vals[out_idx]
+int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st);
+// exclusive->inclusive scan helper: data[i] = sum_{j<=i} data[j], uint32, in place
+void sd_scan_inclusive_u32(sd_ctx *c, uint32_t *data, int64_t n, hipStream_t st);
+
+sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
+                               int32_t n_seq, int64_t n_tokens, hipStream_t st);
+sd_status sd_build_requests_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_tokens,
+                                 const int64_t *d_offsets, int32_t n_seq, hipStream_t st);
+sd_status sd_append_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_new_tokens,
+                         const int32_t *d_new_offsets, int32_t n_slots, hipStream_t st);
+sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
+                            hipStream_t st);
+sd_status sd_accept_impl(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t *d_target,
+                         int32_t *d_accept_len, int32_t *d_accept_path, int32_t *d_bonus,
+                         hipStream_t st);
+
+static inline int sd_bits_for(uint64_t max_value) {  // bits needed to hold values 0..max_value
+    int b = 1;
+    while (b < 64 && (max_value >> b) != 0) b++;
+    return b;
+}

@@ -1,0 +1,258 @@
+// LSD radix sort of (uint64 key, uint32 value) pairs and a device-wide prefix sum, both
+// hand-written for 64-wide wavefronts.  Used by the suffix-array construction in sd_build.hip.
+//
+// One pass = three launches: per-tile digit histogram, prefix sum over the (digit, tile)
+// table, stable scatter.  Inside a tile the stable rank of a key among keys with the same
+// digit comes from wave-wide ballots (all lanes holding the same digit find each other with
+// one ballot per digit bit), so no shared-memory atomics are contended.  The scatter first
+// orders the tile by digit in LDS, so that global writes go out as runs of neighbouring lanes.
+#include "sd_internal.h"
+
+namespace {
+
+constexpr int RS_THREADS = 256;
+constexpr int RS_WAVES = RS_THREADS / SD_WAVE;
+constexpr int RS_ITEMS = 16;
+constexpr int RS_TILE = RS_THREADS * RS_ITEMS;  // keys per workgroup
+constexpr int RS_BITS = 8;
+constexpr int RS_BINS = 1 << RS_BITS;
+
+__device__ __forceinline__ uint64_t lanemask_lt() {
+    return (1ull << (threadIdx.x & 63)) - 1ull;
+}
+
+// lanes (among `valid` ones) whose digit equals this lane's digit
+__device__ __forceinline__ uint64_t match_digit(uint32_t d, bool valid) {
+    uint64_t peers = __ballot(valid);
+#pragma unroll
+    for (int b = 0; b < RS_BITS; b++) {
+        bool bit = (d >> b) & 1u;
+        uint64_t m = __ballot(valid && bit);
+        peers &= bit ? m : ~m;
+    }
+    return peers;
+}
+
+// exclusive prefix sum of one value per thread over a 256-thread workgroup
+__device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t *s_wave /*[RS_WAVES]*/,
+                                                        uint32_t *total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t t = __shfl_up(inc, o);
+        if (lane >= o) inc += t;
+    }
+    if (lane == 63) s_wave[w] = inc;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < RS_WAVES; i++) {
+        uint32_t t = s_wave[i];
+        if (i < w) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    if (total) *total = tot;
+    return base + inc - v;
+}
+
+__global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t *__restrict__ keys,
+                                                           int64_t n, int shift,
+                                                           uint32_t *__restrict__ tile_hist,
+                                                           int64_t ntiles) {
+    __shared__ uint32_t s_cnt[RS_WAVES][RS_BINS];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    for (int i = tid; i < RS_WAVES * RS_BINS; i += RS_THREADS) (&s_cnt[0][0])[i] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * RS_TILE;
+    const uint64_t lt = lanemask_lt();
+#pragma unroll 4
+    for (int k = 0; k < RS_ITEMS; k++) {
+        int64_t idx = base + (int64_t)k * RS_THREADS + tid;
+        bool valid = idx < n;
+        uint32_t d = valid ? (uint32_t)((keys[idx] >> shift) & (RS_BINS - 1)) : 0u;
+        uint64_t peers = match_digit(d, valid);
+        if (valid && (peers & lt) == 0) s_cnt[w][d] += (uint32_t)__popcll(peers);
+    }
+    __syncthreads();
+    uint32_t tot = 0;
+#pragma unroll
+    for (int i = 0; i < RS_WAVES; i++) tot += s_cnt[i][tid];
+    tile_hist[(int64_t)tid * ntiles + blockIdx.x] = tot;
+}
+
+__global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
+    const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin, uint64_t *__restrict__ kout,
+    uint32_t *__restrict__ vout, int64_t n, int shift, const uint32_t *__restrict__ offs_incl,
+    int64_t ntiles) {
+    __shared__ uint64_t s_keys[RS_TILE];
+    __shared__ uint32_t s_vals[RS_TILE];
+    __shared__ volatile uint32_t s_wcnt[RS_WAVES][RS_BINS];
+    __shared__ uint32_t s_excl[RS_BINS];
+    __shared__ uint32_t s_gbase[RS_BINS];
+    __shared__ uint32_t s_wave[RS_WAVES];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    for (int i = tid; i < RS_WAVES * RS_BINS; i += RS_THREADS) (&s_wcnt[0][0])[i] = 0;
+    __syncthreads();
+    const int64_t base = (int64_t)blockIdx.x * RS_TILE;
+    const int cnt = (int)((n - base) < RS_TILE ? (n - base) : RS_TILE);
+    const uint64_t lt = lanemask_lt();
+
+    uint64_t key[RS_ITEMS];
+    uint32_t val[RS_ITEMS];
+    uint32_t rnk[RS_ITEMS];
+    // wave w owns keys [w*1024, (w+1)*1024) of the tile, item k of lane l is key k*64 + l of
+    // that range: the stable order is (wave, item, lane).
+#pragma unroll
+    for (int k = 0; k < RS_ITEMS; k++) {
+        int j = w * (RS_ITEMS * 64) + k * 64 + lane;
+        bool valid = j < cnt;
+        key[k] = valid ? kin[base + j] : 0ull;
+        val[k] = valid ? vin[base + j] : 0u;
+    }
+#pragma unroll
+    for (int k = 0; k < RS_ITEMS; k++) {
+        int j = w * (RS_ITEMS * 64) + k * 64 + lane;
+        bool valid = j < cnt;
+        uint32_t d = (uint32_t)((key[k] >> shift) & (RS_BINS - 1));
+        uint64_t peers = match_digit(d, valid);
+        uint32_t pre = s_wcnt[w][d];
+        uint32_t below = (uint32_t)__popcll(peers & lt);
+        if (valid && below == 0) s_wcnt[w][d] = pre + (uint32_t)__popcll(peers);
+        rnk[k] = pre + below;
+    }
+    __syncthreads();
+    {
+        const int d = tid;
+        uint32_t acc = 0;
+#pragma unroll
+        for (int i = 0; i < RS_WAVES; i++) {
+            uint32_t c = s_wcnt[i][d];
+            s_wcnt[i][d] = acc;  // keys of digit d held by earlier waves of this tile
+            acc += c;
+        }
+        uint32_t ex = block_excl_scan_256(acc, s_wave, nullptr);
+        s_excl[d] = ex;
+        int64_t idx = (int64_t)d * ntiles + blockIdx.x;
+        s_gbase[d] = idx > 0 ? offs_incl[idx - 1] : 0u;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < RS_ITEMS; k++) {
+        int j = w * (RS_ITEMS * 64) + k * 64 + lane;
+        if (j < cnt) {
+            uint32_t d = (uint32_t)((key[k] >> shift) & (RS_BINS - 1));
+            uint32_t pos = s_excl[d] + s_wcnt[w][d] + rnk[k];
+            s_keys[pos] = key[k];
+            s_vals[pos] = val[k];
+        }
+    }
+    __syncthreads();
+#pragma unroll 4
+    for (int k = 0; k < RS_ITEMS; k++) {
+        int j = k * RS_THREADS + tid;
+        if (j < cnt) {
+            uint64_t kk = s_keys[j];
+            uint32_t d = (uint32_t)((kk >> shift) & (RS_BINS - 1));
+            uint32_t out = s_gbase[d] + ((uint32_t)j - s_excl[d]);
+            kout[out] = kk;
+            vout[out] = s_vals[j];
+        }
+    }
+}
+
+// ---- device-wide inclusive prefix sum (uint32), three launches ------------------------------
+constexpr int SC_THREADS = 256;
+constexpr int SC_ITEMS = 16;
+constexpr int SC_TILE = SC_THREADS * SC_ITEMS;
+
+__global__ __launch_bounds__(SC_THREADS) void k_scan_tile_sums(const uint32_t *__restrict__ data,
+                                                               int64_t n,
+                                                               uint32_t *__restrict__ partials) {
+    __shared__ uint32_t s_wave[SC_THREADS / 64];
+    const int64_t base = (int64_t)blockIdx.x * SC_TILE;
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < SC_ITEMS; k++) {
+        int64_t i = base + (int64_t)k * SC_THREADS + threadIdx.x;
+        if (i < n) s += data[i];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if ((threadIdx.x & 63) == 0) s_wave[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int i = 0; i < SC_THREADS / 64; i++) t += s_wave[i];
+        partials[blockIdx.x] = t;
+    }
+}
+
+// single workgroup: partials[i] <- sum of partials[0..i) (exclusive), any length
+__global__ __launch_bounds__(SC_THREADS) void k_scan_partials(uint32_t *partials, int64_t m) {
+    __shared__ uint32_t s_wave[SC_THREADS / 64];
+    __shared__ uint32_t s_carry;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < m; base += SC_THREADS) {
+        int64_t i = base + threadIdx.x;
+        uint32_t v = i < m ? partials[i] : 0u;
+        uint32_t tot;
+        uint32_t ex = block_excl_scan_256(v, s_wave, &tot);
+        uint32_t carry = s_carry;
+        if (i < m) partials[i] = carry + ex;
+        __syncthreads();
+        if (threadIdx.x == 0) s_carry = carry + tot;
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(SC_THREADS) void k_scan_apply(uint32_t *__restrict__ data, int64_t n,
+                                                           const uint32_t *__restrict__ partials) {
+    __shared__ uint32_t s_wave[SC_THREADS / 64];
+    const int64_t base = (int64_t)blockIdx.x * SC_TILE + (int64_t)threadIdx.x * SC_ITEMS;
+    uint32_t v[SC_ITEMS];
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < SC_ITEMS; k++) {
+        int64_t i = base + k;
+        v[k] = i < n ? data[i] : 0u;
+        s += v[k];
+    }
+    uint32_t ex = block_excl_scan_256(s, s_wave, nullptr) + partials[blockIdx.x];
+#pragma unroll
+    for (int k = 0; k < SC_ITEMS; k++) {
+        int64_t i = base + k;
+        ex += v[k];
+        if (i < n) data[i] = ex;
+    }
+}
+
+}  // namespace
+
+void sd_scan_inclusive_u32(sd_ctx *c, uint32_t *data, int64_t n, hipStream_t st) {
+    if (n <= 0) return;
+    int64_t nt = (n + SC_TILE - 1) / SC_TILE;
+    hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, data, n,
+                       c->b_partials);
+    hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(SC_THREADS), 0, st, c->b_partials, nt);
+    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, data, n,
+                       c->b_partials);
+}
+
+int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st) {
+    int cur = in_idx;
+    if (n <= 0) return cur;
+    int64_t ntiles = (n + RS_TILE - 1) / RS_TILE;
+    for (int shift = 0; shift < nbits; shift += RS_BITS) {
+        hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
+                           c->b_keys[cur], n, shift, c->b_hist, ntiles);
+        sd_scan_inclusive_u32(c, c->b_hist, (int64_t)RS_BINS * ntiles, st);
+        hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
+                           c->b_keys[cur], c->b_vals[cur], c->b_keys[cur ^ 1], c->b_vals[cur ^ 1],
+                           n, shift, c->b_hist, ntiles);
+        cur ^= 1;
+    }
+    return cur;
+}

@@ -1,0 +1,166 @@
+"""Helpers shared by the GPU parity tests: run the oracle and the HIP path on the same
+inputs and compare them element by element."""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+
+REL_TOL = 1e-12   # bar on fp64 scores (the paths agree bit for bit in practice)
+
+
+def oracle_global_trie(docs, D, vocab, contexts=None, P=None):
+    """Global trie; when contexts are given only suffixes that start with one of their last P
+    tokens are inserted (exact for every pattern those contexts can ask about)."""
+    allowed = None
+    if contexts is not None:
+        allowed = np.zeros(vocab, np.uint8)
+        for x in contexts:
+            if len(x):
+                allowed[np.asarray(x[-P:], dtype=np.int64)] = 1
+    t = oracle.Trie(D)
+    for d in docs:
+        if len(d):
+            t.add_doc(d, allowed)
+    return t
+
+
+def oracle_speculate_batch(tg, contexts, D, P, alpha, min_score, max_nodes, request_tries=None):
+    B = len(contexts)
+    out = dict(n_nodes=np.zeros(B, np.int32), tokens=np.full((B, max_nodes), -1, np.int32),
+               parents=np.full((B, max_nodes), -1, np.int32),
+               scores=np.zeros((B, max_nodes), np.float64), tree_score=np.zeros(B, np.float64),
+               match_len=np.zeros(B, np.int32), source=np.full(B, -1, np.int32))
+    for b, x in enumerate(contexts):
+        if request_tries is not None:
+            tr = request_tries[b]
+        else:
+            tr = oracle.Trie(D)
+            if len(x):
+                tr.append(x)
+        g = oracle.generate(tg, tr, x, P, alpha, min_score)
+        n = g["n_nodes"]
+        out["n_nodes"][b] = n
+        out["tokens"][b, :n] = g["tokens"]
+        out["parents"][b, :n] = g["parents"]
+        out["scores"][b, :n] = g["scores"]
+        out["tree_score"][b] = g["tree_score"]
+        out["match_len"][b] = g["match_len"]
+        out["source"][b] = g["source"]
+    return out
+
+
+class GpuPath:
+    """The HIP library driven through its binding, inputs handed over as numpy arrays."""
+
+    def __init__(self, vocab, D, P, alpha, min_score, max_slots, max_ctx, max_global):
+        import torch
+        import paper_2411_04975_amd as sd
+        self.sd, self.torch = sd, torch
+        self.dev = torch.device("cuda", 0)
+        self.ctx = sd.sd_create(vocab, D, P, alpha, min_score, max_slots, max_ctx, max_global, 0)
+        self.max_nodes = self.ctx.max_nodes
+
+    def close(self):
+        self.sd.sd_destroy(self.ctx)
+
+    def _seqs(self, seqs):
+        torch = self.torch
+        lens = np.array([len(s) for s in seqs], np.int64)
+        offs = np.zeros(len(seqs) + 1, np.int64)
+        np.cumsum(lens, out=offs[1:])
+        flat = np.concatenate([np.asarray(s, np.int32) for s in seqs]) if len(seqs) and offs[-1] \
+            else np.zeros(0, np.int32)
+        d_tok = torch.from_numpy(np.ascontiguousarray(flat)).to(self.dev)
+        if d_tok.numel() == 0:
+            d_tok = torch.zeros(1, dtype=torch.int32, device=self.dev)
+        return d_tok, torch.from_numpy(offs).to(self.dev), int(offs[-1])
+
+    def build_global(self, docs):
+        d_tok, d_off, n = self._seqs(docs)
+        self.sd.sd_index_build(self.ctx, self.sd.SD_SCOPE_GLOBAL, None, d_tok, d_off, n)
+
+    def build_requests(self, slots, contexts):
+        d_tok, d_off, n = self._seqs(contexts)
+        d_slots = self.torch.tensor(list(slots), dtype=self.torch.int32, device=self.dev)
+        self.sd.sd_index_build(self.ctx, self.sd.SD_SCOPE_REQUESTS, d_slots, d_tok, d_off, n)
+
+    def append(self, slots, new_tokens):
+        torch = self.torch
+        lens = np.array([len(s) for s in new_tokens], np.int32)
+        offs = np.zeros(len(new_tokens) + 1, np.int32)
+        np.cumsum(lens, out=offs[1:])
+        flat = np.concatenate([np.asarray(s, np.int32) for s in new_tokens]) if offs[-1] \
+            else np.zeros(1, np.int32)
+        self.sd.sd_index_append(self.ctx,
+                                torch.tensor(list(slots), dtype=torch.int32, device=self.dev),
+                                torch.from_numpy(flat).to(self.dev),
+                                torch.from_numpy(offs).to(self.dev))
+
+    def speculate(self, slots, max_nodes=None):
+        torch = self.torch
+        B = len(slots)
+        mn = max_nodes or self.max_nodes
+        tr = self.sd.Trees(B, mn, self.dev)
+        # poison the outputs so that unwritten entries show up
+        tr.tokens.fill_(-7); tr.parents.fill_(-7); tr.scores.fill_(-7.0); tr.n_nodes.fill_(-7)
+        tr.match_len.fill_(-7); tr.source.fill_(-7); tr.tree_score.fill_(-7.0)
+        self.sd.sd_speculate(self.ctx, torch.tensor(list(slots), dtype=torch.int32,
+                                                    device=self.dev), tr)
+        torch.cuda.synchronize()
+        self.trees = tr
+        return dict(n_nodes=tr.n_nodes.cpu().numpy(), tokens=tr.tokens.cpu().numpy(),
+                    parents=tr.parents.cpu().numpy(), scores=tr.scores.cpu().numpy(),
+                    tree_score=tr.tree_score.cpu().numpy(), match_len=tr.match_len.cpu().numpy(),
+                    source=tr.source.cpu().numpy())
+
+    def accept(self, target):
+        torch = self.torch
+        tr = self.trees
+        B, mn = tr.batch, tr.max_nodes
+        d_t = torch.from_numpy(np.ascontiguousarray(target, np.int32)).to(self.dev)
+        al = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        ap = torch.full((B, mn), -7, dtype=torch.int32, device=self.dev)
+        bo = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        self.sd.sd_accept(self.ctx, tr, B, d_t, al, ap, bo)
+        torch.cuda.synchronize()
+        return al.cpu().numpy(), ap.cpu().numpy(), bo.cpu().numpy()
+
+    def stats(self):
+        return self.sd.sd_get_stats(self.ctx)
+
+
+def compare_trees(got, want, label=""):
+    """Bit-exact on structure, REL_TOL on scores.  Returns a list of mismatch descriptions."""
+    bad = []
+    for k in ("n_nodes", "match_len", "source", "tokens", "parents"):
+        if not np.array_equal(got[k], want[k]):
+            rows = np.nonzero((got[k] != want[k]).reshape(got[k].shape[0], -1).any(axis=1))[0]
+            b = int(rows[0])
+            bad.append("%s %s differs for %d requests; first b=%d got=%s want=%s" % (
+                label, k, len(rows), b, got[k][b], want[k][b]))
+    for k in ("scores", "tree_score"):
+        g, w = got[k], want[k]
+        err = np.abs(g - w) > REL_TOL * np.abs(w)
+        if err.any():
+            bad.append("%s %s off beyond %g at %s" % (label, k, REL_TOL, np.argwhere(err)[:3]))
+    return bad
+
+
+def node_depths(parents, n):
+    d = np.zeros(n, np.int64)
+    for j in range(n):
+        d[j] = 1 if parents[j] < 0 else d[parents[j]] + 1
+    return d
+
+
+def targets_from_future(out, future, max_nodes):
+    """Simulated greedy verifier: the target token at a node of depth k is future[k]."""
+    B = out["n_nodes"].shape[0]
+    tgt = np.zeros((B, max_nodes + 1), np.int32)
+    for b in range(B):
+        n = int(out["n_nodes"][b])
+        tgt[b, :] = future[b, 0]
+        d = node_depths(out["parents"][b], n)
+        tgt[b, 1:1 + n] = future[b, d]
+    return tgt

