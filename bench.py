@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Benchmark of the SuffixDecoding draft-generation path on one MI355X.
+
+A step is one decode step over the whole batch: sd_speculate (match, expand, select), the
+simulated greedy verifier, sd_accept, and sd_index_append of the accepted + bonus tokens.
+The two index builds (global corpus, request contexts) happen once per run and are timed
+separately in the same run (index_build_tokens_per_s).  Inputs are synthetic, resident in HBM
+before any timed region starts.
+
+Prints ONE JSON line.  `value` = speculation trees per second over K timed steps.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def _traffic_from_profiles(kernel: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary
+    for this kernel has been committed under profiles/."""
+    path = os.path.join(ROOT, "profiles", "%s_large_pmc.md" % kernel)
+    try:
+        m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(w, n_requests: int, build_tokens: int):
+    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
+    import numpy as np
+    import oracle
+    from tests import parity
+    docs = w.docs()
+    # (a) index build: plain trie over the first documents, about build_tokens tokens
+    t = oracle.Trie(w.D)
+    n = 0
+    t0 = time.perf_counter()
+    for d in docs:
+        t.add_doc(d)
+        n += len(d)
+        if n >= build_tokens:
+            break
+    build_s = time.perf_counter() - t0
+    del t
+    # (b) draft generation for the first n_requests requests against the full corpus; the
+    # global trie holds exactly the suffixes those requests can reach
+    contexts = [w.contexts[b] for b in range(n_requests)]
+    tg = parity.oracle_global_trie(docs, w.D, w.vocab, contexts, w.P)
+    tries = []
+    for x in contexts:
+        tr = oracle.Trie(w.D)
+        tr.append(x)
+        tries.append(tr)
+    t0 = time.perf_counter()
+    drafted = 0
+    for x, tr in zip(contexts, tries):
+        g = oracle.generate(tg, tr, x, w.P, w.alpha, w.min_score)
+        drafted += g["n_nodes"]
+    spec_s = time.perf_counter() - t0
+    return {
+        "value": n_requests / spec_s, "unit": "trees/s", "cores": 1, "kind": "oracle",
+        "sample": "first %d requests of the batch against the full %d-token corpus "
+                  "(GenerateCandidateTree only, tries prebuilt); build leg: plain trie over the "
+                  "first %d corpus tokens" % (n_requests, len(w.corpus), n),
+        "us_per_drafted_token": spec_s / max(drafted, 1) * 1e6,
+        "index_build_tokens_per_s": n / build_s,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large")
+    ap.add_argument("--build-reps", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path has no "
+              "multi-GPU leg, see DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2411_04975_amd as sd
+    from workloads import CONFIGS, make_workload, verifier
+
+    K, W = args.steps, args.warmup
+    cfg = CONFIGS[args.workload]
+    mn = int(np.floor(cfg["alpha"] * cfg["P"]))
+    total_steps = K + W
+    w = make_workload(args.workload, seed=args.seed, future_len=(total_steps + 2) * (mn + 1) + mn + 2)
+    dev = torch.device("cuda", 0)
+    torch.cuda.set_device(dev)
+    B, ctx_len = w.batch, w.ctx_len
+    n_tokens, n_docs = int(w.corpus.shape[0]), len(w.doc_offsets) - 1
+
+    i32 = torch.int32
+    d_corpus = torch.from_numpy(w.corpus).to(dev)
+    d_doc_off = torch.from_numpy(w.doc_offsets).to(dev)
+    d_ctx = torch.from_numpy(w.contexts.reshape(-1)).to(dev)
+    d_ctx_off = torch.arange(0, (B + 1) * ctx_len, ctx_len, dtype=torch.int64, device=dev)
+    d_future = torch.from_numpy(w.future).to(dev)
+    d_slots = torch.arange(B, dtype=i32, device=dev)
+    max_ctx = ctx_len + (total_steps + 1) * (mn + 1)
+
+    ctx = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, B, max_ctx, n_tokens + n_docs, 0)
+    trees = sd.Trees(B, mn, dev)
+    d_target = torch.zeros((B, mn + 1), dtype=i32, device=dev)
+    d_alen = torch.zeros(B, dtype=i32, device=dev)
+    d_apath = torch.zeros((B, mn), dtype=i32, device=dev)
+    d_bonus = torch.zeros(B, dtype=i32, device=dev)
+    d_new = torch.zeros(B * (mn + 1), dtype=i32, device=dev)
+    d_newoff = torch.zeros(B + 1, dtype=i32, device=dev)
+    d_pos = torch.zeros(B, dtype=i32, device=dev)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    # ---- index builds (timed separately, inputs already in HBM) -------------------------
+    def build_global():
+        sd.sd_index_build(ctx, sd.SD_SCOPE_GLOBAL, None, d_corpus, d_doc_off, n_tokens)
+
+    def build_requests():
+        sd.sd_index_build(ctx, sd.SD_SCOPE_REQUESTS, d_slots, d_ctx, d_ctx_off, B * ctx_len)
+
+    build_global()
+    torch.cuda.synchronize()
+    build_ms = []
+    for _ in range(args.build_reps):
+        e0, e1 = ev(), ev()
+        e0.record()
+        build_global()
+        e1.record()
+        torch.cuda.synchronize()
+        build_ms.append(e0.elapsed_time(e1))
+    build_ms.sort()
+    g_build_ms = build_ms[len(build_ms) // 2]
+    sd.sd_debug_profile(ctx, 1)
+    build_global()
+    prof_build = sd.sd_debug_profile_read(ctx)
+    sd.sd_debug_profile(ctx, 0)
+    e0, e1 = ev(), ev()
+    e0.record()
+    build_requests()
+    e1.record()
+    torch.cuda.synchronize()
+    r_build_ms = e0.elapsed_time(e1)
+
+    # ---- decode steps ---------------------------------------------------------------------
+    def step():
+        sd.sd_speculate(ctx, d_slots, trees)
+        verifier.targets(trees.n_nodes, trees.parents, d_future, d_pos, d_target)
+        sd.sd_accept(ctx, trees, B, d_target, d_alen, d_apath, d_bonus)
+        verifier.collect(trees.tokens, d_alen, d_apath, d_bonus, d_new, d_newoff, d_pos)
+        sd.sd_index_append(ctx, d_slots, d_new, d_newoff)
+
+    def reset():
+        build_requests()
+        d_pos.zero_()
+
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(K):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    mean_nodes = float(trees.n_nodes.float().mean().item())
+    mean_accept = float(d_alen.float().mean().item())
+    stats = sd.sd_get_stats(ctx)
+    assert stats["err_bad_token"] == 0 and stats["err_bad_slot"] == 0 and \
+        stats["err_ctx_overflow"] == 0, stats
+
+    # ---- per-kernel durations (HIP events on the launch stream) over the same K steps -----
+    reset()
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+    sd.sd_debug_profile(ctx, 1)
+    sd.sd_debug_profile_read(ctx)
+    for _ in range(K):
+        step()
+    prof = sd.sd_debug_profile_read(ctx)
+    # ---- algorithmic bytes of the same launches (counting variants, untimed) --------------
+    reset()
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+    sd.sd_debug_profile(ctx, 2)
+    sd.sd_debug_profile_read(ctx)
+    for _ in range(K):
+        step()
+    cnt = sd.sd_debug_profile_read(ctx)
+    sd.sd_debug_profile(ctx, 0)
+
+    exp_ms = prof["expand"]["ms"] / max(prof["expand"]["launches"], 1)
+    exp_bytes = cnt["expand"]["algo_bytes"] / max(cnt["expand"]["launches"], 1)
+    achieved = exp_bytes / (exp_ms * 1e-3) / 1e9 if exp_ms > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": "k_expand", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": _traffic_from_profiles("k_expand"),
+                "algo_bytes_per_launch": exp_bytes, "avg_launch_ms": exp_ms}
+    N = n_tokens + n_docs
+    sc = prof_build["sort_scatter"]
+    sc_ms = sc["ms"] / max(sc["launches"], 1)
+    sc_ach = 24.0 * N / (sc_ms * 1e-3) / 1e9 if sc_ms > 0 else 0.0
+    roofline_build = {"bound": "hbm", "kernel": "k_radix_scatter", "achieved": sc_ach,
+                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sc_ach / HBM_PEAK_GBS,
+                      "traffic": _traffic_from_profiles("k_radix_scatter"),
+                      "algo_bytes_per_launch": 24.0 * N, "avg_launch_ms": sc_ms,
+                      "launches_per_build": sc["launches"]}
+    kernels_ms = {k: v["ms"] / max(v["launches"], 1) for k, v in prof.items() if v["launches"]}
+    build_kernels_ms = {k: v["ms"] for k, v in prof_build.items() if v["launches"]}
+
+    out = {
+        "metric": "speculation trees/sec (batch %d, %s-token corpus)" % (B, format(n_tokens, ",")),
+        "value": B * K / elapsed, "unit": "trees/s", "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "int32+f64", "data": "synthetic",
+        "config": {"workload": w.name, "batch": B, "ctx_len": ctx_len, "corpus_tokens": n_tokens,
+                   "corpus_docs": n_docs, "vocab": w.vocab, "D": w.D, "P": w.P, "alpha": w.alpha,
+                   "min_score": w.min_score, "max_nodes": mn, "seed": args.seed,
+                   "generator": {k: v for k, v in w.params.items()
+                                 if k in ("kind", "n_templates", "template_len", "span", "mut",
+                                          "doc_len", "zipf_s")},
+                   "step": "sd_speculate + simulated verifier + sd_accept + sd_index_append"},
+        "index_build_tokens_per_s": n_tokens / (g_build_ms * 1e-3),
+        "index_build_ms": g_build_ms, "request_build_ms": r_build_ms,
+        "request_build_tokens_per_s": B * ctx_len / (r_build_ms * 1e-3),
+        "mean_tree_nodes": mean_nodes, "mean_accept_len": mean_accept,
+        "kernel_ms_per_launch": kernels_ms, "build_kernel_ms_total": build_kernels_ms,
+        "roofline": roofline, "roofline_build": roofline_build,
+        "index_bytes": stats["index_bytes"], "scratch_bytes": stats["scratch_bytes"],
+    }
+    sd.sd_destroy(ctx)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, n_requests=min(16, B), build_tokens=300_000)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

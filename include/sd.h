@@ -165,6 +165,28 @@ sd_status sd_accept(sd_ctx *ctx, sd_trees trees, int32_t batch, const int32_t *d
 /* Synchronises the device and copies counters and sticky flags to the host. */
 sd_status sd_get_stats(sd_ctx *ctx, sd_stats *host_out);
 
+/* Measurement hooks.  With profiling on, every kernel launch of the library is
+ * bracketed by HIP events on the caller's stream (at most SD_PROF_MAX_SPANS
+ * launches are kept between two reads).  mode 0 = off, 1 = time kernels,
+ * 2 = time kernels and run the counting variants of the speculation kernels,
+ * which add up the bytes the algorithm asks for (suffix-array words, text
+ * tokens, occurrence records, emitted nodes).  sd_debug_profile_read
+ * synchronises, reports per-kernel launch counts, total milliseconds and
+ * counted bytes since the previous read, and clears them. */
+enum {
+    SD_K_OCCURRENCES = 0, SD_K_EXPAND = 1, SD_K_SELECT = 2, SD_K_ACCEPT = 3, SD_K_APPEND = 4,
+    SD_K_REQ_BUILD = 5, SD_K_SORT_HIST = 6, SD_K_SORT_SCAN = 7, SD_K_SORT_SCATTER = 8,
+    SD_K_BUILD_OTHER = 9, SD_K_COUNT = 10
+};
+#define SD_PROF_MAX_SPANS 8192
+typedef struct {
+    int64_t launches[SD_K_COUNT];
+    double ms[SD_K_COUNT];
+    int64_t algo_bytes[SD_K_COUNT];
+} sd_profile;
+sd_status sd_debug_profile(sd_ctx *ctx, int32_t mode);
+sd_status sd_debug_profile_read(sd_ctx *ctx, sd_profile *host_out);
+
 /* Test hook: synchronises, then copies the global index to host buffers:
  * the laid-out text (documents back to back, -1 after each) and the suffix
  * array over it, `*n_positions` entries each (tokens + documents).  Returns

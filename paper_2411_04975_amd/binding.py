@@ -50,6 +50,15 @@ class _Stats(C.Structure):
                 ("index_bytes", C.c_int64), ("scratch_bytes", C.c_int64)]
 
 
+KERNEL_NAMES = ["occurrences", "expand", "select", "accept", "append", "req_build", "sort_hist",
+                "sort_scan", "sort_scatter", "build_other"]
+
+
+class _Profile(C.Structure):
+    _fields_ = [("launches", C.c_int64 * 10), ("ms", C.c_double * 10),
+                ("algo_bytes", C.c_int64 * 10)]
+
+
 _lib = None
 
 
@@ -82,6 +91,10 @@ def _load():
     L.sd_accept.argtypes = [vp, _Trees, C.c_int32, vp, vp, vp, vp, vp]
     L.sd_get_stats.restype = C.c_int
     L.sd_get_stats.argtypes = [vp, C.POINTER(_Stats)]
+    L.sd_debug_profile.restype = C.c_int
+    L.sd_debug_profile.argtypes = [vp, C.c_int32]
+    L.sd_debug_profile_read.restype = C.c_int
+    L.sd_debug_profile_read.argtypes = [vp, C.POINTER(_Profile)]
     L.sd_debug_read_global.restype = C.c_int
     L.sd_debug_read_global.argtypes = [vp, vp, vp, C.c_int64, C.POINTER(C.c_int64)]
     _lib = L
@@ -236,3 +249,16 @@ def sd_debug_read_global(ctx: _Ctx):
     _check(ctx, L.sd_debug_read_global(ctx.handle, text.ctypes.data_as(C.c_void_p),
                                        sa.ctypes.data_as(C.c_void_p), n.value, C.byref(n)))
     return text[:n.value], sa[:n.value]
+
+
+def sd_debug_profile(ctx: _Ctx, mode: int) -> None:
+    """0 = off, 1 = HIP-event timing of every kernel, 2 = timing + byte-counting variants."""
+    _check(ctx, _load().sd_debug_profile(ctx.handle, mode))
+
+
+def sd_debug_profile_read(ctx: _Ctx) -> dict:
+    """Per kernel: launches, total ms and counted algorithmic bytes since the last read."""
+    pr = _Profile()
+    _check(ctx, _load().sd_debug_profile_read(ctx.handle, C.byref(pr)))
+    return {n: dict(launches=int(pr.launches[i]), ms=float(pr.ms[i]),
+                    algo_bytes=int(pr.algo_bytes[i])) for i, n in enumerate(KERNEL_NAMES)}

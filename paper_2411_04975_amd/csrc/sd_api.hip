@@ -36,6 +36,12 @@ void free_all(sd_ctx *c) {
                     c->s_unit_score, c->s_unit_tok, c->s_unit_par, c->s_unit_sc, c->d_err};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
+    if (c->d_algo_bytes) (void)hipFree(c->d_algo_bytes);
+    if (c->prof_ev) {
+        for (int i = 0; i < 2 * SD_PROF_MAX_SPANS; i++)
+            if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
+        delete[] c->prof_ev;
+    }
 }
 
 }  // namespace
@@ -94,6 +100,7 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     ok = ok && dev_alloc(&c->s_unit_par, B * 2 * P * c->max_nodes, sb);
     ok = ok && dev_alloc(&c->s_unit_sc, B * 2 * P * c->max_nodes, sb);
     ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb);
+    ok = ok && dev_alloc(&c->d_algo_bytes, SD_K_COUNT, sb);
     if (!ok) {
         free_all(c);
         delete c;
@@ -105,6 +112,7 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     sd_fill_i32(c->r_text, B * c->r_stride, SD_END_TOKEN, nullptr);
     sd_fill_i32(c->r_len, B, 0, nullptr);
     sd_fill_i32(c->d_err, SD_DEVERR_N, 0, nullptr);
+    sd_fill_i32((int32_t *)c->d_algo_bytes, 2 * SD_K_COUNT, 0, nullptr);
     if (hipDeviceSynchronize() != hipSuccess) {
         free_all(c);
         delete c;
@@ -208,6 +216,40 @@ sd_status sd_get_stats(sd_ctx *c, sd_stats *o) {
     o->reserved = 0;
     o->index_bytes = c->index_bytes;
     o->scratch_bytes = c->scratch_bytes;
+    return SD_OK;
+}
+
+sd_status sd_debug_profile(sd_ctx *c, int32_t mode) {
+    if (!c || mode < 0 || mode > 2) return SD_ERR_INVALID_ARG;
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
+    if (mode && !c->prof_ev) {
+        c->prof_ev = new (std::nothrow) hipEvent_t[2 * SD_PROF_MAX_SPANS]();
+        if (!c->prof_ev) return fail(c, SD_ERR_OOM, "event pool");
+        for (int i = 0; i < 2 * SD_PROF_MAX_SPANS; i++)
+            if (hipEventCreate(&c->prof_ev[i]) != hipSuccess) return fail(c, SD_ERR_HIP, "hipEventCreate");
+    }
+    c->prof_mode = mode;
+    return SD_OK;
+}
+
+sd_status sd_debug_profile_read(sd_ctx *c, sd_profile *o) {
+    if (!c || !o) return SD_ERR_INVALID_ARG;
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
+    if (hipDeviceSynchronize() != hipSuccess) return fail(c, SD_ERR_HIP, "device synchronize failed");
+    for (int k = 0; k < SD_K_COUNT; k++) { o->launches[k] = 0; o->ms[k] = 0.0; o->algo_bytes[k] = 0; }
+    for (int i = 0; i < c->prof_n; i++) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, c->prof_ev[2 * i], c->prof_ev[2 * i + 1]) != hipSuccess)
+            return fail(c, SD_ERR_HIP, "hipEventElapsedTime");
+        o->launches[c->prof_kind[i]]++;
+        o->ms[c->prof_kind[i]] += (double)ms;
+    }
+    c->prof_n = 0;
+    unsigned long long ab[SD_K_COUNT];
+    if (hipMemcpy(ab, c->d_algo_bytes, sizeof(ab), hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(c, SD_ERR_HIP, "hipMemcpy");
+    for (int k = 0; k < SD_K_COUNT; k++) o->algo_bytes[k] = (int64_t)ab[k];
+    if (hipMemset(c->d_algo_bytes, 0, sizeof(ab)) != hipSuccess) return fail(c, SD_ERR_HIP, "hipMemset");
     return SD_OK;
 }
 

@@ -190,42 +190,36 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
     c->g_tokens = n_tokens;
     c->g_docs = n_seq;
     if (n_tokens > 0)
-        hipLaunchKernelGGL(k_layout_text, dim3(nblk(n_tokens)), dim3(TB), 0, st, d_tokens, d_offsets,
-                           n_seq, n_tokens, c->g_text, vocab, c->d_err);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_layout_text, dim3(nblk(n_tokens)), dim3(TB), 0, d_tokens, d_offsets, n_seq, n_tokens, c->g_text, vocab, c->d_err);
     {
         int64_t m = n_seq > SD_TEXT_PAD ? n_seq : SD_TEXT_PAD;
-        hipLaunchKernelGGL(k_layout_marks, dim3(nblk(m)), dim3(TB), 0, st, d_offsets, n_seq, N,
-                           c->g_text);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_layout_marks, dim3(nblk(m)), dim3(TB), 0, d_offsets, n_seq, N, c->g_text);
     }
     if (N > 0) {
         const int tok_bits = sd_bits_for((uint64_t)vocab);  // codes 0..vocab
-        hipLaunchKernelGGL(k_init_keys, dim3(nblk(N)), dim3(TB), 0, st, c->g_text, N, tok_bits,
-                           c->b_keys[0], c->b_vals[0]);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_init_keys, dim3(nblk(N)), dim3(TB), 0, c->g_text, N, tok_bits, c->b_keys[0], c->b_vals[0]);
         int cur = sd_sort_pairs(c, N, 2 * tok_bits, 0, st);
         const int rank_bits = sd_bits_for((uint64_t)N);  // ranks 0..N
         int64_t h = 2;
         for (;;) {
-            hipLaunchKernelGGL(k_group_flags, dim3(nblk(N)), dim3(TB), 0, st, c->b_keys[cur], N,
-                               c->b_flags);
+            SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_group_flags, dim3(nblk(N)), dim3(TB), 0, c->b_keys[cur], N, c->b_flags);
             sd_scan_inclusive_u32(c, c->b_flags, N, st);
-            hipLaunchKernelGGL(k_assign_rank, dim3(nblk(N)), dim3(TB), 0, st, c->b_vals[cur],
-                               c->b_flags, N, c->b_rank);
+            SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_assign_rank, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_flags, N, c->b_rank);
             if (h >= c->cfg.D) break;
-            hipLaunchKernelGGL(k_round_keys, dim3(nblk(N)), dim3(TB), 0, st, c->b_vals[cur],
-                               c->b_rank, N, h, rank_bits, c->b_keys[cur]);
+            SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_rank, N, h, rank_bits, c->b_keys[cur]);
             cur = sd_sort_pairs(c, N, 2 * rank_bits, cur, st);
             h *= 2;
         }
-        hipLaunchKernelGGL(k_copy_sa, dim3(nblk(N)), dim3(TB), 0, st, c->b_vals[cur], N, c->g_sa);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_copy_sa, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], N, c->g_sa);
     }
-    hipLaunchKernelGGL(k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, st, c->g_text, c->g_sa,
-                       N, vocab, c->g_bucket);
+    SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, N, vocab, c->g_bucket);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
 sd_status sd_build_requests_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_tokens,
                                  const int64_t *d_offsets, int32_t n_seq, hipStream_t st) {
     if (n_seq == 0) return SD_OK;
+    sd_span sp(c, SD_K_REQ_BUILD, st);
     hipLaunchKernelGGL(k_req_build, dim3((unsigned)n_seq), dim3(TB), 0, st, d_slot_ids, d_tokens,
                        d_offsets, c->r_text, c->r_len, c->r_stride, c->cfg.max_ctx_tokens,
                        c->cfg.max_batch_slots, c->cfg.vocab, c->d_err);
@@ -235,6 +229,7 @@ sd_status sd_build_requests_impl(sd_ctx *c, const int32_t *d_slot_ids, const int
 sd_status sd_append_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_new_tokens,
                          const int32_t *d_new_offsets, int32_t n_slots, hipStream_t st) {
     if (n_slots == 0) return SD_OK;
+    sd_span sp(c, SD_K_APPEND, st);
     hipLaunchKernelGGL(k_req_append, dim3((unsigned)n_slots), dim3(64), 0, st, d_slot_ids,
                        d_new_tokens, d_new_offsets, c->r_text, c->r_len, c->r_stride,
                        c->cfg.max_ctx_tokens, c->cfg.max_batch_slots, c->cfg.vocab, c->d_err);

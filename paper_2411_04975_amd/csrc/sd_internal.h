@@ -57,6 +57,13 @@ struct sd_ctx {
     double *s_unit_sc = nullptr;
 
     int32_t *d_err = nullptr;        // [SD_DEVERR_N]
+
+    // ---- measurement hooks ---------------------------------------------
+    int prof_mode = 0;
+    hipEvent_t *prof_ev = nullptr;   // [2 * SD_PROF_MAX_SPANS]
+    int prof_kind[SD_PROF_MAX_SPANS];
+    int prof_n = 0;
+    unsigned long long *d_algo_bytes = nullptr;  // [SD_K_COUNT]
     int64_t index_bytes = 0, scratch_bytes = 0;
 };
 
@@ -77,6 +84,29 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
 sd_status sd_accept_impl(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t *d_target,
                          int32_t *d_accept_len, int32_t *d_accept_path, int32_t *d_bonus,
                          hipStream_t st);
+
+// event bracket around one kernel launch when profiling is on
+struct sd_span {
+    sd_ctx *c;
+    hipStream_t st;
+    int slot;
+    sd_span(sd_ctx *ctx, int kind, hipStream_t stream) : c(ctx), st(stream), slot(-1) {
+        if (c->prof_mode && c->prof_n < SD_PROF_MAX_SPANS) {
+            slot = c->prof_n++;
+            c->prof_kind[slot] = kind;
+            (void)hipEventRecord(c->prof_ev[2 * slot], st);
+        }
+    }
+    ~sd_span() {
+        if (slot >= 0) (void)hipEventRecord(c->prof_ev[2 * slot + 1], st);
+    }
+};
+
+#define SD_LAUNCH(c, kind, st, kernel, grid, block, lds, ...)              \
+    do {                                                                    \
+        sd_span sd_sp_(c, kind, st);                                        \
+        hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__);      \
+    } while (0)
 
 static inline int sd_bits_for(uint64_t max_value) {  // bits needed to hold values 0..max_value
     int b = 1;

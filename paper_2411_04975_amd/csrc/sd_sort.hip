@@ -61,7 +61,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t *__res
                                                            int64_t n, int shift,
                                                            uint32_t *__restrict__ tile_hist,
                                                            int64_t ntiles) {
-    __shared__ uint32_t s_cnt[RS_WAVES][RS_BINS];
+    __shared__ volatile uint32_t s_cnt[RS_WAVES][RS_BINS];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     for (int i = tid; i < RS_WAVES * RS_BINS; i += RS_THREADS) (&s_cnt[0][0])[i] = 0;
     __syncthreads();
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t *__res
         bool valid = idx < n;
         uint32_t d = valid ? (uint32_t)((keys[idx] >> shift) & (RS_BINS - 1)) : 0u;
         uint64_t peers = match_digit(d, valid);
-        if (valid && (peers & lt) == 0) s_cnt[w][d] += (uint32_t)__popcll(peers);
+        if (valid && (peers & lt) == 0) s_cnt[w][d] = s_cnt[w][d] + (uint32_t)__popcll(peers);
     }
     __syncthreads();
     uint32_t tot = 0;
@@ -234,6 +234,7 @@ __global__ __launch_bounds__(SC_THREADS) void k_scan_apply(uint32_t *__restrict_
 void sd_scan_inclusive_u32(sd_ctx *c, uint32_t *data, int64_t n, hipStream_t st) {
     if (n <= 0) return;
     int64_t nt = (n + SC_TILE - 1) / SC_TILE;
+    sd_span sp(c, SD_K_SORT_SCAN, st);
     hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, data, n,
                        c->b_partials);
     hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(SC_THREADS), 0, st, c->b_partials, nt);
@@ -246,12 +247,18 @@ int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st) {
     if (n <= 0) return cur;
     int64_t ntiles = (n + RS_TILE - 1) / RS_TILE;
     for (int shift = 0; shift < nbits; shift += RS_BITS) {
-        hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
-                           c->b_keys[cur], n, shift, c->b_hist, ntiles);
+        {
+            sd_span sp(c, SD_K_SORT_HIST, st);
+            hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
+                               c->b_keys[cur], n, shift, c->b_hist, ntiles);
+        }
         sd_scan_inclusive_u32(c, c->b_hist, (int64_t)RS_BINS * ntiles, st);
-        hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
-                           c->b_keys[cur], c->b_vals[cur], c->b_keys[cur ^ 1], c->b_vals[cur ^ 1],
-                           n, shift, c->b_hist, ntiles);
+        {
+            sd_span sp(c, SD_K_SORT_SCATTER, st);
+            hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
+                               c->b_keys[cur], c->b_vals[cur], c->b_keys[cur ^ 1],
+                               c->b_vals[cur ^ 1], n, shift, c->b_hist, ntiles);
+        }
         cur ^= 1;
     }
     return cur;

@@ -37,7 +37,21 @@ struct SpecParams {
     int32_t *unit_tok, *unit_par;
     double *unit_sc;
     int32_t *err;
+    unsigned long long *algo_bytes;
 };
+
+// In the counting variants (STATS) every lane adds up the bytes it asks memory for: 4 per
+// suffix-array word or token, 8 per occurrence record.  Loads that all lanes share are counted
+// once.  The timed variants compile the counters away.
+#define SD_CNT(n) do { if (STATS) nb += (unsigned)(n); } while (0)
+
+template <bool STATS>
+__device__ __forceinline__ void flush_count(unsigned nb, unsigned long long *dst) {
+    if (!STATS) return;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) nb += __shfl_xor(nb, o);
+    if ((threadIdx.x & 63) == 0) atomicAdd(dst, (unsigned long long)nb);
+}
 
 __device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << (threadIdx.x & 63)) - 1ull; }
 
@@ -48,10 +62,13 @@ constexpr int OCC_THREADS = 256;
 constexpr int OCC_LDS_SORT = 2048;
 
 // order of two occurrences by the tokens that follow them (end marker lowest), then by position
-__device__ __forceinline__ bool occ_less(const int32_t *__restrict__ x, int2 a, int2 b, int depth) {
+template <bool STATS>
+__device__ __forceinline__ bool occ_less(const int32_t *__restrict__ x, int2 a, int2 b, int depth,
+                                         unsigned &nb) {
     const int32_t *pa = x + a.x + 1, *pb = x + b.x + 1;
     for (int k = 0; k < depth; k++) {
         int32_t ta = pa[k], tb = pb[k];
+        SD_CNT(8);
         if (ta != tb) return ta < tb;
         if (ta == SD_END_TOKEN) break;
     }
@@ -60,7 +77,8 @@ __device__ __forceinline__ bool occ_less(const int32_t *__restrict__ x, int2 a, 
 
 // bitonic network in its all-ascending form (mirror step, then half-cleaners); positions at or
 // beyond m act as +infinity and are never touched, so m need not be a power of two
-__device__ void occ_sort(int2 *arr, int m, const int32_t *__restrict__ x, int depth) {
+template <bool STATS>
+__device__ void occ_sort(int2 *arr, int m, const int32_t *__restrict__ x, int depth, unsigned &nb) {
     int n2 = 1;
     while (n2 < m) n2 <<= 1;
     for (int k = 2; k <= n2; k <<= 1) {
@@ -69,7 +87,7 @@ __device__ void occ_sort(int2 *arr, int m, const int32_t *__restrict__ x, int de
                 int l = (j == (k >> 1)) ? (i ^ (k - 1)) : (i ^ j);
                 if (l > i && l < m) {
                     int2 a = arr[i], b = arr[l];
-                    if (occ_less(x, b, a, depth)) {
+                    if (occ_less<STATS>(x, b, a, depth, nb)) {
                         arr[i] = b;
                         arr[l] = a;
                     }
@@ -80,6 +98,7 @@ __device__ void occ_sort(int2 *arr, int m, const int32_t *__restrict__ x, int de
     }
 }
 
+template <bool STATS>
 __global__ __launch_bounds__(OCC_THREADS) void k_req_occurrences(SpecParams p,
                                                                  const int32_t *__restrict__ slot_ids) {
     __shared__ int s_m;
@@ -92,6 +111,7 @@ __global__ __launch_bounds__(OCC_THREADS) void k_req_occurrences(SpecParams p,
     const int t = slot_ok ? p.r_len[slot] : 0;
     const int32_t *x = p.r_text + (int64_t)(slot_ok ? slot : 0) * p.r_stride;
     int2 *occ = p.occ + (int64_t)b * p.max_ctx;
+    unsigned nb = 0;
     if (tid == 0) s_m = 0;
     if (tid < 72) s_cnt[tid] = 0;
     __syncthreads();
@@ -101,6 +121,7 @@ __global__ __launch_bounds__(OCC_THREADS) void k_req_occurrences(SpecParams p,
         for (int base = 0; base < t; base += OCC_THREADS) {
             int e = base + tid;
             bool hit = e < t && x[e] == last;
+            if (e < t) SD_CNT(4);
             uint64_t mask = __ballot(hit);
             if (mask) {
                 int leader = __ffsll((unsigned long long)mask) - 1;
@@ -119,6 +140,7 @@ __global__ __launch_bounds__(OCC_THREADS) void k_req_occurrences(SpecParams p,
         int lim = e + 1 < p.P ? e + 1 : p.P;
         int l = 1;
         while (l < lim && x[e - l] == x[t - 1 - l]) l++;
+        SD_CNT(8 * l + 8);
         occ[i].y = l;
         atomicAdd(&s_cnt[l], 1);
     }
@@ -138,12 +160,13 @@ __global__ __launch_bounds__(OCC_THREADS) void k_req_occurrences(SpecParams p,
         if (m <= OCC_LDS_SORT) {
             for (int i = tid; i < m; i += OCC_THREADS) s_sort[i] = occ[i];
             __syncthreads();
-            occ_sort(s_sort, m, x, depth);
+            occ_sort<STATS>(s_sort, m, x, depth, nb);
             for (int i = tid; i < m; i += OCC_THREADS) occ[i] = s_sort[i];
         } else {
-            occ_sort(occ, m, x, depth);
+            occ_sort<STATS>(occ, m, x, depth, nb);
         }
     }
+    flush_count<STATS>(nb, p.algo_bytes + SD_K_OCCURRENCES);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -244,9 +267,10 @@ __device__ void frontier_insert(Frontier &f, bool cand, double sc, int32_t tok, 
 
 // Children of the node [lo, hi) at depth d (its path has d tokens), as frontier candidates with
 // score = ps * (COUNT(child) / COUNT(node)).
+template <bool STATS>
 __device__ void push_children(Frontier &f, const int32_t *__restrict__ sa,
                               const int32_t *__restrict__ text, int32_t lo, int32_t hi, int32_t d,
-                              int32_t parent, double ps, double min_score, int32_t D) {
+                              int32_t parent, double ps, double min_score, int32_t D, unsigned &nb) {
     if (d >= D) return;  // a path of D tokens has no continuation
     const int lane = threadIdx.x & 63;
     const int32_t m = hi - lo;
@@ -255,6 +279,7 @@ __device__ void push_children(Frontier &f, const int32_t *__restrict__ sa,
         const bool in = lane < m;
         int32_t tok = 0x7fffffff;
         if (in) tok = text[(int64_t)sa[lo + lane] + d];
+        if (in) SD_CNT(8);
         int32_t prev = __shfl_up(tok, 1);
         bool start = in && (lane == 0 || tok != prev);
         uint64_t S = __ballot(start);
@@ -280,8 +305,10 @@ __device__ void push_children(Frontier &f, const int32_t *__restrict__ sa,
         const int32_t q = (int32_t)(lo + (in ? k : 0) * stride);
         int32_t tok = 0x7fffffff;
         if (in) tok = text[(int64_t)sa[q] + d];
+        if (in) SD_CNT(8);
         int32_t prevtok = __shfl_up(tok, 1);
         if (lane == 0) prevtok = k == 0 ? (int32_t)0x80000000 : text[(int64_t)sa[q - stride] + d];
+        if (lane == 0 && k != 0) SD_CNT(8);
         const bool first = in && tok >= 0 && tok != prevtok;
         int32_t lb = q, ub = hi;
         if (first) {
@@ -289,6 +316,7 @@ __device__ void push_children(Frontier &f, const int32_t *__restrict__ sa,
                 int32_t l = (int32_t)(q - stride + 1), h = q;
                 while (l < h) {
                     int32_t mid = l + ((h - l) >> 1);
+                    SD_CNT(8);
                     if (text[(int64_t)sa[mid] + d] < tok) l = mid + 1; else h = mid;
                 }
                 lb = l;
@@ -296,6 +324,7 @@ __device__ void push_children(Frontier &f, const int32_t *__restrict__ sa,
             int32_t l = q + 1, h = hi;  // first position after q holding a larger token
             while (l < h) {
                 int32_t mid = l + ((h - l) >> 1);
+                SD_CNT(8);
                 if (text[(int64_t)sa[mid] + d] <= tok) l = mid + 1; else h = mid;
             }
             ub = l;
@@ -306,9 +335,11 @@ __device__ void push_children(Frontier &f, const int32_t *__restrict__ sa,
     }
 }
 
+template <bool STATS>
 __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__restrict__ slot_ids) {
     extern __shared__ double smem[];
     const int lane = threadIdx.x;
+    unsigned nb = 0;
     const int cap = p.max_nodes;
     // LDS carve-up: frontier (score, tok, par, lo, hi, dep) and the tree (score, tok, par)
     double *f_score = smem;
@@ -336,6 +367,8 @@ __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__re
                 // pattern's first token form one bucket; binary search inside it, comparing
                 // the p pattern tokens lane-parallel (lane k holds pattern token k).
                 const int32_t wk = lane < pl ? x[t - pl + lane] : 0;
+                if (lane < pl) SD_CNT(4);
+                if (lane == 0) SD_CNT(8);  // the two bucket bounds
                 const int32_t w0 = __shfl(wk, 0);
                 lo = p.g_bucket[w0 + 1];
                 hi = p.g_bucket[w0 + 2];
@@ -347,6 +380,7 @@ __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__re
                         int32_t mid = l + ((h - l) >> 1);
                         int64_t pos = sa[mid];
                         int32_t tk = lane < pl ? text[pos + lane] : 0;
+                        SD_CNT(lane < pl ? (lane == 0 ? 8 : 4) : 0);
                         uint64_t ne = __ballot(lane < pl && tk != wk);
                         bool less = false;
                         if (ne) {
@@ -361,6 +395,7 @@ __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__re
                         int32_t mid = l + ((h - l) >> 1);
                         int64_t pos = sa[mid];
                         int32_t tk = lane < pl ? text[pos + lane] : 0;
+                        SD_CNT(lane < pl ? (lane == 0 ? 8 : 4) : 0);
                         uint64_t ne = __ballot(lane < pl && tk != wk);
                         bool greater = false;
                         if (ne) {
@@ -385,9 +420,11 @@ __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__re
                 int i = base + lane;
                 int2 o = make_int2(0, 0);
                 if (i < m1) o = occ[i];
+                if (i < m1) SD_CNT(8);
                 bool keep = i < m1 && o.y >= pl;
                 uint64_t mk = __ballot(keep);
                 if (keep) usa[w + __popcll(mk & lanemask_lt())] = o.x - pl + 1;
+                if (keep) SD_CNT(4);
                 w += __popcll(mk);
             }
             __threadfence_block();
@@ -406,7 +443,7 @@ __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__re
         f.score = f_score; f.tok = f_tok; f.par = f_par; f.lo = f_lo; f.hi = f_hi; f.dep = f_dep;
         f.n = 0;
         f.cap = K;
-        push_children(f, sa, text, lo, hi, pl, -1, 1.0, p.min_score, p.D);
+        push_children<STATS>(f, sa, text, lo, hi, pl, -1, 1.0, p.min_score, p.D, nb);
         while (n < K && f.n > 0) {
             Key best = frontier_pick(f, true);
             if (best.s < p.min_score) break;
@@ -425,7 +462,7 @@ __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__re
             total += best.s;
             __syncthreads();
             if (n + 1 < K)  // the last node taken cannot contribute further nodes
-                push_children(f, sa, text, blo, bhi, bdep, n, best.s, p.min_score, p.D);
+                push_children<STATS>(f, sa, text, blo, bhi, bdep, n, best.s, p.min_score, p.D, nb);
             n++;
         }
     }
@@ -434,21 +471,27 @@ __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__re
         p.unit_tok[uidx * cap + i] = t_tok[i];
         p.unit_par[uidx * cap + i] = t_par[i];
         p.unit_sc[uidx * cap + i] = t_score[i];
+        SD_CNT(16);
     }
     if (lane == 0) {
         p.unit_n[uidx] = n;
         p.unit_score[uidx] = total;
+        SD_CNT(12);
     }
+    flush_count<STATS>(nb, p.algo_bytes + SD_K_EXPAND);
 }
 
+template <bool STATS>
 __global__ __launch_bounds__(64) void k_select(SpecParams p, sd_trees out) {
     const int lane = threadIdx.x, b = blockIdx.x;
+    unsigned nb = 0;
     const int units = 2 * p.P, cap = p.max_nodes;
     // strictly-greater scan in unit order = the earliest unit among those with the top score
     double bs = 0.0;
     int bu = -1;
     for (int u = lane; u < units; u += 64) {
         double s = p.unit_score[(int64_t)b * units + u];
+        SD_CNT(8);
         if (s > bs) { bs = s; bu = u; }
     }
 #pragma unroll
@@ -466,13 +509,16 @@ __global__ __launch_bounds__(64) void k_select(SpecParams p, sd_trees out) {
         out.d_tokens[ob + i] = live ? p.unit_tok[ub + i] : -1;
         out.d_parents[ob + i] = live ? p.unit_par[ub + i] : -1;
         out.d_scores[ob + i] = live ? p.unit_sc[ub + i] : 0.0;
+        SD_CNT(live ? 32 : 16);
     }
     if (lane == 0) {
         out.d_n_nodes[b] = n;
         out.d_tree_score[b] = bu >= 0 ? bs : 0.0;
         out.d_match_len[b] = bu >= 0 ? bu % p.P + 1 : 0;
         out.d_source[b] = bu >= 0 ? bu / p.P : -1;
+        SD_CNT(24);
     }
+    flush_count<STATS>(nb, p.algo_bytes + SD_K_SELECT);
 }
 
 __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nodes,
@@ -524,20 +570,33 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     p.occ = c->s_occ; p.occ_n = c->s_occ_n; p.cntL = c->s_cntL; p.unit_sa = c->s_unit_sa;
     p.unit_n = c->s_unit_n; p.unit_score = c->s_unit_score; p.unit_tok = c->s_unit_tok;
     p.unit_par = c->s_unit_par; p.unit_sc = c->s_unit_sc; p.err = c->d_err;
-    hipLaunchKernelGGL(k_req_occurrences, dim3((unsigned)batch), dim3(OCC_THREADS), 0, st, p,
-                       d_slot_ids);
+    p.algo_bytes = c->d_algo_bytes;
+    const bool stats = c->prof_mode == 2;
     const size_t lds = (size_t)c->max_nodes * (2 * sizeof(double) + 7 * sizeof(int32_t));
-    hipLaunchKernelGGL(k_expand, dim3((unsigned)(batch * 2 * c->cfg.P)), dim3(64), lds, st, p,
-                       d_slot_ids);
-    hipLaunchKernelGGL(k_select, dim3((unsigned)batch), dim3(64), 0, st, p, out);
+    const dim3 g_units((unsigned)(batch * 2 * c->cfg.P)), g_req((unsigned)batch);
+    {
+        sd_span sp(c, SD_K_OCCURRENCES, st);
+        if (stats) hipLaunchKernelGGL(k_req_occurrences<true>, g_req, dim3(OCC_THREADS), 0, st, p, d_slot_ids);
+        else hipLaunchKernelGGL(k_req_occurrences<false>, g_req, dim3(OCC_THREADS), 0, st, p, d_slot_ids);
+    }
+    {
+        sd_span sp(c, SD_K_EXPAND, st);
+        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, dim3(64), lds, st, p, d_slot_ids);
+        else hipLaunchKernelGGL(k_expand<false>, g_units, dim3(64), lds, st, p, d_slot_ids);
+    }
+    {
+        sd_span sp(c, SD_K_SELECT, st);
+        if (stats) hipLaunchKernelGGL(k_select<true>, g_req, dim3(64), 0, st, p, out);
+        else hipLaunchKernelGGL(k_select<false>, g_req, dim3(64), 0, st, p, out);
+    }
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
 sd_status sd_accept_impl(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t *d_target,
                          int32_t *d_accept_len, int32_t *d_accept_path, int32_t *d_bonus,
                          hipStream_t st) {
-    (void)c;
     if (batch == 0) return SD_OK;
+    sd_span sp(c, SD_K_ACCEPT, st);
     hipLaunchKernelGGL(k_accept, dim3((unsigned)batch), dim3(64), 0, st, trees.d_n_nodes,
                        trees.d_tokens, trees.d_parents, trees.max_nodes, d_target, d_accept_len,
                        d_accept_path, d_bonus);

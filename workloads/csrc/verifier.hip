@@ -1,0 +1,92 @@
+// Synthetic serving-loop glue for benchmarks and tests: a simulated greedy target model and
+// the collection of accepted tokens.  This is workload code, not part of the draft-generation
+// library: it plays the role of the LLM verifier (Section 4.1, "Simulated Ablations": a
+// drafted token is accepted iff it equals the ground-truth response token at that position).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+// target[b][0] = future[b][pos[b]]; target[b][1+j] = future[b][pos[b] + depth(j)], where
+// depth(j) is the number of draft nodes on the path from the tree root to node j (>= 1).
+__global__ __launch_bounds__(64) void k_targets(const int32_t *__restrict__ n_nodes,
+                                                const int32_t *__restrict__ parents, int max_nodes,
+                                                const int32_t *__restrict__ future,
+                                                int64_t future_stride,
+                                                const int32_t *__restrict__ pos,
+                                                int32_t *__restrict__ target) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int n = n_nodes[b];
+    const int32_t *par = parents + (int64_t)b * max_nodes;
+    const int32_t *fut = future + (int64_t)b * future_stride + pos[b];
+    int32_t *tgt = target + (int64_t)b * (max_nodes + 1);
+    if (lane == 0) tgt[0] = fut[0];
+    for (int j = lane; j < max_nodes; j += 64) {
+        int32_t v = fut[0];
+        if (j < n) {
+            int d = 1;
+            for (int q = par[j]; q >= 0; q = par[q]) d++;
+            v = fut[d];
+        }
+        tgt[1 + j] = v;
+    }
+}
+
+// one workgroup: new_offsets = exclusive scan of (accept_len + 1); new tokens of request b are
+// its accepted draft tokens followed by the bonus token; pos[b] += accept_len[b] + 1.
+__global__ __launch_bounds__(1024) void k_collect(const int32_t *__restrict__ tokens,
+                                                  int max_nodes,
+                                                  const int32_t *__restrict__ accept_len,
+                                                  const int32_t *__restrict__ accept_path,
+                                                  const int32_t *__restrict__ bonus, int batch,
+                                                  int32_t *__restrict__ new_tokens,
+                                                  int32_t *__restrict__ new_offsets,
+                                                  int32_t *__restrict__ pos) {
+    __shared__ int32_t s_off[1025];
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+        int acc = 0;
+        for (int b = 0; b < batch; b++) {
+            s_off[b] = acc;
+            acc += accept_len[b] + 1;
+        }
+        s_off[batch] = acc;
+    }
+    __syncthreads();
+    for (int b = tid; b <= batch; b += 1024) new_offsets[b] = s_off[b];
+    for (int b = tid; b < batch; b += 1024) {
+        const int L = accept_len[b];
+        int32_t *dst = new_tokens + s_off[b];
+        for (int i = 0; i < L; i++)
+            dst[i] = tokens[(int64_t)b * max_nodes + accept_path[(int64_t)b * max_nodes + i]];
+        dst[L] = bonus[b];
+        pos[b] += L + 1;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+// all pointers are device pointers; batch <= 1024 for wl_collect
+int wl_targets(const int32_t *d_n_nodes, const int32_t *d_parents, int max_nodes,
+               const int32_t *d_future, int64_t future_stride, const int32_t *d_pos, int batch,
+               int32_t *d_target, void *stream) {
+    if (batch <= 0) return 0;
+    hipLaunchKernelGGL(k_targets, dim3((unsigned)batch), dim3(64), 0, (hipStream_t)stream, d_n_nodes,
+                       d_parents, max_nodes, d_future, future_stride, d_pos, d_target);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+int wl_collect(const int32_t *d_tokens, int max_nodes, const int32_t *d_accept_len,
+               const int32_t *d_accept_path, const int32_t *d_bonus, int batch,
+               int32_t *d_new_tokens, int32_t *d_new_offsets, int32_t *d_pos, void *stream) {
+    if (batch <= 0) return 0;
+    if (batch > 1024) return 2;
+    hipLaunchKernelGGL(k_collect, dim3(1), dim3(1024), 0, (hipStream_t)stream, d_tokens, max_nodes,
+                       d_accept_len, d_accept_path, d_bonus, batch, d_new_tokens, d_new_offsets,
+                       d_pos);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
+
+}  // extern "C"
