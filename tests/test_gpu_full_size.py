@@ -1,0 +1,88 @@
+"""GPU parity at the benchmark configurations' full sizes, in the launch configuration
+bench.py times (whole batch, full corpus).  The oracle checks a sample of requests one by one
+(its global trie holds exactly the suffixes those requests can reach); properties that hold
+at any size are checked for every request."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from tests import parity
+from workloads import make_workload
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_properties(got, w):
+    """Invariants of any valid result (Section 3 definitions + the size cap)."""
+    n, ml = got["n_nodes"], got["match_len"]
+    assert np.all(n <= np.floor(w.alpha * ml)) and np.all(n <= w.max_nodes) and np.all(n >= 0)
+    assert np.all((n == 0) == (got["source"] == -1))
+    idx = np.arange(w.max_nodes)[None, :]
+    live = idx < n[:, None]
+    assert np.all(got["tokens"][~live] == -1) and np.all(got["parents"][~live] == -1)
+    assert np.all(got["scores"][~live] == 0.0)
+    assert np.all(got["parents"][live] < np.broadcast_to(idx, live.shape)[live])
+    assert np.all(got["parents"][live] >= -1)
+    sc = got["scores"]
+    assert np.all(sc[live] >= w.min_score) and np.all(sc[live] <= 1.0)
+    # best-first on a monotone tree: scores never increase in insertion order
+    assert np.all((sc[:, 1:] <= sc[:, :-1]) | ~live[:, 1:])
+    for b in range(len(n)):
+        k = int(n[b])
+        assert float(np.cumsum(sc[b, :k])[-1] if k else 0.0) == pytest.approx(
+            got["tree_score"][b], rel=1e-12)
+        assert len({(int(got["parents"][b, j]), int(got["tokens"][b, j])) for j in range(k)}) == k
+        d = parity.node_depths(got["parents"][b], k)
+        assert k == 0 or d.max() <= w.D - ml[b]
+
+
+def _run_full(name, sample, seed=0):
+    w = make_workload(name, seed=seed)
+    docs = w.docs()
+    B = w.batch
+    contexts = [w.contexts[b] for b in range(B)]
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, w.ctx_len + 128,
+                       len(w.corpus) + len(docs))
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), contexts)
+        got = g.speculate(range(B))
+        st = g.stats()
+        assert st["err_bad_token"] == 0 and st["err_bad_slot"] == 0
+        _check_properties(got, w)
+        rng = np.random.default_rng(1)
+        pick = sorted(rng.choice(B, size=min(sample, B), replace=False).tolist())
+        sub = [contexts[b] for b in pick]
+        tg = parity.oracle_global_trie(docs, w.D, w.vocab, sub, w.P)
+        want = parity.oracle_speculate_batch(tg, sub, w.D, w.P, w.alpha, w.min_score, w.max_nodes)
+        got_sub = {k: v[pick] for k, v in got.items()}
+        bad = parity.compare_trees(got_sub, want, name)
+        assert not bad, "\n".join(bad)
+        # acceptance on the whole batch, oracle on the sample
+        tgt = parity.targets_from_future(got, w.future, w.max_nodes)
+        al, ap, bo = g.accept(tgt)
+        for i, b in enumerate(pick):
+            k = int(want["n_nodes"][i])
+            L, path, bonus = oracle.accept(want["tokens"][i, :k], want["parents"][i, :k], tgt[b])
+            assert al[b] == L and bo[b] == bonus and list(ap[b, :L]) == list(path)
+        assert np.all(al <= got["n_nodes"])
+        return got, want
+    finally:
+        g.close()
+
+
+def test_agentic_full():
+    got, want = _run_full("agentic", sample=64)
+    assert (got["n_nodes"] > 0).mean() > 0.5
+
+
+def test_large_full_sampled():
+    got, want = _run_full("large", sample=24)
+    assert (got["n_nodes"] > 0).mean() > 0.5 and got["n_nodes"].max() > 32
+
+
+def test_lowrep_full_sampled():
+    got, want = _run_full("lowrep", sample=24)
+    assert (got["n_nodes"] > 0).mean() > 0.3
