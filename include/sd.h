@@ -176,7 +176,7 @@ sd_status sd_get_stats(sd_ctx *ctx, sd_stats *host_out);
 enum {
     SD_K_OCCURRENCES = 0, SD_K_EXPAND = 1, SD_K_SELECT = 2, SD_K_ACCEPT = 3, SD_K_APPEND = 4,
     SD_K_REQ_BUILD = 5, SD_K_SORT_HIST = 6, SD_K_SORT_SCAN = 7, SD_K_SORT_SCATTER = 8,
-    SD_K_BUILD_OTHER = 9, SD_K_COUNT = 10
+    SD_K_BUILD_OTHER = 9, SD_K_EXPAND_REQ = 10, SD_K_COUNT = 11
 };
 #define SD_PROF_MAX_SPANS 8192
 typedef struct {
@@ -186,6 +186,13 @@ typedef struct {
 } sd_profile;
 sd_status sd_debug_profile(sd_ctx *ctx, int32_t mode);
 sd_status sd_debug_profile_read(sd_ctx *ctx, sd_profile *host_out);
+
+/* Latency profile: after an sd_speculate call made with profiling mode 2, copies four
+ * wall-clock marks per (request, index, p) unit -- ticks since the unit started at the end of
+ * its set-up, of MatchPattern, of the first child enumeration, and of the whole unit; unit
+ * index = (b * 2 + index) * P + (p - 1), `count` = 4 * units -- and the tick rate in kHz.
+ * Synchronises. */
+sd_status sd_debug_read_unit_ticks(sd_ctx *ctx, uint32_t *h_ticks, int64_t count, int32_t *khz);
 
 /* Test hook: synchronises, then copies the global index to host buffers:
  * the laid-out text (documents back to back, -1 after each) and the suffix

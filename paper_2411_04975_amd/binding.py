@@ -51,12 +51,12 @@ class _Stats(C.Structure):
 
 
 KERNEL_NAMES = ["occurrences", "expand", "select", "accept", "append", "req_build", "sort_hist",
-                "sort_scan", "sort_scatter", "build_other"]
+                "sort_scan", "sort_scatter", "build_other", "expand_req"]
 
 
 class _Profile(C.Structure):
-    _fields_ = [("launches", C.c_int64 * 10), ("ms", C.c_double * 10),
-                ("algo_bytes", C.c_int64 * 10)]
+    _fields_ = [("launches", C.c_int64 * 11), ("ms", C.c_double * 11),
+                ("algo_bytes", C.c_int64 * 11)]
 
 
 _lib = None
@@ -95,6 +95,8 @@ def _load():
     L.sd_debug_profile.argtypes = [vp, C.c_int32]
     L.sd_debug_profile_read.restype = C.c_int
     L.sd_debug_profile_read.argtypes = [vp, C.POINTER(_Profile)]
+    L.sd_debug_read_unit_ticks.restype = C.c_int
+    L.sd_debug_read_unit_ticks.argtypes = [vp, vp, C.c_int64, C.POINTER(C.c_int32)]
     L.sd_debug_read_global.restype = C.c_int
     L.sd_debug_read_global.argtypes = [vp, vp, vp, C.c_int64, C.POINTER(C.c_int64)]
     _lib = L
@@ -262,3 +264,15 @@ def sd_debug_profile_read(ctx: _Ctx) -> dict:
     _check(ctx, _load().sd_debug_profile_read(ctx.handle, C.byref(pr)))
     return {n: dict(launches=int(pr.launches[i]), ms=float(pr.ms[i]),
                     algo_bytes=int(pr.algo_bytes[i])) for i, n in enumerate(KERNEL_NAMES)}
+
+
+def sd_debug_read_unit_ticks(ctx: _Ctx, batch: int):
+    """Microseconds since unit start at four marks (set-up, match, root children, end) for each
+    unit of the last counted sd_speculate: array [batch, 2, P, 4]."""
+    import numpy as np
+    n = batch * 2 * ctx.cfg.P * 4
+    t = np.zeros(n, np.uint32)
+    khz = C.c_int32()
+    _check(ctx, _load().sd_debug_read_unit_ticks(ctx.handle, t.ctypes.data_as(C.c_void_p), n,
+                                                 C.byref(khz)))
+    return t.reshape(batch, 2, ctx.cfg.P, 4).astype(np.float64) * (1e3 / max(khz.value, 1))

@@ -30,13 +30,17 @@ bool dev_alloc(T **p, int64_t count, int64_t *acc) {
 }
 
 void free_all(sd_ctx *c) {
-    void *ptrs[] = {c->g_text, c->g_sa, c->g_bucket, c->b_keys[0], c->b_keys[1], c->b_vals[0],
+    void *ptrs[] = {c->g_text, c->g_sa, c->g_bucket, c->g_tok1, c->b_keys[0], c->b_keys[1], c->b_vals[0],
                     c->b_vals[1], c->b_rank, c->b_flags, c->b_hist, c->b_partials, c->r_text,
                     c->r_len, c->s_occ, c->s_occ_n, c->s_cntL, c->s_unit_sa, c->s_unit_n,
-                    c->s_unit_score, c->s_unit_tok, c->s_unit_par, c->s_unit_sc, c->d_err};
+                    c->s_unit_score, c->s_unit_tok, c->s_unit_par, c->s_unit_sc, c->d_err,
+                    c->s_unit_ticks};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (c->d_algo_bytes) (void)hipFree(c->d_algo_bytes);
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    if (c->aux_stream) (void)hipStreamDestroy(c->aux_stream);
     if (c->prof_ev) {
         for (int i = 0; i < 2 * SD_PROF_MAX_SPANS; i++)
             if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
@@ -85,6 +89,7 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     int64_t *ib = &c->index_bytes, *sb = &c->scratch_bytes;
     ok = ok && dev_alloc(&c->g_text, cap + SD_TEXT_PAD + 64, ib);
     ok = ok && dev_alloc(&c->g_sa, cap, ib);
+    ok = ok && dev_alloc(&c->g_tok1, cap, ib);
     ok = ok && dev_alloc(&c->g_bucket, (int64_t)cfg->vocab + 2, ib);
     ok = ok && dev_alloc(&c->b_keys[0], cap, sb) && dev_alloc(&c->b_keys[1], cap, sb);
     ok = ok && dev_alloc(&c->b_vals[0], cap, sb) && dev_alloc(&c->b_vals[1], cap, sb);
@@ -100,11 +105,19 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     ok = ok && dev_alloc(&c->s_unit_par, B * 2 * P * c->max_nodes, sb);
     ok = ok && dev_alloc(&c->s_unit_sc, B * 2 * P * c->max_nodes, sb);
     ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb);
+    ok = ok && dev_alloc(&c->s_unit_ticks, B * 2 * P * 4, sb);
     ok = ok && dev_alloc(&c->d_algo_bytes, SD_K_COUNT, sb);
     if (!ok) {
         free_all(c);
         delete c;
         return SD_ERR_OOM;
+    }
+    if (hipStreamCreateWithFlags(&c->aux_stream, hipStreamNonBlocking) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+        free_all(c);
+        delete c;
+        return SD_ERR_HIP;
     }
     // empty global index, empty contexts, clear flags
     sd_fill_i32(c->g_text, SD_TEXT_PAD, SD_END_TOKEN, nullptr);
@@ -250,6 +263,22 @@ sd_status sd_debug_profile_read(sd_ctx *c, sd_profile *o) {
         return fail(c, SD_ERR_HIP, "hipMemcpy");
     for (int k = 0; k < SD_K_COUNT; k++) o->algo_bytes[k] = (int64_t)ab[k];
     if (hipMemset(c->d_algo_bytes, 0, sizeof(ab)) != hipSuccess) return fail(c, SD_ERR_HIP, "hipMemset");
+    return SD_OK;
+}
+
+sd_status sd_debug_read_unit_ticks(sd_ctx *c, uint32_t *h_ticks, int64_t count, int32_t *khz) {
+    if (!c || !h_ticks || !khz || count < 0) return SD_ERR_INVALID_ARG;
+    if (count > (int64_t)c->cfg.max_batch_slots * 2 * c->cfg.P * 4)
+        return fail(c, SD_ERR_CAPACITY, "more units than the context holds");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
+    if (hipDeviceSynchronize() != hipSuccess) return fail(c, SD_ERR_HIP, "device synchronize failed");
+    int rate = 0;
+    if (hipDeviceGetAttribute(&rate, hipDeviceAttributeWallClockRate, c->cfg.device) != hipSuccess)
+        return fail(c, SD_ERR_HIP, "hipDeviceGetAttribute");
+    *khz = rate;
+    if (count && hipMemcpy(h_ticks, c->s_unit_ticks, (size_t)count * sizeof(uint32_t),
+                           hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(c, SD_ERR_HIP, "hipMemcpy");
     return SD_OK;
 }
 

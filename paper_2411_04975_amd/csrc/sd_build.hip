@@ -87,10 +87,18 @@ __global__ __launch_bounds__(TB) void k_round_keys(const uint32_t *__restrict__ 
     keys[i] = (r1 << rank_bits) | r2;
 }
 
-__global__ __launch_bounds__(TB) void k_copy_sa(const uint32_t *__restrict__ vals, int64_t N,
-                                                int32_t *__restrict__ sa) {
+// final suffix array plus the second-token column: tok1[i] = second token of suffix i.  Inside
+// the bucket of a first token the column is sorted, so the second pattern token is located by a
+// coalesced scan of the column instead of dependent (suffix array -> text) probes.
+__global__ __launch_bounds__(TB) void k_finish_sa(const uint32_t *__restrict__ vals,
+                                                  const int32_t *__restrict__ text, int64_t N,
+                                                  int32_t *__restrict__ sa,
+                                                  int32_t *__restrict__ tok1) {
     int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
-    if (i < N) sa[i] = (int32_t)vals[i];
+    if (i >= N) return;
+    uint32_t p = vals[i];
+    sa[i] = (int32_t)p;
+    tok1[i] = text[(int64_t)p + 1];
 }
 
 // bucket[c] = first index whose suffix starts with token code (token + 1) >= c
@@ -210,7 +218,8 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
             cur = sd_sort_pairs(c, N, 2 * rank_bits, cur, st);
             h *= 2;
         }
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_copy_sa, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], N, c->g_sa);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_finish_sa, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur],
+                  c->g_text, N, c->g_sa, c->g_tok1);
     }
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, N, vocab, c->g_bucket);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;

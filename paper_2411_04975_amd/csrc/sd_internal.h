@@ -27,6 +27,7 @@ struct sd_ctx {
     int32_t *g_text = nullptr;
     int32_t *g_sa = nullptr;
     int32_t *g_bucket = nullptr;
+    int32_t *g_tok1 = nullptr;   // g_tok1[i] = g_text[g_sa[i] + 1]: second token of suffix i
     int64_t g_cap = 0;       // capacity in positions (tokens + documents)
     int64_t g_N = 0;         // positions in use
     int64_t g_tokens = 0, g_docs = 0;
@@ -55,8 +56,14 @@ struct sd_ctx {
     int32_t *s_unit_tok = nullptr;   // [B][2P][max_nodes]
     int32_t *s_unit_par = nullptr;
     double *s_unit_sc = nullptr;
+    uint32_t *s_unit_ticks = nullptr;  // [B][2P][4], written by the counting kernel variants
 
     int32_t *d_err = nullptr;        // [SD_DEVERR_N]
+
+    // second stream + events: lets the request-context scan of sd_speculate overlap with the
+    // global-index units (default priority; joined back before the call's last kernels)
+    hipStream_t aux_stream = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
 
     // ---- measurement hooks ---------------------------------------------
     int prof_mode = 0;

@@ -24,7 +24,7 @@
 namespace {
 
 struct SpecParams {
-    const int32_t *g_text, *g_sa, *g_bucket;
+    const int32_t *g_text, *g_sa, *g_bucket, *g_tok1;
     int32_t g_N;
     const int32_t *r_text, *r_len;
     int64_t r_stride;
@@ -38,6 +38,7 @@ struct SpecParams {
     double *unit_sc;
     int32_t *err;
     unsigned long long *algo_bytes;
+    uint32_t *unit_ticks;  // counting variants only: wall-clock ticks each unit took
 };
 
 // In the counting variants (STATS) every lane adds up the bytes it asks memory for: 4 per
@@ -116,19 +117,41 @@ __global__ __launch_bounds__(OCC_THREADS) void k_req_occurrences(SpecParams p,
     if (tid < 72) s_cnt[tid] = 0;
     __syncthreads();
     if (t > 0) {
+        // Coalesced scan, 16 tokens per thread and round (four 16-byte loads in flight).  Tokens
+        // past the context end are end markers, which never equal the last token, so the tail
+        // needs no bounds test; rows start 256-byte aligned.
         const int32_t last = x[t - 1];
-        const uint64_t lt = lanemask_lt();
-        for (int base = 0; base < t; base += OCC_THREADS) {
-            int e = base + tid;
-            bool hit = e < t && x[e] == last;
-            if (e < t) SD_CNT(4);
-            uint64_t mask = __ballot(hit);
-            if (mask) {
-                int leader = __ffsll((unsigned long long)mask) - 1;
-                int off = 0;
-                if (lane == leader) off = atomicAdd(&s_m, __popcll(mask));
-                off = __shfl(off, leader);
-                if (hit) occ[off + __popcll(mask & lt)].x = e;
+        const int4 *x4 = reinterpret_cast<const int4 *>(x);
+        const int nq = (t + 3) >> 2;
+        for (int q0 = 0; q0 < nq; q0 += 4 * OCC_THREADS) {
+            int4 v[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                int q = q0 + k * OCC_THREADS + tid;
+                v[k] = q < nq ? x4[q] : make_int4(-1, -1, -1, -1);
+                if (q < nq) SD_CNT(16);
+            }
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const int e0 = 4 * (q0 + k * OCC_THREADS + tid);
+                const int h0 = v[k].x == last, h1 = v[k].y == last, h2 = v[k].z == last,
+                          h3 = v[k].w == last;
+                const int nh = h0 + h1 + h2 + h3;
+                if (__ballot(nh > 0)) {
+                    int inc = nh;  // inclusive prefix over the lanes of the wave
+#pragma unroll
+                    for (int o = 1; o < 64; o <<= 1) {
+                        int u = __shfl_up(inc, o);
+                        if (lane >= o) inc += u;
+                    }
+                    int off = 0;
+                    if (lane == 63) off = atomicAdd(&s_m, inc);
+                    off = __shfl(off, 63) + inc - nh;
+                    if (h0) occ[off++].x = e0;
+                    if (h1) occ[off++].x = e0 + 1;
+                    if (h2) occ[off++].x = e0 + 2;
+                    if (h3) occ[off++].x = e0 + 3;
+                }
             }
         }
     }
@@ -172,6 +195,15 @@ __global__ __launch_bounds__(OCC_THREADS) void k_req_occurrences(SpecParams p,
 // ------------------------------------------------------------------------------------------
 // expansion
 // ------------------------------------------------------------------------------------------
+// All cross-lane traffic of a unit stays inside one wavefront.  The LDS operations of a wave
+// are issued and completed in order, so what one lane wrote is seen by a later read of another
+// lane without a hardware barrier; wsync() only stops the compiler from moving LDS accesses
+// across it.
+__device__ __forceinline__ void wsync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 struct Key {
     double s;
     int32_t tok, par, idx;  // idx < 0: no entry
@@ -193,8 +225,34 @@ __device__ __forceinline__ Key key_shfl_xor(const Key &k, int o) {
     return r;
 }
 
-// wave-wide best (want_best) or worst entry; every lane returns the same key
-__device__ __forceinline__ Key wave_pick(Key mine, bool want_best) {
+struct Frontier {
+    double *score;
+    int32_t *tok, *par, *lo, *hi, *dep;
+    int n, cap;
+};
+
+// Best (want_best) or worst entry of the frontier, slot `skip` left out; every lane returns
+// the same key.  Small frontiers (the usual case) are scanned by all lanes alike with
+// broadcast LDS reads; larger ones take one entry per lane and a butterfly.
+__device__ __forceinline__ Key frontier_pick(const Frontier &f, bool want_best, int skip) {
+    const int lane = threadIdx.x & 63;
+    Key mine;
+    mine.idx = -1; mine.s = 0.0; mine.tok = 0; mine.par = 0;
+    if (f.n <= 6) {
+        for (int i = 0; i < f.n; i++) {
+            if (i == skip) continue;
+            Key k;
+            k.s = f.score[i]; k.tok = f.tok[i]; k.par = f.par[i]; k.idx = i;
+            if (mine.idx < 0 || (want_best ? key_better(k, mine) : key_better(mine, k))) mine = k;
+        }
+        return mine;
+    }
+    for (int i = lane; i < f.n; i += 64) {
+        if (i == skip) continue;
+        Key k;
+        k.s = f.score[i]; k.tok = f.tok[i]; k.par = f.par[i]; k.idx = i;
+        if (mine.idx < 0 || (want_best ? key_better(k, mine) : key_better(mine, k))) mine = k;
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
         Key other = key_shfl_xor(mine, o);
@@ -207,43 +265,44 @@ __device__ __forceinline__ Key wave_pick(Key mine, bool want_best) {
     return mine;
 }
 
-struct Frontier {
-    double *score;
-    int32_t *tok, *par, *lo, *hi, *dep;
-    int n, cap;
-};
-
-__device__ __forceinline__ Key frontier_pick(const Frontier &f, bool want_best) {
-    const int lane = threadIdx.x & 63;
-    Key mine;
-    mine.idx = -1; mine.s = 0.0; mine.tok = 0; mine.par = 0;
-    for (int i = lane; i < f.n; i += 64) {
-        Key k;
-        k.s = f.score[i]; k.tok = f.tok[i]; k.par = f.par[i]; k.idx = i;
-        if (mine.idx < 0 || (want_best ? key_better(k, mine) : key_better(mine, k))) mine = k;
+// close the slot freed by the node just taken: the last entry moves into it
+__device__ __forceinline__ void frontier_close(Frontier &f, int hole) {
+    if (hole < 0) return;
+    const int last = f.n - 1;
+    if (hole != last && (threadIdx.x & 63) == 0) {
+        f.score[hole] = f.score[last]; f.tok[hole] = f.tok[last]; f.par[hole] = f.par[last];
+        f.lo[hole] = f.lo[last]; f.hi[hole] = f.hi[last]; f.dep[hole] = f.dep[last];
     }
-    return wave_pick(mine, want_best);
+    f.n = last;
+    wsync();
 }
 
-// Add the candidates held by the lanes with `cand` set.  The frontier keeps at most `cap`
-// entries: a candidate that does not rank among the best `cap` can never be selected, because
-// at most `cap` more nodes are ever taken from it.
-__device__ void frontier_insert(Frontier &f, bool cand, double sc, int32_t tok, int32_t par,
-                                int32_t lo, int32_t hi, int32_t dep) {
+// Add the candidates held by the lanes with `cand` set; `hole` (>= 0) is the slot of the node
+// just taken, which the first candidate reuses.  The frontier keeps at most `cap` entries: a
+// candidate that does not rank among the best `cap` can never be selected, because at most
+// `cap` more nodes are ever taken from it.
+__device__ void frontier_put(Frontier &f, int hole, bool cand, double sc, int32_t tok, int32_t par,
+                             int32_t lo, int32_t hi, int32_t dep) {
     const int lane = threadIdx.x & 63;
     uint64_t C = __ballot(cand);
-    if (C == 0) return;
-    int nc = __popcll(C);
-    if (f.n + nc <= f.cap) {
+    if (C == 0) {
+        frontier_close(f, hole);
+        return;
+    }
+    const int nc = __popcll(C);
+    const int stay = f.n - (hole >= 0 ? 1 : 0);
+    if (stay + nc <= f.cap) {
         if (cand) {
-            int s = f.n + __popcll(C & lanemask_lt());
+            int j = __popcll(C & lanemask_lt());
+            int s = hole >= 0 ? (j == 0 ? hole : f.n + j - 1) : f.n + j;
             f.score[s] = sc; f.tok[s] = tok; f.par[s] = par; f.lo[s] = lo; f.hi[s] = hi;
             f.dep[s] = dep;
         }
-        f.n += nc;
-        __syncthreads();
+        f.n = stay + nc;
+        wsync();
         return;
     }
+    frontier_close(f, hole);
     while (C) {
         int src = __ffsll((unsigned long long)C) - 1;
         C &= C - 1;
@@ -254,31 +313,92 @@ __device__ void frontier_insert(Frontier &f, bool cand, double sc, int32_t tok, 
         if (f.n < f.cap) {
             s = f.n++;
         } else {
-            Key worst = frontier_pick(f, false);
+            Key worst = frontier_pick(f, false, -1);
             if (key_better(nk, worst)) s = worst.idx;
         }
         if (s >= 0 && lane == 0) {
             f.score[s] = nk.s; f.tok[s] = nk.tok; f.par[s] = nk.par; f.lo[s] = nlo; f.hi[s] = nhi;
             f.dep[s] = ndep;
         }
-        __syncthreads();
+        wsync();
     }
 }
 
+// LDS staging of one narrow part of a suffix list: the positions of up to 64 consecutive
+// suffixes and, per suffix, a window of W consecutive tokens starting at depth cb[slot].
+// Sibling branches of the speculation tree are disjoint suffix ranges and a suffix is only
+// ever asked for deeper tokens, so each slot's window moves forward only.  With W tokens per
+// slot one coalesced fill serves W levels of the tree: expansion then runs out of LDS.
+constexpr int TC_TOKENS = 512;
+constexpr int CB_NONE = -(1 << 30);
+constexpr int CHAIN_MAX_M = 8;  // widest node the unary-run shortcut looks at
+
+struct Stage {
+    int32_t *pos, *cb, *tc;  // LDS: [64], [64], [TC_TOKENS]
+    int lo, m, wlog;         // staged range [lo, lo + m) of the suffix list, window = 1 << wlog
+};
+
+__device__ __forceinline__ void stage_set_width(Stage &s, int m) {
+    int p2 = 1;
+    while (p2 < m) p2 <<= 1;
+    int w = TC_TOKENS / p2;
+    if (w > 64) w = 64;
+    s.wlog = 31 - __clz(w);
+}
+
+// Stage the node [lo, lo + m) (m <= 64) and make every one of its windows cover depth d.
+// Returns the window base of this lane's suffix (lanes < m).
+__device__ __forceinline__ int stage_node(Stage &sg, const int32_t *__restrict__ sa,
+                                          const int32_t *__restrict__ text, int32_t lo, int32_t m,
+                                          int32_t d) {
+    const int lane = threadIdx.x & 63;
+    const bool in = lane < m;
+    if (!(lo >= sg.lo && lo + m <= sg.lo + sg.m)) {
+        sg.lo = lo;
+        sg.m = m;
+        stage_set_width(sg, m);
+        if (in) {
+            sg.pos[lane] = sa[lo + lane];
+            sg.cb[lane] = CB_NONE;
+        }
+        wsync();
+    }
+    const int slot0 = lo - sg.lo, slot = slot0 + lane;
+    const int W = 1 << sg.wlog;
+    int mycb = in ? sg.cb[slot] : d;
+    const bool miss = in && !(mycb <= d && d < mycb + W);
+    if (__ballot(miss)) {  // move the windows of this node's suffixes to depth d
+        wsync();
+        if (in) sg.cb[slot] = d;
+        const int total = m << sg.wlog;
+        for (int idx = lane; idx < total; idx += 64) {
+            int ii = slot0 + (idx >> sg.wlog), k = idx & (W - 1);
+            sg.tc[(ii << sg.wlog) + k] = text[(int64_t)sg.pos[ii] + d + k];
+        }
+        wsync();
+        mycb = d;
+    }
+    return mycb;
+}
+
 // Children of the node [lo, hi) at depth d (its path has d tokens), as frontier candidates with
-// score = ps * (COUNT(child) / COUNT(node)).
+// score = ps * (COUNT(child) / COUNT(node)).  `hole` is the frontier slot the node came from.
 template <bool STATS>
-__device__ void push_children(Frontier &f, const int32_t *__restrict__ sa,
+__device__ void push_children(Frontier &f, int hole, Stage &sg, const int32_t *__restrict__ sa,
                               const int32_t *__restrict__ text, int32_t lo, int32_t hi, int32_t d,
                               int32_t parent, double ps, double min_score, int32_t D, unsigned &nb) {
-    if (d >= D) return;  // a path of D tokens has no continuation
+    if (d >= D) {  // a path of D tokens has no continuation
+        frontier_close(f, hole);
+        return;
+    }
     const int lane = threadIdx.x & 63;
     const int32_t m = hi - lo;
     const double den = (double)m;
     if (m <= 64) {
         const bool in = lane < m;
+        const int mycb = stage_node(sg, sa, text, lo, m, d);
         int32_t tok = 0x7fffffff;
-        if (in) tok = text[(int64_t)sa[lo + lane] + d];
+        if (in) tok = sg.tc[((lo - sg.lo + lane) << sg.wlog) + (d - mycb)];
         if (in) SD_CNT(8);
         int32_t prev = __shfl_up(tok, 1);
         bool start = in && (lane == 0 || tok != prev);
@@ -286,9 +406,9 @@ __device__ void push_children(Frontier &f, const int32_t *__restrict__ sa,
         uint64_t above = lane == 63 ? 0ull : (S >> (lane + 1));
         int32_t e = above ? lane + 1 + (__ffsll((unsigned long long)above) - 1) : m;
         int32_t c = e - lane;
-        double sc = ps * ((double)c / den);
+        double sc = c == m ? ps : ps * ((double)c / den);  // x / x == 1 and ps * 1 == ps exactly
         bool cand = start && tok >= 0 && sc >= min_score;
-        frontier_insert(f, cand, sc, tok, parent, lo + lane, lo + e, d + 1);
+        frontier_put(f, hole, cand, sc, tok, parent, lo + lane, lo + e, d + 1);
         return;
     }
     // Wide node: a child that can still reach min_score has at least c_min occurrences, so its
@@ -296,6 +416,7 @@ __device__ void push_children(Frontier &f, const int32_t *__restrict__ sa,
     // bracket the run of each distinct probed token by binary search.  The bound is taken a
     // little low (factor 1 - 1e-9) so that rounding can never hide an admissible child; the
     // exact binary64 test below decides.
+    frontier_close(f, hole);
     int64_t stride = (int64_t)floor(min_score * den / ps * (1.0 - 1e-9));
     if (stride < 1) stride = 1;
     const int64_t np = ((int64_t)m + stride - 1) / stride;
@@ -331,90 +452,325 @@ __device__ void push_children(Frontier &f, const int32_t *__restrict__ sa,
         }
         double sc = ps * ((double)(ub - lb) / den);
         bool cand = first && sc >= min_score;
-        frontier_insert(f, cand, sc, tok, parent, lb, ub, d + 1);
+        frontier_put(f, -1, cand, sc, tok, parent, lb, ub, d + 1);
     }
 }
 
+// MatchPattern on a sorted suffix array: narrows [lo, hi), the bucket of the pattern's first
+// token, to the suffixes that start with all pl pattern tokens.  Lower and upper bound are
+// searched together: each step loads both probe suffixes at once, and the two halves of the
+// wave compare one probe each against the pattern (lane k of a half holds pattern token k).
 template <bool STATS>
-__global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__restrict__ slot_ids) {
+__device__ void match_range(const int32_t *__restrict__ sa, const int32_t *__restrict__ text,
+                            int32_t &lo, int32_t &hi, int32_t wk, int pl, unsigned &nb) {
+    const int lane = threadIdx.x & 63;
+    int32_t la = lo, ha = hi, lu = lo, hu = hi;
+    if (pl <= 32) {
+        const int half = lane >> 5, k = lane & 31;
+        const int32_t wq = __shfl(wk, k);
+        const bool act = k < pl;
+        while (la < ha || lu < hu) {
+            const bool doA = la < ha, doB = lu < hu;
+            const int32_t midA = la + ((ha - la) >> 1), midB = lu + ((hu - lu) >> 1);
+            const int64_t posA = doA ? sa[midA] : 0, posB = doB ? sa[midB] : 0;
+            if (lane == 0) SD_CNT(4 * ((int)doA + (int)doB));
+            const bool on = act && (half ? doB : doA);
+            const int32_t tk = on ? text[(half ? posB : posA) + k] : wq;
+            if (on) SD_CNT(4);
+            const uint64_t ne = __ballot(on && tk != wq);
+            const uint32_t neA = (uint32_t)ne, neB = (uint32_t)(ne >> 32);
+            int cA = 0, cB = 0;
+            if (neA) {
+                int fl = __ffs(neA) - 1;
+                cA = __shfl(tk, fl) < __shfl(wq, fl) ? -1 : 1;
+            }
+            if (neB) {
+                int fl = 32 + __ffs(neB) - 1;
+                cB = __shfl(tk, fl) < __shfl(wq, fl) ? -1 : 1;
+            }
+            if (doA) { if (cA < 0) la = midA + 1; else ha = midA; }
+            if (doB) { if (cB <= 0) lu = midB + 1; else hu = midB; }
+        }
+    } else {
+        const bool act = lane < pl;
+        while (la < ha) {  // first suffix whose leading pl tokens are >= the pattern
+            int32_t mid = la + ((ha - la) >> 1);
+            int64_t pos = sa[mid];
+            int32_t tk = act ? text[pos + lane] : 0;
+            SD_CNT(act ? (lane == 0 ? 8 : 4) : 0);
+            uint64_t ne = __ballot(act && tk != wk);
+            bool less = false;
+            if (ne) {
+                int fl = __ffsll((unsigned long long)ne) - 1;
+                less = __shfl(tk, fl) < __shfl(wk, fl);
+            }
+            if (less) la = mid + 1; else ha = mid;
+        }
+        lu = la;
+        while (lu < hu) {  // first suffix whose leading pl tokens are > the pattern
+            int32_t mid = lu + ((hu - lu) >> 1);
+            int64_t pos = sa[mid];
+            int32_t tk = act ? text[pos + lane] : 0;
+            SD_CNT(act ? (lane == 0 ? 8 : 4) : 0);
+            uint64_t ne = __ballot(act && tk != wk);
+            bool greater = false;
+            if (ne) {
+                int fl = __ffsll((unsigned long long)ne) - 1;
+                greater = __shfl(tk, fl) > __shfl(wk, fl);
+            }
+            if (!greater) lu = mid + 1; else hu = mid;
+        }
+    }
+    lo = la;
+    hi = lu;
+}
+
+// Tied single-occurrence chains.  When every frontier entry that shares the top score is a
+// node with one occurrence (at most TIE_MAX of them, all staged), each of them heads a chain
+// whose nodes all keep that score (count ratio 1/1), while everything else in the frontier
+// scores strictly lower.  The greedy rule therefore keeps taking the head with the lowest
+// (token, parent) among these chains until they end or K is reached: a merge that needs no
+// frontier traffic.  Returns false (and changes nothing) if the frontier does not have that form.
+constexpr int TIE_MAX = 4;
+
+template <bool STATS>
+__device__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ text, double s,
+                            int K, int D, int &n, double &total, int32_t *t_tok, int32_t *t_par,
+                            double *t_score, unsigned &nb) {
+    const int lane = threadIdx.x & 63;
+    if (f.n > 64) return false;
+    const bool have = lane < f.n;
+    const bool tie = have && f.score[lane] == s;
+    const int32_t mylo = have ? f.lo[lane] : 0, myhi = have ? f.hi[lane] : 0;
+    const bool fit = myhi - mylo == 1 && mylo >= sg.lo && mylo < sg.lo + sg.m;
+    const uint64_t T = __ballot(tie);
+    const int j = __popcll(T);
+    if (j > TIE_MAX || __ballot(tie && !fit)) return false;
+    // chain heads into uniform registers
+    int32_t ctok[TIE_MAX], cpar[TIE_MAX], cdep[TIE_MAX], cslot[TIE_MAX];
+    {
+        uint64_t rest = T;
+#pragma unroll
+        for (int c = 0; c < TIE_MAX; c++) {
+            ctok[c] = 0; cpar[c] = 0; cdep[c] = 0; cslot[c] = 0;
+            if (rest) {
+                int i = __ffsll((unsigned long long)rest) - 1;
+                rest &= rest - 1;
+                ctok[c] = f.tok[i]; cpar[c] = f.par[i]; cdep[c] = f.dep[i];
+                cslot[c] = f.lo[i] - sg.lo;
+            }
+        }
+    }
+    // take the tied entries out of the frontier (the others keep their relative order)
+    {
+        const bool keep = have && !tie;
+        const double ks = keep ? f.score[lane] : 0.0;
+        const int32_t kt = keep ? f.tok[lane] : 0, kp = keep ? f.par[lane] : 0,
+                      kd = keep ? f.dep[lane] : 0;
+        const int dst = __popcll(__ballot(keep) & lanemask_lt());
+        wsync();
+        if (keep) {
+            f.score[dst] = ks; f.tok[dst] = kt; f.par[dst] = kp; f.lo[dst] = mylo; f.hi[dst] = myhi;
+            f.dep[dst] = kd;
+        }
+        f.n -= j;
+        wsync();
+    }
+    const int W = 1 << sg.wlog;
+    unsigned alive = (1u << j) - 1u;
+    while (n < K && alive) {
+        int c = __ffs(alive) - 1;
+#pragma unroll
+        for (int o = 1; o < TIE_MAX; o++)
+            if (o > c && ((alive >> o) & 1u)) {
+                int32_t tc_ = 0, pc_ = 0;
+#pragma unroll
+                for (int q = 0; q < TIE_MAX; q++)
+                    if (q == c) { tc_ = ctok[q]; pc_ = cpar[q]; }
+                if (ctok[o] < tc_ || (ctok[o] == tc_ && cpar[o] < pc_)) c = o;
+            }
+        int32_t etok = 0, epar = 0, e = 0, slot = 0;
+#pragma unroll
+        for (int q = 0; q < TIE_MAX; q++)
+            if (q == c) { etok = ctok[q]; epar = cpar[q]; e = cdep[q]; slot = cslot[q]; }
+        if (lane == 0) {
+            t_tok[n] = etok; t_par[n] = epar; t_score[n] = s;
+        }
+        total += s;
+        SD_CNT(lane == 0 ? 8 : 0);
+        // the node just taken has depth e; its only possible child is the suffix's token e
+        int32_t next = -1;
+        if (e < D) {
+            int off = e - sg.cb[slot];
+            if (off < 0 || off >= W) {  // move this suffix's window to depth e
+                wsync();
+                if (lane == 0) sg.cb[slot] = e;
+                if (lane < W) sg.tc[(slot << sg.wlog) + lane] = text[(int64_t)sg.pos[slot] + e + lane];
+                wsync();
+                off = 0;
+            }
+            next = sg.tc[(slot << sg.wlog) + off];
+        }
+#pragma unroll
+        for (int q = 0; q < TIE_MAX; q++)
+            if (q == c) { ctok[q] = next; cpar[q] = n; cdep[q] = e + 1; }
+        if (next < 0) alive &= ~(1u << c);
+        n++;
+    }
+    // surviving heads go back into the frontier
+#pragma unroll
+    for (int q = 0; q < TIE_MAX; q++)
+        if ((alive >> q) & 1u) {
+            if (lane == 0) {
+                const int d = f.n;
+                f.score[d] = s; f.tok[d] = ctok[q]; f.par[d] = cpar[q]; f.lo[d] = sg.lo + cslot[q];
+                f.hi[d] = sg.lo + cslot[q] + 1; f.dep[d] = cdep[q];
+            }
+            f.n++;
+        }
+    wsync();
+    return true;
+}
+
+// MatchPattern on the global index.  The pattern's first token selects a bucket of the suffix
+// array; the second token is located in the bucket's second-token column (sorted, read with
+// coalesced loads: buckets up to SCAN_MAX entries are simply scanned); the few suffixes left
+// are compared with the whole pattern lane-parallel.  The dependent chain is
+// bucket -> column -> suffix array -> text, whatever p is.
+constexpr int SCAN_MAX = 256;
+constexpr int DIRECT_MAX = 8;
+
+template <bool STATS>
+__device__ void match_global(const SpecParams &p, int32_t wk, int pl, int32_t &lo, int32_t &hi,
+                             unsigned &nb) {
+    const int lane = threadIdx.x & 63;
+    const int32_t w0 = __shfl(wk, 0);
+    const int32_t bv = lane < 2 ? p.g_bucket[w0 + 1 + lane] : 0;
+    if (lane < 2) SD_CNT(4);
+    lo = __shfl(bv, 0);
+    hi = __shfl(bv, 1);
+    if (pl == 1 || lo >= hi) return;
+    const int32_t w1 = __shfl(wk, 1);
+    const int32_t *col = p.g_tok1;
+    int32_t l = lo, h = hi;
+    if (h - l > SCAN_MAX) {  // wide bucket: bracket the second token by binary search first
+        int32_t la = l, ha = h, lu = l, hu = h;
+        while (la < ha || lu < hu) {
+            const bool doA = la < ha, doB = lu < hu;
+            const int32_t midA = la + ((ha - la) >> 1), midB = lu + ((hu - lu) >> 1);
+            int32_t v = 0;
+            if (lane == 0 && doA) v = col[midA];
+            if (lane == 1 && doB) v = col[midB];
+            if (lane < 2) SD_CNT(4);
+            const int32_t vA = __shfl(v, 0), vB = __shfl(v, 1);
+            if (doA) { if (vA < w1) la = midA + 1; else ha = midA; }
+            if (doB) { if (vB <= w1) lu = midB + 1; else hu = midB; }
+        }
+        l = la;
+        h = lu;
+    } else {
+        int32_t v[SCAN_MAX / 64];
+#pragma unroll
+        for (int c = 0; c < SCAN_MAX / 64; c++) {
+            int32_t i = l + c * 64 + lane;
+            v[c] = i < h ? col[i] : 0x7fffffff;
+            if (i < h) SD_CNT(4);
+        }
+        int nless = 0, nleq = 0;
+#pragma unroll
+        for (int c = 0; c < SCAN_MAX / 64; c++) {
+            nless += __popcll(__ballot(v[c] < w1));
+            nleq += __popcll(__ballot(v[c] <= w1));
+        }
+        h = l + nleq;
+        l = l + nless;
+    }
+    lo = l;
+    hi = h;
+    if (pl == 2 || lo >= hi) return;
+    if (hi - lo <= DIRECT_MAX) {  // compare every remaining suffix with the whole pattern
+        const int32_t cnt = hi - lo;
+        const int64_t pos = lane < cnt ? p.g_sa[lo + lane] : 0;
+        if (lane < cnt) SD_CNT(4);
+        int32_t tk[DIRECT_MAX];
+#pragma unroll
+        for (int c = 0; c < DIRECT_MAX; c++) {
+            const int64_t pc = __shfl(pos, c);
+            tk[c] = (c < cnt && lane < pl) ? p.g_text[pc + lane] : wk;
+            if (c < cnt && lane < pl) SD_CNT(4);
+        }
+        int nless = 0, nleq = 0;
+#pragma unroll
+        for (int c = 0; c < DIRECT_MAX; c++) {
+            const uint64_t ne = __ballot(c < cnt && lane < pl && tk[c] != wk);
+            int r = 0;
+            if (ne) {
+                int fl = __ffsll((unsigned long long)ne) - 1;
+                r = __shfl(tk[c], fl) < __shfl(wk, fl) ? -1 : 1;
+            }
+            if (c < cnt) {
+                nless += r < 0;
+                nleq += r <= 0;
+            }
+        }
+        hi = lo + nleq;
+        lo = lo + nless;
+        return;
+    }
+    match_range<STATS>(p.g_sa, p.g_text, lo, hi, wk, pl, nb);
+}
+
+// One wavefront per unit (request b, pattern length pl) of one index (src 0 global, 1 request).
+template <bool STATS>
+__global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *__restrict__ slot_ids,
+                                               int src) {
     extern __shared__ double smem[];
     const int lane = threadIdx.x;
     unsigned nb = 0;
+    const uint64_t tick0 = STATS ? wall_clock64() : 0;
     const int cap = p.max_nodes;
-    // LDS carve-up: frontier (score, tok, par, lo, hi, dep) and the tree (score, tok, par)
-    double *f_score = smem;
-    double *t_score = f_score + cap;
-    int32_t *f_tok = (int32_t *)(t_score + cap);
-    int32_t *f_par = f_tok + cap, *f_lo = f_par + cap, *f_hi = f_lo + cap, *f_dep = f_hi + cap;
-    int32_t *t_tok = f_dep + cap, *t_par = t_tok + cap;
+    // LDS carve-up: frontier (score, tok, par, lo, hi, dep), tree (score, tok, par), staging
+    Frontier f;
+    f.score = smem;
+    double *t_score = f.score + cap;
+    f.tok = (int32_t *)(t_score + cap);
+    f.par = f.tok + cap; f.lo = f.par + cap; f.hi = f.lo + cap; f.dep = f.hi + cap;
+    int32_t *t_tok = f.dep + cap, *t_par = t_tok + cap;
+    Stage sg;
+    sg.pos = t_par + cap; sg.cb = sg.pos + 64; sg.tc = sg.cb + 64;
+    sg.lo = 0; sg.m = 0; sg.wlog = 0;
 
-    const int units = 2 * p.P;
-    const int b = blockIdx.x / units, r = blockIdx.x % units;
-    const int src = r / p.P, pl = r % p.P + 1;
-    const int64_t uidx = (int64_t)b * units + r;
+    // units with long patterns grow the largest trees: they are dispatched first
+    const int nreq = gridDim.x / p.P;
+    const int b = blockIdx.x % nreq, pl = p.P - blockIdx.x / nreq;
+    const int64_t uidx = (int64_t)b * (2 * p.P) + src * p.P + (pl - 1);
     const int32_t slot = slot_ids[b];
     const bool slot_ok = slot >= 0 && slot < p.max_slots;
     const int t = slot_ok ? p.r_len[slot] : 0;
     const int32_t *x = p.r_text + (int64_t)(slot_ok ? slot : 0) * p.r_stride;
     const int K = (int)floor(p.alpha * (double)pl);
+    uint32_t tick_setup = 0, tick_match = 0, tick_root = 0;
+    if (STATS) tick_setup = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(t & 0);
 
     const int32_t *sa = nullptr, *text = nullptr;
     int32_t lo = 0, hi = 0;
     if (pl <= t && K >= 1) {
         if (src == 0) {
             if (p.g_N > 0) {
-                // MatchPattern on the global suffix array: all suffixes starting with the
-                // pattern's first token form one bucket; binary search inside it, comparing
-                // the p pattern tokens lane-parallel (lane k holds pattern token k).
-                const int32_t wk = lane < pl ? x[t - pl + lane] : 0;
+                const int32_t wk = lane < pl ? x[t - pl + lane] : 0;  // lane k: pattern token k
                 if (lane < pl) SD_CNT(4);
-                if (lane == 0) SD_CNT(8);  // the two bucket bounds
-                const int32_t w0 = __shfl(wk, 0);
-                lo = p.g_bucket[w0 + 1];
-                hi = p.g_bucket[w0 + 2];
                 sa = p.g_sa;
                 text = p.g_text;
-                if (pl > 1 && lo < hi) {
-                    int32_t l = lo, h = hi;
-                    while (l < h) {  // first suffix whose leading p tokens are >= the pattern
-                        int32_t mid = l + ((h - l) >> 1);
-                        int64_t pos = sa[mid];
-                        int32_t tk = lane < pl ? text[pos + lane] : 0;
-                        SD_CNT(lane < pl ? (lane == 0 ? 8 : 4) : 0);
-                        uint64_t ne = __ballot(lane < pl && tk != wk);
-                        bool less = false;
-                        if (ne) {
-                            int fl = __ffsll((unsigned long long)ne) - 1;
-                            less = __shfl(tk, fl) < __shfl(wk, fl);
-                        }
-                        if (less) l = mid + 1; else h = mid;
-                    }
-                    const int32_t lb = l;
-                    h = hi;
-                    while (l < h) {  // first suffix whose leading p tokens are > the pattern
-                        int32_t mid = l + ((h - l) >> 1);
-                        int64_t pos = sa[mid];
-                        int32_t tk = lane < pl ? text[pos + lane] : 0;
-                        SD_CNT(lane < pl ? (lane == 0 ? 8 : 4) : 0);
-                        uint64_t ne = __ballot(lane < pl && tk != wk);
-                        bool greater = false;
-                        if (ne) {
-                            int fl = __ffsll((unsigned long long)ne) - 1;
-                            greater = __shfl(tk, fl) > __shfl(wk, fl);
-                        }
-                        if (!greater) l = mid + 1; else h = mid;
-                    }
-                    lo = lb;
-                    hi = l;
-                }
+                match_global<STATS>(p, wk, pl, lo, hi, nb);
             }
         } else {
-            // per-request structure: occurrences whose left-extension reaches p, in the
+            // per-request structure: occurrences whose left-extension reaches pl, in the
             // order k_req_occurrences left them (sorted by what follows)
             const int m1 = p.occ_n[b];
             const int m = p.cntL[(int64_t)b * (p.P + 1) + pl];
             const int2 *occ = p.occ + (int64_t)b * p.max_ctx;
             int32_t *usa = p.unit_sa + ((int64_t)b * p.P + (pl - 1)) * p.max_ctx;
+            const bool narrow = m <= 64;
             int w = 0;
             for (int base = 0; base < m1; base += 64) {
                 int i = base + lane;
@@ -423,9 +779,18 @@ __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__re
                 if (i < m1) SD_CNT(8);
                 bool keep = i < m1 && o.y >= pl;
                 uint64_t mk = __ballot(keep);
-                if (keep) usa[w + __popcll(mk & lanemask_lt())] = o.x - pl + 1;
-                if (keep) SD_CNT(4);
+                if (keep) {
+                    int dst = w + __popcll(mk & lanemask_lt());
+                    if (narrow) { sg.pos[dst] = o.x - pl + 1; sg.cb[dst] = CB_NONE; }
+                    else usa[dst] = o.x - pl + 1;
+                    SD_CNT(4);
+                }
                 w += __popcll(mk);
+            }
+            if (narrow) {  // the whole list is staged: nothing below it ever reads `usa`
+                sg.lo = 0;
+                sg.m = m;
+                stage_set_width(sg, m > 0 ? m : 1);
             }
             __threadfence_block();
             __syncthreads();
@@ -438,35 +803,69 @@ __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__re
 
     int n = 0;
     double total = 0.0;
+    if (STATS) tick_match = (uint32_t)(wall_clock64() - tick0) + (uint32_t)((hi - lo) & 0);
     if (hi > lo) {
-        Frontier f;
-        f.score = f_score; f.tok = f_tok; f.par = f_par; f.lo = f_lo; f.hi = f_hi; f.dep = f_dep;
         f.n = 0;
         f.cap = K;
-        push_children<STATS>(f, sa, text, lo, hi, pl, -1, 1.0, p.min_score, p.D, nb);
+        push_children<STATS>(f, -1, sg, sa, text, lo, hi, pl, -1, 1.0, p.min_score, p.D, nb);
+        if (STATS) tick_root = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(f.n & 0);
         while (n < K && f.n > 0) {
-            Key best = frontier_pick(f, true);
+            const Key best = frontier_pick(f, true, -1);
             if (best.s < p.min_score) break;
+            if (tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok, t_par, t_score, nb))
+                continue;
             const int bi = best.idx;
-            const int32_t blo = f.lo[bi], bhi = f.hi[bi], bdep = f.dep[bi];
-            __syncthreads();
+            const int32_t blo = f.lo[bi], bhi = f.hi[bi];
+            int32_t d = f.dep[bi];
             if (lane == 0) {
                 t_tok[n] = best.tok; t_par[n] = best.par; t_score[n] = best.s;
-                const int last = f.n - 1;
-                if (bi != last) {
-                    f.score[bi] = f.score[last]; f.tok[bi] = f.tok[last]; f.par[bi] = f.par[last];
-                    f.lo[bi] = f.lo[last]; f.hi[bi] = f.hi[last]; f.dep[bi] = f.dep[last];
+            }
+            total += best.s;
+            int cur = n++;
+            // Unary run: while all suffixes of the node agree on the next token and none has
+            // ended, the node has exactly one child, with the node's own score (count ratio 1).
+            // If that score is strictly above everything else in the frontier, the greedy
+            // rule must take that child next, and so on down the run: take the run at once.
+            const int32_t m = bhi - blo;
+            if (n < K && d < p.D && m <= CHAIN_MAX_M) {
+                stage_node(sg, sa, text, blo, m, d);
+                const int slot0 = blo - sg.lo, W = 1 << sg.wlog;
+                int32_t tk = -2;
+                for (int i = 0; i < m; i++) {
+                    int off = d + lane - sg.cb[slot0 + i];
+                    int32_t v = off < W ? sg.tc[((slot0 + i) << sg.wlog) + off] : -2;
+                    tk = (i == 0 || v == tk) ? v : -2;
+                }
+                int lim = K - n < p.D - d ? K - n : p.D - d;
+                uint64_t ok = __ballot(tk >= 0 && lane < lim);
+                int L = ~ok ? __ffsll((unsigned long long)~ok) - 1 : 64;
+                if (L > 0) {
+                    bool dominant = f.n == 1;
+                    if (!dominant) {
+                        Key second = frontier_pick(f, true, bi);
+                        dominant = second.s < best.s;
+                    }
+                    if (dominant) {
+                        if (lane < L) {
+                            t_tok[n + lane] = tk; t_par[n + lane] = cur + lane;
+                            t_score[n + lane] = best.s;
+                            SD_CNT(8 * m);
+                        }
+                        for (int i = 0; i < L; i++) total += best.s;
+                        cur += L;
+                        n += L;
+                        d += L;
+                    }
                 }
             }
-            f.n--;
-            total += best.s;
-            __syncthreads();
-            if (n + 1 < K)  // the last node taken cannot contribute further nodes
-                push_children<STATS>(f, sa, text, blo, bhi, bdep, n, best.s, p.min_score, p.D, nb);
-            n++;
+            if (n < K)
+                push_children<STATS>(f, bi, sg, sa, text, blo, bhi, d, cur, best.s, p.min_score, p.D,
+                                     nb);
+            else
+                frontier_close(f, bi);  // the last node taken cannot contribute further nodes
         }
     }
-    __syncthreads();
+    wsync();
     for (int i = lane; i < n; i += 64) {
         p.unit_tok[uidx * cap + i] = t_tok[i];
         p.unit_par[uidx * cap + i] = t_par[i];
@@ -477,6 +876,12 @@ __global__ __launch_bounds__(64) void k_expand(SpecParams p, const int32_t *__re
         p.unit_n[uidx] = n;
         p.unit_score[uidx] = total;
         SD_CNT(12);
+        if (STATS) {  // phase marks: setup, match, root children, whole unit
+            p.unit_ticks[uidx * 4 + 0] = tick_setup;
+            p.unit_ticks[uidx * 4 + 1] = tick_match;
+            p.unit_ticks[uidx * 4 + 2] = tick_root;
+            p.unit_ticks[uidx * 4 + 3] = (uint32_t)(wall_clock64() - tick0);
+        }
     }
     flush_count<STATS>(nb, p.algo_bytes + SD_K_EXPAND);
 }
@@ -528,31 +933,45 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nod
                                                int32_t *__restrict__ accept_len,
                                                int32_t *__restrict__ accept_path,
                                                int32_t *__restrict__ bonus) {
+    // the whole tree sits in registers (node j in lane j % 64) and the targets in LDS, so the
+    // walk itself touches no global memory
+    __shared__ int32_t s_tgt[257];
+    __shared__ int32_t s_path[256];
     const int lane = threadIdx.x, b = blockIdx.x;
     int n = n_nodes[b];
     if (n > max_nodes) n = max_nodes;
+    if (n < 0) n = 0;
     const int32_t *tok = tokens + (int64_t)b * max_nodes, *par = parents + (int64_t)b * max_nodes;
     const int32_t *tgt = target + (int64_t)b * (max_nodes + 1);
     int32_t *path = accept_path + (int64_t)b * max_nodes;
+    int32_t mt[4], mp[4];
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        int j = lane + 64 * r;
+        mt[r] = j < n ? tok[j] : -1;
+        mp[r] = j < n ? par[j] : -2;
+    }
+    for (int i = lane; i <= max_nodes; i += 64) s_tgt[i] = tgt[i];
+    __syncthreads();
     int v = -1, L = 0;
     while (L < n) {
-        const int32_t want = tgt[v + 1];
+        const int32_t want = s_tgt[v + 1];
         int found = -1;
-        for (int base = 0; base < n && found < 0; base += 64) {
-            int j = base + lane;
-            bool hit = j < n && par[j] == v && tok[j] == want;
-            uint64_t m = __ballot(hit);
-            if (m) found = base + __ffsll((unsigned long long)m) - 1;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            uint64_t m = __ballot(mp[r] == v && mt[r] == want);
+            if (m && found < 0) found = 64 * r + __ffsll((unsigned long long)m) - 1;
         }
         if (found < 0) break;
-        if (lane == 0) path[L] = found;
+        if (lane == 0) s_path[L] = found;
         L++;
         v = found;
     }
-    for (int i = L + lane; i < max_nodes; i += 64) path[i] = -1;
+    __syncthreads();
+    for (int i = lane; i < max_nodes; i += 64) path[i] = i < L ? s_path[i] : -1;
     if (lane == 0) {
         accept_len[b] = L;
-        bonus[b] = tgt[v + 1];
+        bonus[b] = s_tgt[v + 1];
     }
 }
 
@@ -562,7 +981,8 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
                             hipStream_t st) {
     if (batch == 0) return SD_OK;
     SpecParams p;
-    p.g_text = c->g_text; p.g_sa = c->g_sa; p.g_bucket = c->g_bucket; p.g_N = (int32_t)c->g_N;
+    p.g_text = c->g_text; p.g_sa = c->g_sa; p.g_bucket = c->g_bucket; p.g_tok1 = c->g_tok1;
+    p.g_N = (int32_t)c->g_N;
     p.r_text = c->r_text; p.r_len = c->r_len; p.r_stride = c->r_stride;
     p.max_slots = c->cfg.max_batch_slots; p.max_ctx = c->cfg.max_ctx_tokens;
     p.D = c->cfg.D; p.P = c->cfg.P; p.max_nodes = c->max_nodes;
@@ -571,18 +991,32 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     p.unit_n = c->s_unit_n; p.unit_score = c->s_unit_score; p.unit_tok = c->s_unit_tok;
     p.unit_par = c->s_unit_par; p.unit_sc = c->s_unit_sc; p.err = c->d_err;
     p.algo_bytes = c->d_algo_bytes;
+    p.unit_ticks = c->s_unit_ticks;
     const bool stats = c->prof_mode == 2;
-    const size_t lds = (size_t)c->max_nodes * (2 * sizeof(double) + 7 * sizeof(int32_t));
-    const dim3 g_units((unsigned)(batch * 2 * c->cfg.P)), g_req((unsigned)batch);
+    const size_t lds = (size_t)c->max_nodes * (2 * sizeof(double) + 7 * sizeof(int32_t)) +
+                       (64 + 64 + TC_TOKENS) * sizeof(int32_t);
+    const dim3 g_units((unsigned)(batch * c->cfg.P)), g_req((unsigned)batch);
+    // The scan of the request contexts does not depend on the global index: it runs on the
+    // context's second stream while the global units expand on the caller's stream.
+    if (hipEventRecord(c->ev_fork, st) != hipSuccess ||
+        hipStreamWaitEvent(c->aux_stream, c->ev_fork, 0) != hipSuccess)
+        return SD_ERR_HIP;
     {
-        sd_span sp(c, SD_K_OCCURRENCES, st);
-        if (stats) hipLaunchKernelGGL(k_req_occurrences<true>, g_req, dim3(OCC_THREADS), 0, st, p, d_slot_ids);
-        else hipLaunchKernelGGL(k_req_occurrences<false>, g_req, dim3(OCC_THREADS), 0, st, p, d_slot_ids);
+        sd_span sp(c, SD_K_OCCURRENCES, c->aux_stream);
+        if (stats) hipLaunchKernelGGL(k_req_occurrences<true>, g_req, dim3(OCC_THREADS), 0, c->aux_stream, p, d_slot_ids);
+        else hipLaunchKernelGGL(k_req_occurrences<false>, g_req, dim3(OCC_THREADS), 0, c->aux_stream, p, d_slot_ids);
     }
+    if (hipEventRecord(c->ev_join, c->aux_stream) != hipSuccess) return SD_ERR_HIP;
     {
         sd_span sp(c, SD_K_EXPAND, st);
-        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, dim3(64), lds, st, p, d_slot_ids);
-        else hipLaunchKernelGGL(k_expand<false>, g_units, dim3(64), lds, st, p, d_slot_ids);
+        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, dim3(64), lds, st, p, d_slot_ids, 0);
+        else hipLaunchKernelGGL(k_expand<false>, g_units, dim3(64), lds, st, p, d_slot_ids, 0);
+    }
+    if (hipStreamWaitEvent(st, c->ev_join, 0) != hipSuccess) return SD_ERR_HIP;
+    {
+        sd_span sp(c, SD_K_EXPAND_REQ, st);
+        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, dim3(64), lds, st, p, d_slot_ids, 1);
+        else hipLaunchKernelGGL(k_expand<false>, g_units, dim3(64), lds, st, p, d_slot_ids, 1);
     }
     {
         sd_span sp(c, SD_K_SELECT, st);

@@ -32,35 +32,30 @@ __global__ __launch_bounds__(64) void k_targets(const int32_t *__restrict__ n_no
     }
 }
 
-// one workgroup: new_offsets = exclusive scan of (accept_len + 1); new tokens of request b are
-// its accepted draft tokens followed by the bonus token; pos[b] += accept_len[b] + 1.
-__global__ __launch_bounds__(1024) void k_collect(const int32_t *__restrict__ tokens,
-                                                  int max_nodes,
-                                                  const int32_t *__restrict__ accept_len,
-                                                  const int32_t *__restrict__ accept_path,
-                                                  const int32_t *__restrict__ bonus, int batch,
-                                                  int32_t *__restrict__ new_tokens,
-                                                  int32_t *__restrict__ new_offsets,
-                                                  int32_t *__restrict__ pos) {
-    __shared__ int32_t s_off[1025];
-    const int tid = threadIdx.x;
-    if (tid == 0) {
-        int acc = 0;
-        for (int b = 0; b < batch; b++) {
-            s_off[b] = acc;
-            acc += accept_len[b] + 1;
-        }
-        s_off[batch] = acc;
-    }
-    __syncthreads();
-    for (int b = tid; b <= batch; b += 1024) new_offsets[b] = s_off[b];
-    for (int b = tid; b < batch; b += 1024) {
-        const int L = accept_len[b];
-        int32_t *dst = new_tokens + s_off[b];
-        for (int i = 0; i < L; i++)
-            dst[i] = tokens[(int64_t)b * max_nodes + accept_path[(int64_t)b * max_nodes + i]];
+// one wavefront per request: new_offsets[b] = sum over earlier requests of (accept_len + 1);
+// the new tokens of request b are its accepted draft tokens followed by the bonus token;
+// pos[b] += accept_len[b] + 1.
+__global__ __launch_bounds__(64) void k_collect(const int32_t *__restrict__ tokens, int max_nodes,
+                                                const int32_t *__restrict__ accept_len,
+                                                const int32_t *__restrict__ accept_path,
+                                                const int32_t *__restrict__ bonus, int batch,
+                                                int32_t *__restrict__ new_tokens,
+                                                int32_t *__restrict__ new_offsets,
+                                                int32_t *__restrict__ pos) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    int off = 0;
+    for (int i = lane; i < b; i += 64) off += accept_len[i] + 1;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) off += __shfl_xor(off, o);
+    const int L = accept_len[b];
+    int32_t *dst = new_tokens + off;
+    for (int i = lane; i < L; i += 64)
+        dst[i] = tokens[(int64_t)b * max_nodes + accept_path[(int64_t)b * max_nodes + i]];
+    if (lane == 0) {
         dst[L] = bonus[b];
+        new_offsets[b] = off;
         pos[b] += L + 1;
+        if (b == batch - 1) new_offsets[batch] = off + L + 1;
     }
 }
 
@@ -68,7 +63,7 @@ __global__ __launch_bounds__(1024) void k_collect(const int32_t *__restrict__ to
 
 extern "C" {
 
-// all pointers are device pointers; batch <= 1024 for wl_collect
+// all pointers are device pointers
 int wl_targets(const int32_t *d_n_nodes, const int32_t *d_parents, int max_nodes,
                const int32_t *d_future, int64_t future_stride, const int32_t *d_pos, int batch,
                int32_t *d_target, void *stream) {
@@ -82,8 +77,7 @@ int wl_collect(const int32_t *d_tokens, int max_nodes, const int32_t *d_accept_l
                const int32_t *d_accept_path, const int32_t *d_bonus, int batch,
                int32_t *d_new_tokens, int32_t *d_new_offsets, int32_t *d_pos, void *stream) {
     if (batch <= 0) return 0;
-    if (batch > 1024) return 2;
-    hipLaunchKernelGGL(k_collect, dim3(1), dim3(1024), 0, (hipStream_t)stream, d_tokens, max_nodes,
+    hipLaunchKernelGGL(k_collect, dim3((unsigned)batch), dim3(64), 0, (hipStream_t)stream, d_tokens, max_nodes,
                        d_accept_len, d_accept_path, d_bonus, batch, d_new_tokens, d_new_offsets,
                        d_pos);
     return hipGetLastError() == hipSuccess ? 0 : 1;
