@@ -25,10 +25,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 
 
-def _traffic_from_profiles(kernel: str):
+def _traffic_from_profiles(kernel: str, workload: str):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary
-    for this kernel has been committed under profiles/."""
-    path = os.path.join(ROOT, "profiles", "%s_large_pmc.md" % kernel)
+    for this kernel and workload has been committed under profiles/."""
+    path = os.path.join(ROOT, "profiles", "%s_%s_pmc.md" % (kernel, workload))
     try:
         m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
         return float(m.group(1)) if m else None
@@ -186,6 +186,23 @@ def main():
     assert stats["err_bad_token"] == 0 and stats["err_bad_slot"] == 0 and \
         stats["err_ctx_overflow"] == 0, stats
 
+    # ---- per-step latency (each step bracketed by events and synchronised) ----------------
+    reset()
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+    lat = []
+    for _ in range(K):
+        e0, e1 = ev(), ev()
+        e0.record()
+        step()
+        e1.record()
+        torch.cuda.synchronize()
+        lat.append(e0.elapsed_time(e1))
+    lat.sort()
+    step_latency = {"median": lat[len(lat) // 2], "p99": lat[min(len(lat) - 1, int(0.99 * len(lat)))],
+                    "max": lat[-1]}
+
     # ---- per-kernel durations (HIP events on the launch stream) over the same K steps -----
     reset()
     for _ in range(W):
@@ -213,7 +230,7 @@ def main():
     achieved = exp_bytes / (exp_ms * 1e-3) / 1e9 if exp_ms > 0 else 0.0
     roofline = {"bound": "hbm", "kernel": "k_expand", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": _traffic_from_profiles("k_expand"),
+                "traffic": _traffic_from_profiles("k_expand", w.name),
                 "algo_bytes_per_launch": exp_bytes, "avg_launch_ms": exp_ms}
     N = n_tokens + n_docs
     sc = prof_build["sort_scatter"]
@@ -221,7 +238,7 @@ def main():
     sc_ach = 24.0 * N / (sc_ms * 1e-3) / 1e9 if sc_ms > 0 else 0.0
     roofline_build = {"bound": "hbm", "kernel": "k_radix_scatter", "achieved": sc_ach,
                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sc_ach / HBM_PEAK_GBS,
-                      "traffic": _traffic_from_profiles("k_radix_scatter"),
+                      "traffic": _traffic_from_profiles("k_radix_scatter", w.name),
                       "algo_bytes_per_launch": 24.0 * N, "avg_launch_ms": sc_ms,
                       "launches_per_build": sc["launches"]}
     kernels_ms = {k: v["ms"] / max(v["launches"], 1) for k, v in prof.items() if v["launches"]}
@@ -242,6 +259,7 @@ def main():
         "index_build_tokens_per_s": n_tokens / (g_build_ms * 1e-3),
         "index_build_ms": g_build_ms, "request_build_ms": r_build_ms,
         "request_build_tokens_per_s": B * ctx_len / (r_build_ms * 1e-3),
+        "step_latency_ms": step_latency,
         "mean_tree_nodes": mean_nodes, "mean_accept_len": mean_accept,
         "kernel_ms_per_launch": kernels_ms, "build_kernel_ms_total": build_kernels_ms,
         "roofline": roofline, "roofline_build": roofline_build,

@@ -720,10 +720,50 @@ __device__ void match_global(const SpecParams &p, int32_t wk, int pl, int32_t &l
     match_range<STATS>(p.g_sa, p.g_text, lo, hi, wk, pl, nb);
 }
 
+// Best tree of request b over its 2P units (GenerateCandidateTree's strictly-greater scan) and
+// coalesced copy of the winner into the caller's buffers.
+template <bool STATS>
+__device__ void select_request(const SpecParams &p, const sd_trees &out, int b, unsigned &nb) {
+    const int lane = threadIdx.x & 63;
+    const int units = 2 * p.P, cap = p.max_nodes;
+    // strictly-greater scan in unit order = the earliest unit among those with the top score
+    double bs = 0.0;
+    int bu = -1;
+    for (int u = lane; u < units; u += 64) {
+        double s = p.unit_score[(int64_t)b * units + u];
+        SD_CNT(8);
+        if (s > bs) { bs = s; bu = u; }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        double os = __shfl_xor(bs, o);
+        int ou = __shfl_xor(bu, o);
+        if (ou >= 0 && (bu < 0 || os > bs || (os == bs && ou < bu))) { bs = os; bu = ou; }
+    }
+    int n = 0;
+    if (bu >= 0) n = p.unit_n[(int64_t)b * units + bu];
+    const int64_t ub = ((int64_t)b * units + (bu >= 0 ? bu : 0)) * cap;
+    const int64_t ob = (int64_t)b * out.max_nodes;
+    for (int i = lane; i < out.max_nodes; i += 64) {
+        bool live = i < n;
+        out.d_tokens[ob + i] = live ? p.unit_tok[ub + i] : -1;
+        out.d_parents[ob + i] = live ? p.unit_par[ub + i] : -1;
+        out.d_scores[ob + i] = live ? p.unit_sc[ub + i] : 0.0;
+        SD_CNT(live ? 32 : 16);
+    }
+    if (lane == 0) {
+        out.d_n_nodes[b] = n;
+        out.d_tree_score[b] = bu >= 0 ? bs : 0.0;
+        out.d_match_len[b] = bu >= 0 ? bu % p.P + 1 : 0;
+        out.d_source[b] = bu >= 0 ? bu / p.P : -1;
+        SD_CNT(24);
+    }
+}
+
 // One wavefront per unit (request b, pattern length pl) of one index (src 0 global, 1 request).
 template <bool STATS>
 __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *__restrict__ slot_ids,
-                                               int src) {
+                                                  int src) {
     extern __shared__ double smem[];
     const int lane = threadIdx.x;
     unsigned nb = 0;
@@ -886,43 +926,12 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
     flush_count<STATS>(nb, p.algo_bytes + SD_K_EXPAND);
 }
 
+// One wavefront per request, after both expansion launches have finished (the kernel boundary
+// is what makes the unit results of all compute dies visible here).
 template <bool STATS>
 __global__ __launch_bounds__(64) void k_select(SpecParams p, sd_trees out) {
-    const int lane = threadIdx.x, b = blockIdx.x;
     unsigned nb = 0;
-    const int units = 2 * p.P, cap = p.max_nodes;
-    // strictly-greater scan in unit order = the earliest unit among those with the top score
-    double bs = 0.0;
-    int bu = -1;
-    for (int u = lane; u < units; u += 64) {
-        double s = p.unit_score[(int64_t)b * units + u];
-        SD_CNT(8);
-        if (s > bs) { bs = s; bu = u; }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        double os = __shfl_xor(bs, o);
-        int ou = __shfl_xor(bu, o);
-        if (ou >= 0 && (bu < 0 || os > bs || (os == bs && ou < bu))) { bs = os; bu = ou; }
-    }
-    int n = 0;
-    if (bu >= 0) n = p.unit_n[(int64_t)b * units + bu];
-    const int64_t ub = ((int64_t)b * units + (bu >= 0 ? bu : 0)) * cap;
-    const int64_t ob = (int64_t)b * out.max_nodes;
-    for (int i = lane; i < out.max_nodes; i += 64) {
-        bool live = i < n;
-        out.d_tokens[ob + i] = live ? p.unit_tok[ub + i] : -1;
-        out.d_parents[ob + i] = live ? p.unit_par[ub + i] : -1;
-        out.d_scores[ob + i] = live ? p.unit_sc[ub + i] : 0.0;
-        SD_CNT(live ? 32 : 16);
-    }
-    if (lane == 0) {
-        out.d_n_nodes[b] = n;
-        out.d_tree_score[b] = bu >= 0 ? bs : 0.0;
-        out.d_match_len[b] = bu >= 0 ? bu % p.P + 1 : 0;
-        out.d_source[b] = bu >= 0 ? bu / p.P : -1;
-        SD_CNT(24);
-    }
+    select_request<STATS>(p, out, blockIdx.x, nb);
     flush_count<STATS>(nb, p.algo_bytes + SD_K_SELECT);
 }
 
@@ -996,8 +1005,9 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     const size_t lds = (size_t)c->max_nodes * (2 * sizeof(double) + 7 * sizeof(int32_t)) +
                        (64 + 64 + TC_TOKENS) * sizeof(int32_t);
     const dim3 g_units((unsigned)(batch * c->cfg.P)), g_req((unsigned)batch);
-    // The scan of the request contexts does not depend on the global index: it runs on the
-    // context's second stream while the global units expand on the caller's stream.
+    // Two concurrent legs: the caller's stream expands the global-index units while the
+    // context's second stream scans the request contexts and expands the per-request units.
+    // They join before the selection kernel.
     if (hipEventRecord(c->ev_fork, st) != hipSuccess ||
         hipStreamWaitEvent(c->aux_stream, c->ev_fork, 0) != hipSuccess)
         return SD_ERR_HIP;
@@ -1006,6 +1016,11 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
         if (stats) hipLaunchKernelGGL(k_req_occurrences<true>, g_req, dim3(OCC_THREADS), 0, c->aux_stream, p, d_slot_ids);
         else hipLaunchKernelGGL(k_req_occurrences<false>, g_req, dim3(OCC_THREADS), 0, c->aux_stream, p, d_slot_ids);
     }
+    {
+        sd_span sp(c, SD_K_EXPAND_REQ, c->aux_stream);
+        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, dim3(64), lds, c->aux_stream, p, d_slot_ids, 1);
+        else hipLaunchKernelGGL(k_expand<false>, g_units, dim3(64), lds, c->aux_stream, p, d_slot_ids, 1);
+    }
     if (hipEventRecord(c->ev_join, c->aux_stream) != hipSuccess) return SD_ERR_HIP;
     {
         sd_span sp(c, SD_K_EXPAND, st);
@@ -1013,11 +1028,6 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
         else hipLaunchKernelGGL(k_expand<false>, g_units, dim3(64), lds, st, p, d_slot_ids, 0);
     }
     if (hipStreamWaitEvent(st, c->ev_join, 0) != hipSuccess) return SD_ERR_HIP;
-    {
-        sd_span sp(c, SD_K_EXPAND_REQ, st);
-        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, dim3(64), lds, st, p, d_slot_ids, 1);
-        else hipLaunchKernelGGL(k_expand<false>, g_units, dim3(64), lds, st, p, d_slot_ids, 1);
-    }
     {
         sd_span sp(c, SD_K_SELECT, st);
         if (stats) hipLaunchKernelGGL(k_select<true>, g_req, dim3(64), 0, st, p, out);

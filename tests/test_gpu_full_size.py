@@ -86,3 +86,66 @@ def test_large_full_sampled():
 def test_lowrep_full_sampled():
     got, want = _run_full("lowrep", sample=24)
     assert (got["n_nodes"] > 0).mean() > 0.3
+
+
+def test_streaming_full_sampled_decode_loop():
+    """100M-token corpus, 512 requests, decode steps with the simulated verifier: speculate,
+    accept, append.  Every step the sampled requests are compared with the oracle (global trie
+    restricted to the suffixes those requests can reach, per-request tries extended online);
+    invariants are checked for the whole batch."""
+    w = make_workload("streaming", seed=0)
+    docs = w.docs()
+    B, mn, steps = w.batch, w.max_nodes, 6
+    contexts = [w.contexts[b].copy() for b in range(B)]
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, w.ctx_len + steps * (mn + 1),
+                       len(w.corpus) + len(docs))
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), contexts)
+        rng = np.random.default_rng(2)
+        pick = sorted(rng.choice(B, size=8, replace=False).tolist())
+        # first tokens the sampled requests can ask about over all steps: context tail + futures
+        reach = [np.concatenate([contexts[b][-w.P:], w.future[b, :steps * (mn + 1)]]) for b in pick]
+        allowed = np.zeros(w.vocab, np.uint8)
+        for r in reach:
+            allowed[r] = 1
+        tg = oracle.Trie(w.D)
+        for d in docs:
+            tg.add_doc(d, allowed)
+        tries = {}
+        for b in pick:
+            tries[b] = oracle.Trie(w.D)
+            tries[b].append(contexts[b])
+        pos = np.zeros(B, np.int64)
+        accepted = 0
+        for step in range(steps):
+            got = g.speculate(range(B))
+            _check_properties(got, w)
+            sub = [contexts[b] for b in pick]
+            want = parity.oracle_speculate_batch(tg, sub, w.D, w.P, w.alpha, w.min_score, mn,
+                                                 request_tries=[tries[b] for b in pick])
+            bad = parity.compare_trees({k: v[pick] for k, v in got.items()}, want,
+                                       "streaming step %d" % step)
+            assert not bad, "\n".join(bad)
+            fut = np.stack([w.future[b, pos[b]:pos[b] + mn + 2] for b in range(B)])
+            tgt = parity.targets_from_future(got, fut, mn)
+            al, ap, bo = g.accept(tgt)
+            new = []
+            for b in range(B):
+                L = int(al[b])
+                toks = [int(got["tokens"][b, j]) for j in ap[b, :L]] + [int(bo[b])]
+                assert toks == [int(v) for v in w.future[b, pos[b]:pos[b] + L + 1]]
+                new.append(np.array(toks, np.int32))
+                contexts[b] = np.concatenate([contexts[b], new[-1]])
+                pos[b] += L + 1
+                accepted += L
+            for i, b in enumerate(pick):
+                k = int(want["n_nodes"][i])
+                L, path, bonus = oracle.accept(want["tokens"][i, :k], want["parents"][i, :k], tgt[b])
+                assert al[b] == L and bo[b] == bonus and list(ap[b, :L]) == list(path)
+                tries[b].append(new[b])
+            g.append(range(B), new)
+        assert accepted > B          # the drafts do get accepted on this workload
+        assert g.stats()["err_ctx_overflow"] == 0
+    finally:
+        g.close()
