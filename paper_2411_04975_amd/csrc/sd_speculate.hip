@@ -56,6 +56,19 @@ __device__ __forceinline__ void flush_count(unsigned nb, unsigned long long *dst
 
 __device__ __forceinline__ uint64_t lanemask_lt() { return (1ull << (threadIdx.x & 63)) - 1ull; }
 
+// Values that are the same in every lane but were read through vector memory or LDS are
+// "divergent" to the compiler, which then runs all the control code around them on the vector
+// ALU.  uni() moves such a value into a scalar register so that compares, selects and branches
+// on it become scalar instructions.
+__device__ __forceinline__ int32_t uni(int32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ double uni(double v) {
+    union { double d; int32_t i[2]; } u;
+    u.d = v;
+    u.i[0] = __builtin_amdgcn_readfirstlane(u.i[0]);
+    u.i[1] = __builtin_amdgcn_readfirstlane(u.i[1]);
+    return u.d;
+}
+
 // ------------------------------------------------------------------------------------------
 // per-request occurrence lists
 // ------------------------------------------------------------------------------------------
@@ -245,6 +258,8 @@ __device__ __forceinline__ Key frontier_pick(const Frontier &f, bool want_best, 
             k.s = f.score[i]; k.tok = f.tok[i]; k.par = f.par[i]; k.idx = i;
             if (mine.idx < 0 || (want_best ? key_better(k, mine) : key_better(mine, k))) mine = k;
         }
+        mine.s = uni(mine.s); mine.tok = uni(mine.tok); mine.par = uni(mine.par);
+        mine.idx = uni(mine.idx);
         return mine;
     }
     for (int i = lane; i < f.n; i += 64) {
@@ -262,6 +277,7 @@ __device__ __forceinline__ Key frontier_pick(const Frontier &f, bool want_best, 
         else take = want_best ? key_better(other, mine) : key_better(mine, other);
         if (take) mine = other;
     }
+    mine.s = uni(mine.s); mine.tok = uni(mine.tok); mine.par = uni(mine.par); mine.idx = uni(mine.idx);
     return mine;
 }
 
@@ -545,7 +561,8 @@ __device__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ 
     const bool fit = myhi - mylo == 1 && mylo >= sg.lo && mylo < sg.lo + sg.m;
     const uint64_t T = __ballot(tie);
     const int j = __popcll(T);
-    if (j > TIE_MAX || __ballot(tie && !fit)) return false;
+    // a single top entry is not a tie: the unary-run shortcut takes its whole chain at once
+    if (j < 2 || j > TIE_MAX || __ballot(tie && !fit)) return false;
     // chain heads into uniform registers
     int32_t ctok[TIE_MAX], cpar[TIE_MAX], cdep[TIE_MAX], cslot[TIE_MAX];
     {
@@ -556,8 +573,8 @@ __device__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ 
             if (rest) {
                 int i = __ffsll((unsigned long long)rest) - 1;
                 rest &= rest - 1;
-                ctok[c] = f.tok[i]; cpar[c] = f.par[i]; cdep[c] = f.dep[i];
-                cslot[c] = f.lo[i] - sg.lo;
+                ctok[c] = uni(f.tok[i]); cpar[c] = uni(f.par[i]); cdep[c] = uni(f.dep[i]);
+                cslot[c] = uni(f.lo[i]) - sg.lo;
             }
         }
     }
@@ -576,46 +593,69 @@ __device__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ 
         f.n -= j;
         wsync();
     }
-    const int W = 1 << sg.wlog;
+    // Each chain's upcoming tokens sit in one register across the wave (lane k: the token k
+    // positions after the chain's current child index), so a step of the merge is a handful of
+    // scalar compares and one lane read; nodes are collected in registers (lane i: i-th node
+    // taken here) and written to the tree in one go.
+    int32_t win[TIE_MAX], woff[TIE_MAX];
+#pragma unroll
+    for (int q = 0; q < TIE_MAX; q++) {
+        woff[q] = 0;
+        win[q] = q < j ? text[(int64_t)sg.pos[cslot[q]] + cdep[q] + lane] : -1;
+    }
     unsigned alive = (1u << j) - 1u;
-    while (n < K && alive) {
+    const int n0 = uni(n);
+    int32_t otok = 0, opar = 0;
+    int nn = uni(n);
+    const int KK = uni(K);
+    while (nn < KK && alive && nn - n0 < 64) {
+        // keep the merge state in scalar registers: every compare and select below is then a
+        // scalar instruction instead of a vector one under an execution mask
+        alive = (unsigned)uni((int32_t)alive);
+#pragma unroll
+        for (int q = 0; q < TIE_MAX; q++) {
+            ctok[q] = uni(ctok[q]); cpar[q] = uni(cpar[q]); cdep[q] = uni(cdep[q]);
+            woff[q] = uni(woff[q]);
+        }
         int c = __ffs(alive) - 1;
+        int32_t etok = 0, epar = 0;
+#pragma unroll
+        for (int q = 0; q < TIE_MAX; q++)
+            if (q == c) { etok = ctok[q]; epar = cpar[q]; }
 #pragma unroll
         for (int o = 1; o < TIE_MAX; o++)
-            if (o > c && ((alive >> o) & 1u)) {
-                int32_t tc_ = 0, pc_ = 0;
-#pragma unroll
-                for (int q = 0; q < TIE_MAX; q++)
-                    if (q == c) { tc_ = ctok[q]; pc_ = cpar[q]; }
-                if (ctok[o] < tc_ || (ctok[o] == tc_ && cpar[o] < pc_)) c = o;
+            if (o > c && ((alive >> o) & 1u) &&
+                (ctok[o] < etok || (ctok[o] == etok && cpar[o] < epar))) {
+                c = o;
+                etok = ctok[o];
+                epar = cpar[o];
             }
-        int32_t etok = 0, epar = 0, e = 0, slot = 0;
-#pragma unroll
-        for (int q = 0; q < TIE_MAX; q++)
-            if (q == c) { etok = ctok[q]; epar = cpar[q]; e = cdep[q]; slot = cslot[q]; }
-        if (lane == 0) {
-            t_tok[n] = etok; t_par[n] = epar; t_score[n] = s;
-        }
+        if (lane == nn - n0) { otok = etok; opar = epar; }
         total += s;
         SD_CNT(lane == 0 ? 8 : 0);
-        // the node just taken has depth e; its only possible child is the suffix's token e
+        // the node just taken has depth e; its only possible child is the suffix's token e,
+        // which is win[c] at offset woff[c]
         int32_t next = -1;
-        if (e < D) {
-            int off = e - sg.cb[slot];
-            if (off < 0 || off >= W) {  // move this suffix's window to depth e
-                wsync();
-                if (lane == 0) sg.cb[slot] = e;
-                if (lane < W) sg.tc[(slot << sg.wlog) + lane] = text[(int64_t)sg.pos[slot] + e + lane];
-                wsync();
-                off = 0;
-            }
-            next = sg.tc[(slot << sg.wlog) + off];
-        }
 #pragma unroll
         for (int q = 0; q < TIE_MAX; q++)
-            if (q == c) { ctok[q] = next; cpar[q] = n; cdep[q] = e + 1; }
+            if (q == c) {
+                const int e = cdep[q];
+                if (e < D) {
+                    if (woff[q] >= 64) {  // reload the window further down the suffix
+                        win[q] = text[(int64_t)sg.pos[cslot[q]] + e + lane];
+                        woff[q] = 0;
+                    }
+                    next = __builtin_amdgcn_readlane(win[q], woff[q]);
+                }
+                woff[q]++;
+                ctok[q] = next; cpar[q] = nn; cdep[q] = e + 1;
+            }
         if (next < 0) alive &= ~(1u << c);
-        n++;
+        nn++;
+    }
+    n = nn;
+    if (lane < n - n0) {
+        t_tok[n0 + lane] = otok; t_par[n0 + lane] = opar; t_score[n0 + lane] = s;
     }
     // surviving heads go back into the frontier
 #pragma unroll
@@ -644,13 +684,13 @@ template <bool STATS>
 __device__ void match_global(const SpecParams &p, int32_t wk, int pl, int32_t &lo, int32_t &hi,
                              unsigned &nb) {
     const int lane = threadIdx.x & 63;
-    const int32_t w0 = __shfl(wk, 0);
+    const int32_t w0 = __builtin_amdgcn_readlane(wk, 0);
     const int32_t bv = lane < 2 ? p.g_bucket[w0 + 1 + lane] : 0;
     if (lane < 2) SD_CNT(4);
-    lo = __shfl(bv, 0);
-    hi = __shfl(bv, 1);
+    lo = __builtin_amdgcn_readlane(bv, 0);
+    hi = __builtin_amdgcn_readlane(bv, 1);
     if (pl == 1 || lo >= hi) return;
-    const int32_t w1 = __shfl(wk, 1);
+    const int32_t w1 = __builtin_amdgcn_readlane(wk, 1);
     const int32_t *col = p.g_tok1;
     int32_t l = lo, h = hi;
     if (h - l > SCAN_MAX) {  // wide bucket: bracket the second token by binary search first
@@ -662,7 +702,7 @@ __device__ void match_global(const SpecParams &p, int32_t wk, int pl, int32_t &l
             if (lane == 0 && doA) v = col[midA];
             if (lane == 1 && doB) v = col[midB];
             if (lane < 2) SD_CNT(4);
-            const int32_t vA = __shfl(v, 0), vB = __shfl(v, 1);
+            const int32_t vA = __builtin_amdgcn_readlane(v, 0), vB = __builtin_amdgcn_readlane(v, 1);
             if (doA) { if (vA < w1) la = midA + 1; else ha = midA; }
             if (doB) { if (vB <= w1) lu = midB + 1; else hu = midB; }
         }
@@ -784,9 +824,9 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
     const int nreq = gridDim.x / p.P;
     const int b = blockIdx.x % nreq, pl = p.P - blockIdx.x / nreq;
     const int64_t uidx = (int64_t)b * (2 * p.P) + src * p.P + (pl - 1);
-    const int32_t slot = slot_ids[b];
+    const int32_t slot = uni(slot_ids[b]);
     const bool slot_ok = slot >= 0 && slot < p.max_slots;
-    const int t = slot_ok ? p.r_len[slot] : 0;
+    const int t = slot_ok ? uni(p.r_len[slot]) : 0;
     const int32_t *x = p.r_text + (int64_t)(slot_ok ? slot : 0) * p.r_stride;
     const int K = (int)floor(p.alpha * (double)pl);
     uint32_t tick_setup = 0, tick_match = 0, tick_root = 0;
@@ -806,8 +846,10 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
         } else {
             // per-request structure: occurrences whose left-extension reaches pl, in the
             // order k_req_occurrences left them (sorted by what follows)
-            const int m1 = p.occ_n[b];
-            const int m = p.cntL[(int64_t)b * (p.P + 1) + pl];
+            const int m = uni(p.cntL[(int64_t)b * (p.P + 1) + pl]);
+            // m == 1 is the context's own tail alone: it stops at the end marker, so the
+            // unit has no candidate at all and nothing else needs to be read
+            const int m1 = m > 1 ? uni(p.occ_n[b]) : 0;
             const int2 *occ = p.occ + (int64_t)b * p.max_ctx;
             int32_t *usa = p.unit_sa + ((int64_t)b * p.P + (pl - 1)) * p.max_ctx;
             const bool narrow = m <= 64;
@@ -835,7 +877,7 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
             __threadfence_block();
             __syncthreads();
             lo = 0;
-            hi = m;  // == w
+            hi = m > 1 ? m : 0;  // == w when the list was gathered
             sa = usa;
             text = x;
         }
@@ -855,8 +897,8 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
             if (tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok, t_par, t_score, nb))
                 continue;
             const int bi = best.idx;
-            const int32_t blo = f.lo[bi], bhi = f.hi[bi];
-            int32_t d = f.dep[bi];
+            const int32_t blo = uni(f.lo[bi]), bhi = uni(f.hi[bi]);
+            int32_t d = uni(f.dep[bi]);
             if (lane == 0) {
                 t_tok[n] = best.tok; t_par[n] = best.par; t_score[n] = best.s;
             }
@@ -935,6 +977,12 @@ __global__ __launch_bounds__(64) void k_select(SpecParams p, sd_trees out) {
     flush_count<STATS>(nb, p.algo_bytes + SD_K_SELECT);
 }
 
+// Greedy verification walk, one wavefront per request, without walking: a node is "good" if
+// its token equals the target token at its parent; it is accepted iff it and all its
+// ancestors are good (siblings carry distinct tokens, so the accepted nodes form one path).
+// Ancestor chains are resolved by pointer jumping in LDS (log2(depth) rounds); because a
+// parent always has a lower index than its child, the path in walk order is the accepted
+// nodes in index order.
 __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nodes,
                                                const int32_t *__restrict__ tokens,
                                                const int32_t *__restrict__ parents, int max_nodes,
@@ -942,10 +990,9 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nod
                                                int32_t *__restrict__ accept_len,
                                                int32_t *__restrict__ accept_path,
                                                int32_t *__restrict__ bonus) {
-    // the whole tree sits in registers (node j in lane j % 64) and the targets in LDS, so the
-    // walk itself touches no global memory
     __shared__ int32_t s_tgt[257];
-    __shared__ int32_t s_path[256];
+    __shared__ int32_t s_anc[256];
+    __shared__ int32_t s_ok[256];
     const int lane = threadIdx.x, b = blockIdx.x;
     int n = n_nodes[b];
     if (n > max_nodes) n = max_nodes;
@@ -958,29 +1005,60 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nod
     for (int r = 0; r < 4; r++) {
         int j = lane + 64 * r;
         mt[r] = j < n ? tok[j] : -1;
-        mp[r] = j < n ? par[j] : -2;
+        mp[r] = j < n ? par[j] : -1;
     }
     for (int i = lane; i <= max_nodes; i += 64) s_tgt[i] = tgt[i];
     __syncthreads();
-    int v = -1, L = 0;
-    while (L < n) {
-        const int32_t want = s_tgt[v + 1];
-        int found = -1;
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-            uint64_t m = __ballot(mp[r] == v && mt[r] == want);
-            if (m && found < 0) found = 64 * r + __ffsll((unsigned long long)m) - 1;
+    for (int r = 0; r < 4; r++) {
+        int j = lane + 64 * r;
+        if (j < n) {
+            const bool wellformed = mp[r] >= -1 && mp[r] < j;
+            s_ok[j] = wellformed && mt[r] == s_tgt[mp[r] + 1];
+            s_anc[j] = wellformed ? mp[r] : -1;
         }
-        if (found < 0) break;
-        if (lane == 0) s_path[L] = found;
-        L++;
-        v = found;
     }
     __syncthreads();
-    for (int i = lane; i < max_nodes; i += 64) path[i] = i < L ? s_path[i] : -1;
+    for (int round = 0; round < 8; round++) {  // 2^8 >= the deepest possible path
+        int32_t ok[4], an[4];
+        bool open = false;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            int j = lane + 64 * r;
+            ok[r] = 0; an[r] = -1;
+            if (j < n) {
+                const int a = s_anc[j];
+                ok[r] = s_ok[j];
+                if (a >= 0) {
+                    ok[r] &= s_ok[a];
+                    an[r] = s_anc[a];
+                    open = true;
+                }
+            }
+        }
+        if (!__ballot(open)) break;
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            int j = lane + 64 * r;
+            if (j < n) { s_ok[j] = ok[r]; s_anc[j] = an[r]; }
+        }
+        __syncthreads();
+    }
+    int L = 0, last = -1;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        int j = lane + 64 * r;
+        const bool acc = j < n && s_ok[j];
+        const uint64_t m = __ballot(acc);
+        if (acc) path[L + __popcll(m & lanemask_lt())] = j;
+        if (m) last = 64 * r + 63 - __clzll((unsigned long long)m);
+        L += __popcll(m);
+    }
+    for (int i = L + lane; i < max_nodes; i += 64) path[i] = -1;
     if (lane == 0) {
         accept_len[b] = L;
-        bonus[b] = s_tgt[v + 1];
+        bonus[b] = s_tgt[last + 1];
     }
 }
 

@@ -246,3 +246,76 @@ def test_device_flags_bad_token_slot_and_overflow():
         assert not parity.compare_trees(got, want)
     finally:
         g.close()
+
+
+def test_decode_step_in_a_hip_graph_matches_eager():
+    """A decode step (speculate, verifier glue, accept, append) captured into a HIP graph and
+    replayed several times, with eager work and synchronisations in between, must give the
+    results of the same steps enqueued eagerly on a second context."""
+    import torch
+    import paper_2411_04975_amd as sd
+    from workloads import verifier
+    w = make_workload(scaled("tiny", batch=16), seed=3)
+    dev = torch.device("cuda", 0)
+    i32 = torch.int32
+    B, mn, steps = w.batch, w.max_nodes, 5
+    docs_tok = torch.from_numpy(w.corpus).to(dev)
+    docs_off = torch.from_numpy(w.doc_offsets).to(dev)
+    ctx_tok = torch.from_numpy(w.contexts.reshape(-1)).to(dev)
+    ctx_off = torch.arange(0, (B + 1) * w.ctx_len, w.ctx_len, dtype=torch.int64, device=dev)
+    future = torch.from_numpy(w.future).to(dev)
+    slots = torch.arange(B, dtype=i32, device=dev)
+
+    class Loop:
+        def __init__(self):
+            self.ctx = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, B,
+                                    w.ctx_len + (steps + 3) * (mn + 1), len(w.corpus) + 64, 0)
+            sd.sd_index_build(self.ctx, sd.SD_SCOPE_GLOBAL, None, docs_tok, docs_off, len(w.corpus))
+            sd.sd_index_build(self.ctx, sd.SD_SCOPE_REQUESTS, slots, ctx_tok, ctx_off,
+                              B * w.ctx_len)
+            self.trees = sd.Trees(B, mn, dev)
+            self.target = torch.zeros((B, mn + 1), dtype=i32, device=dev)
+            self.alen = torch.zeros(B, dtype=i32, device=dev)
+            self.apath = torch.zeros((B, mn), dtype=i32, device=dev)
+            self.bonus = torch.zeros(B, dtype=i32, device=dev)
+            self.new = torch.zeros(B * (mn + 1), dtype=i32, device=dev)
+            self.newoff = torch.zeros(B + 1, dtype=i32, device=dev)
+            self.pos = torch.zeros(B, dtype=i32, device=dev)
+
+        def step(self):
+            sd.sd_speculate(self.ctx, slots, self.trees)
+            verifier.targets(self.trees.n_nodes, self.trees.parents, future, self.pos, self.target)
+            sd.sd_accept(self.ctx, self.trees, B, self.target, self.alen, self.apath, self.bonus)
+            verifier.collect(self.trees.tokens, self.alen, self.apath, self.bonus, self.new,
+                             self.newoff, self.pos)
+            sd.sd_index_append(self.ctx, slots, self.new, self.newoff)
+
+        def snapshot(self):
+            torch.cuda.synchronize()
+            t = self.trees
+            return [x.clone() for x in (t.n_nodes, t.tokens, t.parents, t.scores, t.tree_score,
+                                        t.match_len, t.source, self.alen, self.apath, self.bonus,
+                                        self.pos)]
+
+    eager, graphed = Loop(), Loop()
+    try:
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            graphed.step()
+        torch.cuda.synchronize()
+        moved = 0
+        for i in range(steps):
+            eager.step()
+            want = eager.snapshot()
+            g.replay()
+            got = graphed.snapshot()
+            for a, b in zip(got, want):
+                assert torch.equal(a, b), "replay %d differs from the eager step" % i
+            moved += int(want[7].sum())
+            # unrelated eager work between replays
+            _ = (torch.arange(1000, device=dev) * 2).sum().item()
+        assert moved > 0
+    finally:
+        sd.sd_destroy(eager.ctx)
+        sd.sd_destroy(graphed.ctx)
