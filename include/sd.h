@@ -42,6 +42,14 @@
  *    nodes only, at most floor(alpha * p) of them.
  *  - Between candidate trees a strictly greater SCORE wins, scanning the
  *    global index for p = 1..P first and the per-request index after it.
+ *
+ * Variants (sd_config): den_mode 1 uses the denominator as printed in Section 3,
+ * C(N) = COUNT(N) / sum of COUNT over N's siblings (occurrences that stop at
+ * the parent are left out); linear 1 is the "linear" speculation of the
+ * baseline-comparison figure, which only grows one chain: after a node is
+ * added, only its own children are candidates; tau is the threshold of the
+ * hybrid scheme (Section 3, "Hybrid Suffix Speculative Decoding"): a request's
+ * draft is flagged for use iff SCORE > tau.
  */
 #ifndef SD_H
 #define SD_H
@@ -63,7 +71,7 @@ typedef enum {
     SD_ERR_STATE = 5
 } sd_status;
 
-/* Limits checked by sd_create: 1 <= P < D <= 255, P <= 64, alpha > 0,
+/* Limits checked by sd_create: den_mode and linear in {0, 1}, tau >= 0, 1 <= P < D <= 255, P <= 64, alpha > 0,
  * 1 <= floor(alpha*P) <= 256, 0 <= min_score <= 1, 1 <= vocab <= 2^24,
  * max_batch_slots >= 1, max_ctx_tokens >= 1, 0 <= max_global_tokens (documents
  * included, each document costs one extra position) < 2^31 - 4096. */
@@ -77,6 +85,9 @@ typedef struct {
     int32_t max_ctx_tokens;  /* per slot, growth by sd_index_append included        */
     int64_t max_global_tokens;
     int32_t device;          /* HIP device ordinal                                  */
+    int32_t den_mode;        /* 0: COUNT(parent) denominator; 1: sum over siblings  */
+    int32_t linear;          /* 0: tree speculation; 1: single chain                */
+    double tau;              /* hybrid threshold on SCORE (0 = always use the draft) */
 } sd_config;
 
 typedef enum { SD_SCOPE_GLOBAL = 0, SD_SCOPE_REQUESTS = 1 } sd_scope;
@@ -99,6 +110,7 @@ typedef struct {
     double *d_scores;     /* [batch * max_nodes] */
     double *d_tree_score; /* [batch]             */
     int32_t max_nodes;    /* >= floor(alpha * P) */
+    int32_t *d_use_draft; /* [batch] or NULL: 1 iff SCORE > tau (hybrid fallback gate) */
 } sd_trees;
 
 typedef struct {

@@ -33,7 +33,10 @@
  *   - a candidate whose score is below min_score is never added;
  *   - N_p itself is not a draft node: tree size and SCORE count draft nodes;
  *   - between candidate trees a strictly greater SCORE wins, scanning the
- *     global structure p = 1..P first, then the per-request one.
+ *     global structure p = 1..P first, then the per-request one;
+ *   - "linear" variant (caption of the baseline-comparison figure: speculation
+ *     that "only allows sequential token chains"): the candidates of a step are
+ *     the children of the node added last (of N_p at the start), nothing else.
  *
  * Pins: tests/test_oracle_pins.py checks this file against brute-force corpus
  * scans, closed forms and trie invariants written independently in Python.
@@ -303,7 +306,7 @@ static int cand_better(const sdo_cand *a, const sdo_cand *b) {
  * Outputs tokens/parents/scores of the draft nodes in the order they were
  * added (parent -1 = child of N_p) and SCORE = sum of scores in that order.
  * Returns the number of draft nodes. */
-int sdo_expand(const sdo_trie *t, int32_t np, int K, double min_score, int den_mode,
+int sdo_expand(const sdo_trie *t, int32_t np, int K, double min_score, int den_mode, int linear,
                int32_t *tokens, int32_t *parents, double *scores, double *tree_score) {
     sdo_frontier f = {0, 0, 0};
     int n = 0;
@@ -321,6 +324,7 @@ int sdo_expand(const sdo_trie *t, int32_t np, int K, double min_score, int den_m
         total += b.score;
         f.a[best] = f.a[f.n - 1];
         f.n--;
+        if (linear) f.n = 0; /* a chain: only the new node's children may follow */
         frontier_add_children(t, &f, b.node, n, b.score, den_mode);
         n++;
     }
@@ -331,13 +335,13 @@ int sdo_expand(const sdo_trie *t, int32_t np, int K, double min_score, int den_m
 
 /* One (structure, p) unit: match then expand with K = floor(alpha * p). */
 int sdo_speculate_unit(const sdo_trie *t, const int32_t *x, int64_t tlen, int p, double alpha,
-                       double min_score, int den_mode, int32_t *tokens, int32_t *parents,
-                       double *scores, double *tree_score) {
+                       double min_score, int den_mode, int linear, int32_t *tokens,
+                       int32_t *parents, double *scores, double *tree_score) {
     *tree_score = 0.0;
     int32_t np = sdo_match(t, x, tlen, p);
     if (np < 0) return -1;
     int K = (int)floor(alpha * (double)p);
-    return sdo_expand(t, np, K, min_score, den_mode, tokens, parents, scores, tree_score);
+    return sdo_expand(t, np, K, min_score, den_mode, linear, tokens, parents, scores, tree_score);
 }
 
 /* GenerateCandidateTree (Algorithm 1): best tree over {global, request} x p=1..P.
@@ -346,8 +350,9 @@ int sdo_speculate_unit(const sdo_trie *t, const int32_t *x, int64_t tlen, int p,
  * match_len (0 if none) and source (0 global, 1 request, -1 none).
  * tokens/parents/scores need room for floor(alpha*P) entries; tmp_* likewise. */
 int sdo_generate(const sdo_trie *tg, const sdo_trie *tr, const int32_t *x, int64_t tlen, int P,
-                 double alpha, double min_score, int den_mode, int32_t *tokens, int32_t *parents,
-                 double *scores, double *tree_score, int32_t *match_len, int32_t *source) {
+                 double alpha, double min_score, int den_mode, int linear, int32_t *tokens,
+                 int32_t *parents, double *scores, double *tree_score, int32_t *match_len,
+                 int32_t *source) {
     int maxn = (int)floor(alpha * (double)P);
     if (maxn < 1) maxn = 1;
     int32_t *tt = (int32_t *)malloc(sizeof(int32_t) * (size_t)maxn);
@@ -361,7 +366,8 @@ int sdo_generate(const sdo_trie *tg, const sdo_trie *tr, const int32_t *x, int64
         if (!t) continue;
         for (int p = 1; p <= P; p++) {
             double sc;
-            int n = sdo_speculate_unit(t, x, tlen, p, alpha, min_score, den_mode, tt, tp, ts, &sc);
+            int n = sdo_speculate_unit(t, x, tlen, p, alpha, min_score, den_mode, linear, tt, tp, ts,
+                                       &sc);
             if (n > 0 && sc > best) {
                 best = sc; best_n = n; *match_len = p; *source = s;
                 memcpy(tokens, tt, sizeof(int32_t) * (size_t)n);

@@ -58,10 +58,10 @@ def _load():
     L.sdo_match.argtypes = [vp, i32p, C.c_int64, C.c_int]
     L.sdo_speculate_unit.restype = C.c_int
     L.sdo_speculate_unit.argtypes = [vp, i32p, C.c_int64, C.c_int, C.c_double, C.c_double, C.c_int,
-                                     i32p, i32p, f64p, f64p]
+                                     C.c_int, i32p, i32p, f64p, f64p]
     L.sdo_generate.restype = C.c_int
     L.sdo_generate.argtypes = [vp, vp, i32p, C.c_int64, C.c_int, C.c_double, C.c_double, C.c_int,
-                               i32p, i32p, f64p, f64p, i32p, i32p]
+                               C.c_int, i32p, i32p, f64p, f64p, i32p, i32p]
     L.sdo_accept.restype = C.c_int
     L.sdo_accept.argtypes = [C.c_int, i32p, i32p, i32p, i32p, i32p]
     _lib = L
@@ -138,9 +138,11 @@ class Trie:
         return int(self._L.sdo_match(self._h, _p(x, C.c_int32), x.shape[0], p))
 
 
-def speculate_unit(trie: Trie, x, p: int, alpha: float, min_score: float, den_mode: int = 0):
+def speculate_unit(trie: Trie, x, p: int, alpha: float, min_score: float, den_mode: int = 0,
+                   linear: int = 0):
     """One (structure, p) unit.  Returns None if the pattern does not match, else
-    (tokens, parents, scores, tree_score)."""
+    (tokens, parents, scores, tree_score).  den_mode 1 = the printed sibling-sum denominator;
+    linear 1 = the chain-only variant."""
     L = _load()
     x = _i32(x)
     K = max(1, int(np.floor(alpha * p)))
@@ -149,7 +151,7 @@ def speculate_unit(trie: Trie, x, p: int, alpha: float, min_score: float, den_mo
     sc = np.zeros(K, np.float64)
     ts = C.c_double()
     n = L.sdo_speculate_unit(trie._h, _p(x, C.c_int32), x.shape[0], p, alpha, min_score, den_mode,
-                             _p(tok, C.c_int32), _p(par, C.c_int32), _p(sc, C.c_double),
+                             linear, _p(tok, C.c_int32), _p(par, C.c_int32), _p(sc, C.c_double),
                              C.byref(ts))
     if n < 0:
         return None
@@ -157,7 +159,7 @@ def speculate_unit(trie: Trie, x, p: int, alpha: float, min_score: float, den_mo
 
 
 def generate(tg: Optional[Trie], tr: Optional[Trie], x, P: int, alpha: float, min_score: float,
-             den_mode: int = 0):
+             den_mode: int = 0, linear: int = 0):
     """GenerateCandidateTree.  Returns dict(tokens, parents, scores, tree_score, match_len,
     source, n_nodes)."""
     L = _load()
@@ -169,7 +171,7 @@ def generate(tg: Optional[Trie], tr: Optional[Trie], x, P: int, alpha: float, mi
     ts = C.c_double()
     ml, src = C.c_int32(), C.c_int32()
     n = L.sdo_generate(tg._h if tg is not None else None, tr._h if tr is not None else None,
-                       _p(x, C.c_int32), x.shape[0], P, alpha, min_score, den_mode,
+                       _p(x, C.c_int32), x.shape[0], P, alpha, min_score, den_mode, linear,
                        _p(tok, C.c_int32), _p(par, C.c_int32), _p(sc, C.c_double), C.byref(ts),
                        C.byref(ml), C.byref(src))
     return dict(tokens=tok[:n].copy(), parents=par[:n].copy(), scores=sc[:n].copy(),

@@ -34,13 +34,15 @@ class _Config(C.Structure):
     _fields_ = [("vocab", C.c_int32), ("D", C.c_int32), ("P", C.c_int32), ("alpha", C.c_double),
                 ("min_score", C.c_double), ("max_batch_slots", C.c_int32),
                 ("max_ctx_tokens", C.c_int32), ("max_global_tokens", C.c_int64),
-                ("device", C.c_int32)]
+                ("device", C.c_int32), ("den_mode", C.c_int32), ("linear", C.c_int32),
+                ("tau", C.c_double)]
 
 
 class _Trees(C.Structure):
     _fields_ = [("d_n_nodes", C.c_void_p), ("d_tokens", C.c_void_p), ("d_parents", C.c_void_p),
                 ("d_match_len", C.c_void_p), ("d_source", C.c_void_p), ("d_scores", C.c_void_p),
-                ("d_tree_score", C.c_void_p), ("max_nodes", C.c_int32)]
+                ("d_tree_score", C.c_void_p), ("max_nodes", C.c_int32),
+                ("d_use_draft", C.c_void_p)]
 
 
 class _Stats(C.Structure):
@@ -144,10 +146,11 @@ def _stream(stream, ctx: _Ctx):
 
 
 def sd_create(vocab: int, D: int, P: int, alpha: float, min_score: float, max_batch_slots: int,
-              max_ctx_tokens: int, max_global_tokens: int, device: int = 0) -> _Ctx:
+              max_ctx_tokens: int, max_global_tokens: int, device: int = 0, den_mode: int = 0,
+              linear: int = 0, tau: float = 0.0) -> _Ctx:
     L = _load()
     cfg = _Config(vocab, D, P, alpha, min_score, max_batch_slots, max_ctx_tokens, max_global_tokens,
-                  device)
+                  device, den_mode, linear, tau)
     h = C.c_void_p()
     code = L.sd_create(C.byref(cfg), C.byref(h))
     if code != 0:
@@ -174,6 +177,7 @@ class Trees:
         self.source = torch.full((batch,), -1, dtype=i32, device=device)
         self.scores = torch.zeros((batch, max_nodes), dtype=f64, device=device)
         self.tree_score = torch.zeros(batch, dtype=f64, device=device)
+        self.use_draft = torch.zeros(batch, dtype=i32, device=device)
 
     def _struct(self, ctx: _Ctx, batch: int) -> _Trees:
         i32, f64 = torch.int32, torch.float64
@@ -184,7 +188,8 @@ class Trees:
                       _ptr(self.match_len, i32, ctx, batch, "match_len"),
                       _ptr(self.source, i32, ctx, batch, "source"),
                       _ptr(self.scores, f64, ctx, batch * mn, "scores"),
-                      _ptr(self.tree_score, f64, ctx, batch, "tree_score"), mn)
+                      _ptr(self.tree_score, f64, ctx, batch, "tree_score"), mn,
+                      _ptr(self.use_draft, i32, ctx, batch, "use_draft"))
 
 
 def sd_index_build(ctx: _Ctx, scope: int, slot_ids: Optional[torch.Tensor], tokens: torch.Tensor,

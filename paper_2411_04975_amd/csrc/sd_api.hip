@@ -60,6 +60,9 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     if (cfg->P < 1 || cfg->P > 64 || cfg->D <= cfg->P || cfg->D > 255) return SD_ERR_INVALID_ARG;
     if (!(cfg->alpha > 0.0) || !(cfg->min_score >= 0.0) || !(cfg->min_score <= 1.0))
         return SD_ERR_INVALID_ARG;
+    if (cfg->den_mode < 0 || cfg->den_mode > 1 || cfg->linear < 0 || cfg->linear > 1 ||
+        !(cfg->tau >= 0.0))
+        return SD_ERR_INVALID_ARG;
     const double mn = floor(cfg->alpha * (double)cfg->P);
     if (!(mn >= 1.0) || !(mn <= 256.0)) return SD_ERR_INVALID_ARG;
     if (cfg->max_batch_slots < 1 || cfg->max_ctx_tokens < 1 || cfg->max_global_tokens < 0 ||
@@ -82,7 +85,7 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     const int64_t B = cfg->max_batch_slots, P = cfg->P, ctx = cfg->max_ctx_tokens;
     c->r_stride = ((ctx + SD_TEXT_PAD + 63) / 64) * 64;
     const int64_t tiles = (cap + 4095) / 4096 + 1;
-    c->b_hist_cap = 256 * tiles;
+    c->b_hist_cap = 256 * tiles + 256;  // (digit, tile) table + one total per digit
     const int64_t scan_n = c->b_hist_cap > cap ? c->b_hist_cap : cap;
     c->b_partials_cap = (scan_n + 4095) / 4096 + 1;
     bool ok = true;

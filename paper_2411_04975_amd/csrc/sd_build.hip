@@ -75,14 +75,18 @@ __global__ __launch_bounds__(TB) void k_assign_rank(const uint32_t *__restrict__
     rank[sa[i]] = gid[i];
 }
 
+// key of suffix-array entry i for the next round: (its own group number, the group number of
+// the suffix h positions further).  The first is gid[i], read in order; only the second is a
+// gather.
 __global__ __launch_bounds__(TB) void k_round_keys(const uint32_t *__restrict__ sa,
+                                                   const uint32_t *__restrict__ gid,
                                                    const uint32_t *__restrict__ rank, int64_t N,
                                                    int64_t h, int rank_bits,
                                                    uint64_t *__restrict__ keys) {
     int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
     if (i >= N) return;
     int64_t p = sa[i];
-    uint64_t r1 = rank[p];
+    uint64_t r1 = gid[i];
     uint64_t r2 = (p + h < N) ? rank[p + h] : 0u;
     keys[i] = (r1 << rank_bits) | r2;
 }
@@ -214,7 +218,7 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
             sd_scan_inclusive_u32(c, c->b_flags, N, st);
             SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_assign_rank, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_flags, N, c->b_rank);
             if (h >= c->cfg.D) break;
-            SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_rank, N, h, rank_bits, c->b_keys[cur]);
+            SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_flags, c->b_rank, N, h, rank_bits, c->b_keys[cur]);
             cur = sd_sort_pairs(c, N, 2 * rank_bits, cur, st);
             h *= 2;
         }

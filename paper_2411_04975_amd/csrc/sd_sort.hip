@@ -1,8 +1,8 @@
 // LSD radix sort of (uint64 key, uint32 value) pairs and a device-wide prefix sum, both
 // hand-written for 64-wide wavefronts.  Used by the suffix-array construction in sd_build.hip.
 //
-// One pass = three launches: per-tile digit histogram, prefix sum over the (digit, tile)
-// table, stable scatter.  Inside a tile the stable rank of a key among keys with the same
+// One pass = three launches: per-tile digit histogram, per-digit prefix sums along the tiles,
+// stable scatter.  Inside a tile the stable rank of a key among keys with the same
 // digit comes from wave-wide ballots (all lanes holding the same digit find each other with
 // one ballot per digit bit), so no shared-memory atomics are contended.  The scatter first
 // orders the tile by digit in LDS, so that global writes go out as runs of neighbouring lanes.
@@ -82,10 +82,44 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t *__res
     tile_hist[(int64_t)tid * ntiles + blockIdx.x] = tot;
 }
 
+// One workgroup per digit: exclusive prefix sum along the digit's row of the (digit, tile)
+// table, in place, and the row total.  The scatter adds the prefix over digit totals itself
+// (256 values), so a pass needs no device-wide scan.
+__global__ __launch_bounds__(RS_THREADS) void k_radix_rowscan(uint32_t *__restrict__ tile_hist,
+                                                              int64_t ntiles,
+                                                              uint32_t *__restrict__ row_total) {
+    __shared__ uint32_t s_wave[RS_WAVES];
+    __shared__ uint32_t s_carry;
+    uint32_t *row = tile_hist + (int64_t)blockIdx.x * ntiles;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    constexpr int PER = 8;
+    for (int64_t base = 0; base < ntiles; base += RS_THREADS * PER) {
+        const int64_t i0 = base + (int64_t)threadIdx.x * PER;
+        uint32_t v[PER], sum = 0;
+#pragma unroll
+        for (int k = 0; k < PER; k++) {
+            v[k] = i0 + k < ntiles ? row[i0 + k] : 0u;
+            sum += v[k];
+        }
+        uint32_t tot;
+        uint32_t ex = block_excl_scan_256(sum, s_wave, &tot) + s_carry;
+#pragma unroll
+        for (int k = 0; k < PER; k++) {
+            if (i0 + k < ntiles) row[i0 + k] = ex;
+            ex += v[k];
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) s_carry += tot;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) row_total[blockIdx.x] = s_carry;
+}
+
 __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
     const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin, uint64_t *__restrict__ kout,
-    uint32_t *__restrict__ vout, int64_t n, int shift, const uint32_t *__restrict__ offs_incl,
-    int64_t ntiles) {
+    uint32_t *__restrict__ vout, int64_t n, int shift, const uint32_t *__restrict__ row_excl,
+    const uint32_t *__restrict__ row_total, int64_t ntiles) {
     __shared__ uint64_t s_keys[RS_TILE];
     __shared__ uint32_t s_vals[RS_TILE];
     __shared__ volatile uint32_t s_wcnt[RS_WAVES][RS_BINS];
@@ -134,8 +168,9 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
         }
         uint32_t ex = block_excl_scan_256(acc, s_wave, nullptr);
         s_excl[d] = ex;
-        int64_t idx = (int64_t)d * ntiles + blockIdx.x;
-        s_gbase[d] = idx > 0 ? offs_incl[idx - 1] : 0u;
+        // keys with a smaller digit anywhere + keys with this digit in earlier tiles
+        uint32_t digit_base = block_excl_scan_256(row_total[d], s_wave, nullptr);
+        s_gbase[d] = digit_base + row_excl[(int64_t)d * ntiles + blockIdx.x];
     }
     __syncthreads();
 #pragma unroll
@@ -252,12 +287,17 @@ int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st) {
             hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
                                c->b_keys[cur], n, shift, c->b_hist, ntiles);
         }
-        sd_scan_inclusive_u32(c, c->b_hist, (int64_t)RS_BINS * ntiles, st);
+        {
+            sd_span sp(c, SD_K_SORT_SCAN, st);
+            hipLaunchKernelGGL(k_radix_rowscan, dim3(RS_BINS), dim3(RS_THREADS), 0, st, c->b_hist,
+                               ntiles, c->b_hist + (int64_t)RS_BINS * ntiles);
+        }
         {
             sd_span sp(c, SD_K_SORT_SCATTER, st);
             hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
                                c->b_keys[cur], c->b_vals[cur], c->b_keys[cur ^ 1],
-                               c->b_vals[cur ^ 1], n, shift, c->b_hist, ntiles);
+                               c->b_vals[cur ^ 1], n, shift, c->b_hist,
+                               c->b_hist + (int64_t)RS_BINS * ntiles, ntiles);
         }
         cur ^= 1;
     }

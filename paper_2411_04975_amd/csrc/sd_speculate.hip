@@ -30,7 +30,8 @@ struct SpecParams {
     int64_t r_stride;
     int32_t max_slots, max_ctx;
     int32_t D, P, max_nodes;
-    double alpha, min_score;
+    int32_t den_mode, linear;
+    double alpha, min_score, tau;
     int2 *occ;
     int32_t *occ_n, *cntL, *unit_sa, *unit_n;
     double *unit_score;
@@ -402,27 +403,31 @@ __device__ __forceinline__ int stage_node(Stage &sg, const int32_t *__restrict__
 template <bool STATS>
 __device__ void push_children(Frontier &f, int hole, Stage &sg, const int32_t *__restrict__ sa,
                               const int32_t *__restrict__ text, int32_t lo, int32_t hi, int32_t d,
-                              int32_t parent, double ps, double min_score, int32_t D, unsigned &nb) {
+                              int32_t parent, double ps, double min_score, int32_t D, int den_mode,
+                              unsigned &nb) {
     if (d >= D) {  // a path of D tokens has no continuation
         frontier_close(f, hole);
         return;
     }
     const int lane = threadIdx.x & 63;
     const int32_t m = hi - lo;
-    const double den = (double)m;
     if (m <= 64) {
         const bool in = lane < m;
         const int mycb = stage_node(sg, sa, text, lo, m, d);
         int32_t tok = 0x7fffffff;
         if (in) tok = sg.tc[((lo - sg.lo + lane) << sg.wlog) + (d - mycb)];
         if (in) SD_CNT(8);
+        // denominator of C(N): all occurrences of the node, or (den_mode 1) only those that
+        // go on, i.e. the sum over the children
+        const int32_t dn = den_mode ? m - __popcll(__ballot(in && tok < 0)) : m;
+        const double den = (double)dn;
         int32_t prev = __shfl_up(tok, 1);
         bool start = in && (lane == 0 || tok != prev);
         uint64_t S = __ballot(start);
         uint64_t above = lane == 63 ? 0ull : (S >> (lane + 1));
         int32_t e = above ? lane + 1 + (__ffsll((unsigned long long)above) - 1) : m;
         int32_t c = e - lane;
-        double sc = c == m ? ps : ps * ((double)c / den);  // x / x == 1 and ps * 1 == ps exactly
+        double sc = c == dn ? ps : ps * ((double)c / den);  // x / x == 1 and ps * 1 == ps exactly
         bool cand = start && tok >= 0 && sc >= min_score;
         frontier_put(f, hole, cand, sc, tok, parent, lo + lane, lo + e, d + 1);
         return;
@@ -433,6 +438,18 @@ __device__ void push_children(Frontier &f, int hole, Stage &sg, const int32_t *_
     // little low (factor 1 - 1e-9) so that rounding can never hide an admissible child; the
     // exact binary64 test below decides.
     frontier_close(f, hole);
+    int32_t dn = m;
+    if (den_mode) {  // leave out the suffixes that stop here: they sit first in the range
+        int32_t l = lo, h = hi;
+        while (l < h) {
+            int32_t mid = l + ((h - l) >> 1);
+            if (lane == 0) SD_CNT(8);
+            if (text[(int64_t)sa[mid] + d] < 0) l = mid + 1; else h = mid;
+        }
+        dn = hi - l;
+        if (dn == 0) return;
+    }
+    const double den = (double)dn;
     int64_t stride = (int64_t)floor(min_score * den / ps * (1.0 - 1e-9));
     if (stride < 1) stride = 1;
     const int64_t np = ((int64_t)m + stride - 1) / stride;
@@ -796,6 +813,7 @@ __device__ void select_request(const SpecParams &p, const sd_trees &out, int b, 
         out.d_tree_score[b] = bu >= 0 ? bs : 0.0;
         out.d_match_len[b] = bu >= 0 ? bu % p.P + 1 : 0;
         out.d_source[b] = bu >= 0 ? bu / p.P : -1;
+        if (out.d_use_draft) out.d_use_draft[b] = (bu >= 0 && bs > p.tau) ? 1 : 0;
         SD_CNT(24);
     }
 }
@@ -889,12 +907,14 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
     if (hi > lo) {
         f.n = 0;
         f.cap = K;
-        push_children<STATS>(f, -1, sg, sa, text, lo, hi, pl, -1, 1.0, p.min_score, p.D, nb);
+        push_children<STATS>(f, -1, sg, sa, text, lo, hi, pl, -1, 1.0, p.min_score, p.D, p.den_mode,
+                             nb);
         if (STATS) tick_root = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(f.n & 0);
         while (n < K && f.n > 0) {
             const Key best = frontier_pick(f, true, -1);
             if (best.s < p.min_score) break;
-            if (tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok, t_par, t_score, nb))
+            if (!p.linear &&
+                tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok, t_par, t_score, nb))
                 continue;
             const int bi = best.idx;
             const int32_t blo = uni(f.lo[bi]), bhi = uni(f.hi[bi]);
@@ -904,6 +924,11 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
             }
             total += best.s;
             int cur = n++;
+            int hole = bi;
+            if (p.linear) {  // chain variant: nothing but the new node's children may follow
+                f.n = 0;
+                hole = -1;
+            }
             // Unary run: while all suffixes of the node agree on the next token and none has
             // ended, the node has exactly one child, with the node's own score (count ratio 1).
             // If that score is strictly above everything else in the frontier, the greedy
@@ -922,7 +947,7 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
                 uint64_t ok = __ballot(tk >= 0 && lane < lim);
                 int L = ~ok ? __ffsll((unsigned long long)~ok) - 1 : 64;
                 if (L > 0) {
-                    bool dominant = f.n == 1;
+                    bool dominant = f.n <= 1;
                     if (!dominant) {
                         Key second = frontier_pick(f, true, bi);
                         dominant = second.s < best.s;
@@ -941,10 +966,10 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
                 }
             }
             if (n < K)
-                push_children<STATS>(f, bi, sg, sa, text, blo, bhi, d, cur, best.s, p.min_score, p.D,
-                                     nb);
+                push_children<STATS>(f, hole, sg, sa, text, blo, bhi, d, cur, best.s, p.min_score,
+                                     p.D, p.den_mode, nb);
             else
-                frontier_close(f, bi);  // the last node taken cannot contribute further nodes
+                frontier_close(f, hole);  // the last node taken cannot contribute further nodes
         }
     }
     wsync();
@@ -1073,7 +1098,8 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     p.r_text = c->r_text; p.r_len = c->r_len; p.r_stride = c->r_stride;
     p.max_slots = c->cfg.max_batch_slots; p.max_ctx = c->cfg.max_ctx_tokens;
     p.D = c->cfg.D; p.P = c->cfg.P; p.max_nodes = c->max_nodes;
-    p.alpha = c->cfg.alpha; p.min_score = c->cfg.min_score;
+    p.alpha = c->cfg.alpha; p.min_score = c->cfg.min_score; p.tau = c->cfg.tau;
+    p.den_mode = c->cfg.den_mode; p.linear = c->cfg.linear;
     p.occ = c->s_occ; p.occ_n = c->s_occ_n; p.cntL = c->s_cntL; p.unit_sa = c->s_unit_sa;
     p.unit_n = c->s_unit_n; p.unit_score = c->s_unit_score; p.unit_tok = c->s_unit_tok;
     p.unit_par = c->s_unit_par; p.unit_sc = c->s_unit_sc; p.err = c->d_err;

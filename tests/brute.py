@@ -42,7 +42,7 @@ def ends(docs, w, D):
     return sum(1 for d, i in occurrences(docs, w) if i + k == len(docs[d]))
 
 
-def speculate_unit(docs, x, p, alpha, min_score, D, den_mode=0):
+def speculate_unit(docs, x, p, alpha, min_score, D, den_mode=0, linear=0):
     """Greedy tree for one (collection, p).  Returns None when the last p tokens of x do not
     occur, else (tokens, parents, scores, tree_score)."""
     x = [int(v) for v in x]
@@ -76,6 +76,8 @@ def speculate_unit(docs, x, p, alpha, min_score, D, den_mode=0):
         if best[0] < min_score:
             break
         frontier.remove(best)
+        if linear:
+            del frontier[:]
         j = len(toks)
         toks.append(best[1]); pars.append(best[2]); scs.append(best[0])
         total += best[0]
@@ -83,7 +85,7 @@ def speculate_unit(docs, x, p, alpha, min_score, D, den_mode=0):
     return toks, pars, scs, total
 
 
-def generate(global_docs, request_seq, P, alpha, min_score, D, den_mode=0):
+def generate(global_docs, request_seq, P, alpha, min_score, D, den_mode=0, linear=0):
     """Best tree over (global, p=1..P) then (request, p=1..P); strictly greater wins."""
     x = [int(v) for v in request_seq]
     best = dict(tokens=[], parents=[], scores=[], tree_score=0.0, match_len=0, source=-1)
@@ -91,7 +93,7 @@ def generate(global_docs, request_seq, P, alpha, min_score, D, den_mode=0):
         if docs is None:
             continue
         for p in range(1, P + 1):
-            r = speculate_unit(docs, x, p, alpha, min_score, D, den_mode)
+            r = speculate_unit(docs, x, p, alpha, min_score, D, den_mode, linear)
             if r is None:
                 continue
             if len(r[0]) > 0 and r[3] > best["tree_score"]:

@@ -25,7 +25,8 @@ def oracle_global_trie(docs, D, vocab, contexts=None, P=None):
     return t
 
 
-def oracle_speculate_batch(tg, contexts, D, P, alpha, min_score, max_nodes, request_tries=None):
+def oracle_speculate_batch(tg, contexts, D, P, alpha, min_score, max_nodes, request_tries=None,
+                           den_mode=0, linear=0):
     B = len(contexts)
     out = dict(n_nodes=np.zeros(B, np.int32), tokens=np.full((B, max_nodes), -1, np.int32),
                parents=np.full((B, max_nodes), -1, np.int32),
@@ -38,7 +39,7 @@ def oracle_speculate_batch(tg, contexts, D, P, alpha, min_score, max_nodes, requ
             tr = oracle.Trie(D)
             if len(x):
                 tr.append(x)
-        g = oracle.generate(tg, tr, x, P, alpha, min_score)
+        g = oracle.generate(tg, tr, x, P, alpha, min_score, den_mode, linear)
         n = g["n_nodes"]
         out["n_nodes"][b] = n
         out["tokens"][b, :n] = g["tokens"]
@@ -53,12 +54,14 @@ def oracle_speculate_batch(tg, contexts, D, P, alpha, min_score, max_nodes, requ
 class GpuPath:
     """The HIP library driven through its binding, inputs handed over as numpy arrays."""
 
-    def __init__(self, vocab, D, P, alpha, min_score, max_slots, max_ctx, max_global):
+    def __init__(self, vocab, D, P, alpha, min_score, max_slots, max_ctx, max_global, den_mode=0,
+                 linear=0, tau=0.0):
         import torch
         import paper_2411_04975_amd as sd
         self.sd, self.torch = sd, torch
         self.dev = torch.device("cuda", 0)
-        self.ctx = sd.sd_create(vocab, D, P, alpha, min_score, max_slots, max_ctx, max_global, 0)
+        self.ctx = sd.sd_create(vocab, D, P, alpha, min_score, max_slots, max_ctx, max_global, 0,
+                                den_mode, linear, tau)
         self.max_nodes = self.ctx.max_nodes
 
     def close(self):
@@ -105,6 +108,7 @@ class GpuPath:
         # poison the outputs so that unwritten entries show up
         tr.tokens.fill_(-7); tr.parents.fill_(-7); tr.scores.fill_(-7.0); tr.n_nodes.fill_(-7)
         tr.match_len.fill_(-7); tr.source.fill_(-7); tr.tree_score.fill_(-7.0)
+        tr.use_draft.fill_(-7)
         self.sd.sd_speculate(self.ctx, torch.tensor(list(slots), dtype=torch.int32,
                                                     device=self.dev), tr)
         torch.cuda.synchronize()
@@ -112,7 +116,7 @@ class GpuPath:
         return dict(n_nodes=tr.n_nodes.cpu().numpy(), tokens=tr.tokens.cpu().numpy(),
                     parents=tr.parents.cpu().numpy(), scores=tr.scores.cpu().numpy(),
                     tree_score=tr.tree_score.cpu().numpy(), match_len=tr.match_len.cpu().numpy(),
-                    source=tr.source.cpu().numpy())
+                    source=tr.source.cpu().numpy(), use_draft=tr.use_draft.cpu().numpy())
 
     def accept(self, target):
         torch = self.torch

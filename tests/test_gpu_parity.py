@@ -319,3 +319,69 @@ def test_decode_step_in_a_hip_graph_matches_eager():
     finally:
         sd.sd_destroy(eager.ctx)
         sd.sd_destroy(graphed.ctx)
+
+
+VARIANTS = [(1, 0), (0, 1), (1, 1)]
+
+
+@pytest.mark.parametrize("den_mode,linear", VARIANTS)
+@pytest.mark.parametrize("cfg", ["tiny", "agentic-s", "lowrep-s"])
+def test_variants_sibling_denominator_and_linear(cfg, den_mode, linear):
+    """The printed sibling-sum denominator and the chain-only ("linear") variant, alone and
+    together, against the oracle run with the same switches."""
+    if cfg == "tiny":
+        w = make_workload("tiny", seed=5)
+    elif cfg == "agentic-s":
+        w = make_workload(scaled("agentic", n_docs=300, batch=32, ctx=2048), seed=1, name=cfg)
+    else:
+        w = make_workload(scaled("lowrep", n_docs=150, batch=48, ctx=4096), seed=1, name=cfg)
+    docs = w.docs()
+    contexts = [w.contexts[b] for b in range(w.batch)]
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, w.batch, w.ctx_len + 64,
+                       len(w.corpus) + len(docs), den_mode=den_mode, linear=linear, tau=2.5)
+    try:
+        g.build_global(docs)
+        g.build_requests(range(w.batch), contexts)
+        got = g.speculate(range(w.batch))
+        tg = parity.oracle_global_trie(docs, w.D, w.vocab, contexts, w.P)
+        want = parity.oracle_speculate_batch(tg, contexts, w.D, w.P, w.alpha, w.min_score,
+                                             w.max_nodes, den_mode=den_mode, linear=linear)
+        bad = parity.compare_trees(got, want, "%s den=%d linear=%d" % (cfg, den_mode, linear))
+        assert not bad, "\n".join(bad)
+        # hybrid gate (Section 3): the draft is used iff SCORE > tau
+        assert np.array_equal(got["use_draft"], (want["tree_score"] > 2.5).astype(np.int32))
+        if linear:
+            n = want["n_nodes"]
+            for b in range(w.batch):
+                assert list(got["parents"][b, :n[b]]) == list(range(-1, n[b] - 1))
+        # the switches change results on these inputs (otherwise the test proves nothing)
+        base = parity.oracle_speculate_batch(tg, contexts, w.D, w.P, w.alpha, w.min_score,
+                                             w.max_nodes)
+        if cfg == "tiny":
+            assert any(not np.array_equal(base[k], want[k]) for k in ("tokens", "parents", "scores"))
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("den_mode,linear", VARIANTS)
+def test_variants_on_adversarial_minis(den_mode, linear):
+    rng = np.random.default_rng(8)
+    for name, vocab, D, P, alpha, ms, docs, contexts in MINIS:
+        if contexts is None:
+            contexts = [list(rng.integers(0, vocab, int(rng.integers(1, 300)))) for _ in range(8)]
+        docs_a = [np.asarray(d, np.int32) for d in docs]
+        ctx_a = [np.asarray(c, np.int32) for c in contexts]
+        B = len(ctx_a)
+        g = parity.GpuPath(vocab, D, P, alpha, ms, B, 512, sum(len(d) for d in docs_a) + len(docs_a),
+                           den_mode=den_mode, linear=linear)
+        try:
+            g.build_global(docs_a)
+            g.build_requests(range(B), ctx_a)
+            got = g.speculate(range(B))
+            tg = parity.oracle_global_trie(docs_a, D, vocab)
+            want = parity.oracle_speculate_batch(tg, ctx_a, D, P, alpha, ms, g.max_nodes,
+                                                 den_mode=den_mode, linear=linear)
+            bad = parity.compare_trees(got, want, name)
+            assert not bad, "\n".join(bad)
+        finally:
+            g.close()

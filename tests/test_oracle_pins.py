@@ -397,3 +397,66 @@ def test_planted_mistakes_are_caught():
     assert run(lambda d, x, p: brute.speculate_unit(d, x, p, alpha, ms, D, 1)) > 0
     # pattern taken from the wrong end of the context
     assert run(lambda d, x, p: brute.speculate_unit(d, x[::-1], p, alpha, ms, D)) > 0
+
+
+@pytest.mark.parametrize("den_mode", [0, 1])
+@pytest.mark.parametrize("seed,vocab,D,P,alpha,ms", [
+    (0, 2, 6, 3, 2.0, 0.05), (1, 3, 8, 4, 1.0, 0.1), (2, 4, 10, 5, 3.0, 0.0), (3, 3, 5, 4, 1.5, 0.3)])
+def test_linear_variant_matches_trie_free_speculator(seed, vocab, D, P, alpha, ms, den_mode):
+    rng = np.random.default_rng(200 + seed)
+    docs = _rand_docs(rng, vocab, 4, 5, 40)
+    tg = oracle.Trie(D)
+    for d in docs:
+        tg.add_doc(d)
+    differs = 0
+    for q in range(6):
+        x = rng.integers(0, vocab, size=int(rng.integers(1, 25))).astype(np.int32)
+        tr = oracle.Trie(D)
+        tr.append(x)
+        for p in range(1, P + 1):
+            for trie, coll in ((tg, docs), (tr, [x])):
+                got = oracle.speculate_unit(trie, x, p, alpha, ms, den_mode, 1)
+                want = brute.speculate_unit(coll, x, p, alpha, ms, D, den_mode, 1)
+                if want is None:
+                    assert got is None
+                    continue
+                assert list(got[0]) == want[0] and list(got[1]) == want[1]
+                assert [float(s).hex() for s in got[2]] == [float(s).hex() for s in want[2]]
+                # a chain: every node hangs off the previous one
+                assert list(got[1]) == list(range(-1, len(got[0]) - 1))
+                tree = oracle.speculate_unit(trie, x, p, alpha, ms, den_mode, 0)
+                differs += list(tree[1]) != list(got[1])
+        got = oracle.generate(tg, tr, x, P, alpha, ms, den_mode, 1)
+        want = brute.generate(docs, x, P, alpha, ms, D, den_mode, 1)
+        assert list(got["tokens"]) == want["tokens"] and got["match_len"] == want["match_len"]
+        assert got["source"] == want["source"]
+        assert float(got["tree_score"]).hex() == float(want["tree_score"]).hex()
+    assert differs > 0      # the tree variant does branch on these inputs
+
+
+def test_linear_variant_follows_the_most_frequent_child(tiny_workload):
+    """Closed form for the chain variant: at every step the next token is the most frequent
+    continuation of the path so far (ties to the lower token)."""
+    w = tiny_workload
+    docs = w.docs()
+    tg = oracle.Trie(w.D)
+    for d in docs:
+        tg.add_doc(d)
+    seen = 0
+    for r in range(w.batch):
+        x = w.contexts[r]
+        for p in (1, 2, 3, 5, 8):
+            got = oracle.speculate_unit(tg, x, p, 2.0, 0.1, 0, 1)
+            if got is None:
+                continue
+            path = [int(v) for v in x[-p:]]
+            c_root = tg.lookup(path)[0]
+            for j in range(len(got[0])):
+                ch = tg.children(path)
+                top = max(ch.values())
+                best_tok = min(t_ for t_, c_ in ch.items() if c_ == top)
+                assert int(got[0][j]) == best_tok
+                path.append(best_tok)
+                assert got[2][j] == pytest.approx(tg.lookup(path)[0] / c_root, rel=1e-14)
+                seen += 1
+    assert seen > 30
