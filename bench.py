@@ -141,6 +141,12 @@ def main():
 
     build_global()
     torch.cuda.synchronize()
+    # a plain device copy of known size (the corpus: 4 B read + 4 B written per token) so that
+    # rocprofv3 counter runs of this script can calibrate FETCH_SIZE / WRITE_SIZE
+    calib = torch.empty_like(d_corpus)
+    calib.copy_(d_corpus)
+    torch.cuda.synchronize()
+    del calib
     build_ms = []
     for _ in range(args.build_reps):
         e0, e1 = ev(), ev()
