@@ -352,6 +352,7 @@ constexpr int CHAIN_MAX_M = 8;  // widest node the unary-run shortcut looks at
 
 struct Stage {
     int32_t *pos, *cb, *tc;  // LDS: [64], [64], [TC_TOKENS]
+    int32_t *tmp;            // LDS: [128] scratch of the chain merge
     int lo, m, wlog;         // staged range [lo, lo + m) of the suffix list, window = 1 << wlog
 };
 
@@ -625,7 +626,127 @@ __device__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ 
     int32_t otok = 0, opar = 0;
     int nn = uni(n);
     const int KK = uni(K);
-    while (nn < KK && alive && nn - n0 < 64) {
+
+    // Whole-chain merge.  Merging a sequence X with a chain Y under "take the head with the
+    // lower (token, parent)": element x_t leaves after exactly r(t) elements of Y, where r(t)
+    // is the first j >= r(t-1) at which y_j does not beat x_t.  y_j beats x_t if its token is
+    // lower, or equal with the lower parent index; parents are the chain predecessors, so on
+    // equal tokens y_j wins iff y_(j-1) left before x_t's own predecessor x_t', i.e. iff
+    // j <= r(t') (for chain heads the given parent indices decide).  One ballot pair per x_t
+    // gives {j : y_j < x_t} and {j : y_j == x_t} as lane masks, r(t) follows with a few scalar
+    // bit operations, and the output positions are t + r(t) for X and j + #{t : r(t) <= j} for
+    // Y.  More chains are merged in one after the other (taking the best head among k chains
+    // equals merging them pairwise).  A chain that does not fit one 64-token window sends
+    // the whole thing to the step-by-step merge below.
+    bool merged = false;
+    {
+        const int room = KK - n0 < 64 ? KK - n0 : 64;
+        bool fits = true;
+#pragma unroll
+        for (int q = 0; q < TIE_MAX; q++)
+            if (q < j && D - cdep[q] > 63) fits = false;
+        if (fits && room > 0) {
+            int32_t st[TIE_MAX];
+            int alen[TIE_MAX];
+#pragma unroll
+            for (int q = 0; q < TIE_MAX; q++) {
+                // sequence of chain q: element 0 is the frontier entry, element k its k-th
+                // descendant (token at child index cdep + k - 1)
+                const int32_t up = __shfl_up(win[q], 1);
+                st[q] = lane == 0 ? ctok[q] : up;
+                const uint64_t bad = __ballot(lane >= 1 && (up < 0 || cdep[q] + lane - 1 >= D));
+                alen[q] = q < j ? (bad ? __ffsll((unsigned long long)bad) - 1 : 64) : 0;
+            }
+            // merged sequence so far: token, meta = chain << 8 | element index, index of the
+            // same chain's previous element in the sequence (-1: chain head), the chain's
+            // given parent index
+            int32_t zt = st[0], zm = lane, zprev = lane - 1, zinit = cpar[0];
+            int lz = alen[0] < room ? alen[0] : room;
+            int32_t *T = sg.tmp, *M = sg.tmp + 64;
+#pragma unroll
+            for (int q = 1; q < TIE_MAX; q++) {
+                if (q >= j) continue;
+                const int ly = alen[q] < room ? alen[q] : room;
+                const int32_t yt = st[q];
+                const int32_t yinit = cpar[q];
+                int r = 0;
+                int32_t myr = 0, before = 0;
+                for (int t = 0; t < lz; t++) {
+                    const int32_t xt = __builtin_amdgcn_readlane(zt, t);
+                    const int32_t tp = __builtin_amdgcn_readlane(zprev, t);
+                    uint64_t lt = __ballot(lane < ly && yt < xt);
+                    const uint64_t eq = __ballot(lane < ly && yt == xt);
+                    if (eq) {  // ties: y_j wins for j <= R
+                        int R;
+                        if (tp >= 0) R = __builtin_amdgcn_readlane(myr, tp);
+                        else R = yinit < __builtin_amdgcn_readlane(zinit, t) ? 0 : -1;
+                        const uint64_t le = R < 0 ? 0ull : (R >= 63 ? ~0ull : ((2ull << R) - 1ull));
+                        lt |= eq & le;
+                    }
+                    if (r < 64) {
+                        const uint64_t rest = ~(lt >> r);
+                        r = rest ? r + __ffsll((unsigned long long)rest) - 1 : 64;
+                    }
+                    if (lane == t) myr = r;
+                    before += lane >= r ? 1 : 0;
+                }
+                wsync();
+                if (lane < lz && lane + myr < 64) { T[lane + myr] = zt; M[lane + myr] = zm; }
+                if (lane < ly && lane + before < 64) {
+                    T[lane + before] = yt;
+                    M[lane + before] = (q << 8) | lane;
+                }
+                wsync();
+                lz = lz + ly < room ? lz + ly : room;
+                zt = T[lane];
+                zm = M[lane];
+                // predecessor links and given parents of the new sequence
+                zprev = -1;
+                zinit = 0;
+#pragma unroll
+                for (int c = 0; c < TIE_MAX; c++) {
+                    if (c > q) continue;
+                    const bool mine = lane < lz && (zm >> 8) == c;
+                    const uint64_t mc = __ballot(mine);
+                    if (mine) {
+                        const uint64_t prev = mc & lanemask_lt();
+                        zprev = prev ? 63 - __clzll((unsigned long long)prev) : -1;
+                        zinit = cpar[c];
+                    }
+                }
+            }
+            {
+                const bool live = lane < lz;
+                const int myc = zm >> 8, myi = zm & 255;
+                int32_t par = 0;
+                alive = 0;
+#pragma unroll
+                for (int q = 0; q < TIE_MAX; q++) {
+                    if (q >= j) continue;
+                    const uint64_t mq = __ballot(live && myc == q);
+                    if (live && myc == q) {
+                        const uint64_t prev = mq & lanemask_lt();
+                        par = myi == 0 ? cpar[q] : n0 + 63 - __clzll((unsigned long long)prev);
+                    }
+                    const int used = __popcll(mq);
+                    if (used < alen[q]) {  // the chain goes on: its next element is the new head
+                        alive |= 1u << q;
+                        ctok[q] = __builtin_amdgcn_readlane(st[q], used);
+                        if (used > 0) cpar[q] = n0 + 63 - __clzll((unsigned long long)mq);
+                        cdep[q] += used;
+                    }
+                }
+                if (live) {
+                    t_tok[n0 + lane] = zt; t_par[n0 + lane] = par; t_score[n0 + lane] = s;
+                    SD_CNT(8);
+                }
+                for (int i = 0; i < lz; i++) total += s;
+                nn = n0 + lz;
+                merged = true;
+            }
+        }
+    }
+    while (!merged && nn < KK && alive && nn - n0 < 64) {
         // keep the merge state in scalar registers: every compare and select below is then a
         // scalar instruction instead of a vector one under an execution mask
         alive = (unsigned)uni((int32_t)alive);
@@ -671,7 +792,7 @@ __device__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ 
         nn++;
     }
     n = nn;
-    if (lane < n - n0) {
+    if (!merged && lane < n - n0) {
         t_tok[n0 + lane] = otok; t_par[n0 + lane] = opar; t_score[n0 + lane] = s;
     }
     // surviving heads go back into the frontier
@@ -835,7 +956,7 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
     f.par = f.tok + cap; f.lo = f.par + cap; f.hi = f.lo + cap; f.dep = f.hi + cap;
     int32_t *t_tok = f.dep + cap, *t_par = t_tok + cap;
     Stage sg;
-    sg.pos = t_par + cap; sg.cb = sg.pos + 64; sg.tc = sg.cb + 64;
+    sg.pos = t_par + cap; sg.cb = sg.pos + 64; sg.tc = sg.cb + 64; sg.tmp = sg.tc + TC_TOKENS;
     sg.lo = 0; sg.m = 0; sg.wlog = 0;
 
     // units with long patterns grow the largest trees: they are dispatched first
@@ -1107,7 +1228,7 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     p.unit_ticks = c->s_unit_ticks;
     const bool stats = c->prof_mode == 2;
     const size_t lds = (size_t)c->max_nodes * (2 * sizeof(double) + 7 * sizeof(int32_t)) +
-                       (64 + 64 + TC_TOKENS) * sizeof(int32_t);
+                       (64 + 64 + TC_TOKENS + 128) * sizeof(int32_t);
     const dim3 g_units((unsigned)(batch * c->cfg.P)), g_req((unsigned)batch);
     // Two concurrent legs: the caller's stream expands the global-index units while the
     // context's second stream scans the request contexts and expands the per-request units.
