@@ -346,7 +346,10 @@ __device__ void frontier_put(Frontier &f, int hole, bool cand, double sc, int32_
 // Sibling branches of the speculation tree are disjoint suffix ranges and a suffix is only
 // ever asked for deeper tokens, so each slot's window moves forward only.  With W tokens per
 // slot one coalesced fill serves W levels of the tree: expansion then runs out of LDS.
-constexpr int TC_TOKENS = 512;
+#ifndef SD_TC_TOKENS
+#define SD_TC_TOKENS 512
+#endif
+constexpr int TC_TOKENS = SD_TC_TOKENS;
 constexpr int CB_NONE = -(1 << 30);
 constexpr int CHAIN_MAX_M = 8;  // widest node the unary-run shortcut looks at
 
@@ -940,17 +943,28 @@ __device__ void select_request(const SpecParams &p, const sd_trees &out, int b, 
 }
 
 // One wavefront per unit (request b, pattern length pl) of one index (src 0 global, 1 request).
+// A workgroup carries EXPAND_WAVES independent units; its waves share nothing and never meet
+// at a barrier.  One unit per workgroup measured fastest on MI355X (a larger workgroup keeps
+// its LDS and wave slots until its slowest unit is done): 81 us per decode step against 86
+// and 90 us with two and four units per workgroup.
+#ifndef SD_EXPAND_WAVES
+#define SD_EXPAND_WAVES 1
+#endif
+constexpr int EXPAND_WAVES = SD_EXPAND_WAVES;
+
 template <bool STATS>
-__global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *__restrict__ slot_ids,
-                                                  int src) {
+__global__ __launch_bounds__(64 * EXPAND_WAVES, 8) void k_expand(
+    SpecParams p, const int32_t *__restrict__ slot_ids, int src, int nreq, int lds_per_wave) {
     extern __shared__ double smem[];
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int unit = blockIdx.x * EXPAND_WAVES + wave;
+    if (unit >= nreq * p.P) return;
     unsigned nb = 0;
     const uint64_t tick0 = STATS ? wall_clock64() : 0;
     const int cap = p.max_nodes;
     // LDS carve-up: frontier (score, tok, par, lo, hi, dep), tree (score, tok, par), staging
     Frontier f;
-    f.score = smem;
+    f.score = smem + (size_t)wave * (lds_per_wave / 8);
     double *t_score = f.score + cap;
     f.tok = (int32_t *)(t_score + cap);
     f.par = f.tok + cap; f.lo = f.par + cap; f.hi = f.lo + cap; f.dep = f.hi + cap;
@@ -960,8 +974,11 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
     sg.lo = 0; sg.m = 0; sg.wlog = 0;
 
     // units with long patterns grow the largest trees: they are dispatched first
-    const int nreq = gridDim.x / p.P;
-    const int b = blockIdx.x % nreq, pl = p.P - blockIdx.x / nreq;
+#ifdef SD_NO_LPT
+    const int b = unit / p.P, pl = unit % p.P + 1;
+#else
+    const int b = unit % nreq, pl = p.P - unit / nreq;
+#endif
     const int64_t uidx = (int64_t)b * (2 * p.P) + src * p.P + (pl - 1);
     const int32_t slot = uni(slot_ids[b]);
     const bool slot_ok = slot >= 0 && slot < p.max_slots;
@@ -1014,7 +1031,7 @@ __global__ __launch_bounds__(64, 8) void k_expand(SpecParams p, const int32_t *_
                 stage_set_width(sg, m > 0 ? m : 1);
             }
             __threadfence_block();
-            __syncthreads();
+            wsync();
             lo = 0;
             hi = m > 1 ? m : 0;  // == w when the list was gathered
             sa = usa;
@@ -1227,9 +1244,13 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     p.algo_bytes = c->d_algo_bytes;
     p.unit_ticks = c->s_unit_ticks;
     const bool stats = c->prof_mode == 2;
-    const size_t lds = (size_t)c->max_nodes * (2 * sizeof(double) + 7 * sizeof(int32_t)) +
-                       (64 + 64 + TC_TOKENS + 128) * sizeof(int32_t);
-    const dim3 g_units((unsigned)(batch * c->cfg.P)), g_req((unsigned)batch);
+    size_t lds_wave = (size_t)c->max_nodes * (2 * sizeof(double) + 7 * sizeof(int32_t)) +
+                      (64 + 64 + TC_TOKENS + 128) * sizeof(int32_t);
+    lds_wave = (lds_wave + 7) / 8 * 8;
+    const size_t lds = lds_wave * EXPAND_WAVES;
+    const int n_units = batch * c->cfg.P;
+    const dim3 g_units((unsigned)((n_units + EXPAND_WAVES - 1) / EXPAND_WAVES)), g_req((unsigned)batch);
+    const dim3 b_units(64 * EXPAND_WAVES);
     // Two concurrent legs: the caller's stream expands the global-index units while the
     // context's second stream scans the request contexts and expands the per-request units.
     // They join before the selection kernel.
@@ -1243,14 +1264,14 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     }
     {
         sd_span sp(c, SD_K_EXPAND_REQ, c->aux_stream);
-        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, dim3(64), lds, c->aux_stream, p, d_slot_ids, 1);
-        else hipLaunchKernelGGL(k_expand<false>, g_units, dim3(64), lds, c->aux_stream, p, d_slot_ids, 1);
+        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, b_units, lds, c->aux_stream, p, d_slot_ids, 1, batch, (int)lds_wave);
+        else hipLaunchKernelGGL(k_expand<false>, g_units, b_units, lds, c->aux_stream, p, d_slot_ids, 1, batch, (int)lds_wave);
     }
     if (hipEventRecord(c->ev_join, c->aux_stream) != hipSuccess) return SD_ERR_HIP;
     {
         sd_span sp(c, SD_K_EXPAND, st);
-        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, dim3(64), lds, st, p, d_slot_ids, 0);
-        else hipLaunchKernelGGL(k_expand<false>, g_units, dim3(64), lds, st, p, d_slot_ids, 0);
+        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, b_units, lds, st, p, d_slot_ids, 0, batch, (int)lds_wave);
+        else hipLaunchKernelGGL(k_expand<false>, g_units, b_units, lds, st, p, d_slot_ids, 0, batch, (int)lds_wave);
     }
     if (hipStreamWaitEvent(st, c->ev_join, 0) != hipSuccess) return SD_ERR_HIP;
     {
