@@ -673,8 +673,11 @@ __device__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ 
                 const int32_t yt = st[q];
                 const int32_t yinit = cpar[q];
                 int r = 0;
-                int32_t myr = 0, before = 0;
-                for (int t = 0; t < lz; t++) {
+                // x_t lands at t + r(t) and r never decreases: once that reaches `room` neither
+                // x_t nor anything after it is kept, and every y_j still unplaced lands at
+                // j + t >= room as well.  Lanes the loop never reached keep myr = 64 (dropped).
+                int32_t myr = 64, before = 0;
+                for (int t = 0; t < lz && t + r < room; t++) {
                     const int32_t xt = __builtin_amdgcn_readlane(zt, t);
                     const int32_t tp = __builtin_amdgcn_readlane(zprev, t);
                     uint64_t lt = __ballot(lane < ly && yt < xt);
@@ -951,9 +954,15 @@ __device__ void select_request(const SpecParams &p, const sd_trees &out, int b, 
 #define SD_EXPAND_WAVES 1
 #endif
 constexpr int EXPAND_WAVES = SD_EXPAND_WAVES;
+// Five waves per SIMD leave 96 registers per lane: the kernel then keeps its whole state in
+// registers.  At eight waves (64 registers) it spilled 27 vector registers to scratch memory
+// and ran 10% slower, although more units were resident at once.
+#ifndef SD_EXPAND_OCC
+#define SD_EXPAND_OCC 5
+#endif
 
 template <bool STATS>
-__global__ __launch_bounds__(64 * EXPAND_WAVES, 8) void k_expand(
+__global__ __launch_bounds__(64 * EXPAND_WAVES, SD_EXPAND_OCC) void k_expand(
     SpecParams p, const int32_t *__restrict__ slot_ids, int src, int nreq, int lds_per_wave) {
     extern __shared__ double smem[];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
