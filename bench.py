@@ -141,12 +141,27 @@ def main():
 
     build_global()
     torch.cuda.synchronize()
-    # a plain device copy of known size (the corpus: 4 B read + 4 B written per token) so that
-    # rocprofv3 counter runs of this script can calibrate FETCH_SIZE / WRITE_SIZE
+    # The hand-written streaming copy of known size (the corpus: 4 B read + 4 B written per
+    # token) lets rocprofv3 counter runs of this script calibrate FETCH_SIZE / WRITE_SIZE; the
+    # same kernel over 2 x 512 MiB gives the achievable HBM rate of this run.
     calib = torch.empty_like(d_corpus)
-    calib.copy_(d_corpus)
+    if n_tokens % 4 == 0:
+        verifier.stream_copy(d_corpus, calib)
     torch.cuda.synchronize()
     del calib
+    big_a = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+    big_b = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+    big_a.zero_()
+    copy_ms = []
+    for _ in range(6):
+        e0, e1 = ev(), ev()
+        e0.record()
+        verifier.stream_copy(big_a, big_b)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_ms.append(e0.elapsed_time(e1))
+    achievable_gbs = 2.0 * big_a.numel() / (min(copy_ms[1:]) * 1e-3) / 1e9
+    del big_a, big_b
     build_ms = []
     for _ in range(args.build_reps):
         e0, e1 = ev(), ev()
@@ -225,6 +240,44 @@ def main():
     step_latency = {"median": lat[len(lat) // 2], "p99": lat[min(len(lat) - 1, int(0.99 * len(lat)))],
                     "max": lat[-1]}
 
+    # ---- sd_speculate alone: median over 50 calls from one fixed state, and against batch ---
+    reset()
+    for _ in range(W):
+        step()
+    torch.cuda.synchronize()
+
+    def time_speculate(slots_t, reps):
+        for _ in range(5):
+            sd.sd_speculate(ctx, slots_t, trees)
+        torch.cuda.synchronize()
+        run = None
+        if not args.no_graph:
+            g2 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g2):
+                sd.sd_speculate(ctx, slots_t, trees)
+            torch.cuda.synchronize()
+            run = g2.replay
+        else:
+            run = lambda: sd.sd_speculate(ctx, slots_t, trees)
+        ts = []
+        for _ in range(reps):
+            e0, e1 = ev(), ev()
+            e0.record()
+            run()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        ts.sort()
+        return ts[len(ts) // 2]
+
+    spec_ms = time_speculate(d_slots, 50)
+    latency_by_batch = {}
+    nb = 1
+    while nb < B:
+        latency_by_batch[str(nb)] = time_speculate(d_slots[:nb].contiguous(), 20) * 1e3
+        nb *= 4
+    latency_by_batch[str(B)] = spec_ms * 1e3
+
     # ---- per-kernel durations (HIP events on the launch stream) over the same K steps -----
     reset()
     for _ in range(W):
@@ -253,7 +306,8 @@ def main():
     roofline = {"bound": "hbm", "kernel": "k_expand", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": _traffic_from_profiles("k_expand", w.name),
-                "algo_bytes_per_launch": exp_bytes, "avg_launch_ms": exp_ms}
+                "algo_bytes_per_launch": exp_bytes, "avg_launch_ms": exp_ms,
+                "achievable": achievable_gbs, "frac_of_achievable": achieved / achievable_gbs}
     N = n_tokens + n_docs
     sc = prof_build["sort_scatter"]
     sc_ms = sc["ms"] / max(sc["launches"], 1)
@@ -262,7 +316,8 @@ def main():
                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sc_ach / HBM_PEAK_GBS,
                       "traffic": _traffic_from_profiles("k_radix_scatter", w.name),
                       "algo_bytes_per_launch": 24.0 * N, "avg_launch_ms": sc_ms,
-                      "launches_per_build": sc["launches"]}
+                      "launches_per_build": sc["launches"], "achievable": achievable_gbs,
+                      "frac_of_achievable": sc_ach / achievable_gbs}
     kernels_ms = {k: v["ms"] / max(v["launches"], 1) for k, v in prof.items() if v["launches"]}
     build_kernels_ms = {k: v["ms"] for k, v in prof_build.items() if v["launches"]}
 
@@ -283,6 +338,9 @@ def main():
         "index_build_ms": g_build_ms, "request_build_ms": r_build_ms,
         "request_build_tokens_per_s": B * ctx_len / (r_build_ms * 1e-3),
         "step_latency_ms": step_latency,
+        "speculate_only_ms_median": spec_ms, "speculate_only_trees_per_s": B / (spec_ms * 1e-3),
+        "speculate_latency_us_by_batch": latency_by_batch,
+        "stream_copy_gbs": achievable_gbs,
         "mean_tree_nodes": mean_nodes, "mean_accept_len": mean_accept,
         "kernel_ms_per_launch": kernels_ms, "build_kernel_ms_total": build_kernels_ms,
         "roofline": roofline, "roofline_build": roofline_build,

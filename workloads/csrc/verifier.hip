@@ -59,9 +59,31 @@ __global__ __launch_bounds__(64) void k_collect(const int32_t *__restrict__ toke
     }
 }
 
+// Plain streaming copy, 16 bytes per lane per trip, grid-stride: the reference rate that
+// bandwidth figures of the other kernels are set against (and the known-size kernel that
+// hardware byte counters are calibrated on).
+__global__ __launch_bounds__(256) void k_stream_copy(const int4 *__restrict__ src,
+                                                     int4 *__restrict__ dst, int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        dst[i] = src[i];
+}
+
 }  // namespace
 
 extern "C" {
+
+// copies n_bytes (a multiple of 16, both pointers 16-byte aligned) from d_src to d_dst
+int wl_stream_copy(const void *d_src, void *d_dst, int64_t n_bytes, void *stream) {
+    if (n_bytes <= 0) return 0;
+    if (n_bytes % 16 || ((uintptr_t)d_src & 15) || ((uintptr_t)d_dst & 15)) return 2;
+    const int64_t n16 = n_bytes / 16;
+    int64_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;  // 32 workgroups per compute unit, grid-stride
+    hipLaunchKernelGGL(k_stream_copy, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       (const int4 *)d_src, (int4 *)d_dst, n16);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
 
 // all pointers are device pointers
 int wl_targets(const int32_t *d_n_nodes, const int32_t *d_parents, int max_nodes,

@@ -38,6 +38,8 @@ def _load():
         L.wl_targets.argtypes = [vp, vp, C.c_int, vp, C.c_int64, vp, C.c_int, vp, vp]
         L.wl_collect.restype = C.c_int
         L.wl_collect.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp]
+        L.wl_stream_copy.restype = C.c_int
+        L.wl_stream_copy.argtypes = [vp, vp, C.c_int64, vp]
         _lib = L
     return _lib
 
@@ -65,3 +67,14 @@ def collect(tokens, accept_len, accept_path, bonus, new_tokens, new_offsets, pos
     rc = _load().wl_collect(_p(tokens), mn, _p(accept_len), _p(accept_path), _p(bonus), B,
                             _p(new_tokens), _p(new_offsets), _p(pos), C.c_void_p(st))
     assert rc == 0
+
+
+def stream_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """dst[:] = src[:] with the hand-written streaming copy kernel (sizes a multiple of 16 B)."""
+    assert src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()
+    nbytes = src.numel() * src.element_size()
+    assert nbytes == dst.numel() * dst.element_size()
+    st = torch.cuda.current_stream(src.device).cuda_stream
+    rc = _load().wl_stream_copy(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), nbytes,
+                                C.c_void_p(st))
+    assert rc == 0, rc
