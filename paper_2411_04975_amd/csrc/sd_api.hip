@@ -32,15 +32,10 @@ bool dev_alloc(T **p, int64_t count, int64_t *acc) {
 void free_all(sd_ctx *c) {
     void *ptrs[] = {c->g_text, c->g_sa, c->g_bucket, c->g_tok1, c->b_keys[0], c->b_keys[1], c->b_vals[0],
                     c->b_vals[1], c->b_rank, c->b_flags, c->b_hist, c->b_partials, c->r_text,
-                    c->r_len, c->s_occ, c->s_occ_n, c->s_cntL, c->s_unit_sa, c->s_unit_n,
-                    c->s_unit_score, c->s_unit_tok, c->s_unit_par, c->s_unit_sc, c->d_err,
-                    c->s_unit_ticks};
+                    c->r_len, c->s_occ, c->s_unit_sa, c->d_err, c->s_unit_ticks};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (c->d_algo_bytes) (void)hipFree(c->d_algo_bytes);
-    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
-    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
-    if (c->aux_stream) (void)hipStreamDestroy(c->aux_stream);
     if (c->prof_ev) {
         for (int i = 0; i < 2 * SD_PROF_MAX_SPANS; i++)
             if (c->prof_ev[i]) (void)hipEventDestroy(c->prof_ev[i]);
@@ -100,13 +95,8 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     ok = ok && dev_alloc(&c->b_hist, c->b_hist_cap, sb);
     ok = ok && dev_alloc(&c->b_partials, c->b_partials_cap, sb);
     ok = ok && dev_alloc(&c->r_text, B * c->r_stride, sb) && dev_alloc(&c->r_len, B, sb);
-    ok = ok && dev_alloc(&c->s_occ, B * ctx, sb) && dev_alloc(&c->s_occ_n, B, sb);
-    ok = ok && dev_alloc(&c->s_cntL, B * (P + 1), sb);
+    ok = ok && dev_alloc(&c->s_occ, B * ctx, sb);
     ok = ok && dev_alloc(&c->s_unit_sa, B * P * ctx, sb);
-    ok = ok && dev_alloc(&c->s_unit_n, B * 2 * P, sb) && dev_alloc(&c->s_unit_score, B * 2 * P, sb);
-    ok = ok && dev_alloc(&c->s_unit_tok, B * 2 * P * c->max_nodes, sb);
-    ok = ok && dev_alloc(&c->s_unit_par, B * 2 * P * c->max_nodes, sb);
-    ok = ok && dev_alloc(&c->s_unit_sc, B * 2 * P * c->max_nodes, sb);
     ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb);
     ok = ok && dev_alloc(&c->s_unit_ticks, B * 2 * P * 4, sb);
     ok = ok && dev_alloc(&c->d_algo_bytes, SD_K_COUNT, sb);
@@ -115,9 +105,7 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
         delete c;
         return SD_ERR_OOM;
     }
-    if (hipStreamCreateWithFlags(&c->aux_stream, hipStreamNonBlocking) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
-        hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess) {
+    if (sd_speculate_setup(c) != SD_OK) {
         free_all(c);
         delete c;
         return SD_ERR_HIP;

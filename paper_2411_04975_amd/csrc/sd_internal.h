@@ -48,22 +48,14 @@ struct sd_ctx {
 
     // ---- speculate scratch (sized for max_batch_slots requests) -------
     int2 *s_occ = nullptr;           // [B][max_ctx]: (end position e, common-suffix length L)
-    int32_t *s_occ_n = nullptr;      // [B]
-    int32_t *s_cntL = nullptr;       // [B][P+1]: occurrences with L >= p
-    int32_t *s_unit_sa = nullptr;    // [B][P][max_ctx]: per-(request,p) suffix lists
-    int32_t *s_unit_n = nullptr;     // [B][2P] nodes of each unit tree
-    double *s_unit_score = nullptr;  // [B][2P]
-    int32_t *s_unit_tok = nullptr;   // [B][2P][max_nodes]
-    int32_t *s_unit_par = nullptr;
-    double *s_unit_sc = nullptr;
+    int32_t *s_unit_sa = nullptr;    // [B][P][max_ctx]: per-(request,p) suffix lists (wide matches)
     uint32_t *s_unit_ticks = nullptr;  // [B][2P][4], written by the counting kernel variants
 
     int32_t *d_err = nullptr;        // [SD_DEVERR_N]
 
-    // second stream + events: lets the request-context scan of sd_speculate overlap with the
-    // global-index units (default priority; joined back before the call's last kernels)
-    hipStream_t aux_stream = nullptr;
-    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    int n_cu = 0;                    // compute units of the device
+    size_t lds_optin = 0;            // largest dynamic LDS size a workgroup may ask for
+    size_t lds_cu = 0;               // LDS of one compute unit
 
     // ---- measurement hooks ---------------------------------------------
     int prof_mode = 0;
@@ -86,6 +78,7 @@ sd_status sd_build_requests_impl(sd_ctx *c, const int32_t *d_slot_ids, const int
                                  const int64_t *d_offsets, int32_t n_seq, hipStream_t st);
 sd_status sd_append_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_new_tokens,
                          const int32_t *d_new_offsets, int32_t n_slots, hipStream_t st);
+sd_status sd_speculate_setup(sd_ctx *c);  // device limits and kernel attributes, once per context
 sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
                             hipStream_t st);
 sd_status sd_accept_impl(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t *d_target,

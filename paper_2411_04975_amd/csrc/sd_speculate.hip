@@ -33,10 +33,7 @@ struct SpecParams {
     int32_t den_mode, linear;
     double alpha, min_score, tau;
     int2 *occ;
-    int32_t *occ_n, *cntL, *unit_sa, *unit_n;
-    double *unit_score;
-    int32_t *unit_tok, *unit_par;
-    double *unit_sc;
+    int32_t *unit_sa;
     int32_t *err;
     unsigned long long *algo_bytes;
     uint32_t *unit_ticks;  // counting variants only: wall-clock ticks each unit took
@@ -73,7 +70,6 @@ __device__ __forceinline__ double uni(double v) {
 // ------------------------------------------------------------------------------------------
 // per-request occurrence lists
 // ------------------------------------------------------------------------------------------
-constexpr int OCC_THREADS = 256;
 constexpr int OCC_LDS_SORT = 2048;
 
 // order of two occurrences by the tokens that follow them (end marker lowest), then by position
@@ -91,14 +87,15 @@ __device__ __forceinline__ bool occ_less(const int32_t *__restrict__ x, int2 a, 
 }
 
 // bitonic network in its all-ascending form (mirror step, then half-cleaners); positions at or
-// beyond m act as +infinity and are never touched, so m need not be a power of two
+// beyond m act as +infinity and are never touched, so m need not be a power of two.  Run by
+// the whole workgroup.
 template <bool STATS>
-__device__ void occ_sort(int2 *arr, int m, const int32_t *__restrict__ x, int depth, unsigned &nb) {
+__device__ __forceinline__ void occ_sort(int2 *arr, int m, const int32_t *__restrict__ x, int depth, unsigned &nb) {
     int n2 = 1;
     while (n2 < m) n2 <<= 1;
     for (int k = 2; k <= n2; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = threadIdx.x; i < m; i += OCC_THREADS) {
+            for (int i = threadIdx.x; i < m; i += blockDim.x) {
                 int l = (j == (k >> 1)) ? (i ^ (k - 1)) : (i ^ j);
                 if (l > i && l < m) {
                     int2 a = arr[i], b = arr[l];
@@ -113,41 +110,46 @@ __device__ void occ_sort(int2 *arr, int m, const int32_t *__restrict__ x, int de
     }
 }
 
+// Workgroup-shared state of one request.
+struct WgShared {
+    int m;           // occurrences of the context's last token
+    int next;        // head of the unit queue
+    int cnt[72];     // [l]: occurrences whose left-extension is l; afterwards: is at least l
+    double best_s[16];
+    int best_o[16];
+};
+
+// MatchPattern on the per-request structure, for all pattern lengths at once, by the whole
+// workgroup: the occurrences of the last token, each with its left-extension L(e) (how many
+// tokens before it agree with the context's tail, capped at P), sorted by what follows them.
+// The occurrences with L >= p, in that order, are the sorted suffix list below the pattern of
+// length p.  Ends with a workgroup barrier.
 template <bool STATS>
-__global__ __launch_bounds__(OCC_THREADS) void k_req_occurrences(SpecParams p,
-                                                                 const int32_t *__restrict__ slot_ids) {
-    __shared__ int s_m;
-    __shared__ int s_cnt[72];
-    __shared__ int2 s_sort[OCC_LDS_SORT];
-    const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
-    const int32_t slot = slot_ids[b];
-    const bool slot_ok = slot >= 0 && slot < p.max_slots;
-    if (!slot_ok && tid == 0) atomicOr(&p.err[SD_DEVERR_SLOT], 1);
-    const int t = slot_ok ? p.r_len[slot] : 0;
-    const int32_t *x = p.r_text + (int64_t)(slot_ok ? slot : 0) * p.r_stride;
+__device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, int t, const int32_t *__restrict__ x,
+                                    int2 *s_sort, WgShared &sh, unsigned &nb) {
+    const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
     int2 *occ = p.occ + (int64_t)b * p.max_ctx;
-    unsigned nb = 0;
-    if (tid == 0) s_m = 0;
-    if (tid < 72) s_cnt[tid] = 0;
+    if (tid == 0) { sh.m = 0; sh.next = 0; }
+    if (tid < 72) sh.cnt[tid] = 0;
     __syncthreads();
     if (t > 0) {
-        // Coalesced scan, 16 tokens per thread and round (four 16-byte loads in flight).  Tokens
-        // past the context end are end markers, which never equal the last token, so the tail
-        // needs no bounds test; rows start 256-byte aligned.
+        // Coalesced scan, 16 bytes per load, four loads in flight per thread.  Tokens past the
+        // context end are end markers, which never equal the last token, so the tail needs no
+        // bounds test; rows start 256-byte aligned.
         const int32_t last = x[t - 1];
         const int4 *x4 = reinterpret_cast<const int4 *>(x);
         const int nq = (t + 3) >> 2;
-        for (int q0 = 0; q0 < nq; q0 += 4 * OCC_THREADS) {
+        for (int q0 = 0; q0 < nq; q0 += 4 * nthr) {
             int4 v[4];
 #pragma unroll
             for (int k = 0; k < 4; k++) {
-                int q = q0 + k * OCC_THREADS + tid;
+                int q = q0 + k * nthr + tid;
                 v[k] = q < nq ? x4[q] : make_int4(-1, -1, -1, -1);
                 if (q < nq) SD_CNT(16);
             }
 #pragma unroll
             for (int k = 0; k < 4; k++) {
-                const int e0 = 4 * (q0 + k * OCC_THREADS + tid);
+                const int e0 = 4 * (q0 + k * nthr + tid);
                 const int h0 = v[k].x == last, h1 = v[k].y == last, h2 = v[k].z == last,
                           h3 = v[k].w == last;
                 const int nh = h0 + h1 + h2 + h3;
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(OCC_THREADS) void k_req_occurrences(SpecParams p,
                         if (lane >= o) inc += u;
                     }
                     int off = 0;
-                    if (lane == 63) off = atomicAdd(&s_m, inc);
+                    if (lane == 63) off = atomicAdd(&sh.m, inc);
                     off = __shfl(off, 63) + inc - nh;
                     if (h0) occ[off++].x = e0;
                     if (h1) occ[off++].x = e0 + 1;
@@ -170,40 +172,39 @@ __global__ __launch_bounds__(OCC_THREADS) void k_req_occurrences(SpecParams p,
         }
     }
     __syncthreads();
-    const int m = s_m;
+    const int m = sh.m;
     // how far each occurrence extends to the left together with the context's own tail
-    for (int i = tid; i < m; i += OCC_THREADS) {
+    for (int i = tid; i < m; i += nthr) {
         int e = occ[i].x;
         int lim = e + 1 < p.P ? e + 1 : p.P;
         int l = 1;
         while (l < lim && x[e - l] == x[t - 1 - l]) l++;
         SD_CNT(8 * l + 8);
         occ[i].y = l;
-        atomicAdd(&s_cnt[l], 1);
+        atomicAdd(&sh.cnt[l], 1);
     }
     __syncthreads();
-    if (tid == 0) {
+    if (tid == 0) {  // nothing below reads cnt before the closing barrier
         int acc = 0;
-        int32_t *cl = p.cntL + (int64_t)b * (p.P + 1);
         for (int l = p.P; l >= 1; l--) {
-            acc += s_cnt[l];
-            cl[l] = acc;
+            acc += sh.cnt[l];
+            sh.cnt[l] = acc;
         }
-        cl[0] = m;
-        p.occ_n[b] = m;
+        sh.cnt[0] = m;
     }
     if (m > 1) {
         const int depth = p.D - 1;
         if (m <= OCC_LDS_SORT) {
-            for (int i = tid; i < m; i += OCC_THREADS) s_sort[i] = occ[i];
+            for (int i = tid; i < m; i += nthr) s_sort[i] = occ[i];
             __syncthreads();
             occ_sort<STATS>(s_sort, m, x, depth, nb);
-            for (int i = tid; i < m; i += OCC_THREADS) occ[i] = s_sort[i];
+            for (int i = tid; i < m; i += nthr) occ[i] = s_sort[i];
         } else {
             occ_sort<STATS>(occ, m, x, depth, nb);
         }
     }
-    flush_count<STATS>(nb, p.algo_bytes + SD_K_OCCURRENCES);
+    __threadfence_block();
+    __syncthreads();
 }
 
 // ------------------------------------------------------------------------------------------
@@ -298,7 +299,7 @@ __device__ __forceinline__ void frontier_close(Frontier &f, int hole) {
 // just taken, which the first candidate reuses.  The frontier keeps at most `cap` entries: a
 // candidate that does not rank among the best `cap` can never be selected, because at most
 // `cap` more nodes are ever taken from it.
-__device__ void frontier_put(Frontier &f, int hole, bool cand, double sc, int32_t tok, int32_t par,
+__device__ __forceinline__ void frontier_put(Frontier &f, int hole, bool cand, double sc, int32_t tok, int32_t par,
                              int32_t lo, int32_t hi, int32_t dep) {
     const int lane = threadIdx.x & 63;
     uint64_t C = __ballot(cand);
@@ -405,7 +406,7 @@ __device__ __forceinline__ int stage_node(Stage &sg, const int32_t *__restrict__
 // Children of the node [lo, hi) at depth d (its path has d tokens), as frontier candidates with
 // score = ps * (COUNT(child) / COUNT(node)).  `hole` is the frontier slot the node came from.
 template <bool STATS>
-__device__ void push_children(Frontier &f, int hole, Stage &sg, const int32_t *__restrict__ sa,
+__device__ __forceinline__ void push_children(Frontier &f, int hole, Stage &sg, const int32_t *__restrict__ sa,
                               const int32_t *__restrict__ text, int32_t lo, int32_t hi, int32_t d,
                               int32_t parent, double ps, double min_score, int32_t D, int den_mode,
                               unsigned &nb) {
@@ -498,7 +499,7 @@ __device__ void push_children(Frontier &f, int hole, Stage &sg, const int32_t *_
 // searched together: each step loads both probe suffixes at once, and the two halves of the
 // wave compare one probe each against the pattern (lane k of a half holds pattern token k).
 template <bool STATS>
-__device__ void match_range(const int32_t *__restrict__ sa, const int32_t *__restrict__ text,
+__device__ __forceinline__ void match_range(const int32_t *__restrict__ sa, const int32_t *__restrict__ text,
                             int32_t &lo, int32_t &hi, int32_t wk, int pl, unsigned &nb) {
     const int lane = threadIdx.x & 63;
     int32_t la = lo, ha = hi, lu = lo, hu = hi;
@@ -571,7 +572,7 @@ __device__ void match_range(const int32_t *__restrict__ sa, const int32_t *__res
 constexpr int TIE_MAX = 4;
 
 template <bool STATS>
-__device__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ text, double s,
+__device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ text, double s,
                             int K, int D, int &n, double &total, int32_t *t_tok, int32_t *t_par,
                             double *t_score, unsigned &nb) {
     const int lane = threadIdx.x & 63;
@@ -825,7 +826,7 @@ constexpr int SCAN_MAX = 256;
 constexpr int DIRECT_MAX = 8;
 
 template <bool STATS>
-__device__ void match_global(const SpecParams &p, int32_t wk, int pl, int32_t &lo, int32_t &hi,
+__device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, int pl, int32_t &lo, int32_t &hi,
                              unsigned &nb) {
     const int lane = threadIdx.x & 63;
     const int32_t w0 = __builtin_amdgcn_readlane(wk, 0);
@@ -904,97 +905,20 @@ __device__ void match_global(const SpecParams &p, int32_t wk, int pl, int32_t &l
     match_range<STATS>(p.g_sa, p.g_text, lo, hi, wk, pl, nb);
 }
 
-// Best tree of request b over its 2P units (GenerateCandidateTree's strictly-greater scan) and
-// coalesced copy of the winner into the caller's buffers.
+// One unit (request b, index src: 0 global / 1 request, pattern length pl) on one wavefront:
+// MatchPattern, then ExpandSpeculationTree into the LDS tree (t_tok, t_par, t_score).  Returns
+// the number of draft nodes and leaves their SCORE in `total`.
 template <bool STATS>
-__device__ void select_request(const SpecParams &p, const sd_trees &out, int b, unsigned &nb) {
+__device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh, int b, int t,
+                        const int32_t *__restrict__ x, int src, int pl, Frontier &f, Stage &sg,
+                        int32_t *t_tok, int32_t *t_par, double *t_score, double &total,
+                        unsigned &nb) {
     const int lane = threadIdx.x & 63;
-    const int units = 2 * p.P, cap = p.max_nodes;
-    // strictly-greater scan in unit order = the earliest unit among those with the top score
-    double bs = 0.0;
-    int bu = -1;
-    for (int u = lane; u < units; u += 64) {
-        double s = p.unit_score[(int64_t)b * units + u];
-        SD_CNT(8);
-        if (s > bs) { bs = s; bu = u; }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        double os = __shfl_xor(bs, o);
-        int ou = __shfl_xor(bu, o);
-        if (ou >= 0 && (bu < 0 || os > bs || (os == bs && ou < bu))) { bs = os; bu = ou; }
-    }
-    int n = 0;
-    if (bu >= 0) n = p.unit_n[(int64_t)b * units + bu];
-    const int64_t ub = ((int64_t)b * units + (bu >= 0 ? bu : 0)) * cap;
-    const int64_t ob = (int64_t)b * out.max_nodes;
-    for (int i = lane; i < out.max_nodes; i += 64) {
-        bool live = i < n;
-        out.d_tokens[ob + i] = live ? p.unit_tok[ub + i] : -1;
-        out.d_parents[ob + i] = live ? p.unit_par[ub + i] : -1;
-        out.d_scores[ob + i] = live ? p.unit_sc[ub + i] : 0.0;
-        SD_CNT(live ? 32 : 16);
-    }
-    if (lane == 0) {
-        out.d_n_nodes[b] = n;
-        out.d_tree_score[b] = bu >= 0 ? bs : 0.0;
-        out.d_match_len[b] = bu >= 0 ? bu % p.P + 1 : 0;
-        out.d_source[b] = bu >= 0 ? bu / p.P : -1;
-        if (out.d_use_draft) out.d_use_draft[b] = (bu >= 0 && bs > p.tau) ? 1 : 0;
-        SD_CNT(24);
-    }
-}
-
-// One wavefront per unit (request b, pattern length pl) of one index (src 0 global, 1 request).
-// A workgroup carries EXPAND_WAVES independent units; its waves share nothing and never meet
-// at a barrier.  One unit per workgroup measured fastest on MI355X (a larger workgroup keeps
-// its LDS and wave slots until its slowest unit is done): 81 us per decode step against 86
-// and 90 us with two and four units per workgroup.
-#ifndef SD_EXPAND_WAVES
-#define SD_EXPAND_WAVES 1
-#endif
-constexpr int EXPAND_WAVES = SD_EXPAND_WAVES;
-// Five waves per SIMD leave 96 registers per lane: the kernel then keeps its whole state in
-// registers.  At eight waves (64 registers) it spilled 27 vector registers to scratch memory
-// and ran 10% slower, although more units were resident at once.
-#ifndef SD_EXPAND_OCC
-#define SD_EXPAND_OCC 5
-#endif
-
-template <bool STATS>
-__global__ __launch_bounds__(64 * EXPAND_WAVES, SD_EXPAND_OCC) void k_expand(
-    SpecParams p, const int32_t *__restrict__ slot_ids, int src, int nreq, int lds_per_wave) {
-    extern __shared__ double smem[];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int unit = blockIdx.x * EXPAND_WAVES + wave;
-    if (unit >= nreq * p.P) return;
-    unsigned nb = 0;
     const uint64_t tick0 = STATS ? wall_clock64() : 0;
-    const int cap = p.max_nodes;
-    // LDS carve-up: frontier (score, tok, par, lo, hi, dep), tree (score, tok, par), staging
-    Frontier f;
-    f.score = smem + (size_t)wave * (lds_per_wave / 8);
-    double *t_score = f.score + cap;
-    f.tok = (int32_t *)(t_score + cap);
-    f.par = f.tok + cap; f.lo = f.par + cap; f.hi = f.lo + cap; f.dep = f.hi + cap;
-    int32_t *t_tok = f.dep + cap, *t_par = t_tok + cap;
-    Stage sg;
-    sg.pos = t_par + cap; sg.cb = sg.pos + 64; sg.tc = sg.cb + 64; sg.tmp = sg.tc + TC_TOKENS;
-    sg.lo = 0; sg.m = 0; sg.wlog = 0;
-
-    // units with long patterns grow the largest trees: they are dispatched first
-#ifdef SD_NO_LPT
-    const int b = unit / p.P, pl = unit % p.P + 1;
-#else
-    const int b = unit % nreq, pl = p.P - unit / nreq;
-#endif
     const int64_t uidx = (int64_t)b * (2 * p.P) + src * p.P + (pl - 1);
-    const int32_t slot = uni(slot_ids[b]);
-    const bool slot_ok = slot >= 0 && slot < p.max_slots;
-    const int t = slot_ok ? uni(p.r_len[slot]) : 0;
-    const int32_t *x = p.r_text + (int64_t)(slot_ok ? slot : 0) * p.r_stride;
     const int K = (int)floor(p.alpha * (double)pl);
     uint32_t tick_setup = 0, tick_match = 0, tick_root = 0;
+    sg.lo = 0; sg.m = 0; sg.wlog = 0;
     if (STATS) tick_setup = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(t & 0);
 
     const int32_t *sa = nullptr, *text = nullptr;
@@ -1010,11 +934,11 @@ __global__ __launch_bounds__(64 * EXPAND_WAVES, SD_EXPAND_OCC) void k_expand(
             }
         } else {
             // per-request structure: occurrences whose left-extension reaches pl, in the
-            // order k_req_occurrences left them (sorted by what follows)
-            const int m = uni(p.cntL[(int64_t)b * (p.P + 1) + pl]);
+            // order request_occurrences left them (sorted by what follows)
+            const int m = uni(sh.cnt[pl]);
             // m == 1 is the context's own tail alone: it stops at the end marker, so the
             // unit has no candidate at all and nothing else needs to be read
-            const int m1 = m > 1 ? uni(p.occ_n[b]) : 0;
+            const int m1 = m > 1 ? uni(sh.m) : 0;
             const int2 *occ = p.occ + (int64_t)b * p.max_ctx;
             int32_t *usa = p.unit_sa + ((int64_t)b * p.P + (pl - 1)) * p.max_ctx;
             const bool narrow = m <= 64;
@@ -1049,7 +973,7 @@ __global__ __launch_bounds__(64 * EXPAND_WAVES, SD_EXPAND_OCC) void k_expand(
     }
 
     int n = 0;
-    double total = 0.0;
+    total = 0.0;
     if (STATS) tick_match = (uint32_t)(wall_clock64() - tick0) + (uint32_t)((hi - lo) & 0);
     if (hi > lo) {
         f.n = 0;
@@ -1120,33 +1044,110 @@ __global__ __launch_bounds__(64 * EXPAND_WAVES, SD_EXPAND_OCC) void k_expand(
         }
     }
     wsync();
-    for (int i = lane; i < n; i += 64) {
-        p.unit_tok[uidx * cap + i] = t_tok[i];
-        p.unit_par[uidx * cap + i] = t_par[i];
-        p.unit_sc[uidx * cap + i] = t_score[i];
-        SD_CNT(16);
+    if (STATS && lane == 0) {  // phase marks: set-up, match, root children, whole unit
+        p.unit_ticks[uidx * 4 + 0] = tick_setup;
+        p.unit_ticks[uidx * 4 + 1] = tick_match;
+        p.unit_ticks[uidx * 4 + 2] = tick_root;
+        p.unit_ticks[uidx * 4 + 3] = (uint32_t)(wall_clock64() - tick0);
     }
-    if (lane == 0) {
-        p.unit_n[uidx] = n;
-        p.unit_score[uidx] = total;
-        SD_CNT(12);
-        if (STATS) {  // phase marks: setup, match, root children, whole unit
-            p.unit_ticks[uidx * 4 + 0] = tick_setup;
-            p.unit_ticks[uidx * 4 + 1] = tick_match;
-            p.unit_ticks[uidx * 4 + 2] = tick_root;
-            p.unit_ticks[uidx * 4 + 3] = (uint32_t)(wall_clock64() - tick0);
+    return n;
+}
+
+// GenerateCandidateTree for one request per workgroup.  All waves first build the request's
+// occurrence lists together; then each wave takes units (index, pattern length) from a queue in
+// LDS, longest patterns first, and keeps the best tree it has seen in its own LDS (two tree
+// buffers per wave: the unit being grown and the wave's best so far).  The strictly-greater
+// scan of Alg. 1 over (global, p = 1..P), (request, p = 1..P) picks the earliest unit among
+// those with the top SCORE, so "best" means SCORE high, then scan position low; the waves'
+// candidates meet in LDS after a barrier and the winning wave writes its tree out, padded
+// with -1 / 0.0.  Nothing but the final tree leaves the compute unit.
+#ifndef SD_SPEC_OCC
+#define SD_SPEC_OCC 4
+#endif
+
+template <bool STATS>
+__global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t *__restrict__ slot_ids,
+                                                    sd_trees out, int lds_per_wave) {
+    extern __shared__ double smem[];
+    __shared__ WgShared sh;
+    // the wave index is the same in all lanes: keep it (and every LDS address derived from it)
+    // in scalar registers
+    const int lane = threadIdx.x & 63, wave = uni((int32_t)(threadIdx.x >> 6)), nw = blockDim.x >> 6;
+    const int b = blockIdx.x;
+    unsigned nb = 0;
+    const int32_t slot = uni(slot_ids[b]);
+    const bool slot_ok = slot >= 0 && slot < p.max_slots;
+    if (!slot_ok && threadIdx.x == 0) atomicOr(&p.err[SD_DEVERR_SLOT], 1);
+    const int t = slot_ok ? uni(p.r_len[slot]) : 0;
+    const int32_t *x = p.r_text + (int64_t)(slot_ok ? slot : 0) * p.r_stride;
+
+    request_occurrences<STATS>(p, b, t, x, reinterpret_cast<int2 *>(smem), sh, nb);
+
+    // per-wave LDS: frontier (score, tok, par, lo, hi, dep), two trees (score, tok, par), staging
+    const int cap = p.max_nodes;
+    Frontier f;
+    f.score = smem + (size_t)wave * (lds_per_wave / 8);
+    double *const tsc0 = f.score + cap, *const tsc1 = tsc0 + cap;
+    f.tok = (int32_t *)(tsc1 + cap);
+    f.par = f.tok + cap; f.lo = f.par + cap; f.hi = f.lo + cap; f.dep = f.hi + cap;
+    int32_t *const ttk0 = f.dep + cap, *const tpr0 = ttk0 + cap;
+    int32_t *const ttk1 = tpr0 + cap, *const tpr1 = ttk1 + cap;
+    Stage sg;
+    sg.pos = tpr1 + cap; sg.cb = sg.pos + 64; sg.tc = sg.cb + 64; sg.tmp = sg.tc + TC_TOKENS;
+    f.n = 0; f.cap = 0;
+
+    double best_s = 0.0;
+    int best_o = -1, best_n = 0, cur = 0;
+    const int units = 2 * p.P;
+    for (;;) {
+        int u = 0;
+        if (lane == 0) u = atomicAdd(&sh.next, 1);
+        u = uni(u);
+        if (u >= units) break;
+        const int src = u >= p.P ? 1 : 0;
+        const int pl = p.P - (u - src * p.P);  // long patterns grow the largest trees: first
+        double total = 0.0;
+        const int n = run_unit<STATS>(p, sh, b, t, x, src, pl, f, sg, cur ? ttk1 : ttk0,
+                                      cur ? tpr1 : tpr0, cur ? tsc1 : tsc0, total, nb);
+        const int order = src * p.P + (pl - 1);
+        if (n > 0 && total > 0.0 &&
+            (best_o < 0 || total > best_s || (total == best_s && order < best_o))) {
+            best_s = total; best_o = order; best_n = n;
+            cur ^= 1;  // the tree just grown is kept; the next unit grows into the other buffer
+        }
+    }
+    if (lane == 0) { sh.best_s[wave] = best_s; sh.best_o[wave] = best_o; }
+    __syncthreads();
+    double ws = 0.0;
+    int wo = -1, ww = -1;
+    for (int w = 0; w < nw; w++) {
+        const double s = sh.best_s[w];
+        const int o = sh.best_o[w];
+        if (o >= 0 && (ww < 0 || s > ws || (s == ws && o < wo))) { ws = s; wo = o; ww = w; }
+    }
+    if (wave == (ww < 0 ? 0 : ww)) {
+        const int n = ww < 0 ? 0 : best_n;
+        const int kept = cur ^ 1;  // the buffer the wave's best tree was left in
+        const int32_t *btk = kept ? ttk1 : ttk0, *bpr = kept ? tpr1 : tpr0;
+        const double *bsc = kept ? tsc1 : tsc0;
+        const int64_t ob = (int64_t)b * out.max_nodes;
+        for (int i = lane; i < out.max_nodes; i += 64) {
+            const bool live = i < n;
+            out.d_tokens[ob + i] = live ? btk[i] : -1;
+            out.d_parents[ob + i] = live ? bpr[i] : -1;
+            out.d_scores[ob + i] = live ? bsc[i] : 0.0;
+            SD_CNT(16);
+        }
+        if (lane == 0) {
+            out.d_n_nodes[b] = n;
+            out.d_tree_score[b] = ww >= 0 ? ws : 0.0;
+            out.d_match_len[b] = ww >= 0 ? wo % p.P + 1 : 0;
+            out.d_source[b] = ww >= 0 ? wo / p.P : -1;
+            if (out.d_use_draft) out.d_use_draft[b] = (ww >= 0 && ws > p.tau) ? 1 : 0;
+            SD_CNT(24);
         }
     }
     flush_count<STATS>(nb, p.algo_bytes + SD_K_EXPAND);
-}
-
-// One wavefront per request, after both expansion launches have finished (the kernel boundary
-// is what makes the unit results of all compute dies visible here).
-template <bool STATS>
-__global__ __launch_bounds__(64) void k_select(SpecParams p, sd_trees out) {
-    unsigned nb = 0;
-    select_request<STATS>(p, out, blockIdx.x, nb);
-    flush_count<STATS>(nb, p.algo_bytes + SD_K_SELECT);
 }
 
 // Greedy verification walk, one wavefront per request, without walking: a node is "good" if
@@ -1236,6 +1237,25 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nod
 
 }  // namespace
 
+sd_status sd_speculate_setup(sd_ctx *c) {
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, c->cfg.device) != hipSuccess) return SD_ERR_HIP;
+    c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
+    c->lds_cu = prop.maxSharedMemoryPerMultiProcessor > 0 ? prop.maxSharedMemoryPerMultiProcessor
+                                                          : prop.sharedMemPerBlock;
+    int optin = 0;
+    if (hipDeviceGetAttribute(&optin, hipDeviceAttributeSharedMemPerBlockOptin, c->cfg.device) !=
+            hipSuccess || optin <= 0)
+        optin = (int)prop.sharedMemPerBlock;
+    c->lds_optin = (size_t)optin > sizeof(WgShared) + 256 ? (size_t)optin - sizeof(WgShared) - 256 : 0;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_speculate<false>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->lds_optin) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_speculate<true>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->lds_optin) != hipSuccess)
+        return SD_ERR_HIP;
+    return SD_OK;
+}
+
 sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
                             hipStream_t st) {
     if (batch == 0) return SD_OK;
@@ -1247,46 +1267,31 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     p.D = c->cfg.D; p.P = c->cfg.P; p.max_nodes = c->max_nodes;
     p.alpha = c->cfg.alpha; p.min_score = c->cfg.min_score; p.tau = c->cfg.tau;
     p.den_mode = c->cfg.den_mode; p.linear = c->cfg.linear;
-    p.occ = c->s_occ; p.occ_n = c->s_occ_n; p.cntL = c->s_cntL; p.unit_sa = c->s_unit_sa;
-    p.unit_n = c->s_unit_n; p.unit_score = c->s_unit_score; p.unit_tok = c->s_unit_tok;
-    p.unit_par = c->s_unit_par; p.unit_sc = c->s_unit_sc; p.err = c->d_err;
+    p.occ = c->s_occ; p.unit_sa = c->s_unit_sa;
+    p.err = c->d_err;
     p.algo_bytes = c->d_algo_bytes;
     p.unit_ticks = c->s_unit_ticks;
     const bool stats = c->prof_mode == 2;
-    size_t lds_wave = (size_t)c->max_nodes * (2 * sizeof(double) + 7 * sizeof(int32_t)) +
+    // per wave: frontier 6 arrays, two trees of 3 arrays, staging
+    size_t lds_wave = (size_t)c->max_nodes * (3 * sizeof(double) + 9 * sizeof(int32_t)) +
                       (64 + 64 + TC_TOKENS + 128) * sizeof(int32_t);
     lds_wave = (lds_wave + 7) / 8 * 8;
-    const size_t lds = lds_wave * EXPAND_WAVES;
-    const int n_units = batch * c->cfg.P;
-    const dim3 g_units((unsigned)((n_units + EXPAND_WAVES - 1) / EXPAND_WAVES)), g_req((unsigned)batch);
-    const dim3 b_units(64 * EXPAND_WAVES);
-    // Two concurrent legs: the caller's stream expands the global-index units while the
-    // context's second stream scans the request contexts and expands the per-request units.
-    // They join before the selection kernel.
-    if (hipEventRecord(c->ev_fork, st) != hipSuccess ||
-        hipStreamWaitEvent(c->aux_stream, c->ev_fork, 0) != hipSuccess)
-        return SD_ERR_HIP;
-    {
-        sd_span sp(c, SD_K_OCCURRENCES, c->aux_stream);
-        if (stats) hipLaunchKernelGGL(k_req_occurrences<true>, g_req, dim3(OCC_THREADS), 0, c->aux_stream, p, d_slot_ids);
-        else hipLaunchKernelGGL(k_req_occurrences<false>, g_req, dim3(OCC_THREADS), 0, c->aux_stream, p, d_slot_ids);
-    }
-    {
-        sd_span sp(c, SD_K_EXPAND_REQ, c->aux_stream);
-        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, b_units, lds, c->aux_stream, p, d_slot_ids, 1, batch, (int)lds_wave);
-        else hipLaunchKernelGGL(k_expand<false>, g_units, b_units, lds, c->aux_stream, p, d_slot_ids, 1, batch, (int)lds_wave);
-    }
-    if (hipEventRecord(c->ev_join, c->aux_stream) != hipSuccess) return SD_ERR_HIP;
+    // Waves per request: the compute units hold ceil(batch / #CU) workgroups each at SD_SPEC_OCC
+    // waves per SIMD, within the LDS of one compute unit; at least as much LDS as the
+    // occurrence sort needs.
+    const int per_cu = (batch + c->n_cu - 1) / c->n_cu;
+    int nw = 4 * SD_SPEC_OCC / per_cu;
+    const size_t lds_cu = c->lds_cu > 2048 * (size_t)per_cu ? c->lds_cu - 2048 * (size_t)per_cu : 0;
+    while (nw > 1 && (size_t)nw * lds_wave * per_cu > lds_cu) nw--;
+    if (nw > 16) nw = 16;
+    if (nw < 1) nw = 1;
+    size_t lds = (size_t)nw * lds_wave;
+    if (lds < OCC_LDS_SORT * sizeof(int2)) lds = OCC_LDS_SORT * sizeof(int2);
+    if (lds > c->lds_optin) return SD_ERR_CAPACITY;
     {
         sd_span sp(c, SD_K_EXPAND, st);
-        if (stats) hipLaunchKernelGGL(k_expand<true>, g_units, b_units, lds, st, p, d_slot_ids, 0, batch, (int)lds_wave);
-        else hipLaunchKernelGGL(k_expand<false>, g_units, b_units, lds, st, p, d_slot_ids, 0, batch, (int)lds_wave);
-    }
-    if (hipStreamWaitEvent(st, c->ev_join, 0) != hipSuccess) return SD_ERR_HIP;
-    {
-        sd_span sp(c, SD_K_SELECT, st);
-        if (stats) hipLaunchKernelGGL(k_select<true>, g_req, dim3(64), 0, st, p, out);
-        else hipLaunchKernelGGL(k_select<false>, g_req, dim3(64), 0, st, p, out);
+        if (stats) hipLaunchKernelGGL(k_speculate<true>, dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
+        else hipLaunchKernelGGL(k_speculate<false>, dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
     }
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
