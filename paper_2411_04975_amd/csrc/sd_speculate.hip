@@ -115,6 +115,7 @@ struct WgShared {
     int m;           // occurrences of the context's last token
     int next;        // head of the unit queue
     int cnt[72];     // [l]: occurrences whose left-extension is l; afterwards: is at least l
+    int g_lo[65], g_hi[65];  // [p]: suffix-array range of the pattern of length p (global index)
     double best_s[16];
     int best_o[16];
 };
@@ -574,7 +575,7 @@ constexpr int TIE_MAX = 4;
 template <bool STATS>
 __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ text, double s,
                             int K, int D, int &n, double &total, int32_t *t_tok, int32_t *t_par,
-                            double *t_score, unsigned &nb) {
+                            double *t_score, bool &deepest, unsigned &nb) {
     const int lane = threadIdx.x & 63;
     if (f.n > 64) return false;
     const bool have = lane < f.n;
@@ -736,6 +737,7 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
                         par = myi == 0 ? cpar[q] : n0 + 63 - __clzll((unsigned long long)prev);
                     }
                     const int used = __popcll(mq);
+                    if (used > 0 && cdep[q] + used - 1 >= D) deepest = true;
                     if (used < alen[q]) {  // the chain goes on: its next element is the new head
                         alive |= 1u << q;
                         ctok[q] = __builtin_amdgcn_readlane(st[q], used);
@@ -785,6 +787,7 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         for (int q = 0; q < TIE_MAX; q++)
             if (q == c) {
                 const int e = cdep[q];
+                if (e >= D) deepest = true;
                 if (e < D) {
                     if (woff[q] >= 64) {  // reload the window further down the suffix
                         win[q] = text[(int64_t)sg.pos[cslot[q]] + e + lane];
@@ -906,14 +909,16 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
 }
 
 // One unit (request b, index src: 0 global / 1 request, pattern length pl) on one wavefront:
-// MatchPattern, then ExpandSpeculationTree into the LDS tree (t_tok, t_par, t_score).  Returns
-// the number of draft nodes and leaves their SCORE in `total`.
+// ExpandSpeculationTree below the matched node into the LDS tree (t_tok, t_par, t_score).
+// Returns the number of draft nodes and leaves their SCORE in `total`; `deepest` tells whether
+// a node of depth D (which may have no children) was taken.
 template <bool STATS>
 __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh, int b, int t,
                         const int32_t *__restrict__ x, int src, int pl, Frontier &f, Stage &sg,
                         int32_t *t_tok, int32_t *t_par, double *t_score, double &total,
-                        unsigned &nb) {
+                        bool &deepest, unsigned &nb) {
     const int lane = threadIdx.x & 63;
+    deepest = false;
     const uint64_t tick0 = STATS ? wall_clock64() : 0;
     const int64_t uidx = (int64_t)b * (2 * p.P) + src * p.P + (pl - 1);
     const int K = (int)floor(p.alpha * (double)pl);
@@ -924,14 +929,11 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
     const int32_t *sa = nullptr, *text = nullptr;
     int32_t lo = 0, hi = 0;
     if (pl <= t && K >= 1) {
-        if (src == 0) {
-            if (p.g_N > 0) {
-                const int32_t wk = lane < pl ? x[t - pl + lane] : 0;  // lane k: pattern token k
-                if (lane < pl) SD_CNT(4);
-                sa = p.g_sa;
-                text = p.g_text;
-                match_global<STATS>(p, wk, pl, lo, hi, nb);
-            }
+        if (src == 0) {  // matched by the whole workgroup beforehand
+            sa = p.g_sa;
+            text = p.g_text;
+            lo = uni(sh.g_lo[pl]);
+            hi = uni(sh.g_hi[pl]);
         } else {
             // per-request structure: occurrences whose left-extension reaches pl, in the
             // order request_occurrences left them (sorted by what follows)
@@ -985,11 +987,13 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
             const Key best = frontier_pick(f, true, -1);
             if (best.s < p.min_score) break;
             if (!p.linear &&
-                tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok, t_par, t_score, nb))
+                tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok, t_par, t_score,
+                                   deepest, nb))
                 continue;
             const int bi = best.idx;
             const int32_t blo = uni(f.lo[bi]), bhi = uni(f.hi[bi]);
             int32_t d = uni(f.dep[bi]);
+            if (d >= p.D) deepest = true;
             if (lane == 0) {
                 t_tok[n] = best.tok; t_par[n] = best.par; t_score[n] = best.s;
             }
@@ -1033,6 +1037,7 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
                         cur += L;
                         n += L;
                         d += L;
+                        if (d >= p.D) deepest = true;
                     }
                 }
             }
@@ -1054,9 +1059,10 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
 }
 
 // GenerateCandidateTree for one request per workgroup.  All waves first build the request's
-// occurrence lists together; then each wave takes units (index, pattern length) from a queue in
-// LDS, longest patterns first, and keeps the best tree it has seen in its own LDS (two tree
-// buffers per wave: the unit being grown and the wave's best so far).  The strictly-greater
+// occurrence lists together and match the P patterns against the global index; then each wave
+// takes runs of pattern lengths with equal counts from a queue in LDS, longest patterns first,
+// and keeps the best tree it has seen in its own LDS (two tree buffers per wave: the tree
+// being grown and the wave's best so far).  The strictly-greater
 // scan of Alg. 1 over (global, p = 1..P), (request, p = 1..P) picks the earliest unit among
 // those with the top SCORE, so "best" means SCORE high, then scan position low; the waves'
 // candidates meet in LDS after a barrier and the winning wave writes its tree out, padded
@@ -1096,24 +1102,78 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
     sg.pos = tpr1 + cap; sg.cb = sg.pos + 64; sg.tc = sg.cb + 64; sg.tmp = sg.tc + TC_TOKENS;
     f.n = 0; f.cap = 0;
 
+    // MatchPattern on the global index for every pattern length, spread over the waves
+    const int P = p.P;
+    for (int pl = 1 + wave; pl <= P; pl += nw) {
+        int32_t lo = 0, hi = 0;
+        if (pl <= t && p.g_N > 0) {
+            const int32_t wk = lane < pl ? x[t - pl + lane] : 0;  // lane k: pattern token k
+            if (lane < pl) SD_CNT(4);
+            match_global<STATS>(p, wk, pl, lo, hi, nb);
+        }
+        if (lane == 0) { sh.g_lo[pl] = lo; sh.g_hi[pl] = hi; }
+    }
+    __syncthreads();
+
+    // Pattern lengths with the same number of occurrences in an index have the same
+    // occurrences (the longer pattern's are among the shorter one's), hence the same subtree
+    // below the matched node: their trees are prefixes of one greedy order, cut at K(p) nodes,
+    // unless the depth bound D interferes.  So per run of equal counts only the longest pattern
+    // is expanded; if no node of depth D was taken, every shorter pattern of the run has the
+    // same tree when its K reaches that size (and a strictly lower SCORE otherwise), and the
+    // strictly-greater scan of Alg. 1 would keep the shortest of those.  If the bound did
+    // interfere, the next shorter pattern is expanded on its own, and so on.
+    // A pattern of length q with q + K(q) >= D could reach the bound; whether it does is only
+    // known after its expansion, and waiting for that would serialise the run.  Such patterns
+    // are therefore taken one by one (all in parallel), and runs are formed among the shorter
+    // ones, where the bound cannot interfere.
+    // Runs: entry i stands for pattern length P - i; lane i looks at entry i.
+    int cg = 0, cr = 0, cgp = -1, crp = -1;
+    bool alone = true;  // the next longer pattern may reach the depth bound
+    if (lane < P) {
+        const int pl = P - lane;
+        cg = sh.g_hi[pl] - sh.g_lo[pl];
+        cr = sh.cnt[pl];
+        if (lane > 0) {
+            cgp = sh.g_hi[pl + 1] - sh.g_lo[pl + 1];
+            crp = sh.cnt[pl + 1];
+            alone = pl + 1 + (int)floor(p.alpha * (double)(pl + 1)) >= p.D;
+        }
+    }
+    // a request-side list of one entry is the context's own tail: nothing follows it
+    const uint64_t start_g = __ballot(lane < P && cg > 0 && (alone || cg != cgp));
+    const uint64_t start_r = __ballot(lane < P && cr > 1 && (alone || cr != crp));
+    const int ng = __popcll(start_g), nruns = ng + __popcll(start_r);
+
     double best_s = 0.0;
     int best_o = -1, best_n = 0, cur = 0;
-    const int units = 2 * p.P;
     for (;;) {
-        int u = 0;
-        if (lane == 0) u = atomicAdd(&sh.next, 1);
-        u = uni(u);
-        if (u >= units) break;
-        const int src = u >= p.P ? 1 : 0;
-        const int pl = p.P - (u - src * p.P);  // long patterns grow the largest trees: first
-        double total = 0.0;
-        const int n = run_unit<STATS>(p, sh, b, t, x, src, pl, f, sg, cur ? ttk1 : ttk0,
-                                      cur ? tpr1 : tpr0, cur ? tsc1 : tsc0, total, nb);
-        const int order = src * p.P + (pl - 1);
-        if (n > 0 && total > 0.0 &&
-            (best_o < 0 || total > best_s || (total == best_s && order < best_o))) {
-            best_s = total; best_o = order; best_n = n;
-            cur ^= 1;  // the tree just grown is kept; the next unit grows into the other buffer
+        int g = 0;
+        if (lane == 0) g = atomicAdd(&sh.next, 1);
+        g = uni(g);
+        if (g >= nruns) break;
+        const int src = g >= ng ? 1 : 0;
+        uint64_t m = src ? start_r : start_g;
+        for (int k = src ? g - ng : g; k > 0; k--) m &= m - 1;
+        const int i0 = __ffsll((unsigned long long)m) - 1;
+        m &= m - 1;
+        const int i1 = m ? __ffsll((unsigned long long)m) - 1 : P;
+        const int p_lo = P - i1 + 1;
+        for (int pl = P - i0; pl >= p_lo; pl--) {
+            double total = 0.0;
+            bool deepest = false;
+            const int n = run_unit<STATS>(p, sh, b, t, x, src, pl, f, sg, cur ? ttk1 : ttk0,
+                                          cur ? tpr1 : tpr0, cur ? tsc1 : tsc0, total, deepest, nb);
+            int pstar = pl;  // shortest pattern of the run with this very tree
+            if (!deepest)
+                while (pstar > p_lo && (int)floor(p.alpha * (double)(pstar - 1)) >= n) pstar--;
+            const int order = src * P + (pstar - 1);
+            if (n > 0 && total > 0.0 &&
+                (best_o < 0 || total > best_s || (total == best_s && order < best_o))) {
+                best_s = total; best_o = order; best_n = n;
+                cur ^= 1;  // the tree just grown is kept; the next one grows into the other buffer
+            }
+            if (!deepest) break;
         }
     }
     if (lane == 0) { sh.best_s[wave] = best_s; sh.best_o[wave] = best_o; }
