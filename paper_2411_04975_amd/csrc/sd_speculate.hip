@@ -570,7 +570,26 @@ __device__ __forceinline__ void match_range(const int32_t *__restrict__ sa, cons
 // scores strictly lower.  The greedy rule therefore keeps taking the head with the lowest
 // (token, parent) among these chains until they end or K is reached: a merge that needs no
 // frontier traffic.  Returns false (and changes nothing) if the frontier does not have that form.
-constexpr int TIE_MAX = 4;
+//
+// The chains are merged as whole sequences, one after the other (taking the best head among k
+// chains equals merging them pairwise, because (token, parent) keys are distinct).  Merging a
+// sequence X with a chain Y under "take the head with the lower (token, parent)": element x_t
+// leaves after exactly r(t) elements of Y, where r(t) is the first j >= r(t-1) at which y_j
+// does not beat x_t.  y_j beats x_t if its token is lower, or equal with the lower parent
+// index; parents are the chain predecessors, so on equal tokens y_j wins iff y_(j-1) left
+// before x_t's own predecessor x_t', i.e. iff j <= r(t') (for chain heads the given parent
+// indices decide).  One pair of ballots per x_t gives {j : y_j < x_t} and {j : y_j == x_t} as
+// lane masks and r(t) follows with a few scalar bit operations.  x_t lands at t + r(t); the
+// elements of Y fill the positions left over, in order.  At most 63 nodes are taken per call
+// (one 64-token window per chain: its head plus 63 tokens), the caller comes back for more.
+// Per-chain state lives in the lanes of vector registers (lane q: chain q).
+constexpr int TIE_MAX = 12;
+
+__device__ __forceinline__ uint64_t ballot64(bool pred) { return __builtin_amdgcn_ballot_w64(pred); }
+// v with lane `idx` replaced by the uniform value `val`
+__device__ __forceinline__ int32_t set_lane(int32_t val, int idx, int32_t v) {
+    return (int)(threadIdx.x & 63) == idx ? val : v;
+}
 
 template <bool STATS>
 __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_t *__restrict__ text, double s,
@@ -582,240 +601,147 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
     const bool tie = have && f.score[lane] == s;
     const int32_t mylo = have ? f.lo[lane] : 0, myhi = have ? f.hi[lane] : 0;
     const bool fit = myhi - mylo == 1 && mylo >= sg.lo && mylo < sg.lo + sg.m;
-    const uint64_t T = __ballot(tie);
+    const uint64_t T = ballot64(tie);
     const int j = __popcll(T);
     // a single top entry is not a tie: the unary-run shortcut takes its whole chain at once
-    if (j < 2 || j > TIE_MAX || __ballot(tie && !fit)) return false;
-    // chain heads into uniform registers
-    int32_t ctok[TIE_MAX], cpar[TIE_MAX], cdep[TIE_MAX], cslot[TIE_MAX];
-    {
-        uint64_t rest = T;
-#pragma unroll
-        for (int c = 0; c < TIE_MAX; c++) {
-            ctok[c] = 0; cpar[c] = 0; cdep[c] = 0; cslot[c] = 0;
-            if (rest) {
-                int i = __ffsll((unsigned long long)rest) - 1;
-                rest &= rest - 1;
-                ctok[c] = uni(f.tok[i]); cpar[c] = uni(f.par[i]); cdep[c] = uni(f.dep[i]);
-                cslot[c] = uni(f.lo[i]) - sg.lo;
-            }
-        }
-    }
+    if (j < 2 || j > TIE_MAX || ballot64(tie && !fit)) return false;
+    int32_t *TT = sg.tmp, *MM = sg.tmp + 64;
+    // chain q = the q-th tied entry in frontier order; its head moves into lane q
+    const int32_t etok = have ? f.tok[lane] : 0, epar = have ? f.par[lane] : 0,
+                  edep = have ? f.dep[lane] : 0;
+    const double eks = have ? f.score[lane] : 0.0;
+    if (tie) TT[__popcll(T & lanemask_lt())] = lane;
+    wsync();
+    const int srcl = lane < j ? TT[lane] : 0;
+    const int32_t ctokv = __shfl(etok, srcl), cparv = __shfl(epar, srcl), cdepv = __shfl(edep, srcl),
+                  cslotv = __shfl(mylo, srcl) - sg.lo;
+    const int32_t cposv = lane < j ? sg.pos[cslotv] : 0;
     // take the tied entries out of the frontier (the others keep their relative order)
     {
         const bool keep = have && !tie;
-        const double ks = keep ? f.score[lane] : 0.0;
-        const int32_t kt = keep ? f.tok[lane] : 0, kp = keep ? f.par[lane] : 0,
-                      kd = keep ? f.dep[lane] : 0;
-        const int dst = __popcll(__ballot(keep) & lanemask_lt());
+        const int dst = __popcll(ballot64(keep) & lanemask_lt());
         wsync();
         if (keep) {
-            f.score[dst] = ks; f.tok[dst] = kt; f.par[dst] = kp; f.lo[dst] = mylo; f.hi[dst] = myhi;
-            f.dep[dst] = kd;
+            f.score[dst] = eks; f.tok[dst] = etok; f.par[dst] = epar; f.lo[dst] = mylo; f.hi[dst] = myhi;
+            f.dep[dst] = edep;
         }
         f.n -= j;
         wsync();
     }
-    // Each chain's upcoming tokens sit in one register across the wave (lane k: the token k
-    // positions after the chain's current child index), so a step of the merge is a handful of
-    // scalar compares and one lane read; nodes are collected in registers (lane i: i-th node
-    // taken here) and written to the tree in one go.
-    int32_t win[TIE_MAX], woff[TIE_MAX];
-#pragma unroll
-    for (int q = 0; q < TIE_MAX; q++) {
-        woff[q] = 0;
-        win[q] = q < j ? text[(int64_t)sg.pos[cslot[q]] + cdep[q] + lane] : -1;
-    }
-    unsigned alive = (1u << j) - 1u;
-    const int n0 = uni(n);
-    int32_t otok = 0, opar = 0;
-    int nn = uni(n);
-    const int KK = uni(K);
-
-    // Whole-chain merge.  Merging a sequence X with a chain Y under "take the head with the
-    // lower (token, parent)": element x_t leaves after exactly r(t) elements of Y, where r(t)
-    // is the first j >= r(t-1) at which y_j does not beat x_t.  y_j beats x_t if its token is
-    // lower, or equal with the lower parent index; parents are the chain predecessors, so on
-    // equal tokens y_j wins iff y_(j-1) left before x_t's own predecessor x_t', i.e. iff
-    // j <= r(t') (for chain heads the given parent indices decide).  One ballot pair per x_t
-    // gives {j : y_j < x_t} and {j : y_j == x_t} as lane masks, r(t) follows with a few scalar
-    // bit operations, and the output positions are t + r(t) for X and j + #{t : r(t) <= j} for
-    // Y.  More chains are merged in one after the other (taking the best head among k chains
-    // equals merging them pairwise).  A chain that does not fit one 64-token window sends
-    // the whole thing to the step-by-step merge below.
-    bool merged = false;
+    const int n0 = uni(n), KK = uni(K);
+    const int room = KK - n0 < 63 ? KK - n0 : 63;
+    // chain q as a sequence: element 0 is the frontier entry, element k its k-th descendant
+    // (the token at child index cdep + k - 1); `alen` = how many elements exist
+    int32_t alenv = 0;
+    int32_t zt, zm = lane, zprev = lane - 1, zinit;
+    int lz;
+    int32_t wnext = text[(int64_t)__builtin_amdgcn_readlane(cposv, 0) + __builtin_amdgcn_readlane(cdepv, 0) + lane];
     {
-        const int room = KK - n0 < 64 ? KK - n0 : 64;
-        bool fits = true;
-#pragma unroll
-        for (int q = 0; q < TIE_MAX; q++)
-            if (q < j && D - cdep[q] > 63) fits = false;
-        if (fits && room > 0) {
-            int32_t st[TIE_MAX];
-            int alen[TIE_MAX];
-#pragma unroll
-            for (int q = 0; q < TIE_MAX; q++) {
-                // sequence of chain q: element 0 is the frontier entry, element k its k-th
-                // descendant (token at child index cdep + k - 1)
-                const int32_t up = __shfl_up(win[q], 1);
-                st[q] = lane == 0 ? ctok[q] : up;
-                const uint64_t bad = __ballot(lane >= 1 && (up < 0 || cdep[q] + lane - 1 >= D));
-                alen[q] = q < j ? (bad ? __ffsll((unsigned long long)bad) - 1 : 64) : 0;
+        const int32_t w = wnext;
+        wnext = text[(int64_t)__builtin_amdgcn_readlane(cposv, 1) + __builtin_amdgcn_readlane(cdepv, 1) + lane];
+        const int cd = __builtin_amdgcn_readlane(cdepv, 0);
+        const int32_t up = __shfl_up(w, 1);
+        zt = lane == 0 ? __builtin_amdgcn_readlane(ctokv, 0) : up;
+        const uint64_t bad = ballot64(lane >= 1 && (up < 0 || cd + lane - 1 >= D));
+        const int a = bad ? __ffsll((unsigned long long)bad) - 1 : 64;
+        alenv = set_lane(a, 0, alenv);
+        lz = a < room ? a : room;
+        zinit = __builtin_amdgcn_readlane(cparv, 0);
+    }
+    for (int q = 1; q < j; q++) {
+        const int32_t w = wnext;
+        if (q + 1 < j)
+            wnext = text[(int64_t)__builtin_amdgcn_readlane(cposv, q + 1) +
+                         __builtin_amdgcn_readlane(cdepv, q + 1) + lane];
+        const int cd = __builtin_amdgcn_readlane(cdepv, q);
+        const int32_t up = __shfl_up(w, 1);
+        const int32_t yt = lane == 0 ? __builtin_amdgcn_readlane(ctokv, q) : up;
+        const uint64_t bad = ballot64(lane >= 1 && (up < 0 || cd + lane - 1 >= D));
+        const int a = bad ? __ffsll((unsigned long long)bad) - 1 : 64;
+        alenv = set_lane(a, q, alenv);
+        const int ly = a < room ? a : room;
+        const uint64_t ymask = ly >= 64 ? ~0ull : ((1ull << ly) - 1ull);
+        const int32_t yinit = __builtin_amdgcn_readlane(cparv, q);
+        // x_t lands at t + r(t) and r never decreases: once that reaches `room` neither x_t nor
+        // anything after it is kept, and every y_j still unplaced lands at j + t >= room as
+        // well.  Lanes the loop never reached keep myr = 64 (dropped).
+        int r = 0;
+        int32_t myr = 64;
+        for (int t = 0; t < lz && t + r < room; t++) {
+            const int32_t xt = __builtin_amdgcn_readlane(zt, t);
+            uint64_t lt = ballot64(yt < xt) & ymask;
+            const uint64_t eq = ballot64(yt == xt) & ymask;
+            if (eq) {  // ties: y_j wins for j <= R
+                const int32_t tp = __builtin_amdgcn_readlane(zprev, t);
+                int R;
+                if (tp >= 0) R = __builtin_amdgcn_readlane(myr, tp);
+                else R = yinit < __builtin_amdgcn_readlane(zinit, t) ? 0 : -1;
+                const uint64_t le = R < 0 ? 0ull : (R >= 63 ? ~0ull : ((2ull << R) - 1ull));
+                lt |= eq & le;
             }
-            // merged sequence so far: token, meta = chain << 8 | element index, index of the
-            // same chain's previous element in the sequence (-1: chain head), the chain's
-            // given parent index
-            int32_t zt = st[0], zm = lane, zprev = lane - 1, zinit = cpar[0];
-            int lz = alen[0] < room ? alen[0] : room;
-            int32_t *T = sg.tmp, *M = sg.tmp + 64;
-#pragma unroll
-            for (int q = 1; q < TIE_MAX; q++) {
-                if (q >= j) continue;
-                const int ly = alen[q] < room ? alen[q] : room;
-                const int32_t yt = st[q];
-                const int32_t yinit = cpar[q];
-                int r = 0;
-                // x_t lands at t + r(t) and r never decreases: once that reaches `room` neither
-                // x_t nor anything after it is kept, and every y_j still unplaced lands at
-                // j + t >= room as well.  Lanes the loop never reached keep myr = 64 (dropped).
-                int32_t myr = 64, before = 0;
-                for (int t = 0; t < lz && t + r < room; t++) {
-                    const int32_t xt = __builtin_amdgcn_readlane(zt, t);
-                    const int32_t tp = __builtin_amdgcn_readlane(zprev, t);
-                    uint64_t lt = __ballot(lane < ly && yt < xt);
-                    const uint64_t eq = __ballot(lane < ly && yt == xt);
-                    if (eq) {  // ties: y_j wins for j <= R
-                        int R;
-                        if (tp >= 0) R = __builtin_amdgcn_readlane(myr, tp);
-                        else R = yinit < __builtin_amdgcn_readlane(zinit, t) ? 0 : -1;
-                        const uint64_t le = R < 0 ? 0ull : (R >= 63 ? ~0ull : ((2ull << R) - 1ull));
-                        lt |= eq & le;
-                    }
-                    if (r < 64) {
-                        const uint64_t rest = ~(lt >> r);
-                        r = rest ? r + __ffsll((unsigned long long)rest) - 1 : 64;
-                    }
-                    if (lane == t) myr = r;
-                    before += lane >= r ? 1 : 0;
-                }
-                wsync();
-                if (lane < lz && lane + myr < 64) { T[lane + myr] = zt; M[lane + myr] = zm; }
-                if (lane < ly && lane + before < 64) {
-                    T[lane + before] = yt;
-                    M[lane + before] = (q << 8) | lane;
-                }
-                wsync();
-                lz = lz + ly < room ? lz + ly : room;
-                zt = T[lane];
-                zm = M[lane];
-                // predecessor links and given parents of the new sequence
-                zprev = -1;
-                zinit = 0;
-#pragma unroll
-                for (int c = 0; c < TIE_MAX; c++) {
-                    if (c > q) continue;
-                    const bool mine = lane < lz && (zm >> 8) == c;
-                    const uint64_t mc = __ballot(mine);
-                    if (mine) {
-                        const uint64_t prev = mc & lanemask_lt();
-                        zprev = prev ? 63 - __clzll((unsigned long long)prev) : -1;
-                        zinit = cpar[c];
-                    }
-                }
+            if (r < 64) {
+                const uint64_t rest = ~(lt >> r);
+                r = rest ? r + __ffsll((unsigned long long)rest) - 1 : 64;
             }
-            {
-                const bool live = lane < lz;
-                const int myc = zm >> 8, myi = zm & 255;
-                int32_t par = 0;
-                alive = 0;
-#pragma unroll
-                for (int q = 0; q < TIE_MAX; q++) {
-                    if (q >= j) continue;
-                    const uint64_t mq = __ballot(live && myc == q);
-                    if (live && myc == q) {
-                        const uint64_t prev = mq & lanemask_lt();
-                        par = myi == 0 ? cpar[q] : n0 + 63 - __clzll((unsigned long long)prev);
-                    }
-                    const int used = __popcll(mq);
-                    if (used > 0 && cdep[q] + used - 1 >= D) deepest = true;
-                    if (used < alen[q]) {  // the chain goes on: its next element is the new head
-                        alive |= 1u << q;
-                        ctok[q] = __builtin_amdgcn_readlane(st[q], used);
-                        if (used > 0) cpar[q] = n0 + 63 - __clzll((unsigned long long)mq);
-                        cdep[q] += used;
-                    }
-                }
-                if (live) {
-                    t_tok[n0 + lane] = zt; t_par[n0 + lane] = par; t_score[n0 + lane] = s;
-                    SD_CNT(8);
-                }
-                for (int i = 0; i < lz; i++) total += s;
-                nn = n0 + lz;
-                merged = true;
+            myr = set_lane(r, t, myr);
+        }
+        wsync();
+        MM[lane] = -1;
+        wsync();
+        if (lane < lz && lane + myr < 64) { TT[lane + myr] = zt; MM[lane + myr] = zm; }
+        wsync();
+        const int32_t mt = TT[lane], mm = MM[lane];
+        const bool hole = mm == -1;  // not taken by X: the holes take Y's elements in order
+        const int h = __popcll(ballot64(hole) & lanemask_lt());
+        const int32_t yv = __shfl(yt, h);
+        zt = hole ? yv : mt;
+        zm = hole ? ((q << 8) | h) : mm;
+        lz = lz + ly < room ? lz + ly : room;
+        // predecessor links and given parents of the new sequence
+        zprev = -1;
+        for (int c = 0; c <= q; c++) {
+            const bool mine = lane < lz && (zm >> 8) == c;
+            const uint64_t mc = ballot64(mine);
+            if (mine) {
+                const uint64_t prev = mc & lanemask_lt();
+                zprev = prev ? 63 - __clzll((unsigned long long)prev) : -1;
             }
         }
+        zinit = __shfl(cparv, (zm >> 8) & 63);
+        wsync();
     }
-    while (!merged && nn < KK && alive && nn - n0 < 64) {
-        // keep the merge state in scalar registers: every compare and select below is then a
-        // scalar instruction instead of a vector one under an execution mask
-        alive = (unsigned)uni((int32_t)alive);
-#pragma unroll
-        for (int q = 0; q < TIE_MAX; q++) {
-            ctok[q] = uni(ctok[q]); cpar[q] = uni(cpar[q]); cdep[q] = uni(cdep[q]);
-            woff[q] = uni(woff[q]);
-        }
-        int c = __ffs(alive) - 1;
-        int32_t etok = 0, epar = 0;
-#pragma unroll
-        for (int q = 0; q < TIE_MAX; q++)
-            if (q == c) { etok = ctok[q]; epar = cpar[q]; }
-#pragma unroll
-        for (int o = 1; o < TIE_MAX; o++)
-            if (o > c && ((alive >> o) & 1u) &&
-                (ctok[o] < etok || (ctok[o] == etok && cpar[o] < epar))) {
-                c = o;
-                etok = ctok[o];
-                epar = cpar[o];
-            }
-        if (lane == nn - n0) { otok = etok; opar = epar; }
-        total += s;
-        SD_CNT(lane == 0 ? 8 : 0);
-        // the node just taken has depth e; its only possible child is the suffix's token e,
-        // which is win[c] at offset woff[c]
-        int32_t next = -1;
-#pragma unroll
-        for (int q = 0; q < TIE_MAX; q++)
-            if (q == c) {
-                const int e = cdep[q];
-                if (e >= D) deepest = true;
-                if (e < D) {
-                    if (woff[q] >= 64) {  // reload the window further down the suffix
-                        win[q] = text[(int64_t)sg.pos[cslot[q]] + e + lane];
-                        woff[q] = 0;
-                    }
-                    next = __builtin_amdgcn_readlane(win[q], woff[q]);
-                }
-                woff[q]++;
-                ctok[q] = next; cpar[q] = nn; cdep[q] = e + 1;
-            }
-        if (next < 0) alive &= ~(1u << c);
-        nn++;
+    const bool live = lane < lz;
+    const int myc = zm >> 8;
+    if (live) {
+        t_tok[n0 + lane] = zt; t_par[n0 + lane] = zprev < 0 ? zinit : n0 + zprev; t_score[n0 + lane] = s;
+        SD_CNT(8);
     }
+    for (int i = 0; i < lz; i++) total += s;
+    const int nn = n0 + lz;
+    // per chain: how many elements were taken and where the last of them went
+    int32_t usedv = 0, lastv = 0;
+    for (int q = 0; q < j; q++) {
+        const uint64_t mq = ballot64(live && myc == q);
+        usedv = set_lane((int)__popcll(mq), q, usedv);
+        lastv = set_lane(mq ? 63 - (int)__clzll((unsigned long long)mq) : 0, q, lastv);
+    }
+    if (ballot64(lane < j && usedv > 0 && cdepv + usedv - 1 >= D)) deepest = true;
     n = nn;
-    if (!merged && lane < n - n0) {
-        t_tok[n0 + lane] = otok; t_par[n0 + lane] = opar; t_score[n0 + lane] = s;
-    }
-    // surviving heads go back into the frontier
-#pragma unroll
-    for (int q = 0; q < TIE_MAX; q++)
-        if ((alive >> q) & 1u) {
-            if (lane == 0) {
-                const int d = f.n;
-                f.score[d] = s; f.tok[d] = ctok[q]; f.par[d] = cpar[q]; f.lo[d] = sg.lo + cslot[q];
-                f.hi[d] = sg.lo + cslot[q] + 1; f.dep[d] = cdep[q];
-            }
-            f.n++;
+    if (nn < KK) {  // chains that go on put their next element back into the frontier
+        const bool goes_on = lane < j && usedv < alenv;
+        int32_t ntok = ctokv;
+        if (goes_on && usedv > 0) {
+            ntok = text[(int64_t)cposv + cdepv + usedv - 1];
+            SD_CNT(4);
         }
+        const uint64_t A = ballot64(goes_on);
+        if (goes_on) {
+            const int d = f.n + __popcll(A & lanemask_lt());
+            f.score[d] = s; f.tok[d] = ntok; f.par[d] = usedv > 0 ? n0 + lastv : cparv;
+            f.lo[d] = sg.lo + cslotv; f.hi[d] = sg.lo + cslotv + 1; f.dep[d] = cdepv + usedv;
+        }
+        f.n += __popcll(A);
+    }
     wsync();
     return true;
 }
