@@ -119,6 +119,36 @@ def test_non_identity_slots_and_partial_batch(tiny_workload):
     _run_workload(w, slots=slots)
 
 
+
+def _more_minis():
+    """Cases aimed at the chain merge (token ties, more chains than one call merges, chains
+    longer than one window), at the depth bound inside runs of equal counts, and at the
+    largest tree size."""
+    out = []
+    # three symbols, deep bound, big trees: long single-occurrence chains full of token ties
+    rng = np.random.default_rng(21)
+    doc = list(rng.integers(0, 3, 700))
+    ctxs = [doc[a:a + ln] for a, ln in ((100, 40), (333, 25), (10, 12), (600, 9), (250, 60))]
+    out.append(("ties-deep-window", 3, 200, 8, 8.0, 0.01, [doc, doc[50:400]], ctxs))
+    # one pattern followed by many different one-off continuations (10 and 14 tied chains)
+    docs = []
+    for fan in (10, 14):
+        for i in range(fan):
+            docs.append([7, 8, 50 + fan] + [1000 * fan + 40 * i + k for k in range(30)])
+    out.append(("many-tied-chains", 20000, 40, 4, 8.0, 0.01, docs,
+                [[3, 7, 8, 60], [5, 7, 8, 64], [7, 8, 60, 10000], [8, 64]]))
+    # periodic text: every pattern length has the same chain below it and the depth bound cuts it
+    per = [4, 9, 2, 7, 5]
+    out.append(("periodic-depth-bound", 16, 14, 8, 3.0, 0.05, [per * 30, per * 3 + [1, 2, 3]],
+                [per * 4, (per * 4)[:-2], per * 2 + [4, 9], [9, 2, 7]]))
+    # largest tree size the library accepts
+    rng = np.random.default_rng(22)
+    doc = list(rng.integers(0, 4, 3000))
+    ctxs = [doc[a:a + ln] for a, ln in ((500, 300), (1200, 80), (2500, 150), (40, 70))]
+    out.append(("largest-trees", 4, 255, 64, 4.0, 0.001, [doc], ctxs))
+    return out
+
+
 MINIS = [
     # vocab, D, P, alpha, min_score, docs, contexts
     ("all-equal", 2, 6, 3, 2.0, 0.05, [[1] * 50], [[1] * 20, [1], [0, 1, 1]]),
@@ -131,7 +161,7 @@ MINIS = [
     ("binary-wide", 2, 12, 6, 4.0, 0.02,
      [list(np.random.default_rng(11).integers(0, 2, 400))], None),
     ("alpha-below-one", 5, 9, 6, 0.5, 0.1, [[0, 1, 2, 3, 4] * 12], [[3, 4, 0, 1, 2, 3]]),
-]
+] + _more_minis()
 
 
 @pytest.mark.parametrize("name,vocab,D,P,alpha,ms,docs,contexts", MINIS,
