@@ -164,25 +164,44 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                     int off = 0;
                     if (lane == 63) off = atomicAdd(&sh.m, inc);
                     off = __shfl(off, 63) + inc - nh;
-                    if (h0) occ[off++].x = e0;
-                    if (h1) occ[off++].x = e0 + 1;
-                    if (h2) occ[off++].x = e0 + 2;
-                    if (h3) occ[off++].x = e0 + 3;
+                    // the first OCC_LDS_SORT hits are also kept in LDS, where they are sorted
+                    const int es[4] = {e0, e0 + 1, e0 + 2, e0 + 3};
+                    const int hs[4] = {h0, h1, h2, h3};
+#pragma unroll
+                    for (int c = 0; c < 4; c++)
+                        if (hs[c]) {
+                            occ[off].x = es[c];
+                            if (off < OCC_LDS_SORT) s_sort[off].x = es[c];
+                            off++;
+                        }
                 }
             }
         }
     }
     __syncthreads();
     const int m = sh.m;
-    // how far each occurrence extends to the left together with the context's own tail
-    for (int i = tid; i < m; i += nthr) {
-        int e = occ[i].x;
-        int lim = e + 1 < p.P ? e + 1 : p.P;
-        int l = 1;
-        while (l < lim && x[e - l] == x[t - 1 - l]) l++;
-        SD_CNT(8 * l + 8);
-        occ[i].y = l;
-        atomicAdd(&sh.cnt[l], 1);
+    const bool in_lds = m <= OCC_LDS_SORT;
+    // How far each occurrence extends to the left together with the context's own tail: one
+    // occurrence per wave and trip, lane k compares the k-th token before both ends.
+    {
+        const int wave = uni((int32_t)(tid >> 6)), nw = nthr >> 6;
+        int32_t tl = 0;
+        if (m > 0 && lane < p.P && lane < t) tl = x[t - 1 - lane];
+        for (int i = wave; i < m; i += nw) {
+            const int e = uni(in_lds ? s_sort[i].x : occ[i].x);
+            const int lim = e + 1 < p.P ? e + 1 : p.P;
+            int32_t v = 0;
+            if (lane < lim) v = x[e - lane];
+            if (lane < lim) SD_CNT(8);
+            const uint64_t mis = __ballot(lane >= 1 && lane < lim && v != tl);
+            const int l = mis ? __ffsll((unsigned long long)mis) - 1 : lim;
+            if (lane == 0) {
+                if (in_lds) s_sort[i].y = l;
+                else occ[i].y = l;
+                atomicAdd(&sh.cnt[l], 1);
+                SD_CNT(8);
+            }
+        }
     }
     __syncthreads();
     if (tid == 0) {  // nothing below reads cnt before the closing barrier
@@ -193,12 +212,10 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
         }
         sh.cnt[0] = m;
     }
-    if (m > 1) {
+    if (m > 0) {
         const int depth = p.D - 1;
-        if (m <= OCC_LDS_SORT) {
-            for (int i = tid; i < m; i += nthr) s_sort[i] = occ[i];
-            __syncthreads();
-            occ_sort<STATS>(s_sort, m, x, depth, nb);
+        if (in_lds) {
+            if (m > 1) occ_sort<STATS>(s_sort, m, x, depth, nb);
             for (int i = tid; i < m; i += nthr) occ[i] = s_sort[i];
         } else {
             occ_sort<STATS>(occ, m, x, depth, nb);
