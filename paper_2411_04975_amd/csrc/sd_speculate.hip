@@ -125,28 +125,39 @@ struct WgShared {
 // tokens before it agree with the context's tail, capped at P), sorted by what follows them.
 // The occurrences with L >= p, in that order, are the sorted suffix list below the pattern of
 // length p.  Ends with a workgroup barrier.
-template <bool STATS>
+// `between` runs after the first round of scan loads has been issued and before their results
+// are looked at: independent work (the global matches) that hides behind them.
+template <bool STATS, class Between>
 __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, int t, const int32_t *__restrict__ x,
-                                    int2 *s_sort, WgShared &sh, unsigned &nb) {
+                                    int2 *s_sort, WgShared &sh, unsigned &nb, Between between) {
     const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
     int2 *occ = p.occ + (int64_t)b * p.max_ctx;
     if (tid == 0) { sh.m = 0; sh.next = 0; }
     if (tid < 72) sh.cnt[tid] = 0;
+    // Coalesced scan, 16 bytes per load, four loads in flight per thread.  Tokens past the
+    // context end are end markers, which never equal the last token, so the tail needs no
+    // bounds test; rows start 256-byte aligned.
+    const int4 *x4 = reinterpret_cast<const int4 *>(x);
+    const int nq = t > 0 ? (t + 3) >> 2 : 0;
+    int4 v[4];
+#pragma unroll
+    for (int k = 0; k < 4; k++) {
+        int q = k * nthr + tid;
+        v[k] = q < nq ? x4[q] : make_int4(-1, -1, -1, -1);
+        if (q < nq) SD_CNT(16);
+    }
+    const int32_t last = t > 0 ? x[t - 1] : 0;
+    between();
     __syncthreads();
     if (t > 0) {
-        // Coalesced scan, 16 bytes per load, four loads in flight per thread.  Tokens past the
-        // context end are end markers, which never equal the last token, so the tail needs no
-        // bounds test; rows start 256-byte aligned.
-        const int32_t last = x[t - 1];
-        const int4 *x4 = reinterpret_cast<const int4 *>(x);
-        const int nq = (t + 3) >> 2;
         for (int q0 = 0; q0 < nq; q0 += 4 * nthr) {
-            int4 v[4];
+            if (q0 > 0) {
 #pragma unroll
-            for (int k = 0; k < 4; k++) {
-                int q = q0 + k * nthr + tid;
-                v[k] = q < nq ? x4[q] : make_int4(-1, -1, -1, -1);
-                if (q < nq) SD_CNT(16);
+                for (int k = 0; k < 4; k++) {
+                    int q = q0 + k * nthr + tid;
+                    v[k] = q < nq ? x4[q] : make_int4(-1, -1, -1, -1);
+                    if (q < nq) SD_CNT(16);
+                }
             }
 #pragma unroll
             for (int k = 0; k < 4; k++) {
@@ -1030,7 +1041,20 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
     const int t = slot_ok ? uni(p.r_len[slot]) : 0;
     const int32_t *x = p.r_text + (int64_t)(slot_ok ? slot : 0) * p.r_stride;
 
-    request_occurrences<STATS>(p, b, t, x, reinterpret_cast<int2 *>(smem), sh, nb);
+    // MatchPattern on the global index for every pattern length, spread over the waves, runs
+    // while the first loads of the context scan are in flight
+    const int P = p.P;
+    request_occurrences<STATS>(p, b, t, x, reinterpret_cast<int2 *>(smem), sh, nb, [&]() {
+        for (int pl = 1 + wave; pl <= P; pl += nw) {
+            int32_t lo = 0, hi = 0;
+            if (pl <= t && p.g_N > 0) {
+                const int32_t wk = lane < pl ? x[t - pl + lane] : 0;  // lane k: pattern token k
+                if (lane < pl) SD_CNT(4);
+                match_global<STATS>(p, wk, pl, lo, hi, nb);
+            }
+            if (lane == 0) { sh.g_lo[pl] = lo; sh.g_hi[pl] = hi; }
+        }
+    });
 
     // per-wave LDS: frontier (score, tok, par, lo, hi, dep), two trees (score, tok, par), staging
     const int cap = p.max_nodes;
@@ -1044,19 +1068,6 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
     Stage sg;
     sg.pos = tpr1 + cap; sg.cb = sg.pos + 64; sg.tc = sg.cb + 64; sg.tmp = sg.tc + TC_TOKENS;
     f.n = 0; f.cap = 0;
-
-    // MatchPattern on the global index for every pattern length, spread over the waves
-    const int P = p.P;
-    for (int pl = 1 + wave; pl <= P; pl += nw) {
-        int32_t lo = 0, hi = 0;
-        if (pl <= t && p.g_N > 0) {
-            const int32_t wk = lane < pl ? x[t - pl + lane] : 0;  // lane k: pattern token k
-            if (lane < pl) SD_CNT(4);
-            match_global<STATS>(p, wk, pl, lo, hi, nb);
-        }
-        if (lane == 0) { sh.g_lo[pl] = lo; sh.g_hi[pl] = hi; }
-    }
-    __syncthreads();
 
     // Pattern lengths with the same number of occurrences in an index have the same
     // occurrences (the longer pattern's are among the shorter one's), hence the same subtree
