@@ -195,7 +195,7 @@ def main():
         build_requests()
         d_pos.zero_()
 
-    # The step is launch-bound from Python (nine launches of a few microseconds each), so the
+    # The step is launch-bound from Python (five launches of a few microseconds each), so the
     # timed loop replays a HIP graph captured from one step: the same kernels, enqueued by the
     # same C-ABI calls.  --no-graph times host-side enqueueing instead.
     for _ in range(W):
@@ -300,12 +300,12 @@ def main():
     cnt = sd.sd_debug_profile_read(ctx)
     sd.sd_debug_profile(ctx, 0)
 
-    exp_ms = prof["expand"]["ms"] / max(prof["expand"]["launches"], 1)
-    exp_bytes = cnt["expand"]["algo_bytes"] / max(cnt["expand"]["launches"], 1)
+    exp_ms = prof["speculate"]["ms"] / max(prof["speculate"]["launches"], 1)
+    exp_bytes = cnt["speculate"]["algo_bytes"] / max(cnt["speculate"]["launches"], 1)
     achieved = exp_bytes / (exp_ms * 1e-3) / 1e9 if exp_ms > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": "k_expand", "achieved": achieved, "peak": HBM_PEAK_GBS,
+    roofline = {"bound": "hbm", "kernel": "k_speculate", "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": _traffic_from_profiles("k_expand", w.name),
+                "traffic": _traffic_from_profiles("k_speculate", w.name),
                 "algo_bytes_per_launch": exp_bytes, "avg_launch_ms": exp_ms,
                 "achievable": achievable_gbs, "frac_of_achievable": achieved / achievable_gbs}
     N = n_tokens + n_docs

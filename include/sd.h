@@ -180,15 +180,14 @@ sd_status sd_get_stats(sd_ctx *ctx, sd_stats *host_out);
 /* Measurement hooks.  With profiling on, every kernel launch of the library is
  * bracketed by HIP events on the caller's stream (at most SD_PROF_MAX_SPANS
  * launches are kept between two reads).  mode 0 = off, 1 = time kernels,
- * 2 = time kernels and run the counting variants of the speculation kernels,
- * which add up the bytes the algorithm asks for (suffix-array words, text
- * tokens, occurrence records, emitted nodes).  sd_debug_profile_read
+ * 2 = time kernels and run the counting variant of the speculation kernel,
+ * which adds up the bytes the algorithm asks for (context tokens scanned,
+ * suffix-array words, text tokens, occurrence records, emitted nodes).  sd_debug_profile_read
  * synchronises, reports per-kernel launch counts, total milliseconds and
  * counted bytes since the previous read, and clears them. */
 enum {
-    SD_K_OCCURRENCES = 0, SD_K_EXPAND = 1, SD_K_SELECT = 2, SD_K_ACCEPT = 3, SD_K_APPEND = 4,
-    SD_K_REQ_BUILD = 5, SD_K_SORT_HIST = 6, SD_K_SORT_SCAN = 7, SD_K_SORT_SCATTER = 8,
-    SD_K_BUILD_OTHER = 9, SD_K_EXPAND_REQ = 10, SD_K_COUNT = 11
+    SD_K_SPECULATE = 0, SD_K_ACCEPT = 1, SD_K_APPEND = 2, SD_K_REQ_BUILD = 3, SD_K_SORT_HIST = 4,
+    SD_K_SORT_SCAN = 5, SD_K_SORT_SCATTER = 6, SD_K_BUILD_OTHER = 7, SD_K_COUNT = 8
 };
 #define SD_PROF_MAX_SPANS 8192
 typedef struct {
@@ -201,8 +200,10 @@ sd_status sd_debug_profile_read(sd_ctx *ctx, sd_profile *host_out);
 
 /* Latency profile: after an sd_speculate call made with profiling mode 2, copies four
  * wall-clock marks per (request, index, p) unit -- ticks since the unit started at the end of
- * its set-up, of MatchPattern, of the first child enumeration, and of the whole unit; unit
+ * its set-up, of reading its match, of the first child enumeration, and of the whole unit; unit
  * index = (b * 2 + index) * P + (p - 1), `count` = 4 * units -- and the tick rate in kHz.
+ * Only units that were expanded are written (a pattern length whose tree is known from a
+ * longer pattern of the same request is not); the others keep what the buffer held.
  * Synchronises. */
 sd_status sd_debug_read_unit_ticks(sd_ctx *ctx, uint32_t *h_ticks, int64_t count, int32_t *khz);
 

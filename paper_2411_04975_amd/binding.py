@@ -52,13 +52,13 @@ class _Stats(C.Structure):
                 ("index_bytes", C.c_int64), ("scratch_bytes", C.c_int64)]
 
 
-KERNEL_NAMES = ["occurrences", "expand", "select", "accept", "append", "req_build", "sort_hist",
-                "sort_scan", "sort_scatter", "build_other", "expand_req"]
+KERNEL_NAMES = ["speculate", "accept", "append", "req_build", "sort_hist", "sort_scan",
+                "sort_scatter", "build_other"]
 
 
 class _Profile(C.Structure):
-    _fields_ = [("launches", C.c_int64 * 11), ("ms", C.c_double * 11),
-                ("algo_bytes", C.c_int64 * 11)]
+    _fields_ = [("launches", C.c_int64 * len(KERNEL_NAMES)), ("ms", C.c_double * len(KERNEL_NAMES)),
+                ("algo_bytes", C.c_int64 * len(KERNEL_NAMES))]
 
 
 _lib = None

@@ -1161,7 +1161,7 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
             SD_CNT(24);
         }
     }
-    flush_count<STATS>(nb, p.algo_bytes + SD_K_EXPAND);
+    flush_count<STATS>(nb, p.algo_bytes + SD_K_SPECULATE);
 }
 
 // Greedy verification walk, one wavefront per request, without walking: a node is "good" if
@@ -1303,7 +1303,7 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     if (lds < OCC_LDS_SORT * sizeof(int2)) lds = OCC_LDS_SORT * sizeof(int2);
     if (lds > c->lds_optin) return SD_ERR_CAPACITY;
     {
-        sd_span sp(c, SD_K_EXPAND, st);
+        sd_span sp(c, SD_K_SPECULATE, st);
         if (stats) hipLaunchKernelGGL(k_speculate<true>, dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
         else hipLaunchKernelGGL(k_speculate<false>, dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
     }
