@@ -346,6 +346,30 @@ def main():
         "roofline": roofline, "roofline_build": roofline_build,
         "index_bytes": stats["index_bytes"], "scratch_bytes": stats["scratch_bytes"],
     }
+    # ---- online insertion: the outputs of one batch (B documents of max_nodes + 1 tokens) are
+    # added to the global index; done last because it grows the index.  The context was sized
+    # for the corpus alone, so a second context with room for the insertions does this leg.
+    ins_docs, ins_len, ins_reps = B, mn + 1, 3
+    ctx2 = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, 1, 64,
+                        n_tokens + n_docs + ins_reps * ins_docs * (ins_len + 1), 0)
+    sd.sd_index_build(ctx2, sd.SD_SCOPE_GLOBAL, None, d_corpus, d_doc_off, n_tokens)
+    d_ins = d_future[:, :ins_len * ins_reps].contiguous()
+    d_ins_off = torch.arange(0, (ins_docs + 1) * ins_len, ins_len, dtype=torch.int64, device=dev)
+    ins_ms = []
+    for r in range(ins_reps):
+        chunk = d_ins[:, r * ins_len:(r + 1) * ins_len].contiguous().reshape(-1)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        sd.sd_index_insert(ctx2, chunk, d_ins_off, ins_docs * ins_len)
+        e1.record()
+        torch.cuda.synchronize()
+        ins_ms.append(e0.elapsed_time(e1))
+    ins_ms.sort()
+    out["index_insert"] = {"documents": ins_docs, "tokens": ins_docs * ins_len,
+                           "ms_median": ins_ms[len(ins_ms) // 2],
+                           "tokens_per_s": ins_docs * ins_len / (ins_ms[len(ins_ms) // 2] * 1e-3)}
+    sd.sd_destroy(ctx2)
     sd.sd_destroy(ctx)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, n_requests=min(16, B), build_tokens=300_000)

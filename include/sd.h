@@ -145,6 +145,21 @@ sd_status sd_index_build(sd_ctx *ctx, sd_scope scope, const int32_t *d_slot_ids,
                          const int32_t *d_tokens, const int64_t *d_seq_offsets, int32_t n_seq,
                          int64_t n_tokens, void *hip_stream);
 
+/* Online insertion of finished outputs into the global index (Section 3: the
+ * global structure is built offline or "updated online" from finished
+ * requests; Appendix, "Effect of input distribution shift").  The n_seq
+ * sequences (same layout and ownership as for sd_index_build: device tokens,
+ * int64 device offsets, n_tokens = offsets[n_seq] given by the host) are added
+ * as new documents.  Afterwards the global index holds exactly what
+ * sd_index_build over the old and the new documents together would hold.
+ * Cost: a sort of the new tokens plus one pass over the old index.
+ * Total positions (tokens + documents) may not exceed max_global_tokens
+ * (SD_ERR_CAPACITY; nothing is enqueued).  Like sd_index_build(GLOBAL), the
+ * call changes sizes and buffers that later sd_speculate calls read on the
+ * host side: work captured into a HIP graph before it must be captured anew. */
+sd_status sd_index_insert(sd_ctx *ctx, const int32_t *d_tokens, const int64_t *d_seq_offsets,
+                          int32_t n_seq, int64_t n_tokens, void *hip_stream);
+
 /* Extend the contexts of n_slots distinct slots: slot d_slot_ids[i] receives
  * d_new_tokens[d_new_offsets[i] .. d_new_offsets[i+1]) (int32 offsets, device).
  * Afterwards the per-request index equals the one a fresh build over the longer
@@ -187,7 +202,8 @@ sd_status sd_get_stats(sd_ctx *ctx, sd_stats *host_out);
  * counted bytes since the previous read, and clears them. */
 enum {
     SD_K_SPECULATE = 0, SD_K_ACCEPT = 1, SD_K_APPEND = 2, SD_K_REQ_BUILD = 3, SD_K_SORT_HIST = 4,
-    SD_K_SORT_SCAN = 5, SD_K_SORT_SCATTER = 6, SD_K_BUILD_OTHER = 7, SD_K_COUNT = 8
+    SD_K_SORT_SCAN = 5, SD_K_SORT_SCATTER = 6, SD_K_BUILD_OTHER = 7, SD_K_INSERT = 8,
+    SD_K_COUNT = 9
 };
 #define SD_PROF_MAX_SPANS 8192
 typedef struct {

@@ -53,7 +53,7 @@ class _Stats(C.Structure):
 
 
 KERNEL_NAMES = ["speculate", "accept", "append", "req_build", "sort_hist", "sort_scan",
-                "sort_scatter", "build_other"]
+                "sort_scatter", "build_other", "insert"]
 
 
 class _Profile(C.Structure):
@@ -85,6 +85,8 @@ def _load():
     L.sd_last_error.argtypes = [vp]
     L.sd_index_build.restype = C.c_int
     L.sd_index_build.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int32, C.c_int64, vp]
+    L.sd_index_insert.restype = C.c_int
+    L.sd_index_insert.argtypes = [vp, vp, vp, C.c_int32, C.c_int64, vp]
     L.sd_index_append.restype = C.c_int
     L.sd_index_append.argtypes = [vp, vp, vp, vp, C.c_int32, vp]
     L.sd_speculate.restype = C.c_int
@@ -202,6 +204,19 @@ def sd_index_build(ctx: _Ctx, scope: int, slot_ids: Optional[torch.Tensor], toke
         ctx.handle, scope,
         _ptr(slot_ids, torch.int32, ctx, n_seq if scope == SD_SCOPE_REQUESTS else 0, "slot_ids"),
         _ptr(tokens, torch.int32, ctx, n_tokens, "tokens"),
+        _ptr(seq_offsets, torch.int64, ctx, n_seq + 1, "seq_offsets"), n_seq, n_tokens,
+        _stream(stream, ctx))
+    _check(ctx, code)
+
+
+def sd_index_insert(ctx: _Ctx, tokens: torch.Tensor, seq_offsets: torch.Tensor, n_tokens: int,
+                    stream=None) -> None:
+    """Adds documents to the global index; `n_tokens` = seq_offsets[-1], known to the caller."""
+    n_seq = int(seq_offsets.numel()) - 1
+    if n_seq < 0:
+        raise ValueError("seq_offsets needs at least one entry")
+    code = _load().sd_index_insert(
+        ctx.handle, _ptr(tokens, torch.int32, ctx, n_tokens, "tokens"),
         _ptr(seq_offsets, torch.int64, ctx, n_seq + 1, "seq_offsets"), n_seq, n_tokens,
         _stream(stream, ctx))
     _check(ctx, code)

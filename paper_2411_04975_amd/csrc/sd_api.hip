@@ -86,11 +86,12 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     bool ok = true;
     int64_t *ib = &c->index_bytes, *sb = &c->scratch_bytes;
     ok = ok && dev_alloc(&c->g_text, cap + SD_TEXT_PAD + 64, ib);
-    ok = ok && dev_alloc(&c->g_sa, cap, ib);
-    ok = ok && dev_alloc(&c->g_tok1, cap, ib);
+    // g_sa / g_tok1 change places with build scratch buffers on insertion: same sizes as those
+    ok = ok && dev_alloc(&c->g_sa, cap + 64, ib);
+    ok = ok && dev_alloc(&c->g_tok1, cap + 64, ib);
     ok = ok && dev_alloc(&c->g_bucket, (int64_t)cfg->vocab + 2, ib);
     ok = ok && dev_alloc(&c->b_keys[0], cap, sb) && dev_alloc(&c->b_keys[1], cap, sb);
-    ok = ok && dev_alloc(&c->b_vals[0], cap, sb) && dev_alloc(&c->b_vals[1], cap, sb);
+    ok = ok && dev_alloc(&c->b_vals[0], cap + 64, sb) && dev_alloc(&c->b_vals[1], cap + 64, sb);
     ok = ok && dev_alloc(&c->b_rank, cap + 64, sb) && dev_alloc(&c->b_flags, cap, sb);
     ok = ok && dev_alloc(&c->b_hist, c->b_hist_cap, sb);
     ok = ok && dev_alloc(&c->b_partials, c->b_partials_cap, sb);
@@ -157,6 +158,19 @@ sd_status sd_index_build(sd_ctx *c, sd_scope scope, const int32_t *d_slot_ids,
         return sd_build_requests_impl(c, d_slot_ids, d_tokens, d_seq_offsets, n_seq, st);
     }
     return fail(c, SD_ERR_INVALID_ARG, "unknown scope");
+}
+
+sd_status sd_index_insert(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_seq_offsets,
+                          int32_t n_seq, int64_t n_tokens, void *hip_stream) {
+    if (!c) return SD_ERR_INVALID_ARG;
+    if (n_seq < 0 || n_tokens < 0) return fail(c, SD_ERR_INVALID_ARG, "negative size");
+    if (!d_seq_offsets) return fail(c, SD_ERR_INVALID_ARG, "d_seq_offsets is null");
+    if (n_tokens > 0 && !d_tokens) return fail(c, SD_ERR_INVALID_ARG, "d_tokens is null");
+    if (c->g_N + n_tokens + (int64_t)n_seq > c->g_cap)
+        return fail(c, SD_ERR_CAPACITY, "corpus exceeds max_global_tokens");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
+    return sd_insert_global_impl(c, d_tokens, d_seq_offsets, n_seq, n_tokens,
+                                 (hipStream_t)hip_stream);
 }
 
 sd_status sd_index_append(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_new_tokens,

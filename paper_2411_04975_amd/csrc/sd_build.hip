@@ -119,6 +119,67 @@ __global__ __launch_bounds__(TB) void k_bucket(const int32_t *__restrict__ text,
     bucket[c] = (int32_t)lo;
 }
 
+// ---- online insertion into the global index -------------------------------------------------
+// New documents are laid out behind the old text and sorted among themselves (the same prefix
+// doubling, over the new part only).  Each new suffix is then ranked in the old suffix array by
+// comparing up to D tokens (end marker lowest; a new suffix goes behind old ones it ties with),
+// and old and new entries are merged into a second buffer in one pass: old entry i moves up
+// by the number of new suffixes ranked at or before it, new entry j lands at rank_j + j.
+
+// rank[j] = number of old suffixes that sort before, or tie with, new suffix j
+__global__ __launch_bounds__(TB) void k_insert_rank(const int32_t *__restrict__ text,
+                                                    const int32_t *__restrict__ sa, int64_t N,
+                                                    const int32_t *__restrict__ bucket,
+                                                    const uint32_t *__restrict__ dsa, int64_t M,
+                                                    int64_t base, int32_t D,
+                                                    uint32_t *__restrict__ rank) {
+    int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (j >= M) return;
+    const int32_t *w = text + base + dsa[j];
+    const int32_t c0 = w[0] + 1;  // token code, 0 for the end marker
+    int64_t lo = bucket[c0], hi = bucket[c0 + 1];  // old suffixes with the same first token
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        const int32_t *v = text + sa[mid];
+        int cmp = 0;  // sign of (old suffix - new suffix) on the first D tokens
+        for (int k = 0; k < D; k++) {
+            const int32_t a = v[k], b = w[k];
+            if (a != b) { cmp = a < b ? -1 : 1; break; }
+            if (a == SD_END_TOKEN) break;
+        }
+        if (cmp <= 0) lo = mid + 1; else hi = mid;
+    }
+    rank[j] = (uint32_t)lo;
+}
+
+__global__ __launch_bounds__(TB) void k_insert_merge_old(const int32_t *__restrict__ sa,
+                                                         const int32_t *__restrict__ tok1, int64_t N,
+                                                         const uint32_t *__restrict__ rank, int64_t M,
+                                                         int32_t *__restrict__ sa_out,
+                                                         int32_t *__restrict__ tok1_out) {
+    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (i >= N) return;
+    int64_t lo = 0, hi = M;  // number of new suffixes with rank <= i
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)rank[mid] <= i) lo = mid + 1; else hi = mid;
+    }
+    sa_out[i + lo] = sa[i];
+    tok1_out[i + lo] = tok1[i];
+}
+
+__global__ __launch_bounds__(TB) void k_insert_merge_new(const int32_t *__restrict__ text,
+                                                         const uint32_t *__restrict__ dsa,
+                                                         const uint32_t *__restrict__ rank, int64_t M,
+                                                         int64_t base, int32_t *__restrict__ sa_out,
+                                                         int32_t *__restrict__ tok1_out) {
+    int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (j >= M) return;
+    const int64_t pos = base + dsa[j];
+    sa_out[(int64_t)rank[j] + j] = (int32_t)pos;
+    tok1_out[(int64_t)rank[j] + j] = text[pos + 1];
+}
+
 __global__ __launch_bounds__(TB) void k_fill_i32(int32_t *p, int64_t n, int32_t v) {
     int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
     if (i < n) p[i] = v;
@@ -194,6 +255,27 @@ inline unsigned nblk(int64_t n) { return (unsigned)((n + TB - 1) / TB); }
 
 }  // namespace
 
+// Sorts the N positions of `text` (documents with an end marker after each, padding behind)
+// by their suffixes, compared on at least D tokens.  Returns which of b_vals[0/1] holds the
+// sorted positions.
+static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, hipStream_t st) {
+    const int tok_bits = sd_bits_for((uint64_t)c->cfg.vocab);  // codes 0..vocab
+    SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_init_keys, dim3(nblk(N)), dim3(TB), 0, text, N, tok_bits, c->b_keys[0], c->b_vals[0]);
+    int cur = sd_sort_pairs(c, N, 2 * tok_bits, 0, st);
+    const int rank_bits = sd_bits_for((uint64_t)N);  // ranks 0..N
+    int64_t h = 2;
+    for (;;) {
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_group_flags, dim3(nblk(N)), dim3(TB), 0, c->b_keys[cur], N, c->b_flags);
+        sd_scan_inclusive_u32(c, c->b_flags, N, st);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_assign_rank, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_flags, N, c->b_rank);
+        if (h >= c->cfg.D) break;
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_flags, c->b_rank, N, h, rank_bits, c->b_keys[cur]);
+        cur = sd_sort_pairs(c, N, 2 * rank_bits, cur, st);
+        h *= 2;
+    }
+    return cur;
+}
+
 sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
                                int32_t n_seq, int64_t n_tokens, hipStream_t st) {
     const int64_t N = n_tokens + n_seq;
@@ -208,24 +290,46 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_layout_marks, dim3(nblk(m)), dim3(TB), 0, d_offsets, n_seq, N, c->g_text);
     }
     if (N > 0) {
-        const int tok_bits = sd_bits_for((uint64_t)vocab);  // codes 0..vocab
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_init_keys, dim3(nblk(N)), dim3(TB), 0, c->g_text, N, tok_bits, c->b_keys[0], c->b_vals[0]);
-        int cur = sd_sort_pairs(c, N, 2 * tok_bits, 0, st);
-        const int rank_bits = sd_bits_for((uint64_t)N);  // ranks 0..N
-        int64_t h = 2;
-        for (;;) {
-            SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_group_flags, dim3(nblk(N)), dim3(TB), 0, c->b_keys[cur], N, c->b_flags);
-            sd_scan_inclusive_u32(c, c->b_flags, N, st);
-            SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_assign_rank, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_flags, N, c->b_rank);
-            if (h >= c->cfg.D) break;
-            SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_flags, c->b_rank, N, h, rank_bits, c->b_keys[cur]);
-            cur = sd_sort_pairs(c, N, 2 * rank_bits, cur, st);
-            h *= 2;
-        }
+        const int cur = build_sorted_positions(c, c->g_text, N, st);
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_finish_sa, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur],
                   c->g_text, N, c->g_sa, c->g_tok1);
     }
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, N, vocab, c->g_bucket);
+    return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+// Online insertion (Section 3: the global tree "can be ... updated online" with finished
+// outputs; Appendix, "Effect of input distribution shift").  Afterwards the index holds
+// exactly what a build over the old and the new documents together would hold.
+sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
+                                int32_t n_seq, int64_t n_tokens, hipStream_t st) {
+    const int64_t N = c->g_N, M = n_tokens + n_seq;
+    const int32_t vocab = c->cfg.vocab;
+    if (M == 0) return SD_OK;
+    int32_t *ntext = c->g_text + N;
+    if (n_tokens > 0)
+        SD_LAUNCH(c, SD_K_INSERT, st, k_layout_text, dim3(nblk(n_tokens)), dim3(TB), 0, d_tokens, d_offsets, n_seq, n_tokens, ntext, vocab, c->d_err);
+    {
+        int64_t m = n_seq > SD_TEXT_PAD ? n_seq : SD_TEXT_PAD;
+        SD_LAUNCH(c, SD_K_INSERT, st, k_layout_marks, dim3(nblk(m)), dim3(TB), 0, d_offsets, n_seq, M, ntext);
+    }
+    const int cur = build_sorted_positions(c, ntext, M, st);
+    // b_vals[cur]: new positions in order; b_flags: their ranks in the old array; merged arrays
+    // go to b_vals[1 - cur] and b_rank, which then change places with g_sa and g_tok1
+    uint32_t *dsa = c->b_vals[cur], *rank = c->b_flags;
+    int32_t *sa_out = (int32_t *)c->b_vals[1 - cur], *tok1_out = (int32_t *)c->b_rank;
+    SD_LAUNCH(c, SD_K_INSERT, st, k_insert_rank, dim3(nblk(M)), dim3(TB), 0, c->g_text, c->g_sa, N, c->g_bucket, dsa, M, N, c->cfg.D, rank);
+    if (N > 0)
+        SD_LAUNCH(c, SD_K_INSERT, st, k_insert_merge_old, dim3(nblk(N)), dim3(TB), 0, c->g_sa, c->g_tok1, N, rank, M, sa_out, tok1_out);
+    SD_LAUNCH(c, SD_K_INSERT, st, k_insert_merge_new, dim3(nblk(M)), dim3(TB), 0, c->g_text, dsa, rank, M, N, sa_out, tok1_out);
+    c->b_vals[1 - cur] = (uint32_t *)c->g_sa;
+    c->b_rank = (uint32_t *)c->g_tok1;
+    c->g_sa = sa_out;
+    c->g_tok1 = tok1_out;
+    c->g_N = N + M;
+    c->g_tokens += n_tokens;
+    c->g_docs += n_seq;
+    SD_LAUNCH(c, SD_K_INSERT, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, c->g_N, vocab, c->g_bucket);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 

@@ -74,6 +74,8 @@ void sd_scan_inclusive_u32(sd_ctx *c, uint32_t *data, int64_t n, hipStream_t st)
 
 sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
                                int32_t n_seq, int64_t n_tokens, hipStream_t st);
+sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
+                                int32_t n_seq, int64_t n_tokens, hipStream_t st);
 sd_status sd_build_requests_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_tokens,
                                  const int64_t *d_offsets, int32_t n_seq, hipStream_t st);
 sd_status sd_append_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_new_tokens,

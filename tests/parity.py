@@ -83,6 +83,10 @@ class GpuPath:
         d_tok, d_off, n = self._seqs(docs)
         self.sd.sd_index_build(self.ctx, self.sd.SD_SCOPE_GLOBAL, None, d_tok, d_off, n)
 
+    def insert_global(self, docs):
+        d_tok, d_off, n = self._seqs(docs)
+        self.sd.sd_index_insert(self.ctx, d_tok, d_off, n)
+
     def build_requests(self, slots, contexts):
         d_tok, d_off, n = self._seqs(contexts)
         d_slots = self.torch.tensor(list(slots), dtype=self.torch.int32, device=self.dev)

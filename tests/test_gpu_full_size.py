@@ -73,6 +73,37 @@ def _run_full(name, sample, seed=0):
         g.close()
 
 
+def test_large_insert_then_speculate_sampled():
+    """Headline corpus built from 95% of its documents, the rest inserted online in two batches
+    (about 250k tokens each): sampled requests against the oracle trie over all documents."""
+    w = make_workload("large", seed=0)
+    docs = w.docs()
+    B = w.batch
+    contexts = [w.contexts[b] for b in range(B)]
+    n0 = int(len(docs) * 0.95)
+    n1 = n0 + (len(docs) - n0) // 2
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, w.ctx_len + 128,
+                       len(w.corpus) + len(docs))
+    try:
+        g.build_global(docs[:n0])
+        g.build_requests(range(B), contexts)
+        g.insert_global(docs[n0:n1])
+        g.insert_global(docs[n1:])
+        got = g.speculate(range(B))
+        st = g.stats()
+        assert st["err_bad_token"] == 0 and st["err_bad_slot"] == 0
+        _check_properties(got, w)
+        rng = np.random.default_rng(4)
+        pick = sorted(rng.choice(B, size=16, replace=False).tolist())
+        sub = [contexts[b] for b in pick]
+        tg = parity.oracle_global_trie(docs, w.D, w.vocab, sub, w.P)
+        want = parity.oracle_speculate_batch(tg, sub, w.D, w.P, w.alpha, w.min_score, w.max_nodes)
+        bad = parity.compare_trees({k: v[pick] for k, v in got.items()}, want, "large+insert")
+        assert not bad, "\n".join(bad)
+    finally:
+        g.close()
+
+
 def test_agentic_full():
     got, want = _run_full("agentic", sample=64)
     assert (got["n_nodes"] > 0).mean() > 0.5

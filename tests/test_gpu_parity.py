@@ -415,3 +415,84 @@ def test_variants_on_adversarial_minis(den_mode, linear):
             assert not bad, "\n".join(bad)
         finally:
             g.close()
+
+
+# ---- online insertion into the global index -------------------------------------------------
+def _sorted_on_D(text, sa, D):
+    N = len(sa)
+    pad = np.concatenate([text, np.full(D, -1, np.int32)])
+    keys = np.stack([pad[sa + k] for k in range(D)], axis=1).astype(np.int64)
+    ended = np.cumsum(keys == -1, axis=1) > 0
+    keys[ended] = -1
+    a, b = keys[:-1], keys[1:]
+    diff = a != b
+    first = diff.argmax(axis=1)
+    rows = np.arange(N - 1)
+    return bool((~diff.any(axis=1) | (a[rows, first] < b[rows, first])).all()), keys
+
+
+def test_insert_equals_build_over_all_documents(tiny_workload):
+    """Documents inserted in uneven batches (one of them empty, one with an empty document):
+    afterwards text, suffix-array order, interval widths and speculation results are those of one
+    build over all documents, and of the oracle trie that received the same documents."""
+    w = tiny_workload
+    import paper_2411_04975_amd as sd
+    docs = [np.asarray(d, np.int32) for d in w.docs()]
+    docs.insert(7, np.zeros(0, np.int32))
+    N = sum(len(d) for d in docs) + len(docs)
+    cuts = [0, 5, 5, 6, 20, len(docs)]
+    contexts = [w.contexts[i] for i in range(w.batch)]
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, w.batch, w.ctx_len + 8, N)
+    h = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, w.batch, w.ctx_len + 8, N)
+    try:
+        g.build_requests(range(w.batch), contexts)
+        h.build_requests(range(w.batch), contexts)
+        tg = oracle.Trie(w.D)
+        for a, b in zip(cuts[:-1], cuts[1:]):
+            if a == 0:
+                g.build_global(docs[a:b])
+            else:
+                g.insert_global(docs[a:b])
+            for d in docs[a:b]:
+                tg.add_doc(d)
+            got = g.speculate(range(w.batch))
+            want = parity.oracle_speculate_batch(tg, contexts, w.D, w.P, w.alpha, w.min_score,
+                                                 g.max_nodes)
+            bad = parity.compare_trees(got, want, "after documents [%d, %d)" % (a, b))
+            assert not bad, "\n".join(bad)
+        text, sa = sd.sd_debug_read_global(g.ctx)
+        h.build_global(docs)
+        text2, sa2 = sd.sd_debug_read_global(h.ctx)
+        st = g.stats()
+    finally:
+        g.close()
+        h.close()
+    assert st["err_bad_token"] == 0
+    assert len(sa) == N and np.array_equal(np.sort(sa), np.arange(N))
+    assert np.array_equal(text, text2)
+    ok, keys = _sorted_on_D(text, sa, w.D)
+    assert ok
+    ok2, keys2 = _sorted_on_D(text2, sa2, w.D)
+    assert ok2 and np.array_equal(keys, keys2)   # same D-token key at every rank
+
+
+def test_insert_into_empty_index_and_capacity():
+    import paper_2411_04975_amd as sd
+    docs = [np.array([3, 1, 4, 1, 5, 9, 2, 6, 5, 3, 5], np.int32), np.array([1, 5, 9, 2], np.int32)]
+    ctxs = [np.array([4, 1, 5], np.int32), np.array([9, 2], np.int32)]
+    g = parity.GpuPath(10, 8, 4, 2.0, 0.05, 2, 32, 40)
+    try:
+        g.build_requests(range(2), ctxs)
+        g.insert_global(docs[:1])                    # nothing built before
+        g.insert_global([])                           # no documents: no change
+        g.insert_global(docs[1:])
+        got = g.speculate(range(2))
+        tg = parity.oracle_global_trie(docs, 8, 10)
+        want = parity.oracle_speculate_batch(tg, ctxs, 8, 4, 2.0, 0.05, g.max_nodes)
+        assert not parity.compare_trees(got, want)
+        with pytest.raises(sd.SdError):               # 17 positions held, 40 allowed
+            g.insert_global([np.arange(30, dtype=np.int32) % 10])
+        got2 = g.speculate(range(2))                  # the refused call changed nothing
+        assert not parity.compare_trees(got2, want)
+    finally:
+        g.close()
