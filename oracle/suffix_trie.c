@@ -19,6 +19,8 @@
  *   - Section 2 "Speculative Decoding" item 2 and Section 4.1 "Simulated
  *     Ablations": accept drafted tokens up to the first disagreement with the
  *     target model's greedy token.
+ *   - Appendix "Predicting SuffixDecoding Effectiveness": the empirical entropy
+ *     of a tree, steps (2) and (3).
  *
  * Readings this oracle takes where the paper is silent (each is listed in the
  * design notes of the repository):
@@ -37,6 +39,10 @@
  *   - "linear" variant (caption of the baseline-comparison figure: speculation
  *     that "only allows sequential token chains"): the candidates of a step are
  *     the children of the node added last (of N_p at the start), nothing else.
+ *   - empirical entropy: a node's output distribution is COUNT(child) over the
+ *     sum of its children's COUNTs; entropy in bits; every node with a child
+ *     (the root included) is weighted by that sum, i.e. by how many times a
+ *     next token was observed below it.
  *
  * Pins: tests/test_oracle_pins.py checks this file against brute-force corpus
  * scans, closed forms and trie invariants written independently in Python.
@@ -251,6 +257,30 @@ void sdo_trie_dump(const sdo_trie *t, int32_t *token, int32_t *count, int32_t *e
     for (int64_t i = 0; i < t->n_nodes; i++)
         for (int32_t ch = t->nodes[i].first_child; ch >= 0; ch = t->nodes[ch].next_sibling)
             parent[ch] = (int32_t)i;
+}
+
+/* Empirical entropy of the tree (Appendix, "Predicting SuffixDecoding
+ * Effectiveness", steps 2 and 3): for every node with children, the entropy (in
+ * bits) of the distribution COUNT(child) / sum of the children's COUNTs;
+ * returned is the average over those nodes weighted by that sum.  *weight
+ * receives the total weight.  0 for a tree without any child. */
+double sdo_trie_entropy(const sdo_trie *t, double *weight) {
+    double acc = 0.0, wsum = 0.0;
+    for (int64_t v = 0; v < t->n_nodes; v++) {
+        double s = 0.0;
+        for (int32_t ch = t->nodes[v].first_child; ch >= 0; ch = t->nodes[ch].next_sibling)
+            s += (double)t->nodes[ch].count;
+        if (s <= 0.0) continue;
+        double h = 0.0;
+        for (int32_t ch = t->nodes[v].first_child; ch >= 0; ch = t->nodes[ch].next_sibling) {
+            const double q = (double)t->nodes[ch].count / s;
+            h -= q * log2(q);
+        }
+        acc += s * h;
+        wsum += s;
+    }
+    if (weight) *weight = wsum;
+    return wsum > 0.0 ? acc / wsum : 0.0;
 }
 
 /* MatchPattern (Algorithm 1): follow the last p tokens of x[0..tlen) from the

@@ -54,6 +54,8 @@ def _load():
     L.sdo_trie_children.restype = C.c_int64
     L.sdo_trie_children.argtypes = [vp, i32p, C.c_int, i32p, i64p, C.c_int64]
     L.sdo_trie_dump.argtypes = [vp, i32p, i32p, i32p, i32p, i32p]
+    L.sdo_trie_entropy.restype = C.c_double
+    L.sdo_trie_entropy.argtypes = [vp, f64p]
     L.sdo_match.restype = C.c_int32
     L.sdo_match.argtypes = [vp, i32p, C.c_int64, C.c_int]
     L.sdo_speculate_unit.restype = C.c_int
@@ -132,6 +134,13 @@ class Trie:
         arrs = [np.zeros(n, np.int32) for _ in range(5)]
         self._L.sdo_trie_dump(self._h, *[_p(a, C.c_int32) for a in arrs])
         return dict(token=arrs[0], count=arrs[1], ends=arrs[2], parent=arrs[3], depth=arrs[4])
+
+    def entropy(self) -> Tuple[float, float]:
+        """(weighted mean entropy in bits, total weight): Appendix, "Predicting SuffixDecoding
+        Effectiveness"."""
+        w = C.c_double()
+        h = self._L.sdo_trie_entropy(self._h, C.byref(w))
+        return float(h), float(w.value)
 
     def match(self, x, p: int) -> int:
         x = _i32(x)

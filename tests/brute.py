@@ -119,3 +119,23 @@ def accept_by_enumeration(tokens, parents, target):
             best_path = path
     last = best_path[-1] if best_path else -1
     return len(best_path), best_path, target[last + 1]
+
+
+def entropy(docs, D):
+    """Empirical entropy of the depth-bounded suffix tree over `docs` (Appendix, "Predicting
+    SuffixDecoding Effectiveness"), from substring counts alone: for every distinct substring w
+    with |w| < D (the empty one included) that is followed by some token, the entropy in bits
+    of "which token follows w", weighted by how many times something follows w.
+    Returns (weighted mean, total weight)."""
+    follow = {}
+    for doc in docs:
+        doc = [int(v) for v in doc]
+        for i in range(len(doc)):
+            for k in range(0, min(D - 1, i) + 1):   # context = the k tokens before position i
+                follow.setdefault(tuple(doc[i - k:i]), Counter())[doc[i]] += 1
+    acc = wsum = 0.0
+    for w, c in follow.items():
+        s = sum(c.values())
+        acc += s * -sum((v / s) * math.log2(v / s) for v in c.values())
+        wsum += s
+    return (acc / wsum if wsum else 0.0), wsum

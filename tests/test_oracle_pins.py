@@ -460,3 +460,67 @@ def test_linear_variant_follows_the_most_frequent_child(tiny_workload):
                 assert got[2][j] == pytest.approx(tg.lookup(path)[0] / c_root, rel=1e-14)
                 seen += 1
     assert seen > 30
+
+
+# ---- empirical entropy (Appendix, "Predicting SuffixDecoding Effectiveness") -------------------
+@pytest.mark.parametrize("seed,vocab,D,n_docs", [(0, 2, 3, 3), (1, 3, 5, 4), (2, 5, 8, 6), (3, 4, 1, 3),
+                                                 (4, 50, 6, 5)])
+def test_entropy_matches_brute_force(seed, vocab, D, n_docs):
+    rng = np.random.default_rng(100 + seed)
+    docs = _rand_docs(rng, vocab, n_docs, 1, 40)
+    docs.append(np.zeros(0, np.int32))
+    t = oracle.Trie(D)
+    for d in docs:
+        t.add_doc(d)
+    h, w = t.entropy()
+    hb, wb = brute.entropy(docs, D)
+    assert w == wb
+    assert h == pytest.approx(hb, rel=1e-12, abs=1e-15)
+
+
+def test_entropy_closed_forms():
+    # all tokens distinct: only the root is uncertain (n equally likely first tokens); every
+    # other node has one child.  weight = number of (context, next token) observations
+    n, D = 37, 6
+    t = oracle.Trie(D)
+    t.add_doc(np.arange(n, dtype=np.int32))
+    h, w = t.entropy()
+    weight = sum(n - k for k in range(D))            # contexts of length k = 0..D-1
+    assert w == weight
+    assert h == pytest.approx(n * math.log2(n) / weight, rel=1e-13)
+    # a periodic document: after one token everything is determined
+    q, reps, D = 5, 9, 4
+    t = oracle.Trie(D)
+    t.add_doc(np.tile(np.arange(q, dtype=np.int32), reps))
+    h, w = t.entropy()
+    n = q * reps
+    assert w == sum(n - k for k in range(D))
+    assert h == pytest.approx(n * math.log2(q) / w, rel=1e-13)
+    # two equally likely continuations after every context of length 1 .. D-1 built by hand:
+    # documents "a b" and "a c", D = 2: root sees a (x2), b, c; node a sees b, c
+    t = oracle.Trie(2)
+    t.add_doc(np.array([0, 1], np.int32))
+    t.add_doc(np.array([0, 2], np.int32))
+    h, w = t.entropy()
+    root = 4 * (-(0.5 * math.log2(0.5) + 2 * 0.25 * math.log2(0.25)))   # weight 4, H = 1.5
+    node_a = 2 * 1.0                                                     # weight 2, H = 1
+    assert w == 6 and h == pytest.approx((root + node_a) / 6, rel=1e-14)
+    # nothing to predict: empty corpus and single-token documents with D = 1 (root only)
+    assert oracle.Trie(3).entropy() == (0.0, 0.0)
+
+
+def test_entropy_orders_structured_below_random(tiny_workload):
+    """The use the paper makes of it: repetitive text scores lower than random text."""
+    w = tiny_workload
+    t = oracle.Trie(w.D)
+    for d in w.docs()[:10]:
+        t.add_doc(d)
+    rng = np.random.default_rng(0)
+    r = oracle.Trie(w.D)
+    for d in w.docs()[:10]:
+        r.add_doc(rng.integers(0, 64, len(d)).astype(np.int32))
+    z = oracle.Trie(w.D)
+    for d in w.docs()[:10]:
+        z.add_doc(rng.integers(0, w.vocab, len(d)).astype(np.int32))
+    assert t.entropy()[0] < r.entropy()[0]
+    assert t.entropy()[0] < z.entropy()[0]
