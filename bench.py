@@ -346,6 +346,15 @@ def main():
         "roofline": roofline, "roofline_build": roofline_build,
         "index_bytes": stats["index_bytes"], "scratch_bytes": stats["scratch_bytes"],
     }
+    # ---- empirical entropy of the global index (the paper's effectiveness predictor) -------
+    t0 = time.perf_counter()
+    ent_bits, ent_weight = sd.sd_index_entropy(ctx)
+    ent_ms = (time.perf_counter() - t0) * 1e3
+    t0 = time.perf_counter()
+    sd.sd_index_entropy(ctx)
+    ent_ms = min(ent_ms, (time.perf_counter() - t0) * 1e3)
+    out["index_entropy"] = {"mean_bits": ent_bits, "weight": ent_weight, "ms": ent_ms}
+
     # ---- online insertion: the outputs of one batch (B documents of max_nodes + 1 tokens) are
     # added to the global index; done last because it grows the index.  The context was sized
     # for the corpus alone, so a second context with room for the insertions does this leg.

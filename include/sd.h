@@ -160,6 +160,17 @@ sd_status sd_index_build(sd_ctx *ctx, sd_scope scope, const int32_t *d_slot_ids,
 sd_status sd_index_insert(sd_ctx *ctx, const int32_t *d_tokens, const int64_t *d_seq_offsets,
                           int32_t n_seq, int64_t n_tokens, void *hip_stream);
 
+/* Empirical entropy of the global index (Appendix, "Predicting SuffixDecoding
+ * Effectiveness"): for every node of the depth-bounded suffix tree that has a
+ * child (the root included), the entropy in bits of COUNT(child) / (sum of the
+ * children's COUNTs); *h_mean_bits receives the average of these weighted by
+ * that sum, *h_weight the total weight (= the number of (context, next token)
+ * observations with contexts of 0..D-1 tokens).  Both are HOST pointers.
+ * 0 / 0 for an empty index.  Enqueues its kernels on hip_stream, then
+ * synchronises that stream.  Uses build scratch: not to be overlapped with
+ * sd_index_build / sd_index_insert on another stream. */
+sd_status sd_index_entropy(sd_ctx *ctx, double *h_mean_bits, double *h_weight, void *hip_stream);
+
 /* Extend the contexts of n_slots distinct slots: slot d_slot_ids[i] receives
  * d_new_tokens[d_new_offsets[i] .. d_new_offsets[i+1]) (int32 offsets, device).
  * Afterwards the per-request index equals the one a fresh build over the longer

@@ -85,6 +85,8 @@ def _load():
     L.sd_last_error.argtypes = [vp]
     L.sd_index_build.restype = C.c_int
     L.sd_index_build.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int32, C.c_int64, vp]
+    L.sd_index_entropy.restype = C.c_int
+    L.sd_index_entropy.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_double), vp]
     L.sd_index_insert.restype = C.c_int
     L.sd_index_insert.argtypes = [vp, vp, vp, C.c_int32, C.c_int64, vp]
     L.sd_index_append.restype = C.c_int
@@ -220,6 +222,13 @@ def sd_index_insert(ctx: _Ctx, tokens: torch.Tensor, seq_offsets: torch.Tensor, 
         _ptr(seq_offsets, torch.int64, ctx, n_seq + 1, "seq_offsets"), n_seq, n_tokens,
         _stream(stream, ctx))
     _check(ctx, code)
+
+
+def sd_index_entropy(ctx: _Ctx, stream=None):
+    """(weighted mean entropy of the global index in bits, total weight).  Synchronises."""
+    h, w = C.c_double(), C.c_double()
+    _check(ctx, _load().sd_index_entropy(ctx.handle, C.byref(h), C.byref(w), _stream(stream, ctx)))
+    return float(h.value), float(w.value)
 
 
 def sd_index_append(ctx: _Ctx, slot_ids: torch.Tensor, new_tokens: torch.Tensor,

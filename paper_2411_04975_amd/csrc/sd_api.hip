@@ -32,7 +32,7 @@ bool dev_alloc(T **p, int64_t count, int64_t *acc) {
 void free_all(sd_ctx *c) {
     void *ptrs[] = {c->g_text, c->g_sa, c->g_bucket, c->g_tok1, c->b_keys[0], c->b_keys[1], c->b_vals[0],
                     c->b_vals[1], c->b_rank, c->b_flags, c->b_hist, c->b_partials, c->r_text,
-                    c->r_len, c->s_occ, c->s_unit_sa, c->d_err, c->s_unit_ticks};
+                    c->r_len, c->s_occ, c->s_unit_sa, c->d_err, c->s_unit_ticks, c->d_entropy};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (c->d_algo_bytes) (void)hipFree(c->d_algo_bytes);
@@ -98,7 +98,7 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     ok = ok && dev_alloc(&c->r_text, B * c->r_stride, sb) && dev_alloc(&c->r_len, B, sb);
     ok = ok && dev_alloc(&c->s_occ, B * ctx, sb);
     ok = ok && dev_alloc(&c->s_unit_sa, B * P * ctx, sb);
-    ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb);
+    ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb) && dev_alloc(&c->d_entropy, 4, sb);
     ok = ok && dev_alloc(&c->s_unit_ticks, B * 2 * P * 4, sb);
     ok = ok && dev_alloc(&c->d_algo_bytes, SD_K_COUNT, sb);
     if (!ok) {
@@ -171,6 +171,14 @@ sd_status sd_index_insert(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_s
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
     return sd_insert_global_impl(c, d_tokens, d_seq_offsets, n_seq, n_tokens,
                                  (hipStream_t)hip_stream);
+}
+
+sd_status sd_index_entropy(sd_ctx *c, double *h_mean_bits, double *h_weight, void *hip_stream) {
+    if (!c) return SD_ERR_INVALID_ARG;
+    if (!h_mean_bits || !h_weight) return fail(c, SD_ERR_INVALID_ARG, "null output pointer");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
+    sd_status rc = sd_entropy_impl(c, h_mean_bits, h_weight, (hipStream_t)hip_stream);
+    return rc == SD_OK ? SD_OK : fail(c, rc, "entropy kernels failed");
 }
 
 sd_status sd_index_append(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_new_tokens,

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <string.h>
 #include <string>
 
 #include "../../include/sd.h"
@@ -52,6 +53,7 @@ struct sd_ctx {
     uint32_t *s_unit_ticks = nullptr;  // [B][2P][4], written by the counting kernel variants
 
     int32_t *d_err = nullptr;        // [SD_DEVERR_N]
+    double *d_entropy = nullptr;     // [3] accumulators of sd_index_entropy
 
     int n_cu = 0;                    // compute units of the device
     size_t lds_optin = 0;            // largest dynamic LDS size a workgroup may ask for
@@ -76,6 +78,8 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
                                int32_t n_seq, int64_t n_tokens, hipStream_t st);
 sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
                                 int32_t n_seq, int64_t n_tokens, hipStream_t st);
+void sd_fill_i32(int32_t *p, int64_t n, int32_t v, hipStream_t st);
+sd_status sd_entropy_impl(sd_ctx *c, double *h_mean_bits, double *h_weight, hipStream_t st);
 sd_status sd_build_requests_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_tokens,
                                  const int64_t *d_offsets, int32_t n_seq, hipStream_t st);
 sd_status sd_append_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_new_tokens,

@@ -87,6 +87,9 @@ class GpuPath:
         d_tok, d_off, n = self._seqs(docs)
         self.sd.sd_index_insert(self.ctx, d_tok, d_off, n)
 
+    def entropy(self):
+        return self.sd.sd_index_entropy(self.ctx)
+
     def build_requests(self, slots, contexts):
         d_tok, d_off, n = self._seqs(contexts)
         d_slots = self.torch.tensor(list(slots), dtype=self.torch.int32, device=self.dev)

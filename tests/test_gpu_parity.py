@@ -496,3 +496,48 @@ def test_insert_into_empty_index_and_capacity():
         assert not parity.compare_trees(got2, want)
     finally:
         g.close()
+
+
+# ---- empirical entropy of the global index ----------------------------------------------------
+# Tolerance: both sides add up to ~1e7 terms of size <= 2^40 in different orders and with
+# different log2 routines; 1e-9 relative is far above that noise and far below any real error.
+ENTROPY_RTOL = 1e-9
+
+
+@pytest.mark.parametrize("case", ["tiny", "tiny-D3", "binary", "all-equal", "distinct", "zipf",
+                                  "empty-docs"])
+def test_entropy_matches_oracle(case, tiny_workload):
+    rng = np.random.default_rng(31)
+    if case == "tiny":
+        D, vocab, docs = tiny_workload.D, tiny_workload.vocab, tiny_workload.docs()
+    elif case == "tiny-D3":
+        D, vocab, docs = 3, tiny_workload.vocab, tiny_workload.docs()[:7]
+    elif case == "binary":
+        D, vocab, docs = 12, 2, [rng.integers(0, 2, int(n)).astype(np.int32) for n in (300, 1, 77, 500)]
+    elif case == "all-equal":
+        D, vocab, docs = 9, 3, [np.full(400, 1, np.int32), np.full(5, 1, np.int32), np.full(30, 2, np.int32)]
+    elif case == "distinct":
+        D, vocab, docs = 6, 1000, [np.arange(700, dtype=np.int32)]
+    elif case == "zipf":
+        w = make_workload(scaled("lowrep", n_docs=40, doc_len=(500, 500), batch=2, ctx=64), seed=3)
+        D, vocab, docs = w.D, w.vocab, w.docs()
+    else:
+        D, vocab, docs = 5, 7, [np.zeros(0, np.int32), np.array([3], np.int32), np.zeros(0, np.int32),
+                                np.array([3, 3, 4], np.int32)]
+    docs = [np.asarray(d, np.int32) for d in docs]
+    N = sum(len(d) for d in docs) + len(docs)
+    g = parity.GpuPath(vocab, D, min(4, D - 1), 1.0, 0.1, 1, 16, N + 8)
+    try:
+        assert g.entropy() == (0.0, 0.0)             # nothing built yet
+        g.build_global(docs)
+        h, wt = g.entropy()
+        h2, wt2 = g.entropy()                        # repeatable, and leaves the index alone
+    finally:
+        g.close()
+    t = oracle.Trie(D)
+    for d in docs:
+        t.add_doc(d)
+    ho, wo = t.entropy()
+    assert wt == wo and wt2 == wo
+    assert h == pytest.approx(ho, rel=ENTROPY_RTOL, abs=1e-15)
+    assert h2 == pytest.approx(ho, rel=ENTROPY_RTOL, abs=1e-15)
