@@ -88,6 +88,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
                     help="enqueue every step from the host instead of replaying a captured HIP graph")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="end the step with sd_accept, the collection glue and sd_index_append "
+                         "as three launches instead of sd_accept_append")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -122,7 +125,7 @@ def main():
     ctx = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, B, max_ctx, n_tokens + n_docs, 0)
     trees = sd.Trees(B, mn, dev)
     d_target = torch.zeros((B, mn + 1), dtype=i32, device=dev)
-    d_alen = torch.zeros(B, dtype=i32, device=dev)
+    d_alen = torch.full((B,), -1, dtype=i32, device=dev)
     d_apath = torch.zeros((B, mn), dtype=i32, device=dev)
     d_bonus = torch.zeros(B, dtype=i32, device=dev)
     d_new = torch.zeros(B * (mn + 1), dtype=i32, device=dev)
@@ -184,16 +187,26 @@ def main():
     r_build_ms = e0.elapsed_time(e1)
 
     # ---- decode steps ---------------------------------------------------------------------
-    def step():
+    def step_separate():
         sd.sd_speculate(ctx, d_slots, trees)
         verifier.targets(trees.n_nodes, trees.parents, d_future, d_pos, d_target)
         sd.sd_accept(ctx, trees, B, d_target, d_alen, d_apath, d_bonus)
         verifier.collect(trees.tokens, d_alen, d_apath, d_bonus, d_new, d_newoff, d_pos)
         sd.sd_index_append(ctx, d_slots, d_new, d_newoff)
 
+    def step_fused():
+        # the verifier stand-in moves its positions on by what the previous step produced;
+        # sd_accept_append does sd_accept and sd_index_append of the result in one launch
+        sd.sd_speculate(ctx, d_slots, trees)
+        verifier.targets(trees.n_nodes, trees.parents, d_future, d_pos, d_target, advance=d_alen)
+        sd.sd_accept_append(ctx, trees, d_slots, d_target, d_alen, d_apath, d_bonus)
+
+    step = step_separate if args.separate_calls else step_fused
+
     def reset():
         build_requests()
         d_pos.zero_()
+        d_alen.fill_(-1)
 
     # The step is launch-bound from Python (five launches of a few microseconds each), so the
     # timed loop replays a HIP graph captured from one step: the same kernels, enqueued by the
@@ -333,7 +346,9 @@ def main():
                    "generator": {k: v for k, v in w.params.items()
                                  if k in ("kind", "n_templates", "template_len", "span", "mut",
                                           "doc_len", "zipf_s")},
-                   "step": "sd_speculate + simulated verifier + sd_accept + sd_index_append"},
+                   "step": ("sd_speculate + simulated verifier + sd_accept + sd_index_append"
+                            if args.separate_calls else
+                            "sd_speculate + simulated verifier + sd_accept_append")},
         "index_build_tokens_per_s": n_tokens / (g_build_ms * 1e-3),
         "index_build_ms": g_build_ms, "request_build_ms": r_build_ms,
         "request_build_tokens_per_s": B * ctx_len / (r_build_ms * 1e-3),

@@ -195,10 +195,25 @@ sd_status sd_speculate(sd_ctx *ctx, const int32_t *d_slot_ids, int32_t batch, sd
  * current node is accepted and becomes the current node, until no child does.
  * d_accept_len[b] = number of accepted nodes, d_accept_path[b*max_nodes ..]
  * their indices in order (rest -1), d_bonus[b] = the target token at the last
- * accepted node (the token the target model contributes itself). */
+ * accepted node (the token the target model contributes itself).
+ * trees.max_nodes <= 256. */
 sd_status sd_accept(sd_ctx *ctx, sd_trees trees, int32_t batch, const int32_t *d_target_tokens,
                     int32_t *d_accept_len, int32_t *d_accept_path, int32_t *d_bonus,
                     void *hip_stream);
+
+/* sd_accept, and in the same launch sd_index_append of what it found: the
+ * context of slot d_slot_ids[b] is extended by the tokens of request b's
+ * accepted draft nodes, in path order, and then by its bonus token
+ * (d_accept_len[b] + 1 tokens), which is how a decode step ends (Section 2,
+ * step 2: the accepted tokens and the target model's own token join the
+ * output; Section 3: the per-request structure follows the output online).
+ * Outputs as for sd_accept.  Slot ids must be distinct.  A bad slot id, a
+ * context that would outgrow max_ctx_tokens or a token outside [0, vocab)
+ * raise the sticky flags of sd_get_stats, as sd_index_append does; the accept
+ * outputs are written regardless.  batch <= max_batch_slots. */
+sd_status sd_accept_append(sd_ctx *ctx, sd_trees trees, const int32_t *d_slot_ids, int32_t batch,
+                           const int32_t *d_target_tokens, int32_t *d_accept_len,
+                           int32_t *d_accept_path, int32_t *d_bonus, void *hip_stream);
 
 /* Synchronises the device and copies counters and sticky flags to the host. */
 sd_status sd_get_stats(sd_ctx *ctx, sd_stats *host_out);

@@ -95,6 +95,8 @@ def _load():
     L.sd_speculate.argtypes = [vp, vp, C.c_int32, _Trees, vp]
     L.sd_accept.restype = C.c_int
     L.sd_accept.argtypes = [vp, _Trees, C.c_int32, vp, vp, vp, vp, vp]
+    L.sd_accept_append.restype = C.c_int
+    L.sd_accept_append.argtypes = [vp, _Trees, vp, C.c_int32, vp, vp, vp, vp, vp]
     L.sd_get_stats.restype = C.c_int
     L.sd_get_stats.argtypes = [vp, C.POINTER(_Stats)]
     L.sd_debug_profile.restype = C.c_int
@@ -260,6 +262,22 @@ def sd_accept(ctx: _Ctx, trees: Trees, batch: int, target_tokens: torch.Tensor,
                              _ptr(accept_len, i32, ctx, batch, "accept_len"),
                              _ptr(accept_path, i32, ctx, batch * mn, "accept_path"),
                              _ptr(bonus, i32, ctx, batch, "bonus"), _stream(stream, ctx))
+    _check(ctx, code)
+
+
+def sd_accept_append(ctx: _Ctx, trees: Trees, slot_ids: torch.Tensor, target_tokens: torch.Tensor,
+                     accept_len: torch.Tensor, accept_path: torch.Tensor, bonus: torch.Tensor,
+                     stream=None) -> None:
+    """sd_accept plus sd_index_append of the accepted tokens and the bonus token, one launch."""
+    i32 = torch.int32
+    mn = trees.max_nodes
+    batch = int(slot_ids.numel())
+    code = _load().sd_accept_append(ctx.handle, trees._struct(ctx, batch),
+                                    _ptr(slot_ids, i32, ctx, batch, "slot_ids"), batch,
+                                    _ptr(target_tokens, i32, ctx, batch * (mn + 1), "target_tokens"),
+                                    _ptr(accept_len, i32, ctx, batch, "accept_len"),
+                                    _ptr(accept_path, i32, ctx, batch * mn, "accept_path"),
+                                    _ptr(bonus, i32, ctx, batch, "bonus"), _stream(stream, ctx))
     _check(ctx, code)
 
 

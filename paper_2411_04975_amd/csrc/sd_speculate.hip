@@ -1170,13 +1170,24 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
 // Ancestor chains are resolved by pointer jumping in LDS (log2(depth) rounds); because a
 // parent always has a lower index than its child, the path in walk order is the accepted
 // nodes in index order.
+// With APPEND the accepted draft tokens and the bonus token are also written behind the context
+// of the request's slot (what sd_index_append would do with them), in the same launch.
+struct AppendArgs {
+    const int32_t *slot_ids;
+    int32_t *r_text, *r_len;
+    int64_t stride;
+    int32_t max_ctx, max_slots, vocab;
+    int32_t *err;
+};
+
+template <bool APPEND>
 __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nodes,
                                                const int32_t *__restrict__ tokens,
                                                const int32_t *__restrict__ parents, int max_nodes,
                                                const int32_t *__restrict__ target,
                                                int32_t *__restrict__ accept_len,
                                                int32_t *__restrict__ accept_path,
-                                               int32_t *__restrict__ bonus) {
+                                               int32_t *__restrict__ bonus, AppendArgs ap) {
     __shared__ int32_t s_tgt[257];
     __shared__ int32_t s_anc[256];
     __shared__ int32_t s_ok[256];
@@ -1232,20 +1243,62 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nod
         }
         __syncthreads();
     }
+    uint64_t am[4];
     int L = 0, last = -1;
 #pragma unroll
     for (int r = 0; r < 4; r++) {
         int j = lane + 64 * r;
-        const bool acc = j < n && s_ok[j];
-        const uint64_t m = __ballot(acc);
-        if (acc) path[L + __popcll(m & lanemask_lt())] = j;
-        if (m) last = 64 * r + 63 - __clzll((unsigned long long)m);
-        L += __popcll(m);
+        am[r] = __ballot(j < n && s_ok[j]);
+        if (am[r]) last = 64 * r + 63 - __clzll((unsigned long long)am[r]);
+        L += __popcll(am[r]);
+    }
+    const int32_t bon = s_tgt[last + 1];
+    int32_t *row = nullptr;
+    int32_t old = 0;
+    if (APPEND) {  // L accepted tokens and the bonus token go behind the slot's context
+        const int32_t slot = ap.slot_ids[b];
+        if (slot < 0 || slot >= ap.max_slots) {
+            if (lane == 0) atomicOr(&ap.err[SD_DEVERR_SLOT], 1);
+        } else {
+            old = ap.r_len[slot];
+            if ((int64_t)old + L + 1 > ap.max_ctx) {
+                if (lane == 0) atomicOr(&ap.err[SD_DEVERR_CTX], 1);
+            } else {
+                row = ap.r_text + (int64_t)slot * ap.stride;
+            }
+        }
+    }
+    int done = 0;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        int j = lane + 64 * r;
+        if ((am[r] >> lane) & 1ull) {
+            const int at = done + __popcll(am[r] & lanemask_lt());
+            path[at] = j;
+            if (APPEND && row) {
+                int32_t t = mt[r];
+                if (t < 0 || t >= ap.vocab) {
+                    atomicOr(&ap.err[SD_DEVERR_TOKEN], 1);
+                    t = 0;
+                }
+                row[old + at] = t;
+            }
+        }
+        done += __popcll(am[r]);
     }
     for (int i = L + lane; i < max_nodes; i += 64) path[i] = -1;
     if (lane == 0) {
         accept_len[b] = L;
-        bonus[b] = s_tgt[last + 1];
+        bonus[b] = bon;
+        if (APPEND && row) {
+            int32_t t = bon;
+            if (t < 0 || t >= ap.vocab) {
+                atomicOr(&ap.err[SD_DEVERR_TOKEN], 1);
+                t = 0;
+            }
+            row[old + L] = t;
+            ap.r_len[ap.slot_ids[b]] = old + L + 1;
+        }
     }
 }
 
@@ -1315,8 +1368,21 @@ sd_status sd_accept_impl(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t
                          hipStream_t st) {
     if (batch == 0) return SD_OK;
     sd_span sp(c, SD_K_ACCEPT, st);
-    hipLaunchKernelGGL(k_accept, dim3((unsigned)batch), dim3(64), 0, st, trees.d_n_nodes,
+    hipLaunchKernelGGL(k_accept<false>, dim3((unsigned)batch), dim3(64), 0, st, trees.d_n_nodes,
                        trees.d_tokens, trees.d_parents, trees.max_nodes, d_target, d_accept_len,
-                       d_accept_path, d_bonus);
+                       d_accept_path, d_bonus, AppendArgs{});
+    return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+sd_status sd_accept_append_impl(sd_ctx *c, sd_trees trees, const int32_t *d_slot_ids, int32_t batch,
+                                const int32_t *d_target, int32_t *d_accept_len,
+                                int32_t *d_accept_path, int32_t *d_bonus, hipStream_t st) {
+    if (batch == 0) return SD_OK;
+    sd_span sp(c, SD_K_ACCEPT, st);
+    AppendArgs ap{d_slot_ids, c->r_text, c->r_len, c->r_stride, c->cfg.max_ctx_tokens,
+                  c->cfg.max_batch_slots, c->cfg.vocab, c->d_err};
+    hipLaunchKernelGGL(k_accept<true>, dim3((unsigned)batch), dim3(64), 0, st, trees.d_n_nodes,
+                       trees.d_tokens, trees.d_parents, trees.max_nodes, d_target, d_accept_len,
+                       d_accept_path, d_bonus, ap);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }

@@ -137,6 +137,21 @@ class GpuPath:
         torch.cuda.synchronize()
         return al.cpu().numpy(), ap.cpu().numpy(), bo.cpu().numpy()
 
+    def accept_append(self, slots, target):
+        """sd_accept and sd_index_append of its result in one launch."""
+        torch = self.torch
+        tr = self.trees
+        B, mn = tr.batch, tr.max_nodes
+        d_t = torch.from_numpy(np.ascontiguousarray(target, np.int32)).to(self.dev)
+        al = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        ap = torch.full((B, mn), -7, dtype=torch.int32, device=self.dev)
+        bo = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        self.sd.sd_accept_append(self.ctx, tr,
+                                 torch.tensor(list(slots), dtype=torch.int32, device=self.dev),
+                                 d_t, al, ap, bo)
+        torch.cuda.synchronize()
+        return al.cpu().numpy(), ap.cpu().numpy(), bo.cpu().numpy()
+
     def stats(self):
         return self.sd.sd_get_stats(self.ctx)
 

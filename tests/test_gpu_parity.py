@@ -233,7 +233,10 @@ def test_append_equals_rebuild_and_streaming_loop():
             assert not bad, "\n".join(bad)
             fut = np.stack([w.future[b, pos[b]:pos[b] + mn + 2] for b in range(B)])
             tgt = parity.targets_from_future(want, fut, mn)
-            al, ap, bo = g.accept(tgt)
+            # odd steps end with the fused call (accept + append in one launch), even steps
+            # with the two separate calls: the contexts must come out the same either way
+            fused = step % 2 == 1
+            al, ap, bo = g.accept_append(range(B), tgt) if fused else g.accept(tgt)
             new = []
             for b in range(B):
                 n = int(want["n_nodes"][b])
@@ -246,7 +249,8 @@ def test_append_equals_rebuild_and_streaming_loop():
                 contexts[b] = np.concatenate([contexts[b], new[-1]])
                 pos[b] += L + 1
                 total_acc += L
-            g.append(range(B), new)
+            if not fused:
+                g.append(range(B), new)
         assert total_acc > 0
         # a context rebuilt from scratch gives the same trees as the appended one
         got_app = g.speculate(range(B))
@@ -274,6 +278,17 @@ def test_device_flags_bad_token_slot_and_overflow():
             parity.oracle_global_trie([np.array([1, 2, 3, 0, 4], np.int32)], 6, 10),
             [np.arange(8, dtype=np.int32) % 10], 6, 3, 1.0, 0.1, g.max_nodes)
         assert not parity.compare_trees(got, want)
+        # the fused accept + append raises the same flags and leaves the context alone
+        g.build_requests([1], [np.arange(16, dtype=np.int32) % 10])     # slot 1 is full
+        g.speculate([1])
+        tgt = np.zeros((1, g.max_nodes + 1), np.int32)
+        al, ap, bo = g.accept_append([1], tgt)
+        assert g.stats()["err_ctx_overflow"] == 1 and bo[0] == 0
+        got = g.speculate([1])
+        want = parity.oracle_speculate_batch(
+            parity.oracle_global_trie([np.array([1, 2, 3, 0, 4], np.int32)], 6, 10),
+            [np.arange(16, dtype=np.int32) % 10], 6, 3, 1.0, 0.1, g.max_nodes)
+        assert not parity.compare_trees(got, want)
     finally:
         g.close()
 
@@ -297,7 +312,7 @@ def test_decode_step_in_a_hip_graph_matches_eager():
     slots = torch.arange(B, dtype=i32, device=dev)
 
     class Loop:
-        def __init__(self):
+        def __init__(self, fused=False):
             self.ctx = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, B,
                                     w.ctx_len + (steps + 3) * (mn + 1), len(w.corpus) + 64, 0)
             sd.sd_index_build(self.ctx, sd.SD_SCOPE_GLOBAL, None, docs_tok, docs_off, len(w.corpus))
@@ -311,9 +326,18 @@ def test_decode_step_in_a_hip_graph_matches_eager():
             self.new = torch.zeros(B * (mn + 1), dtype=i32, device=dev)
             self.newoff = torch.zeros(B + 1, dtype=i32, device=dev)
             self.pos = torch.zeros(B, dtype=i32, device=dev)
+            self.fused = fused
+            if fused:
+                self.alen.fill_(-1)
 
         def step(self):
             sd.sd_speculate(self.ctx, slots, self.trees)
+            if self.fused:   # the step bench.py times
+                verifier.targets(self.trees.n_nodes, self.trees.parents, future, self.pos,
+                                 self.target, advance=self.alen)
+                sd.sd_accept_append(self.ctx, self.trees, slots, self.target, self.alen,
+                                    self.apath, self.bonus)
+                return
             verifier.targets(self.trees.n_nodes, self.trees.parents, future, self.pos, self.target)
             sd.sd_accept(self.ctx, self.trees, B, self.target, self.alen, self.apath, self.bonus)
             verifier.collect(self.trees.tokens, self.alen, self.apath, self.bonus, self.new,
@@ -327,12 +351,15 @@ def test_decode_step_in_a_hip_graph_matches_eager():
                                         t.match_len, t.source, self.alen, self.apath, self.bonus,
                                         self.pos)]
 
-    eager, graphed = Loop(), Loop()
+    eager, graphed, fused = Loop(), Loop(), Loop(fused=True)
     try:
         torch.cuda.synchronize()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             graphed.step()
+        gf = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gf):
+            fused.step()
         torch.cuda.synchronize()
         moved = 0
         for i in range(steps):
@@ -342,6 +369,11 @@ def test_decode_step_in_a_hip_graph_matches_eager():
             got = graphed.snapshot()
             for a, b in zip(got, want):
                 assert torch.equal(a, b), "replay %d differs from the eager step" % i
+            # the three-launch step: same trees and acceptance (its positions lag by one step)
+            gf.replay()
+            gotf = fused.snapshot()
+            for a, b in zip(gotf[:10], want[:10]):
+                assert torch.equal(a, b), "fused replay %d differs from the eager step" % i
             moved += int(want[7].sum())
             # unrelated eager work between replays
             _ = (torch.arange(1000, device=dev) * 2).sum().item()
@@ -349,6 +381,7 @@ def test_decode_step_in_a_hip_graph_matches_eager():
     finally:
         sd.sd_destroy(eager.ctx)
         sd.sd_destroy(graphed.ctx)
+        sd.sd_destroy(fused.ctx)
 
 
 VARIANTS = [(1, 0), (0, 1), (1, 1)]

@@ -9,16 +9,20 @@ namespace {
 
 // target[b][0] = future[b][pos[b]]; target[b][1+j] = future[b][pos[b] + depth(j)], where
 // depth(j) is the number of draft nodes on the path from the tree root to node j (>= 1).
+// With `advance` given, pos[b] first moves on by advance[b] + 1 (the tokens the previous step
+// produced: its accepted draft tokens and the bonus token; -1 = nothing yet).
 __global__ __launch_bounds__(64) void k_targets(const int32_t *__restrict__ n_nodes,
                                                 const int32_t *__restrict__ parents, int max_nodes,
                                                 const int32_t *__restrict__ future,
-                                                int64_t future_stride,
-                                                const int32_t *__restrict__ pos,
+                                                int64_t future_stride, int32_t *__restrict__ pos,
+                                                const int32_t *__restrict__ advance,
                                                 int32_t *__restrict__ target) {
     const int b = blockIdx.x, lane = threadIdx.x;
     const int n = n_nodes[b];
     const int32_t *par = parents + (int64_t)b * max_nodes;
-    const int32_t *fut = future + (int64_t)b * future_stride + pos[b];
+    const int32_t p0 = pos[b] + (advance ? advance[b] + 1 : 0);
+    if (advance && lane == 0) pos[b] = p0;
+    const int32_t *fut = future + (int64_t)b * future_stride + p0;
     int32_t *tgt = target + (int64_t)b * (max_nodes + 1);
     if (lane == 0) tgt[0] = fut[0];
     for (int j = lane; j < max_nodes; j += 64) {
@@ -87,11 +91,11 @@ int wl_stream_copy(const void *d_src, void *d_dst, int64_t n_bytes, void *stream
 
 // all pointers are device pointers
 int wl_targets(const int32_t *d_n_nodes, const int32_t *d_parents, int max_nodes,
-               const int32_t *d_future, int64_t future_stride, const int32_t *d_pos, int batch,
-               int32_t *d_target, void *stream) {
+               const int32_t *d_future, int64_t future_stride, int32_t *d_pos,
+               const int32_t *d_advance, int batch, int32_t *d_target, void *stream) {
     if (batch <= 0) return 0;
     hipLaunchKernelGGL(k_targets, dim3((unsigned)batch), dim3(64), 0, (hipStream_t)stream, d_n_nodes,
-                       d_parents, max_nodes, d_future, future_stride, d_pos, d_target);
+                       d_parents, max_nodes, d_future, future_stride, d_pos, d_advance, d_target);
     return hipGetLastError() == hipSuccess ? 0 : 1;
 }
 

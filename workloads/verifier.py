@@ -35,7 +35,7 @@ def _load():
         L = C.CDLL(LIB_PATH)
         vp = C.c_void_p
         L.wl_targets.restype = C.c_int
-        L.wl_targets.argtypes = [vp, vp, C.c_int, vp, C.c_int64, vp, C.c_int, vp, vp]
+        L.wl_targets.argtypes = [vp, vp, C.c_int, vp, C.c_int64, vp, vp, C.c_int, vp, vp]
         L.wl_collect.restype = C.c_int
         L.wl_collect.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp]
         L.wl_stream_copy.restype = C.c_int
@@ -49,12 +49,15 @@ def _p(t: torch.Tensor):
     return C.c_void_p(t.data_ptr())
 
 
-def targets(n_nodes, parents, future, pos, target) -> None:
-    """target[b, 0] = future[b, pos[b]], target[b, 1+j] = future[b, pos[b] + depth(node j)]."""
+def targets(n_nodes, parents, future, pos, target, advance=None) -> None:
+    """target[b, 0] = future[b, pos[b]], target[b, 1+j] = future[b, pos[b] + depth(node j)].
+    With `advance` (the previous step's accept lengths, -1 before the first step) pos moves on by
+    advance + 1 first."""
     B, mn = parents.shape
     assert target.shape == (B, mn + 1) and future.shape[0] == B
     st = torch.cuda.current_stream(parents.device).cuda_stream
-    rc = _load().wl_targets(_p(n_nodes), _p(parents), mn, _p(future), future.shape[1], _p(pos), B,
+    rc = _load().wl_targets(_p(n_nodes), _p(parents), mn, _p(future), future.shape[1], _p(pos),
+                            _p(advance) if advance is not None else C.c_void_p(0), B,
                             _p(target), C.c_void_p(st))
     assert rc == 0
 
