@@ -67,6 +67,15 @@ __device__ __forceinline__ double uni(double v) {
     return u.d;
 }
 
+// All cross-lane traffic of a unit stays inside one wavefront.  The LDS operations of a wave
+// are issued and completed in order, so what one lane wrote is seen by a later read of another
+// lane without a hardware barrier; wsync() only stops the compiler from moving LDS accesses
+// across it.
+__device__ __forceinline__ void wsync() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // ------------------------------------------------------------------------------------------
 // per-request occurrence lists
 // ------------------------------------------------------------------------------------------
@@ -88,24 +97,44 @@ __device__ __forceinline__ bool occ_less(const int32_t *__restrict__ x, int2 a, 
 
 // bitonic network in its all-ascending form (mirror step, then half-cleaners); positions at or
 // beyond m act as +infinity and are never touched, so m need not be a power of two.  Run by
-// the whole workgroup.
+// the whole workgroup.  With `key` given (the two tokens after each occurrence packed into one
+// word, kept beside the records) most compares are decided without touching memory; equal
+// keys fall back to the token-by-token compare.
 template <bool STATS>
-__device__ __forceinline__ void occ_sort(int2 *arr, int m, const int32_t *__restrict__ x, int depth, unsigned &nb) {
+__device__ __forceinline__ void occ_sort(int2 *arr, uint64_t *key, int m, const int32_t *__restrict__ x, int depth, unsigned &nb) {
     int n2 = 1;
     while (n2 < m) n2 <<= 1;
+    // Thread t handles elements t, t + blockDim, ...: a wave owns whole aligned blocks of 64
+    // elements.  A step whose partners stay inside such a block needs no workgroup barrier
+    // before or after another step of that kind: wave-level ordering of the LDS (or, for the
+    // global-memory case, of the wave's own accesses) is enough.
+    const bool wave_local_ok = key != nullptr;  // records in LDS
     for (int k = 2; k <= n2; k <<= 1) {
         for (int j = k >> 1; j > 0; j >>= 1) {
+            const bool mirror = j == (k >> 1);
             for (int i = threadIdx.x; i < m; i += blockDim.x) {
-                int l = (j == (k >> 1)) ? (i ^ (k - 1)) : (i ^ j);
+                int l = mirror ? (i ^ (k - 1)) : (i ^ j);
                 if (l > i && l < m) {
                     int2 a = arr[i], b = arr[l];
-                    if (occ_less<STATS>(x, b, a, depth, nb)) {
+                    bool swap;
+                    if (key) {
+                        const uint64_t ka = key[i], kb = key[l];
+                        swap = ka != kb ? kb < ka : occ_less<STATS>(x, b, a, depth, nb);
+                        if (swap) { key[i] = kb; key[l] = ka; }
+                    } else {
+                        swap = occ_less<STATS>(x, b, a, depth, nb);
+                    }
+                    if (swap) {
                         arr[i] = b;
                         arr[l] = a;
                     }
                 }
             }
-            __syncthreads();
+            // the step after this one: (k, j / 2), or the mirror step of 2k
+            const bool local = wave_local_ok && (mirror ? k <= 64 : j < 64);
+            const bool next_local = wave_local_ok && (j > 1 ? (j >> 1) < 64 : 2 * k <= 64);
+            if (local && next_local) wsync();
+            else __syncthreads();
         }
     }
 }
@@ -226,10 +255,23 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
     if (m > 0) {
         const int depth = p.D - 1;
         if (in_lds) {
-            if (m > 1) occ_sort<STATS>(s_sort, m, x, depth, nb);
+            if (m > 1) {
+                // sort key: the two tokens after the occurrence, end marker lowest (rows are
+                // padded with end markers, and only a pattern's own tail is followed by one)
+                uint64_t *key = reinterpret_cast<uint64_t *>(s_sort + OCC_LDS_SORT);
+                for (int i = tid; i < m; i += nthr) {
+                    const int e = s_sort[i].x;
+                    const uint32_t t1 = (uint32_t)(x[e + 1] + 1);
+                    const uint32_t t2 = depth >= 2 ? (uint32_t)(x[e + 2] + 1) : 0u;
+                    key[i] = ((uint64_t)t1 << 32) | t2;
+                    SD_CNT(8);
+                }
+                __syncthreads();
+                occ_sort<STATS>(s_sort, key, m, x, depth, nb);
+            }
             for (int i = tid; i < m; i += nthr) occ[i] = s_sort[i];
         } else {
-            occ_sort<STATS>(occ, m, x, depth, nb);
+            occ_sort<STATS>(occ, nullptr, m, x, depth, nb);
         }
     }
     __threadfence_block();
@@ -239,15 +281,6 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
 // ------------------------------------------------------------------------------------------
 // expansion
 // ------------------------------------------------------------------------------------------
-// All cross-lane traffic of a unit stays inside one wavefront.  The LDS operations of a wave
-// are issued and completed in order, so what one lane wrote is seen by a later read of another
-// lane without a hardware barrier; wsync() only stops the compiler from moving LDS accesses
-// across it.
-__device__ __forceinline__ void wsync() {
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
 struct Key {
     double s;
     int32_t tok, par, idx;  // idx < 0: no entry
@@ -780,6 +813,10 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
 // are compared with the whole pattern lane-parallel.  The dependent chain is
 // bucket -> column -> suffix array -> text, whatever p is.
 constexpr int SCAN_MAX = 256;
+#ifndef SD_COL_FAN
+#define SD_COL_FAN 8
+#endif
+constexpr int COL_FAN = SD_COL_FAN;  // probes per bound and round in a wide bucket (<= 32)
 constexpr int DIRECT_MAX = 8;
 
 template <bool STATS>
@@ -795,18 +832,47 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
     const int32_t w1 = __builtin_amdgcn_readlane(wk, 1);
     const int32_t *col = p.g_tok1;
     int32_t l = lo, h = hi;
-    if (h - l > SCAN_MAX) {  // wide bucket: bracket the second token by binary search first
-        int32_t la = l, ha = h, lu = l, hu = h;
+    if (h - l > SCAN_MAX) {
+        // wide bucket: lower and upper bound of the second token by COL_FAN-way search, one half
+        // of the wave per bound: every round probes COL_FAN evenly spaced column entries per
+        // bound and keeps the gap in which the answer lies.  Every probe moves a whole memory
+        // line for four bytes, so a wide fan trades latency for traffic: 32 probes per bound
+        // were faster for one request and much slower for 256 (the low-repetition workload went
+        // from 100 to 154 us per call); 8 keep the traffic near that of a binary search.
+        int32_t la = l, ha = h, lu = l, hu = h;  // the bounds lie in [la, ha] and [lu, hu]
+        const int half = lane >> 5, k = lane & 31;
         while (la < ha || lu < hu) {
-            const bool doA = la < ha, doB = lu < hu;
-            const int32_t midA = la + ((ha - la) >> 1), midB = lu + ((hu - lu) >> 1);
+            const int32_t lo_ = half ? lu : la, hi_ = half ? hu : ha;
+            const int32_t n = hi_ - lo_;
+            const int32_t step = (n + COL_FAN - 1) / COL_FAN;
+            const int64_t idx = (int64_t)lo_ + (int64_t)k * step;
+            const bool valid = k < COL_FAN && n > 0 && idx < hi_;
             int32_t v = 0;
-            if (lane == 0 && doA) v = col[midA];
-            if (lane == 1 && doB) v = col[midB];
-            if (lane < 2) SD_CNT(4);
-            const int32_t vA = __builtin_amdgcn_readlane(v, 0), vB = __builtin_amdgcn_readlane(v, 1);
-            if (doA) { if (vA < w1) la = midA + 1; else ha = midA; }
-            if (doB) { if (vB <= w1) lu = midB + 1; else hu = midB; }
+            if (valid) v = col[idx];
+            if (valid) SD_CNT(4);
+            // probes holding a smaller (lower bound) / not larger (upper bound) token: a prefix
+            const uint64_t pm = __ballot(valid && (half ? v <= w1 : v < w1));
+            const int cA = __popc((uint32_t)pm), cB = __popc((uint32_t)(pm >> 32));
+            if (la < ha) {
+                const int32_t st = (ha - la + COL_FAN - 1) / COL_FAN;
+                if (cA == 0) ha = la;
+                else {
+                    const int64_t q = (int64_t)la + (int64_t)(cA - 1) * st;
+                    const int64_t nh = q + st < ha ? q + st : ha;
+                    la = (int32_t)(q + 1);
+                    ha = (int32_t)(nh > q + 1 ? nh : q + 1);
+                }
+            }
+            if (lu < hu) {
+                const int32_t st = (hu - lu + COL_FAN - 1) / COL_FAN;
+                if (cB == 0) hu = lu;
+                else {
+                    const int64_t q = (int64_t)lu + (int64_t)(cB - 1) * st;
+                    const int64_t nh = q + st < hu ? q + st : hu;
+                    lu = (int32_t)(q + 1);
+                    hu = (int32_t)(nh > q + 1 ? nh : q + 1);
+                }
+            }
         }
         l = la;
         h = lu;
@@ -1353,7 +1419,10 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     if (nw > 16) nw = 16;
     if (nw < 1) nw = 1;
     size_t lds = (size_t)nw * lds_wave;
-    if (lds < OCC_LDS_SORT * sizeof(int2)) lds = OCC_LDS_SORT * sizeof(int2);
+    // the occurrence sort keeps 2048 records and their keys in the same LDS before the waves
+    // take it over
+    if (lds < OCC_LDS_SORT * (sizeof(int2) + sizeof(uint64_t)))
+        lds = OCC_LDS_SORT * (sizeof(int2) + sizeof(uint64_t));
     if (lds > c->lds_optin) return SD_ERR_CAPACITY;
     {
         sd_span sp(c, SD_K_SPECULATE, st);
