@@ -313,6 +313,39 @@ def main():
     cnt = sd.sd_debug_profile_read(ctx)
     sd.sd_debug_profile(ctx, 0)
 
+    # ---- latency profile of sd_speculate: wall-clock marks inside the timing variant --------
+    reset()
+    for _ in range(W):
+        step()
+    sd.sd_debug_profile(ctx, 3)
+    sd.sd_debug_profile_read(ctx)
+    for _ in range(3):
+        sd.sd_speculate(ctx, d_slots, trees)
+    rt, khz = sd.sd_debug_read_request_ticks(ctx, B)
+    sd.sd_debug_profile_read(ctx)
+    sd.sd_debug_profile(ctx, 0)
+    us = 1e3 / max(khz, 1)
+    nw = int(rt[0, 0, 7]) if rt[0, 0, 7] else 16
+    rt = rt[:, :nw, :].astype(np.int64)
+    start = (rt[:, 0, 0] - rt[:, 0, 0].min()) * us
+    req_end = start + rt[:, :, 4].max(axis=1) * us
+    runs_us = (rt[:, :, 3] - rt[:, :, 2]) * us
+
+    def pct(a, q):
+        return float(np.percentile(a, q))
+
+    latency_profile = {
+        "note": "wall-clock marks (100 MHz) inside the timing variant of k_speculate, batch %d, "
+                "one workgroup of %d waves per request; microseconds" % (B, nw),
+        "workgroup_start_spread": float(start.max()),
+        "occurrences_and_matches_done": {"p50": pct(rt[:, 0, 1] * us, 50), "max": float(rt[:, 0, 1].max() * us)},
+        "longest_wave_in_runs": {"p50": pct(runs_us.max(axis=1), 50), "p90": pct(runs_us.max(axis=1), 90),
+                                 "max": float(runs_us.max())},
+        "request_finished_at": {"p50": pct(req_end, 50), "p90": pct(req_end, 90), "max": float(req_end.max())},
+        "runs_per_request_mean": float(rt[:, 0, 5].mean()),
+        "last_token_occurrences_in_context": {"mean": float(rt[:, 0, 6].mean()), "max": int(rt[:, 0, 6].max())},
+    }
+
     exp_ms = prof["speculate"]["ms"] / max(prof["speculate"]["launches"], 1)
     exp_bytes = cnt["speculate"]["algo_bytes"] / max(cnt["speculate"]["launches"], 1)
     achieved = exp_bytes / (exp_ms * 1e-3) / 1e9 if exp_ms > 0 else 0.0
@@ -355,6 +388,7 @@ def main():
         "step_latency_ms": step_latency,
         "speculate_only_ms_median": spec_ms, "speculate_only_trees_per_s": B / (spec_ms * 1e-3),
         "speculate_latency_us_by_batch": latency_by_batch,
+        "speculate_latency_profile": latency_profile,
         "stream_copy_gbs": achievable_gbs,
         "mean_tree_nodes": mean_nodes, "mean_accept_len": mean_accept,
         "kernel_ms_per_launch": kernels_ms, "build_kernel_ms_total": build_kernels_ms,

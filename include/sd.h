@@ -223,7 +223,9 @@ sd_status sd_get_stats(sd_ctx *ctx, sd_stats *host_out);
  * launches are kept between two reads).  mode 0 = off, 1 = time kernels,
  * 2 = time kernels and run the counting variant of the speculation kernel,
  * which adds up the bytes the algorithm asks for (context tokens scanned,
- * suffix-array words, text tokens, occurrence records, emitted nodes).  sd_debug_profile_read
+ * suffix-array words, text tokens, occurrence records, emitted nodes),
+ * 3 = time kernels and run the timing variant of the speculation kernel,
+ * which leaves wall-clock marks for the two sd_debug_read_*_ticks calls.  sd_debug_profile_read
  * synchronises, reports per-kernel launch counts, total milliseconds and
  * counted bytes since the previous read, and clears them. */
 enum {
@@ -240,7 +242,7 @@ typedef struct {
 sd_status sd_debug_profile(sd_ctx *ctx, int32_t mode);
 sd_status sd_debug_profile_read(sd_ctx *ctx, sd_profile *host_out);
 
-/* Latency profile: after an sd_speculate call made with profiling mode 2, copies four
+/* Latency profile: after an sd_speculate call made with profiling mode 3, copies four
  * wall-clock marks per (request, index, p) unit -- ticks since the unit started at the end of
  * its set-up, of reading its match, of the first child enumeration, and of the whole unit; unit
  * index = (b * 2 + index) * P + (p - 1), `count` = 4 * units -- and the tick rate in kHz.
@@ -248,6 +250,16 @@ sd_status sd_debug_profile_read(sd_ctx *ctx, sd_profile *host_out);
  * longer pattern of the same request is not); the others keep what the buffer held.
  * Synchronises. */
 sd_status sd_debug_read_unit_ticks(sd_ctx *ctx, uint32_t *h_ticks, int64_t count, int32_t *khz);
+
+/* Latency profile per request: after an sd_speculate call made with profiling mode 3, copies
+ * 8 words for each of the 16 possible waves of each of the first `batch` requests of that call
+ * (h_ticks holds batch * 16 * 8 words; waves that did not run leave their words untouched):
+ * [0] the workgroup's start on the device-wide wall clock (low 32 bits), then ticks since that
+ * start when [1] the request's occurrence lists and global matches were done, [2] the runs of
+ * pattern lengths were set up, [3] this wave found no further run to take, [4] the workgroup's
+ * closing barrier was passed; [5] runs of the request, [6] occurrences of its last token in its
+ * context, [7] waves of the workgroup.  Also the tick rate in kHz.  Synchronises. */
+sd_status sd_debug_read_request_ticks(sd_ctx *ctx, uint32_t *h_ticks, int32_t batch, int32_t *khz);
 
 /* Test hook: synchronises, then copies the global index to host buffers:
  * the laid-out text (documents back to back, -1 after each) and the suffix

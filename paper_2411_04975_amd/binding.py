@@ -103,6 +103,8 @@ def _load():
     L.sd_debug_profile.argtypes = [vp, C.c_int32]
     L.sd_debug_profile_read.restype = C.c_int
     L.sd_debug_profile_read.argtypes = [vp, C.POINTER(_Profile)]
+    L.sd_debug_read_request_ticks.restype = C.c_int
+    L.sd_debug_read_request_ticks.argtypes = [vp, vp, C.c_int32, C.POINTER(C.c_int32)]
     L.sd_debug_read_unit_ticks.restype = C.c_int
     L.sd_debug_read_unit_ticks.argtypes = [vp, vp, C.c_int64, C.POINTER(C.c_int32)]
     L.sd_debug_read_global.restype = C.c_int
@@ -287,6 +289,17 @@ def sd_get_stats(ctx: _Ctx) -> dict:
     return {k: getattr(s, k) for k, _ in _Stats._fields_ if k != "reserved"}
 
 
+def sd_debug_read_request_ticks(ctx: _Ctx, batch: int):
+    """Per-request phase marks of the last sd_speculate made in profiling mode 3: array
+    [batch, 16 waves, 8] of uint32 (see include/sd.h) and the tick rate in kHz."""
+    import numpy as np
+    t = np.zeros(batch * 16 * 8, np.uint32)
+    khz = C.c_int32()
+    _check(ctx, _load().sd_debug_read_request_ticks(ctx.handle, t.ctypes.data_as(C.c_void_p), batch,
+                                                    C.byref(khz)))
+    return t.reshape(batch, 16, 8), int(khz.value)
+
+
 def sd_debug_read_global(ctx: _Ctx):
     """Test hook: (text, suffix array) of the global index as numpy int32 arrays."""
     import numpy as np
@@ -315,7 +328,7 @@ def sd_debug_profile_read(ctx: _Ctx) -> dict:
 
 def sd_debug_read_unit_ticks(ctx: _Ctx, batch: int):
     """Microseconds since unit start at four marks (set-up, match, root children, end) for each
-    unit of the last counted sd_speculate: array [batch, 2, P, 4]."""
+    unit expanded by the last sd_speculate made in profiling mode 3: array [batch, 2, P, 4]."""
     import numpy as np
     n = batch * 2 * ctx.cfg.P * 4
     t = np.zeros(n, np.uint32)

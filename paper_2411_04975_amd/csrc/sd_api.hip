@@ -99,7 +99,7 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     ok = ok && dev_alloc(&c->s_occ, B * ctx, sb);
     ok = ok && dev_alloc(&c->s_unit_sa, B * P * ctx, sb);
     ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb) && dev_alloc(&c->d_entropy, 4, sb);
-    ok = ok && dev_alloc(&c->s_unit_ticks, B * 2 * P * 4, sb);
+    ok = ok && dev_alloc(&c->s_unit_ticks, B * 2 * P * 4 + B * 16 * 8, sb);
     ok = ok && dev_alloc(&c->d_algo_bytes, SD_K_COUNT, sb);
     if (!ok) {
         free_all(c);
@@ -263,7 +263,7 @@ sd_status sd_get_stats(sd_ctx *c, sd_stats *o) {
 }
 
 sd_status sd_debug_profile(sd_ctx *c, int32_t mode) {
-    if (!c || mode < 0 || mode > 2) return SD_ERR_INVALID_ARG;
+    if (!c || mode < 0 || mode > 3) return SD_ERR_INVALID_ARG;
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
     if (mode && !c->prof_ev) {
         c->prof_ev = new (std::nothrow) hipEvent_t[2 * SD_PROF_MAX_SPANS]();
@@ -307,6 +307,23 @@ sd_status sd_debug_read_unit_ticks(sd_ctx *c, uint32_t *h_ticks, int64_t count, 
         return fail(c, SD_ERR_HIP, "hipDeviceGetAttribute");
     *khz = rate;
     if (count && hipMemcpy(h_ticks, c->s_unit_ticks, (size_t)count * sizeof(uint32_t),
+                           hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(c, SD_ERR_HIP, "hipMemcpy");
+    return SD_OK;
+}
+
+sd_status sd_debug_read_request_ticks(sd_ctx *c, uint32_t *h_ticks, int32_t batch, int32_t *khz) {
+    if (!c || !h_ticks || !khz || batch < 0) return SD_ERR_INVALID_ARG;
+    if (batch > c->cfg.max_batch_slots)
+        return fail(c, SD_ERR_CAPACITY, "more requests than the context holds");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
+    if (hipDeviceSynchronize() != hipSuccess) return fail(c, SD_ERR_HIP, "device synchronize failed");
+    int rate = 0;
+    if (hipDeviceGetAttribute(&rate, hipDeviceAttributeWallClockRate, c->cfg.device) != hipSuccess)
+        return fail(c, SD_ERR_HIP, "hipDeviceGetAttribute");
+    *khz = rate;
+    const uint32_t *src = c->s_unit_ticks + (int64_t)c->cfg.max_batch_slots * 2 * c->cfg.P * 4;
+    if (batch && hipMemcpy(h_ticks, src, (size_t)batch * 16 * 8 * sizeof(uint32_t),
                            hipMemcpyDeviceToHost) != hipSuccess)
         return fail(c, SD_ERR_HIP, "hipMemcpy");
     return SD_OK;

@@ -36,7 +36,8 @@ struct SpecParams {
     int32_t *unit_sa;
     int32_t *err;
     unsigned long long *algo_bytes;
-    uint32_t *unit_ticks;  // counting variants only: wall-clock ticks each unit took
+    uint32_t *unit_ticks;  // timing variant only: wall-clock marks of each expanded unit
+    uint32_t *wg_ticks;    // timing variant only: [request][16 waves][8] phase marks
 };
 
 // In the counting variants (STATS) every lane adds up the bytes it asks memory for: 4 per
@@ -932,19 +933,19 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
 // ExpandSpeculationTree below the matched node into the LDS tree (t_tok, t_par, t_score).
 // Returns the number of draft nodes and leaves their SCORE in `total`; `deepest` tells whether
 // a node of depth D (which may have no children) was taken.
-template <bool STATS>
+template <bool STATS, bool TICKS>
 __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh, int b, int t,
                         const int32_t *__restrict__ x, int src, int pl, Frontier &f, Stage &sg,
                         int32_t *t_tok, int32_t *t_par, double *t_score, double &total,
                         bool &deepest, unsigned &nb) {
     const int lane = threadIdx.x & 63;
     deepest = false;
-    const uint64_t tick0 = STATS ? wall_clock64() : 0;
+    const uint64_t tick0 = TICKS ? wall_clock64() : 0;
     const int64_t uidx = (int64_t)b * (2 * p.P) + src * p.P + (pl - 1);
     const int K = (int)floor(p.alpha * (double)pl);
     uint32_t tick_setup = 0, tick_match = 0, tick_root = 0;
     sg.lo = 0; sg.m = 0; sg.wlog = 0;
-    if (STATS) tick_setup = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(t & 0);
+    if (TICKS) tick_setup = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(t & 0);
 
     const int32_t *sa = nullptr, *text = nullptr;
     int32_t lo = 0, hi = 0;
@@ -996,13 +997,13 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
 
     int n = 0;
     total = 0.0;
-    if (STATS) tick_match = (uint32_t)(wall_clock64() - tick0) + (uint32_t)((hi - lo) & 0);
+    if (TICKS) tick_match = (uint32_t)(wall_clock64() - tick0) + (uint32_t)((hi - lo) & 0);
     if (hi > lo) {
         f.n = 0;
         f.cap = K;
         push_children<STATS>(f, -1, sg, sa, text, lo, hi, pl, -1, 1.0, p.min_score, p.D, p.den_mode,
                              nb);
-        if (STATS) tick_root = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(f.n & 0);
+        if (TICKS) tick_root = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(f.n & 0);
         while (n < K && f.n > 0) {
             const Key best = frontier_pick(f, true, -1);
             if (best.s < p.min_score) break;
@@ -1069,7 +1070,7 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
         }
     }
     wsync();
-    if (STATS && lane == 0) {  // phase marks: set-up, match, root children, whole unit
+    if (TICKS && lane == 0) {  // phase marks: set-up, match, root children, whole unit
         p.unit_ticks[uidx * 4 + 0] = tick_setup;
         p.unit_ticks[uidx * 4 + 1] = tick_match;
         p.unit_ticks[uidx * 4 + 2] = tick_root;
@@ -1091,7 +1092,7 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
 #define SD_SPEC_OCC 4
 #endif
 
-template <bool STATS>
+template <bool STATS, bool TICKS>
 __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t *__restrict__ slot_ids,
                                                     sd_trees out, int lds_per_wave) {
     extern __shared__ double smem[];
@@ -1110,6 +1111,7 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
     // MatchPattern on the global index for every pattern length, spread over the waves, runs
     // while the first loads of the context scan are in flight
     const int P = p.P;
+    const uint64_t wg0 = TICKS ? wall_clock64() : 0;
     request_occurrences<STATS>(p, b, t, x, reinterpret_cast<int2 *>(smem), sh, nb, [&]() {
         for (int pl = 1 + wave; pl <= P; pl += nw) {
             int32_t lo = 0, hi = 0;
@@ -1121,6 +1123,7 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
             if (lane == 0) { sh.g_lo[pl] = lo; sh.g_hi[pl] = hi; }
         }
     });
+    const uint64_t wg1 = TICKS ? wall_clock64() : 0;
 
     // per-wave LDS: frontier (score, tok, par, lo, hi, dep), two trees (score, tok, par), staging
     const int cap = p.max_nodes;
@@ -1165,6 +1168,7 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
     const uint64_t start_r = __ballot(lane < P && cr > 1 && (alone || cr != crp));
     const int ng = __popcll(start_g), nruns = ng + __popcll(start_r);
 
+    const uint64_t wg2 = TICKS ? wall_clock64() : 0;
     double best_s = 0.0;
     int best_o = -1, best_n = 0, cur = 0;
     for (;;) {
@@ -1182,7 +1186,7 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
         for (int pl = P - i0; pl >= p_lo; pl--) {
             double total = 0.0;
             bool deepest = false;
-            const int n = run_unit<STATS>(p, sh, b, t, x, src, pl, f, sg, cur ? ttk1 : ttk0,
+            const int n = run_unit<STATS, TICKS>(p, sh, b, t, x, src, pl, f, sg, cur ? ttk1 : ttk0,
                                           cur ? tpr1 : tpr0, cur ? tsc1 : tsc0, total, deepest, nb);
             int pstar = pl;  // shortest pattern of the run with this very tree
             if (!deepest)
@@ -1196,8 +1200,18 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
             if (!deepest) break;
         }
     }
+    const uint64_t wg3 = TICKS ? wall_clock64() : 0;
     if (lane == 0) { sh.best_s[wave] = best_s; sh.best_o[wave] = best_o; }
     __syncthreads();
+    if (TICKS && lane == 0 && wave < 16) {
+        // per wave: start (absolute, low 32 bits), then ticks since the start at: occurrences
+        // and global matches done, runs set up, this wave out of runs, barrier passed;
+        // number of runs; occurrences of the last token
+        uint32_t *wt = p.wg_ticks + ((int64_t)b * 16 + wave) * 8;
+        wt[0] = (uint32_t)wg0; wt[1] = (uint32_t)(wg1 - wg0); wt[2] = (uint32_t)(wg2 - wg0);
+        wt[3] = (uint32_t)(wg3 - wg0); wt[4] = (uint32_t)(wall_clock64() - wg0);
+        wt[5] = (uint32_t)nruns; wt[6] = (uint32_t)sh.m; wt[7] = (uint32_t)nw;
+    }
     double ws = 0.0;
     int wo = -1, ww = -1;
     for (int w = 0; w < nw; w++) {
@@ -1381,10 +1395,12 @@ sd_status sd_speculate_setup(sd_ctx *c) {
             hipSuccess || optin <= 0)
         optin = (int)prop.sharedMemPerBlock;
     c->lds_optin = (size_t)optin > sizeof(WgShared) + 256 ? (size_t)optin - sizeof(WgShared) - 256 : 0;
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&k_speculate<false>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->lds_optin) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void *>(&k_speculate<true>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)c->lds_optin) != hipSuccess)
+    const void *kernels[3] = {reinterpret_cast<const void *>(&k_speculate<false, false>),
+                              reinterpret_cast<const void *>(&k_speculate<true, false>),
+                              reinterpret_cast<const void *>(&k_speculate<false, true>)};
+    for (const void *k : kernels)
+        if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)c->lds_optin) != hipSuccess)
         return SD_ERR_HIP;
     return SD_OK;
 }
@@ -1404,7 +1420,8 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     p.err = c->d_err;
     p.algo_bytes = c->d_algo_bytes;
     p.unit_ticks = c->s_unit_ticks;
-    const bool stats = c->prof_mode == 2;
+    p.wg_ticks = c->s_unit_ticks + (int64_t)c->cfg.max_batch_slots * 2 * c->cfg.P * 4;
+    const bool stats = c->prof_mode == 2, ticks = c->prof_mode == 3;
     // per wave: frontier 6 arrays, two trees of 3 arrays, staging
     size_t lds_wave = (size_t)c->max_nodes * (3 * sizeof(double) + 9 * sizeof(int32_t)) +
                       (64 + 64 + TC_TOKENS + 128) * sizeof(int32_t);
@@ -1426,8 +1443,9 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     if (lds > c->lds_optin) return SD_ERR_CAPACITY;
     {
         sd_span sp(c, SD_K_SPECULATE, st);
-        if (stats) hipLaunchKernelGGL(k_speculate<true>, dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
-        else hipLaunchKernelGGL(k_speculate<false>, dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
+        if (stats) hipLaunchKernelGGL((k_speculate<true, false>), dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
+        else if (ticks) hipLaunchKernelGGL((k_speculate<false, true>), dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
+        else hipLaunchKernelGGL((k_speculate<false, false>), dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
     }
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
