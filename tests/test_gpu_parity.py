@@ -574,3 +574,43 @@ def test_entropy_matches_oracle(case, tiny_workload):
     assert wt == wo and wt2 == wo
     assert h == pytest.approx(ho, rel=ENTROPY_RTOL, abs=1e-15)
     assert h2 == pytest.approx(ho, rel=ENTROPY_RTOL, abs=1e-15)
+
+
+def test_profiling_variants_give_the_same_trees(tiny_workload):
+    """The counting (mode 2) and timing (mode 3) variants of the speculation kernel are the
+    measured kernel plus bookkeeping: same trees, plausible counters and marks."""
+    import paper_2411_04975_amd as sd
+    w = tiny_workload
+    docs = w.docs()
+    B = w.batch
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, w.ctx_len + 8,
+                       len(w.corpus) + len(docs))
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), [w.contexts[b] for b in range(B)])
+        base = g.speculate(range(B))
+        sd.sd_debug_profile(g.ctx, 2)
+        sd.sd_debug_profile_read(g.ctx)
+        counted = g.speculate(range(B))
+        prof = sd.sd_debug_profile_read(g.ctx)
+        sd.sd_debug_profile(g.ctx, 3)
+        timed = g.speculate(range(B))
+        rt, khz = sd.sd_debug_read_request_ticks(g.ctx, B)
+        ut = sd.sd_debug_read_unit_ticks(g.ctx, B)
+        sd.sd_debug_profile(g.ctx, 0)
+    finally:
+        g.close()
+    for other in (counted, timed):
+        for k in base:
+            assert np.array_equal(base[k], other[k]), k
+    assert prof["speculate"]["launches"] == 1 and prof["speculate"]["ms"] > 0
+    # at least the context scan (4 B per token) and the emitted trees are counted
+    assert prof["speculate"]["algo_bytes"] >= B * w.ctx_len * 4
+    assert khz > 0
+    nw = int(rt[0, 0, 7])
+    assert 1 <= nw <= 16
+    m = rt[:, :nw, :].astype(np.int64)
+    assert np.all(m[:, :, 1] <= m[:, :, 2]) and np.all(m[:, :, 2] <= m[:, :, 3])
+    assert np.all(m[:, :, 3] <= m[:, :, 4])
+    assert np.all(m[:, 0, 6] >= 1)                     # the context's own last token
+    assert ut.shape == (B, 2, w.P, 4)
