@@ -17,19 +17,24 @@ __global__ __launch_bounds__(64) void k_targets(const int32_t *__restrict__ n_no
                                                 int64_t future_stride, int32_t *__restrict__ pos,
                                                 const int32_t *__restrict__ advance,
                                                 int32_t *__restrict__ target) {
+    __shared__ int32_t s_par[256];
     const int b = blockIdx.x, lane = threadIdx.x;
-    const int n = n_nodes[b];
+    int n = n_nodes[b];
+    if (n > 256) n = 256;
     const int32_t *par = parents + (int64_t)b * max_nodes;
     const int32_t p0 = pos[b] + (advance ? advance[b] + 1 : 0);
     if (advance && lane == 0) pos[b] = p0;
     const int32_t *fut = future + (int64_t)b * future_stride + p0;
     int32_t *tgt = target + (int64_t)b * (max_nodes + 1);
-    if (lane == 0) tgt[0] = fut[0];
+    for (int j = lane; j < n; j += 64) s_par[j] = par[j];   // ancestor walks run out of LDS
+    __syncthreads();
+    const int32_t f0 = fut[0];
+    if (lane == 0) tgt[0] = f0;
     for (int j = lane; j < max_nodes; j += 64) {
-        int32_t v = fut[0];
+        int32_t v = f0;
         if (j < n) {
             int d = 1;
-            for (int q = par[j]; q >= 0; q = par[q]) d++;
+            for (int q = s_par[j]; q >= 0 && q < j; q = s_par[q]) d++;
             v = fut[d];
         }
         tgt[1 + j] = v;
