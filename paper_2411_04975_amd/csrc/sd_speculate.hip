@@ -820,20 +820,11 @@ constexpr int SCAN_MAX = 256;
 constexpr int COL_FAN = SD_COL_FAN;  // probes per bound and round in a wide bucket (<= 32)
 constexpr int DIRECT_MAX = 8;
 
+// second stage for a wide bucket [l, h): narrows it to the entries whose second token is w1
 template <bool STATS>
-__device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, int pl, int32_t &lo, int32_t &hi,
-                             unsigned &nb) {
+__device__ __forceinline__ void col_range_wide(const int32_t *__restrict__ col, int32_t w1, int32_t &l,
+                                               int32_t &h, unsigned &nb) {
     const int lane = threadIdx.x & 63;
-    const int32_t w0 = __builtin_amdgcn_readlane(wk, 0);
-    const int32_t bv = lane < 2 ? p.g_bucket[w0 + 1 + lane] : 0;
-    if (lane < 2) SD_CNT(4);
-    lo = __builtin_amdgcn_readlane(bv, 0);
-    hi = __builtin_amdgcn_readlane(bv, 1);
-    if (pl == 1 || lo >= hi) return;
-    const int32_t w1 = __builtin_amdgcn_readlane(wk, 1);
-    const int32_t *col = p.g_tok1;
-    int32_t l = lo, h = hi;
-    if (h - l > SCAN_MAX) {
         // wide bucket: lower and upper bound of the second token by COL_FAN-way search, one half
         // of the wave per bound: every round probes COL_FAN evenly spaced column entries per
         // bound and keeps the gap in which the answer lies.  Every probe moves a whole memory
@@ -877,25 +868,13 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
         }
         l = la;
         h = lu;
-    } else {
-        int32_t v[SCAN_MAX / 64];
-#pragma unroll
-        for (int c = 0; c < SCAN_MAX / 64; c++) {
-            int32_t i = l + c * 64 + lane;
-            v[c] = i < h ? col[i] : 0x7fffffff;
-            if (i < h) SD_CNT(4);
-        }
-        int nless = 0, nleq = 0;
-#pragma unroll
-        for (int c = 0; c < SCAN_MAX / 64; c++) {
-            nless += __popcll(__ballot(v[c] < w1));
-            nleq += __popcll(__ballot(v[c] <= w1));
-        }
-        h = l + nleq;
-        l = l + nless;
-    }
-    lo = l;
-    hi = h;
+}
+
+// last stage for one pattern: [lo, hi) holds the suffixes that start with its first two tokens
+template <bool STATS>
+__device__ __forceinline__ void match_rest(const SpecParams &p, int32_t wk, int pl, int32_t &lo,
+                                           int32_t &hi, unsigned &nb) {
+    const int lane = threadIdx.x & 63;
     if (pl == 2 || lo >= hi) return;
     if (hi - lo <= DIRECT_MAX) {  // compare every remaining suffix with the whole pattern
         const int32_t cnt = hi - lo;
@@ -927,6 +906,128 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
         return;
     }
     match_range<STATS>(p.g_sa, p.g_text, lo, hi, wk, pl, nb);
+}
+
+template <bool STATS>
+__device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, int pl, int32_t &lo, int32_t &hi,
+                             unsigned &nb) {
+    const int lane = threadIdx.x & 63;
+    const int32_t w0 = __builtin_amdgcn_readlane(wk, 0);
+    const int32_t bv = lane < 2 ? p.g_bucket[w0 + 1 + lane] : 0;
+    if (lane < 2) SD_CNT(4);
+    lo = __builtin_amdgcn_readlane(bv, 0);
+    hi = __builtin_amdgcn_readlane(bv, 1);
+    if (pl == 1 || lo >= hi) return;
+    const int32_t w1 = __builtin_amdgcn_readlane(wk, 1);
+    const int32_t *col = p.g_tok1;
+    int32_t l = lo, h = hi;
+    if (h - l > SCAN_MAX) {
+        col_range_wide<STATS>(col, w1, l, h, nb);
+    } else {
+        int32_t v[SCAN_MAX / 64];
+#pragma unroll
+        for (int c = 0; c < SCAN_MAX / 64; c++) {
+            int32_t i = l + c * 64 + lane;
+            v[c] = i < h ? col[i] : 0x7fffffff;
+            if (i < h) SD_CNT(4);
+        }
+        int nless = 0, nleq = 0;
+#pragma unroll
+        for (int c = 0; c < SCAN_MAX / 64; c++) {
+            nless += __popcll(__ballot(v[c] < w1));
+            nleq += __popcll(__ballot(v[c] <= w1));
+        }
+        h = l + nleq;
+        l = l + nless;
+    }
+    lo = l;
+    hi = h;
+    match_rest<STATS>(p, wk, pl, lo, hi, nb);
+}
+
+// Two patterns of one context at once (pattern lengths plA, plB <= 32; lane k of wkA / wkB holds
+// pattern token k).  The stages of the two searches are issued side by side, so that the wave
+// waits for memory once per stage instead of once per stage and pattern: both bucket reads in
+// one load, both column scans together, and the final compare with one half of the wave per
+// pattern.  A pattern that leaves the common route (wide bucket, more than DIRECT_MAX
+// candidates) finishes on its own with the single-pattern stages.
+template <bool STATS>
+__device__ __forceinline__ void match_global_pair(const SpecParams &p, int32_t wkA, int plA, int32_t wkB,
+                                                  int plB, int32_t &loA, int32_t &hiA, int32_t &loB,
+                                                  int32_t &hiB, unsigned &nb) {
+    const int lane = threadIdx.x & 63, half = lane >> 5, k = lane & 31;
+    const int32_t w0A = __builtin_amdgcn_readlane(wkA, 0), w0B = __builtin_amdgcn_readlane(wkB, 0);
+    const int32_t bv = lane < 4 ? p.g_bucket[(lane < 2 ? w0A : w0B) + 1 + (lane & 1)] : 0;
+    if (lane < 4) SD_CNT(4);
+    loA = __builtin_amdgcn_readlane(bv, 0); hiA = __builtin_amdgcn_readlane(bv, 1);
+    loB = __builtin_amdgcn_readlane(bv, 2); hiB = __builtin_amdgcn_readlane(bv, 3);
+    const bool goA = plA > 1 && loA < hiA, goB = plB > 1 && loB < hiB;  // second stage needed
+    const int32_t w1A = __builtin_amdgcn_readlane(wkA, 1), w1B = __builtin_amdgcn_readlane(wkB, 1);
+    const int32_t *col = p.g_tok1;
+    const bool narrowA = goA && hiA - loA <= SCAN_MAX, narrowB = goB && hiB - loB <= SCAN_MAX;
+    {
+        int32_t vA[SCAN_MAX / 64], vB[SCAN_MAX / 64];
+#pragma unroll
+        for (int c = 0; c < SCAN_MAX / 64; c++) {
+            const int32_t iA = loA + c * 64 + lane, iB = loB + c * 64 + lane;
+            vA[c] = narrowA && iA < hiA ? col[iA] : 0x7fffffff;
+            vB[c] = narrowB && iB < hiB ? col[iB] : 0x7fffffff;
+            if (narrowA && iA < hiA) SD_CNT(4);
+            if (narrowB && iB < hiB) SD_CNT(4);
+        }
+        int lsA = 0, leA = 0, lsB = 0, leB = 0;
+#pragma unroll
+        for (int c = 0; c < SCAN_MAX / 64; c++) {
+            lsA += __popcll(__ballot(vA[c] < w1A)); leA += __popcll(__ballot(vA[c] <= w1A));
+            lsB += __popcll(__ballot(vB[c] < w1B)); leB += __popcll(__ballot(vB[c] <= w1B));
+        }
+        if (narrowA) { hiA = loA + leA; loA = loA + lsA; }
+        if (narrowB) { hiB = loB + leB; loB = loB + lsB; }
+    }
+    if (goA && !narrowA) col_range_wide<STATS>(col, w1A, loA, hiA, nb);
+    if (goB && !narrowB) col_range_wide<STATS>(col, w1B, loB, hiB, nb);
+    // last stage: compare the few suffixes left with the whole pattern, A in the lower half of
+    // the wave and B in the upper half
+    const bool restA = goA && plA > 2 && loA < hiA, restB = goB && plB > 2 && loB < hiB;
+    const bool dirA = restA && hiA - loA <= DIRECT_MAX, dirB = restB && hiB - loB <= DIRECT_MAX;
+    if (dirA || dirB) {
+        const int32_t cntA = dirA ? hiA - loA : 0, cntB = dirB ? hiB - loB : 0;
+        const int32_t cnt = half ? cntB : cntA, plh = half ? plB : plA;
+        const int64_t pos = k < cnt ? p.g_sa[(half ? loB : loA) + k] : 0;  // lane 32 h + c: suffix c
+        if (k < cnt) SD_CNT(4);
+        // pattern token k of this half's pattern (the shuffle runs with all lanes on: a lane
+        // that is switched off would hand out zero)
+        const int32_t wkBk = __shfl(wkB, k);
+        const int32_t wkh = half ? wkBk : wkA;
+        int32_t tk[DIRECT_MAX];
+#pragma unroll
+        for (int c = 0; c < DIRECT_MAX; c++) {
+            const int64_t pc = __shfl(pos, half * 32 + c);
+            tk[c] = (c < cnt && k < plh) ? p.g_text[pc + k] : wkh;
+            if (c < cnt && k < plh) SD_CNT(4);
+        }
+        int lsA = 0, leA = 0, lsB = 0, leB = 0;
+#pragma unroll
+        for (int c = 0; c < DIRECT_MAX; c++) {
+            const uint64_t ne = __ballot(c < cnt && k < plh && tk[c] != wkh);
+            const uint32_t neA = (uint32_t)ne, neB = (uint32_t)(ne >> 32);
+            int rA = 0, rB = 0;
+            if (neA) {
+                const int fl = __ffs(neA) - 1;
+                rA = __shfl(tk[c], fl) < __shfl(wkh, fl) ? -1 : 1;
+            }
+            if (neB) {
+                const int fl = 32 + __ffs(neB) - 1;
+                rB = __shfl(tk[c], fl) < __shfl(wkh, fl) ? -1 : 1;
+            }
+            if (c < cntA) { lsA += rA < 0; leA += rA <= 0; }
+            if (c < cntB) { lsB += rB < 0; leB += rB <= 0; }
+        }
+        if (dirA) { hiA = loA + leA; loA = loA + lsA; }
+        if (dirB) { hiB = loB + leB; loB = loB + lsB; }
+    }
+    if (restA && !dirA) match_range<STATS>(p.g_sa, p.g_text, loA, hiA, wkA, plA, nb);
+    if (restB && !dirB) match_range<STATS>(p.g_sa, p.g_text, loB, hiB, wkB, plB, nb);
 }
 
 // One unit (request b, index src: 0 global / 1 request, pattern length pl) on one wavefront:
@@ -1113,14 +1214,25 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
     const int P = p.P;
     const uint64_t wg0 = TICKS ? wall_clock64() : 0;
     request_occurrences<STATS>(p, b, t, x, reinterpret_cast<int2 *>(smem), sh, nb, [&]() {
-        for (int pl = 1 + wave; pl <= P; pl += nw) {
-            int32_t lo = 0, hi = 0;
-            if (pl <= t && p.g_N > 0) {
-                const int32_t wk = lane < pl ? x[t - pl + lane] : 0;  // lane k: pattern token k
-                if (lane < pl) SD_CNT(4);
-                match_global<STATS>(p, wk, pl, lo, hi, nb);
+        for (int plA = 1 + wave; plA <= P; plA += 2 * nw) {
+            const int plB = plA + nw;  // a wave takes its pattern lengths two at a time
+            const bool okA = plA <= t && p.g_N > 0, okB = plB <= P && plB <= t && p.g_N > 0;
+            int32_t loA = 0, hiA = 0, loB = 0, hiB = 0;
+            // lane k: pattern token k
+            const int32_t wkA = okA && lane < plA ? x[t - plA + lane] : 0;
+            const int32_t wkB = okB && lane < plB ? x[t - plB + lane] : 0;
+            if (okA && lane < plA) SD_CNT(4);
+            if (okB && lane < plB) SD_CNT(4);
+            if (okA && okB && plB <= 32)
+                match_global_pair<STATS>(p, wkA, plA, wkB, plB, loA, hiA, loB, hiB, nb);
+            else {
+                if (okA) match_global<STATS>(p, wkA, plA, loA, hiA, nb);
+                if (okB) match_global<STATS>(p, wkB, plB, loB, hiB, nb);
             }
-            if (lane == 0) { sh.g_lo[pl] = lo; sh.g_hi[pl] = hi; }
+            if (lane == 0) {
+                sh.g_lo[plA] = loA; sh.g_hi[plA] = hiA;
+                if (plB <= P) { sh.g_lo[plB] = loB; sh.g_hi[plB] = hiB; }
+            }
         }
     });
     const uint64_t wg1 = TICKS ? wall_clock64() : 0;
