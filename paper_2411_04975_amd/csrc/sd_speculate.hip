@@ -227,15 +227,18 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
     {
         const int wave = uni((int32_t)(tid >> 6)), nw = nthr >> 6;
         int32_t tl = 0;
-        if (m > 0 && lane < p.P && lane < t) tl = x[t - 1 - lane];
+        if (m > 1 && lane < p.P && lane < t) tl = x[t - 1 - lane];
         for (int i = wave; i < m; i += nw) {
             const int e = uni(in_lds ? s_sort[i].x : occ[i].x);
             const int lim = e + 1 < p.P ? e + 1 : p.P;
-            int32_t v = 0;
-            if (lane < lim) v = x[e - lane];
-            if (lane < lim) SD_CNT(8);
-            const uint64_t mis = __ballot(lane >= 1 && lane < lim && v != tl);
-            const int l = mis ? __ffsll((unsigned long long)mis) - 1 : lim;
+            int l = lim;  // the context's own tail agrees with itself all the way: nothing to read
+            if (e != t - 1) {
+                int32_t v = 0;
+                if (lane < lim) v = x[e - lane];
+                if (lane < lim) SD_CNT(8);
+                const uint64_t mis = __ballot(lane >= 1 && lane < lim && v != tl);
+                if (mis) l = __ffsll((unsigned long long)mis) - 1;
+            }
             if (lane == 0) {
                 if (in_lds) s_sort[i].y = l;
                 else occ[i].y = l;
