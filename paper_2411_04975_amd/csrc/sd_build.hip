@@ -10,7 +10,9 @@
 // The sort is prefix doubling: positions are first ordered by their leading two tokens, then
 // each round orders them by the pair (rank of the first h tokens, rank of the next h tokens),
 // which doubles the compared length until it reaches D.  Ranks are group numbers of the
-// previous round, so every round is one radix sort of 2*ceil(log2 N) bit keys.
+// previous round, so every round is one radix sort of 2*ceil(log2 N) bit keys; the keys are
+// built in position order (two sequential reads of the rank array), the only random access
+// of a round is the scatter of the new ranks.
 //
 // Per-request index: the contexts are kept as plain token rows (one per slot) followed by end
 // markers; occurrences are found by scanning the row at speculation time, so building is a
@@ -60,35 +62,20 @@ __global__ __launch_bounds__(TB) void k_init_keys(const int32_t *__restrict__ te
     vals[i] = (uint32_t)i;
 }
 
-__global__ __launch_bounds__(TB) void k_group_flags(const uint64_t *__restrict__ keys, int64_t N,
-                                                    uint32_t *__restrict__ flags) {
-    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
-    if (i >= N) return;
-    flags[i] = (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
-}
-
-__global__ __launch_bounds__(TB) void k_assign_rank(const uint32_t *__restrict__ sa,
-                                                    const uint32_t *__restrict__ gid, int64_t N,
-                                                    uint32_t *__restrict__ rank) {
-    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
-    if (i >= N) return;
-    rank[sa[i]] = gid[i];
-}
-
-// key of suffix-array entry i for the next round: (its own group number, the group number of
-// the suffix h positions further).  The first is gid[i], read in order; only the second is a
-// gather.
-__global__ __launch_bounds__(TB) void k_round_keys(const uint32_t *__restrict__ sa,
-                                                   const uint32_t *__restrict__ gid,
-                                                   const uint32_t *__restrict__ rank, int64_t N,
+// Key of position q for the next round: (group number of its first h tokens, group number of
+// the h tokens after them), with the position itself as the value.  Built in position order:
+// both ranks are read in order (the second h entries further on), nothing is gathered; the
+// radix sort does not care in which order its input arrives.
+__global__ __launch_bounds__(TB) void k_round_keys(const uint32_t *__restrict__ rank, int64_t N,
                                                    int64_t h, int rank_bits,
-                                                   uint64_t *__restrict__ keys) {
-    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
-    if (i >= N) return;
-    int64_t p = sa[i];
-    uint64_t r1 = gid[i];
-    uint64_t r2 = (p + h < N) ? rank[p + h] : 0u;
-    keys[i] = (r1 << rank_bits) | r2;
+                                                   uint64_t *__restrict__ keys,
+                                                   uint32_t *__restrict__ vals) {
+    int64_t q = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (q >= N) return;
+    uint64_t r1 = rank[q];
+    uint64_t r2 = (q + h < N) ? rank[q + h] : 0u;
+    keys[q] = (r1 << rank_bits) | r2;
+    vals[q] = (uint32_t)q;
 }
 
 // final suffix array plus the second-token column: tok1[i] = second token of suffix i.  Inside
@@ -263,15 +250,11 @@ static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, hip
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_init_keys, dim3(nblk(N)), dim3(TB), 0, text, N, tok_bits, c->b_keys[0], c->b_vals[0]);
     int cur = sd_sort_pairs(c, N, 2 * tok_bits, 0, st);
     const int rank_bits = sd_bits_for((uint64_t)N);  // ranks 0..N
-    int64_t h = 2;
-    for (;;) {
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_group_flags, dim3(nblk(N)), dim3(TB), 0, c->b_keys[cur], N, c->b_flags);
-        sd_scan_inclusive_u32(c, c->b_flags, N, st);
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_assign_rank, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_flags, N, c->b_rank);
-        if (h >= c->cfg.D) break;
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], c->b_flags, c->b_rank, N, h, rank_bits, c->b_keys[cur]);
+    // so far the positions are ordered by their first h = 2 tokens
+    for (int64_t h = 2; h < c->cfg.D; h *= 2) {
+        sd_group_ranks(c, c->b_keys[cur], c->b_vals[cur], N, c->b_rank, st);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N)), dim3(TB), 0, c->b_rank, N, h, rank_bits, c->b_keys[cur], c->b_vals[cur]);
         cur = sd_sort_pairs(c, N, 2 * rank_bits, cur, st);
-        h *= 2;
     }
     return cur;
 }

@@ -71,8 +71,9 @@ struct sd_ctx {
 // ---- launchers implemented in the other translation units ---------------
 // radix sort of (key, value) pairs on bits [0, nbits); result ends in keys[out_idx]/vals[out_idx]
 int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st);
-// exclusive->inclusive scan helper: data[i] = sum_{j<=i} data[j], uint32, in place
-void sd_scan_inclusive_u32(sd_ctx *c, uint32_t *data, int64_t n, hipStream_t st);
+// rank[vals[i]] = 1-based group number of keys[i] in the sorted array keys[0..n)
+void sd_group_ranks(sd_ctx *c, const uint64_t *keys, const uint32_t *vals, int64_t n,
+                    uint32_t *rank, hipStream_t st);
 
 sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
                                int32_t n_seq, int64_t n_tokens, hipStream_t st);

@@ -197,32 +197,10 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
     }
 }
 
-// ---- device-wide inclusive prefix sum (uint32), three launches ------------------------------
+// ---- tiles of the device-wide scans ------------------------------------------------------
 constexpr int SC_THREADS = 256;
 constexpr int SC_ITEMS = 16;
 constexpr int SC_TILE = SC_THREADS * SC_ITEMS;
-
-__global__ __launch_bounds__(SC_THREADS) void k_scan_tile_sums(const uint32_t *__restrict__ data,
-                                                               int64_t n,
-                                                               uint32_t *__restrict__ partials) {
-    __shared__ uint32_t s_wave[SC_THREADS / 64];
-    const int64_t base = (int64_t)blockIdx.x * SC_TILE;
-    uint32_t s = 0;
-#pragma unroll
-    for (int k = 0; k < SC_ITEMS; k++) {
-        int64_t i = base + (int64_t)k * SC_THREADS + threadIdx.x;
-        if (i < n) s += data[i];
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-    if ((threadIdx.x & 63) == 0) s_wave[threadIdx.x >> 6] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t t = 0;
-        for (int i = 0; i < SC_THREADS / 64; i++) t += s_wave[i];
-        partials[blockIdx.x] = t;
-    }
-}
 
 // single workgroup: partials[i] <- sum of partials[0..i) (exclusive), any length
 __global__ __launch_bounds__(SC_THREADS) void k_scan_partials(uint32_t *partials, int64_t m) {
@@ -243,39 +221,73 @@ __global__ __launch_bounds__(SC_THREADS) void k_scan_partials(uint32_t *partials
     }
 }
 
-__global__ __launch_bounds__(SC_THREADS) void k_scan_apply(uint32_t *__restrict__ data, int64_t n,
-                                                           const uint32_t *__restrict__ partials) {
+// ---- group numbers of a sorted key array, written by position -------------------------------
+// rank[vals[i]] = number of distinct keys among keys[0..i] (so the first group is 1; 0 stays
+// free for "beyond the end").  Flag, scan and scatter in two passes over the keys instead of
+// flag pass + three scan launches + scatter pass.
+__global__ __launch_bounds__(SC_THREADS) void k_rank_tile_sums(const uint64_t *__restrict__ keys,
+                                                               int64_t n,
+                                                               uint32_t *__restrict__ partials) {
     __shared__ uint32_t s_wave[SC_THREADS / 64];
-    const int64_t base = (int64_t)blockIdx.x * SC_TILE + (int64_t)threadIdx.x * SC_ITEMS;
-    uint32_t v[SC_ITEMS];
+    const int64_t base = (int64_t)blockIdx.x * SC_TILE;
     uint32_t s = 0;
 #pragma unroll
     for (int k = 0; k < SC_ITEMS; k++) {
+        int64_t i = base + (int64_t)k * SC_THREADS + threadIdx.x;
+        if (i < n) s += (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    if ((threadIdx.x & 63) == 0) s_wave[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+        for (int i = 0; i < SC_THREADS / 64; i++) t += s_wave[i];
+        partials[blockIdx.x] = t;
+    }
+}
+
+__global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__restrict__ keys,
+                                                           const uint32_t *__restrict__ vals,
+                                                           int64_t n,
+                                                           const uint32_t *__restrict__ partials,
+                                                           uint32_t *__restrict__ rank) {
+    __shared__ uint32_t s_wave[SC_THREADS / 64];
+    const int64_t base = (int64_t)blockIdx.x * SC_TILE + (int64_t)threadIdx.x * SC_ITEMS;
+    uint32_t f[SC_ITEMS];
+    uint32_t s = 0;
+    uint64_t prev = base > 0 && base - 1 < n ? keys[base - 1] : 0ull;
+#pragma unroll
+    for (int k = 0; k < SC_ITEMS; k++) {
         int64_t i = base + k;
-        v[k] = i < n ? data[i] : 0u;
-        s += v[k];
+        uint64_t key = i < n ? keys[i] : 0ull;
+        f[k] = i < n && (i == 0 || key != prev) ? 1u : 0u;
+        prev = key;
+        s += f[k];
     }
     uint32_t ex = block_excl_scan_256(s, s_wave, nullptr) + partials[blockIdx.x];
 #pragma unroll
     for (int k = 0; k < SC_ITEMS; k++) {
         int64_t i = base + k;
-        ex += v[k];
-        if (i < n) data[i] = ex;
+        ex += f[k];
+        if (i < n) rank[vals[i]] = ex;
     }
 }
 
 }  // namespace
 
-void sd_scan_inclusive_u32(sd_ctx *c, uint32_t *data, int64_t n, hipStream_t st) {
+void sd_group_ranks(sd_ctx *c, const uint64_t *keys, const uint32_t *vals, int64_t n,
+                    uint32_t *rank, hipStream_t st) {
     if (n <= 0) return;
     int64_t nt = (n + SC_TILE - 1) / SC_TILE;
     sd_span sp(c, SD_K_SORT_SCAN, st);
-    hipLaunchKernelGGL(k_scan_tile_sums, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, data, n,
+    hipLaunchKernelGGL(k_rank_tile_sums, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, keys, n,
                        c->b_partials);
     hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(SC_THREADS), 0, st, c->b_partials, nt);
-    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, data, n,
-                       c->b_partials);
+    hipLaunchKernelGGL(k_rank_apply, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, keys, vals, n,
+                       c->b_partials, rank);
 }
+
 
 int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st) {
     int cur = in_idx;
