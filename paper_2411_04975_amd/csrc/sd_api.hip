@@ -32,7 +32,8 @@ bool dev_alloc(T **p, int64_t count, int64_t *acc) {
 void free_all(sd_ctx *c) {
     void *ptrs[] = {c->g_text, c->g_sa, c->g_bucket, c->g_tok1, c->b_keys[0], c->b_keys[1], c->b_vals[0],
                     c->b_vals[1], c->b_rank, c->b_flags, c->b_hist, c->b_partials, c->r_text,
-                    c->r_len, c->s_occ, c->s_unit_sa, c->d_err, c->s_unit_ticks, c->d_entropy};
+                    c->r_len, c->s_occ, c->s_unit_sa, c->d_err, c->s_unit_ticks, c->d_entropy,
+                    c->d_round_flag};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (c->d_algo_bytes) (void)hipFree(c->d_algo_bytes);
@@ -98,7 +99,8 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     ok = ok && dev_alloc(&c->r_text, B * c->r_stride, sb) && dev_alloc(&c->r_len, B, sb);
     ok = ok && dev_alloc(&c->s_occ, B * ctx, sb);
     ok = ok && dev_alloc(&c->s_unit_sa, B * P * ctx, sb);
-    ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb) && dev_alloc(&c->d_entropy, 4, sb);
+    ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb) && dev_alloc(&c->d_entropy, 4, sb) &&
+         dev_alloc(&c->d_round_flag, 8, sb);
     ok = ok && dev_alloc(&c->s_unit_ticks, B * 2 * P * 4 + B * 16 * 8, sb);
     ok = ok && dev_alloc(&c->d_algo_bytes, SD_K_COUNT, sb);
     if (!ok) {

@@ -69,13 +69,65 @@ __global__ __launch_bounds__(TB) void k_init_keys(const int32_t *__restrict__ te
 __global__ __launch_bounds__(TB) void k_round_keys(const uint32_t *__restrict__ rank, int64_t N,
                                                    int64_t h, int rank_bits,
                                                    uint64_t *__restrict__ keys,
-                                                   uint32_t *__restrict__ vals) {
+                                                   uint32_t *__restrict__ vals,
+                                                   const int32_t *__restrict__ run_if) {
     int64_t q = (int64_t)blockIdx.x * TB + threadIdx.x;
-    if (q >= N) return;
+    if (q >= N || (run_if && *run_if == 0)) return;
     uint64_t r1 = rank[q];
     uint64_t r2 = (q + h < N) ? rank[q + h] : 0u;
     keys[q] = (r1 << rank_bits) | r2;
     vals[q] = (uint32_t)q;
+}
+
+// One doubling round without a device-wide sort, for arrays whose groups are short.  The array
+// is already ordered by the first h tokens (gid[i] = group of entry i, non-decreasing), so a
+// round only reorders inside groups, by the group number of the next h tokens.  A workgroup
+// stages a tile of entries plus a halo of SMALL_HALO on both sides in LDS: (group, rank of the
+// second half, position).  Every entry of the tile finds the ends of its group by walking left
+// and right in LDS, counts the members that sort before it (rank of the second half, then
+// previous order) and writes itself, with its new key, to that place of the output arrays.
+// A group longer than SMALL_HALO raises *too_long: the caller then runs the radix sort round
+// instead (whose kernels otherwise return at once).
+constexpr int SMALL_TILE = 1024, SMALL_HALO = 64, SMALL_THREADS = 256;
+constexpr int SMALL_LDS = SMALL_TILE + 2 * SMALL_HALO;
+
+__global__ __launch_bounds__(SMALL_THREADS) void k_round_small(
+    const uint32_t *__restrict__ vals, const uint32_t *__restrict__ gid,
+    const uint32_t *__restrict__ rank, int64_t N, int64_t h, int rank_bits,
+    uint64_t *__restrict__ keys_out, uint32_t *__restrict__ vals_out, int32_t *too_long) {
+    __shared__ uint32_t s_g[SMALL_LDS], s_r2[SMALL_LDS], s_pos[SMALL_LDS];
+    const int64_t first = (int64_t)blockIdx.x * SMALL_TILE - SMALL_HALO;  // array index of LDS slot 0
+    for (int k = threadIdx.x; k < SMALL_LDS; k += SMALL_THREADS) {
+        const int64_t i = first + k;
+        uint32_t g = 0, r2 = 0, pos = 0;  // group 0 does not exist: marks slots outside the array
+        if (i >= 0 && i < N) {
+            g = gid[i];
+            pos = vals[i];
+            r2 = (int64_t)pos + h < N ? rank[(int64_t)pos + h] : 0u;
+        }
+        s_g[k] = g; s_r2[k] = r2; s_pos[k] = pos;
+    }
+    __syncthreads();
+    bool bad = false;
+    for (int k = SMALL_HALO + threadIdx.x; k < SMALL_HALO + SMALL_TILE; k += SMALL_THREADS) {
+        if (first + k >= N) break;
+        const uint32_t g = s_g[k], r2 = s_r2[k];
+        int lo = k, hi = k + 1;  // the group is [lo, hi)
+        while (lo > 0 && k - lo < SMALL_HALO && s_g[lo - 1] == g) lo--;
+        while (hi < SMALL_LDS && hi - k <= SMALL_HALO && s_g[hi] == g) hi++;
+        // the walk was cut short although the group goes on: too long for this kernel
+        if ((lo > 0 && s_g[lo - 1] == g) || (lo == 0 && first > 0 && s_g[0] == g) ||
+            (hi < SMALL_LDS && s_g[hi] == g) || (hi == SMALL_LDS && first + SMALL_LDS < N)) {
+            bad = true;
+            continue;
+        }
+        int before = 0;
+        for (int j = lo; j < hi; j++) before += (s_r2[j] < r2 || (s_r2[j] == r2 && j < k)) ? 1 : 0;
+        const int64_t dst = first + lo + before;
+        keys_out[dst] = ((uint64_t)g << rank_bits) | r2;
+        vals_out[dst] = s_pos[k];
+    }
+    if (bad) *too_long = 1;
 }
 
 // final suffix array plus the second-token column: tok1[i] = second token of suffix i.  Inside
@@ -250,11 +302,24 @@ static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, hip
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_init_keys, dim3(nblk(N)), dim3(TB), 0, text, N, tok_bits, c->b_keys[0], c->b_vals[0]);
     int cur = sd_sort_pairs(c, N, 2 * tok_bits, 0, st);
     const int rank_bits = sd_bits_for((uint64_t)N);  // ranks 0..N
-    // so far the positions are ordered by their first h = 2 tokens
-    for (int64_t h = 2; h < c->cfg.D; h *= 2) {
-        sd_group_ranks(c, c->b_keys[cur], c->b_vals[cur], N, c->b_rank, st);
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N)), dim3(TB), 0, c->b_rank, N, h, rank_bits, c->b_keys[cur], c->b_vals[cur]);
-        cur = sd_sort_pairs(c, N, 2 * rank_bits, cur, st);
+    // So far the positions are ordered by their first h = 2 tokens.  Each round first tries the
+    // in-tile reordering (enough once no group is longer than its halo, which stays true for
+    // all later rounds); the device-wide sort follows, and does something only if that failed.
+    // Both leave the round's result in the other buffer pair.
+    sd_fill_i32(c->d_round_flag, 8, 0, st);
+    const int passes = (2 * rank_bits + 7) / 8;  // of the radix sort: odd ones swap buffers
+    int round = 0;
+    for (int64_t h = 2; h < c->cfg.D; h *= 2, round++) {
+        int32_t *flag = c->d_round_flag + (round < 8 ? round : 7);
+        sd_group_ranks(c, c->b_keys[cur], c->b_vals[cur], N, c->b_rank, c->b_flags, st);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_small,
+                  dim3((unsigned)((N + SMALL_TILE - 1) / SMALL_TILE)), dim3(SMALL_THREADS), 0,
+                  c->b_vals[cur], c->b_flags, c->b_rank, N, h, rank_bits, c->b_keys[cur ^ 1],
+                  c->b_vals[cur ^ 1], flag);
+        const int start = (passes & 1) ? cur : cur ^ 1;
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N)), dim3(TB), 0, c->b_rank, N, h, rank_bits, c->b_keys[start], c->b_vals[start], flag);
+        (void)sd_sort_pairs(c, N, 2 * rank_bits, start, st, flag);
+        cur ^= 1;
     }
     return cur;
 }

@@ -54,6 +54,7 @@ struct sd_ctx {
 
     int32_t *d_err = nullptr;        // [SD_DEVERR_N]
     double *d_entropy = nullptr;     // [3] accumulators of sd_index_entropy
+    int32_t *d_round_flag = nullptr; // [8] per doubling round: groups too long for the in-tile sort
 
     int n_cu = 0;                    // compute units of the device
     size_t lds_optin = 0;            // largest dynamic LDS size a workgroup may ask for
@@ -70,10 +71,12 @@ struct sd_ctx {
 
 // ---- launchers implemented in the other translation units ---------------
 // radix sort of (key, value) pairs on bits [0, nbits); result ends in keys[out_idx]/vals[out_idx]
-int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st);
-// rank[vals[i]] = 1-based group number of keys[i] in the sorted array keys[0..n)
+// every kernel of the sort returns at once if run_if is given and *run_if == 0 (device memory)
+int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st,
+                  const int32_t *run_if = nullptr);
+// rank[vals[i]] = gid[i] = 1-based group number of keys[i] in the sorted array keys[0..n)
 void sd_group_ranks(sd_ctx *c, const uint64_t *keys, const uint32_t *vals, int64_t n,
-                    uint32_t *rank, hipStream_t st);
+                    uint32_t *rank, uint32_t *gid, hipStream_t st);
 
 sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
                                int32_t n_seq, int64_t n_tokens, hipStream_t st);

@@ -60,8 +60,10 @@ __device__ __forceinline__ uint32_t block_excl_scan_256(uint32_t v, uint32_t *s_
 __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t *__restrict__ keys,
                                                            int64_t n, int shift,
                                                            uint32_t *__restrict__ tile_hist,
-                                                           int64_t ntiles) {
+                                                           int64_t ntiles,
+                                                           const int32_t *__restrict__ run_if) {
     __shared__ volatile uint32_t s_cnt[RS_WAVES][RS_BINS];
+    if (run_if && *run_if == 0) return;  // same for the whole grid: the pass is not needed
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     for (int i = tid; i < RS_WAVES * RS_BINS; i += RS_THREADS) (&s_cnt[0][0])[i] = 0;
     __syncthreads();
@@ -87,9 +89,11 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t *__res
 // (256 values), so a pass needs no device-wide scan.
 __global__ __launch_bounds__(RS_THREADS) void k_radix_rowscan(uint32_t *__restrict__ tile_hist,
                                                               int64_t ntiles,
-                                                              uint32_t *__restrict__ row_total) {
+                                                              uint32_t *__restrict__ row_total,
+                                                              const int32_t *__restrict__ run_if) {
     __shared__ uint32_t s_wave[RS_WAVES];
     __shared__ uint32_t s_carry;
+    if (run_if && *run_if == 0) return;
     uint32_t *row = tile_hist + (int64_t)blockIdx.x * ntiles;
     if (threadIdx.x == 0) s_carry = 0;
     __syncthreads();
@@ -119,7 +123,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_rowscan(uint32_t *__restri
 __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
     const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin, uint64_t *__restrict__ kout,
     uint32_t *__restrict__ vout, int64_t n, int shift, const uint32_t *__restrict__ row_excl,
-    const uint32_t *__restrict__ row_total, int64_t ntiles) {
+    const uint32_t *__restrict__ row_total, int64_t ntiles, const int32_t *__restrict__ run_if) {
     __shared__ uint64_t s_keys[RS_TILE];
     __shared__ uint32_t s_vals[RS_TILE];
     __shared__ volatile uint32_t s_wcnt[RS_WAVES][RS_BINS];
@@ -127,6 +131,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
     __shared__ uint32_t s_gbase[RS_BINS];
     __shared__ uint32_t s_wave[RS_WAVES];
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    if (run_if && *run_if == 0) return;
     for (int i = tid; i < RS_WAVES * RS_BINS; i += RS_THREADS) (&s_wcnt[0][0])[i] = 0;
     __syncthreads();
     const int64_t base = (int64_t)blockIdx.x * RS_TILE;
@@ -222,8 +227,8 @@ __global__ __launch_bounds__(SC_THREADS) void k_scan_partials(uint32_t *partials
 }
 
 // ---- group numbers of a sorted key array, written by position -------------------------------
-// rank[vals[i]] = number of distinct keys among keys[0..i] (so the first group is 1; 0 stays
-// free for "beyond the end").  Flag, scan and scatter in two passes over the keys instead of
+// rank[vals[i]] = gid[i] = number of distinct keys among keys[0..i] (so the first group is 1;
+// 0 stays free for "beyond the end").  Flag, scan and scatter in two passes over the keys instead of
 // flag pass + three scan launches + scatter pass.
 __global__ __launch_bounds__(SC_THREADS) void k_rank_tile_sums(const uint64_t *__restrict__ keys,
                                                                int64_t n,
@@ -251,7 +256,8 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__res
                                                            const uint32_t *__restrict__ vals,
                                                            int64_t n,
                                                            const uint32_t *__restrict__ partials,
-                                                           uint32_t *__restrict__ rank) {
+                                                           uint32_t *__restrict__ rank,
+                                                           uint32_t *__restrict__ gid) {
     __shared__ uint32_t s_wave[SC_THREADS / 64];
     const int64_t base = (int64_t)blockIdx.x * SC_TILE + (int64_t)threadIdx.x * SC_ITEMS;
     uint32_t f[SC_ITEMS];
@@ -270,14 +276,17 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__res
     for (int k = 0; k < SC_ITEMS; k++) {
         int64_t i = base + k;
         ex += f[k];
-        if (i < n) rank[vals[i]] = ex;
+        if (i < n) {
+            rank[vals[i]] = ex;
+            gid[i] = ex;
+        }
     }
 }
 
 }  // namespace
 
 void sd_group_ranks(sd_ctx *c, const uint64_t *keys, const uint32_t *vals, int64_t n,
-                    uint32_t *rank, hipStream_t st) {
+                    uint32_t *rank, uint32_t *gid, hipStream_t st) {
     if (n <= 0) return;
     int64_t nt = (n + SC_TILE - 1) / SC_TILE;
     sd_span sp(c, SD_K_SORT_SCAN, st);
@@ -285,11 +294,11 @@ void sd_group_ranks(sd_ctx *c, const uint64_t *keys, const uint32_t *vals, int64
                        c->b_partials);
     hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(SC_THREADS), 0, st, c->b_partials, nt);
     hipLaunchKernelGGL(k_rank_apply, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, keys, vals, n,
-                       c->b_partials, rank);
+                       c->b_partials, rank, gid);
 }
 
 
-int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st) {
+int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st, const int32_t *run_if) {
     int cur = in_idx;
     if (n <= 0) return cur;
     int64_t ntiles = (n + RS_TILE - 1) / RS_TILE;
@@ -297,19 +306,19 @@ int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st) {
         {
             sd_span sp(c, SD_K_SORT_HIST, st);
             hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
-                               c->b_keys[cur], n, shift, c->b_hist, ntiles);
+                               c->b_keys[cur], n, shift, c->b_hist, ntiles, run_if);
         }
         {
             sd_span sp(c, SD_K_SORT_SCAN, st);
             hipLaunchKernelGGL(k_radix_rowscan, dim3(RS_BINS), dim3(RS_THREADS), 0, st, c->b_hist,
-                               ntiles, c->b_hist + (int64_t)RS_BINS * ntiles);
+                               ntiles, c->b_hist + (int64_t)RS_BINS * ntiles, run_if);
         }
         {
             sd_span sp(c, SD_K_SORT_SCATTER, st);
             hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
                                c->b_keys[cur], c->b_vals[cur], c->b_keys[cur ^ 1],
                                c->b_vals[cur ^ 1], n, shift, c->b_hist,
-                               c->b_hist + (int64_t)RS_BINS * ntiles, ntiles);
+                               c->b_hist + (int64_t)RS_BINS * ntiles, ntiles, run_if);
         }
         cur ^= 1;
     }
