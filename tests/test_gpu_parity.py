@@ -614,3 +614,34 @@ def test_profiling_variants_give_the_same_trees(tiny_workload):
     assert np.all(m[:, :, 3] <= m[:, :, 4])
     assert np.all(m[:, 0, 6] >= 1)                     # the context's own last token
     assert ut.shape == (B, 2, w.P, 4)
+
+
+@pytest.mark.parametrize("D", [5, 16, 40])
+def test_suffix_array_with_long_and_short_groups(D):
+    """Runs of one token (groups of hundreds of equal prefixes, which need the device-wide sort
+    rounds) next to random text (groups of one or two, reordered inside LDS tiles), a group that
+    straddles tile boundaries, documents of one token and empty ones: the result must be a
+    permutation ordered on D tokens, and insertion must keep it so."""
+    import paper_2411_04975_amd as sd
+    rng = np.random.default_rng(77)
+    docs = [np.full(300, 7, np.int32), rng.integers(0, 50, 3000).astype(np.int32),
+            np.tile(np.array([1, 2, 3], np.int32), 400), np.zeros(0, np.int32),
+            np.array([9], np.int32), rng.integers(0, 3, 2500).astype(np.int32),
+            np.full(70, 7, np.int32)]
+    more = [np.full(130, 7, np.int32), rng.integers(0, 50, 500).astype(np.int32)]
+    N = sum(len(d) for d in docs + more) + len(docs) + len(more)
+    g = parity.GpuPath(64, D, 4, 1.0, 0.1, 1, 16, N)
+    try:
+        g.build_global(docs)
+        text, sa = sd.sd_debug_read_global(g.ctx)
+        n0 = sum(len(d) for d in docs) + len(docs)
+        assert len(sa) == n0 and np.array_equal(np.sort(sa), np.arange(n0))
+        assert _sorted_on_D(text, sa, D)[0]
+        g.insert_global(more)
+        text, sa = sd.sd_debug_read_global(g.ctx)
+        assert len(sa) == N and np.array_equal(np.sort(sa), np.arange(N))
+        assert _sorted_on_D(text, sa, D)[0]
+        want_text = np.concatenate([np.concatenate([d, [-1]]) for d in docs + more]).astype(np.int32)
+        assert np.array_equal(text, want_text)
+    finally:
+        g.close()
