@@ -160,7 +160,9 @@ def test_streaming_full_sampled_decode_loop():
             assert not bad, "\n".join(bad)
             fut = np.stack([w.future[b, pos[b]:pos[b] + mn + 2] for b in range(B)])
             tgt = parity.targets_from_future(got, fut, mn)
-            al, ap, bo = g.accept(tgt)
+            # odd steps end the way bench.py's step does: accept and append in one launch
+            fused = step % 2 == 1
+            al, ap, bo = g.accept_append(range(B), tgt) if fused else g.accept(tgt)
             new = []
             for b in range(B):
                 L = int(al[b])
@@ -175,7 +177,8 @@ def test_streaming_full_sampled_decode_loop():
                 L, path, bonus = oracle.accept(want["tokens"][i, :k], want["parents"][i, :k], tgt[b])
                 assert al[b] == L and bo[b] == bonus and list(ap[b, :L]) == list(path)
                 tries[b].append(new[b])
-            g.append(range(B), new)
+            if not fused:
+                g.append(range(B), new)
         assert accepted > B          # the drafts do get accepted on this workload
         assert g.stats()["err_ctx_overflow"] == 0
     finally:
