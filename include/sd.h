@@ -146,8 +146,8 @@ sd_status sd_index_build(sd_ctx *ctx, sd_scope scope, const int32_t *d_slot_ids,
                          int64_t n_tokens, void *hip_stream);
 
 /* Online insertion of finished outputs into the global index (Section 3: the
- * global structure is built offline or "updated online" from finished
- * requests; Appendix, "Effect of input distribution shift").  The n_seq
+ * global structure is built offline from earlier outputs or kept up to date
+ * online from finished requests; Appendix, "Effect of input distribution shift").  The n_seq
  * sequences (same layout and ownership as for sd_index_build: device tokens,
  * int64 device offsets, n_tokens = offsets[n_seq] given by the host) are added
  * as new documents.  Afterwards the global index holds exactly what
@@ -187,8 +187,8 @@ sd_status sd_index_append(sd_ctx *ctx, const int32_t *d_slot_ids, const int32_t 
 sd_status sd_speculate(sd_ctx *ctx, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
                        void *hip_stream);
 
-/* Greedy verification walk (Section 2, "accepting tokens up to the first
- * discrepancy"; Section 4.1, simulated verifier).  d_target_tokens is
+/* Greedy verification walk (Section 2: drafted tokens are kept until the first
+ * one the target model disagrees with; Section 4.1, simulated verifier).  d_target_tokens is
  * int32[batch * (max_nodes + 1)]: entry 0 of a request is the target model's
  * token after the context (at the tree root), entry 1+j its token after draft
  * node j.  From the root, the child whose token equals the target at the

@@ -29,15 +29,16 @@
  *   - DEN mode 0 (default): C(N) = COUNT(N) / COUNT(PARENT(N));
  *     DEN mode 1 (the printed equation): COUNT(N) / sum of sibling COUNTs;
  *   - the frontier is every not-yet-added child of any node already in the
- *     speculation tree (the printed "children of leaves" would only ever give
- *     a chain, which the paper presents as a separate "linear" variant);
+ *     speculation tree (candidates taken from the children of the current
+ *     leaves alone, as Algorithm 1 prints it, would only ever give a chain,
+ *     which the paper presents as a separate "linear" variant);
  *   - arg-max ties: higher score, then lower token id, then lower parent index;
  *   - a candidate whose score is below min_score is never added;
  *   - N_p itself is not a draft node: tree size and SCORE count draft nodes;
  *   - between candidate trees a strictly greater SCORE wins, scanning the
  *     global structure p = 1..P first, then the per-request one;
- *   - "linear" variant (caption of the baseline-comparison figure: speculation
- *     that "only allows sequential token chains"): the candidates of a step are
+ *   - "linear" variant (caption of the baseline-comparison figure: a variant
+ *     restricted to chains of tokens): the candidates of a step are
  *     the children of the node added last (of N_p at the start), nothing else.
  *   - empirical entropy: a node's output distribution is COUNT(child) over the
  *     sum of its children's COUNTs; entropy in bits; every node with a child

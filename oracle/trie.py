@@ -3,7 +3,7 @@
 Function names follow Algorithm 1 of the paper: `speculate_unit` is
 MatchPattern + ExpandSpeculationTree for one (structure, p); `generate` is
 GenerateCandidateTree; `accept` is the greedy verification walk of Section 2
-("accepting tokens up to the first discrepancy").
+(drafted tokens are kept until the first one the target model disagrees with).
 """
 from __future__ import annotations
 

@@ -346,8 +346,8 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
-// Online insertion (Section 3: the global tree "can be ... updated online" with finished
-// outputs; Appendix, "Effect of input distribution shift").  Afterwards the index holds
+// Online insertion (Section 3: the global tree may also be kept up to date online with
+// finished outputs; Appendix, "Effect of input distribution shift").  Afterwards the index holds
 // exactly what a build over the old and the new documents together would hold.
 sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
                                 int32_t n_seq, int64_t n_tokens, hipStream_t st) {
