@@ -95,7 +95,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path has no "
-              "multi-GPU leg, see DESIGN.md)" % args.gpus, file=sys.stderr)
+              "multi-GPU leg: requests are independent, so more GPUs would each take a share of "
+              "the batch with a replica of the global index)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
