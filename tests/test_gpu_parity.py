@@ -645,3 +645,90 @@ def test_suffix_array_with_long_and_short_groups(D):
         assert np.array_equal(text, want_text)
     finally:
         g.close()
+
+
+def _fuzz_case(seed):
+    """A small random configuration: vocabulary, bounds, thresholds, variants, document and
+    context shapes all drawn from the seed (repetitive and random text mixed)."""
+    rng = np.random.default_rng(1000 + seed)
+    vocab = int(rng.choice([2, 3, 5, 17, 300]))
+    P = int(rng.integers(1, 13))
+    D = int(P + rng.integers(1, 30))
+    alpha = float(rng.choice([0.5, 1.0, 1.5, 2.0, 4.0, 7.3]))
+    if np.floor(alpha * P) < 1:
+        alpha = 1.0
+    ms = float(rng.choice([0.0, 0.01, 0.05, 0.2, 0.5, 1.0]))
+    den_mode, linear = int(rng.integers(0, 2)), int(rng.integers(0, 4) == 0)
+    base = rng.integers(0, vocab, int(rng.integers(5, 60)))
+
+    def seq(n):
+        parts, total = [], 0
+        while total < n:
+            if rng.random() < 0.6:                       # a copy of a piece of the base text
+                a = int(rng.integers(0, len(base)))
+                piece = base[a:a + int(rng.integers(1, 25))]
+            else:
+                piece = rng.integers(0, vocab, int(rng.integers(1, 12)))
+            parts.append(piece)
+            total += len(piece)
+        return np.concatenate(parts)[:n].astype(np.int32) if n else np.zeros(0, np.int32)
+
+    docs = [seq(int(rng.integers(0, 400))) for _ in range(int(rng.integers(1, 9)))]
+    ctxs = [seq(int(rng.integers(0, 200))) for _ in range(int(rng.integers(1, 6)))]
+    return vocab, D, P, alpha, ms, den_mode, linear, docs, ctxs
+
+
+@pytest.mark.parametrize("chunk", range(6))
+def test_fuzz_small_configurations(chunk):
+    """60 random small configurations (10 per test), every switch of the library drawn at
+    random, each compared with the oracle after build, after an insertion and after an append."""
+    for seed in range(chunk * 10, chunk * 10 + 10):
+        vocab, D, P, alpha, ms, den_mode, linear, docs, ctxs = _fuzz_case(seed)
+        rng = np.random.default_rng(5000 + seed)
+        cut = int(rng.integers(0, len(docs) + 1))
+        B = len(ctxs)
+        N = sum(len(d) for d in docs) + len(docs)
+        g = parity.GpuPath(vocab, D, P, alpha, ms, B, 256, N + 4, den_mode=den_mode, linear=linear)
+        label = "fuzz seed %d (vocab %d D %d P %d alpha %g ms %g den %d lin %d)" % (
+            seed, vocab, D, P, alpha, ms, den_mode, linear)
+        try:
+            g.build_global(docs[:cut])
+            g.build_requests(range(B), ctxs)
+            tg = oracle.Trie(D)
+            for d in docs[:cut]:
+                tg.add_doc(d)
+            tries = []
+            for x in ctxs:
+                t = oracle.Trie(D)
+                t.append(x)
+                tries.append(t)
+
+            def check(tag):
+                got = g.speculate(range(B))
+                want = parity.oracle_speculate_batch(tg, ctxs, D, P, alpha, ms, g.max_nodes,
+                                                     request_tries=tries, den_mode=den_mode,
+                                                     linear=linear)
+                bad = parity.compare_trees(got, want, label + " " + tag)
+                assert not bad, "\n".join(bad)
+                return want
+
+            check("after build")
+            g.insert_global(docs[cut:])
+            for d in docs[cut:]:
+                tg.add_doc(d)
+            want = check("after insert")
+            # append a few tokens per request: the best tree's first tokens, or random ones
+            new = []
+            for b in range(B):
+                k = int(rng.integers(0, 4))
+                toks = [int(v) for v in want["tokens"][b, :min(k, int(want["n_nodes"][b]))]]
+                toks += [int(v) for v in rng.integers(0, vocab, k - len(toks))]
+                new.append(np.array(toks, np.int32))
+                tries[b].append(new[-1])
+                ctxs[b] = np.concatenate([ctxs[b], new[-1]])
+            g.append(range(B), new)
+            check("after append")
+            st = g.stats()
+            assert st["err_bad_token"] == 0 and st["err_bad_slot"] == 0 and st["err_ctx_overflow"] == 0
+        finally:
+            g.close()
