@@ -636,7 +636,7 @@ __device__ __forceinline__ void match_range(const int32_t *__restrict__ sa, cons
 // (token, parent) among these chains until they end or K is reached: a merge that needs no
 // frontier traffic.  Returns false (and changes nothing) if the frontier does not have that form.
 //
-// The chains are merged as whole sequences, one after the other (taking the best head among k
+// Few chains are merged as whole sequences, one after the other (taking the best head among k
 // chains equals merging them pairwise, because (token, parent) keys are distinct).  Merging a
 // sequence X with a chain Y under "take the head with the lower (token, parent)": element x_t
 // leaves after exactly r(t) elements of Y, where r(t) is the first j >= r(t-1) at which y_j
@@ -648,7 +648,13 @@ __device__ __forceinline__ void match_range(const int32_t *__restrict__ sa, cons
 // elements of Y fill the positions left over, in order.  At most 63 nodes are taken per call
 // (one 64-token window per chain: its head plus 63 tokens), the caller comes back for more.
 // Per-chain state lives in the lanes of vector registers (lane q: chain q).
-constexpr int TIE_MAX = 12;
+constexpr int TIE_MAX = 64;
+#ifndef SD_KWAY_MIN
+#define SD_KWAY_MIN 4
+#endif
+// From this many chains on the merge goes step by step over all chains at once (below); fewer
+// chains are merged as whole sequences.  4 measured best on the synthetic workloads (2, 3, 6, 10 tried).
+constexpr int KWAY_MIN = SD_KWAY_MIN;
 
 __device__ __forceinline__ uint64_t ballot64(bool pred) { return __builtin_amdgcn_ballot_w64(pred); }
 // v with lane `idx` replaced by the uniform value `val`
@@ -694,6 +700,80 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         wsync();
     }
     const int n0 = uni(n), KK = uni(K);
+    if (j >= KWAY_MIN) {
+        // Many chains: one pass that takes the lowest head each step.  The heads sit
+        // in the lanes with their rank among the heads (0 = lowest key); a step takes the
+        // head of rank 0, moves every other rank up, and ranks the chain's next element among
+        // the others with one ballot.  That element's parent is the node just taken, the
+        // highest index so far, so on equal tokens every older head goes first: the ballot
+        // needs tokens only.  The chains' upcoming tokens sit in LDS (the staging windows'
+        // space, handed back afterwards), W per chain.
+        int jp2 = 1;
+        while (jp2 < j) jp2 <<= 1;
+        const int wlog = 31 - __clz(TC_TOKENS / jp2), W = 1 << wlog;
+        bool alive = lane < j;
+        int32_t htok = ctokv, hpar = cparv, hdep = cdepv;
+        const int32_t pos0 = cposv + cdepv;  // text index of the token of the chain's element 1
+        int32_t e = 0, wbase = 0;            // head = element e; window = text offsets [wbase, wbase + W)
+        auto fill = [&]() {
+            wsync();
+            const int total = j << wlog;
+            for (int b0 = 0; b0 < total; b0 += 64) {
+                const int idx = b0 + lane, q = (idx >> wlog) & 63;
+                const int32_t pq = __shfl(pos0, q), wq = __shfl(wbase, q);  // all lanes take part
+                if (idx < total) {
+                    sg.tc[idx] = text[(int64_t)pq + wq + (idx & (W - 1))];
+                    SD_CNT(4);
+                }
+            }
+            wsync();
+        };
+        fill();
+        int32_t rank = 0;
+        for (int q = 0; q < j; q++) {
+            const int32_t kt = __builtin_amdgcn_readlane(htok, q), kp = __builtin_amdgcn_readlane(hpar, q);
+            rank += (kt < htok || (kt == htok && kp < hpar)) ? 1 : 0;
+        }
+        int32_t nexttok = alive ? sg.tc[lane << wlog] : -1;  // token of element e + 1
+        int nn = n0;
+        double tot = total;
+        bool deep = false;
+        while (nn < KK) {
+            const uint64_t first = ballot64(alive && rank == 0);
+            if (!first) break;  // no chain left
+            const int w = __ffsll((unsigned long long)first) - 1;
+            const int32_t wtok = __builtin_amdgcn_readlane(htok, w), wpar = __builtin_amdgcn_readlane(hpar, w),
+                          wdep = __builtin_amdgcn_readlane(hdep, w);
+            if (lane == 0) { t_tok[nn] = wtok; t_par[nn] = wpar; t_score[nn] = s; }
+            SD_CNT(lane == 0 ? 8 : 0);
+            tot += s;
+            if (wdep >= D) deep = true;
+            const int32_t nt = __builtin_amdgcn_readlane(nexttok, w);
+            const bool on = nt >= 0 && wdep < D;  // the chain has a next element
+            if (alive) rank -= 1;
+            const bool me = lane == w;
+            if (me) { htok = nt; hpar = nn; hdep = wdep + 1; e += 1; alive = on; }
+            if (on) {
+                if (__builtin_amdgcn_readlane(e - wbase, w) >= W) {  // its window is used up
+                    wbase = e;
+                    fill();
+                }
+                if (me) nexttok = sg.tc[(lane << wlog) + (e - wbase)];
+                const bool older_first = alive && !me && htok <= nt;
+                const int nr = __popcll(ballot64(older_first));
+                if (alive && !me && !older_first) rank += 1;
+                if (me) rank = nr;
+            }
+            nn++;
+        }
+        wsync();
+        if (lane < 64) sg.cb[lane] = CB_NONE;  // the staged token windows were overwritten
+        wsync();
+        n = nn;
+        total = tot;
+        if (deep) deepest = true;
+        return true;
+    }
     const int room = KK - n0 < 63 ? KK - n0 : 63;
     // chain q as a sequence: element 0 is the frontier entry, element k its k-th descendant
     // (the token at child index cdep + k - 1); `alen` = how many elements exist
