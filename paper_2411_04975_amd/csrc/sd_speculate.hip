@@ -656,6 +656,18 @@ constexpr int TIE_MAX = 64;
 // chains are merged as whole sequences.  4 measured best on the synthetic workloads (2, 3, 6, 10 tried).
 constexpr int KWAY_MIN = SD_KWAY_MIN;
 
+// total + s + s + ... (n times), added one by one in that order like the sequential sum of node
+// scores it stands for
+__device__ __forceinline__ double add_times(double total, double s, int n) {
+    int i = 0;
+    for (; i + 8 <= n; i += 8) {
+        total += s; total += s; total += s; total += s;
+        total += s; total += s; total += s; total += s;
+    }
+    for (; i < n; i++) total += s;
+    return total;
+}
+
 __device__ __forceinline__ uint64_t ballot64(bool pred) { return __builtin_amdgcn_ballot_w64(pred); }
 // v with lane `idx` replaced by the uniform value `val`
 __device__ __forceinline__ int32_t set_lane(int32_t val, int idx, int32_t v) {
@@ -812,6 +824,20 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         // well.  Lanes the loop never reached keep myr = 64 (dropped).
         int r = 0;
         int32_t myr = 64;
+        if (q == 1) {
+            // X is still a plain chain: x_t's predecessor is x_(t-1), which left after r(t-1)
+            // elements of Y, so among the j >= r(t-1) still in question an equal token wins
+            // only at j = r(t-1); for x_0 the given parents decide, and only y_0 can win
+            const uint64_t tie0 = yinit < __builtin_amdgcn_readlane(zinit, 0) ? 1ull : 0ull;
+            for (int t = 0; t < lz && t + r < room; t++) {  // r < 63 inside the loop
+                const int32_t xt = __builtin_amdgcn_readlane(zt, t);
+                const uint64_t lt = ballot64(yt < xt), eq = ballot64(yt == xt);
+                const uint64_t wins = (lt | (eq & (t ? 1ull << r : tie0))) & ymask;
+                const uint64_t rest = ~(wins >> r);
+                r = rest ? r + __ffsll((unsigned long long)rest) - 1 : 64;
+                myr = set_lane(r, t, myr);
+            }
+        } else
         for (int t = 0; t < lz && t + r < room; t++) {
             const int32_t xt = __builtin_amdgcn_readlane(zt, t);
             uint64_t lt = ballot64(yt < xt) & ymask;
@@ -861,7 +887,7 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         t_tok[n0 + lane] = zt; t_par[n0 + lane] = zprev < 0 ? zinit : n0 + zprev; t_score[n0 + lane] = s;
         SD_CNT(8);
     }
-    for (int i = 0; i < lz; i++) total += s;
+    total = add_times(total, s, lz);
     const int nn = n0 + lz;
     // per chain: how many elements were taken and where the last of them went
     int32_t usedv = 0, lastv = 0;
@@ -1238,7 +1264,7 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
                             t_score[n + lane] = best.s;
                             SD_CNT(8 * m);
                         }
-                        for (int i = 0; i < L; i++) total += best.s;
+                        total = add_times(total, best.s, L);
                         cur += L;
                         n += L;
                         d += L;
