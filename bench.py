@@ -323,6 +323,7 @@ def main():
     for _ in range(3):
         sd.sd_speculate(ctx, d_slots, trees)
     rt, khz = sd.sd_debug_read_request_ticks(ctx, B)
+    ut = sd.sd_debug_read_unit_ticks(ctx, B)   # [B, 2, P, 4] microseconds
     sd.sd_debug_profile_read(ctx)
     sd.sd_debug_profile(ctx, 0)
     us = 1e3 / max(khz, 1)
@@ -335,6 +336,17 @@ def main():
     def pct(a, q):
         return float(np.percentile(a, q))
 
+    # the requests that finish last decide the kernel's duration: what their longest unit was
+    slowest = []
+    for b_ in np.argsort(req_end)[::-1][:4]:
+        src_, p_ = np.unravel_index(int(np.argmax(ut[b_, :, :, 3])), ut[b_, :, :, 3].shape)
+        slowest.append({"request": int(b_), "finished_at": float(req_end[b_]),
+                        "occurrences_and_matches_done": float(rt[b_, 0, 1] * us),
+                        "runs": int(rt[b_, 0, 5]), "longest_wave_in_runs": float(runs_us[b_].max()),
+                        "longest_unit": {"index": "request" if src_ else "global", "p": int(p_) + 1,
+                                         "root_children_at": float(ut[b_, src_, p_, 2]),
+                                         "done_at": float(ut[b_, src_, p_, 3])}})
+
     latency_profile = {
         "note": "wall-clock marks (100 MHz) inside the timing variant of k_speculate, batch %d, "
                 "one workgroup of %d waves per request; microseconds" % (B, nw),
@@ -343,6 +355,7 @@ def main():
         "longest_wave_in_runs": {"p50": pct(runs_us.max(axis=1), 50), "p90": pct(runs_us.max(axis=1), 90),
                                  "max": float(runs_us.max())},
         "request_finished_at": {"p50": pct(req_end, 50), "p90": pct(req_end, 90), "max": float(req_end.max())},
+        "slowest_requests": slowest,
         "runs_per_request_mean": float(rt[:, 0, 5].mean()),
         "last_token_occurrences_in_context": {"mean": float(rt[:, 0, 6].mean()), "max": int(rt[:, 0, 6].max())},
     }

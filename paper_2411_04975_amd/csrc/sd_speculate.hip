@@ -419,6 +419,10 @@ __device__ __forceinline__ void frontier_put(Frontier &f, int hole, bool cand, d
 constexpr int TC_TOKENS = SD_TC_TOKENS;
 constexpr int CB_NONE = -(1 << 30);
 constexpr int CHAIN_MAX_M = 8;  // widest node the unary-run shortcut looks at
+#ifndef SD_MED_MAX
+#define SD_MED_MAX 256
+#endif
+constexpr int MED_MAX = SD_MED_MAX;  // widest node whose suffixes are all read (a multiple of 64)
 
 struct Stage {
     int32_t *pos, *cb, *tc;  // LDS: [64], [64], [TC_TOKENS]
@@ -501,6 +505,67 @@ __device__ __forceinline__ void push_children(Frontier &f, int hole, Stage &sg, 
         double sc = c == dn ? ps : ps * ((double)c / den);  // x / x == 1 and ps * 1 == ps exactly
         bool cand = start && tok >= 0 && sc >= min_score;
         frontier_put(f, hole, cand, sc, tok, parent, lo + lane, lo + e, d + 1);
+        return;
+    }
+    if (m <= MED_MAX) {
+        // Medium node: read the next token of every suffix (all loads in flight together) and
+        // take the children from the run boundaries, 64 suffixes at a time.  A run that is
+        // still open at the end of a group of 64 is carried into the next group.
+        frontier_close(f, hole);
+        int32_t tk[MED_MAX / 64];
+        int64_t ps_[MED_MAX / 64];
+#pragma unroll
+        for (int c = 0; c < MED_MAX / 64; c++) {
+            const int32_t i = lo + c * 64 + lane;
+            ps_[c] = i < hi ? sa[i] : 0;
+        }
+        int32_t ended = 0;
+#pragma unroll
+        for (int c = 0; c < MED_MAX / 64; c++) {
+            const bool in = lo + c * 64 + lane < hi;
+            tk[c] = in ? text[ps_[c] + d] : 0x7fffffff;
+            if (in) SD_CNT(8);
+            ended += __popcll(__ballot(in && tk[c] < 0));
+        }
+        const int32_t dn = den_mode ? m - ended : m;
+        if (dn == 0) return;
+        const double den = (double)dn;
+        bool open = false;  // the carried run: token and first position
+        int32_t otok = 0, olb = 0;
+#pragma unroll
+        for (int c = 0; c < MED_MAX / 64; c++) {
+            const int32_t base = lo + c * 64;
+            if (base >= hi) break;
+            const bool in = base + lane < hi, lastgrp = base + 64 >= hi;
+            const int32_t tok = tk[c];
+            int32_t prev = __shfl_up(tok, 1);
+            if (lane == 0) prev = c == 0 ? (int32_t)0x80000000 : __builtin_amdgcn_readlane(tk[c > 0 ? c - 1 : 0], 63);
+            const bool start = in && tok != prev;
+            const uint64_t S = __ballot(start);
+            if (open && (S || lastgrp)) {  // the carried run ends at the first start of this group
+                const int32_t ub = S ? base + __ffsll((unsigned long long)S) - 1 : hi;
+                const int32_t cnt = ub - olb;
+                const double sc = cnt == dn ? ps : ps * ((double)cnt / den);
+                frontier_put(f, -1, lane == 0 && otok >= 0 && sc >= min_score, sc, otok, parent, olb, ub,
+                             d + 1);
+                open = false;
+            }
+            if (S) {
+                const uint64_t above = lane == 63 ? 0ull : (S >> (lane + 1));
+                const bool closed = above != 0 || lastgrp;
+                const int32_t e = above ? base + lane + 1 + (__ffsll((unsigned long long)above) - 1) : hi;
+                const int32_t cnt = e - (base + lane);
+                const double sc = cnt == dn ? ps : ps * ((double)cnt / den);
+                const bool cand = start && closed && tok >= 0 && sc >= min_score;
+                frontier_put(f, -1, cand, sc, tok, parent, base + lane, e, d + 1);
+                if (!lastgrp) {  // the last run of the group stays open
+                    const int ll = 63 - __clzll((unsigned long long)S);
+                    open = true;
+                    otok = __builtin_amdgcn_readlane(tok, ll);
+                    olb = base + ll;
+                }
+            }
+        }
         return;
     }
     // Wide node: a child that can still reach min_score has at least c_min occurrences, so its
@@ -723,67 +788,94 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         int jp2 = 1;
         while (jp2 < j) jp2 <<= 1;
         const int wlog = 31 - __clz(TC_TOKENS / jp2), W = 1 << wlog;
-        bool alive = lane < j;
-        int32_t htok = ctokv, hpar = cparv, hdep = cdepv;
+        // Per chain (lane q < j): the head's token, parent and depth, its rank, and the tokens
+        // of the next two elements.  Tokens compare as unsigned numbers, which puts the end
+        // marker (-1) above every real token: a chain whose next element does not exist (end
+        // of the text, or the depth bound) gets the marker as its head, which is how it dies;
+        // lanes >= j start dead.  Dead heads rank behind all live ones.
+        const uint32_t DEAD = 0xffffffffu;
+        const bool chain = lane < j;
+        uint32_t htok = chain ? (uint32_t)ctokv : DEAD;
+        int32_t hpar = cparv, hdep = chain ? cdepv : 0;
         const int32_t pos0 = cposv + cdepv;  // text index of the token of the chain's element 1
-        int32_t e = 0, wbase = 0;            // head = element e; window = text offsets [wbase, wbase + W)
+        const int base = (chain ? lane : 0) << wlog;
+        int32_t abase = 0;
+        uint32_t nexttok = DEAD, n2 = DEAD, cand = DEAD;
+        // token windows: W tokens per chain from the element after its head on
         auto fill = [&]() {
             wsync();
             const int total = j << wlog;
+            const int32_t adv = hdep - cdepv;  // elements of the chain taken so far
             for (int b0 = 0; b0 < total; b0 += 64) {
                 const int idx = b0 + lane, q = (idx >> wlog) & 63;
-                const int32_t pq = __shfl(pos0, q), wq = __shfl(wbase, q);  // all lanes take part
+                const int32_t pq = __shfl(pos0, q), aq = __shfl(adv, q);  // all lanes take part
                 if (idx < total) {
-                    sg.tc[idx] = text[(int64_t)pq + wq + (idx & (W - 1))];
+                    sg.tc[idx] = text[(int64_t)pq + aq + (idx & (W - 1))];
                     SD_CNT(4);
                 }
             }
             wsync();
+            abase = base + 1 - hdep;
+            nexttok = chain ? (uint32_t)sg.tc[base] : DEAD;
+            n2 = (uint32_t)sg.tc[base + 1];
+            cand = hdep < D ? nexttok : DEAD;
         };
-        fill();
-        int32_t rank = 0;
-        for (int q = 0; q < j; q++) {
-            const int32_t kt = __builtin_amdgcn_readlane(htok, q), kp = __builtin_amdgcn_readlane(hpar, q);
-            rank += (kt < htok || (kt == htok && kp < hpar)) ? 1 : 0;
+        int32_t rank = 1 << 20;
+        if (chain) {
+            rank = 0;
+            for (int q = 0; q < j; q++) {
+                const uint32_t kt = (uint32_t)__builtin_amdgcn_readlane(ctokv, q);
+                const int32_t kp = __builtin_amdgcn_readlane(cparv, q);
+                rank += (kt < htok || (kt == htok && kp < hpar)) ? 1 : 0;
+            }
         }
-        int32_t nexttok = alive ? sg.tc[lane << wlog] : -1;  // token of element e + 1
         int nn = n0;
         double tot = total;
-        bool deep = false;
-        while (nn < KK) {
-            const uint64_t first = ballot64(alive && rank == 0);
-            if (!first) break;  // no chain left
-            const int w = __ffsll((unsigned long long)first) - 1;
-            const int32_t wtok = __builtin_amdgcn_readlane(htok, w), wpar = __builtin_amdgcn_readlane(hpar, w),
-                          wdep = __builtin_amdgcn_readlane(hdep, w);
-            if (lane == 0) { t_tok[nn] = wtok; t_par[nn] = wpar; t_score[nn] = s; }
-            SD_CNT(lane == 0 ? 8 : 0);
-            tot += s;
-            if (wdep >= D) deep = true;
-            const int32_t nt = __builtin_amdgcn_readlane(nexttok, w);
-            const bool on = nt >= 0 && wdep < D;  // the chain has a next element
-            if (alive) rank -= 1;
-            const bool me = lane == w;
-            if (me) { htok = nt; hpar = nn; hdep = wdep + 1; e += 1; alive = on; }
-            if (on) {
-                if (__builtin_amdgcn_readlane(e - wbase, w) >= W) {  // its window is used up
-                    wbase = e;
-                    fill();
-                }
-                if (me) nexttok = sg.tc[(lane << wlog) + (e - wbase)];
-                const bool older_first = alive && !me && htok <= nt;
-                const int nr = __popcll(ballot64(older_first));
-                if (alive && !me && !older_first) rank += 1;
-                if (me) rank = nr;
+        bool done = false;
+        // a chain moves by at most one element per step and looks two elements ahead
+        const int burst = W - 2 < 64 ? W - 2 : 64;
+        while (nn < KK && !done) {
+            fill();
+            const int lim = KK - nn < burst ? KK - nn : burst;
+            int32_t otok = 0, opar = 0;  // lane k: the node taken in step k of this burst
+            int k = 0;
+            for (; k < lim; k++) {
+                const uint64_t first = ballot64(rank == 0);
+                if (!first) { done = true; break; }
+                const int w = __ffsll((unsigned long long)first) - 1;
+                const uint32_t wtok = (uint32_t)__builtin_amdgcn_readlane((int32_t)htok, w);
+                if (wtok == DEAD) { done = true; break; }  // no chain left
+                const int32_t wpar = __builtin_amdgcn_readlane(hpar, w);
+                const uint32_t nt = (uint32_t)__builtin_amdgcn_readlane((int32_t)cand, w);
+                otok = set_lane((int32_t)wtok, k, otok);
+                opar = set_lane(wpar, k, opar);
+                tot += s;
+                // The new head's parent is the node just taken, the highest index so far: among
+                // equal tokens every other head goes first.
+                const bool me = lane == w;
+                const bool older = !me && htok <= nt;
+                const int nr = __popcll(ballot64(older));
+                rank = me ? nr : rank - (older ? 1 : 0);
+                htok = me ? nt : htok;
+                hpar = me ? nn + k : hpar;
+                hdep += me ? 1 : 0;
+                nexttok = me ? n2 : nexttok;
+                n2 = (uint32_t)sg.tc[abase + hdep];
+                cand = hdep < D ? nexttok : DEAD;
             }
-            nn++;
+            if (lane < k) {
+                t_tok[nn + lane] = otok; t_par[nn + lane] = opar; t_score[nn + lane] = s;
+                SD_CNT(8);
+            }
+            nn += k;
         }
+        // a head of depth D that was taken left its chain at depth D + 1
+        if (ballot64(chain && hdep > D)) deepest = true;
         wsync();
         if (lane < 64) sg.cb[lane] = CB_NONE;  // the staged token windows were overwritten
         wsync();
         n = nn;
         total = tot;
-        if (deep) deepest = true;
         return true;
     }
     const int room = KK - n0 < 63 ? KK - n0 : 63;
