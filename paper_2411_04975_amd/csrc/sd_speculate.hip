@@ -297,29 +297,71 @@ __device__ __forceinline__ bool key_better(const Key &a, const Key &b) {
     return a.par < b.par;
 }
 
-__device__ __forceinline__ Key key_shfl_xor(const Key &k, int o) {
-    Key r;
-    r.s = __shfl_xor(k.s, o);
-    r.tok = __shfl_xor(k.tok, o);
-    r.par = __shfl_xor(k.par, o);
-    r.idx = __shfl_xor(k.idx, o);
-    return r;
-}
-
 struct Frontier {
     double *score;
     int32_t *tok, *par, *lo, *hi, *dep;
     int n, cap;
 };
 
+// Wave-wide maximum in every lane.  Inside a row of 16 lanes the values meet through four
+// data-parallel moves (lane ^ 1, lane ^ 2, 7 - lane within 8, 15 - lane within 16); the four
+// row results are then read out as scalars.
+template <int CTRL>
+__device__ __forceinline__ int32_t dpp_move(int32_t v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+#ifndef SD_PICK_SCAN_MAX
+#define SD_PICK_SCAN_MAX 3
+#endif
+constexpr int PICK_SCAN_MAX = SD_PICK_SCAN_MAX;
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    uint32_t o;
+    o = (uint32_t)dpp_move<DPP_XOR1>((int32_t)v); v = o > v ? o : v;
+    o = (uint32_t)dpp_move<DPP_XOR2>((int32_t)v); v = o > v ? o : v;
+    o = (uint32_t)dpp_move<DPP_HALF_MIRROR>((int32_t)v); v = o > v ? o : v;
+    o = (uint32_t)dpp_move<DPP_MIRROR>((int32_t)v); v = o > v ? o : v;
+    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 0),
+                   b = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 16),
+                   c = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 32),
+                   d = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 48);
+    const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_move_f64(double v) {
+    const int32_t lo = dpp_move<CTRL>(__double2loint(v)), hi = dpp_move<CTRL>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double wave_max_f64(double v) {  // no NaNs among the inputs
+    double o;
+    o = dpp_move_f64<DPP_XOR1>(v); v = o > v ? o : v;
+    o = dpp_move_f64<DPP_XOR2>(v); v = o > v ? o : v;
+    o = dpp_move_f64<DPP_HALF_MIRROR>(v); v = o > v ? o : v;
+    o = dpp_move_f64<DPP_MIRROR>(v); v = o > v ? o : v;
+    double r = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 0),
+                                __builtin_amdgcn_readlane(__double2loint(v), 0));
+#pragma unroll
+    for (int l = 16; l < 64; l += 16) {
+        const double x = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
+                                          __builtin_amdgcn_readlane(__double2loint(v), l));
+        r = x > r ? x : r;
+    }
+    return r;
+}
+
 // Best (want_best) or worst entry of the frontier, slot `skip` left out; every lane returns
-// the same key.  Small frontiers (the usual case) are scanned by all lanes alike with
-// broadcast LDS reads; larger ones take one entry per lane and a butterfly.
+// the same key (idx < 0: there is none).  Lane l looks at the entries l, l + 64, ...; across
+// the lanes the extreme score is found first, and only if several lanes hold it the extreme
+// token among those, then the extreme parent.
 __device__ __forceinline__ Key frontier_pick(const Frontier &f, bool want_best, int skip) {
     const int lane = threadIdx.x & 63;
     Key mine;
     mine.idx = -1; mine.s = 0.0; mine.tok = 0; mine.par = 0;
-    if (f.n <= 6) {
+    if (f.n <= PICK_SCAN_MAX) {  // a handful of entries: every lane scans them all (broadcast reads)
         for (int i = 0; i < f.n; i++) {
             if (i == skip) continue;
             Key k;
@@ -336,17 +378,35 @@ __device__ __forceinline__ Key frontier_pick(const Frontier &f, bool want_best, 
         k.s = f.score[i]; k.tok = f.tok[i]; k.par = f.par[i]; k.idx = i;
         if (mine.idx < 0 || (want_best ? key_better(k, mine) : key_better(mine, k))) mine = k;
     }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        Key other = key_shfl_xor(mine, o);
-        bool take;
-        if (other.idx < 0) take = false;
-        else if (mine.idx < 0) take = true;
-        else take = want_best ? key_better(other, mine) : key_better(mine, other);
-        if (take) mine = other;
+    const bool valid = mine.idx >= 0;
+    // scores are positive and finite; tokens are >= 0 and parents >= -1 in the frontier.  The
+    // worst entry has the lowest score, then the highest token, then the highest parent.
+    const double sv = valid ? (want_best ? mine.s : -mine.s) : -__longlong_as_double(0x7ff0000000000000ll);
+    const double sx = wave_max_f64(sv);
+    uint64_t T = __ballot(valid && sv == sx);
+    if (T & (T - 1)) {
+        const uint32_t tv = (uint32_t)mine.tok, tk = want_best ? ~tv : tv;
+        const bool in1 = (T >> lane) & 1;
+        const uint32_t tx = wave_max_u32(in1 ? tk : 0u);
+        T = __ballot(in1 && tk == tx);
+        if (T & (T - 1)) {
+            const uint32_t pv = (uint32_t)(mine.par + 1), pk = want_best ? ~pv : pv;
+            const bool in2 = (T >> lane) & 1;
+            const uint32_t px = wave_max_u32(in2 ? pk : 0u);
+            T = __ballot(in2 && pk == px);
+        }
     }
-    mine.s = uni(mine.s); mine.tok = uni(mine.tok); mine.par = uni(mine.par); mine.idx = uni(mine.idx);
-    return mine;
+    Key r;
+    r.idx = -1; r.s = 0.0; r.tok = 0; r.par = 0;
+    if (T) {
+        const int w = __ffsll((unsigned long long)T) - 1;
+        r.s = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(mine.s), w),
+                               __builtin_amdgcn_readlane(__double2loint(mine.s), w));
+        r.tok = __builtin_amdgcn_readlane(mine.tok, w);
+        r.par = __builtin_amdgcn_readlane(mine.par, w);
+        r.idx = __builtin_amdgcn_readlane(mine.idx, w);
+    }
+    return r;
 }
 
 // close the slot freed by the node just taken: the last entry moves into it
@@ -471,6 +531,31 @@ __device__ __forceinline__ int stage_node(Stage &sg, const int32_t *__restrict__
         mycb = d;
     }
     return mycb;
+}
+
+// Lane l: the token that all m staged suffixes from slot0 on hold at depth d + l, or -2 if they
+// differ there or a window does not reach that far (m <= M).  All window bases are read first,
+// then all tokens: two rounds of LDS reads in flight together instead of 2 m dependent ones
+// (the slots past m repeat the last suffix).
+template <int M>
+__device__ __forceinline__ int32_t common_token(const Stage &sg, int slot0, int m, int d, int W) {
+    const int lane = threadIdx.x & 63;
+    int32_t off[M], v[M];
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        const int ii = i < m ? i : m - 1;
+        off[i] = d + lane - sg.cb[slot0 + ii];
+    }
+#pragma unroll
+    for (int i = 0; i < M; i++) {
+        const int ii = i < m ? i : m - 1;
+        const int o = off[i] < W ? off[i] : W - 1;
+        v[i] = sg.tc[((slot0 + ii) << sg.wlog) + o];
+    }
+    int32_t tk = off[0] < W ? v[0] : -2;
+#pragma unroll
+    for (int i = 1; i < M; i++) tk = (off[i] < W && v[i] == tk) ? tk : -2;
+    return tk;
 }
 
 // Children of the node [lo, hi) at depth d (its path has d tokens), as frontier candidates with
@@ -1335,12 +1420,9 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
             if (n < K && d < p.D && m <= CHAIN_MAX_M) {
                 stage_node(sg, sa, text, blo, m, d);
                 const int slot0 = blo - sg.lo, W = 1 << sg.wlog;
-                int32_t tk = -2;
-                for (int i = 0; i < m; i++) {
-                    int off = d + lane - sg.cb[slot0 + i];
-                    int32_t v = off < W ? sg.tc[((slot0 + i) << sg.wlog) + off] : -2;
-                    tk = (i == 0 || v == tk) ? v : -2;
-                }
+                const int32_t tk = m <= CHAIN_MAX_M / 2
+                                       ? common_token<CHAIN_MAX_M / 2>(sg, slot0, m, d, W)
+                                       : common_token<CHAIN_MAX_M>(sg, slot0, m, d, W);
                 int lim = K - n < p.D - d ? K - n : p.D - d;
                 uint64_t ok = __ballot(tk >= 0 && lane < lim);
                 int L = ~ok ? __ffsll((unsigned long long)~ok) - 1 : 64;
