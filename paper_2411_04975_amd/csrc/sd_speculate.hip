@@ -353,17 +353,16 @@ __device__ __forceinline__ double wave_max_f64(double v) {  // no NaNs among the
     return r;
 }
 
-// Best (want_best) or worst entry of the frontier, slot `skip` left out; every lane returns
+// Best (want_best) or worst entry of the frontier; every lane returns
 // the same key (idx < 0: there is none).  Lane l looks at the entries l, l + 64, ...; across
 // the lanes the extreme score is found first, and only if several lanes hold it the extreme
 // token among those, then the extreme parent.
-__device__ __forceinline__ Key frontier_pick(const Frontier &f, bool want_best, int skip) {
+__device__ __forceinline__ Key frontier_pick(const Frontier &f, bool want_best) {
     const int lane = threadIdx.x & 63;
     Key mine;
     mine.idx = -1; mine.s = 0.0; mine.tok = 0; mine.par = 0;
     if (f.n <= PICK_SCAN_MAX) {  // a handful of entries: every lane scans them all (broadcast reads)
         for (int i = 0; i < f.n; i++) {
-            if (i == skip) continue;
             Key k;
             k.s = f.score[i]; k.tok = f.tok[i]; k.par = f.par[i]; k.idx = i;
             if (mine.idx < 0 || (want_best ? key_better(k, mine) : key_better(mine, k))) mine = k;
@@ -373,7 +372,6 @@ __device__ __forceinline__ Key frontier_pick(const Frontier &f, bool want_best, 
         return mine;
     }
     for (int i = lane; i < f.n; i += 64) {
-        if (i == skip) continue;
         Key k;
         k.s = f.score[i]; k.tok = f.tok[i]; k.par = f.par[i]; k.idx = i;
         if (mine.idx < 0 || (want_best ? key_better(k, mine) : key_better(mine, k))) mine = k;
@@ -457,7 +455,7 @@ __device__ __forceinline__ void frontier_put(Frontier &f, int hole, bool cand, d
         if (f.n < f.cap) {
             s = f.n++;
         } else {
-            Key worst = frontier_pick(f, false, -1);
+            Key worst = frontier_pick(f, false);
             if (key_better(nk, worst)) s = worst.idx;
         }
         if (s >= 0 && lane == 0) {
@@ -1392,9 +1390,16 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
                              nb);
         if (TICKS) tick_root = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(f.n & 0);
         while (n < K && f.n > 0) {
-            const Key best = frontier_pick(f, true, -1);
+            const Key best = frontier_pick(f, true);
             if (best.s < p.min_score) break;
-            if (!p.linear &&
+            // How many entries hold the top score: several may be tied chains; a single one
+            // is strictly above everything else in the frontier.
+            int ntop = 0;
+            for (int i0 = 0; i0 < f.n; i0 += 64) {
+                const int i = i0 + lane;
+                ntop += __popcll(__ballot(i < f.n && f.score[i] == best.s));
+            }
+            if (ntop >= 2 && !p.linear &&
                 tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok, t_par, t_score,
                                    deepest, nb))
                 continue;
@@ -1414,10 +1419,11 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
             }
             // Unary run: while all suffixes of the node agree on the next token and none has
             // ended, the node has exactly one child, with the node's own score (count ratio 1).
-            // If that score is strictly above everything else in the frontier, the greedy
-            // rule must take that child next, and so on down the run: take the run at once.
+            // If that score is strictly above everything else in the frontier (no other entry
+            // shares the top score), the greedy rule must take that child next, and so on down
+            // the run: take the run at once.
             const int32_t m = bhi - blo;
-            if (n < K && d < p.D && m <= CHAIN_MAX_M) {
+            if (n < K && d < p.D && m <= CHAIN_MAX_M && (ntop == 1 || p.linear)) {
                 stage_node(sg, sa, text, blo, m, d);
                 const int slot0 = blo - sg.lo, W = 1 << sg.wlog;
                 const int32_t tk = m <= CHAIN_MAX_M / 2
@@ -1427,23 +1433,16 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
                 uint64_t ok = __ballot(tk >= 0 && lane < lim);
                 int L = ~ok ? __ffsll((unsigned long long)~ok) - 1 : 64;
                 if (L > 0) {
-                    bool dominant = f.n <= 1;
-                    if (!dominant) {
-                        Key second = frontier_pick(f, true, bi);
-                        dominant = second.s < best.s;
+                    if (lane < L) {
+                        t_tok[n + lane] = tk; t_par[n + lane] = cur + lane;
+                        t_score[n + lane] = best.s;
+                        SD_CNT(8 * m);
                     }
-                    if (dominant) {
-                        if (lane < L) {
-                            t_tok[n + lane] = tk; t_par[n + lane] = cur + lane;
-                            t_score[n + lane] = best.s;
-                            SD_CNT(8 * m);
-                        }
-                        total = add_times(total, best.s, L);
-                        cur += L;
-                        n += L;
-                        d += L;
-                        if (d >= p.D) deepest = true;
-                    }
+                    total = add_times(total, best.s, L);
+                    cur += L;
+                    n += L;
+                    d += L;
+                    if (d >= p.D) deepest = true;
                 }
             }
             if (n < K)
