@@ -248,13 +248,17 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
         }
     }
     __syncthreads();
-    if (tid == 0) {  // nothing below reads cnt before the closing barrier
-        int acc = 0;
-        for (int l = p.P; l >= 1; l--) {
-            acc += sh.cnt[l];
-            sh.cnt[l] = acc;
+    if (tid < 64) {  // cnt[l] becomes the sum over l' >= l (lane l - 1 holds cnt[l]); nothing
+                     // below reads cnt before the closing barrier
+        const bool mine = lane < p.P;
+        int c = mine ? sh.cnt[lane + 1] : 0;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int u = __shfl_down(c, o);
+            if (lane + o < 64) c += u;
         }
-        sh.cnt[0] = m;
+        if (mine) sh.cnt[lane + 1] = c;
+        if (lane == 0) sh.cnt[0] = m;
     }
     if (m > 0) {
         const int depth = p.D - 1;
