@@ -155,11 +155,13 @@ struct WgShared {
 // tokens before it agree with the context's tail, capped at P), sorted by what follows them.
 // The occurrences with L >= p, in that order, are the sorted suffix list below the pattern of
 // length p.  Ends with a workgroup barrier.
-// `between` runs after the first round of scan loads has been issued and before their results
-// are looked at: independent work (the global matches) that hides behind them.
-template <bool STATS, class Between>
+// Independent work of the caller (the global matches) hides the latencies in here: `pre` runs
+// right after the first round of scan loads has been issued (it issues the caller's own first
+// loads), `between` after this wave has dealt with its part of the scan, while other waves may
+// still be at it.
+template <bool STATS, class Pre, class Between>
 __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, int t, const int32_t *__restrict__ x,
-                                    int2 *s_sort, WgShared &sh, unsigned &nb, Between between) {
+                                    int2 *s_sort, WgShared &sh, unsigned &nb, Pre pre, Between between) {
     const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
     int2 *occ = p.occ + (int64_t)b * p.max_ctx;
     if (tid == 0) { sh.m = 0; sh.next = 0; }
@@ -177,8 +179,8 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
         if (q < nq) SD_CNT(16);
     }
     const int32_t last = t > 0 ? x[t - 1] : 0;
-    between();
-    __syncthreads();
+    pre();
+    __syncthreads();  // the counters above are set
     if (t > 0) {
         for (int q0 = 0; q0 < nq; q0 += 4 * nthr) {
             if (q0 > 0) {
@@ -196,15 +198,14 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                           h3 = v[k].w == last;
                 const int nh = h0 + h1 + h2 + h3;
                 if (__ballot(nh > 0)) {
-                    int inc = nh;  // inclusive prefix over the lanes of the wave
-#pragma unroll
-                    for (int o = 1; o < 64; o <<= 1) {
-                        int u = __shfl_up(inc, o);
-                        if (lane >= o) inc += u;
-                    }
+                    // hits in the lanes below this one: nh <= 4, one ballot per bit of it
+                    const uint64_t b0 = __ballot(nh & 1), b1 = __ballot(nh & 2), b2 = __ballot(nh & 4);
+                    const uint64_t lt = lanemask_lt();
+                    const int below = __popcll(b0 & lt) + 2 * __popcll(b1 & lt) + 4 * __popcll(b2 & lt);
+                    const int all = __popcll(b0) + 2 * __popcll(b1) + 4 * __popcll(b2);
                     int off = 0;
-                    if (lane == 63) off = atomicAdd(&sh.m, inc);
-                    off = __shfl(off, 63) + inc - nh;
+                    if (lane == 0) off = atomicAdd(&sh.m, all);
+                    off = uni(off) + below;
                     // the first OCC_LDS_SORT hits are also kept in LDS, where they are sorted
                     const int es[4] = {e0, e0 + 1, e0 + 2, e0 + 3};
                     const int hs[4] = {h0, h1, h2, h3};
@@ -219,6 +220,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
             }
         }
     }
+    between();
     __syncthreads();
     const int m = sh.m;
     const bool in_lds = m <= OCC_LDS_SORT;
@@ -1495,18 +1497,28 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
     const int t = slot_ok ? uni(p.r_len[slot]) : 0;
     const int32_t *x = p.r_text + (int64_t)(slot_ok ? slot : 0) * p.r_stride;
 
-    // MatchPattern on the global index for every pattern length, spread over the waves, runs
-    // while the first loads of the context scan are in flight
+    // MatchPattern on the global index for every pattern length, spread over the waves: the
+    // pattern tokens are fetched together with the context scan's first loads, and the dependent
+    // loads of the matching itself follow once the wave has looked at its part of the scan
     const int P = p.P;
     const uint64_t wg0 = TICKS ? wall_clock64() : 0;
+    // lane k: pattern token k of the wave's first two pattern lengths
+    int32_t wkA0 = 0, wkB0 = 0;
     request_occurrences<STATS>(p, b, t, x, reinterpret_cast<int2 *>(smem), sh, nb, [&]() {
+        const int plA = 1 + wave, plB = plA + nw;
+        if (plA <= P && plA <= t && p.g_N > 0 && lane < plA) wkA0 = x[t - plA + lane];
+        if (plB <= P && plB <= t && p.g_N > 0 && lane < plB) wkB0 = x[t - plB + lane];
+    }, [&]() {
         for (int plA = 1 + wave; plA <= P; plA += 2 * nw) {
             const int plB = plA + nw;  // a wave takes its pattern lengths two at a time
             const bool okA = plA <= t && p.g_N > 0, okB = plB <= P && plB <= t && p.g_N > 0;
             int32_t loA = 0, hiA = 0, loB = 0, hiB = 0;
-            // lane k: pattern token k
-            const int32_t wkA = okA && lane < plA ? x[t - plA + lane] : 0;
-            const int32_t wkB = okB && lane < plB ? x[t - plB + lane] : 0;
+            const bool first = plA == 1 + wave;
+            int32_t wkA = wkA0, wkB = wkB0;
+            if (!first) {
+                wkA = okA && lane < plA ? x[t - plA + lane] : 0;
+                wkB = okB && lane < plB ? x[t - plB + lane] : 0;
+            }
             if (okA && lane < plA) SD_CNT(4);
             if (okB && lane < plB) SD_CNT(4);
             if (okA && okB && plB <= 32)
