@@ -90,7 +90,10 @@ def main():
                     help="enqueue every step from the host instead of replaying a captured HIP graph")
     ap.add_argument("--separate-calls", action="store_true",
                     help="end the step with sd_accept, the collection glue and sd_index_append "
-                         "as three launches instead of sd_accept_append")
+                         "as three launches instead of one fused launch")
+    ap.add_argument("--two-launches", action="store_true",
+                    help="sd_speculate and sd_accept_append as two launches per step instead of "
+                         "sd_accept_append_speculate (the end of a step and the next draft in one)")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -202,12 +205,23 @@ def main():
         verifier.targets(trees.n_nodes, trees.parents, d_future, d_pos, d_target, advance=d_alen)
         sd.sd_accept_append(ctx, trees, d_slots, d_target, d_alen, d_apath, d_bonus)
 
-    step = step_separate if args.separate_calls else step_fused
+    def step_next():
+        # One library launch per step: the trees hold the current drafts; the verifier stand-in
+        # produces their target tokens; sd_accept_append_speculate ends the step (acceptance,
+        # append) and drafts the next trees from the extended contexts.  Per step the same
+        # work as above: one speculation, one verification, one acceptance, one append.
+        verifier.targets(trees.n_nodes, trees.parents, d_future, d_pos, d_target, advance=d_alen)
+        sd.sd_accept_append_speculate(ctx, trees, d_slots, d_target, d_alen, d_apath, d_bonus)
+
+    one_launch = not (args.separate_calls or args.two_launches)
+    step = step_separate if args.separate_calls else step_fused if args.two_launches else step_next
 
     def reset():
         build_requests()
         d_pos.zero_()
         d_alen.fill_(-1)
+        if one_launch:  # the first drafts: every later step leaves the next ones behind
+            sd.sd_speculate(ctx, d_slots, trees)
 
     # The step is launch-bound from Python (five launches of a few microseconds each), so the
     # timed loop replays a HIP graph captured from one step: the same kernels, enqueued by the
@@ -360,10 +374,19 @@ def main():
         "last_token_occurrences_in_context": {"mean": float(rt[:, 0, 6].mean()), "max": int(rt[:, 0, 6].max())},
     }
 
-    exp_ms = prof["speculate"]["ms"] / max(prof["speculate"]["launches"], 1)
+    # the dominant kernel: k_speculate, in the one-launch step its form that accepts and appends
+    # first (the counting variant exists for the separate kernels, which the library falls
+    # back to while counting; the bytes of acceptance and append are added by formula: tree
+    # tokens and parents, target tokens, path, two result words, appended tokens)
+    kname = "accept_speculate" if one_launch else "speculate"
+    exp_ms = prof[kname]["ms"] / max(prof[kname]["launches"], 1)
     exp_bytes = cnt["speculate"]["algo_bytes"] / max(cnt["speculate"]["launches"], 1)
+    if one_launch:
+        exp_bytes += B * (8.0 * mean_nodes + 4.0 * (mn + 1) + 4.0 * mn + 8.0 + 4.0 * (mean_accept + 1))
     achieved = exp_bytes / (exp_ms * 1e-3) / 1e9 if exp_ms > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": "k_speculate", "achieved": achieved, "peak": HBM_PEAK_GBS,
+    roofline = {"bound": "hbm",
+                "kernel": "k_speculate<accept and append first>" if one_launch else "k_speculate",
+                "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "traffic": _traffic_from_profiles("k_speculate", w.name),
                 "algo_bytes_per_launch": exp_bytes, "avg_launch_ms": exp_ms,
@@ -395,7 +418,10 @@ def main():
                                           "doc_len", "zipf_s")},
                    "step": ("sd_speculate + simulated verifier + sd_accept + sd_index_append"
                             if args.separate_calls else
-                            "sd_speculate + simulated verifier + sd_accept_append")},
+                            "sd_speculate + simulated verifier + sd_accept_append"
+                            if args.two_launches else
+                            "simulated verifier + sd_accept_append_speculate (verification of "
+                            "the current drafts, acceptance, append, next drafts)")},
         "index_build_tokens_per_s": n_tokens / (g_build_ms * 1e-3),
         "index_build_ms": g_build_ms, "request_build_ms": r_build_ms,
         "request_build_tokens_per_s": B * ctx_len / (r_build_ms * 1e-3),

@@ -215,6 +215,21 @@ sd_status sd_accept_append(sd_ctx *ctx, sd_trees trees, const int32_t *d_slot_id
                            const int32_t *d_target_tokens, int32_t *d_accept_len,
                            int32_t *d_accept_path, int32_t *d_bonus, void *hip_stream);
 
+/* sd_accept_append, and in the same launch sd_speculate for the same slots
+ * from the contexts just extended: the end of one decoding step and the
+ * beginning of the next (Section 2: verification, acceptance and the next
+ * speculation follow each other for every request), with one kernel launch
+ * between two calls of the target model instead of two.  `trees` is both
+ * input (the drafts that were verified against d_target_tokens) and output
+ * (the next drafts): every request's old tree is read before its new one is
+ * written.  Results, flags and limits are those of sd_accept_append followed
+ * by sd_speculate(ctx, d_slot_ids, batch, trees): trees.max_nodes must be
+ * floor(alpha*P) <= max_nodes <= 256, slot ids distinct. */
+sd_status sd_accept_append_speculate(sd_ctx *ctx, sd_trees trees, const int32_t *d_slot_ids,
+                                     int32_t batch, const int32_t *d_target_tokens,
+                                     int32_t *d_accept_len, int32_t *d_accept_path,
+                                     int32_t *d_bonus, void *hip_stream);
+
 /* Synchronises the device and copies counters and sticky flags to the host. */
 sd_status sd_get_stats(sd_ctx *ctx, sd_stats *host_out);
 
@@ -231,7 +246,7 @@ sd_status sd_get_stats(sd_ctx *ctx, sd_stats *host_out);
 enum {
     SD_K_SPECULATE = 0, SD_K_ACCEPT = 1, SD_K_APPEND = 2, SD_K_REQ_BUILD = 3, SD_K_SORT_HIST = 4,
     SD_K_SORT_SCAN = 5, SD_K_SORT_SCATTER = 6, SD_K_BUILD_OTHER = 7, SD_K_INSERT = 8,
-    SD_K_COUNT = 9
+    SD_K_ACCEPT_SPECULATE = 9, SD_K_COUNT = 10
 };
 #define SD_PROF_MAX_SPANS 8192
 typedef struct {

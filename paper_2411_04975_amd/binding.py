@@ -53,7 +53,7 @@ class _Stats(C.Structure):
 
 
 KERNEL_NAMES = ["speculate", "accept", "append", "req_build", "sort_hist", "sort_scan",
-                "sort_scatter", "build_other", "insert"]
+                "sort_scatter", "build_other", "insert", "accept_speculate"]
 
 
 class _Profile(C.Structure):
@@ -97,6 +97,8 @@ def _load():
     L.sd_accept.argtypes = [vp, _Trees, C.c_int32, vp, vp, vp, vp, vp]
     L.sd_accept_append.restype = C.c_int
     L.sd_accept_append.argtypes = [vp, _Trees, vp, C.c_int32, vp, vp, vp, vp, vp]
+    L.sd_accept_append_speculate.restype = C.c_int
+    L.sd_accept_append_speculate.argtypes = [vp, _Trees, vp, C.c_int32, vp, vp, vp, vp, vp]
     L.sd_get_stats.restype = C.c_int
     L.sd_get_stats.argtypes = [vp, C.POINTER(_Stats)]
     L.sd_debug_profile.restype = C.c_int
@@ -280,6 +282,23 @@ def sd_accept_append(ctx: _Ctx, trees: Trees, slot_ids: torch.Tensor, target_tok
                                     _ptr(accept_len, i32, ctx, batch, "accept_len"),
                                     _ptr(accept_path, i32, ctx, batch * mn, "accept_path"),
                                     _ptr(bonus, i32, ctx, batch, "bonus"), _stream(stream, ctx))
+    _check(ctx, code)
+
+
+def sd_accept_append_speculate(ctx: _Ctx, trees: Trees, slot_ids: torch.Tensor,
+                               target_tokens: torch.Tensor, accept_len: torch.Tensor,
+                               accept_path: torch.Tensor, bonus: torch.Tensor, stream=None) -> None:
+    """sd_accept_append of the verified drafts in `trees`, then sd_speculate of the next drafts into
+    `trees`, one launch."""
+    i32 = torch.int32
+    mn = trees.max_nodes
+    batch = int(slot_ids.numel())
+    code = _load().sd_accept_append_speculate(
+        ctx.handle, trees._struct(ctx, batch), _ptr(slot_ids, i32, ctx, batch, "slot_ids"), batch,
+        _ptr(target_tokens, i32, ctx, batch * (mn + 1), "target_tokens"),
+        _ptr(accept_len, i32, ctx, batch, "accept_len"),
+        _ptr(accept_path, i32, ctx, batch * mn, "accept_path"),
+        _ptr(bonus, i32, ctx, batch, "bonus"), _stream(stream, ctx))
     _check(ctx, code)
 
 

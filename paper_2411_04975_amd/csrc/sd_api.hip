@@ -246,6 +246,25 @@ sd_status sd_accept_append(sd_ctx *c, sd_trees trees, const int32_t *d_slot_ids,
                                  d_accept_path, d_bonus, (hipStream_t)hip_stream);
 }
 
+sd_status sd_accept_append_speculate(sd_ctx *c, sd_trees trees, const int32_t *d_slot_ids,
+                                     int32_t batch, const int32_t *d_target_tokens,
+                                     int32_t *d_accept_len, int32_t *d_accept_path,
+                                     int32_t *d_bonus, void *hip_stream) {
+    if (!c) return SD_ERR_INVALID_ARG;
+    if (batch < 0) return fail(c, SD_ERR_INVALID_ARG, "negative batch");
+    if (batch > c->cfg.max_batch_slots) return fail(c, SD_ERR_CAPACITY, "more slots than configured");
+    if (batch == 0) return SD_OK;
+    if (!d_slot_ids || !trees_ok(trees) || !d_target_tokens || !d_accept_len || !d_accept_path ||
+        !d_bonus)
+        return fail(c, SD_ERR_INVALID_ARG, "null pointer");
+    if (trees.max_nodes < c->max_nodes)
+        return fail(c, SD_ERR_INVALID_ARG, "trees.max_nodes below floor(alpha*P)");
+    if (trees.max_nodes > 256) return fail(c, SD_ERR_INVALID_ARG, "trees.max_nodes above 256");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
+    return sd_accept_append_speculate_impl(c, trees, d_slot_ids, batch, d_target_tokens, d_accept_len,
+                                           d_accept_path, d_bonus, (hipStream_t)hip_stream);
+}
+
 sd_status sd_get_stats(sd_ctx *c, sd_stats *o) {
     if (!c || !o) return SD_ERR_INVALID_ARG;
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");

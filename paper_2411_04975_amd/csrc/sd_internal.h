@@ -95,6 +95,10 @@ sd_status sd_accept_impl(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t
                          int32_t *d_accept_len, int32_t *d_accept_path, int32_t *d_bonus,
                          hipStream_t st);
 
+sd_status sd_accept_append_speculate_impl(sd_ctx *c, sd_trees trees, const int32_t *d_slot_ids,
+                                          int32_t batch, const int32_t *d_target,
+                                          int32_t *d_accept_len, int32_t *d_accept_path,
+                                          int32_t *d_bonus, hipStream_t st);
 sd_status sd_accept_append_impl(sd_ctx *c, sd_trees trees, const int32_t *d_slot_ids, int32_t batch,
                                 const int32_t *d_target, int32_t *d_accept_len,
                                 int32_t *d_accept_path, int32_t *d_bonus, hipStream_t st);

@@ -144,6 +144,8 @@ __device__ __forceinline__ void occ_sort(int2 *arr, uint64_t *key, int m, const 
 struct WgShared {
     int m;           // occurrences of the context's last token
     int next;        // head of the unit queue
+    int t_new;       // context length after the append of the fused form
+    int newtok[260]; // fused form: the tokens appended in this launch
     int cnt[72];     // [l]: occurrences whose left-extension is l; afterwards: is at least l
     int g_lo[65], g_hi[65];  // [p]: suffix-array range of the pattern of length p (global index)
     double best_s[16];
@@ -154,34 +156,52 @@ struct WgShared {
 // workgroup: the occurrences of the last token, each with its left-extension L(e) (how many
 // tokens before it agree with the context's tail, capped at P), sorted by what follows them.
 // The occurrences with L >= p, in that order, are the sorted suffix list below the pattern of
-// length p.  Ends with a workgroup barrier.
-// Independent work of the caller (the global matches) hides the latencies in here: `pre` runs
-// right after the first round of scan loads has been issued (it issues the caller's own first
-// loads), `between` after this wave has dealt with its part of the scan, while other waves may
-// still be at it.
-template <bool STATS, class Pre, class Between>
-__device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, int t, const int32_t *__restrict__ x,
-                                    int2 *s_sort, WgShared &sh, unsigned &nb, Pre pre, Between between) {
-    const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
-    int2 *occ = p.occ + (int64_t)b * p.max_ctx;
+// length p.
+// Two steps with a workgroup barrier of the caller between them: occ_scan_issue sets the
+// counters and issues the first round of scan loads over the t_old tokens the context is known
+// to hold at that time; request_occurrences does the rest for the context of t >= t_old tokens,
+// of which those from t_old on (appended meanwhile by the first wave) are taken from `newtok`
+// in LDS.  `between` is independent work of the caller (the global matches), run after this
+// wave has dealt with its part of the scan, while other waves may still be at it.
+struct ScanState {
+    int4 v[4];         // the first round of scan loads
+    int32_t last_old;  // token t_old - 1
+};
+
+template <bool STATS>
+__device__ __forceinline__ void occ_scan_issue(int t_old, const int32_t *__restrict__ x, WgShared &sh,
+                                               ScanState &st, unsigned &nb) {
+    const int tid = threadIdx.x, nthr = blockDim.x;
     if (tid == 0) { sh.m = 0; sh.next = 0; }
     if (tid < 72) sh.cnt[tid] = 0;
-    // Coalesced scan, 16 bytes per load, four loads in flight per thread.  Tokens past the
-    // context end are end markers, which never equal the last token, so the tail needs no
-    // bounds test; rows start 256-byte aligned.
+    // Coalesced scan, 16 bytes per load, four loads in flight per thread; rows start 256-byte
+    // aligned.
     const int4 *x4 = reinterpret_cast<const int4 *>(x);
-    const int nq = t > 0 ? (t + 3) >> 2 : 0;
-    int4 v[4];
+    const int nq = t_old > 0 ? (t_old + 3) >> 2 : 0;
 #pragma unroll
     for (int k = 0; k < 4; k++) {
         int q = k * nthr + tid;
-        v[k] = q < nq ? x4[q] : make_int4(-1, -1, -1, -1);
+        st.v[k] = q < nq ? x4[q] : make_int4(-1, -1, -1, -1);
         if (q < nq) SD_CNT(16);
     }
-    const int32_t last = t > 0 ? x[t - 1] : 0;
-    pre();
-    __syncthreads();  // the counters above are set
+    st.last_old = t_old > 0 ? x[t_old - 1] : 0;
+}
+
+template <bool STATS, class Between>
+__device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, int t, int t_old,
+                                    const int32_t *newtok, const int32_t *__restrict__ x,
+                                    int2 *s_sort, WgShared &sh, ScanState &st, unsigned &nb,
+                                    Between between) {
+    const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
+    int2 *occ = p.occ + (int64_t)b * p.max_ctx;
+    const int4 *x4 = reinterpret_cast<const int4 *>(x);
+    const int nq = t_old > 0 ? (t_old + 3) >> 2 : 0;
+    int4(&v)[4] = st.v;
+    const int n_new = t - t_old;
+    const int32_t last = n_new > 0 ? newtok[n_new - 1] : st.last_old;
     if (t > 0) {
+        // the first t_old tokens, from memory (what sits behind them in a loaded word is not
+        // looked at: end markers, or appended tokens that the load may have missed)
         for (int q0 = 0; q0 < nq; q0 += 4 * nthr) {
             if (q0 > 0) {
 #pragma unroll
@@ -194,8 +214,8 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
 #pragma unroll
             for (int k = 0; k < 4; k++) {
                 const int e0 = 4 * (q0 + k * nthr + tid);
-                const int h0 = v[k].x == last, h1 = v[k].y == last, h2 = v[k].z == last,
-                          h3 = v[k].w == last;
+                const int h0 = v[k].x == last && e0 < t_old, h1 = v[k].y == last && e0 + 1 < t_old,
+                          h2 = v[k].z == last && e0 + 2 < t_old, h3 = v[k].w == last && e0 + 3 < t_old;
                 const int nh = h0 + h1 + h2 + h3;
                 if (__ballot(nh > 0)) {
                     // hits in the lanes below this one: nh <= 4, one ballot per bit of it
@@ -216,6 +236,22 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                             if (off < OCC_LDS_SORT) s_sort[off].x = es[c];
                             off++;
                         }
+                }
+            }
+        }
+        // the appended tokens, from LDS
+        if (tid < 64) {
+            for (int i0 = 0; i0 < n_new; i0 += 64) {
+                const int i = i0 + lane;
+                const uint64_t hm = __ballot(i < n_new && newtok[i] == last);
+                if (hm) {
+                    int off = 0;
+                    if (lane == 0) off = atomicAdd(&sh.m, (int)__popcll(hm));
+                    off = uni(off) + __popcll(hm & lanemask_lt());
+                    if ((hm >> lane) & 1) {
+                        occ[off].x = t_old + i;
+                        if (off < OCC_LDS_SORT) s_sort[off].x = t_old + i;
+                    }
                 }
             }
         }
@@ -1468,6 +1504,164 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
     return n;
 }
 
+struct AppendArgs {
+    const int32_t *slot_ids;
+    int32_t *r_text, *r_len;
+    int64_t stride;
+    int32_t max_ctx, max_slots, vocab;
+    int32_t *err;
+};
+
+// What sd_accept hands back besides the trees it reads.
+struct AcceptArgs {
+    const int32_t *target;
+    int32_t *accept_len, *accept_path, *bonus;
+};
+
+// Acceptance for request b on one wavefront (max_nodes <= 256): node j is accepted iff its
+// token equals the target token at its parent's position and its parent is accepted, which
+// pointer jumping over the parent links settles in at most eight rounds.  s_tgt[257], s_anc[256]
+// and s_ok[256] are LDS of the calling wave.  With APPEND the accepted tokens and the bonus
+// token go behind the slot's context (and into s_new in LDS if that is given).  Returns the
+// slot's context length afterwards (0 for a bad slot), which only the APPEND form looks up.
+template <bool APPEND>
+__device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_nodes,
+                                           const int32_t *__restrict__ tokens,
+                                           const int32_t *__restrict__ parents, int max_nodes,
+                                           const AcceptArgs &aa, const AppendArgs &ap, int32_t *s_tgt,
+                                           int32_t *s_anc, int32_t *s_ok, int32_t *s_new) {
+    const int lane = threadIdx.x & 63;
+    const int32_t *tok = tokens + (int64_t)b * max_nodes, *par = parents + (int64_t)b * max_nodes;
+    const int32_t *tgt = aa.target + (int64_t)b * (max_nodes + 1);
+    int32_t *path = aa.accept_path + (int64_t)b * max_nodes;
+    // every load of the tree and the targets is issued before the node count is looked at
+    int n = n_nodes[b];
+    int32_t mt[4], mp[4];
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        int j = lane + 64 * r;
+        mt[r] = j < max_nodes ? tok[j] : -1;
+        mp[r] = j < max_nodes ? par[j] : -1;
+    }
+    for (int i = lane; i <= max_nodes; i += 64) s_tgt[i] = tgt[i];
+    if (n > max_nodes) n = max_nodes;
+    if (n < 0) n = 0;
+#pragma unroll
+    for (int r = 0; r < 4; r++)
+        if (lane + 64 * r >= n) { mt[r] = -1; mp[r] = -1; }
+    wsync();
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        int j = lane + 64 * r;
+        if (j < n) {
+            const bool wellformed = mp[r] >= -1 && mp[r] < j;
+            s_ok[j] = wellformed && mt[r] == s_tgt[mp[r] + 1];
+            s_anc[j] = wellformed ? mp[r] : -1;
+        }
+    }
+    wsync();
+    for (int round = 0; round < 8; round++) {  // 2^8 >= the deepest possible path
+        int32_t ok[4], an[4];
+        bool open = false;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            int j = lane + 64 * r;
+            ok[r] = 0; an[r] = -1;
+            if (j < n) {
+                const int a = s_anc[j];
+                ok[r] = s_ok[j];
+                if (a >= 0) {
+                    ok[r] &= s_ok[a];
+                    an[r] = s_anc[a];
+                    open = true;
+                }
+            }
+        }
+        if (!__ballot(open)) break;
+        wsync();
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            int j = lane + 64 * r;
+            if (j < n) { s_ok[j] = ok[r]; s_anc[j] = an[r]; }
+        }
+        wsync();
+    }
+    uint64_t am[4];
+    int L = 0, last = -1;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        int j = lane + 64 * r;
+        am[r] = __ballot(j < n && s_ok[j]);
+        if (am[r]) last = 64 * r + 63 - __clzll((unsigned long long)am[r]);
+        L += __popcll(am[r]);
+    }
+    const int32_t bon = s_tgt[last + 1];
+    int32_t *row = nullptr;
+    int32_t old = 0;
+    bool slot_ok = false;
+    if (APPEND) {  // L accepted tokens and the bonus token go behind the slot's context
+        const int32_t slot = ap.slot_ids[b];
+        if (slot < 0 || slot >= ap.max_slots) {
+            if (lane == 0) atomicOr(&ap.err[SD_DEVERR_SLOT], 1);
+        } else {
+            slot_ok = true;
+            old = ap.r_len[slot];
+            if ((int64_t)old + L + 1 > ap.max_ctx) {
+                if (lane == 0) atomicOr(&ap.err[SD_DEVERR_CTX], 1);
+            } else {
+                row = ap.r_text + (int64_t)slot * ap.stride;
+            }
+        }
+    }
+    int done = 0;
+#pragma unroll
+    for (int r = 0; r < 4; r++) {
+        int j = lane + 64 * r;
+        if ((am[r] >> lane) & 1ull) {
+            const int at = done + __popcll(am[r] & lanemask_lt());
+            path[at] = j;
+            if (APPEND && row) {
+                int32_t t = mt[r];
+                if (t < 0 || t >= ap.vocab) {
+                    atomicOr(&ap.err[SD_DEVERR_TOKEN], 1);
+                    t = 0;
+                }
+                row[old + at] = t;
+                if (s_new) s_new[at] = t;
+            }
+        }
+        done += __popcll(am[r]);
+    }
+    for (int i = L + lane; i < max_nodes; i += 64) path[i] = -1;
+    if (lane == 0) {
+        aa.accept_len[b] = L;
+        aa.bonus[b] = bon;
+        if (APPEND && row) {
+            int32_t t = bon;
+            if (t < 0 || t >= ap.vocab) {
+                atomicOr(&ap.err[SD_DEVERR_TOKEN], 1);
+                t = 0;
+            }
+            row[old + L] = t;
+            if (s_new) s_new[L] = t;
+            ap.r_len[ap.slot_ids[b]] = old + L + 1;
+        }
+    }
+    return !slot_ok ? 0 : (row ? old + L + 1 : old);
+}
+
+template <bool APPEND>
+__global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nodes,
+                                               const int32_t *__restrict__ tokens,
+                                               const int32_t *__restrict__ parents, int max_nodes,
+                                               AcceptArgs aa, AppendArgs ap) {
+    __shared__ int32_t s_tgt[257];
+    __shared__ int32_t s_anc[256];
+    __shared__ int32_t s_ok[256];
+    accept_wave<APPEND>(blockIdx.x, n_nodes, tokens, parents, max_nodes, aa, ap, s_tgt, s_anc, s_ok,
+                        nullptr);
+}
+
 // GenerateCandidateTree for one request per workgroup.  All waves first build the request's
 // occurrence lists together and match the P patterns against the global index; then each wave
 // takes runs of pattern lengths with equal counts from a queue in LDS, longest patterns first,
@@ -1481,9 +1675,14 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
 #define SD_SPEC_OCC 4
 #endif
 
-template <bool STATS, bool TICKS>
+// With ACCEPT the workgroup first settles the verification of the request's previous tree (the
+// one `out` still holds, against aa.target) on its first wave, appends the accepted tokens and
+// the bonus token to the request's context, and then drafts the next tree from the extended
+// context into `out`: the end of one decoding step and the start of the next in one launch.
+template <bool STATS, bool TICKS, bool ACCEPT>
 __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t *__restrict__ slot_ids,
-                                                    sd_trees out, int lds_per_wave) {
+                                                    sd_trees out, int lds_per_wave, AcceptArgs aa,
+                                                    AppendArgs ap) {
     extern __shared__ double smem[];
     __shared__ WgShared sh;
     // the wave index is the same in all lanes: keep it (and every LDS address derived from it)
@@ -1494,21 +1693,47 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
     const int32_t slot = uni(slot_ids[b]);
     const bool slot_ok = slot >= 0 && slot < p.max_slots;
     if (!slot_ok && threadIdx.x == 0) atomicOr(&p.err[SD_DEVERR_SLOT], 1);
-    const int t = slot_ok ? uni(p.r_len[slot]) : 0;
+    // the context length before this launch appends anything
+    const int t_old = slot_ok ? uni(p.r_len[slot]) : 0;
     const int32_t *x = p.r_text + (int64_t)(slot_ok ? slot : 0) * p.r_stride;
 
-    // MatchPattern on the global index for every pattern length, spread over the waves: the
-    // pattern tokens are fetched together with the context scan's first loads, and the dependent
-    // loads of the matching itself follow once the wave has looked at its part of the scan
+    // MatchPattern on the global index for every pattern length, spread over the waves.  The
+    // pattern tokens are fetched together with the context scan's first loads, and the
+    // dependent loads of the matching follow once the wave has looked at its part of the scan.
+    // The fused form starts the scan's loads, settles acceptance and append on the first wave
+    // meanwhile, and fetches the pattern tokens once the appended tokens are in memory.
     const int P = p.P;
     const uint64_t wg0 = TICKS ? wall_clock64() : 0;
+    int2 *const s_sort = reinterpret_cast<int2 *>(smem);
+    ScanState scan;
+    occ_scan_issue<STATS>(t_old, x, sh, scan, nb);
+    int t = t_old;
     // lane k: pattern token k of the wave's first two pattern lengths
     int32_t wkA0 = 0, wkB0 = 0;
-    request_occurrences<STATS>(p, b, t, x, reinterpret_cast<int2 *>(smem), sh, nb, [&]() {
+    auto pattern_tokens = [&]() {
         const int plA = 1 + wave, plB = plA + nw;
         if (plA <= P && plA <= t && p.g_N > 0 && lane < plA) wkA0 = x[t - plA + lane];
         if (plB <= P && plB <= t && p.g_N > 0 && lane < plB) wkB0 = x[t - plB + lane];
-    }, [&]() {
+    };
+    if (ACCEPT) {
+        if (wave == 0) {
+            // LDS that the occurrence sort takes over afterwards
+            int32_t *s_tgt = reinterpret_cast<int32_t *>(smem), *s_anc = s_tgt + 260, *s_ok = s_anc + 256;
+            const int nl = accept_wave<true>(b, out.d_n_nodes, out.d_tokens, out.d_parents,
+                                             out.max_nodes, aa, ap, s_tgt, s_anc, s_ok, sh.newtok);
+            if (lane == 0) sh.t_new = nl;
+        }
+        // The barrier orders the first wave's stores to the row before the other waves' loads
+        // at workgroup scope, which is all that is needed: the waves of a workgroup share one
+        // compute unit and its cache, and only this workgroup touches the row.
+        __syncthreads();
+        t = slot_ok ? uni(sh.t_new) : 0;
+        pattern_tokens();
+    } else {
+        pattern_tokens();
+        __syncthreads();  // the counters of the occurrence list are set
+    }
+    request_occurrences<STATS>(p, b, t, t_old, sh.newtok, x, s_sort, sh, scan, nb, [&]() {
         for (int plA = 1 + wave; plA <= P; plA += 2 * nw) {
             const int plB = plA + nw;  // a wave takes its pattern lengths two at a time
             const bool okA = plA <= t && p.g_N > 0, okB = plB <= P && plB <= t && p.g_N > 0;
@@ -1662,136 +1887,6 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
 // nodes in index order.
 // With APPEND the accepted draft tokens and the bonus token are also written behind the context
 // of the request's slot (what sd_index_append would do with them), in the same launch.
-struct AppendArgs {
-    const int32_t *slot_ids;
-    int32_t *r_text, *r_len;
-    int64_t stride;
-    int32_t max_ctx, max_slots, vocab;
-    int32_t *err;
-};
-
-template <bool APPEND>
-__global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nodes,
-                                               const int32_t *__restrict__ tokens,
-                                               const int32_t *__restrict__ parents, int max_nodes,
-                                               const int32_t *__restrict__ target,
-                                               int32_t *__restrict__ accept_len,
-                                               int32_t *__restrict__ accept_path,
-                                               int32_t *__restrict__ bonus, AppendArgs ap) {
-    __shared__ int32_t s_tgt[257];
-    __shared__ int32_t s_anc[256];
-    __shared__ int32_t s_ok[256];
-    const int lane = threadIdx.x, b = blockIdx.x;
-    int n = n_nodes[b];
-    if (n > max_nodes) n = max_nodes;
-    if (n < 0) n = 0;
-    const int32_t *tok = tokens + (int64_t)b * max_nodes, *par = parents + (int64_t)b * max_nodes;
-    const int32_t *tgt = target + (int64_t)b * (max_nodes + 1);
-    int32_t *path = accept_path + (int64_t)b * max_nodes;
-    int32_t mt[4], mp[4];
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-        int j = lane + 64 * r;
-        mt[r] = j < n ? tok[j] : -1;
-        mp[r] = j < n ? par[j] : -1;
-    }
-    for (int i = lane; i <= max_nodes; i += 64) s_tgt[i] = tgt[i];
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-        int j = lane + 64 * r;
-        if (j < n) {
-            const bool wellformed = mp[r] >= -1 && mp[r] < j;
-            s_ok[j] = wellformed && mt[r] == s_tgt[mp[r] + 1];
-            s_anc[j] = wellformed ? mp[r] : -1;
-        }
-    }
-    __syncthreads();
-    for (int round = 0; round < 8; round++) {  // 2^8 >= the deepest possible path
-        int32_t ok[4], an[4];
-        bool open = false;
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            int j = lane + 64 * r;
-            ok[r] = 0; an[r] = -1;
-            if (j < n) {
-                const int a = s_anc[j];
-                ok[r] = s_ok[j];
-                if (a >= 0) {
-                    ok[r] &= s_ok[a];
-                    an[r] = s_anc[a];
-                    open = true;
-                }
-            }
-        }
-        if (!__ballot(open)) break;
-        __syncthreads();
-#pragma unroll
-        for (int r = 0; r < 4; r++) {
-            int j = lane + 64 * r;
-            if (j < n) { s_ok[j] = ok[r]; s_anc[j] = an[r]; }
-        }
-        __syncthreads();
-    }
-    uint64_t am[4];
-    int L = 0, last = -1;
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-        int j = lane + 64 * r;
-        am[r] = __ballot(j < n && s_ok[j]);
-        if (am[r]) last = 64 * r + 63 - __clzll((unsigned long long)am[r]);
-        L += __popcll(am[r]);
-    }
-    const int32_t bon = s_tgt[last + 1];
-    int32_t *row = nullptr;
-    int32_t old = 0;
-    if (APPEND) {  // L accepted tokens and the bonus token go behind the slot's context
-        const int32_t slot = ap.slot_ids[b];
-        if (slot < 0 || slot >= ap.max_slots) {
-            if (lane == 0) atomicOr(&ap.err[SD_DEVERR_SLOT], 1);
-        } else {
-            old = ap.r_len[slot];
-            if ((int64_t)old + L + 1 > ap.max_ctx) {
-                if (lane == 0) atomicOr(&ap.err[SD_DEVERR_CTX], 1);
-            } else {
-                row = ap.r_text + (int64_t)slot * ap.stride;
-            }
-        }
-    }
-    int done = 0;
-#pragma unroll
-    for (int r = 0; r < 4; r++) {
-        int j = lane + 64 * r;
-        if ((am[r] >> lane) & 1ull) {
-            const int at = done + __popcll(am[r] & lanemask_lt());
-            path[at] = j;
-            if (APPEND && row) {
-                int32_t t = mt[r];
-                if (t < 0 || t >= ap.vocab) {
-                    atomicOr(&ap.err[SD_DEVERR_TOKEN], 1);
-                    t = 0;
-                }
-                row[old + at] = t;
-            }
-        }
-        done += __popcll(am[r]);
-    }
-    for (int i = L + lane; i < max_nodes; i += 64) path[i] = -1;
-    if (lane == 0) {
-        accept_len[b] = L;
-        bonus[b] = bon;
-        if (APPEND && row) {
-            int32_t t = bon;
-            if (t < 0 || t >= ap.vocab) {
-                atomicOr(&ap.err[SD_DEVERR_TOKEN], 1);
-                t = 0;
-            }
-            row[old + L] = t;
-            ap.r_len[ap.slot_ids[b]] = old + L + 1;
-        }
-    }
-}
-
 }  // namespace
 
 sd_status sd_speculate_setup(sd_ctx *c) {
@@ -1805,9 +1900,10 @@ sd_status sd_speculate_setup(sd_ctx *c) {
             hipSuccess || optin <= 0)
         optin = (int)prop.sharedMemPerBlock;
     c->lds_optin = (size_t)optin > sizeof(WgShared) + 256 ? (size_t)optin - sizeof(WgShared) - 256 : 0;
-    const void *kernels[3] = {reinterpret_cast<const void *>(&k_speculate<false, false>),
-                              reinterpret_cast<const void *>(&k_speculate<true, false>),
-                              reinterpret_cast<const void *>(&k_speculate<false, true>)};
+    const void *kernels[4] = {reinterpret_cast<const void *>(&k_speculate<false, false, false>),
+                              reinterpret_cast<const void *>(&k_speculate<true, false, false>),
+                              reinterpret_cast<const void *>(&k_speculate<false, true, false>),
+                              reinterpret_cast<const void *>(&k_speculate<false, false, true>)};
     for (const void *k : kernels)
         if (hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)c->lds_optin) != hipSuccess)
@@ -1815,9 +1911,11 @@ sd_status sd_speculate_setup(sd_ctx *c) {
     return SD_OK;
 }
 
-sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
-                            hipStream_t st) {
-    if (batch == 0) return SD_OK;
+namespace {
+
+// Launches k_speculate; with `aa` the fused form that first accepts and appends.
+sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
+                           const AcceptArgs *aa, hipStream_t st) {
     SpecParams p;
     p.g_text = c->g_text; p.g_sa = c->g_sa; p.g_bucket = c->g_bucket; p.g_tok1 = c->g_tok1;
     p.g_N = (int32_t)c->g_N;
@@ -1851,13 +1949,50 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
     if (lds < OCC_LDS_SORT * (sizeof(int2) + sizeof(uint64_t)))
         lds = OCC_LDS_SORT * (sizeof(int2) + sizeof(uint64_t));
     if (lds > c->lds_optin) return SD_ERR_CAPACITY;
-    {
+    const dim3 grid((unsigned)batch), block(64 * nw);
+    if (aa) {
+        sd_span sp(c, SD_K_ACCEPT_SPECULATE, st);
+        const AppendArgs ap{d_slot_ids, c->r_text, c->r_len, c->r_stride, c->cfg.max_ctx_tokens,
+                            c->cfg.max_batch_slots, c->cfg.vocab, c->d_err};
+        hipLaunchKernelGGL((k_speculate<false, false, true>), grid, block, lds, st, p, d_slot_ids, out,
+                           (int)lds_wave, *aa, ap);
+    } else {
         sd_span sp(c, SD_K_SPECULATE, st);
-        if (stats) hipLaunchKernelGGL((k_speculate<true, false>), dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
-        else if (ticks) hipLaunchKernelGGL((k_speculate<false, true>), dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
-        else hipLaunchKernelGGL((k_speculate<false, false>), dim3((unsigned)batch), dim3(64 * nw), lds, st, p, d_slot_ids, out, (int)lds_wave);
+        const AcceptArgs none{};
+        const AppendArgs nap{};
+        if (stats)
+            hipLaunchKernelGGL((k_speculate<true, false, false>), grid, block, lds, st, p, d_slot_ids,
+                               out, (int)lds_wave, none, nap);
+        else if (ticks)
+            hipLaunchKernelGGL((k_speculate<false, true, false>), grid, block, lds, st, p, d_slot_ids,
+                               out, (int)lds_wave, none, nap);
+        else
+            hipLaunchKernelGGL((k_speculate<false, false, false>), grid, block, lds, st, p, d_slot_ids,
+                               out, (int)lds_wave, none, nap);
     }
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
+}
+
+}  // namespace
+
+sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
+                            hipStream_t st) {
+    if (batch == 0) return SD_OK;
+    return launch_speculate(c, d_slot_ids, batch, out, nullptr, st);
+}
+
+sd_status sd_accept_append_speculate_impl(sd_ctx *c, sd_trees trees, const int32_t *d_slot_ids,
+                                          int32_t batch, const int32_t *d_target,
+                                          int32_t *d_accept_len, int32_t *d_accept_path,
+                                          int32_t *d_bonus, hipStream_t st) {
+    if (batch == 0) return SD_OK;
+    if (c->prof_mode >= 2) {  // the counting and timing variants exist for the separate kernels only
+        const sd_status rc = sd_accept_append_impl(c, trees, d_slot_ids, batch, d_target, d_accept_len,
+                                                   d_accept_path, d_bonus, st);
+        return rc != SD_OK ? rc : sd_speculate_impl(c, d_slot_ids, batch, trees, st);
+    }
+    const AcceptArgs aa{d_target, d_accept_len, d_accept_path, d_bonus};
+    return launch_speculate(c, d_slot_ids, batch, trees, &aa, st);
 }
 
 sd_status sd_accept_impl(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t *d_target,
@@ -1866,8 +2001,8 @@ sd_status sd_accept_impl(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t
     if (batch == 0) return SD_OK;
     sd_span sp(c, SD_K_ACCEPT, st);
     hipLaunchKernelGGL(k_accept<false>, dim3((unsigned)batch), dim3(64), 0, st, trees.d_n_nodes,
-                       trees.d_tokens, trees.d_parents, trees.max_nodes, d_target, d_accept_len,
-                       d_accept_path, d_bonus, AppendArgs{});
+                       trees.d_tokens, trees.d_parents, trees.max_nodes,
+                       AcceptArgs{d_target, d_accept_len, d_accept_path, d_bonus}, AppendArgs{});
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
@@ -1879,7 +2014,7 @@ sd_status sd_accept_append_impl(sd_ctx *c, sd_trees trees, const int32_t *d_slot
     AppendArgs ap{d_slot_ids, c->r_text, c->r_len, c->r_stride, c->cfg.max_ctx_tokens,
                   c->cfg.max_batch_slots, c->cfg.vocab, c->d_err};
     hipLaunchKernelGGL(k_accept<true>, dim3((unsigned)batch), dim3(64), 0, st, trees.d_n_nodes,
-                       trees.d_tokens, trees.d_parents, trees.max_nodes, d_target, d_accept_len,
-                       d_accept_path, d_bonus, ap);
+                       trees.d_tokens, trees.d_parents, trees.max_nodes,
+                       AcceptArgs{d_target, d_accept_len, d_accept_path, d_bonus}, ap);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }

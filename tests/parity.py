@@ -152,6 +152,25 @@ class GpuPath:
         torch.cuda.synchronize()
         return al.cpu().numpy(), ap.cpu().numpy(), bo.cpu().numpy()
 
+    def accept_append_speculate(self, slots, target):
+        """sd_accept_append of the current trees and sd_speculate of the next ones in one launch;
+        returns the accept outputs and the new trees."""
+        torch = self.torch
+        tr = self.trees
+        B, mn = tr.batch, tr.max_nodes
+        d_t = torch.from_numpy(np.ascontiguousarray(target, np.int32)).to(self.dev)
+        al = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        ap = torch.full((B, mn), -7, dtype=torch.int32, device=self.dev)
+        bo = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        self.sd.sd_accept_append_speculate(
+            self.ctx, tr, torch.tensor(list(slots), dtype=torch.int32, device=self.dev), d_t, al, ap, bo)
+        torch.cuda.synchronize()
+        trees = dict(n_nodes=tr.n_nodes.cpu().numpy(), tokens=tr.tokens.cpu().numpy(),
+                     parents=tr.parents.cpu().numpy(), scores=tr.scores.cpu().numpy(),
+                     tree_score=tr.tree_score.cpu().numpy(), match_len=tr.match_len.cpu().numpy(),
+                     source=tr.source.cpu().numpy(), use_draft=tr.use_draft.cpu().numpy())
+        return al.cpu().numpy(), ap.cpu().numpy(), bo.cpu().numpy(), trees
+
     def stats(self):
         return self.sd.sd_get_stats(self.ctx)
 

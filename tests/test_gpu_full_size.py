@@ -149,8 +149,10 @@ def test_streaming_full_sampled_decode_loop():
             tries[b].append(contexts[b])
         pos = np.zeros(B, np.int64)
         accepted = 0
+        got_next = None
         for step in range(steps):
-            got = g.speculate(range(B))
+            got = got_next if got_next is not None else g.speculate(range(B))
+            got_next = None
             _check_properties(got, w)
             sub = [contexts[b] for b in pick]
             want = parity.oracle_speculate_batch(tg, sub, w.D, w.P, w.alpha, w.min_score, mn,
@@ -160,9 +162,14 @@ def test_streaming_full_sampled_decode_loop():
             assert not bad, "\n".join(bad)
             fut = np.stack([w.future[b, pos[b]:pos[b] + mn + 2] for b in range(B)])
             tgt = parity.targets_from_future(got, fut, mn)
-            # odd steps end the way bench.py's step does: accept and append in one launch
-            fused = step % 2 == 1
-            al, ap, bo = g.accept_append(range(B), tgt) if fused else g.accept(tgt)
+            # the three ways to end a step take turns: separate accept and append; both in one
+            # launch; and, as bench.py's step does, both plus the next step's drafts in one launch
+            mode = step % 3
+            fused = mode != 0
+            if mode == 2:
+                al, ap, bo, got_next = g.accept_append_speculate(range(B), tgt)
+            else:
+                al, ap, bo = g.accept_append(range(B), tgt) if fused else g.accept(tgt)
             new = []
             for b in range(B):
                 L = int(al[b])

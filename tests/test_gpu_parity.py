@@ -263,6 +263,75 @@ def test_append_equals_rebuild_and_streaming_loop():
         g.close()
 
 
+def test_fused_step_end_and_next_draft_in_one_launch():
+    """Decode loop in which every step ends with sd_accept_append_speculate: the acceptance, the
+    appended context and the next trees must be those of the oracle, step after step; and a full
+    context makes the fused call raise the overflow flag and draft from the unchanged context."""
+    w = make_workload(scaled("tiny", batch=12, steps=6), seed=9)
+    docs = w.docs()
+    B, mn = w.batch, w.max_nodes
+    contexts = [w.contexts[b].copy() for b in range(B)]
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, w.ctx_len + 6 * (mn + 1),
+                       len(w.corpus) + len(docs))
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), contexts)
+        tg = parity.oracle_global_trie(docs, w.D, w.vocab)
+        tries = []
+        for x in contexts:
+            t = oracle.Trie(w.D)
+            t.append(x)
+            tries.append(t)
+        pos = np.zeros(B, np.int64)
+        got = g.speculate(range(B))
+        total_acc = 0
+        for step in range(6):
+            want = parity.oracle_speculate_batch(tg, contexts, w.D, w.P, w.alpha, w.min_score, mn,
+                                                 request_tries=tries)
+            bad = parity.compare_trees(got, want, "step %d" % step)
+            assert not bad, "\n".join(bad)
+            fut = np.stack([w.future[b, pos[b]:pos[b] + mn + 2] for b in range(B)])
+            tgt = parity.targets_from_future(want, fut, mn)
+            al, ap, bo, got = g.accept_append_speculate(range(B), tgt)
+            for b in range(B):
+                n = int(want["n_nodes"][b])
+                L, path, bonus = oracle.accept(want["tokens"][b, :n], want["parents"][b, :n], tgt[b])
+                assert al[b] == L and bo[b] == bonus and list(ap[b, :L]) == list(path)
+                assert list(ap[b, L:]) == [-1] * (mn - L)
+                new = np.array([int(want["tokens"][b, j]) for j in path] + [int(bonus)], np.int32)
+                tries[b].append(new)
+                contexts[b] = np.concatenate([contexts[b], new])
+                pos[b] += L + 1
+                total_acc += L
+        assert total_acc > 0
+        want = parity.oracle_speculate_batch(tg, contexts, w.D, w.P, w.alpha, w.min_score, mn,
+                                             request_tries=tries)
+        assert not parity.compare_trees(got, want, "after the last step")
+        # the separate calls see the same contexts
+        assert not parity.compare_trees(g.speculate(range(B)), want, "separate speculate")
+        assert g.stats()["err_ctx_overflow"] == 0
+    finally:
+        g.close()
+    g = parity.GpuPath(10, 6, 3, 1.0, 0.1, 2, 16, 100)
+    try:
+        g.build_global([np.array([1, 2, 3, 0, 4], np.int32)])
+        g.build_requests([1], [np.arange(16, dtype=np.int32) % 10])     # slot 1 is full
+        g.speculate([1])
+        tgt = np.zeros((1, g.max_nodes + 1), np.int32)
+        al, ap, bo, got = g.accept_append_speculate([1], tgt)
+        assert g.stats()["err_ctx_overflow"] == 1 and bo[0] == 0
+        want = parity.oracle_speculate_batch(
+            parity.oracle_global_trie([np.array([1, 2, 3, 0, 4], np.int32)], 6, 10),
+            [np.arange(16, dtype=np.int32) % 10], 6, 3, 1.0, 0.1, g.max_nodes)
+        assert not parity.compare_trees(got, want)
+        # a bad slot id: flag raised, empty draft
+        g.speculate([1])
+        al, ap, bo, got = g.accept_append_speculate([7], tgt)
+        assert g.stats()["err_bad_slot"] == 1 and got["n_nodes"][0] == 0
+    finally:
+        g.close()
+
+
 def test_device_flags_bad_token_slot_and_overflow():
     g = parity.GpuPath(10, 6, 3, 1.0, 0.1, 2, 16, 100)
     try:
@@ -312,7 +381,7 @@ def test_decode_step_in_a_hip_graph_matches_eager():
     slots = torch.arange(B, dtype=i32, device=dev)
 
     class Loop:
-        def __init__(self, fused=False):
+        def __init__(self, fused=False, one_launch=False):
             self.ctx = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, B,
                                     w.ctx_len + (steps + 3) * (mn + 1), len(w.corpus) + 64, 0)
             sd.sd_index_build(self.ctx, sd.SD_SCOPE_GLOBAL, None, docs_tok, docs_off, len(w.corpus))
@@ -327,12 +396,21 @@ def test_decode_step_in_a_hip_graph_matches_eager():
             self.newoff = torch.zeros(B + 1, dtype=i32, device=dev)
             self.pos = torch.zeros(B, dtype=i32, device=dev)
             self.fused = fused
-            if fused:
+            self.one_launch = one_launch
+            if fused or one_launch:
                 self.alen.fill_(-1)
+            if one_launch:   # the first drafts; every step leaves the next ones behind
+                sd.sd_speculate(self.ctx, slots, self.trees)
 
         def step(self):
+            if self.one_launch:   # the step bench.py times
+                verifier.targets(self.trees.n_nodes, self.trees.parents, future, self.pos,
+                                 self.target, advance=self.alen)
+                sd.sd_accept_append_speculate(self.ctx, self.trees, slots, self.target, self.alen,
+                                              self.apath, self.bonus)
+                return
             sd.sd_speculate(self.ctx, slots, self.trees)
-            if self.fused:   # the step bench.py times
+            if self.fused:
                 verifier.targets(self.trees.n_nodes, self.trees.parents, future, self.pos,
                                  self.target, advance=self.alen)
                 sd.sd_accept_append(self.ctx, self.trees, slots, self.target, self.alen,
@@ -351,9 +429,13 @@ def test_decode_step_in_a_hip_graph_matches_eager():
                                         t.match_len, t.source, self.alen, self.apath, self.bonus,
                                         self.pos)]
 
-    eager, graphed, fused = Loop(), Loop(), Loop(fused=True)
+    eager, graphed, fused, one = Loop(), Loop(), Loop(fused=True), Loop(one_launch=True)
     try:
         torch.cuda.synchronize()
+        first = one.snapshot()
+        g1 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g1):
+            one.step()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             graphed.step()
@@ -374,6 +456,14 @@ def test_decode_step_in_a_hip_graph_matches_eager():
             gotf = fused.snapshot()
             for a, b in zip(gotf[:10], want[:10]):
                 assert torch.equal(a, b), "fused replay %d differs from the eager step" % i
+            # the step with one library launch: this step's acceptance, and the next step's drafts
+            g1.replay()
+            got1 = one.snapshot()
+            for a, b in zip(first[:7], want[:7]):
+                assert torch.equal(a, b), "one-launch step %d: drafts differ from the eager step" % i
+            for a, b in zip(got1[7:10], want[7:10]):
+                assert torch.equal(a, b), "one-launch step %d: acceptance differs" % i
+            first = got1
             moved += int(want[7].sum())
             # unrelated eager work between replays
             _ = (torch.arange(1000, device=dev) * 2).sum().item()
@@ -382,6 +472,7 @@ def test_decode_step_in_a_hip_graph_matches_eager():
         sd.sd_destroy(eager.ctx)
         sd.sd_destroy(graphed.ctx)
         sd.sd_destroy(fused.ctx)
+        sd.sd_destroy(one.ctx)
 
 
 VARIANTS = [(1, 0), (0, 1), (1, 1)]

@@ -21,7 +21,7 @@ def test_library_exports_every_declared_symbol():
         pytest.skip("libsd.so not built in this checkout")
     lib = C.CDLL(binding.lib_path())
     names = _declared_symbols()
-    assert {"sd_create", "sd_destroy", "sd_index_build", "sd_index_append", "sd_index_insert", "sd_index_entropy", "sd_accept_append",
+    assert {"sd_create", "sd_destroy", "sd_index_build", "sd_index_append", "sd_index_insert", "sd_index_entropy", "sd_accept_append", "sd_accept_append_speculate",
             "sd_speculate", "sd_accept", "sd_get_stats", "sd_last_error"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
