@@ -140,6 +140,69 @@ __device__ __forceinline__ void occ_sort(int2 *arr, uint64_t *key, int m, const 
     }
 }
 
+// Wave-wide maximum in every lane.  Inside a row of 16 lanes the values meet through four
+// data-parallel moves (lane ^ 1, lane ^ 2, 7 - lane within 8, 15 - lane within 16); the four
+// row results are then read out as scalars.
+template <int CTRL>
+__device__ __forceinline__ int32_t dpp_move(int32_t v) {
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+#ifndef SD_PICK_SCAN_MAX
+#define SD_PICK_SCAN_MAX 3
+#endif
+constexpr int PICK_SCAN_MAX = SD_PICK_SCAN_MAX;
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
+    uint32_t o;
+    o = (uint32_t)dpp_move<DPP_XOR1>((int32_t)v); v = o > v ? o : v;
+    o = (uint32_t)dpp_move<DPP_XOR2>((int32_t)v); v = o > v ? o : v;
+    o = (uint32_t)dpp_move<DPP_HALF_MIRROR>((int32_t)v); v = o > v ? o : v;
+    o = (uint32_t)dpp_move<DPP_MIRROR>((int32_t)v); v = o > v ? o : v;
+    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 0),
+                   b = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 16),
+                   c = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 32),
+                   d = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 48);
+    const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
+    return ab > cd ? ab : cd;
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_move_f64(double v) {
+    const int32_t lo = dpp_move<CTRL>(__double2loint(v)), hi = dpp_move<CTRL>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+
+__device__ __forceinline__ double wave_max_f64(double v) {  // no NaNs among the inputs
+    double o;
+    o = dpp_move_f64<DPP_XOR1>(v); v = o > v ? o : v;
+    o = dpp_move_f64<DPP_XOR2>(v); v = o > v ? o : v;
+    o = dpp_move_f64<DPP_HALF_MIRROR>(v); v = o > v ? o : v;
+    o = dpp_move_f64<DPP_MIRROR>(v); v = o > v ? o : v;
+    double r = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 0),
+                                __builtin_amdgcn_readlane(__double2loint(v), 0));
+#pragma unroll
+    for (int l = 16; l < 64; l += 16) {
+        const double x = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
+                                          __builtin_amdgcn_readlane(__double2loint(v), l));
+        r = x > r ? x : r;
+    }
+    return r;
+}
+
+// Inclusive prefix sum over the lanes: four shifted adds inside each row of 16 lanes (a lane
+// without a source adds zero), then the totals of the rows below.
+__device__ __forceinline__ int32_t wave_inclusive_sum(int32_t v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);  // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);  // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);  // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);  // row_shr:8
+    const int32_t t0 = __builtin_amdgcn_readlane(v, 15), t1 = __builtin_amdgcn_readlane(v, 31),
+                  t2 = __builtin_amdgcn_readlane(v, 47);
+    const int row = (threadIdx.x & 63) >> 4;
+    return v + (row >= 1 ? t0 : 0) + (row >= 2 ? t1 : 0) + (row >= 3 ? t2 : 0);
+}
+
 // Workgroup-shared state of one request.
 struct WgShared {
     int m;           // occurrences of the context's last token
@@ -259,6 +322,9 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
     between();
     __syncthreads();
     const int m = sh.m;
+    // A single occurrence is the context's own last token: nothing follows it, so no pattern
+    // has a continuation in this index, and the counts stay at zero, which says just that.
+    if (m <= 1) return;
     const bool in_lds = m <= OCC_LDS_SORT;
     // How far each occurrence extends to the left together with the context's own tail: one
     // occurrence per wave and trip, lane k compares the k-th token before both ends.
@@ -286,16 +352,12 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
         }
     }
     __syncthreads();
-    if (tid < 64) {  // cnt[l] becomes the sum over l' >= l (lane l - 1 holds cnt[l]); nothing
-                     // below reads cnt before the closing barrier
+    if (tid < 64) {  // cnt[l] becomes the sum over l' >= l (lane k holds cnt[P - k], so that a
+                     // prefix sum over the lanes does it); nothing below reads cnt before the
+                     // closing barrier
         const bool mine = lane < p.P;
-        int c = mine ? sh.cnt[lane + 1] : 0;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int u = __shfl_down(c, o);
-            if (lane + o < 64) c += u;
-        }
-        if (mine) sh.cnt[lane + 1] = c;
+        const int c = wave_inclusive_sum(mine ? sh.cnt[p.P - lane] : 0);
+        if (mine) sh.cnt[p.P - lane] = c;
         if (lane == 0) sh.cnt[0] = m;
     }
     if (m > 0) {
@@ -344,56 +406,6 @@ struct Frontier {
     int32_t *tok, *par, *lo, *hi, *dep;
     int n, cap;
 };
-
-// Wave-wide maximum in every lane.  Inside a row of 16 lanes the values meet through four
-// data-parallel moves (lane ^ 1, lane ^ 2, 7 - lane within 8, 15 - lane within 16); the four
-// row results are then read out as scalars.
-template <int CTRL>
-__device__ __forceinline__ int32_t dpp_move(int32_t v) {
-    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
-}
-#ifndef SD_PICK_SCAN_MAX
-#define SD_PICK_SCAN_MAX 3
-#endif
-constexpr int PICK_SCAN_MAX = SD_PICK_SCAN_MAX;
-constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
-
-__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
-    uint32_t o;
-    o = (uint32_t)dpp_move<DPP_XOR1>((int32_t)v); v = o > v ? o : v;
-    o = (uint32_t)dpp_move<DPP_XOR2>((int32_t)v); v = o > v ? o : v;
-    o = (uint32_t)dpp_move<DPP_HALF_MIRROR>((int32_t)v); v = o > v ? o : v;
-    o = (uint32_t)dpp_move<DPP_MIRROR>((int32_t)v); v = o > v ? o : v;
-    const uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 0),
-                   b = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 16),
-                   c = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 32),
-                   d = (uint32_t)__builtin_amdgcn_readlane((int32_t)v, 48);
-    const uint32_t ab = a > b ? a : b, cd = c > d ? c : d;
-    return ab > cd ? ab : cd;
-}
-
-template <int CTRL>
-__device__ __forceinline__ double dpp_move_f64(double v) {
-    const int32_t lo = dpp_move<CTRL>(__double2loint(v)), hi = dpp_move<CTRL>(__double2hiint(v));
-    return __hiloint2double(hi, lo);
-}
-
-__device__ __forceinline__ double wave_max_f64(double v) {  // no NaNs among the inputs
-    double o;
-    o = dpp_move_f64<DPP_XOR1>(v); v = o > v ? o : v;
-    o = dpp_move_f64<DPP_XOR2>(v); v = o > v ? o : v;
-    o = dpp_move_f64<DPP_HALF_MIRROR>(v); v = o > v ? o : v;
-    o = dpp_move_f64<DPP_MIRROR>(v); v = o > v ? o : v;
-    double r = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), 0),
-                                __builtin_amdgcn_readlane(__double2loint(v), 0));
-#pragma unroll
-    for (int l = 16; l < 64; l += 16) {
-        const double x = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), l),
-                                          __builtin_amdgcn_readlane(__double2loint(v), l));
-        r = x > r ? x : r;
-    }
-    return r;
-}
 
 // Best (want_best) or worst entry of the frontier; every lane returns
 // the same key (idx < 0: there is none).  Lane l looks at the entries l, l + 64, ...; across
@@ -1847,12 +1859,23 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
         wt[3] = (uint32_t)(wg3 - wg0); wt[4] = (uint32_t)(wall_clock64() - wg0);
         wt[5] = (uint32_t)nruns; wt[6] = (uint32_t)sh.m; wt[7] = (uint32_t)nw;
     }
+    // the winning wave: top SCORE, then the earliest unit in scan order (lane w looks at wave w;
+    // units are distinct, so the second criterion leaves one wave)
     double ws = 0.0;
     int wo = -1, ww = -1;
-    for (int w = 0; w < nw; w++) {
-        const double s = sh.best_s[w];
-        const int o = sh.best_o[w];
-        if (o >= 0 && (ww < 0 || s > ws || (s == ws && o < wo))) { ws = s; wo = o; ww = w; }
+    {
+        const double s = lane < nw ? sh.best_s[lane] : 0.0;
+        const int o = lane < nw ? sh.best_o[lane] : -1;
+        const bool valid = o >= 0;
+        const double sx = wave_max_f64(valid ? s : -__longlong_as_double(0x7ff0000000000000ll));
+        const bool top = valid && s == sx;
+        const uint32_t ox = wave_max_u32(top ? ~(uint32_t)o : 0u);
+        const uint64_t W = __ballot(top && ~(uint32_t)o == ox);
+        if (W) {
+            ww = __ffsll((unsigned long long)W) - 1;
+            ws = sx;
+            wo = (int)~ox;
+        }
     }
     if (wave == (ww < 0 ? 0 : ww)) {
         const int n = ww < 0 ? 0 : best_n;
