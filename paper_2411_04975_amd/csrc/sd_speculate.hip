@@ -736,19 +736,70 @@ __device__ __forceinline__ void push_children(Frontier &f, int hole, Stage &sg, 
         int32_t prevtok = __shfl_up(tok, 1);
         if (lane == 0) prevtok = k == 0 ? (int32_t)0x80000000 : text[(int64_t)sa[q - stride] + d];
         if (lane == 0 && k != 0) SD_CNT(8);
-        const bool first = in && tok >= 0 && tok != prevtok;
+        const bool change = in && tok != prevtok;
+        const bool first = change && tok >= 0;
+        // The run of a probed token starts in (q - stride, q] and ends behind the last probe
+        // that holds the token: before the next probe if there is one (in this group of 64),
+        // else before hi, which is at most a stride away unless further groups follow.
+        const uint64_t Cm = __ballot(change);
+        const uint64_t above = lane == 63 ? 0ull : (Cm >> (lane + 1));
+        const int n_in = np - k0 < 64 ? (int)(np - k0) : 64;  // probes in this group
+        int nxt = above ? lane + 1 + (__ffsll((unsigned long long)above) - 1) : 64;
+        if (nxt > n_in) nxt = n_in;  // the next probe with another token, or the end of the group
+        const int32_t q_ls = (int32_t)(q + (int64_t)(nxt - 1 - lane) * stride);
+        int32_t lb_lo = q, lb_hi = q, ub_lo = q_ls + 1, ub_hi = hi;  // (hi: the run may go on into the next group)
+        if (k > 0) lb_lo = (int32_t)(q - stride + 1);
+        if (nxt < n_in) ub_hi = (int32_t)(q_ls + stride);
         int32_t lb = q, ub = hi;
-        if (first) {
-            if (k > 0) {  // first position in (q - stride, q] holding tok
-                int32_t l = (int32_t)(q - stride + 1), h = q;
-                while (l < h) {
-                    int32_t mid = l + ((h - l) >> 1);
-                    SD_CNT(8);
-                    if (text[(int64_t)sa[mid] + d] < tok) l = mid + 1; else h = mid;
-                }
-                lb = l;
+        const uint64_t Fm = __ballot(first);
+        const int nf = __popcll(Fm);
+        if (nf > 0 && nf <= 32) {
+            // All 2 nf searches (lower and upper end of every run) side by side: search j gets
+            // G lanes, which probe G points of its interval per round ((G + 1)-ary search).
+            const int G = 64 / (2 * nf);
+            wsync();
+            if (first) sg.tmp[__popcll(Fm & lanemask_lt())] = lane;
+            wsync();
+            const int srch = lane / G, sub = lane - srch * G;
+            const bool act = srch < 2 * nf;
+            const int srcl = act ? sg.tmp[srch >> 1] : 0;
+            const bool upper = srch & 1;
+            const int32_t ctok = __shfl(tok, srcl);
+            // (the shuffles run with all lanes on; the choice between the two ends is the
+            // reading lane's)
+            const int32_t l0 = __shfl(lb_lo, srcl), h0 = __shfl(lb_hi, srcl);
+            const int32_t l1 = __shfl(ub_lo, srcl), h1 = __shfl(ub_hi, srcl);
+            int32_t l = upper ? l1 : l0, h = upper ? h1 : h0;
+            if (!act) { l = 0; h = 0; }
+            const uint64_t gmask = G >= 64 ? ~0ull : ((1ull << G) - 1ull);
+            while (__ballot(l < h)) {
+                const bool go = l < h;
+                const int64_t n = (int64_t)h - l;
+                const int32_t pt = (int32_t)(l + n * (sub + 1) / (G + 1));
+                int32_t v = 0;
+                if (go) v = text[(int64_t)sa[pt] + d];
+                if (go) SD_CNT(8);
+                // the answer is the first position whose token is >= (lower end) or > (upper
+                // end) the run's token: the probes that say "not yet" form a prefix
+                const bool notyet = go && (upper ? v <= ctok : v < ctok);
+                const uint64_t nm = __ballot(notyet);
+                const int cf = __popcll((nm >> (srch * G)) & gmask);
+                const int32_t nl = cf > 0 ? (int32_t)(l + n * cf / (G + 1)) + 1 : l;
+                const int32_t nh = cf < G ? (int32_t)(l + n * (cf + 1) / (G + 1)) : h;
+                if (go) { l = nl; h = nh; }
             }
-            int32_t l = q + 1, h = hi;  // first position after q holding a larger token
+            const int r = __popcll(Fm & lanemask_lt());
+            const int32_t lbv = __shfl(l, (2 * r) * G & 63), ubv = __shfl(l, (2 * r + 1) * G & 63);
+            if (first) { lb = lbv; ub = ubv; }
+        } else if (first) {
+            int32_t l = lb_lo, h = lb_hi;
+            while (l < h) {
+                int32_t mid = l + ((h - l) >> 1);
+                SD_CNT(8);
+                if (text[(int64_t)sa[mid] + d] < tok) l = mid + 1; else h = mid;
+            }
+            lb = l;
+            l = ub_lo; h = ub_hi;
             while (l < h) {
                 int32_t mid = l + ((h - l) >> 1);
                 SD_CNT(8);
