@@ -120,7 +120,9 @@ __device__ __forceinline__ void occ_sort(int2 *arr, uint64_t *key, int m, const 
                     bool swap;
                     if (key) {
                         const uint64_t ka = key[i], kb = key[l];
-                        swap = ka != kb ? kb < ka : occ_less<STATS>(x, b, a, depth, nb);
+                        // equal keys with the low bit clear: two occurrences that are never asked
+                        // for more than the key's two tokens (see the caller): any order will do
+                        swap = ka != kb ? kb < ka : ((ka & 1) ? occ_less<STATS>(x, b, a, depth, nb) : false);
                         if (swap) { key[i] = kb; key[l] = ka; }
                     } else {
                         swap = occ_less<STATS>(x, b, a, depth, nb);
@@ -326,28 +328,48 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
     // has a continuation in this index, and the counts stay at zero, which says just that.
     if (m <= 1) return;
     const bool in_lds = m <= OCC_LDS_SORT;
-    // How far each occurrence extends to the left together with the context's own tail: one
-    // occurrence per wave and trip, lane k compares the k-th token before both ends.
+    // How far each occurrence extends to the left together with the context's own tail.  An
+    // occurrence takes PP lanes (P rounded up to a power of two): lane k of them compares the
+    // k-th token before both ends.  A wave handles 64 / PP occurrences side by side and four
+    // such batches per trip, all loads of a trip in flight together.
     {
         const int wave = uni((int32_t)(tid >> 6)), nw = nthr >> 6;
+        int pplog = 0;
+        while ((1 << pplog) < p.P) pplog++;
+        const int PP = 1 << pplog, G = 64 >> pplog, g = lane >> pplog, k = lane & (PP - 1);
+        const uint64_t gmask = PP >= 64 ? ~0ull : ((1ull << PP) - 1ull);
         int32_t tl = 0;
-        if (m > 1 && lane < p.P && lane < t) tl = x[t - 1 - lane];
-        for (int i = wave; i < m; i += nw) {
-            const int e = uni(in_lds ? s_sort[i].x : occ[i].x);
-            const int lim = e + 1 < p.P ? e + 1 : p.P;
-            int l = lim;  // the context's own tail agrees with itself all the way: nothing to read
-            if (e != t - 1) {
-                int32_t v = 0;
-                if (lane < lim) v = x[e - lane];
-                if (lane < lim) SD_CNT(8);
-                const uint64_t mis = __ballot(lane >= 1 && lane < lim && v != tl);
-                if (mis) l = __ffsll((unsigned long long)mis) - 1;
+        if (k < p.P && k < t) tl = x[t - 1 - k];
+        constexpr int U = 4;
+        for (int i0 = wave * G * U; i0 < m; i0 += nw * G * U) {
+            int e[U];
+            int32_t v[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const int i = i0 + u * G + g;
+                e[u] = i < m ? (in_lds ? s_sort[i].x : occ[i].x) : -1;
             }
-            if (lane == 0) {
-                if (in_lds) s_sort[i].y = l;
-                else occ[i].y = l;
-                atomicAdd(&sh.cnt[l], 1);
-                SD_CNT(8);
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const int lim = e[u] + 1 < p.P ? e[u] + 1 : p.P;  // (0 for an empty place)
+                // the context's own tail agrees with itself all the way: nothing to read
+                const bool rd = e[u] >= 0 && e[u] != t - 1 && k < lim;
+                v[u] = rd ? x[e[u] - k] : tl;
+                if (rd) SD_CNT(8);
+            }
+#pragma unroll
+            for (int u = 0; u < U; u++) {
+                const int lim = e[u] + 1 < p.P ? e[u] + 1 : p.P;
+                const uint64_t mis = __ballot(k >= 1 && k < lim && v[u] != tl);
+                const uint64_t gm = (mis >> (g << pplog)) & gmask;
+                const int l = gm ? __ffsll((unsigned long long)gm) - 1 : lim;
+                if (k == 0 && e[u] >= 0) {
+                    const int i = i0 + u * G + g;
+                    if (in_lds) s_sort[i].y = l;
+                    else occ[i].y = l;
+                    atomicAdd(&sh.cnt[l], 1);
+                    SD_CNT(8);
+                }
             }
         }
     }
@@ -364,14 +386,21 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
         const int depth = p.D - 1;
         if (in_lds) {
             if (m > 1) {
-                // sort key: the two tokens after the occurrence, end marker lowest (rows are
-                // padded with end markers, and only a pattern's own tail is followed by one)
+                // Sort key: the two tokens after the occurrence, end marker lowest (rows are
+                // padded with end markers, and only a pattern's own tail is followed by one), then
+                // one bit that says whether the occurrence can ever be asked for more.  An
+                // occurrence with left-extension L belongs to the lists of the patterns p <= L,
+                // whose trees have at most floor(alpha p) <= floor(alpha L) nodes and therefore
+                // look at no token further than that many places behind it.  Where that is two
+                // or less the key is the whole order; such occurrences come before the others
+                // of the same key, which are ordered among themselves by the tokens beyond.
                 uint64_t *key = reinterpret_cast<uint64_t *>(s_sort + OCC_LDS_SORT);
                 for (int i = tid; i < m; i += nthr) {
                     const int e = s_sort[i].x;
                     const uint32_t t1 = (uint32_t)(x[e + 1] + 1);
                     const uint32_t t2 = depth >= 2 ? (uint32_t)(x[e + 2] + 1) : 0u;
-                    key[i] = ((uint64_t)t1 << 32) | t2;
+                    const uint64_t more = floor(p.alpha * (double)s_sort[i].y) > 2.0 ? 1u : 0u;
+                    key[i] = ((uint64_t)t1 << 33) | ((uint64_t)t2 << 1) | more;
                     SD_CNT(8);
                 }
                 __syncthreads();
