@@ -1237,14 +1237,16 @@ constexpr int SCAN_MAX = 256;
 #endif
 constexpr int COL_FAN = SD_COL_FAN;  // probes per bound and round in a wide bucket (<= 32)
 constexpr int DIRECT_MAX = 8;
+constexpr int LEVEL_MIN = 256;  // ranges above this are narrowed token by token first
 
-// second stage for a wide bucket [l, h): narrows it to the entries whose second token is w1
-template <bool STATS>
-__device__ __forceinline__ void col_range_wide(const int32_t *__restrict__ col, int32_t w1, int32_t &l,
-                                               int32_t &h, unsigned &nb) {
+// Narrows the sorted range [l, h) to the entries whose token (tok_at(i), non-decreasing over
+// the range) is w1.
+template <bool STATS, class TokAt>
+__device__ __forceinline__ void range_fan(TokAt tok_at, int32_t w1, int32_t &l, int32_t &h,
+                                          unsigned &nb) {
     const int lane = threadIdx.x & 63;
-        // wide bucket: lower and upper bound of the second token by COL_FAN-way search, one half
-        // of the wave per bound: every round probes COL_FAN evenly spaced column entries per
+        // lower and upper bound of the token by COL_FAN-way search, one half
+        // of the wave per bound: every round probes COL_FAN evenly spaced entries per
         // bound and keeps the gap in which the answer lies.  Every probe moves a whole memory
         // line for four bytes, so a wide fan trades latency for traffic: 32 probes per bound
         // were faster for one request and much slower for 256 (the low-repetition workload went
@@ -1258,8 +1260,7 @@ __device__ __forceinline__ void col_range_wide(const int32_t *__restrict__ col, 
             const int64_t idx = (int64_t)lo_ + (int64_t)k * step;
             const bool valid = k < COL_FAN && n > 0 && idx < hi_;
             int32_t v = 0;
-            if (valid) v = col[idx];
-            if (valid) SD_CNT(4);
+            if (valid) v = tok_at(idx);
             // probes holding a smaller (lower bound) / not larger (upper bound) token: a prefix
             const uint64_t pm = __ballot(valid && (half ? v <= w1 : v < w1));
             const int cA = __popc((uint32_t)pm), cB = __popc((uint32_t)(pm >> 32));
@@ -1294,7 +1295,29 @@ __device__ __forceinline__ void match_rest(const SpecParams &p, int32_t wk, int 
                                            int32_t &hi, unsigned &nb) {
     const int lane = threadIdx.x & 63;
     if (pl == 2 || lo >= hi) return;
-    if (hi - lo <= DIRECT_MAX) {  // compare every remaining suffix with the whole pattern
+    // A long range is first narrowed by the pattern's third token, then its fourth, ... with
+    // the multi-way search (the suffixes of the range agree on everything before, so the token
+    // at that depth is sorted over the range): a level usually shrinks the range by orders of
+    // magnitude.  Once the range is short, or a level hardly shrank it (many suffixes that
+    // share the whole pattern), whole-pattern compares finish the job.
+    int depth = 2;
+    while (hi - lo > LEVEL_MIN && depth < pl) {
+        const int32_t w = __shfl(wk, depth);
+        const int32_t *sa = p.g_sa, *text = p.g_text;
+        const int32_t before = hi - lo;
+        range_fan<STATS>([&](int64_t i) {
+            SD_CNT(8);
+            return text[(int64_t)sa[i] + depth];
+        }, w, lo, hi, nb);
+        depth++;
+        if ((int64_t)(hi - lo) * 4 > before) break;
+    }
+    if (lo >= hi || depth >= pl) return;
+    if (hi - lo > DIRECT_MAX) {
+        match_range<STATS>(p.g_sa, p.g_text, lo, hi, wk, pl, nb);
+        return;
+    }
+    {  // compare every remaining suffix with the whole pattern
         const int32_t cnt = hi - lo;
         const int64_t pos = lane < cnt ? p.g_sa[lo + lane] : 0;
         if (lane < cnt) SD_CNT(4);
@@ -1321,9 +1344,7 @@ __device__ __forceinline__ void match_rest(const SpecParams &p, int32_t wk, int 
         }
         hi = lo + nleq;
         lo = lo + nless;
-        return;
     }
-    match_range<STATS>(p.g_sa, p.g_text, lo, hi, wk, pl, nb);
 }
 
 template <bool STATS>
@@ -1340,7 +1361,7 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
     const int32_t *col = p.g_tok1;
     int32_t l = lo, h = hi;
     if (h - l > SCAN_MAX) {
-        col_range_wide<STATS>(col, w1, l, h, nb);
+        range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1, l, h, nb);
     } else {
         int32_t v[SCAN_MAX / 64];
 #pragma unroll
@@ -1402,8 +1423,8 @@ __device__ __forceinline__ void match_global_pair(const SpecParams &p, int32_t w
         if (narrowA) { hiA = loA + leA; loA = loA + lsA; }
         if (narrowB) { hiB = loB + leB; loB = loB + lsB; }
     }
-    if (goA && !narrowA) col_range_wide<STATS>(col, w1A, loA, hiA, nb);
-    if (goB && !narrowB) col_range_wide<STATS>(col, w1B, loB, hiB, nb);
+    if (goA && !narrowA) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1A, loA, hiA, nb);
+    if (goB && !narrowB) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1B, loB, hiB, nb);
     // last stage: compare the few suffixes left with the whole pattern, A in the lower half of
     // the wave and B in the upper half
     const bool restA = goA && plA > 2 && loA < hiA, restB = goB && plB > 2 && loB < hiB;
@@ -1444,8 +1465,8 @@ __device__ __forceinline__ void match_global_pair(const SpecParams &p, int32_t w
         if (dirA) { hiA = loA + leA; loA = loA + lsA; }
         if (dirB) { hiB = loB + leB; loB = loB + lsB; }
     }
-    if (restA && !dirA) match_range<STATS>(p.g_sa, p.g_text, loA, hiA, wkA, plA, nb);
-    if (restB && !dirB) match_range<STATS>(p.g_sa, p.g_text, loB, hiB, wkB, plB, nb);
+    if (restA && !dirA) match_rest<STATS>(p, wkA, plA, loA, hiA, nb);
+    if (restB && !dirB) match_rest<STATS>(p, wkB, plB, loB, hiB, nb);
 }
 
 // One unit (request b, index src: 0 global / 1 request, pattern length pl) on one wavefront:
