@@ -141,6 +141,18 @@ def _more_minis():
     per = [4, 9, 2, 7, 5]
     out.append(("periodic-depth-bound", 16, 14, 8, 3.0, 0.05, [per * 30, per * 3 + [1, 2, 3]],
                 [per * 4, (per * 4)[:-2], per * 2 + [4, 9], [9, 2, 7]]))
+    # forty tied chains: the step-by-step merge works in bursts of six nodes between refills of
+    # its token windows
+    docs = [[7, 8, 90] + [2000 + 37 * i + k for k in range(10)] for i in range(40)]
+    out.append(("forty-tied-chains", 20000, 40, 4, 8.0, 0.01, docs,
+                [[1, 7, 8, 90], [8, 90], [90]]))
+    # a wide node with three hundred children of one or two occurrences each: every probe of a
+    # group opens a run of its own; and the same with eight occurrences per child (several
+    # groups of probes, a handful of runs in each)
+    docs = [[5, 1000 + i, 7, i % 3] for i in range(300)] + [[5, 1000 + i, 9] for i in range(0, 300, 7)]
+    out.append(("fan-out-singles", 20000, 12, 3, 8.0, 0.001, docs, [[5], [2, 5], [7, 1]]))
+    docs = [[6, 500 + i % 100, i % 5, i % 2] for i in range(800)]
+    out.append(("fan-out-eights", 20000, 12, 3, 8.0, 0.001, docs, [[6], [3, 6], [6, 510]]))
     # largest tree size the library accepts
     rng = np.random.default_rng(22)
     doc = list(rng.integers(0, 4, 3000))
