@@ -62,18 +62,22 @@ def cpu_baseline(w, n_requests: int, build_tokens: int):
         tr = oracle.Trie(w.D)
         tr.append(x)
         tries.append(tr)
-    t0 = time.perf_counter()
-    drafted = 0
-    for x, tr in zip(contexts, tries):
-        g = oracle.generate(tg, tr, x, w.P, w.alpha, w.min_score)
-        drafted += g["n_nodes"]
-    spec_s = time.perf_counter() - t0
+    reps = []
+    for _ in range(5):   # median of five passes over the sample
+        t0 = time.perf_counter()
+        drafted = 0
+        for x, tr in zip(contexts, tries):
+            g = oracle.generate(tg, tr, x, w.P, w.alpha, w.min_score)
+            drafted += g["n_nodes"]
+        reps.append(time.perf_counter() - t0)
+    spec_s = sorted(reps)[len(reps) // 2]
     return {
         "value": n_requests / spec_s, "unit": "trees/s", "cores": 1, "kind": "oracle",
         "sample": "first %d requests of the batch against the full %d-token corpus "
-                  "(GenerateCandidateTree only, tries prebuilt); build leg: plain trie over the "
+                  "(GenerateCandidateTree only, tries prebuilt, median of five passes); build leg: plain trie over the "
                   "first %d corpus tokens" % (n_requests, len(w.corpus), n),
         "us_per_drafted_token": spec_s / max(drafted, 1) * 1e6,
+        "first_pass_trees_per_s": n_requests / reps[0],   # caches cold: every later pass is faster
         "index_build_tokens_per_s": n / build_s,
     }
 
@@ -470,7 +474,7 @@ def main():
     sd.sd_destroy(ctx2)
     sd.sd_destroy(ctx)
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, n_requests=min(16, B), build_tokens=300_000)
+        out["cpu_baseline"] = cpu_baseline(w, n_requests=min(32, B), build_tokens=300_000)
     print(json.dumps(out))
 
 

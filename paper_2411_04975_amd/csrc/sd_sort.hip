@@ -298,23 +298,25 @@ void sd_group_ranks(sd_ctx *c, const uint64_t *keys, const uint32_t *vals, int64
 }
 
 
+// (Passes that a device-side switch may turn into no-ops are timed under "other build kernels",
+// so that the sort kernels' own figures hold real passes only.)
 int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st, const int32_t *run_if) {
     int cur = in_idx;
     if (n <= 0) return cur;
     int64_t ntiles = (n + RS_TILE - 1) / RS_TILE;
     for (int shift = 0; shift < nbits; shift += RS_BITS) {
         {
-            sd_span sp(c, SD_K_SORT_HIST, st);
+            sd_span sp(c, run_if ? SD_K_BUILD_OTHER : SD_K_SORT_HIST, st);
             hipLaunchKernelGGL(k_radix_hist, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
                                c->b_keys[cur], n, shift, c->b_hist, ntiles, run_if);
         }
         {
-            sd_span sp(c, SD_K_SORT_SCAN, st);
+            sd_span sp(c, run_if ? SD_K_BUILD_OTHER : SD_K_SORT_SCAN, st);
             hipLaunchKernelGGL(k_radix_rowscan, dim3(RS_BINS), dim3(RS_THREADS), 0, st, c->b_hist,
                                ntiles, c->b_hist + (int64_t)RS_BINS * ntiles, run_if);
         }
         {
-            sd_span sp(c, SD_K_SORT_SCATTER, st);
+            sd_span sp(c, run_if ? SD_K_BUILD_OTHER : SD_K_SORT_SCATTER, st);
             hipLaunchKernelGGL(k_radix_scatter, dim3((unsigned)ntiles), dim3(RS_THREADS), 0, st,
                                c->b_keys[cur], c->b_vals[cur], c->b_keys[cur ^ 1],
                                c->b_vals[cur ^ 1], n, shift, c->b_hist,
