@@ -92,6 +92,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
                     help="enqueue every step from the host instead of replaying a captured HIP graph")
+    ap.add_argument("--steps-per-graph", type=int, default=0,
+                    help="decode steps captured into one HIP graph for the timed loop; 0 (default): "
+                         "all of them, one graph launch for the timed region (the steps depend on "
+                         "each other through device memory only); 1: one launch per step")
     ap.add_argument("--separate-calls", action="store_true",
                     help="end the step with sd_accept, the collection glue and sd_index_append "
                          "as three launches instead of one fused launch")
@@ -227,9 +231,10 @@ def main():
         if one_launch:  # the first drafts: every later step leaves the next ones behind
             sd.sd_speculate(ctx, d_slots, trees)
 
-    # The step is launch-bound from Python (five launches of a few microseconds each), so the
-    # timed loop replays a HIP graph captured from one step: the same kernels, enqueued by the
-    # same C-ABI calls.  --no-graph times host-side enqueueing instead.
+    # The timed loop replays a HIP graph captured from the steps: the same kernels, enqueued by
+    # the same C-ABI calls, without the host between them (a graph launch costs about 4 us, so
+    # one graph holds all timed steps; --steps-per-graph 1 replays step by step, --no-graph
+    # times host-side enqueueing instead).
     for _ in range(W):
         step()
     torch.cuda.synchronize()
@@ -239,14 +244,28 @@ def main():
         with torch.cuda.graph(graph):
             step()
         torch.cuda.synchronize()
+        S = K if args.steps_per_graph <= 0 else max(1, min(args.steps_per_graph, K))
+        graph_s = graph
+        if S > 1:
+            graph_s = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph_s):
+                for _ in range(S):
+                    step()
+            torch.cuda.synchronize()
         reset()                       # capture ran no work; start the timed region from a
         for _ in range(W):            # known state: W eager warm-up steps after a rebuild
             step()
         torch.cuda.synchronize()
     run_step = graph.replay if graph is not None else step
     t0 = time.perf_counter()
-    for _ in range(K):
-        run_step()
+    if graph is not None:
+        for _ in range(K // S):
+            graph_s.replay()
+        for _ in range(K % S):
+            graph.replay()
+    else:
+        for _ in range(K):
+            step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     mean_nodes = float(trees.n_nodes.float().mean().item())
@@ -413,7 +432,8 @@ def main():
         "value": B * K / elapsed, "unit": "trees/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int32+f64", "data": "synthetic",
-        "launch": "hip-graph replay" if graph is not None else "host enqueue",
+        "launch": ("hip-graph replay, %d step%s per graph" % (S, "" if S == 1 else "s"))
+                  if graph is not None else "host enqueue",
         "config": {"workload": w.name, "batch": B, "ctx_len": ctx_len, "corpus_tokens": n_tokens,
                    "corpus_docs": n_docs, "vocab": w.vocab, "D": w.D, "P": w.P, "alpha": w.alpha,
                    "min_score": w.min_score, "max_nodes": mn, "seed": args.seed,
