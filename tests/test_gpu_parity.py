@@ -719,6 +719,67 @@ def test_profiling_variants_give_the_same_trees(tiny_workload):
     assert ut.shape == (B, 2, w.P, 4)
 
 
+def test_fused_step_under_profiling_modes_and_bad_arguments(tiny_workload):
+    """sd_accept_append_speculate gives the same results whatever the profiling mode (the
+    counting and timing variants exist for the separate kernels, which it then runs), is
+    timed under its own name in mode 1, and turns bad arguments into errors on the host."""
+    import torch
+    import paper_2411_04975_amd as sd
+    w = tiny_workload
+    docs = w.docs()
+    B, mn = w.batch, w.max_nodes
+    results = []
+    for mode in (0, 1, 2, 3):
+        g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, w.ctx_len + 2 * (mn + 1),
+                           len(w.corpus) + len(docs))
+        try:
+            g.build_global(docs)
+            g.build_requests(range(B), [w.contexts[b] for b in range(B)])
+            got = g.speculate(range(B))
+            fut = np.stack([w.future[b, :mn + 2] for b in range(B)])
+            tgt = parity.targets_from_future(got, fut, mn)
+            sd.sd_debug_profile(g.ctx, mode)
+            sd.sd_debug_profile_read(g.ctx)
+            al, ap, bo, nxt = g.accept_append_speculate(range(B), tgt)
+            prof = sd.sd_debug_profile_read(g.ctx)
+            sd.sd_debug_profile(g.ctx, 0)
+            results.append((al, ap, bo, nxt))
+            if mode == 1:
+                assert prof["accept_speculate"]["launches"] == 1 and prof["speculate"]["launches"] == 0
+            if mode >= 2:
+                assert prof["accept"]["launches"] == 1 and prof["speculate"]["launches"] == 1
+            if mode == 0:
+                dev = g.dev
+                i32 = torch.int32
+                slots = torch.arange(B, dtype=i32, device=dev)
+                d_t = torch.zeros((B, mn + 1), dtype=i32, device=dev)
+                al_, ap_, bo_ = (torch.zeros(B, dtype=i32, device=dev),
+                                 torch.zeros((B, mn), dtype=i32, device=dev),
+                                 torch.zeros(B, dtype=i32, device=dev))
+                small = sd.Trees(B, mn - 1, dev) if mn > 1 else None
+                if small is not None:
+                    with pytest.raises(sd.SdError):        # fewer nodes than floor(alpha P)
+                        sd.sd_accept_append_speculate(g.ctx, small, slots, d_t[:, :mn].contiguous(),
+                                                      al_, ap_[:, :mn - 1].contiguous(), bo_)
+                many = torch.arange(B + 1, dtype=i32, device=dev)
+                big = sd.Trees(B + 1, mn, dev)
+                with pytest.raises(sd.SdError):            # more requests than slots
+                    sd.sd_accept_append_speculate(
+                        g.ctx, big, many, torch.zeros((B + 1, mn + 1), dtype=i32, device=dev),
+                        torch.zeros(B + 1, dtype=i32, device=dev),
+                        torch.zeros((B + 1, mn), dtype=i32, device=dev),
+                        torch.zeros(B + 1, dtype=i32, device=dev))
+                assert g.stats()["err_bad_slot"] == 0      # nothing was launched
+        finally:
+            g.close()
+    base = results[0]
+    for other in results[1:]:
+        for a, b in zip(base[:3], other[:3]):
+            assert np.array_equal(a, b)
+        for k in base[3]:
+            assert np.array_equal(base[3][k], other[3][k]), k
+
+
 @pytest.mark.parametrize("D", [5, 16, 40])
 def test_suffix_array_with_long_and_short_groups(D):
     """Runs of one token (groups of hundreds of equal prefixes, which need the device-wide sort
