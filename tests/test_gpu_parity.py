@@ -344,6 +344,73 @@ def test_fused_step_end_and_next_draft_in_one_launch():
         g.close()
 
 
+def test_accept_on_synthetic_trees():
+    """sd_accept against the oracle's walk on trees that sd_speculate would not produce by
+    itself: chains of every length up to the largest tree (short accepted paths are walked,
+    long ones settled by pointer jumping), bushy random trees, targets that stop the walk
+    anywhere, empty trees."""
+    import torch
+    import paper_2411_04975_amd as sd
+    rng = np.random.default_rng(17)
+    mn = 256
+    cases = []
+    for L in (0, 1, 2, 7, 8, 9, 10, 63, 64, 65, 200, 256):       # a chain accepted up to node L
+        n = 256
+        tok = rng.integers(0, 50, n).astype(np.int32)
+        par = np.arange(-1, n - 1, dtype=np.int32)
+        tgt = np.empty(n + 1, np.int32)
+        tgt[:n] = tok                                               # target at node j-1 = token of j
+        tgt[n] = 3
+        if L < n:
+            tgt[L] = tok[L] + 1                                     # node L is refused
+        cases.append((n, tok, par, tgt))
+    for _ in range(40):                                             # random trees, distinct siblings
+        n = int(rng.integers(0, mn + 1))
+        par = np.array([int(rng.integers(-1, j)) for j in range(n)], np.int32)
+        tok = np.zeros(n, np.int32)
+        seen = {}
+        for j in range(n):
+            k = seen.get(int(par[j]), 0)
+            seen[int(par[j])] = k + 1
+            tok[j] = 100 * k + int(rng.integers(0, 100))            # distinct among siblings
+        tgt = rng.integers(0, 300, mn + 1).astype(np.int32)
+        v = -1                                                      # lay a path of random length
+        for _ in range(int(rng.integers(0, 40))):
+            kids = [j for j in range(n) if par[j] == v]
+            if not kids:
+                break
+            j = kids[int(rng.integers(0, len(kids)))]
+            tgt[v + 1] = tok[j]
+            v = j
+        cases.append((n, tok, par, tgt))
+    B = len(cases)
+    dev = torch.device("cuda", 0)
+    ctx = sd.sd_create(1000, 8, 4, 64.0, 0.1, B, 16, 16, 0)        # floor(alpha P) = 256
+    try:
+        tr = sd.Trees(B, mn, dev)
+        toks = np.full((B, mn), -1, np.int32)
+        pars = np.full((B, mn), -1, np.int32)
+        tgts = np.zeros((B, mn + 1), np.int32)
+        nn = np.zeros(B, np.int32)
+        for b, (n, tok, par, tgt) in enumerate(cases):
+            toks[b, :n] = tok; pars[b, :n] = par; nn[b] = n
+            tgts[b, :len(tgt)] = tgt
+        tr.tokens.copy_(torch.from_numpy(toks)); tr.parents.copy_(torch.from_numpy(pars))
+        tr.n_nodes.copy_(torch.from_numpy(nn))
+        al = torch.full((B,), -7, dtype=torch.int32, device=dev)
+        ap = torch.full((B, mn), -7, dtype=torch.int32, device=dev)
+        bo = torch.full((B,), -7, dtype=torch.int32, device=dev)
+        sd.sd_accept(ctx, tr, B, torch.from_numpy(tgts).to(dev), al, ap, bo)
+        torch.cuda.synchronize()
+        al, ap, bo = al.cpu().numpy(), ap.cpu().numpy(), bo.cpu().numpy()
+        for b, (n, tok, par, tgt) in enumerate(cases):
+            L, path, bonus = oracle.accept(tok, par, tgts[b])
+            assert al[b] == L and bo[b] == bonus, (b, n, al[b], L)
+            assert list(ap[b, :L]) == list(path) and list(ap[b, L:]) == [-1] * (mn - L)
+    finally:
+        sd.sd_destroy(ctx)
+
+
 def test_device_flags_bad_token_slot_and_overflow():
     g = parity.GpuPath(10, 6, 3, 1.0, 0.1, 2, 16, 100)
     try:
