@@ -329,6 +329,44 @@ def main():
         nb *= 4
     latency_by_batch[str(B)] = spec_ms * 1e3
 
+    # ---- sd_speculate against the amount of work: the same batch with contexts cut down to
+    # their last L tokens (0: nothing to do at all; 1: one pattern, one bucket; 64: every
+    # pattern length and every expansion, next to no scan).  Kernel time per launch, 20
+    # launches back to back in one graph: what is left at L = 0 is launch and fixed cost, and
+    # every dependent load on the path from there shows as about a microsecond.
+    def kernel_us(reps=20):
+        for _ in range(3):
+            sd.sd_speculate(ctx, d_slots, trees)
+        torch.cuda.synchronize()
+        gk = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gk):
+            for _ in range(reps):
+                sd.sd_speculate(ctx, d_slots, trees)
+        torch.cuda.synchronize()
+        gk.replay()
+        torch.cuda.synchronize()
+        ts = []
+        for _ in range(5):
+            e0, e1 = ev(), ev()
+            e0.record()
+            gk.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e3 / reps)
+        return min(ts)
+
+    us_by_context = {}
+    ctx2d = d_ctx.view(B, ctx_len)
+    for L in sorted({0, 1, 64, 1024, ctx_len}):
+        if L > ctx_len:
+            continue
+        cut = ctx2d[:, ctx_len - L:].contiguous().reshape(-1) if L > 0 else d_ctx[:1]
+        off = torch.arange(0, (B + 1) * L, max(L, 1), dtype=torch.int64, device=dev) if L > 0 \
+            else torch.zeros(B + 1, dtype=torch.int64, device=dev)
+        sd.sd_index_build(ctx, sd.SD_SCOPE_REQUESTS, d_slots, cut, off, B * L)
+        us_by_context[str(L)] = kernel_us()
+    build_requests()
+
     # ---- per-kernel durations (HIP events on the launch stream) over the same K steps -----
     reset()
     for _ in range(W):
@@ -452,6 +490,7 @@ def main():
         "step_latency_ms": step_latency,
         "speculate_only_ms_median": spec_ms, "speculate_only_trees_per_s": B / (spec_ms * 1e-3),
         "speculate_latency_us_by_batch": latency_by_batch,
+        "speculate_kernel_us_by_context_tokens": us_by_context,
         "speculate_latency_profile": latency_profile,
         "stream_copy_gbs": achievable_gbs,
         "mean_tree_nodes": mean_nodes, "mean_accept_len": mean_accept,
