@@ -99,13 +99,29 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_round_small(
     const int64_t first = (int64_t)blockIdx.x * SMALL_TILE - SMALL_HALO;  // array index of LDS slot 0
     for (int k = threadIdx.x; k < SMALL_LDS; k += SMALL_THREADS) {
         const int64_t i = first + k;
-        uint32_t g = 0, r2 = 0, pos = 0;  // group 0 does not exist: marks slots outside the array
+        uint32_t g = 0, pos = 0;  // group 0 does not exist: marks slots outside the array
         if (i >= 0 && i < N) {
             g = gid[i];
             pos = vals[i];
-            r2 = (int64_t)pos + h < N ? rank[(int64_t)pos + h] : 0u;
         }
-        s_g[k] = g; s_r2[k] = r2; s_pos[k] = pos;
+        s_g[k] = g; s_pos[k] = pos;
+    }
+    __syncthreads();
+    // The rank of the second half is a random 4-byte read per entry: only entries that share
+    // their group with another one need it (a group is numbered by its first place, so an
+    // entry alone in its group is one whose number is its own place and whose right neighbour
+    // has another number).
+    for (int k = threadIdx.x; k < SMALL_LDS; k += SMALL_THREADS) {
+        const int64_t i = first + k;
+        uint32_t r2 = 0;
+        if (i >= 0 && i < N) {
+            const uint32_t g = s_g[k];
+            const bool alone = g == (uint32_t)(i + 1) &&
+                               (i + 1 == N || (k + 1 < SMALL_LDS && s_g[k + 1] != g));
+            const int64_t q = (int64_t)s_pos[k] + h;
+            if (!alone && q < N) r2 = rank[q];
+        }
+        s_r2[k] = r2;
     }
     __syncthreads();
     bool bad = false;
@@ -311,7 +327,7 @@ static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, hip
     int round = 0;
     for (int64_t h = 2; h < c->cfg.D; h *= 2, round++) {
         int32_t *flag = c->d_round_flag + (round < 8 ? round : 7);
-        sd_group_ranks(c, c->b_keys[cur], c->b_vals[cur], N, c->b_rank, c->b_flags, st);
+        sd_group_ranks(c, c->b_keys[cur], c->b_vals[cur], N, c->b_rank, c->b_flags, round == 0, st);
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_small,
                   dim3((unsigned)((N + SMALL_TILE - 1) / SMALL_TILE)), dim3(SMALL_THREADS), 0,
                   c->b_vals[cur], c->b_flags, c->b_rank, N, h, rank_bits, c->b_keys[cur ^ 1],

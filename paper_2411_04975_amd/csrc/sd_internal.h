@@ -74,9 +74,11 @@ struct sd_ctx {
 // every kernel of the sort returns at once if run_if is given and *run_if == 0 (device memory)
 int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st,
                   const int32_t *run_if = nullptr);
-// rank[vals[i]] = gid[i] = 1-based group number of keys[i] in the sorted array keys[0..n)
+// gid[i] = 1 + index of the first entry of the run of equal keys that keys[i] belongs to (sorted
+// array keys[0..n)), rank[vals[i]] = gid[i].  With first == 0, gid must hold the numbers of the
+// previous call over the same places, and rank is stored only where the number changed.
 void sd_group_ranks(sd_ctx *c, const uint64_t *keys, const uint32_t *vals, int64_t n,
-                    uint32_t *rank, uint32_t *gid, hipStream_t st);
+                    uint32_t *rank, uint32_t *gid, int first, hipStream_t st);
 
 sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
                                int32_t n_seq, int64_t n_tokens, hipStream_t st);

@@ -207,8 +207,34 @@ constexpr int SC_THREADS = 256;
 constexpr int SC_ITEMS = 16;
 constexpr int SC_TILE = SC_THREADS * SC_ITEMS;
 
-// single workgroup: partials[i] <- sum of partials[0..i) (exclusive), any length
-__global__ __launch_bounds__(SC_THREADS) void k_scan_partials(uint32_t *partials, int64_t m) {
+// exclusive prefix maximum of one value per thread over a 256-thread workgroup
+__device__ __forceinline__ uint32_t block_excl_scanmax_256(uint32_t v, uint32_t *s_wave /*[RS_WAVES]*/,
+                                                           uint32_t *total) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t t = __shfl_up(inc, o);
+        if (lane >= o) inc = t > inc ? t : inc;
+    }
+    uint32_t ex = __shfl_up(inc, 1);
+    if (lane == 0) ex = 0;
+    if (lane == 63) s_wave[w] = inc;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < RS_WAVES; i++) {
+        uint32_t t = s_wave[i];
+        if (i < w) base = t > base ? t : base;
+        tot = t > tot ? t : tot;
+    }
+    __syncthreads();
+    if (total) *total = tot;
+    return base > ex ? base : ex;
+}
+
+// single workgroup: partials[i] <- maximum of partials[0..i) (exclusive, 0 for i = 0), any length
+__global__ __launch_bounds__(SC_THREADS) void k_scanmax_partials(uint32_t *partials, int64_t m) {
     __shared__ uint32_t s_wave[SC_THREADS / 64];
     __shared__ uint32_t s_carry;
     if (threadIdx.x == 0) s_carry = 0;
@@ -217,20 +243,25 @@ __global__ __launch_bounds__(SC_THREADS) void k_scan_partials(uint32_t *partials
         int64_t i = base + threadIdx.x;
         uint32_t v = i < m ? partials[i] : 0u;
         uint32_t tot;
-        uint32_t ex = block_excl_scan_256(v, s_wave, &tot);
+        uint32_t ex = block_excl_scanmax_256(v, s_wave, &tot);
         uint32_t carry = s_carry;
-        if (i < m) partials[i] = carry + ex;
+        if (i < m) partials[i] = carry > ex ? carry : ex;
         __syncthreads();
-        if (threadIdx.x == 0) s_carry = carry + tot;
+        if (threadIdx.x == 0) s_carry = carry > tot ? carry : tot;
         __syncthreads();
     }
 }
 
 // ---- group numbers of a sorted key array, written by position -------------------------------
-// rank[vals[i]] = gid[i] = number of distinct keys among keys[0..i] (so the first group is 1;
-// 0 stays free for "beyond the end").  Flag, scan and scatter in two passes over the keys instead of
-// flag pass + three scan launches + scatter pass.
-__global__ __launch_bounds__(SC_THREADS) void k_rank_tile_sums(const uint64_t *__restrict__ keys,
+// A group (a run of equal keys) is numbered by where it starts: gid[i] = 1 + index of the first
+// entry of i's group (0 stays free for "beyond the end"), and rank[vals[i]] = gid[i].  Numbers of
+// that kind keep the order of the groups, and they change only for the entries that a split
+// moves out of the front part of their group: in every call but the first one only those
+// entries are written to `rank` (by position: a random 4-byte store each), found by comparing
+// with the number the entry's place had before (places keep their group from call to call, the
+// build only reorders inside groups).  Two passes over the keys: the last group start of every
+// tile, a prefix maximum over the tiles, then numbers and stores.
+__global__ __launch_bounds__(SC_THREADS) void k_rank_tile_last(const uint64_t *__restrict__ keys,
                                                                int64_t n,
                                                                uint32_t *__restrict__ partials) {
     __shared__ uint32_t s_wave[SC_THREADS / 64];
@@ -239,15 +270,18 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_tile_sums(const uint64_t *_
 #pragma unroll
     for (int k = 0; k < SC_ITEMS; k++) {
         int64_t i = base + (int64_t)k * SC_THREADS + threadIdx.x;
-        if (i < n) s += (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
+        if (i < n && (i == 0 || keys[i] != keys[i - 1])) s = (uint32_t)(i + 1) > s ? (uint32_t)(i + 1) : s;
     }
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t t = __shfl_xor(s, o);
+        s = t > s ? t : s;
+    }
     if ((threadIdx.x & 63) == 0) s_wave[threadIdx.x >> 6] = s;
     __syncthreads();
     if (threadIdx.x == 0) {
         uint32_t t = 0;
-        for (int i = 0; i < SC_THREADS / 64; i++) t += s_wave[i];
+        for (int i = 0; i < SC_THREADS / 64; i++) t = s_wave[i] > t ? s_wave[i] : t;
         partials[blockIdx.x] = t;
     }
 }
@@ -257,7 +291,7 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__res
                                                            int64_t n,
                                                            const uint32_t *__restrict__ partials,
                                                            uint32_t *__restrict__ rank,
-                                                           uint32_t *__restrict__ gid) {
+                                                           uint32_t *__restrict__ gid, int first) {
     __shared__ uint32_t s_wave[SC_THREADS / 64];
     const int64_t base = (int64_t)blockIdx.x * SC_TILE + (int64_t)threadIdx.x * SC_ITEMS;
     uint32_t f[SC_ITEMS];
@@ -267,18 +301,22 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__res
     for (int k = 0; k < SC_ITEMS; k++) {
         int64_t i = base + k;
         uint64_t key = i < n ? keys[i] : 0ull;
-        f[k] = i < n && (i == 0 || key != prev) ? 1u : 0u;
+        f[k] = i < n && (i == 0 || key != prev) ? (uint32_t)(i + 1) : 0u;
         prev = key;
-        s += f[k];
+        s = f[k] > s ? f[k] : s;
     }
-    uint32_t ex = block_excl_scan_256(s, s_wave, nullptr) + partials[blockIdx.x];
+    uint32_t ex = block_excl_scanmax_256(s, s_wave, nullptr);
+    const uint32_t before = partials[blockIdx.x];
+    ex = before > ex ? before : ex;
 #pragma unroll
     for (int k = 0; k < SC_ITEMS; k++) {
         int64_t i = base + k;
-        ex += f[k];
+        ex = f[k] > ex ? f[k] : ex;
         if (i < n) {
-            rank[vals[i]] = ex;
-            gid[i] = ex;
+            if (first || gid[i] != ex) {
+                rank[vals[i]] = ex;
+                gid[i] = ex;
+            }
         }
     }
 }
@@ -286,15 +324,15 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__res
 }  // namespace
 
 void sd_group_ranks(sd_ctx *c, const uint64_t *keys, const uint32_t *vals, int64_t n,
-                    uint32_t *rank, uint32_t *gid, hipStream_t st) {
+                    uint32_t *rank, uint32_t *gid, int first, hipStream_t st) {
     if (n <= 0) return;
     int64_t nt = (n + SC_TILE - 1) / SC_TILE;
     sd_span sp(c, SD_K_SORT_SCAN, st);
-    hipLaunchKernelGGL(k_rank_tile_sums, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, keys, n,
+    hipLaunchKernelGGL(k_rank_tile_last, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, keys, n,
                        c->b_partials);
-    hipLaunchKernelGGL(k_scan_partials, dim3(1), dim3(SC_THREADS), 0, st, c->b_partials, nt);
+    hipLaunchKernelGGL(k_scanmax_partials, dim3(1), dim3(SC_THREADS), 0, st, c->b_partials, nt);
     hipLaunchKernelGGL(k_rank_apply, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, keys, vals, n,
-                       c->b_partials, rank, gid);
+                       c->b_partials, rank, gid, first);
 }
 
 
