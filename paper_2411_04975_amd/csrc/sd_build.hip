@@ -29,10 +29,25 @@ __global__ __launch_bounds__(TB) void k_layout_text(const int32_t *__restrict__ 
                                                     const int64_t *__restrict__ offs, int32_t n_seq,
                                                     int64_t n_tokens, int32_t *__restrict__ text,
                                                     int32_t vocab, int32_t *err) {
-    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    // The tokens of a workgroup lie in a few neighbouring documents: two threads find the
+    // documents of its first and last token among all of them, everyone else searches between.
+    __shared__ int32_t s_doc[2];
+    const int64_t i0 = (int64_t)blockIdx.x * TB;
+    const int64_t i1 = i0 + TB - 1 < n_tokens - 1 ? i0 + TB - 1 : n_tokens - 1;
+    if (threadIdx.x < 2) {
+        const int64_t q = threadIdx.x ? i1 : i0;
+        int32_t lo = 0, hi = n_seq;  // largest j with offs[j] <= q, in [lo, hi)
+        while (hi - lo > 1) {
+            int32_t mid = (lo + hi) >> 1;
+            if (offs[mid] <= q) lo = mid; else hi = mid;
+        }
+        s_doc[threadIdx.x] = lo;
+    }
+    __syncthreads();
+    int64_t i = i0 + threadIdx.x;
     if (i >= n_tokens) return;
     // largest j with offs[j] <= i
-    int32_t lo = 0, hi = n_seq;  // answer in [lo, hi)
+    int32_t lo = s_doc[0], hi = s_doc[1] + 1;  // answer in [lo, hi)
     while (hi - lo > 1) {
         int32_t mid = (lo + hi) >> 1;
         if (offs[mid] <= i) lo = mid; else hi = mid;
@@ -71,12 +86,23 @@ __global__ __launch_bounds__(TB) void k_round_keys(const uint32_t *__restrict__ 
                                                    uint64_t *__restrict__ keys,
                                                    uint32_t *__restrict__ vals,
                                                    const int32_t *__restrict__ run_if) {
-    int64_t q = (int64_t)blockIdx.x * TB + threadIdx.x;
-    if (q >= N || (run_if && *run_if == 0)) return;
-    uint64_t r1 = rank[q];
-    uint64_t r2 = (q + h < N) ? rank[q + h] : 0u;
-    keys[q] = (r1 << rank_bits) | r2;
-    vals[q] = (uint32_t)q;
+    if (run_if && *run_if == 0) return;  // (a small grid: switched off, it costs next to nothing)
+    for (int64_t q = (int64_t)blockIdx.x * TB + threadIdx.x; q < N; q += (int64_t)gridDim.x * TB) {
+        uint64_t r1 = rank[q];
+        uint64_t r2 = (q + h < N) ? rank[q + h] : 0u;
+        keys[q] = (r1 << rank_bits) | r2;
+        vals[q] = (uint32_t)q;
+    }
+}
+
+// Second-token column from the keys of the first sort (token codes of the two leading tokens).
+// Every later step only reorders entries inside groups that share at least those two tokens,
+// so the column by place stays what it is here.
+__global__ __launch_bounds__(TB) void k_tok1_from_keys(const uint64_t *__restrict__ keys, int64_t N,
+                                                       int tok_bits, int32_t *__restrict__ tok1) {
+    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (i >= N) return;
+    tok1[i] = (int32_t)(keys[i] & ((1ull << tok_bits) - 1ull)) - 1;
 }
 
 // One doubling round without a device-wide sort, for arrays whose groups are short.  The array
@@ -146,18 +172,15 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_round_small(
     if (bad) *too_long = 1;
 }
 
-// final suffix array plus the second-token column: tok1[i] = second token of suffix i.  Inside
-// the bucket of a first token the column is sorted, so the second pattern token is located by a
-// coalesced scan of the column instead of dependent (suffix array -> text) probes.
-__global__ __launch_bounds__(TB) void k_finish_sa(const uint32_t *__restrict__ vals,
-                                                  const int32_t *__restrict__ text, int64_t N,
-                                                  int32_t *__restrict__ sa,
-                                                  int32_t *__restrict__ tok1) {
+// final suffix array (the second-token column, tok1[i] = second token of suffix i, is written
+// after the first sort: inside the bucket of a first token the column is sorted, so the second
+// pattern token is located by a coalesced scan of the column instead of dependent
+// (suffix array -> text) probes)
+__global__ __launch_bounds__(TB) void k_finish_sa(const uint32_t *__restrict__ vals, int64_t N,
+                                                  int32_t *__restrict__ sa) {
     int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
     if (i >= N) return;
-    uint32_t p = vals[i];
-    sa[i] = (int32_t)p;
-    tok1[i] = text[(int64_t)p + 1];
+    sa[i] = (int32_t)vals[i];
 }
 
 // bucket[c] = first index whose suffix starts with token code (token + 1) >= c
@@ -313,10 +336,13 @@ inline unsigned nblk(int64_t n) { return (unsigned)((n + TB - 1) / TB); }
 // Sorts the N positions of `text` (documents with an end marker after each, padding behind)
 // by their suffixes, compared on at least D tokens.  Returns which of b_vals[0/1] holds the
 // sorted positions.
-static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, hipStream_t st) {
+static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, int32_t *tok1_out,
+                                  hipStream_t st) {
     const int tok_bits = sd_bits_for((uint64_t)c->cfg.vocab);  // codes 0..vocab
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_init_keys, dim3(nblk(N)), dim3(TB), 0, text, N, tok_bits, c->b_keys[0], c->b_vals[0]);
     int cur = sd_sort_pairs(c, N, 2 * tok_bits, 0, st);
+    if (tok1_out)
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_tok1_from_keys, dim3(nblk(N)), dim3(TB), 0, c->b_keys[cur], N, tok_bits, tok1_out);
     const int rank_bits = sd_bits_for((uint64_t)N);  // ranks 0..N
     // So far the positions are ordered by their first h = 2 tokens.  Each round first tries the
     // in-tile reordering (enough once no group is longer than its halo, which stays true for
@@ -333,7 +359,7 @@ static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, hip
                   c->b_vals[cur], c->b_flags, c->b_rank, N, h, rank_bits, c->b_keys[cur ^ 1],
                   c->b_vals[cur ^ 1], flag);
         const int start = (passes & 1) ? cur : cur ^ 1;
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N)), dim3(TB), 0, c->b_rank, N, h, rank_bits, c->b_keys[start], c->b_vals[start], flag);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N) < 4096u ? nblk(N) : 4096u), dim3(TB), 0, c->b_rank, N, h, rank_bits, c->b_keys[start], c->b_vals[start], flag);
         (void)sd_sort_pairs(c, N, 2 * rank_bits, start, st, flag);
         cur ^= 1;
     }
@@ -354,9 +380,9 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_layout_marks, dim3(nblk(m)), dim3(TB), 0, d_offsets, n_seq, N, c->g_text);
     }
     if (N > 0) {
-        const int cur = build_sorted_positions(c, c->g_text, N, st);
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_finish_sa, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur],
-                  c->g_text, N, c->g_sa, c->g_tok1);
+        const int cur = build_sorted_positions(c, c->g_text, N, c->g_tok1, st);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_finish_sa, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], N,
+                  c->g_sa);
     }
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, N, vocab, c->g_bucket);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
@@ -377,7 +403,7 @@ sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_
         int64_t m = n_seq > SD_TEXT_PAD ? n_seq : SD_TEXT_PAD;
         SD_LAUNCH(c, SD_K_INSERT, st, k_layout_marks, dim3(nblk(m)), dim3(TB), 0, d_offsets, n_seq, M, ntext);
     }
-    const int cur = build_sorted_positions(c, ntext, M, st);
+    const int cur = build_sorted_positions(c, ntext, M, nullptr, st);
     // b_vals[cur]: new positions in order; b_flags: their ranks in the old array; merged arrays
     // go to b_vals[1 - cur] and b_rank, which then change places with g_sa and g_tok1
     uint32_t *dsa = c->b_vals[cur], *rank = c->b_flags;
