@@ -31,7 +31,7 @@ bool dev_alloc(T **p, int64_t count, int64_t *acc) {
 
 void free_all(sd_ctx *c) {
     void *ptrs[] = {c->g_text, c->g_sa, c->g_bucket, c->g_tok1, c->b_keys[0], c->b_keys[1], c->b_vals[0],
-                    c->b_vals[1], c->b_rank, c->b_flags, c->b_hist, c->b_partials, c->r_text,
+                    c->b_vals[1], c->b_rank, c->b_flags, c->b_gid2, c->b_hist, c->b_partials, c->r_text,
                     c->r_len, c->s_occ, c->s_unit_sa, c->d_err, c->s_unit_ticks, c->d_entropy,
                     c->d_round_flag};
     for (void *p : ptrs)
@@ -93,7 +93,8 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     ok = ok && dev_alloc(&c->g_bucket, (int64_t)cfg->vocab + 2, ib);
     ok = ok && dev_alloc(&c->b_keys[0], cap, sb) && dev_alloc(&c->b_keys[1], cap, sb);
     ok = ok && dev_alloc(&c->b_vals[0], cap + 64, sb) && dev_alloc(&c->b_vals[1], cap + 64, sb);
-    ok = ok && dev_alloc(&c->b_rank, cap + 64, sb) && dev_alloc(&c->b_flags, cap, sb);
+    ok = ok && dev_alloc(&c->b_rank, cap + 64, sb) && dev_alloc(&c->b_flags, cap, sb) &&
+         dev_alloc(&c->b_gid2, cap, sb);
     ok = ok && dev_alloc(&c->b_hist, c->b_hist_cap, sb);
     ok = ok && dev_alloc(&c->b_partials, c->b_partials_cap, sb);
     ok = ok && dev_alloc(&c->r_text, B * c->r_stride, sb) && dev_alloc(&c->r_len, B, sb);

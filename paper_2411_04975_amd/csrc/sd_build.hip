@@ -106,21 +106,24 @@ __global__ __launch_bounds__(TB) void k_tok1_from_keys(const uint64_t *__restric
 }
 
 // One doubling round without a device-wide sort, for arrays whose groups are short.  The array
-// is already ordered by the first h tokens (gid[i] = group of entry i, non-decreasing), so a
-// round only reorders inside groups, by the group number of the next h tokens.  A workgroup
-// stages a tile of entries plus a halo of SMALL_HALO on both sides in LDS: (group, rank of the
-// second half, position).  Every entry of the tile finds the ends of its group by walking left
-// and right in LDS, counts the members that sort before it (rank of the second half, then
-// previous order) and writes itself, with its new key, to that place of the output arrays.
+// is already ordered by the first h tokens (gid[i] = group of entry i: 1 + the place where the
+// group starts), so a round only reorders inside groups, by the group number of the next h
+// tokens.  A workgroup stages a tile of entries plus a halo of SMALL_HALO on both sides in
+// LDS: (group, rank of the second half, position).  Every entry of the tile finds the ends of
+// its group by walking left and right in LDS, counts the members that sort before it (rank of
+// the second half, then previous order) and writes itself to that place of the output
+// arrays, together with the number of its new group, which starts where the members with a
+// lower second rank end: numbering groups by place needs no scan over the array.
 // A group longer than SMALL_HALO raises *too_long: the caller then runs the radix sort round
-// instead (whose kernels otherwise return at once).
+// instead (whose kernels otherwise return at once).  The ranks by position are brought up to
+// date by k_rank_update afterwards (not in here: other workgroups still read them).
 constexpr int SMALL_TILE = 1024, SMALL_HALO = 64, SMALL_THREADS = 256;
 constexpr int SMALL_LDS = SMALL_TILE + 2 * SMALL_HALO;
 
 __global__ __launch_bounds__(SMALL_THREADS) void k_round_small(
     const uint32_t *__restrict__ vals, const uint32_t *__restrict__ gid,
-    const uint32_t *__restrict__ rank, int64_t N, int64_t h, int rank_bits,
-    uint64_t *__restrict__ keys_out, uint32_t *__restrict__ vals_out, int32_t *too_long) {
+    const uint32_t *__restrict__ rank, int64_t N, int64_t h,
+    uint32_t *__restrict__ gid_out, uint32_t *__restrict__ vals_out, int32_t *too_long) {
     __shared__ uint32_t s_g[SMALL_LDS], s_r2[SMALL_LDS], s_pos[SMALL_LDS];
     const int64_t first = (int64_t)blockIdx.x * SMALL_TILE - SMALL_HALO;  // array index of LDS slot 0
     for (int k = threadIdx.x; k < SMALL_LDS; k += SMALL_THREADS) {
@@ -163,13 +166,31 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_round_small(
             bad = true;
             continue;
         }
-        int before = 0;
-        for (int j = lo; j < hi; j++) before += (s_r2[j] < r2 || (s_r2[j] == r2 && j < k)) ? 1 : 0;
-        const int64_t dst = first + lo + before;
-        keys_out[dst] = ((uint64_t)g << rank_bits) | r2;
+        int less = 0, before = 0;
+        for (int j = lo; j < hi; j++) {
+            less += s_r2[j] < r2 ? 1 : 0;
+            before += (s_r2[j] == r2 && j < k) ? 1 : 0;
+        }
+        const int64_t dst = first + lo + less + before;
+        gid_out[dst] = (uint32_t)(first + lo + less + 1);
         vals_out[dst] = s_pos[k];
     }
     if (bad) *too_long = 1;
+}
+
+// After an in-tile round: rank[position] = new group number, stored only where the number of
+// the entry's place changed (places keep their old group through a round; most groups do not
+// split, and the front part of a group that does keeps its number).
+__global__ __launch_bounds__(TB) void k_rank_update(const uint32_t *__restrict__ vals,
+                                                    const uint32_t *__restrict__ gid_new,
+                                                    const uint32_t *__restrict__ gid_old, int64_t N,
+                                                    uint32_t *__restrict__ rank,
+                                                    const int32_t *__restrict__ skip_if) {
+    if (*skip_if != 0) return;  // the round fell back to the device-wide sort, which does this itself
+    for (int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x; i < N; i += (int64_t)gridDim.x * TB) {
+        const uint32_t g = gid_new[i];
+        if (g != gid_old[i]) rank[vals[i]] = g;
+    }
 }
 
 // final suffix array (the second-token column, tok1[i] = second token of suffix i, is written
@@ -350,18 +371,26 @@ static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, int
     // Both leave the round's result in the other buffer pair.
     sd_fill_i32(c->d_round_flag, 8, 0, st);
     const int passes = (2 * rank_bits + 7) / 8;  // of the radix sort: odd ones swap buffers
+    // group numbers by place and ranks by position after the first sort
+    uint32_t *gid = c->b_flags, *gid_next = c->b_gid2;
+    if (2 < c->cfg.D)
+        sd_group_ranks(c, c->b_keys[cur], c->b_vals[cur], N, c->b_rank, gid, nullptr, st);
     int round = 0;
     for (int64_t h = 2; h < c->cfg.D; h *= 2, round++) {
         int32_t *flag = c->d_round_flag + (round < 8 ? round : 7);
-        sd_group_ranks(c, c->b_keys[cur], c->b_vals[cur], N, c->b_rank, c->b_flags, round == 0, st);
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_small,
                   dim3((unsigned)((N + SMALL_TILE - 1) / SMALL_TILE)), dim3(SMALL_THREADS), 0,
-                  c->b_vals[cur], c->b_flags, c->b_rank, N, h, rank_bits, c->b_keys[cur ^ 1],
-                  c->b_vals[cur ^ 1], flag);
+                  c->b_vals[cur], gid, c->b_rank, N, h, gid_next, c->b_vals[cur ^ 1], flag);
+        if (h * 2 < c->cfg.D)  // (the last round's numbers are not needed by anyone)
+            SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_rank_update, dim3(nblk(N) < 8192u ? nblk(N) : 8192u),
+                      dim3(TB), 0, c->b_vals[cur ^ 1], gid_next, gid, N, c->b_rank, flag);
         const int start = (passes & 1) ? cur : cur ^ 1;
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N) < 4096u ? nblk(N) : 4096u), dim3(TB), 0, c->b_rank, N, h, rank_bits, c->b_keys[start], c->b_vals[start], flag);
         (void)sd_sort_pairs(c, N, 2 * rank_bits, start, st, flag);
+        if (h * 2 < c->cfg.D)
+            sd_group_ranks(c, c->b_keys[cur ^ 1], c->b_vals[cur ^ 1], N, c->b_rank, gid_next, gid, st, flag);
         cur ^= 1;
+        uint32_t *t = gid; gid = gid_next; gid_next = t;
     }
     return cur;
 }

@@ -37,7 +37,8 @@ struct sd_ctx {
     uint64_t *b_keys[2] = {nullptr, nullptr};
     uint32_t *b_vals[2] = {nullptr, nullptr};
     uint32_t *b_rank = nullptr;
-    uint32_t *b_flags = nullptr;     // group-start flags / their scan
+    uint32_t *b_flags = nullptr;     // group numbers by place (one of two buffers, see b_gid2)
+    uint32_t *b_gid2 = nullptr;      // the other one: a doubling round reads one and writes the other
     uint32_t *b_hist = nullptr;      // per-tile digit histograms
     uint32_t *b_partials = nullptr;  // scan partial sums
     int64_t b_hist_cap = 0, b_partials_cap = 0;
@@ -75,10 +76,12 @@ struct sd_ctx {
 int sd_sort_pairs(sd_ctx *c, int64_t n, int nbits, int in_idx, hipStream_t st,
                   const int32_t *run_if = nullptr);
 // gid[i] = 1 + index of the first entry of the run of equal keys that keys[i] belongs to (sorted
-// array keys[0..n)), rank[vals[i]] = gid[i].  With first == 0, gid must hold the numbers of the
-// previous call over the same places, and rank is stored only where the number changed.
+// array keys[0..n)), rank[vals[i]] = gid[i].  With gid_old (another buffer: the numbers the same
+// places had before), rank is stored only where the number changed.
+// Every kernel returns at once if run_if is given and *run_if == 0 (device memory).
 void sd_group_ranks(sd_ctx *c, const uint64_t *keys, const uint32_t *vals, int64_t n,
-                    uint32_t *rank, uint32_t *gid, int first, hipStream_t st);
+                    uint32_t *rank, uint32_t *gid, const uint32_t *gid_old, hipStream_t st,
+                    const int32_t *run_if = nullptr);
 
 sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t *d_offsets,
                                int32_t n_seq, int64_t n_tokens, hipStream_t st);

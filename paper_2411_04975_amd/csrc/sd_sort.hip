@@ -234,9 +234,11 @@ __device__ __forceinline__ uint32_t block_excl_scanmax_256(uint32_t v, uint32_t 
 }
 
 // single workgroup: partials[i] <- maximum of partials[0..i) (exclusive, 0 for i = 0), any length
-__global__ __launch_bounds__(SC_THREADS) void k_scanmax_partials(uint32_t *partials, int64_t m) {
+__global__ __launch_bounds__(SC_THREADS) void k_scanmax_partials(uint32_t *partials, int64_t m,
+                                                                 const int32_t *__restrict__ run_if) {
     __shared__ uint32_t s_wave[SC_THREADS / 64];
     __shared__ uint32_t s_carry;
+    if (run_if && *run_if == 0) return;
     if (threadIdx.x == 0) s_carry = 0;
     __syncthreads();
     for (int64_t base = 0; base < m; base += SC_THREADS) {
@@ -256,15 +258,16 @@ __global__ __launch_bounds__(SC_THREADS) void k_scanmax_partials(uint32_t *parti
 // A group (a run of equal keys) is numbered by where it starts: gid[i] = 1 + index of the first
 // entry of i's group (0 stays free for "beyond the end"), and rank[vals[i]] = gid[i].  Numbers of
 // that kind keep the order of the groups, and they change only for the entries that a split
-// moves out of the front part of their group: in every call but the first one only those
-// entries are written to `rank` (by position: a random 4-byte store each), found by comparing
-// with the number the entry's place had before (places keep their group from call to call, the
-// build only reorders inside groups).  Two passes over the keys: the last group start of every
+// moves out of the front part of their group: given the numbers the places had before
+// (gid_old; places keep their group from round to round, the build only reorders inside
+// groups), only those entries are written to `rank` (by position: a random 4-byte store each).  Two passes over the keys: the last group start of every
 // tile, a prefix maximum over the tiles, then numbers and stores.
 __global__ __launch_bounds__(SC_THREADS) void k_rank_tile_last(const uint64_t *__restrict__ keys,
                                                                int64_t n,
-                                                               uint32_t *__restrict__ partials) {
+                                                               uint32_t *__restrict__ partials,
+                                                               const int32_t *__restrict__ run_if) {
     __shared__ uint32_t s_wave[SC_THREADS / 64];
+    if (run_if && *run_if == 0) return;
     const int64_t base = (int64_t)blockIdx.x * SC_TILE;
     uint32_t s = 0;
 #pragma unroll
@@ -291,8 +294,11 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__res
                                                            int64_t n,
                                                            const uint32_t *__restrict__ partials,
                                                            uint32_t *__restrict__ rank,
-                                                           uint32_t *__restrict__ gid, int first) {
+                                                           uint32_t *__restrict__ gid,
+                                                           const uint32_t *__restrict__ gid_old,
+                                                           const int32_t *__restrict__ run_if) {
     __shared__ uint32_t s_wave[SC_THREADS / 64];
+    if (run_if && *run_if == 0) return;
     const int64_t base = (int64_t)blockIdx.x * SC_TILE + (int64_t)threadIdx.x * SC_ITEMS;
     uint32_t f[SC_ITEMS];
     uint32_t s = 0;
@@ -313,10 +319,8 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__res
         int64_t i = base + k;
         ex = f[k] > ex ? f[k] : ex;
         if (i < n) {
-            if (first || gid[i] != ex) {
-                rank[vals[i]] = ex;
-                gid[i] = ex;
-            }
+            if (!gid_old || gid_old[i] != ex) rank[vals[i]] = ex;
+            gid[i] = ex;
         }
     }
 }
@@ -324,15 +328,16 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__res
 }  // namespace
 
 void sd_group_ranks(sd_ctx *c, const uint64_t *keys, const uint32_t *vals, int64_t n,
-                    uint32_t *rank, uint32_t *gid, int first, hipStream_t st) {
+                    uint32_t *rank, uint32_t *gid, const uint32_t *gid_old, hipStream_t st,
+                    const int32_t *run_if) {
     if (n <= 0) return;
     int64_t nt = (n + SC_TILE - 1) / SC_TILE;
-    sd_span sp(c, SD_K_SORT_SCAN, st);
+    sd_span sp(c, run_if ? SD_K_BUILD_OTHER : SD_K_SORT_SCAN, st);
     hipLaunchKernelGGL(k_rank_tile_last, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, keys, n,
-                       c->b_partials);
-    hipLaunchKernelGGL(k_scanmax_partials, dim3(1), dim3(SC_THREADS), 0, st, c->b_partials, nt);
+                       c->b_partials, run_if);
+    hipLaunchKernelGGL(k_scanmax_partials, dim3(1), dim3(SC_THREADS), 0, st, c->b_partials, nt, run_if);
     hipLaunchKernelGGL(k_rank_apply, dim3((unsigned)nt), dim3(SC_THREADS), 0, st, keys, vals, n,
-                       c->b_partials, rank, gid, first);
+                       c->b_partials, rank, gid, gid_old, run_if);
 }
 
 
