@@ -1642,7 +1642,8 @@ __device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_
                                            const int32_t *__restrict__ tokens,
                                            const int32_t *__restrict__ parents, int max_nodes,
                                            const AcceptArgs &aa, const AppendArgs &ap, int32_t *s_tgt,
-                                           int32_t *s_anc, int32_t *s_ok, int32_t *s_new) {
+                                           int32_t *s_anc, int32_t *s_ok, int32_t *s_new,
+                                           int32_t known_slot = -2, int32_t known_len = 0) {
     const int lane = threadIdx.x & 63;
     const int32_t *tok = tokens + (int64_t)b * max_nodes, *par = parents + (int64_t)b * max_nodes;
     const int32_t *tgt = aa.target + (int64_t)b * (max_nodes + 1);
@@ -1710,15 +1711,17 @@ __device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_
     }
     const int32_t bon = s_tgt[last + 1];
     int32_t *row = nullptr;
-    int32_t old = 0;
+    int32_t old = 0, slot_of_b = 0;
     bool slot_ok = false;
     if (APPEND) {  // L accepted tokens and the bonus token go behind the slot's context
-        const int32_t slot = ap.slot_ids[b];
+        // (a caller that has looked up the slot and its length already passes them in)
+        const int32_t slot = known_slot != -2 ? known_slot : ap.slot_ids[b];
         if (slot < 0 || slot >= ap.max_slots) {
             if (lane == 0) atomicOr(&ap.err[SD_DEVERR_SLOT], 1);
         } else {
             slot_ok = true;
-            old = ap.r_len[slot];
+            slot_of_b = slot;
+            old = known_slot != -2 ? known_len : ap.r_len[slot];
             if ((int64_t)old + L + 1 > ap.max_ctx) {
                 if (lane == 0) atomicOr(&ap.err[SD_DEVERR_CTX], 1);
             } else {
@@ -1757,7 +1760,7 @@ __device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_
             }
             row[old + L] = t;
             if (s_new) s_new[L] = t;
-            ap.r_len[ap.slot_ids[b]] = old + L + 1;
+            ap.r_len[slot_of_b] = old + L + 1;
         }
     }
     return !slot_ok ? 0 : (row ? old + L + 1 : old);
@@ -1833,7 +1836,8 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
             // LDS that the occurrence sort takes over afterwards
             int32_t *s_tgt = reinterpret_cast<int32_t *>(smem), *s_anc = s_tgt + 260, *s_ok = s_anc + 256;
             const int nl = accept_wave<true>(b, out.d_n_nodes, out.d_tokens, out.d_parents,
-                                             out.max_nodes, aa, ap, s_tgt, s_anc, s_ok, sh.newtok);
+                                             out.max_nodes, aa, ap, s_tgt, s_anc, s_ok, sh.newtok,
+                                             slot, t_old);
             if (lane == 0) sh.t_new = nl;
         }
         // The barrier orders the first wave's stores to the row before the other waves' loads
