@@ -54,3 +54,40 @@ def test_binding_has_no_fallback():
                 txt = open(os.path.join(root, f)).read()
                 assert "import oracle" not in txt and "from oracle" not in txt, f
                 assert "suffix_trie" not in txt, f
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py --gpus N with N above 1 exits with a message before anything touches a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and "--gpus 2" in r.stderr
+    assert r.stdout.strip() == ""
+
+
+def test_workload_generators_are_seeded_and_shaped():
+    """The synthetic inputs are functions of (configuration, seed) alone, with the shapes the
+    configuration names."""
+    import numpy as np
+    from workloads import CONFIGS, make_workload, scaled
+    a = make_workload("tiny", seed=3)
+    b = make_workload("tiny", seed=3)
+    c = make_workload("tiny", seed=4)
+    for f in ("corpus", "doc_offsets", "contexts", "future"):
+        assert np.array_equal(getattr(a, f), getattr(b, f)), f
+    assert not np.array_equal(a.corpus, c.corpus)
+    cfg = CONFIGS["tiny"]
+    assert a.contexts.shape == (cfg["batch"], cfg["ctx"]) and a.batch == cfg["batch"]
+    assert a.corpus.dtype == np.int32 and a.contexts.dtype == np.int32
+    assert a.corpus.min() >= 0 and a.corpus.max() < cfg["vocab"]
+    assert a.doc_offsets[0] == 0 and a.doc_offsets[-1] == len(a.corpus)
+    assert np.all(np.diff(a.doc_offsets) > 0)
+    assert a.max_nodes == int(np.floor(cfg["alpha"] * cfg["P"]))
+    z = make_workload(scaled("lowrep", n_docs=20, doc_len=(300, 300), batch=4, ctx=64), seed=1)
+    assert z.contexts.shape == (4, 64) and len(z.corpus) == 20 * 300
+    # the low-repetition stream is skewed: its most frequent token is far above the uniform share
+    top = np.bincount(z.corpus).max() / len(z.corpus)
+    assert top > 20.0 / z.vocab
