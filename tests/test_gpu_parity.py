@@ -411,6 +411,42 @@ def test_accept_on_synthetic_trees():
         sd.sd_destroy(ctx)
 
 
+def test_verifier_stand_in_matches_its_definition():
+    """The simulated target model of the serving-loop glue (the token after a draft node of
+    depth k is the k-th ground-truth token) against the plain numpy statement of the same
+    thing, on chains, bushy trees and empty trees, with and without moving the positions on."""
+    import torch
+    from workloads import verifier
+    rng = np.random.default_rng(23)
+    B, mn, flen = 40, 256, 700
+    dev = torch.device("cuda", 0)
+    pars = np.full((B, mn), -1, np.int32)
+    nn = np.zeros(B, np.int32)
+    for b in range(B):
+        n = int(rng.integers(0, mn + 1)) if b % 4 else (0 if b == 0 else mn)
+        nn[b] = n
+        if b % 3 == 0:
+            pars[b, :n] = np.arange(-1, n - 1)                         # one long chain
+        else:
+            pars[b, :n] = [int(rng.integers(-1, j)) for j in range(n)]
+    future = rng.integers(0, 1000, (B, flen)).astype(np.int32)
+    pos = rng.integers(0, 100, B).astype(np.int32)
+    adv = rng.integers(-1, 20, B).astype(np.int32)
+    for use_adv in (False, True):
+        d_pos = torch.from_numpy(pos.copy()).to(dev)
+        d_tgt = torch.full((B, mn + 1), -7, dtype=torch.int32, device=dev)
+        verifier.targets(torch.from_numpy(nn).to(dev), torch.from_numpy(pars).to(dev),
+                         torch.from_numpy(future).to(dev), d_pos, d_tgt,
+                         advance=torch.from_numpy(adv).to(dev) if use_adv else None)
+        torch.cuda.synchronize()
+        p0 = pos + (adv + 1 if use_adv else 0)
+        assert np.array_equal(d_pos.cpu().numpy(), p0)
+        want = parity.targets_from_future({"n_nodes": nn, "parents": pars},
+                                          np.stack([future[b, p0[b]:p0[b] + mn + 2] for b in range(B)]),
+                                          mn)
+        assert np.array_equal(d_tgt.cpu().numpy(), want)
+
+
 def test_device_flags_bad_token_slot_and_overflow():
     g = parity.GpuPath(10, 6, 3, 1.0, 0.1, 2, 16, 100)
     try:

@@ -17,7 +17,7 @@ __global__ __launch_bounds__(64) void k_targets(const int32_t *__restrict__ n_no
                                                 int64_t future_stride, int32_t *__restrict__ pos,
                                                 const int32_t *__restrict__ advance,
                                                 int32_t *__restrict__ target) {
-    __shared__ int32_t s_par[256];
+    __shared__ int32_t s_anc[256], s_dep[256];
     const int b = blockIdx.x, lane = threadIdx.x;
     int n = n_nodes[b];
     if (n > 256) n = 256;
@@ -26,19 +26,43 @@ __global__ __launch_bounds__(64) void k_targets(const int32_t *__restrict__ n_no
     if (advance && lane == 0) pos[b] = p0;
     const int32_t *fut = future + (int64_t)b * future_stride + p0;
     int32_t *tgt = target + (int64_t)b * (max_nodes + 1);
-    for (int j = lane; j < n; j += 64) s_par[j] = par[j];   // ancestor walks run out of LDS
-    __syncthreads();
     const int32_t f0 = fut[0];
-    if (lane == 0) tgt[0] = f0;
-    for (int j = lane; j < max_nodes; j += 64) {
-        int32_t v = f0;
-        if (j < n) {
-            int d = 1;
-            for (int q = s_par[j]; q >= 0 && q < j; q = s_par[q]) d++;
-            v = fut[d];
-        }
-        tgt[1 + j] = v;
+    // depth of every node by pointer jumping over the parent links (a link must lead to a
+    // lower index): log2(depth) rounds instead of a walk of `depth` dependent steps
+    for (int j = lane; j < n; j += 64) {
+        const int32_t a = par[j];
+        s_anc[j] = (a >= 0 && a < j) ? a : -1;
+        s_dep[j] = 1;
     }
+    __syncthreads();
+    for (int round = 0; round < 8; round++) {
+        int32_t nd[4], na[4];
+        bool open = false;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const int j = lane + 64 * r;
+            nd[r] = 0; na[r] = -1;
+            if (j < n) {
+                const int32_t a = s_anc[j];
+                nd[r] = s_dep[j];
+                if (a >= 0) {
+                    nd[r] += s_dep[a];
+                    na[r] = s_anc[a];
+                    open = true;
+                }
+            }
+        }
+        if (!__ballot(open)) break;
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+            const int j = lane + 64 * r;
+            if (j < n) { s_dep[j] = nd[r]; s_anc[j] = na[r]; }
+        }
+        __syncthreads();
+    }
+    if (lane == 0) tgt[0] = f0;
+    for (int j = lane; j < max_nodes; j += 64) tgt[1 + j] = j < n ? fut[s_dep[j]] : f0;
 }
 
 // one wavefront per request: new_offsets[b] = sum over earlier requests of (accept_len + 1);
