@@ -7,12 +7,16 @@
 // of suffixes that start with w: COUNT(w) is the width of the range, its children are the
 // runs of equal token at offset |w| inside it, and suffixes that stop at w sit first in it.
 //
-// The sort is prefix doubling: positions are first ordered by their leading two tokens, then
-// each round orders them by the pair (rank of the first h tokens, rank of the next h tokens),
-// which doubles the compared length until it reaches D.  Ranks are group numbers of the
-// previous round, so every round is one radix sort of 2*ceil(log2 N) bit keys; the keys are
-// built in position order (two sequential reads of the rank array), the only random access
-// of a round is the scatter of the new ranks.
+// The sort is prefix doubling: positions are first ordered by their leading two tokens (one
+// radix sort), then each round orders them by the pair (rank of the first h tokens, rank of
+// the next h tokens), which doubles the compared length until it reaches D.  Ranks are group
+// numbers of the previous round, a group being numbered by the place where it starts.  A
+// round only has to reorder entries inside the groups of the round before, which a workgroup
+// does in LDS for a tile of the array as long as no group is longer than the tile's halo
+// (k_round_small); only otherwise is the round a device-wide radix sort of 2*ceil(log2 N) bit
+// keys, built in position order from the rank array (k_round_keys).  The random accesses
+// of a round are the gather of the second ranks, for entries that still share a group, and
+// the store of the ranks that changed.
 //
 // Per-request index: the contexts are kept as plain token rows (one per slot) followed by end
 // markers; occurrences are found by scanning the row at speculation time, so building is a
