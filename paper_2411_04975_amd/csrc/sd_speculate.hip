@@ -7,16 +7,20 @@
 // the runs of equal token at offset d inside the range (an end marker, which sorts first,
 // means the suffix stops there and is no child).
 //
-//  k_req_occurrences  one workgroup per request: scan the context for earlier occurrences of
-//                     its last token, measure how far each extends to the left (up to P), and
-//                     sort the occurrences by what follows them.  The occurrences with
-//                     left-extension >= p, in that order, are the sorted suffix list of the
-//                     per-request structure below the pattern of length p.
-//  k_expand           one wavefront per (request, index, p) unit: find the node N_p, then
-//                     grow the tree greedily; the frontier lives in LDS, the arg-max is a
-//                     wave reduction.
-//  k_select           one wavefront per request: strictly-greater scan over the 2P unit
-//                     scores, coalesced copy of the winner.
+// One kernel, k_speculate, one workgroup per request (up to 16 wavefronts):
+//   1. all waves: scan the context for earlier occurrences of its last token, measure how far
+//      each extends to the left (up to P) and sort the occurrences by what follows them; the
+//      occurrences with left-extension >= p, in that order, are the sorted suffix list of the
+//      per-request structure below the pattern of length p.  Meanwhile the waves match the P
+//      patterns against the global index (first token -> bucket, second token -> column,
+//      then the text).
+//   2. pattern lengths with equal occurrence counts share one expansion; the waves take such
+//      runs from a queue in LDS and grow the trees greedily, one wavefront per tree (frontier
+//      and tree in LDS, arg-max by wave-wide maxima, shortcuts for unary runs and for tied
+//      single-occurrence chains).
+//   3. every wave keeps its best tree; the best of the workgroup is written out.
+// The same kernel has a form that first settles the previous step (acceptance of the verified
+// drafts, append of the accepted tokens), and k_accept does that alone.
 #include <math.h>
 
 #include "sd_internal.h"
