@@ -1,5 +1,6 @@
-// LSD radix sort of (uint64 key, uint32 value) pairs and a device-wide prefix sum, both
-// hand-written for 64-wide wavefronts.  Used by the suffix-array construction in sd_build.hip.
+// LSD radix sort of (uint64 key, uint32 value) pairs and the numbering of the groups of a
+// sorted key array (a device-wide prefix maximum), both hand-written for 64-wide wavefronts.
+// Used by the suffix-array construction in sd_build.hip.
 //
 // One pass = three launches: per-tile digit histogram, per-digit prefix sums along the tiles,
 // stable scatter.  Inside a tile the stable rank of a key among keys with the same
