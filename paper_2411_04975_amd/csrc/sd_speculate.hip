@@ -1240,7 +1240,10 @@ constexpr int SCAN_MAX = 256;
 #define SD_COL_FAN 8
 #endif
 constexpr int COL_FAN = SD_COL_FAN;  // probes per bound and round in a wide bucket (<= 32)
-constexpr int DIRECT_MAX = 8;
+#ifndef SD_DIRECT_MAX
+#define SD_DIRECT_MAX 8
+#endif
+constexpr int DIRECT_MAX = SD_DIRECT_MAX;  // up to this many suffixes are compared with the whole pattern at once
 constexpr int LEVEL_MIN = 256;  // ranges above this are narrowed token by token first
 
 // Narrows the sorted range [l, h) to the entries whose token (tok_at(i), non-decreasing over
