@@ -260,9 +260,25 @@ __global__ __launch_bounds__(TB) void k_insert_merge_old(const int32_t *__restri
                                                          const uint32_t *__restrict__ rank, int64_t M,
                                                          int32_t *__restrict__ sa_out,
                                                          int32_t *__restrict__ tok1_out) {
-    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
+    // how many new suffixes rank at or before an old entry: two threads find that for the
+    // first and the last entry of the workgroup among all new suffixes; with few insertions
+    // the two agree for most workgroups, and where they do not the others search between
+    __shared__ int64_t s_cnt[2];
+    const int64_t i0 = (int64_t)blockIdx.x * TB;
+    const int64_t i1 = i0 + TB - 1 < N - 1 ? i0 + TB - 1 : N - 1;
+    if (threadIdx.x < 2) {
+        const int64_t q = threadIdx.x ? i1 : i0;
+        int64_t lo = 0, hi = M;  // number of new suffixes with rank <= q
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) >> 1;
+            if ((int64_t)rank[mid] <= q) lo = mid + 1; else hi = mid;
+        }
+        s_cnt[threadIdx.x] = lo;
+    }
+    __syncthreads();
+    const int64_t i = i0 + threadIdx.x;
     if (i >= N) return;
-    int64_t lo = 0, hi = M;  // number of new suffixes with rank <= i
+    int64_t lo = s_cnt[0], hi = s_cnt[1];  // number of new suffixes with rank <= i
     while (lo < hi) {
         const int64_t mid = (lo + hi) >> 1;
         if ((int64_t)rank[mid] <= i) lo = mid + 1; else hi = mid;
