@@ -999,3 +999,73 @@ def test_fuzz_small_configurations(chunk):
             assert st["err_bad_token"] == 0 and st["err_bad_slot"] == 0 and st["err_ctx_overflow"] == 0
         finally:
             g.close()
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_fuzz_fused_decode_loops(chunk):
+    """40 random small configurations (10 per test), four decode steps each, every step ended by
+    sd_accept_append_speculate: acceptance, appended contexts and next drafts against the
+    oracle.  The targets follow a random draft path for a random number of nodes, so accepted
+    lengths of every size occur; contexts start at every length from empty on."""
+    accepted = 0
+    for seed in range(chunk * 10, chunk * 10 + 10):
+        vocab, D, P, alpha, ms, den_mode, linear, docs, ctxs = _fuzz_case(1000 + seed)
+        rng = np.random.default_rng(9000 + seed)
+        ctxs = [c[:int(rng.integers(0, len(c) + 1))] if rng.random() < 0.3 else c for c in ctxs]
+        B = len(ctxs)
+        N = sum(len(d) for d in docs) + len(docs)
+        g = parity.GpuPath(vocab, D, P, alpha, ms, B, 256 + 5 * 260, N + 4, den_mode=den_mode,
+                           linear=linear)
+        mn = g.max_nodes
+        label = "fused fuzz seed %d (vocab %d D %d P %d alpha %g ms %g den %d lin %d)" % (
+            seed, vocab, D, P, alpha, ms, den_mode, linear)
+        try:
+            g.build_global(docs)
+            g.build_requests(range(B), ctxs)
+            tg = oracle.Trie(D)
+            for d in docs:
+                tg.add_doc(d)
+            tries = []
+            for x in ctxs:
+                t = oracle.Trie(D)
+                t.append(x)
+                tries.append(t)
+            ctxs = [np.asarray(c, np.int32) for c in ctxs]
+            got = g.speculate(range(B))
+            for step in range(4):
+                want = parity.oracle_speculate_batch(tg, ctxs, D, P, alpha, ms, mn,
+                                                     request_tries=tries, den_mode=den_mode,
+                                                     linear=linear)
+                bad = parity.compare_trees(got, want, label + " step %d" % step)
+                assert not bad, "\n".join(bad)
+                # targets: random tokens, then a random root path of the draft made to agree
+                tgt = rng.integers(0, vocab, (B, mn + 1)).astype(np.int32)
+                for b in range(B):
+                    n = int(want["n_nodes"][b])
+                    v = -1
+                    for _ in range(int(rng.integers(0, n + 2))):
+                        kids = [j for j in range(n) if want["parents"][b, j] == v]
+                        if not kids:
+                            break
+                        j = kids[int(rng.integers(0, len(kids)))]
+                        tgt[b, v + 1] = want["tokens"][b, j]
+                        v = j
+                al, ap, bo, got = g.accept_append_speculate(range(B), tgt)
+                for b in range(B):
+                    n = int(want["n_nodes"][b])
+                    L, path, bonus = oracle.accept(want["tokens"][b, :n], want["parents"][b, :n], tgt[b])
+                    assert al[b] == L and bo[b] == bonus and list(ap[b, :L]) == list(path), label
+                    assert list(ap[b, L:]) == [-1] * (mn - L), label
+                    new = np.array([int(want["tokens"][b, j]) for j in path] + [int(bonus)], np.int32)
+                    tries[b].append(new)
+                    ctxs[b] = np.concatenate([ctxs[b], new])
+                    accepted += L
+            want = parity.oracle_speculate_batch(tg, ctxs, D, P, alpha, ms, mn, request_tries=tries,
+                                                 den_mode=den_mode, linear=linear)
+            bad = parity.compare_trees(got, want, label + " after the last step")
+            assert not bad, "\n".join(bad)
+            st = g.stats()
+            assert st["err_ctx_overflow"] == 0 and st["err_bad_token"] == 0, label
+        finally:
+            g.close()
+    assert accepted > 20
