@@ -102,6 +102,9 @@ def main():
     ap.add_argument("--two-launches", action="store_true",
                     help="sd_speculate and sd_accept_append as two launches per step instead of "
                          "sd_accept_append_speculate (the end of a step and the next draft in one)")
+    ap.add_argument("--throughput-batches", default="1024,4096,8192",
+                    help="batch sizes beyond the workload's own at which sd_speculate is timed as "
+                         "throughput work (several workgroups per compute unit); empty: skip")
     ap.add_argument("--seed", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -114,6 +117,7 @@ def main():
     import torch
     import paper_2411_04975_amd as sd
     from workloads import CONFIGS, make_workload, verifier
+    from workloads.synth import extra_contexts
 
     K, W = args.steps, args.warmup
     cfg = CONFIGS[args.workload]
@@ -532,6 +536,66 @@ def main():
                            "tokens_per_s": ins_docs * ins_len / (ins_ms[len(ins_ms) // 2] * 1e-3)}
     sd.sd_destroy(ctx2)
     sd.sd_destroy(ctx)
+
+    # ---- sd_speculate as throughput work: batches of several workgroups per compute unit ----
+    # The workload's own batch is one workgroup per compute unit and bound by its slowest
+    # request; these batches show what the same kernel sustains once the compute units have
+    # requests to overlap.  1024 further contexts are drawn like the workload's; slot i holds
+    # context i % 1024 rotated by (i / 1024) eighths of its length, so every slot asks about
+    # another place of the text.
+    wide = sorted({int(v) for v in args.throughput_batches.split(",") if v.strip()})
+    wide = [nb for nb in wide if nb > B]
+    if wide:
+        drawn = extra_contexts(cfg, args.seed, 1024)
+        nmax = wide[-1]
+        reps = (nmax + 1023) // 1024
+        allc = np.concatenate([np.roll(drawn, -(r * ctx_len // 8) % ctx_len, axis=1) for r in range(reps)])[:nmax]
+        d_wctx = torch.from_numpy(np.ascontiguousarray(allc).reshape(-1)).to(dev)
+        del allc, drawn
+        d_woff = torch.arange(0, (nmax + 1) * ctx_len, ctx_len, dtype=torch.int64, device=dev)
+        d_wslots = torch.arange(nmax, dtype=i32, device=dev)
+        ctx3 = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, nmax, ctx_len + 1,
+                            n_tokens + n_docs, 0)
+        sd.sd_index_build(ctx3, sd.SD_SCOPE_GLOBAL, None, d_corpus, d_doc_off, n_tokens)
+        sd.sd_index_build(ctx3, sd.SD_SCOPE_REQUESTS, d_wslots, d_wctx, d_woff, nmax * ctx_len)
+        torch.cuda.synchronize()
+        by_batch = {}
+        for nb in wide:
+            tr = sd.Trees(nb, mn, dev)
+            sl = d_wslots[:nb].contiguous()
+            for _ in range(3):
+                sd.sd_speculate(ctx3, sl, tr)
+            torch.cuda.synchronize()
+            gw = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gw):
+                for _ in range(10):
+                    sd.sd_speculate(ctx3, sl, tr)
+            torch.cuda.synchronize()
+            ts = []
+            for _ in range(6):
+                e0, e1 = ev(), ev()
+                e0.record()
+                gw.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                ts.append(e0.elapsed_time(e1) / 10)
+            ms = min(ts[1:])
+            sd.sd_debug_profile(ctx3, 2)
+            sd.sd_debug_profile_read(ctx3)
+            sd.sd_speculate(ctx3, sl, tr)
+            nbytes = sd.sd_debug_profile_read(ctx3)["speculate"]["algo_bytes"]
+            sd.sd_debug_profile(ctx3, 0)
+            gbs = nbytes / (ms * 1e-3) / 1e9
+            by_batch[str(nb)] = {"us_per_launch": ms * 1e3, "trees_per_s": nb / (ms * 1e-3),
+                                 "algo_bytes_per_launch": nbytes, "achieved_gbs": gbs,
+                                 "frac_of_peak": gbs / HBM_PEAK_GBS,
+                                 "frac_of_achievable": gbs / achievable_gbs,
+                                 "mean_tree_nodes": float(tr.n_nodes.float().mean().item())}
+            del gw, tr
+        st3 = sd.sd_get_stats(ctx3)
+        assert st3["err_bad_token"] == 0 and st3["err_bad_slot"] == 0, st3
+        sd.sd_destroy(ctx3)
+        out["speculate_throughput_by_batch"] = by_batch
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, n_requests=min(32, B), build_tokens=300_000)
     print(json.dumps(out))

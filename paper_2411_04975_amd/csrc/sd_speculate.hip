@@ -1797,6 +1797,9 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nod
 #ifndef SD_SPEC_OCC
 #define SD_SPEC_OCC 4
 #endif
+#ifndef SD_SPEC_RESIDENT
+#define SD_SPEC_RESIDENT 4  // workgroups per compute unit the wave count is sized for
+#endif
 
 // With ACCEPT the workgroup first settles the verification of the request's previous tree (the
 // one `out` still holds, against aa.target) on its first wave, appends the accepted tokens and
@@ -2069,11 +2072,15 @@ sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, 
     size_t lds_wave = (size_t)c->max_nodes * (3 * sizeof(double) + 9 * sizeof(int32_t)) +
                       (64 + 64 + TC_TOKENS + 128) * sizeof(int32_t);
     lds_wave = (lds_wave + 7) / 8 * 8;
-    // Waves per request: the compute units hold ceil(batch / #CU) workgroups each at SD_SPEC_OCC
-    // waves per SIMD, within the LDS of one compute unit; at least as much LDS as the
-    // occurrence sort needs.
-    const int per_cu = (batch + c->n_cu - 1) / c->n_cu;
-    int nw = 4 * SD_SPEC_OCC / per_cu;
+    // Waves per request.  Up to two workgroups per compute unit share its SD_SPEC_OCC waves per
+    // SIMD between them.  Larger batches are throughput work: a compute unit's LDS holds about
+    // 20 waves' worth of frontier and staging, so workgroups of 5 waves (4 resident at a time,
+    // the rest wait their turn) keep it fullest; from 13 workgroups per compute unit on, 4
+    // waves measured better (less idle time at the workgroup's barriers).  Thinner workgroups
+    // lose: the occurrence sort's LDS floor then limits how many are resident.
+    const int per_cu_all = (batch + c->n_cu - 1) / c->n_cu;
+    const int per_cu = per_cu_all < SD_SPEC_RESIDENT ? per_cu_all : SD_SPEC_RESIDENT;
+    int nw = per_cu_all <= 2 ? 4 * SD_SPEC_OCC / per_cu_all : per_cu_all <= 12 ? 5 : 4;
     const size_t lds_cu = c->lds_cu > 2048 * (size_t)per_cu ? c->lds_cu - 2048 * (size_t)per_cu : 0;
     while (nw > 1 && (size_t)nw * lds_wave * per_cu > lds_cu) nw--;
     if (nw > 16) nw = 16;

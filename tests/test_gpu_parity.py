@@ -914,6 +914,80 @@ def test_suffix_array_with_long_and_short_groups(D):
         g.close()
 
 
+def test_wide_batches_on_thinner_workgroups():
+    """Batches of several workgroups per compute unit run on workgroups of fewer waves (the
+    library sizes them by the batch): 775 and 3329 requests must give the trees of the oracle
+    row by row, and so must a fused step at 775.  The requests are 112 distinct contexts (16
+    drawn ones, each with 0..6 tokens cut off its end), repeated over the slots."""
+    import paper_2411_04975_amd as sd
+    w = make_workload(scaled("tiny", alpha=2.0, min_score=0.05), seed=5)
+    docs = w.docs()
+    mn = w.max_nodes
+    variants = [w.contexts[i % 16][:w.ctx_len - (i // 16)] for i in range(112)]
+    tg = parity.oracle_global_trie(docs, w.D, w.vocab)
+    tries = []
+    for x in variants:
+        t = oracle.Trie(w.D)
+        t.append(x)
+        tries.append(t)
+    want_v = parity.oracle_speculate_batch(tg, variants, w.D, w.P, w.alpha, w.min_score, mn,
+                                           request_tries=tries)
+    assert len(set(want_v["n_nodes"].tolist())) > 3
+
+    def rows(want, B):
+        idx = np.arange(B) % 112
+        return {k: v[idx] for k, v in want.items()}
+
+    B = 3329
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, w.ctx_len + mn + 1,
+                       len(w.corpus) + len(docs))
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), [variants[b % 112] for b in range(B)])
+        for nb in (3329, 775):
+            got = g.speculate(range(nb))
+            bad = parity.compare_trees(got, rows(want_v, nb), "batch %d" % nb)
+            assert not bad, "\n".join(bad)
+            sd.sd_debug_profile(g.ctx, 3)
+            timed = g.speculate(range(nb))
+            rt, _ = sd.sd_debug_read_request_ticks(g.ctx, nb)
+            sd.sd_debug_profile(g.ctx, 0)
+            assert 1 <= int(rt[0, 0, 7]) < 8, "the batch ran on full-width workgroups"
+            assert not parity.compare_trees(timed, rows(want_v, nb), "timing variant, batch %d" % nb)
+        # the fused step at 775: the targets follow each draft's first-child chain for a
+        # number of nodes that depends on the variant, then differ
+        nb = 775
+        tgt_v = np.full((112, mn + 1), w.vocab - 1, np.int32)
+        new_v = []
+        for i in range(112):
+            n = int(want_v["n_nodes"][i])
+            v = -1
+            for _ in range(i % 5):
+                kids = [j for j in range(n) if want_v["parents"][i, j] == v]
+                if not kids:
+                    break
+                tgt_v[i, v + 1] = want_v["tokens"][i, kids[0]]
+                v = kids[0]
+            L, path, bonus = oracle.accept(want_v["tokens"][i, :n], want_v["parents"][i, :n], tgt_v[i])
+            new = np.array([int(want_v["tokens"][i, j]) for j in path] + [int(bonus)], np.int32)
+            new_v.append((L, list(path), bonus))
+            tries[i].append(new)
+            variants[i] = np.concatenate([variants[i], new])
+        al, ap, bo, got = g.accept_append_speculate(range(nb), tgt_v[np.arange(nb) % 112])
+        for b in range(nb):
+            L, path, bonus = new_v[b % 112]
+            assert al[b] == L and bo[b] == bonus and list(ap[b, :L]) == path, b
+        assert sum(v[0] for v in new_v) > 50
+        want2 = parity.oracle_speculate_batch(tg, variants, w.D, w.P, w.alpha, w.min_score, mn,
+                                              request_tries=tries)
+        bad = parity.compare_trees(got, rows(want2, nb), "fused step, batch %d" % nb)
+        assert not bad, "\n".join(bad)
+        st = g.stats()
+        assert st["err_bad_token"] == 0 and st["err_bad_slot"] == 0 and st["err_ctx_overflow"] == 0
+    finally:
+        g.close()
+
+
 def _fuzz_case(seed):
     """A small random configuration: vocabulary, bounds, thresholds, variants, document and
     context shapes all drawn from the seed (repetitive and random text mixed)."""

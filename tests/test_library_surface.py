@@ -91,3 +91,17 @@ def test_workload_generators_are_seeded_and_shaped():
     # the low-repetition stream is skewed: its most frequent token is far above the uniform share
     top = np.bincount(z.corpus).max() / len(z.corpus)
     assert top > 20.0 / z.vocab
+    # further contexts: seeded, shaped, copied from the same templates as the corpus (their
+    # 8-token windows occur in it far more often than chance allows), yet other contexts
+    from workloads.synth import extra_contexts
+    e = extra_contexts("tiny", 3, 5)
+    assert e.shape == (5, cfg["ctx"]) and e.dtype == np.int32
+    assert np.array_equal(e, extra_contexts("tiny", 3, 5))
+    assert not np.array_equal(e[:5], a.contexts[:5])
+    win = set(map(bytes, np.lib.stride_tricks.sliding_window_view(a.corpus, 8)))
+    hits = sum(bytes(x) in win for x in np.lib.stride_tricks.sliding_window_view(e[0], 8))
+    assert hits > 100
+    other = extra_contexts("tiny", 4, 5)       # another seed: other templates
+    assert sum(bytes(x) in win for x in np.lib.stride_tricks.sliding_window_view(other[0], 8)) == 0
+    ez = extra_contexts(scaled("lowrep", ctx=64), 1, 3)
+    assert ez.shape == (3, 64) and ez.max() < z.vocab

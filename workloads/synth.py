@@ -209,3 +209,26 @@ def make_workload(cfg, seed: int = 0, future_len: Optional[int] = None, name: Op
                     corpus=np.ascontiguousarray(corpus), doc_offsets=offs,
                     contexts=np.ascontiguousarray(contexts), future=np.ascontiguousarray(future),
                     seed=seed, steps=steps, params=dict(cfg))
+
+
+def extra_contexts(cfg, seed: int, n: int) -> np.ndarray:
+    """`n` further contexts of a configuration, int32[n, ctx]: drawn by the same process as
+    make_workload's (for a templated configuration from the very templates that
+    make_workload(cfg, seed) copies from), with a generator of their own."""
+    if isinstance(cfg, str):
+        cfg = CONFIGS[cfg]
+    vocab, ctx = int(cfg["vocab"]), int(cfg["ctx"])
+    rng2 = np.random.default_rng(np.random.PCG64([seed, 0x65787472]))
+    if cfg["kind"] == "templated":
+        rng = np.random.default_rng(np.random.PCG64(seed))       # replay the draws up to the templates
+        _doc_lengths(rng, cfg.get("n_docs"), cfg["doc_len"], cfg.get("total"))
+        templates = rng.integers(0, vocab, size=(cfg["n_templates"], cfg["template_len"]),
+                                 dtype=np.int32)
+        toks, _, _ = _templated_sequences(rng2, templates, np.full(n, ctx, np.int64), cfg["span"],
+                                          cfg["mut"], vocab)
+    else:
+        cdf = _zipf_table(vocab, cfg["zipf_s"])
+        toks = np.searchsorted(cdf, rng2.random(n * ctx), side="left").astype(np.int32)
+        np.minimum(toks, vocab - 1, out=toks)
+    return np.ascontiguousarray(toks.reshape(n, ctx))
+
