@@ -35,6 +35,7 @@ struct SpecParams {
     int32_t max_slots, max_ctx;
     int32_t D, P, max_nodes;
     int32_t den_mode, linear;
+    int32_t occ_cap;  // occurrence records (with their keys) that fit the workgroup's LDS
     double alpha, min_score, tau;
     int2 *occ;
     int32_t *unit_sa;
@@ -267,6 +268,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
     const int nq = t_old > 0 ? (t_old + 3) >> 2 : 0;
     int4(&v)[4] = st.v;
     const int n_new = t - t_old;
+    const int occ_cap = p.occ_cap;  // records the workgroup's LDS can sort
     const int32_t last = n_new > 0 ? newtok[n_new - 1] : st.last_old;
     if (t > 0) {
         // the first t_old tokens, from memory (what sits behind them in a loaded word is not
@@ -295,14 +297,14 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                     int off = 0;
                     if (lane == 0) off = atomicAdd(&sh.m, all);
                     off = uni(off) + below;
-                    // the first OCC_LDS_SORT hits are also kept in LDS, where they are sorted
+                    // the first occ_cap hits are also kept in LDS, where they are sorted
                     const int es[4] = {e0, e0 + 1, e0 + 2, e0 + 3};
                     const int hs[4] = {h0, h1, h2, h3};
 #pragma unroll
                     for (int c = 0; c < 4; c++)
                         if (hs[c]) {
                             occ[off].x = es[c];
-                            if (off < OCC_LDS_SORT) s_sort[off].x = es[c];
+                            if (off < occ_cap) s_sort[off].x = es[c];
                             off++;
                         }
                 }
@@ -319,7 +321,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                     off = uni(off) + __popcll(hm & lanemask_lt());
                     if ((hm >> lane) & 1) {
                         occ[off].x = t_old + i;
-                        if (off < OCC_LDS_SORT) s_sort[off].x = t_old + i;
+                        if (off < occ_cap) s_sort[off].x = t_old + i;
                     }
                 }
             }
@@ -331,7 +333,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
     // A single occurrence is the context's own last token: nothing follows it, so no pattern
     // has a continuation in this index, and the counts stay at zero, which says just that.
     if (m <= 1) return;
-    const bool in_lds = m <= OCC_LDS_SORT;
+    const bool in_lds = m <= occ_cap;
     // How far each occurrence extends to the left together with the context's own tail.  An
     // occurrence takes PP lanes (P rounded up to a power of two): lane k of them compares the
     // k-th token before both ends.  A wave handles 64 / PP occurrences side by side and four
@@ -398,7 +400,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                 // look at no token further than that many places behind it.  Where that is two
                 // or less the key is the whole order; such occurrences come before the others
                 // of the same key, which are ordered among themselves by the tokens beyond.
-                uint64_t *key = reinterpret_cast<uint64_t *>(s_sort + OCC_LDS_SORT);
+                uint64_t *key = reinterpret_cast<uint64_t *>(s_sort + occ_cap);
                 for (int i = tid; i < m; i += nthr) {
                     const int e = s_sort[i].x;
                     const uint32_t t1 = (uint32_t)(x[e + 1] + 1);
@@ -2074,23 +2076,26 @@ sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, 
     lds_wave = (lds_wave + 7) / 8 * 8;
     // Waves per request.  Up to two workgroups per compute unit share its SD_SPEC_OCC waves per
     // SIMD between them.  Larger batches are throughput work: a compute unit's LDS holds about
-    // 20 waves' worth of frontier and staging, so workgroups of 5 waves (4 resident at a time,
-    // the rest wait their turn) keep it fullest; from 13 workgroups per compute unit on, 4
-    // waves measured better (less idle time at the workgroup's barriers).  Thinner workgroups
-    // lose: the occurrence sort's LDS floor then limits how many are resident.
+    // 20 waves' worth of frontier and staging, so the workgroups are sized to fill it (three
+    // of 6 waves, four of 5, or five of 4 resident at a time; the rest wait their turn).  From
+    // 9 workgroups per compute unit on, 4 waves measured better than 5 (less idle time at the
+    // workgroup's barriers); thinner workgroups lose, since every request then takes longer
+    // and the end of the launch runs half empty.
     const int per_cu_all = (batch + c->n_cu - 1) / c->n_cu;
     const int per_cu = per_cu_all < SD_SPEC_RESIDENT ? per_cu_all : SD_SPEC_RESIDENT;
-    int nw = per_cu_all <= 2 ? 4 * SD_SPEC_OCC / per_cu_all : per_cu_all <= 12 ? 5 : 4;
+    int nw = per_cu_all <= 2 ? 4 * SD_SPEC_OCC / per_cu_all
+             : per_cu_all == 3 ? 6 : per_cu_all <= 8 ? 5 : 4;
     const size_t lds_cu = c->lds_cu > 2048 * (size_t)per_cu ? c->lds_cu - 2048 * (size_t)per_cu : 0;
     while (nw > 1 && (size_t)nw * lds_wave * per_cu > lds_cu) nw--;
     if (nw > 16) nw = 16;
     if (nw < 1) nw = 1;
     size_t lds = (size_t)nw * lds_wave;
-    // the occurrence sort keeps 2048 records and their keys in the same LDS before the waves
-    // take it over
-    if (lds < OCC_LDS_SORT * (sizeof(int2) + sizeof(uint64_t)))
-        lds = OCC_LDS_SORT * (sizeof(int2) + sizeof(uint64_t));
+    // the occurrence sort keeps up to OCC_LDS_SORT records and their keys in the same LDS
+    // before the waves take it over: as many as fit, and room for at least half of that
+    const size_t rec = sizeof(int2) + sizeof(uint64_t);
+    if (lds < OCC_LDS_SORT / 2 * rec) lds = OCC_LDS_SORT / 2 * rec;
     if (lds > c->lds_optin) return SD_ERR_CAPACITY;
+    p.occ_cap = lds / rec < (size_t)OCC_LDS_SORT ? (int32_t)(lds / rec) : OCC_LDS_SORT;
     const dim3 grid((unsigned)batch), block(64 * nw);
     if (aa) {
         sd_span sp(c, SD_K_ACCEPT_SPECULATE, st);

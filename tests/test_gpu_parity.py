@@ -917,13 +917,21 @@ def test_suffix_array_with_long_and_short_groups(D):
 def test_wide_batches_on_thinner_workgroups():
     """Batches of several workgroups per compute unit run on workgroups of fewer waves (the
     library sizes them by the batch): 775 and 3329 requests must give the trees of the oracle
-    row by row, and so must a fused step at 775.  The requests are 112 distinct contexts (16
-    drawn ones, each with 0..6 tokens cut off its end), repeated over the slots."""
+    row by row, and so must a fused step at 775.  The requests are 114 distinct contexts,
+    repeated over the slots: 16 drawn ones, each with 0..6 tokens cut off its end, and two of
+    three tokens only whose last token occurs about 1400 and 1650 times: thinner workgroups
+    have less LDS, so these are sorted in LDS at one width and in device memory at another."""
     import paper_2411_04975_amd as sd
     w = make_workload(scaled("tiny", alpha=2.0, min_score=0.05), seed=5)
     docs = w.docs()
     mn = w.max_nodes
     variants = [w.contexts[i % 16][:w.ctx_len - (i // 16)] for i in range(112)]
+    rng = np.random.default_rng(77)
+    for share in (0.74, 0.86):
+        x = np.where(rng.random(1900) < share, 7, rng.integers(8, 10, 1900)).astype(np.int32)
+        x[-1] = 7
+        variants.append(x)
+    NV = len(variants)
     tg = parity.oracle_global_trie(docs, w.D, w.vocab)
     tries = []
     for x in variants:
@@ -935,15 +943,15 @@ def test_wide_batches_on_thinner_workgroups():
     assert len(set(want_v["n_nodes"].tolist())) > 3
 
     def rows(want, B):
-        idx = np.arange(B) % 112
+        idx = np.arange(B) % NV
         return {k: v[idx] for k, v in want.items()}
 
     B = 3329
-    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, w.ctx_len + mn + 1,
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, 1900 + mn + 1,
                        len(w.corpus) + len(docs))
     try:
         g.build_global(docs)
-        g.build_requests(range(B), [variants[b % 112] for b in range(B)])
+        g.build_requests(range(B), [variants[b % NV] for b in range(B)])
         for nb in (3329, 775):
             got = g.speculate(range(nb))
             bad = parity.compare_trees(got, rows(want_v, nb), "batch %d" % nb)
@@ -957,9 +965,9 @@ def test_wide_batches_on_thinner_workgroups():
         # the fused step at 775: the targets follow each draft's first-child chain for a
         # number of nodes that depends on the variant, then differ
         nb = 775
-        tgt_v = np.full((112, mn + 1), w.vocab - 1, np.int32)
+        tgt_v = np.full((NV, mn + 1), w.vocab - 1, np.int32)
         new_v = []
-        for i in range(112):
+        for i in range(NV):
             n = int(want_v["n_nodes"][i])
             v = -1
             for _ in range(i % 5):
@@ -973,9 +981,9 @@ def test_wide_batches_on_thinner_workgroups():
             new_v.append((L, list(path), bonus))
             tries[i].append(new)
             variants[i] = np.concatenate([variants[i], new])
-        al, ap, bo, got = g.accept_append_speculate(range(nb), tgt_v[np.arange(nb) % 112])
+        al, ap, bo, got = g.accept_append_speculate(range(nb), tgt_v[np.arange(nb) % NV])
         for b in range(nb):
-            L, path, bonus = new_v[b % 112]
+            L, path, bonus = new_v[b % NV]
             assert al[b] == L and bo[b] == bonus and list(ap[b, :L]) == path, b
         assert sum(v[0] for v in new_v) > 50
         want2 = parity.oracle_speculate_batch(tg, variants, w.D, w.P, w.alpha, w.min_score, mn,
