@@ -1298,6 +1298,52 @@ __device__ __forceinline__ void range_fan(TokAt tok_at, int32_t w1, int32_t &l, 
         h = lu;
 }
 
+// Second stage for buckets a little too wide for the four-loads-per-lane scan (up to WIDE_MAX
+// entries): the same scan with more loads in flight, for two patterns at once.  One memory
+// round instead of the three or four of the multi-way search; the price is reading the whole
+// range, about what the search's probes move in whole lines anyway.
+#ifndef SD_WIDE_MAX
+#define SD_WIDE_MAX 1024
+#endif
+constexpr int WIDE_MAX = SD_WIDE_MAX;  // a multiple of 64; 0 switches the stage off
+// (Not inlined: the route is taken by workloads with buckets of that size only, and kept out
+// of line it costs the others neither registers nor instruction-cache room.)
+struct WideOut {
+    int32_t loA, hiA, loB, hiB;
+    unsigned nb;  // bytes asked for (counting variant)
+};
+template <bool STATS>
+__device__ __attribute__((noinline)) WideOut col_scan_wide(const int32_t *__restrict__ col, bool doA,
+                                                            int32_t w1A, int32_t loA, int32_t hiA,
+                                                            bool doB, int32_t w1B, int32_t loB,
+                                                            int32_t hiB) {
+    unsigned nb = 0;
+    constexpr int C = WIDE_MAX / 64 > 0 ? WIDE_MAX / 64 : 1;
+    const int lane = threadIdx.x & 63;
+    int32_t vA[C], vB[C];
+#pragma unroll
+    for (int c = 0; c < C; c++) {
+        const int32_t iA = loA + c * 64 + lane, iB = loB + c * 64 + lane;
+        vA[c] = doA && iA < hiA ? col[iA] : 0x7fffffff;
+        vB[c] = doB && iB < hiB ? col[iB] : 0x7fffffff;
+        if (doA && iA < hiA) SD_CNT(4);
+        if (doB && iB < hiB) SD_CNT(4);
+    }
+    // per-lane counts (at most C each), "less" in the low and "not greater" in the high half
+    // of a word, summed over the wave at the end
+    int32_t cA = 0, cB = 0;
+#pragma unroll
+    for (int c = 0; c < C; c++) {
+        cA += (vA[c] < w1A ? 1 : 0) + (vA[c] <= w1A ? 0x10000 : 0);
+        cB += (vB[c] < w1B ? 1 : 0) + (vB[c] <= w1B ? 0x10000 : 0);
+    }
+    const int32_t sA = __builtin_amdgcn_readlane(wave_inclusive_sum(cA), 63);
+    const int32_t sB = __builtin_amdgcn_readlane(wave_inclusive_sum(cB), 63);
+    if (doA) { hiA = loA + (sA >> 16); loA = loA + (sA & 0xffff); }
+    if (doB) { hiB = loB + (sB >> 16); loB = loB + (sB & 0xffff); }
+    return WideOut{loA, hiA, loB, hiB, nb};
+}
+
 // last stage for one pattern: [lo, hi) holds the suffixes that start with its first two tokens
 template <bool STATS>
 __device__ __forceinline__ void match_rest(const SpecParams &p, int32_t wk, int pl, int32_t &lo,
@@ -1369,7 +1415,11 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
     const int32_t w1 = __builtin_amdgcn_readlane(wk, 1);
     const int32_t *col = p.g_tok1;
     int32_t l = lo, h = hi;
-    if (h - l > SCAN_MAX) {
+    if (h - l > SCAN_MAX && h - l <= WIDE_MAX) {
+        const WideOut r = col_scan_wide<STATS>(col, true, w1, l, h, false, 0, 0, 0);
+        l = r.loA; h = r.hiA;
+        SD_CNT(r.nb);
+    } else if (h - l > SCAN_MAX) {
         range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1, l, h, nb);
     } else {
         int32_t v[SCAN_MAX / 64];
@@ -1432,8 +1482,14 @@ __device__ __forceinline__ void match_global_pair(const SpecParams &p, int32_t w
         if (narrowA) { hiA = loA + leA; loA = loA + lsA; }
         if (narrowB) { hiB = loB + leB; loB = loB + lsB; }
     }
-    if (goA && !narrowA) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1A, loA, hiA, nb);
-    if (goB && !narrowB) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1B, loB, hiB, nb);
+    const bool midA = goA && !narrowA && hiA - loA <= WIDE_MAX, midB = goB && !narrowB && hiB - loB <= WIDE_MAX;
+    if (midA || midB) {
+        const WideOut r = col_scan_wide<STATS>(col, midA, w1A, loA, hiA, midB, w1B, loB, hiB);
+        loA = r.loA; hiA = r.hiA; loB = r.loB; hiB = r.hiB;
+        SD_CNT(r.nb);
+    }
+    if (goA && !narrowA && !midA) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1A, loA, hiA, nb);
+    if (goB && !narrowB && !midB) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1B, loB, hiB, nb);
     // last stage: compare the few suffixes left with the whole pattern, A in the lower half of
     // the wave and B in the upper half
     const bool restA = goA && plA > 2 && loA < hiA, restB = goB && plB > 2 && loB < hiB;

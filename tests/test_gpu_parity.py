@@ -914,6 +914,50 @@ def test_suffix_array_with_long_and_short_groups(D):
         g.close()
 
 
+@pytest.mark.parametrize("n", [255, 256, 257, 640, 1023, 1024, 1025, 2500])
+def test_first_token_buckets_around_the_scan_limits(n):
+    """The second pattern token is located inside the first token's bucket by one of three
+    routes, chosen by the bucket's size (up to 256 entries, up to 1024, beyond): token 0 gets
+    exactly n occurrences here, other tokens about n / 5 or n / 3, and patterns of every length
+    up to 20 (so that both the one-pattern and the two-patterns-at-once stages run) must match
+    as in the oracle."""
+    rng = np.random.default_rng(n)
+    body = []
+    for i in range(n):
+        body += [0, 1 + int(rng.integers(0, 5)), 6 + int(rng.integers(0, 3))]
+        if rng.random() < 0.3:
+            body.append(9 + int(rng.integers(0, 3)))
+    doc = np.array(body, np.int32)
+    assert int((doc == 0).sum()) == n
+    docs = [doc[:len(doc) // 2], doc[len(doc) // 2:]]
+    ctxs = []
+    for _ in range(12):
+        a = int(rng.integers(0, len(doc) - 30))
+        x = doc[a:a + int(rng.integers(2, 30))].copy()
+        k = int(rng.integers(0, 3))
+        if k == 1:
+            x = np.concatenate([x, [0]])                         # ends with the wide bucket's token
+        elif k == 2:
+            x = np.concatenate([x, [0, 1 + int(rng.integers(0, 5))]])
+        ctxs.append(x.astype(np.int32))
+    vocab, D, P, alpha, ms = 12, 24, 20, 1.0, 0.02
+    B = len(ctxs)
+    g = parity.GpuPath(vocab, D, P, alpha, ms, B, 64, len(doc) + 4)
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), ctxs)
+        got = g.speculate(range(B))
+        tg = oracle.Trie(D)
+        for d in docs:
+            tg.add_doc(d)
+        want = parity.oracle_speculate_batch(tg, ctxs, D, P, alpha, ms, g.max_nodes)
+        bad = parity.compare_trees(got, want, "bucket of %d" % n)
+        assert not bad, "\n".join(bad)
+        assert int((want["source"] == 0).sum()) >= B // 2
+    finally:
+        g.close()
+
+
 def test_wide_batches_on_thinner_workgroups():
     """Batches of several workgroups per compute unit run on workgroups of fewer waves (the
     library sizes them by the batch): 775 and 3329 requests must give the trees of the oracle
