@@ -30,7 +30,7 @@ bool dev_alloc(T **p, int64_t count, int64_t *acc) {
 }
 
 void free_all(sd_ctx *c) {
-    void *ptrs[] = {c->g_text, c->g_sa, c->g_bucket, c->g_tok1, c->b_keys[0], c->b_keys[1], c->b_vals[0],
+    void *ptrs[] = {c->g_text, c->g_sa, c->g_bucket, c->g_tok1, c->g_tok1s, c->b_keys[0], c->b_keys[1], c->b_vals[0],
                     c->b_vals[1], c->b_rank, c->b_flags, c->b_gid2, c->b_hist, c->b_partials, c->r_text,
                     c->r_len, c->s_occ, c->s_unit_sa, c->d_err, c->s_unit_ticks, c->d_entropy,
                     c->d_round_flag};
@@ -90,6 +90,7 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     // g_sa / g_tok1 change places with build scratch buffers on insertion: same sizes as those
     ok = ok && dev_alloc(&c->g_sa, cap + 64, ib);
     ok = ok && dev_alloc(&c->g_tok1, cap + 64, ib);
+    ok = ok && dev_alloc(&c->g_tok1s, cap / 16 + 64, ib);
     ok = ok && dev_alloc(&c->g_bucket, (int64_t)cfg->vocab + 2, ib);
     ok = ok && dev_alloc(&c->b_keys[0], cap, sb) && dev_alloc(&c->b_keys[1], cap, sb);
     ok = ok && dev_alloc(&c->b_vals[0], cap + 64, sb) && dev_alloc(&c->b_vals[1], cap + 64, sb);

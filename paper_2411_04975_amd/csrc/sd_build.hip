@@ -99,6 +99,15 @@ __global__ __launch_bounds__(TB) void k_round_keys(const uint32_t *__restrict__ 
     }
 }
 
+// Every 16th entry of the second-token column, kept beside it: a lookup in a bucket of a few
+// hundred to a few thousand suffixes reads the bucket's samples (a sixteenth of its lines) and
+// then only the two 16-entry blocks that hold the ends of the range.
+__global__ __launch_bounds__(TB) void k_sample_col(const int32_t *__restrict__ col, int64_t N,
+                                                   int32_t *__restrict__ samples) {
+    const int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (j * 16 < N) samples[j] = col[j * 16];
+}
+
 // Second-token column from the keys of the first sort (token codes of the two leading tokens).
 // Every later step only reorders entries inside groups that share at least those two tokens,
 // so the column by place stays what it is here.
@@ -432,6 +441,7 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
         const int cur = build_sorted_positions(c, c->g_text, N, c->g_tok1, st);
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_finish_sa, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], N,
                   c->g_sa);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_sample_col, dim3(nblk((N + 15) / 16)), dim3(TB), 0, c->g_tok1, N, c->g_tok1s);
     }
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, N, vocab, c->g_bucket);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
@@ -468,6 +478,7 @@ sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_
     c->g_N = N + M;
     c->g_tokens += n_tokens;
     c->g_docs += n_seq;
+    SD_LAUNCH(c, SD_K_INSERT, st, k_sample_col, dim3(nblk((c->g_N + 15) / 16)), dim3(TB), 0, c->g_tok1, c->g_N, c->g_tok1s);
     SD_LAUNCH(c, SD_K_INSERT, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, c->g_N, vocab, c->g_bucket);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }

@@ -29,6 +29,7 @@ struct sd_ctx {
     int32_t *g_sa = nullptr;
     int32_t *g_bucket = nullptr;
     int32_t *g_tok1 = nullptr;   // g_tok1[i] = g_text[g_sa[i] + 1]: second token of suffix i
+    int32_t *g_tok1s = nullptr;  // g_tok1s[j] = g_tok1[16 j]: every 16th entry of that column
     int64_t g_cap = 0;       // capacity in positions (tokens + documents)
     int64_t g_N = 0;         // positions in use
     int64_t g_tokens = 0, g_docs = 0;

@@ -28,7 +28,7 @@
 namespace {
 
 struct SpecParams {
-    const int32_t *g_text, *g_sa, *g_bucket, *g_tok1;
+    const int32_t *g_text, *g_sa, *g_bucket, *g_tok1, *g_tok1s;
     int32_t g_N;
     const int32_t *r_text, *r_len;
     int64_t r_stride;
@@ -1298,49 +1298,71 @@ __device__ __forceinline__ void range_fan(TokAt tok_at, int32_t w1, int32_t &l, 
         h = lu;
 }
 
-// Second stage for buckets a little too wide for the four-loads-per-lane scan (up to WIDE_MAX
-// entries): the same scan with more loads in flight, for two patterns at once.  One memory
-// round instead of the three or four of the multi-way search; the price is reading the whole
-// range, about what the search's probes move in whole lines anyway.
-#ifndef SD_WIDE_MAX
-#define SD_WIDE_MAX 1024
-#endif
-constexpr int WIDE_MAX = SD_WIDE_MAX;  // a multiple of 64; 0 switches the stage off
-// (Not inlined: the route is taken by workloads with buckets of that size only, and kept out
-// of line it costs the others neither registers nor instruction-cache room.)
+// Result of an out-of-line second-stage lookup for two patterns.
 struct WideOut {
     int32_t loA, hiA, loB, hiB;
     unsigned nb;  // bytes asked for (counting variant)
 };
+
+// Second stage for buckets of up to SAMPLED_MAX entries through the sampled column (every 16th
+// entry of the column): the bucket's samples are read and counted, which confines each end of
+// the range to the fifteen entries between two samples (or between an end of the bucket and
+// the nearest sample); those two blocks are read next, a quarter of the wave per block (lower
+// and upper end of A, lower and upper end of B).  Two memory rounds and a few lines per pattern;
+// reading such a bucket whole in one round moved eight times the bytes and was slower on the
+// 100M-token corpus, whose buckets are of this size (the step is traffic-bound there).
+// (Not inlined: the route is taken by workloads with buckets of that size only, and kept out
+// of line it costs the others neither registers nor instruction-cache room.)
+constexpr int SAMP_C = 4;                     // sample loads per lane and pattern
+constexpr int SAMPLED_MAX = 64 * SAMP_C * 16;  // widest bucket whose samples one such round covers
 template <bool STATS>
-__device__ __attribute__((noinline)) WideOut col_scan_wide(const int32_t *__restrict__ col, bool doA,
-                                                            int32_t w1A, int32_t loA, int32_t hiA,
-                                                            bool doB, int32_t w1B, int32_t loB,
-                                                            int32_t hiB) {
+__device__ __attribute__((noinline)) WideOut col_sampled(const int32_t *__restrict__ col,
+                                                          const int32_t *__restrict__ samples,
+                                                          bool doA, int32_t w1A, int32_t loA,
+                                                          int32_t hiA, bool doB, int32_t w1B,
+                                                          int32_t loB, int32_t hiB) {
     unsigned nb = 0;
-    constexpr int C = WIDE_MAX / 64 > 0 ? WIDE_MAX / 64 : 1;
     const int lane = threadIdx.x & 63;
-    int32_t vA[C], vB[C];
+    // samples inside a bucket [lo, hi): indices (lo + 15) / 16 .. (hi - 1) / 16
+    const int32_t j0A = (loA + 15) >> 4, j1A = (hiA - 1) >> 4;
+    const int32_t j0B = (loB + 15) >> 4, j1B = (hiB - 1) >> 4;
+    int32_t vA[SAMP_C], vB[SAMP_C];
 #pragma unroll
-    for (int c = 0; c < C; c++) {
-        const int32_t iA = loA + c * 64 + lane, iB = loB + c * 64 + lane;
-        vA[c] = doA && iA < hiA ? col[iA] : 0x7fffffff;
-        vB[c] = doB && iB < hiB ? col[iB] : 0x7fffffff;
-        if (doA && iA < hiA) SD_CNT(4);
-        if (doB && iB < hiB) SD_CNT(4);
+    for (int c = 0; c < SAMP_C; c++) {
+        const int32_t jA = j0A + c * 64 + lane, jB = j0B + c * 64 + lane;
+        vA[c] = doA && jA <= j1A ? samples[jA] : 0x7fffffff;
+        vB[c] = doB && jB <= j1B ? samples[jB] : 0x7fffffff;
+        if (doA && jA <= j1A) SD_CNT(4);
+        if (doB && jB <= j1B) SD_CNT(4);
     }
-    // per-lane counts (at most C each), "less" in the low and "not greater" in the high half
-    // of a word, summed over the wave at the end
-    int32_t cA = 0, cB = 0;
+    int32_t cA = 0, cB = 0;  // samples below the token (low half) and not above it (high half)
 #pragma unroll
-    for (int c = 0; c < C; c++) {
+    for (int c = 0; c < SAMP_C; c++) {
         cA += (vA[c] < w1A ? 1 : 0) + (vA[c] <= w1A ? 0x10000 : 0);
         cB += (vB[c] < w1B ? 1 : 0) + (vB[c] <= w1B ? 0x10000 : 0);
     }
     const int32_t sA = __builtin_amdgcn_readlane(wave_inclusive_sum(cA), 63);
     const int32_t sB = __builtin_amdgcn_readlane(wave_inclusive_sum(cB), 63);
-    if (doA) { hiA = loA + (sA >> 16); loA = loA + (sA & 0xffff); }
-    if (doB) { hiB = loB + (sB >> 16); loB = loB + (sB & 0xffff); }
+    // With c samples below (not above) the token, the lower (upper) end of the range lies
+    // behind sample c - 1 and at or before sample c: in the block of entries between them, or
+    // between the bucket's start and its first sample, or its last sample and its end.
+    const int quarter = lane >> 4, k = lane & 15;
+    const bool isB = quarter >= 2, upper = quarter & 1;
+    const int32_t lo_ = isB ? loB : loA, hi_ = isB ? hiB : hiA, j0 = isB ? j0B : j0A;
+    const int32_t w1 = isB ? w1B : w1A, sc = isB ? sB : sA;
+    const int32_t cnt = upper ? sc >> 16 : sc & 0xffff;
+    const int32_t base = cnt == 0 ? lo_ : ((j0 + cnt - 1) << 4) + 1;
+    int32_t end = (j0 + cnt) << 4;
+    if (end > hi_) end = hi_;
+    const bool act = (isB ? doB : doA) && base + k < end;
+    const int32_t v = act ? col[base + k] : 0x7fffffff;
+    if (act) SD_CNT(4);
+    const uint64_t bm = __ballot(act && (upper ? v <= w1 : v < w1));
+    const int32_t found = base + __popc((uint32_t)(bm >> (quarter * 16)) & 0xffffu);
+    const int32_t nlA = __builtin_amdgcn_readlane(found, 0), nhA = __builtin_amdgcn_readlane(found, 16);
+    const int32_t nlB = __builtin_amdgcn_readlane(found, 32), nhB = __builtin_amdgcn_readlane(found, 48);
+    if (doA) { loA = nlA; hiA = nhA; }
+    if (doB) { loB = nlB; hiB = nhB; }
     return WideOut{loA, hiA, loB, hiB, nb};
 }
 
@@ -1415,8 +1437,8 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
     const int32_t w1 = __builtin_amdgcn_readlane(wk, 1);
     const int32_t *col = p.g_tok1;
     int32_t l = lo, h = hi;
-    if (h - l > SCAN_MAX && h - l <= WIDE_MAX) {
-        const WideOut r = col_scan_wide<STATS>(col, true, w1, l, h, false, 0, 0, 0);
+    if (h - l > SCAN_MAX && h - l <= SAMPLED_MAX) {
+        const WideOut r = col_sampled<STATS>(col, p.g_tok1s, true, w1, l, h, false, 0, 0, 0);
         l = r.loA; h = r.hiA;
         SD_CNT(r.nb);
     } else if (h - l > SCAN_MAX) {
@@ -1482,14 +1504,15 @@ __device__ __forceinline__ void match_global_pair(const SpecParams &p, int32_t w
         if (narrowA) { hiA = loA + leA; loA = loA + lsA; }
         if (narrowB) { hiB = loB + leB; loB = loB + lsB; }
     }
-    const bool midA = goA && !narrowA && hiA - loA <= WIDE_MAX, midB = goB && !narrowB && hiB - loB <= WIDE_MAX;
-    if (midA || midB) {
-        const WideOut r = col_scan_wide<STATS>(col, midA, w1A, loA, hiA, midB, w1B, loB, hiB);
+    const bool smpA = goA && !narrowA && hiA - loA <= SAMPLED_MAX;
+    const bool smpB = goB && !narrowB && hiB - loB <= SAMPLED_MAX;
+    if (smpA || smpB) {
+        const WideOut r = col_sampled<STATS>(col, p.g_tok1s, smpA, w1A, loA, hiA, smpB, w1B, loB, hiB);
         loA = r.loA; hiA = r.hiA; loB = r.loB; hiB = r.hiB;
         SD_CNT(r.nb);
     }
-    if (goA && !narrowA && !midA) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1A, loA, hiA, nb);
-    if (goB && !narrowB && !midB) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1B, loB, hiB, nb);
+    if (goA && !narrowA && !smpA) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1A, loA, hiA, nb);
+    if (goB && !narrowB && !smpB) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1B, loB, hiB, nb);
     // last stage: compare the few suffixes left with the whole pattern, A in the lower half of
     // the wave and B in the upper half
     const bool restA = goA && plA > 2 && loA < hiA, restB = goB && plB > 2 && loB < hiB;
@@ -2113,7 +2136,7 @@ namespace {
 sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
                            const AcceptArgs *aa, hipStream_t st) {
     SpecParams p;
-    p.g_text = c->g_text; p.g_sa = c->g_sa; p.g_bucket = c->g_bucket; p.g_tok1 = c->g_tok1;
+    p.g_text = c->g_text; p.g_sa = c->g_sa; p.g_bucket = c->g_bucket; p.g_tok1 = c->g_tok1; p.g_tok1s = c->g_tok1s;
     p.g_N = (int32_t)c->g_N;
     p.r_text = c->r_text; p.r_len = c->r_len; p.r_stride = c->r_stride;
     p.max_slots = c->cfg.max_batch_slots; p.max_ctx = c->cfg.max_ctx_tokens;

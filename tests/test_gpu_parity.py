@@ -914,7 +914,7 @@ def test_suffix_array_with_long_and_short_groups(D):
         g.close()
 
 
-@pytest.mark.parametrize("n", [255, 256, 257, 640, 1023, 1024, 1025, 2500])
+@pytest.mark.parametrize("n", [255, 256, 257, 640, 1023, 1024, 1025, 2500, 4095, 4096, 4097, 6000])
 def test_first_token_buckets_around_the_scan_limits(n):
     """The second pattern token is located inside the first token's bucket by one of three
     routes, chosen by the bucket's size (up to 256 entries, up to 1024, beyond): token 0 gets
