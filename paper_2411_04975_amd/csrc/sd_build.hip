@@ -99,23 +99,20 @@ __global__ __launch_bounds__(TB) void k_round_keys(const uint32_t *__restrict__ 
     }
 }
 
-// Every 16th entry of the second-token column, kept beside it: a lookup in a bucket of a few
-// hundred to a few thousand suffixes reads the bucket's samples (a sixteenth of its lines) and
-// then only the two 16-entry blocks that hold the ends of the range.
-__global__ __launch_bounds__(TB) void k_sample_col(const int32_t *__restrict__ col, int64_t N,
-                                                   int32_t *__restrict__ samples) {
-    const int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
-    if (j * 16 < N) samples[j] = col[j * 16];
-}
-
 // Second-token column from the keys of the first sort (token codes of the two leading tokens).
 // Every later step only reorders entries inside groups that share at least those two tokens,
-// so the column by place stays what it is here.
+// so the column by place stays what it is here.  Every 16th entry is also kept in the sampled
+// column: a lookup in a bucket of a few hundred to a few thousand suffixes reads the bucket's
+// samples (a sixteenth of its lines) and then only the two 16-entry blocks that hold the ends
+// of the range.
 __global__ __launch_bounds__(TB) void k_tok1_from_keys(const uint64_t *__restrict__ keys, int64_t N,
-                                                       int tok_bits, int32_t *__restrict__ tok1) {
+                                                       int tok_bits, int32_t *__restrict__ tok1,
+                                                       int32_t *__restrict__ samples) {
     int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
     if (i >= N) return;
-    tok1[i] = (int32_t)(keys[i] & ((1ull << tok_bits) - 1ull)) - 1;
+    const int32_t v = (int32_t)(keys[i] & ((1ull << tok_bits) - 1ull)) - 1;
+    tok1[i] = v;
+    if ((i & 15) == 0) samples[i >> 4] = v;
 }
 
 // One doubling round without a device-wide sort, for arrays whose groups are short.  The array
@@ -268,7 +265,8 @@ __global__ __launch_bounds__(TB) void k_insert_merge_old(const int32_t *__restri
                                                          const int32_t *__restrict__ tok1, int64_t N,
                                                          const uint32_t *__restrict__ rank, int64_t M,
                                                          int32_t *__restrict__ sa_out,
-                                                         int32_t *__restrict__ tok1_out) {
+                                                         int32_t *__restrict__ tok1_out,
+                                                         int32_t *__restrict__ samples_out) {
     // how many new suffixes rank at or before an old entry: two threads find that for the
     // first and the last entry of the workgroup among all new suffixes; with few insertions
     // the two agree for most workgroups, and where they do not the others search between
@@ -292,20 +290,25 @@ __global__ __launch_bounds__(TB) void k_insert_merge_old(const int32_t *__restri
         const int64_t mid = (lo + hi) >> 1;
         if ((int64_t)rank[mid] <= i) lo = mid + 1; else hi = mid;
     }
+    const int32_t v = tok1[i];
     sa_out[i + lo] = sa[i];
-    tok1_out[i + lo] = tok1[i];
+    tok1_out[i + lo] = v;
+    if (((i + lo) & 15) == 0) samples_out[(i + lo) >> 4] = v;
 }
 
 __global__ __launch_bounds__(TB) void k_insert_merge_new(const int32_t *__restrict__ text,
                                                          const uint32_t *__restrict__ dsa,
                                                          const uint32_t *__restrict__ rank, int64_t M,
                                                          int64_t base, int32_t *__restrict__ sa_out,
-                                                         int32_t *__restrict__ tok1_out) {
+                                                         int32_t *__restrict__ tok1_out,
+                                                         int32_t *__restrict__ samples_out) {
     int64_t j = (int64_t)blockIdx.x * TB + threadIdx.x;
     if (j >= M) return;
-    const int64_t pos = base + dsa[j];
-    sa_out[(int64_t)rank[j] + j] = (int32_t)pos;
-    tok1_out[(int64_t)rank[j] + j] = text[pos + 1];
+    const int64_t pos = base + dsa[j], dst = (int64_t)rank[j] + j;
+    const int32_t v = text[pos + 1];
+    sa_out[dst] = (int32_t)pos;
+    tok1_out[dst] = v;
+    if ((dst & 15) == 0) samples_out[dst >> 4] = v;
 }
 
 __global__ __launch_bounds__(TB) void k_fill_i32(int32_t *p, int64_t n, int32_t v) {
@@ -392,7 +395,7 @@ static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, int
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_init_keys, dim3(nblk(N)), dim3(TB), 0, text, N, tok_bits, c->b_keys[0], c->b_vals[0]);
     int cur = sd_sort_pairs(c, N, 2 * tok_bits, 0, st);
     if (tok1_out)
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_tok1_from_keys, dim3(nblk(N)), dim3(TB), 0, c->b_keys[cur], N, tok_bits, tok1_out);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_tok1_from_keys, dim3(nblk(N)), dim3(TB), 0, c->b_keys[cur], N, tok_bits, tok1_out, c->g_tok1s);
     const int rank_bits = sd_bits_for((uint64_t)N);  // ranks 0..N
     // So far the positions are ordered by their first h = 2 tokens.  Each round first tries the
     // in-tile reordering (enough once no group is longer than its halo, which stays true for
@@ -441,7 +444,6 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
         const int cur = build_sorted_positions(c, c->g_text, N, c->g_tok1, st);
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_finish_sa, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], N,
                   c->g_sa);
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_sample_col, dim3(nblk((N + 15) / 16)), dim3(TB), 0, c->g_tok1, N, c->g_tok1s);
     }
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, N, vocab, c->g_bucket);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
@@ -469,8 +471,8 @@ sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_
     int32_t *sa_out = (int32_t *)c->b_vals[1 - cur], *tok1_out = (int32_t *)c->b_rank;
     SD_LAUNCH(c, SD_K_INSERT, st, k_insert_rank, dim3(nblk(M)), dim3(TB), 0, c->g_text, c->g_sa, N, c->g_bucket, dsa, M, N, c->cfg.D, rank);
     if (N > 0)
-        SD_LAUNCH(c, SD_K_INSERT, st, k_insert_merge_old, dim3(nblk(N)), dim3(TB), 0, c->g_sa, c->g_tok1, N, rank, M, sa_out, tok1_out);
-    SD_LAUNCH(c, SD_K_INSERT, st, k_insert_merge_new, dim3(nblk(M)), dim3(TB), 0, c->g_text, dsa, rank, M, N, sa_out, tok1_out);
+        SD_LAUNCH(c, SD_K_INSERT, st, k_insert_merge_old, dim3(nblk(N)), dim3(TB), 0, c->g_sa, c->g_tok1, N, rank, M, sa_out, tok1_out, c->g_tok1s);
+    SD_LAUNCH(c, SD_K_INSERT, st, k_insert_merge_new, dim3(nblk(M)), dim3(TB), 0, c->g_text, dsa, rank, M, N, sa_out, tok1_out, c->g_tok1s);
     c->b_vals[1 - cur] = (uint32_t *)c->g_sa;
     c->b_rank = (uint32_t *)c->g_tok1;
     c->g_sa = sa_out;
@@ -478,7 +480,6 @@ sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_
     c->g_N = N + M;
     c->g_tokens += n_tokens;
     c->g_docs += n_seq;
-    SD_LAUNCH(c, SD_K_INSERT, st, k_sample_col, dim3(nblk((c->g_N + 15) / 16)), dim3(TB), 0, c->g_tok1, c->g_N, c->g_tok1s);
     SD_LAUNCH(c, SD_K_INSERT, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, c->g_N, vocab, c->g_bucket);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
