@@ -1876,7 +1876,7 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nod
 // candidates meet in LDS after a barrier and the winning wave writes its tree out, padded
 // with -1 / 0.0.  Nothing but the final tree leaves the compute unit.
 #ifndef SD_SPEC_OCC
-#define SD_SPEC_OCC 4
+#define SD_SPEC_OCC 6  // waves per SIMD that one or two resident workgroups may fill
 #endif
 #ifndef SD_SPEC_RESIDENT
 #define SD_SPEC_RESIDENT 4  // workgroups per compute unit the wave count is sized for
@@ -2153,17 +2153,19 @@ sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, 
     size_t lds_wave = (size_t)c->max_nodes * (3 * sizeof(double) + 9 * sizeof(int32_t)) +
                       (64 + 64 + TC_TOKENS + 128) * sizeof(int32_t);
     lds_wave = (lds_wave + 7) / 8 * 8;
-    // Waves per request.  Up to two workgroups per compute unit share its SD_SPEC_OCC waves per
-    // SIMD between them.  Larger batches are throughput work: a compute unit's LDS holds about
-    // 20 waves' worth of frontier and staging, so the workgroups are sized to fill it (three
-    // of 6 waves, four of 5, or five of 4 resident at a time; the rest wait their turn).  From
-    // 9 workgroups per compute unit on, 4 waves measured better than 5 (less idle time at the
-    // workgroup's barriers); thinner workgroups lose, since every request then takes longer
-    // and the end of the launch runs half empty.
+    // Waves per request.  One workgroup per compute unit takes the 16 waves a workgroup can
+    // have; two share SD_SPEC_OCC waves per SIMD between them (12 each if the LDS allows: the
+    // registers of the kernel leave room for 7 waves per SIMD, and 14 each were not resident
+    // together); three and four likewise (8 and 6 each, or what the LDS allows).  Larger batches
+    // are throughput work: a compute unit's LDS holds about 20 waves' worth of frontier and
+    // staging at the largest tree sizes, so up to eight workgroups per compute unit get 5 waves
+    // (four resident at a time, the rest wait their turn) and more get 4 (five resident; less
+    // idle time at the workgroup's barriers).  Thinner workgroups lose: every request then
+    // takes longer and the end of the launch runs half empty.
     const int per_cu_all = (batch + c->n_cu - 1) / c->n_cu;
     const int per_cu = per_cu_all < SD_SPEC_RESIDENT ? per_cu_all : SD_SPEC_RESIDENT;
     int nw = per_cu_all <= 2 ? 4 * SD_SPEC_OCC / per_cu_all
-             : per_cu_all == 3 ? 6 : per_cu_all <= 8 ? 5 : 4;
+             : per_cu_all == 3 ? 8 : per_cu_all == 4 ? 6 : per_cu_all <= 8 ? 5 : 4;
     const size_t lds_cu = c->lds_cu > 2048 * (size_t)per_cu ? c->lds_cu - 2048 * (size_t)per_cu : 0;
     while (nw > 1 && (size_t)nw * lds_wave * per_cu > lds_cu) nw--;
     if (nw > 16) nw = 16;
