@@ -147,6 +147,50 @@ __device__ __forceinline__ void occ_sort(int2 *arr, uint64_t *key, int m, const 
     }
 }
 
+// The same network with one element per thread, held in registers (n2, the list's length rounded
+// up to a power of two, is at most the workgroup's size; elements beyond the list carry the
+// key ~0 and sink to the end).  A step whose partner sits in the same wave is three lane
+// permutes and a compare; only the steps that cross waves (partner distance 64 and up) go
+// through LDS, with two barriers each: ten of the 55 steps for 1024 elements.  Both partners
+// evaluate the same ordered pair (the lower place's element against the upper place's), so
+// they agree on the outcome.  Every thread of the workgroup calls this (barriers inside).
+template <bool STATS>
+__device__ __forceinline__ int2 occ_sort_regs(int2 rec, uint64_t key, int n2, int2 *s_rec, uint64_t *s_key,
+                                              const int32_t *__restrict__ x, int depth, unsigned &nb) {
+    const int i = threadIdx.x, lane = i & 63;
+    const bool on = i < n2;
+    for (int k = 2; k <= n2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            const int xr = j == (k >> 1) ? k - 1 : j;  // the partner's place is i ^ xr
+            int2 orec = rec;
+            uint64_t okey = key;
+            if (xr < 64) {
+                const int src = lane ^ xr;
+                orec.x = __shfl(rec.x, src);
+                orec.y = __shfl(rec.y, src);
+                const uint32_t klo = (uint32_t)__shfl((int)(uint32_t)key, src);
+                const uint32_t khi = (uint32_t)__shfl((int)(uint32_t)(key >> 32), src);
+                okey = ((uint64_t)khi << 32) | klo;
+            } else {
+                if (on) { s_rec[i] = rec; s_key[i] = key; }
+                __syncthreads();
+                if (on) { orec = s_rec[i ^ xr]; okey = s_key[i ^ xr]; }
+                __syncthreads();
+            }
+            if (on) {
+                const bool lower = (i ^ xr) > i;
+                const int2 a = lower ? rec : orec, b = lower ? orec : rec;  // a: lower place
+                const uint64_t ka = lower ? key : okey, kb = lower ? okey : key;
+                bool swap;
+                if (ka != kb) swap = kb < ka;
+                else swap = ((ka & 1) && ka != ~0ull) ? occ_less<STATS>(x, b, a, depth, nb) : false;
+                if (swap) { rec = orec; key = okey; }
+            }
+        }
+    }
+    return rec;
+}
+
 // Wave-wide maximum in every lane.  Inside a row of 16 lanes the values meet through four
 // data-parallel moves (lane ^ 1, lane ^ 2, 7 - lane within 8, 15 - lane within 16); the four
 // row results are then read out as scalars.
@@ -401,16 +445,33 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                 // or less the key is the whole order; such occurrences come before the others
                 // of the same key, which are ordered among themselves by the tokens beyond.
                 uint64_t *key = reinterpret_cast<uint64_t *>(s_sort + occ_cap);
-                for (int i = tid; i < m; i += nthr) {
-                    const int e = s_sort[i].x;
-                    const uint32_t t1 = (uint32_t)(x[e + 1] + 1);
-                    const uint32_t t2 = depth >= 2 ? (uint32_t)(x[e + 2] + 1) : 0u;
-                    const uint64_t more = floor(p.alpha * (double)s_sort[i].y) > 2.0 ? 1u : 0u;
-                    key[i] = ((uint64_t)t1 << 33) | ((uint64_t)t2 << 1) | more;
-                    SD_CNT(8);
+                int n2 = 1;
+                while (n2 < m) n2 <<= 1;
+                if (n2 <= nthr) {  // one element per thread: sorted in registers
+                    int2 rec = make_int2(0, 0);
+                    uint64_t kk = ~0ull;
+                    if (tid < m) {
+                        rec = s_sort[tid];
+                        const uint32_t t1 = (uint32_t)(x[rec.x + 1] + 1);
+                        const uint32_t t2 = depth >= 2 ? (uint32_t)(x[rec.x + 2] + 1) : 0u;
+                        const uint64_t more = floor(p.alpha * (double)rec.y) > 2.0 ? 1u : 0u;
+                        kk = ((uint64_t)t1 << 33) | ((uint64_t)t2 << 1) | more;
+                        SD_CNT(8);
+                    }
+                    rec = occ_sort_regs<STATS>(rec, kk, n2, s_sort, key, x, depth, nb);
+                    if (tid < m) s_sort[tid] = rec;
+                } else {
+                    for (int i = tid; i < m; i += nthr) {
+                        const int e = s_sort[i].x;
+                        const uint32_t t1 = (uint32_t)(x[e + 1] + 1);
+                        const uint32_t t2 = depth >= 2 ? (uint32_t)(x[e + 2] + 1) : 0u;
+                        const uint64_t more = floor(p.alpha * (double)s_sort[i].y) > 2.0 ? 1u : 0u;
+                        key[i] = ((uint64_t)t1 << 33) | ((uint64_t)t2 << 1) | more;
+                        SD_CNT(8);
+                    }
+                    __syncthreads();
+                    occ_sort<STATS>(s_sort, key, m, x, depth, nb);
                 }
-                __syncthreads();
-                occ_sort<STATS>(s_sort, key, m, x, depth, nb);
             }
             for (int i = tid; i < m; i += nthr) occ[i] = s_sort[i];
         } else {
