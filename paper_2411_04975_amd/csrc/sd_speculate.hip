@@ -557,6 +557,59 @@ __device__ __forceinline__ Key frontier_pick(const Frontier &f, bool want_best) 
     return r;
 }
 
+// The best entry together with its suffix range and depth, and how many entries hold its
+// score (several may be tied chains; a single one is strictly above everything else): what
+// the expansion loop needs of the frontier per step, from one round of LDS reads.
+struct Taken {
+    Key k;
+    int32_t lo, hi, dep;
+    int ntop;
+};
+__device__ __forceinline__ Taken frontier_take(const Frontier &f) {
+    const int lane = threadIdx.x & 63;
+    Taken r;
+    if (f.n > 64) {  // more entries than lanes: the parts one by one
+        r.k = frontier_pick(f, true);
+        r.lo = uni(f.lo[r.k.idx]); r.hi = uni(f.hi[r.k.idx]); r.dep = uni(f.dep[r.k.idx]);
+        r.ntop = 0;
+        for (int i0 = 0; i0 < f.n; i0 += 64) {
+            const int i = i0 + lane;
+            r.ntop += __popcll(__ballot(i < f.n && f.score[i] == r.k.s));
+        }
+        return r;
+    }
+    // lane l holds entry l
+    const bool valid = lane < f.n;
+    const int li = valid ? lane : 0;
+    const double ms = f.score[li];
+    const int32_t mtok = f.tok[li], mpar = f.par[li], mlo = f.lo[li], mhi = f.hi[li], mdep = f.dep[li];
+    const double ninf = -__longlong_as_double(0x7ff0000000000000ll);
+    const double sx = wave_max_f64(valid ? ms : ninf);
+    uint64_t T = __ballot(valid && ms == sx);
+    r.ntop = __popcll(T);
+    if (T & (T - 1)) {  // lowest token among those, then lowest parent
+        const uint32_t tk = ~(uint32_t)mtok;
+        const bool in1 = (T >> lane) & 1;
+        const uint32_t tx = wave_max_u32(in1 ? tk : 0u);
+        T = __ballot(in1 && tk == tx);
+        if (T & (T - 1)) {
+            const uint32_t pk = ~(uint32_t)(mpar + 1);
+            const bool in2 = (T >> lane) & 1;
+            const uint32_t px = wave_max_u32(in2 ? pk : 0u);
+            T = __ballot(in2 && pk == px);
+        }
+    }
+    const int w = __ffsll((unsigned long long)T) - 1;  // f.n > 0: there is one
+    r.k.s = sx;
+    r.k.tok = __builtin_amdgcn_readlane(mtok, w);
+    r.k.par = __builtin_amdgcn_readlane(mpar, w);
+    r.k.idx = w;
+    r.lo = __builtin_amdgcn_readlane(mlo, w);
+    r.hi = __builtin_amdgcn_readlane(mhi, w);
+    r.dep = __builtin_amdgcn_readlane(mdep, w);
+    return r;
+}
+
 // close the slot freed by the node just taken: the last entry moves into it
 __device__ __forceinline__ void frontier_close(Frontier &f, int hole) {
     if (hole < 0) return;
@@ -682,17 +735,19 @@ __device__ __forceinline__ int stage_node(Stage &sg, const int32_t *__restrict__
 }
 
 // Lane l: the token that all m staged suffixes from slot0 on hold at depth d + l, or -2 if they
-// differ there or a window does not reach that far (m <= M).  All window bases are read first,
-// then all tokens: two rounds of LDS reads in flight together instead of 2 m dependent ones
-// (the slots past m repeat the last suffix).
+// differ there or a window does not reach that far (m <= M).  The window bases come from the
+// lanes' registers and all tokens are read in one round of LDS reads (the slots past m repeat
+// the last suffix).
 template <int M>
-__device__ __forceinline__ int32_t common_token(const Stage &sg, int slot0, int m, int d, int W) {
+__device__ __forceinline__ int32_t common_token(const Stage &sg, int slot0, int m, int d, int W,
+                                                int32_t mycb) {
     const int lane = threadIdx.x & 63;
     int32_t off[M], v[M];
+    // window base of suffix i: lane i's value of `mycb` (what stage_node returned)
 #pragma unroll
     for (int i = 0; i < M; i++) {
         const int ii = i < m ? i : m - 1;
-        off[i] = d + lane - sg.cb[slot0 + ii];
+        off[i] = d + lane - __builtin_amdgcn_readlane(mycb, ii);
     }
 #pragma unroll
     for (int i = 0; i < M; i++) {
@@ -1694,22 +1749,17 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
                              nb);
         if (TICKS) tick_root = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(f.n & 0);
         while (n < K && f.n > 0) {
-            const Key best = frontier_pick(f, true);
+            const Taken tk0 = frontier_take(f);
+            const Key best = tk0.k;
             if (best.s < p.min_score) break;
-            // How many entries hold the top score: several may be tied chains; a single one
-            // is strictly above everything else in the frontier.
-            int ntop = 0;
-            for (int i0 = 0; i0 < f.n; i0 += 64) {
-                const int i = i0 + lane;
-                ntop += __popcll(__ballot(i < f.n && f.score[i] == best.s));
-            }
+            const int ntop = tk0.ntop;
             if (ntop >= 2 && !p.linear &&
                 tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok, t_par, t_score,
                                    deepest, nb))
                 continue;
             const int bi = best.idx;
-            const int32_t blo = uni(f.lo[bi]), bhi = uni(f.hi[bi]);
-            int32_t d = uni(f.dep[bi]);
+            const int32_t blo = tk0.lo, bhi = tk0.hi;
+            int32_t d = tk0.dep;
             if (d >= p.D) deepest = true;
             if (lane == 0) {
                 t_tok[n] = best.tok; t_par[n] = best.par; t_score[n] = best.s;
@@ -1728,11 +1778,11 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
             // the run: take the run at once.
             const int32_t m = bhi - blo;
             if (n < K && d < p.D && m <= CHAIN_MAX_M && (ntop == 1 || p.linear)) {
-                stage_node(sg, sa, text, blo, m, d);
+                const int32_t mycb = stage_node(sg, sa, text, blo, m, d);
                 const int slot0 = blo - sg.lo, W = 1 << sg.wlog;
                 const int32_t tk = m <= CHAIN_MAX_M / 2
-                                       ? common_token<CHAIN_MAX_M / 2>(sg, slot0, m, d, W)
-                                       : common_token<CHAIN_MAX_M>(sg, slot0, m, d, W);
+                                       ? common_token<CHAIN_MAX_M / 2>(sg, slot0, m, d, W, mycb)
+                                       : common_token<CHAIN_MAX_M>(sg, slot0, m, d, W, mycb);
                 int lim = K - n < p.D - d ? K - n : p.D - d;
                 uint64_t ok = __ballot(tk >= 0 && lane < lim);
                 int L = ~ok ? __ffsll((unsigned long long)~ok) - 1 : 64;
