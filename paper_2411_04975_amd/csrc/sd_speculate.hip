@@ -198,6 +198,9 @@ template <int CTRL>
 __device__ __forceinline__ int32_t dpp_move(int32_t v) {
     return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
 }
+#ifndef SD_GLIST
+#define SD_GLIST 1  // 0: every pattern length is searched for on its own in the global index
+#endif
 #ifndef SD_PICK_SCAN_MAX
 #define SD_PICK_SCAN_MAX 3
 #endif
@@ -262,6 +265,11 @@ struct WgShared {
     int newtok[260]; // fused form: the tokens appended in this launch
     int cnt[72];     // [l]: occurrences whose left-extension is l; afterwards: is at least l
     int g_lo[65], g_hi[65];  // [p]: suffix-array range of the pattern of length p (global index)
+    // global index, list form (g_mode 1): the g_n2 <= 64 suffixes that start with the context's
+    // last two tokens, in suffix-array order: where each starts and how many tokens of the
+    // context's tail it matches to the left (2 .. P); gcnt[l]: how many match exactly l
+    int gl_pos[64], gl_L[64], gcnt[72];
+    int g_mode, g_n2;
     double best_s[16];
     int best_o[16];
 };
@@ -287,7 +295,7 @@ __device__ __forceinline__ void occ_scan_issue(int t_old, const int32_t *__restr
                                                ScanState &st, unsigned &nb) {
     const int tid = threadIdx.x, nthr = blockDim.x;
     if (tid == 0) { sh.m = 0; sh.next = 0; }
-    if (tid < 72) sh.cnt[tid] = 0;
+    if (tid < 72) { sh.cnt[tid] = 0; sh.gcnt[tid] = 0; }
     // Coalesced scan, 16 bytes per load, four loads in flight per thread; rows start 256-byte
     // aligned.
     const int4 *x4 = reinterpret_cast<const int4 *>(x);
@@ -1541,6 +1549,10 @@ __device__ __forceinline__ void match_rest(const SpecParams &p, int32_t wk, int 
 }
 
 template <bool STATS>
+__device__ __forceinline__ void col_stage(const SpecParams &p, int32_t w1, int32_t &lo, int32_t &hi,
+                                          unsigned &nb);
+
+template <bool STATS>
 __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, int pl, int32_t &lo, int32_t &hi,
                              unsigned &nb) {
     const int lane = threadIdx.x & 63;
@@ -1551,6 +1563,16 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
     hi = __builtin_amdgcn_readlane(bv, 1);
     if (pl == 1 || lo >= hi) return;
     const int32_t w1 = __builtin_amdgcn_readlane(wk, 1);
+    col_stage<STATS>(p, w1, lo, hi, nb);
+    match_rest<STATS>(p, wk, pl, lo, hi, nb);
+}
+
+// Second stage for one pattern: narrows the first token's bucket [lo, hi) to the suffixes whose
+// second token is w1, by the route that fits the bucket's size.
+template <bool STATS>
+__device__ __forceinline__ void col_stage(const SpecParams &p, int32_t w1, int32_t &lo, int32_t &hi,
+                                          unsigned &nb) {
+    const int lane = threadIdx.x & 63;
     const int32_t *col = p.g_tok1;
     int32_t l = lo, h = hi;
     if (h - l > SCAN_MAX && h - l <= SAMPLED_MAX) {
@@ -1578,7 +1600,6 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
     }
     lo = l;
     hi = h;
-    match_rest<STATS>(p, wk, pl, lo, hi, nb);
 }
 
 // Two patterns of one context at once (pattern lengths plA, plB <= 32; lane k of wkA / wkB holds
@@ -1694,7 +1715,28 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
     const int32_t *sa = nullptr, *text = nullptr;
     int32_t lo = 0, hi = 0;
     if (pl <= t && K >= 1) {
-        if (src == 0) {  // matched by the whole workgroup beforehand
+        if (src == 0 && SD_GLIST && pl >= 2 && uni(sh.g_mode) != 0) {
+            // list form: the listed suffixes that match at least pl tokens, in their order
+            // (the suffix array's, i.e. sorted by what follows the pattern), staged whole
+            const int n2 = uni(sh.g_n2);
+            const bool keep = lane < n2 && sh.gl_L[lane] >= pl;
+            const uint64_t mk = __ballot(keep);
+            const int m = __popcll(mk);
+            if (keep) {
+                const int dst = __popcll(mk & lanemask_lt());
+                sg.pos[dst] = sh.gl_pos[lane] - (pl - 2);
+                sg.cb[dst] = CB_NONE;
+            }
+            sg.lo = 0;
+            sg.m = m;
+            stage_set_width(sg, m > 0 ? m : 1);
+            __threadfence_block();
+            wsync();
+            sa = p.g_sa;  // never read: the whole list is staged
+            text = p.g_text;
+            lo = 0;
+            hi = m;
+        } else if (src == 0) {  // matched by the whole workgroup beforehand
             sa = p.g_sa;
             text = p.g_text;
             lo = uni(sh.g_lo[pl]);
@@ -2028,10 +2070,12 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
     int t = t_old;
     // lane k: pattern token k of the wave's first two pattern lengths
     int32_t wkA0 = 0, wkB0 = 0;
+    int32_t tail = 0;  // lane k < P: the k-th token from the context's end
     auto pattern_tokens = [&]() {
         const int plA = 1 + wave, plB = plA + nw;
         if (plA <= P && plA <= t && p.g_N > 0 && lane < plA) wkA0 = x[t - plA + lane];
         if (plB <= P && plB <= t && p.g_N > 0 && lane < plB) wkB0 = x[t - plB + lane];
+        if (SD_GLIST && p.g_N > 0 && lane < P && lane < t) tail = x[t - 1 - lane];
     };
     if (ACCEPT) {
         if (wave == 0) {
@@ -2053,6 +2097,70 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
         __syncthreads();  // the counters of the occurrence list are set
     }
     request_occurrences<STATS>(p, b, t, t_old, sh.newtok, x, s_sort, sh, scan, nb, [&]() {
+        // List form: the suffixes that start with the context's last two tokens are located
+        // once (every wave does that for itself: same loads, no barrier).  If there are at
+        // most 64 of them, every longer pattern's occurrences are among them: the waves share
+        // them out and count how far each agrees with the context's tail to the left, which
+        // settles all pattern lengths in two more rounds of loads (suffix array, text), and
+        // the expansions get their suffix lists from LDS.  Otherwise every pattern length is
+        // searched for on its own, as below.
+        if (SD_GLIST && P >= 2 && t >= 2 && p.g_N > 0) {
+            const int32_t w_last = __builtin_amdgcn_readlane(tail, 0), w_prev = __builtin_amdgcn_readlane(tail, 1);
+            const int32_t bv = lane < 4 ? p.g_bucket[(lane < 2 ? w_prev : w_last) + 1 + (lane & 1)] : 0;
+            if (lane < 4) SD_CNT(4);
+            int32_t lo2 = __builtin_amdgcn_readlane(bv, 0), hi2 = __builtin_amdgcn_readlane(bv, 1);
+            const int32_t lo1 = __builtin_amdgcn_readlane(bv, 2), hi1 = __builtin_amdgcn_readlane(bv, 3);
+            // (a first token with a bucket beyond the sampled lookup's reach would cost a long
+            // search here and most likely leave more than 64 suffixes: not tried)
+            const bool reach = hi2 - lo2 <= SAMPLED_MAX;
+            if (reach && lo2 < hi2) col_stage<STATS>(p, w_last, lo2, hi2, nb);
+            const int n2 = hi2 > lo2 ? hi2 - lo2 : 0;
+            if (reach && n2 <= 64) {
+                int pplog = 0;
+                while ((1 << pplog) < P) pplog++;
+                const int PP = 1 << pplog, G = 64 >> pplog, g = lane >> pplog, k = lane & (PP - 1);
+                const uint64_t gmask = PP >= 64 ? ~0ull : ((1ull << PP) - 1ull);
+                const int32_t tl = __shfl(tail, k);
+                constexpr int U = 4;
+                for (int i0 = wave * G * U; i0 < n2; i0 += nw * G * U) {
+                    int32_t ee[U], v[U];
+#pragma unroll
+                    for (int u = 0; u < U; u++) {  // where the suffix's second token sits
+                        const int i = i0 + u * G + g;
+                        ee[u] = i < n2 ? p.g_sa[lo2 + i] + 1 : -1;
+                        if (i < n2 && k == 0) SD_CNT(4);
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; u++) {
+                        int lim = ee[u] + 1 < P ? ee[u] + 1 : P;  // (0 for an empty place)
+                        lim = lim < t ? lim : t;
+                        const bool rd = ee[u] >= 0 && k < lim;
+                        v[u] = rd ? p.g_text[ee[u] - k] : tl;
+                        if (rd) SD_CNT(4);
+                    }
+#pragma unroll
+                    for (int u = 0; u < U; u++) {
+                        int lim = ee[u] + 1 < P ? ee[u] + 1 : P;
+                        lim = lim < t ? lim : t;
+                        const uint64_t mis = __ballot(k >= 1 && k < lim && v[u] != tl);
+                        const uint64_t gm = (mis >> (g << pplog)) & gmask;
+                        const int l = gm ? __ffsll((unsigned long long)gm) - 1 : lim;
+                        if (k == 0 && ee[u] >= 0) {
+                            const int i = i0 + u * G + g;
+                            sh.gl_pos[i] = ee[u] - 1;
+                            sh.gl_L[i] = l;
+                            atomicAdd(&sh.gcnt[l], 1);
+                        }
+                    }
+                }
+                if (threadIdx.x == 0) {
+                    sh.g_lo[1] = lo1; sh.g_hi[1] = hi1;
+                    sh.g_mode = 1; sh.g_n2 = n2;
+                }
+                return;
+            }
+        }
+        if (threadIdx.x == 0) sh.g_mode = 0;
         for (int plA = 1 + wave; plA <= P; plA += 2 * nw) {
             const int plB = plA + nw;  // a wave takes its pattern lengths two at a time
             const bool okA = plA <= t && p.g_N > 0, okB = plB <= P && plB <= t && p.g_N > 0;
@@ -2107,12 +2215,17 @@ __global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t 
     // Runs: entry i stands for pattern length P - i; lane i looks at entry i.
     int cg = 0, cr = 0, cgp = -1, crp = -1;
     bool alone = true;  // the next longer pattern may reach the depth bound
+    const bool listed = SD_GLIST && uni(sh.g_mode) != 0;
+    // list form: lane i (pattern length P - i) gets the number of listed suffixes that match
+    // at least that many tokens (a running sum over gcnt[P], gcnt[P - 1], ...)
+    const int32_t gsum = listed ? wave_inclusive_sum(lane < P ? sh.gcnt[P - lane] : 0) : 0;
+    const int32_t gsum_up = __shfl_up(gsum, 1);
     if (lane < P) {
         const int pl = P - lane;
-        cg = sh.g_hi[pl] - sh.g_lo[pl];
+        cg = listed && pl >= 2 ? gsum : sh.g_hi[pl] - sh.g_lo[pl];
         cr = sh.cnt[pl];
         if (lane > 0) {
-            cgp = sh.g_hi[pl + 1] - sh.g_lo[pl + 1];
+            cgp = listed ? gsum_up : sh.g_hi[pl + 1] - sh.g_lo[pl + 1];
             crp = sh.cnt[pl + 1];
             alone = pl + 1 + (int)floor(p.alpha * (double)(pl + 1)) >= p.D;
         }
