@@ -958,6 +958,52 @@ def test_first_token_buckets_around_the_scan_limits(n):
         g.close()
 
 
+@pytest.mark.parametrize("n,filler", [(1, 0), (2, 0), (63, 0), (64, 0), (65, 0), (130, 0), (40, 5000),
+                                      (64, 4000), (0, 0)])
+def test_two_token_anchor_around_the_list_limits(n, filler):
+    """All pattern lengths of the global index are settled from the suffixes that start with
+    the context's last two tokens when there are at most 64 of them (and their first token's
+    bucket is within the sampled lookup's reach), and searched for one by one otherwise.  Here
+    the pair (7, 8) occurs exactly n times, each time behind a piece of the context's tail of
+    another length (so every pattern length has its own count), at the very start of a document
+    and behind other documents' ends; `filler` further occurrences of 7 widen its bucket.  Both
+    routes must give the oracle's trees, for contexts of every length from 0 on."""
+    rng = np.random.default_rng(1000 * n + filler)
+    vocab, D, P, alpha, ms = 40, 14, 9, 2.0, 0.01
+    tailtok = rng.integers(10, 40, P - 2).astype(np.int32)          # the context's tail before (7, 8)
+    docs = []
+    for i in range(n):
+        keep = int(rng.integers(0, P - 1))                           # tokens of the tail in front
+        pre = rng.integers(10, 40, int(rng.integers(0, 6))).astype(np.int32) if i % 5 else np.zeros(0, np.int32)
+        cont = rng.integers(0, 4, int(rng.integers(0, 8))).astype(np.int32)   # few distinct tokens: ties
+        docs.append(np.concatenate([pre, tailtok[len(tailtok) - keep:], [7, 8], cont]).astype(np.int32))
+    if filler:
+        docs.append(np.tile(np.array([7, 9], np.int32), filler))
+    docs.append(rng.integers(0, 40, 50).astype(np.int32))
+    order = rng.permutation(len(docs))
+    docs = [docs[i] for i in order]
+    full = np.concatenate([rng.integers(10, 40, 5).astype(np.int32), tailtok, [7, 8]]).astype(np.int32)
+    ctxs = [full[len(full) - k:] for k in range(0, len(full) + 1)]    # lengths 0 .. all
+    ctxs += [np.concatenate([full, [7]]).astype(np.int32), np.concatenate([full[:-1], [9]]).astype(np.int32)]
+    B = len(ctxs)
+    N = sum(len(d) for d in docs) + len(docs)
+    g = parity.GpuPath(vocab, D, P, alpha, ms, B, 64, N + 4)
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), ctxs)
+        got = g.speculate(range(B))
+        tg = oracle.Trie(D)
+        for d in docs:
+            tg.add_doc(d)
+        want = parity.oracle_speculate_batch(tg, ctxs, D, P, alpha, ms, g.max_nodes)
+        bad = parity.compare_trees(got, want, "pair occurs %d times, filler %d" % (n, filler))
+        assert not bad, "\n".join(bad)
+        if n:
+            assert int(want["match_len"].max()) >= 2
+    finally:
+        g.close()
+
+
 def test_wide_batches_on_thinner_workgroups():
     """Batches of several workgroups per compute unit run on workgroups of fewer waves (the
     library sizes them by the batch): 775 and 3329 requests must give the trees of the oracle
