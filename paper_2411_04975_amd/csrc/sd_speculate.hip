@@ -12,8 +12,11 @@
 //      each extends to the left (up to P) and sort the occurrences by what follows them; the
 //      occurrences with left-extension >= p, in that order, are the sorted suffix list of the
 //      per-request structure below the pattern of length p.  Meanwhile the waves match the P
-//      patterns against the global index (first token -> bucket, second token -> column,
-//      then the text).
+//      patterns against the global index: the suffixes that start with the context's last two
+//      tokens are located (first token -> bucket, second token -> column) and, if they are
+//      few, extended to the left in the same way, which settles every pattern length at once
+//      and leaves their sorted suffix lists in LDS; otherwise every pattern length is
+//      searched for on its own (bucket, column, then the text).
 //   2. pattern lengths with equal occurrence counts share one expansion; the waves take such
 //      runs from a queue in LDS and grow the trees greedily, one wavefront per tree (frontier
 //      and tree in LDS, arg-max by wave-wide maxima, shortcuts for unary runs and for tied
@@ -1356,11 +1359,12 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
     return true;
 }
 
-// MatchPattern on the global index.  The pattern's first token selects a bucket of the suffix
-// array; the second token is located in the bucket's second-token column (sorted, read with
-// coalesced loads: buckets up to SCAN_MAX entries are simply scanned); the few suffixes left
-// are compared with the whole pattern lane-parallel.  The dependent chain is
-// bucket -> column -> suffix array -> text, whatever p is.
+// MatchPattern on the global index, one pattern length at a time (the route taken when the
+// context's last two tokens start too many suffixes for the list form).  The pattern's first
+// token selects a bucket of the suffix array; the second token is located in the bucket's
+// second-token column (sorted, read with coalesced loads: buckets up to SCAN_MAX entries are
+// simply scanned); the few suffixes left are compared with the whole pattern lane-parallel.
+// The dependent chain is bucket -> column -> suffix array -> text, whatever p is.
 constexpr int SCAN_MAX = 256;
 #ifndef SD_COL_FAN
 #define SD_COL_FAN 8
