@@ -2044,7 +2044,9 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nod
 // the bonus token to the request's context, and then drafts the next tree from the extended
 // context into `out`: the end of one decoding step and the start of the next in one launch.
 template <bool STATS, bool TICKS, bool ACCEPT>
-__global__ __launch_bounds__(1024) void k_speculate(SpecParams p, const int32_t *__restrict__ slot_ids,
+// (At least six waves per SIMD: two workgroups of twelve waves are resident together when two
+// requests share a compute unit; that is a bound on the kernel's registers.)
+__global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void k_speculate(SpecParams p, const int32_t *__restrict__ slot_ids,
                                                     sd_trees out, int lds_per_wave, AcceptArgs aa,
                                                     AppendArgs ap) {
     extern __shared__ double smem[];
