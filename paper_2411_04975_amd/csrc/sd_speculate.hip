@@ -201,6 +201,9 @@ template <int CTRL>
 __device__ __forceinline__ int32_t dpp_move(int32_t v) {
     return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
 }
+#ifndef SD_SKIP_HOPELESS
+#define SD_SKIP_HOPELESS 1  // 0: every run is expanded
+#endif
 #ifndef SD_GLIST
 #define SD_GLIST 1  // 0: every pattern length is searched for on its own in the global index
 #endif
@@ -264,6 +267,7 @@ __device__ __forceinline__ int32_t wave_inclusive_sum(int32_t v) {
 struct WgShared {
     int m;           // occurrences of the context's last token
     int next;        // head of the unit queue
+    unsigned long long top_bits;  // highest SCORE of a finished tree so far (bits of the double)
     int t_new;       // context length after the append of the fused form
     int newtok[260]; // fused form: the tokens appended in this launch
     int cnt[72];     // [l]: occurrences whose left-extension is l; afterwards: is at least l
@@ -297,7 +301,7 @@ template <bool STATS>
 __device__ __forceinline__ void occ_scan_issue(int t_old, const int32_t *__restrict__ x, WgShared &sh,
                                                ScanState &st, unsigned &nb) {
     const int tid = threadIdx.x, nthr = blockDim.x;
-    if (tid == 0) { sh.m = 0; sh.next = 0; }
+    if (tid == 0) { sh.m = 0; sh.next = 0; sh.top_bits = 0; }
     if (tid < 72) { sh.cnt[tid] = 0; sh.gcnt[tid] = 0; }
     // Coalesced scan, 16 bytes per load, four loads in flight per thread; rows start 256-byte
     // aligned.
@@ -2256,6 +2260,14 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         m &= m - 1;
         const int i1 = m ? __ffsll((unsigned long long)m) - 1 : P;
         const int p_lo = P - i1 + 1;
+        // No node scores above 1, so a tree of K(p) nodes cannot reach a SCORE above K(p): a run
+        // whose longest pattern has fewer nodes to give than the best finished tree already
+        // scores can neither win nor tie, whatever the order, and is left out.  (Which runs
+        // that hits depends on timing; the result does not.)
+        if (SD_SKIP_HOPELESS) {
+            const double top = uni(__longlong_as_double((long long)sh.top_bits));
+            if (floor(p.alpha * (double)(P - i0)) < top) continue;
+        }
         for (int pl = P - i0; pl >= p_lo; pl--) {
             double total = 0.0;
             bool deepest = false;
@@ -2270,6 +2282,9 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
                 best_s = total; best_o = order; best_n = n;
                 cur ^= 1;  // the tree just grown is kept; the next one grows into the other buffer
             }
+            // (positive doubles order like their bit patterns)
+            if (SD_SKIP_HOPELESS && n > 0 && total > 0.0 && lane == 0)
+                atomicMax(&sh.top_bits, (unsigned long long)__double_as_longlong(total));
             if (!deepest) break;
         }
     }
