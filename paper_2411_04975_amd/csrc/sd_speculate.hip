@@ -1802,6 +1802,22 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
             const Taken tk0 = frontier_take(f);
             const Key best = tk0.k;
             if (best.s < p.min_score) break;
+            // Nodes are taken in non-increasing score order, so the K - n nodes still to come
+            // add at most that many times the best score left: a tree that cannot reach the
+            // best finished SCORE any more is given up (it could neither win nor tie; nor could
+            // the shorter patterns of its run, whose trees are its first nodes).  The SCORE is a
+            // sum of rounded additions, which may come out a few units in the last place above
+            // this product form (and two trees of equal nodes must tie exactly): hence the
+            // margin.  Checked once per step here; checks inside the merges of tied chains
+            // cost more than they saved.
+            if (SD_SKIP_HOPELESS) {
+                const double top = uni(__longlong_as_double((long long)sh.top_bits));
+                if ((total + (double)(K - n) * best.s) * (1.0 + 1e-9) < top) {
+                    n = 0;
+                    total = 0.0;
+                    break;
+                }
+            }
             const int ntop = tk0.ntop;
             if (ntop >= 2 && !p.linear &&
                 tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok, t_par, t_score,
