@@ -596,6 +596,13 @@ def main():
         assert st3["err_bad_token"] == 0 and st3["err_bad_slot"] == 0, st3
         sd.sd_destroy(ctx3)
         out["speculate_throughput_by_batch"] = by_batch
+        # the same kernel with the compute units full: its share of the roofline there
+        top_b = str(wide[-1])
+        out["roofline"]["sd_speculate_at_batch_%s" % top_b] = {
+            "achieved": by_batch[top_b]["achieved_gbs"], "frac": by_batch[top_b]["frac_of_peak"],
+            "frac_of_achievable": by_batch[top_b]["frac_of_achievable"],
+            "avg_launch_ms": by_batch[top_b]["us_per_launch"] * 1e-3,
+            "algo_bytes_per_launch": by_batch[top_b]["algo_bytes_per_launch"]}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, n_requests=min(32, B), build_tokens=300_000)
     print(json.dumps(out))
