@@ -68,6 +68,24 @@ def _run_full(name, sample, seed=0):
             L, path, bonus = oracle.accept(want["tokens"][i, :k], want["parents"][i, :k], tgt[b])
             assert al[b] == L and bo[b] == bonus and list(ap[b, :L]) == list(path)
         assert np.all(al <= got["n_nodes"])
+        # the decode step as bench.py runs it: the same acceptance, the append and the next
+        # drafts in one launch over the whole batch; sampled requests against the oracle on
+        # their extended contexts
+        al2, ap2, bo2, nxt = g.accept_append_speculate(range(B), tgt)
+        assert np.array_equal(al2, al) and np.array_equal(bo2, bo) and np.array_equal(ap2, ap)
+        _check_properties(nxt, w)
+        ext = []
+        for i, b in enumerate(pick):
+            k = int(want["n_nodes"][i])
+            L, path, bonus = oracle.accept(want["tokens"][i, :k], want["parents"][i, :k], tgt[b])
+            new = np.array([int(want["tokens"][i, j]) for j in path] + [int(bonus)], np.int32)
+            ext.append(np.concatenate([contexts[b], new]))
+        tg2 = parity.oracle_global_trie(docs, w.D, w.vocab, ext, w.P)
+        want2 = parity.oracle_speculate_batch(tg2, ext, w.D, w.P, w.alpha, w.min_score, w.max_nodes)
+        bad = parity.compare_trees({k: v[pick] for k, v in nxt.items()}, want2, name + " next drafts")
+        assert not bad, "\n".join(bad)
+        st = g.stats()
+        assert st["err_bad_token"] == 0 and st["err_bad_slot"] == 0 and st["err_ctx_overflow"] == 0
         return got, want
     finally:
         g.close()
