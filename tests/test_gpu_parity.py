@@ -744,7 +744,7 @@ ENTROPY_RTOL = 1e-9
 
 
 @pytest.mark.parametrize("case", ["tiny", "tiny-D3", "binary", "all-equal", "distinct", "zipf",
-                                  "empty-docs"])
+                                  "empty-docs", "many-stops", "deep-D", "wide-runs"])
 def test_entropy_matches_oracle(case, tiny_workload):
     rng = np.random.default_rng(31)
     if case == "tiny":
@@ -760,6 +760,27 @@ def test_entropy_matches_oracle(case, tiny_workload):
     elif case == "zipf":
         w = make_workload(scaled("lowrep", n_docs=40, doc_len=(500, 500), batch=2, ctx=64), seed=3)
         D, vocab, docs = w.D, w.vocab, w.docs()
+    elif case == "many-stops":
+        # hundreds of documents end in the same tokens (many suffixes stop at one depth of one
+        # run), others run on past them
+        D, vocab = 8, 50
+        docs = [np.array([int(rng.integers(10, 50)), 5, 6], np.int32) for _ in range(300)]
+        docs += [np.array([7, 5, 6, 7, 8, 5, 6], np.int32) for _ in range(37)]
+        docs += [np.array([5], np.int32)] * 70 + [rng.integers(0, 50, 400).astype(np.int32)]
+    elif case == "deep-D":
+        # the largest depth bound: lengths and shared prefixes up to 255, documents shorter and
+        # longer than D, repeated so that runs reach the bound
+        D, vocab = 255, 9
+        a, b = rng.integers(0, 9, 700).astype(np.int32), rng.integers(0, 9, 300).astype(np.int32)
+        docs = [a, b, a[100:], np.concatenate([b, a[:280]]), a[:255], a[:254], b[40:296]]
+    elif case == "wide-runs":
+        # runs of thousands of suffixes at depths 2, 3 and beyond (one phrase in every document),
+        # with tails that differ
+        D, vocab = 16, 400
+        phrase = np.array([1, 2, 3, 4, 5, 6, 7], np.int32)
+        docs = [np.concatenate([rng.integers(8, 400, int(rng.integers(0, 4))).astype(np.int32), phrase,
+                                rng.integers(8, 400, int(rng.integers(0, 6))).astype(np.int32)])
+                for _ in range(3000)]
     else:
         D, vocab, docs = 5, 7, [np.zeros(0, np.int32), np.array([3], np.int32), np.zeros(0, np.int32),
                                 np.array([3, 3, 4], np.int32)]
