@@ -118,8 +118,41 @@ def test_large_insert_then_speculate_sampled():
         want = parity.oracle_speculate_batch(tg, sub, w.D, w.P, w.alpha, w.min_score, w.max_nodes)
         bad = parity.compare_trees({k: v[pick] for k, v in got.items()}, want, "large+insert")
         assert not bad, "\n".join(bad)
+        # the entropy of the index at full size: its weight has a closed form (every position
+        # weighs min(D, tokens left in its document)), and the index after the insertions must
+        # give what a build over all documents gives
+        h, wt = g.entropy()
+        lens = np.array([len(d) for d in docs], np.int64)
+        full = np.minimum(lens, w.D)                       # positions with fewer than D tokens left
+        closed = int(np.sum(full * (full + 1) // 2 + (lens - full) * w.D))
+        assert wt == float(closed)
+        assert 0.0 < h < math.log2(w.vocab)
+        g.build_global(docs)
+        h2, wt2 = g.entropy()
+        assert wt2 == wt and h2 == pytest.approx(h, rel=1e-9)
     finally:
         g.close()
+
+
+def test_entropy_templated_mid_size_against_oracle():
+    """The headline recipe at 200k tokens and the full depth bound (D = 64): long unary chains,
+    runs of many suffixes at every depth, documents that end inside templates.  Tolerance as in
+    the small entropy cases: summation order and log2 routines differ."""
+    from workloads.synth import scaled
+    w = make_workload(scaled("large", total=200_000, n_templates=60, batch=2, ctx=64), seed=5)
+    docs = w.docs()
+    g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, 1, 16, len(w.corpus) + len(docs) + 8)
+    try:
+        g.build_global(docs)
+        h, wt = g.entropy()
+    finally:
+        g.close()
+    t = oracle.Trie(w.D)
+    for d in docs:
+        t.add_doc(d)
+    ho, wo = t.entropy()
+    assert wt == wo
+    assert h == pytest.approx(ho, rel=1e-9)
 
 
 def test_agentic_full():
