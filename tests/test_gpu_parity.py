@@ -42,8 +42,9 @@ def _run_workload(w, check_accept=True, slots=None):
         g.close()
 
 
-def test_global_index_is_a_sorted_suffix_array(tiny_workload):
-    w = tiny_workload
+@pytest.mark.parametrize("size", ["5-sort-tiles", "11-sort-tiles"])
+def test_global_index_is_a_sorted_suffix_array(size, tiny_workload):
+    w = tiny_workload if size == "5-sort-tiles" else make_workload(scaled("tiny", n_docs=90), seed=2)
     import paper_2411_04975_amd as sd
     docs = w.docs()
     g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, 4, 64, len(w.corpus) + len(docs))
