@@ -129,7 +129,7 @@ def test_large_insert_then_speculate_sampled():
         assert 0.0 < h < math.log2(w.vocab)
         g.build_global(docs)
         h2, wt2 = g.entropy()
-        assert wt2 == wt and h2 == pytest.approx(h, rel=1e-9)
+        assert wt2 == wt and h2 == pytest.approx(h, rel=1e-9, abs=1e-12)
     finally:
         g.close()
 
@@ -152,7 +152,7 @@ def test_entropy_templated_mid_size_against_oracle():
         t.add_doc(d)
     ho, wo = t.entropy()
     assert wt == wo
-    assert h == pytest.approx(ho, rel=1e-9)
+    assert h == pytest.approx(ho, rel=1e-9, abs=1e-12)
 
 
 def test_agentic_full():

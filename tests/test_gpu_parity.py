@@ -742,6 +742,9 @@ def test_insert_into_empty_index_and_capacity():
 # Tolerance: both sides add up to ~1e7 terms of size <= 2^40 in different orders and with
 # different log2 routines; 1e-9 relative is far above that noise and far below any real error.
 ENTROPY_RTOL = 1e-9
+# The mean is a difference of two such sums divided by the weight: where it cancels to (nearly)
+# nothing, what is left is rounding noise of the sums, a few ulps of log2(N) <= 40 bits.
+ENTROPY_ATOL = 1e-12
 
 
 @pytest.mark.parametrize("case", ["tiny", "tiny-D3", "binary", "all-equal", "distinct", "zipf",
@@ -800,8 +803,46 @@ def test_entropy_matches_oracle(case, tiny_workload):
         t.add_doc(d)
     ho, wo = t.entropy()
     assert wt == wo and wt2 == wo
-    assert h == pytest.approx(ho, rel=ENTROPY_RTOL, abs=1e-15)
-    assert h2 == pytest.approx(ho, rel=ENTROPY_RTOL, abs=1e-15)
+    assert h == pytest.approx(ho, rel=ENTROPY_RTOL, abs=ENTROPY_ATOL)
+    assert h2 == pytest.approx(ho, rel=ENTROPY_RTOL, abs=ENTROPY_ATOL)
+
+
+def test_entropy_fuzz_small_corpora():
+    """Seeded corpora of four shapes (random tokens; slices of one text: deep shared prefixes
+    and many suffixes that stop together; runs of one token; common endings) over the range of
+    vocabularies and depth bounds, capacity with and without slack."""
+    for seed in range(120):
+        rng = np.random.default_rng(1000 + seed)
+        vocab = int(rng.choice([2, 3, 5, 17, 300]))
+        D = int(rng.choice([2, 3, 5, 9, 16, 33, 64, 130, 255]))
+        kind = int(rng.integers(0, 4))
+        base = rng.integers(0, vocab, int(rng.integers(1, 600))).astype(np.int32)
+        docs = []
+        for _ in range(int(rng.integers(1, 40))):
+            if kind == 0:
+                d = rng.integers(0, vocab, int(rng.integers(0, 300))).astype(np.int32)
+            elif kind == 1:
+                a = int(rng.integers(0, len(base)))
+                d = base[a:int(rng.integers(a, len(base) + 1))].copy()
+            elif kind == 2:
+                d = np.full(int(rng.integers(0, 400)), int(rng.integers(0, vocab)), np.int32)
+            else:
+                tail = base[-int(rng.integers(1, min(len(base), 12) + 1)):]
+                d = np.concatenate([rng.integers(0, vocab, int(rng.integers(0, 20))).astype(np.int32), tail])
+            docs.append(d)
+        N = sum(len(d) for d in docs) + len(docs)
+        g = parity.GpuPath(vocab, D, min(4, D - 1), 1.0, 0.1, 1, 16, N + int(rng.integers(0, 9)))
+        try:
+            g.build_global(docs)
+            h, wt = g.entropy()
+        finally:
+            g.close()
+        t = oracle.Trie(D)
+        for d in docs:
+            t.add_doc(d)
+        ho, wo = t.entropy()
+        assert wt == wo, (seed, wt, wo)
+        assert h == pytest.approx(ho, rel=ENTROPY_RTOL, abs=ENTROPY_ATOL), (seed, vocab, D, kind)
 
 
 def test_profiling_variants_give_the_same_trees(tiny_workload):
