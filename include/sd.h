@@ -20,9 +20,12 @@
  *    sd_get_stats synchronise.
  *  - Errors the host can see (bad arguments, sizes beyond the configured
  *    capacity) return a code at once and enqueue nothing.  Conditions only the
- *    device can see (a token outside [0, vocab), a slot id out of range, a
- *    context that would outgrow max_ctx_tokens) raise a sticky device flag; the
- *    offending sequence is skipped, and the flag is reported by sd_get_stats.
+ *    device can see raise a sticky device flag that sd_get_stats reports: a
+ *    token outside [0, vocab) is indexed as token 0 (the sequence is kept, so
+ *    counts of paths through token 0 then include an occurrence that never
+ *    existed: a caller that cannot rule such tokens out checks the flag); a
+ *    sequence with a slot id out of range is skipped; a context, or an
+ *    append to one, that would exceed max_ctx_tokens is skipped whole.
  *  - One sd_ctx belongs to one device; calls on one sd_ctx must not overlap.
  *  - Tokens are int32 in [0, vocab).  Sequence i of a (tokens, offsets) pair
  *    is tokens[offsets[i] .. offsets[i+1]).
@@ -122,6 +125,23 @@ typedef struct {
     int32_t reserved;
     int64_t index_bytes;       /* device bytes held by the global index         */
     int64_t scratch_bytes;     /* device bytes of scratch held by the context   */
+    /* Counters of the drafting and acceptance calls, added up on the device by the kernels
+     * themselves since sd_create (means are quotients of two of them; a caller that wants
+     * them per call takes differences). */
+    int64_t spec_requests;     /* requests drafted for (sd_speculate and the fused form)      */
+    int64_t spec_trees;        /* of those: requests that got a tree of at least one node      */
+    int64_t spec_nodes;        /* draft nodes of those trees                                   */
+    int64_t spec_match_len;    /* winning pattern lengths p of those trees, added up           */
+    int64_t spec_from_request; /* trees that came from the per-request index                   */
+    int64_t spec_global_list;  /* requests whose global matches were settled for all pattern
+                                  lengths at once from the suffixes of the last two tokens     */
+    int64_t spec_global_search;/* requests whose pattern lengths were searched one by one      */
+    int64_t spec_request_wide; /* requests with a per-request suffix list of more than 64
+                                  occurrences (written to scratch memory)                      */
+    int64_t spec_occ_in_memory;/* requests whose occurrence list was too long to sort in LDS   */
+    int64_t spec_list_rounds;  /* extra rounds taken because such lists did not fit together   */
+    int64_t accept_requests;   /* requests verified (sd_accept and the fused forms)            */
+    int64_t accept_len;        /* accepted draft nodes, added up                               */
 } sd_stats;
 
 /* Validate the configuration, select `device`, allocate index capacity and
@@ -130,6 +150,10 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out);
 void sd_destroy(sd_ctx *ctx);
 /* Text of the last host-side error of this context (owned by the context). */
 const char *sd_last_error(const sd_ctx *ctx);
+/* floor(alpha * P): the largest tree sd_speculate can emit (MAX_SPEC at p = P, Section 3,
+ * "Adaptive Speculation Lengths"), i.e. the smallest sd_trees.max_nodes it accepts.  0 for a
+ * null context. */
+int32_t sd_max_nodes(const sd_ctx *ctx);
 
 /* Build an index (Section 3, "Suffix Tree Construction").
  * SD_SCOPE_GLOBAL: the n_seq sequences are the documents of the corpus of

@@ -8,7 +8,6 @@ HIP stream, and never computes anything itself.
 from __future__ import annotations
 
 import ctypes as C
-import math
 import os
 from typing import Optional
 
@@ -49,7 +48,12 @@ class _Stats(C.Structure):
     _fields_ = [("global_tokens", C.c_int64), ("global_docs", C.c_int64),
                 ("err_bad_token", C.c_int32), ("err_bad_slot", C.c_int32),
                 ("err_ctx_overflow", C.c_int32), ("reserved", C.c_int32),
-                ("index_bytes", C.c_int64), ("scratch_bytes", C.c_int64)]
+                ("index_bytes", C.c_int64), ("scratch_bytes", C.c_int64)] + [
+        (k, C.c_int64) for k in (
+            "spec_requests", "spec_trees", "spec_nodes", "spec_match_len", "spec_from_request",
+            "spec_global_list", "spec_global_search", "spec_request_wide", "spec_occ_in_memory",
+            "spec_list_rounds", "accept_requests", "accept_len")]
+
 
 
 KERNEL_NAMES = ["speculate", "accept", "append", "req_build", "sort_hist", "sort_scan",
@@ -83,6 +87,8 @@ def _load():
     L.sd_destroy.argtypes = [vp]
     L.sd_last_error.restype = C.c_char_p
     L.sd_last_error.argtypes = [vp]
+    L.sd_max_nodes.restype = C.c_int32
+    L.sd_max_nodes.argtypes = [vp]
     L.sd_index_build.restype = C.c_int
     L.sd_index_build.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int32, C.c_int64, vp]
     L.sd_index_entropy.restype = C.c_int
@@ -121,7 +127,7 @@ class _Ctx:
     def __init__(self, handle, cfg: _Config):
         self.handle = handle
         self.cfg = cfg
-        self.max_nodes = int(math.floor(cfg.alpha * cfg.P))
+        self.max_nodes = int(_load().sd_max_nodes(handle))
         self.device = torch.device("cuda", cfg.device)
 
 

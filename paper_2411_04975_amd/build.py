@@ -24,8 +24,7 @@ def build(verbose: bool = False) -> str:
     """Always recompiles; returns the path of the shared object."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB_PATH + ".tmp.%d" % os.getpid()
-    extra = os.environ.get("SD_EXTRA_HIPCC_FLAGS", "").split()   # tuning experiments only
-    cmd = [hipcc] + HIPCC_FLAGS + extra + ["-o", tmp] + sources()
+    cmd = [hipcc] + HIPCC_FLAGS + ["-o", tmp] + sources()
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)

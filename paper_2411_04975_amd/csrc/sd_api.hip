@@ -33,7 +33,7 @@ void free_all(sd_ctx *c) {
     void *ptrs[] = {c->g_text, c->g_sa, c->g_bucket, c->g_tok1, c->g_tok1s, c->b_keys[0], c->b_keys[1], c->b_vals[0],
                     c->b_vals[1], c->b_rank, c->b_flags, c->b_gid2, c->b_hist, c->b_partials, c->r_text,
                     c->r_len, c->s_occ, c->s_unit_sa, c->d_err, c->s_unit_ticks, c->d_entropy,
-                    c->d_round_flag};
+                    c->d_round_flag, c->d_counters};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (c->d_algo_bytes) (void)hipFree(c->d_algo_bytes);
@@ -100,11 +100,12 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     ok = ok && dev_alloc(&c->b_partials, c->b_partials_cap, sb);
     ok = ok && dev_alloc(&c->r_text, B * c->r_stride, sb) && dev_alloc(&c->r_len, B, sb);
     ok = ok && dev_alloc(&c->s_occ, B * ctx, sb);
-    ok = ok && dev_alloc(&c->s_unit_sa, B * P * ctx, sb);
+    ok = ok && dev_alloc(&c->s_unit_sa, B * ctx, sb);
     ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb) && dev_alloc(&c->d_entropy, 4, sb) &&
          dev_alloc(&c->d_round_flag, 8, sb);
     ok = ok && dev_alloc(&c->s_unit_ticks, B * 2 * P * 4 + B * 16 * 8, sb);
     ok = ok && dev_alloc(&c->d_algo_bytes, SD_K_COUNT, sb);
+    ok = ok && dev_alloc(&c->d_counters, SD_CTR_N, sb);
     if (!ok) {
         free_all(c);
         delete c;
@@ -122,6 +123,7 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     sd_fill_i32(c->r_len, B, 0, nullptr);
     sd_fill_i32(c->d_err, SD_DEVERR_N, 0, nullptr);
     sd_fill_i32((int32_t *)c->d_algo_bytes, 2 * SD_K_COUNT, 0, nullptr);
+    sd_fill_i32((int32_t *)c->d_counters, 2 * SD_CTR_N, 0, nullptr);
     if (hipDeviceSynchronize() != hipSuccess) {
         free_all(c);
         delete c;
@@ -140,6 +142,8 @@ void sd_destroy(sd_ctx *c) {
 }
 
 const char *sd_last_error(const sd_ctx *c) { return c ? c->last_error.c_str() : "null context"; }
+
+int32_t sd_max_nodes(const sd_ctx *c) { return c ? c->max_nodes : 0; }
 
 sd_status sd_index_build(sd_ctx *c, sd_scope scope, const int32_t *d_slot_ids,
                          const int32_t *d_tokens, const int64_t *d_seq_offsets, int32_t n_seq,
@@ -282,6 +286,11 @@ sd_status sd_get_stats(sd_ctx *c, sd_stats *o) {
     o->reserved = 0;
     o->index_bytes = c->index_bytes;
     o->scratch_bytes = c->scratch_bytes;
+    unsigned long long ctr[SD_CTR_N];
+    if (hipMemcpy(ctr, c->d_counters, sizeof(ctr), hipMemcpyDeviceToHost) != hipSuccess)
+        return fail(c, SD_ERR_HIP, "hipMemcpy");
+    int64_t *dst = &o->spec_requests;  // the counter fields follow each other in this order
+    for (int i = 0; i < SD_CTR_N; i++) dst[i] = (int64_t)ctr[i];
     return SD_OK;
 }
 

@@ -13,6 +13,13 @@
 
 // sticky device-side error flags (indices into sd_ctx::d_err)
 enum { SD_DEVERR_TOKEN = 0, SD_DEVERR_SLOT = 1, SD_DEVERR_CTX = 2, SD_DEVERR_N = 4 };
+// device-side counters reported by sd_get_stats (indices into sd_ctx::d_counters, in the
+// order of the sd_stats fields from spec_requests on)
+enum {
+    SD_CTR_REQUESTS = 0, SD_CTR_TREES, SD_CTR_NODES, SD_CTR_MATCH_LEN, SD_CTR_FROM_REQUEST,
+    SD_CTR_GLOBAL_LIST, SD_CTR_GLOBAL_SEARCH, SD_CTR_REQUEST_WIDE, SD_CTR_OCC_IN_MEMORY,
+    SD_CTR_LIST_ROUNDS, SD_CTR_ACCEPT_REQUESTS, SD_CTR_ACCEPT_LEN, SD_CTR_N
+};
 
 struct sd_ctx {
     sd_config cfg;
@@ -51,10 +58,12 @@ struct sd_ctx {
 
     // ---- speculate scratch (sized for max_batch_slots requests) -------
     int2 *s_occ = nullptr;           // [B][max_ctx]: (end position e, common-suffix length L)
-    int32_t *s_unit_sa = nullptr;    // [B][P][max_ctx]: per-(request,p) suffix lists (wide matches)
+    int32_t *s_unit_sa = nullptr;    // [B][max_ctx]: per-request room for suffix lists of more
+                                     // than 64 occurrences (shared by the pattern lengths)
     uint32_t *s_unit_ticks = nullptr;  // [B][2P][4], written by the counting kernel variants
 
     int32_t *d_err = nullptr;        // [SD_DEVERR_N]
+    unsigned long long *d_counters = nullptr;  // [SD_CTR_N]
     double *d_entropy = nullptr;     // [3] accumulators of sd_index_entropy
     int32_t *d_round_flag = nullptr; // [8] per doubling round: groups too long for the in-tile sort
 

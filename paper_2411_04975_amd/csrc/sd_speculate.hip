@@ -43,6 +43,7 @@ struct SpecParams {
     int2 *occ;
     int32_t *unit_sa;
     int32_t *err;
+    unsigned long long *counters;  // what sd_get_stats reports (SD_CTR_*)
     unsigned long long *algo_bytes;
     uint32_t *unit_ticks;  // timing variant only: wall-clock marks of each expanded unit
     uint32_t *wg_ticks;    // timing variant only: [request][16 waves][8] phase marks
@@ -201,16 +202,7 @@ template <int CTRL>
 __device__ __forceinline__ int32_t dpp_move(int32_t v) {
     return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
 }
-#ifndef SD_SKIP_HOPELESS
-#define SD_SKIP_HOPELESS 1  // 0: every run is expanded
-#endif
-#ifndef SD_GLIST
-#define SD_GLIST 1  // 0: every pattern length is searched for on its own in the global index
-#endif
-#ifndef SD_PICK_SCAN_MAX
-#define SD_PICK_SCAN_MAX 3
-#endif
-constexpr int PICK_SCAN_MAX = SD_PICK_SCAN_MAX;
+constexpr int PICK_SCAN_MAX = 3;  // frontiers up to this size are scanned by every lane
 constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
 
 __device__ __forceinline__ uint32_t wave_max_u32(uint32_t v) {
@@ -689,16 +681,10 @@ __device__ __forceinline__ void frontier_put(Frontier &f, int hole, bool cand, d
 // Sibling branches of the speculation tree are disjoint suffix ranges and a suffix is only
 // ever asked for deeper tokens, so each slot's window moves forward only.  With W tokens per
 // slot one coalesced fill serves W levels of the tree: expansion then runs out of LDS.
-#ifndef SD_TC_TOKENS
-#define SD_TC_TOKENS 512
-#endif
-constexpr int TC_TOKENS = SD_TC_TOKENS;
+constexpr int TC_TOKENS = 512;
 constexpr int CB_NONE = -(1 << 30);
 constexpr int CHAIN_MAX_M = 8;  // widest node the unary-run shortcut looks at
-#ifndef SD_MED_MAX
-#define SD_MED_MAX 256
-#endif
-constexpr int MED_MAX = SD_MED_MAX;  // widest node whose suffixes are all read (a multiple of 64)
+constexpr int MED_MAX = 256;  // widest node whose suffixes are all read (a multiple of 64)
 
 struct Stage {
     int32_t *pos, *cb, *tc;  // LDS: [64], [64], [TC_TOKENS]
@@ -1068,12 +1054,9 @@ __device__ __forceinline__ void match_range(const int32_t *__restrict__ sa, cons
 // (one 64-token window per chain: its head plus 63 tokens), the caller comes back for more.
 // Per-chain state lives in the lanes of vector registers (lane q: chain q).
 constexpr int TIE_MAX = 64;
-#ifndef SD_KWAY_MIN
-#define SD_KWAY_MIN 4
-#endif
 // From this many chains on the merge goes step by step over all chains at once (below); fewer
 // chains are merged as whole sequences.  4 measured best on the synthetic workloads (2, 3, 6, 10 tried).
-constexpr int KWAY_MIN = SD_KWAY_MIN;
+constexpr int KWAY_MIN = 4;
 
 // total + s + s + ... (n times), added one by one in that order like the sequential sum of node
 // scores it stands for
@@ -1370,14 +1353,8 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
 // simply scanned); the few suffixes left are compared with the whole pattern lane-parallel.
 // The dependent chain is bucket -> column -> suffix array -> text, whatever p is.
 constexpr int SCAN_MAX = 256;
-#ifndef SD_COL_FAN
-#define SD_COL_FAN 8
-#endif
-constexpr int COL_FAN = SD_COL_FAN;  // probes per bound and round in a wide bucket (<= 32)
-#ifndef SD_DIRECT_MAX
-#define SD_DIRECT_MAX 8
-#endif
-constexpr int DIRECT_MAX = SD_DIRECT_MAX;  // up to this many suffixes are compared with the whole pattern at once
+constexpr int COL_FAN = 8;  // probes per bound and round in a wide bucket (<= 32)
+constexpr int DIRECT_MAX = 8;  // up to this many suffixes are compared with the whole pattern at once
 constexpr int LEVEL_MIN = 256;  // ranges above this are narrowed token by token first
 
 // Narrows the sorted range [l, h) to the entries whose token (tok_at(i), non-decreasing over
@@ -1708,7 +1685,7 @@ __device__ __forceinline__ void match_global_pair(const SpecParams &p, int32_t w
 // a node of depth D (which may have no children) was taken.
 template <bool STATS, bool TICKS>
 __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh, int b, int t,
-                        const int32_t *__restrict__ x, int src, int pl, Frontier &f, Stage &sg,
+                        const int32_t *__restrict__ x, int src, int pl, int usa_off, Frontier &f, Stage &sg,
                         int32_t *t_tok, int32_t *t_par, double *t_score, double &total,
                         bool &deepest, unsigned &nb) {
     const int lane = threadIdx.x & 63;
@@ -1723,7 +1700,7 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
     const int32_t *sa = nullptr, *text = nullptr;
     int32_t lo = 0, hi = 0;
     if (pl <= t && K >= 1) {
-        if (src == 0 && SD_GLIST && pl >= 2 && uni(sh.g_mode) != 0) {
+        if (src == 0 && pl >= 2 && uni(sh.g_mode) != 0) {
             // list form: the listed suffixes that match at least pl tokens, in their order
             // (the suffix array's, i.e. sorted by what follows the pattern), staged whole
             const int n2 = uni(sh.g_n2);
@@ -1757,7 +1734,9 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
             // unit has no candidate at all and nothing else needs to be read
             const int m1 = m > 1 ? uni(sh.m) : 0;
             const int2 *occ = p.occ + (int64_t)b * p.max_ctx;
-            int32_t *usa = p.unit_sa + ((int64_t)b * p.P + (pl - 1)) * p.max_ctx;
+            // a list of more than 64 occurrences goes to the request's row of scratch memory,
+            // at the place the caller has assigned to this run of pattern lengths
+            int32_t *usa = p.unit_sa + (int64_t)b * p.max_ctx + usa_off;
             const bool narrow = m <= 64;
             int w = 0;
             for (int base = 0; base < m1; base += 64) {
@@ -1810,7 +1789,7 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
             // this product form (and two trees of equal nodes must tie exactly): hence the
             // margin.  Checked once per step here; checks inside the merges of tied chains
             // cost more than they saved.
-            if (SD_SKIP_HOPELESS) {
+            {
                 const double top = uni(__longlong_as_double((long long)sh.top_bits));
                 if ((total + (double)(K - n) * best.s) * (1.0 + 1e-9) < top) {
                     n = 0;
@@ -1894,6 +1873,7 @@ struct AppendArgs {
 struct AcceptArgs {
     const int32_t *target;
     int32_t *accept_len, *accept_path, *bonus;
+    unsigned long long *counters;  // what sd_get_stats reports (SD_CTR_*)
 };
 
 // Acceptance for request b on one wavefront (max_nodes <= 256): node j is accepted iff its
@@ -2017,6 +1997,8 @@ __device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_
     if (lane == 0) {
         aa.accept_len[b] = L;
         aa.bonus[b] = bon;
+        atomicAdd(&aa.counters[SD_CTR_ACCEPT_REQUESTS], 1ull);
+        if (L > 0) atomicAdd(&aa.counters[SD_CTR_ACCEPT_LEN], (unsigned long long)L);
         if (APPEND && row) {
             int32_t t = bon;
             if (t < 0 || t >= ap.vocab) {
@@ -2052,12 +2034,8 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nod
 // those with the top SCORE, so "best" means SCORE high, then scan position low; the waves'
 // candidates meet in LDS after a barrier and the winning wave writes its tree out, padded
 // with -1 / 0.0.  Nothing but the final tree leaves the compute unit.
-#ifndef SD_SPEC_OCC
-#define SD_SPEC_OCC 6  // waves per SIMD that one or two resident workgroups may fill
-#endif
-#ifndef SD_SPEC_RESIDENT
-#define SD_SPEC_RESIDENT 4  // workgroups per compute unit the wave count is sized for
-#endif
+constexpr int SPEC_OCC = 6;       // waves per SIMD that one or two resident workgroups may fill
+constexpr int SPEC_RESIDENT = 4;  // workgroups per compute unit the wave count is sized for
 
 // With ACCEPT the workgroup first settles the verification of the request's previous tree (the
 // one `out` still holds, against aa.target) on its first wave, appends the accepted tokens and
@@ -2101,7 +2079,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         const int plA = 1 + wave, plB = plA + nw;
         if (plA <= P && plA <= t && p.g_N > 0 && lane < plA) wkA0 = x[t - plA + lane];
         if (plB <= P && plB <= t && p.g_N > 0 && lane < plB) wkB0 = x[t - plB + lane];
-        if (SD_GLIST && p.g_N > 0 && lane < P && lane < t) tail = x[t - 1 - lane];
+        if (p.g_N > 0 && lane < P && lane < t) tail = x[t - 1 - lane];
     };
     if (ACCEPT) {
         if (wave == 0) {
@@ -2130,7 +2108,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         // settles all pattern lengths in two more rounds of loads (suffix array, text), and
         // the expansions get their suffix lists from LDS.  Otherwise every pattern length is
         // searched for on its own, as below.
-        if (SD_GLIST && P >= 2 && t >= 2 && p.g_N > 0) {
+        if (P >= 2 && t >= 2 && p.g_N > 0) {
             const int32_t w_last = __builtin_amdgcn_readlane(tail, 0), w_prev = __builtin_amdgcn_readlane(tail, 1);
             const int32_t bv = lane < 4 ? p.g_bucket[(lane < 2 ? w_prev : w_last) + 1 + (lane & 1)] : 0;
             if (lane < 4) SD_CNT(4);
@@ -2241,7 +2219,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
     // Runs: entry i stands for pattern length P - i; lane i looks at entry i.
     int cg = 0, cr = 0, cgp = -1, crp = -1;
     bool alone = true;  // the next longer pattern may reach the depth bound
-    const bool listed = SD_GLIST && uni(sh.g_mode) != 0;
+    const bool listed = uni(sh.g_mode) != 0;
     // list form: lane i (pattern length P - i) gets the number of listed suffixes that match
     // at least that many tokens (a running sum over gcnt[P], gcnt[P - 1], ...)
     const int32_t gsum = listed ? wave_inclusive_sum(lane < P ? sh.gcnt[P - lane] : 0) : 0;
@@ -2260,6 +2238,37 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
     const uint64_t start_g = __ballot(lane < P && cg > 0 && (alone || cg != cgp));
     const uint64_t start_r = __ballot(lane < P && cr > 1 && (alone || cr != crp));
     const int ng = __popcll(start_g), nruns = ng + __popcll(start_r);
+    // A request-side suffix list of more than 64 occurrences is written to the request's row
+    // of scratch memory (max_ctx words), which the runs share: going through the runs in queue
+    // order, each such run gets the words behind the previous one's, and when the row is full
+    // the next run starts a new round at the row's beginning.  A round begins with a workgroup
+    // barrier, so every list of the round before is done with.  One list always fits (it holds
+    // at most as many occurrences as the context has tokens); on the workloads at hand all of
+    // a request's lists fit together and there is one round.
+    const uint64_t wide_r = start_r & __ballot(lane < P && cr > 64);
+    // (round, offset into the row) of the k-th request-side run
+    auto place = [&](int kth, int &round, int &off) {
+        int rnd = 0, used = 0, o = 0;
+        uint64_t mm = start_r;
+        for (int k = 0; k <= kth; k++) {
+            const int i = __ffsll((unsigned long long)mm) - 1;
+            mm &= mm - 1;
+            const int c = __builtin_amdgcn_readlane(cr, i);
+            o = used;
+            if (c > 64) {
+                if (used + c > p.max_ctx) { rnd++; o = 0; }
+                used = o + c;
+            }
+        }
+        round = rnd;
+        off = o;
+    };
+    int n_rounds = 1, my_round = 0;
+    if (wide_r) {
+        int off_last;
+        place(nruns - ng - 1, n_rounds, off_last);
+        n_rounds++;
+    }
 
     const uint64_t wg2 = TICKS ? wall_clock64() : 0;
     double best_s = 0.0;
@@ -2270,6 +2279,12 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         g = uni(g);
         if (g >= nruns) break;
         const int src = g >= ng ? 1 : 0;
+        int usa_off = 0;
+        if (src && wide_r) {
+            int rnd;
+            place(g - ng, rnd, usa_off);
+            for (; my_round < rnd; my_round++) __syncthreads();
+        }
         uint64_t m = src ? start_r : start_g;
         for (int k = src ? g - ng : g; k > 0; k--) m &= m - 1;
         const int i0 = __ffsll((unsigned long long)m) - 1;
@@ -2280,14 +2295,14 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         // whose longest pattern has fewer nodes to give than the best finished tree already
         // scores can neither win nor tie, whatever the order, and is left out.  (Which runs
         // that hits depends on timing; the result does not.)
-        if (SD_SKIP_HOPELESS) {
+        {
             const double top = uni(__longlong_as_double((long long)sh.top_bits));
             if (floor(p.alpha * (double)(P - i0)) < top) continue;
         }
         for (int pl = P - i0; pl >= p_lo; pl--) {
             double total = 0.0;
             bool deepest = false;
-            const int n = run_unit<STATS, TICKS>(p, sh, b, t, x, src, pl, f, sg, cur ? ttk1 : ttk0,
+            const int n = run_unit<STATS, TICKS>(p, sh, b, t, x, src, pl, usa_off, f, sg, cur ? ttk1 : ttk0,
                                           cur ? tpr1 : tpr0, cur ? tsc1 : tsc0, total, deepest, nb);
             int pstar = pl;  // shortest pattern of the run with this very tree
             if (!deepest)
@@ -2299,11 +2314,12 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
                 cur ^= 1;  // the tree just grown is kept; the next one grows into the other buffer
             }
             // (positive doubles order like their bit patterns)
-            if (SD_SKIP_HOPELESS && n > 0 && total > 0.0 && lane == 0)
+            if (n > 0 && total > 0.0 && lane == 0)
                 atomicMax(&sh.top_bits, (unsigned long long)__double_as_longlong(total));
             if (!deepest) break;
         }
     }
+    for (; my_round < n_rounds - 1; my_round++) __syncthreads();  // the rounds this wave had no run in
     const uint64_t wg3 = TICKS ? wall_clock64() : 0;
     if (lane == 0) { sh.best_s[wave] = best_s; sh.best_o[wave] = best_o; }
     __syncthreads();
@@ -2354,6 +2370,19 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
             out.d_source[b] = ww >= 0 ? wo / p.P : -1;
             if (out.d_use_draft) out.d_use_draft[b] = (ww >= 0 && ws > p.tau) ? 1 : 0;
             SD_CNT(24);
+            // what sd_get_stats reports about the drafting calls
+            unsigned long long *ctr = p.counters;
+            atomicAdd(&ctr[SD_CTR_REQUESTS], 1ull);
+            if (n > 0) {
+                atomicAdd(&ctr[SD_CTR_TREES], 1ull);
+                atomicAdd(&ctr[SD_CTR_NODES], (unsigned long long)n);
+                atomicAdd(&ctr[SD_CTR_MATCH_LEN], (unsigned long long)(wo % p.P + 1));
+                if (wo >= p.P) atomicAdd(&ctr[SD_CTR_FROM_REQUEST], 1ull);
+            }
+            if (t >= 2 && P >= 2 && p.g_N > 0) atomicAdd(&ctr[listed ? SD_CTR_GLOBAL_LIST : SD_CTR_GLOBAL_SEARCH], 1ull);
+            if (wide_r) atomicAdd(&ctr[SD_CTR_REQUEST_WIDE], 1ull);
+            if (n_rounds > 1) atomicAdd(&ctr[SD_CTR_LIST_ROUNDS], (unsigned long long)(n_rounds - 1));
+            if (uni(sh.m) > p.occ_cap) atomicAdd(&ctr[SD_CTR_OCC_IN_MEMORY], 1ull);
         }
     }
     flush_count<STATS>(nb, p.algo_bytes + SD_K_SPECULATE);
@@ -2406,6 +2435,7 @@ sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, 
     p.den_mode = c->cfg.den_mode; p.linear = c->cfg.linear;
     p.occ = c->s_occ; p.unit_sa = c->s_unit_sa;
     p.err = c->d_err;
+    p.counters = c->d_counters;
     p.algo_bytes = c->d_algo_bytes;
     p.unit_ticks = c->s_unit_ticks;
     p.wg_ticks = c->s_unit_ticks + (int64_t)c->cfg.max_batch_slots * 2 * c->cfg.P * 4;
@@ -2415,7 +2445,7 @@ sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, 
                       (64 + 64 + TC_TOKENS + 128) * sizeof(int32_t);
     lds_wave = (lds_wave + 7) / 8 * 8;
     // Waves per request.  One workgroup per compute unit takes the 16 waves a workgroup can
-    // have; two share SD_SPEC_OCC waves per SIMD between them (12 each if the LDS allows: the
+    // have; two share SPEC_OCC waves per SIMD between them (12 each if the LDS allows: the
     // registers of the kernel leave room for 7 waves per SIMD, and 14 each were not resident
     // together); three and four likewise (8 and 6 each, or what the LDS allows).  Larger batches
     // are throughput work: a compute unit's LDS holds about 20 waves' worth of frontier and
@@ -2424,8 +2454,8 @@ sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, 
     // idle time at the workgroup's barriers).  Thinner workgroups lose: every request then
     // takes longer and the end of the launch runs half empty.
     const int per_cu_all = (batch + c->n_cu - 1) / c->n_cu;
-    const int per_cu = per_cu_all < SD_SPEC_RESIDENT ? per_cu_all : SD_SPEC_RESIDENT;
-    int nw = per_cu_all <= 2 ? 4 * SD_SPEC_OCC / per_cu_all
+    const int per_cu = per_cu_all < SPEC_RESIDENT ? per_cu_all : SPEC_RESIDENT;
+    int nw = per_cu_all <= 2 ? 4 * SPEC_OCC / per_cu_all
              : per_cu_all == 3 ? 8 : per_cu_all == 4 ? 6 : per_cu_all <= 8 ? 5 : 4;
     const size_t lds_cu = c->lds_cu > 2048 * (size_t)per_cu ? c->lds_cu - 2048 * (size_t)per_cu : 0;
     while (nw > 1 && (size_t)nw * lds_wave * per_cu > lds_cu) nw--;
@@ -2480,7 +2510,7 @@ sd_status sd_accept_append_speculate_impl(sd_ctx *c, sd_trees trees, const int32
                                                    d_accept_path, d_bonus, st);
         return rc != SD_OK ? rc : sd_speculate_impl(c, d_slot_ids, batch, trees, st);
     }
-    const AcceptArgs aa{d_target, d_accept_len, d_accept_path, d_bonus};
+    const AcceptArgs aa{d_target, d_accept_len, d_accept_path, d_bonus, c->d_counters};
     return launch_speculate(c, d_slot_ids, batch, trees, &aa, st);
 }
 
@@ -2491,7 +2521,7 @@ sd_status sd_accept_impl(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t
     sd_span sp(c, SD_K_ACCEPT, st);
     hipLaunchKernelGGL(k_accept<false>, dim3((unsigned)batch), dim3(64), 0, st, trees.d_n_nodes,
                        trees.d_tokens, trees.d_parents, trees.max_nodes,
-                       AcceptArgs{d_target, d_accept_len, d_accept_path, d_bonus}, AppendArgs{});
+                       AcceptArgs{d_target, d_accept_len, d_accept_path, d_bonus, c->d_counters}, AppendArgs{});
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
@@ -2504,6 +2534,6 @@ sd_status sd_accept_append_impl(sd_ctx *c, sd_trees trees, const int32_t *d_slot
                   c->cfg.max_batch_slots, c->cfg.vocab, c->d_err};
     hipLaunchKernelGGL(k_accept<true>, dim3((unsigned)batch), dim3(64), 0, st, trees.d_n_nodes,
                        trees.d_tokens, trees.d_parents, trees.max_nodes,
-                       AcceptArgs{d_target, d_accept_len, d_accept_path, d_bonus}, ap);
+                       AcceptArgs{d_target, d_accept_len, d_accept_path, d_bonus, c->d_counters}, ap);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
