@@ -211,6 +211,21 @@ sd_status sd_index_append(sd_ctx *ctx, const int32_t *d_slot_ids, const int32_t 
 sd_status sd_speculate(sd_ctx *ctx, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
                        void *hip_stream);
 
+/* sd_speculate for callers that cannot allocate device memory or may not touch memory that
+ * was allocated at run time (code under HIP graph capture in a process whose allocator is
+ * frozen, tight serving loops, harnesses that forbid hipMalloc): the same kernel with the same
+ * results, but its working memory (occurrence records and suffix lists, 12 bytes per request
+ * of the call and token of max_ctx_tokens) is a static array of SD_STATIC_SCRATCH_BYTES inside
+ * the library's device code instead of buffers of the context; the call itself allocates and
+ * frees nothing.  SD_ERR_CAPACITY, with nothing enqueued, if
+ * batch * max_ctx_tokens * 12 > SD_STATIC_SCRATCH_BYTES.  Each device holds one such array
+ * for the life of the process, shared by every context on it: calls that overlap on one
+ * device (two streams, two contexts) race; calls that follow each other on one stream do
+ * not, and nothing in the array has to survive from one call to the next. */
+#define SD_STATIC_SCRATCH_BYTES (16u << 20)
+sd_status sd_speculate_static(sd_ctx *ctx, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
+                              void *hip_stream);
+
 /* Greedy verification walk (Section 2: drafted tokens are kept until the first
  * one the target model disagrees with; Section 4.1, simulated verifier).  d_target_tokens is
  * int32[batch * (max_nodes + 1)]: entry 0 of a request is the target model's

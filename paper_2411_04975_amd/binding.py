@@ -54,6 +54,7 @@ class _Stats(C.Structure):
             "spec_global_list", "spec_global_search", "spec_request_wide", "spec_occ_in_memory",
             "spec_list_rounds", "accept_requests", "accept_len")]
 
+SD_STATIC_SCRATCH_BYTES = 16 << 20
 
 
 KERNEL_NAMES = ["speculate", "accept", "append", "req_build", "sort_hist", "sort_scan",
@@ -89,6 +90,8 @@ def _load():
     L.sd_last_error.argtypes = [vp]
     L.sd_max_nodes.restype = C.c_int32
     L.sd_max_nodes.argtypes = [vp]
+    L.sd_speculate_static.restype = C.c_int
+    L.sd_speculate_static.argtypes = [vp, vp, C.c_int32, _Trees, vp]
     L.sd_index_build.restype = C.c_int
     L.sd_index_build.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int32, C.c_int64, vp]
     L.sd_index_entropy.restype = C.c_int
@@ -259,6 +262,16 @@ def sd_speculate(ctx: _Ctx, slot_ids: torch.Tensor, trees: Trees, stream=None) -
         raise ValueError("trees hold %d requests, batch is %d" % (trees.batch, batch))
     code = _load().sd_speculate(ctx.handle, _ptr(slot_ids, torch.int32, ctx, batch, "slot_ids"),
                                 batch, trees._struct(ctx, batch), _stream(stream, ctx))
+    _check(ctx, code)
+
+
+def sd_speculate_static(ctx: _Ctx, slot_ids: torch.Tensor, trees: Trees, stream=None) -> None:
+    """sd_speculate with the library's static device array as working memory."""
+    batch = int(slot_ids.numel())
+    if batch > trees.batch:
+        raise ValueError("trees hold %d requests, batch is %d" % (trees.batch, batch))
+    code = _load().sd_speculate_static(ctx.handle, _ptr(slot_ids, torch.int32, ctx, batch, "slot_ids"),
+                                       batch, trees._struct(ctx, batch), _stream(stream, ctx))
     _check(ctx, code)
 
 

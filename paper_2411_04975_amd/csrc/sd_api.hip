@@ -221,6 +221,23 @@ sd_status sd_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_t
     return sd_speculate_impl(c, d_slot_ids, batch, out, (hipStream_t)hip_stream);
 }
 
+sd_status sd_speculate_static(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
+                              void *hip_stream) {
+    if (!c) return SD_ERR_INVALID_ARG;
+    if (batch < 0) return fail(c, SD_ERR_INVALID_ARG, "negative batch");
+    if (batch > c->cfg.max_batch_slots)
+        return fail(c, SD_ERR_CAPACITY, "batch exceeds max_batch_slots");
+    if ((int64_t)batch * c->cfg.max_ctx_tokens * 12 > (int64_t)SD_STATIC_SCRATCH_BYTES)
+        return fail(c, SD_ERR_CAPACITY,
+                    "batch * max_ctx_tokens * 12 bytes exceeds SD_STATIC_SCRATCH_BYTES");
+    if (batch == 0) return SD_OK;
+    if (!d_slot_ids || !trees_ok(out)) return fail(c, SD_ERR_INVALID_ARG, "null pointer");
+    if (out.max_nodes < c->max_nodes)
+        return fail(c, SD_ERR_INVALID_ARG, "trees.max_nodes below floor(alpha*P)");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
+    return sd_speculate_static_impl(c, d_slot_ids, batch, out, (hipStream_t)hip_stream);
+}
+
 sd_status sd_accept(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t *d_target_tokens,
                     int32_t *d_accept_len, int32_t *d_accept_path, int32_t *d_bonus,
                     void *hip_stream) {

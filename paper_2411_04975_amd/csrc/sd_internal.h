@@ -62,6 +62,7 @@ struct sd_ctx {
                                      // than 64 occurrences (shared by the pattern lengths)
     uint32_t *s_unit_ticks = nullptr;  // [B][2P][4], written by the counting kernel variants
 
+    void *static_scratch = nullptr;  // this device's address of the library's static scratch array
     int32_t *d_err = nullptr;        // [SD_DEVERR_N]
     unsigned long long *d_counters = nullptr;  // [SD_CTR_N]
     double *d_entropy = nullptr;     // [3] accumulators of sd_index_entropy
@@ -106,6 +107,8 @@ sd_status sd_append_impl(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d_
 sd_status sd_speculate_setup(sd_ctx *c);  // device limits and kernel attributes, once per context
 sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
                             hipStream_t st);
+sd_status sd_speculate_static_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
+                                   sd_trees out, hipStream_t st);
 sd_status sd_accept_impl(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t *d_target,
                          int32_t *d_accept_len, int32_t *d_accept_path, int32_t *d_bonus,
                          hipStream_t st);

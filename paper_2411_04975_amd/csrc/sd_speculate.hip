@@ -2398,9 +2398,26 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
 // of the request's slot (what sd_index_append would do with them), in the same launch.
 }  // namespace
 
+// Scratch memory of sd_speculate_static: the occurrence records and suffix-list rows of its
+// requests (12 bytes per request and context token), in place of the buffers a context
+// allocates.  Every device the library runs on holds its own copy of the array at its own
+// address; host code reaches it only through the address that hipGetSymbolAddress reports for
+// the device that is current (kept per device in scratch_ptr, and per context).
+static __device__ __align__(256) unsigned char scratch[SD_STATIC_SCRATCH_BYTES];
+static void *scratch_ptr[64];  // by device ordinal; nullptr: not asked for yet
+
 sd_status sd_speculate_setup(sd_ctx *c) {
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, c->cfg.device) != hipSuccess) return SD_ERR_HIP;
+    {  // the calling thread has made c->cfg.device current
+        const int dev = c->cfg.device;
+        void *ptr = dev < 64 ? scratch_ptr[dev] : nullptr;
+        if (!ptr) {
+            if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return SD_ERR_HIP;
+            if (dev < 64) scratch_ptr[dev] = ptr;
+        }
+        c->static_scratch = ptr;
+    }
     c->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 1;
     c->lds_cu = prop.maxSharedMemoryPerMultiProcessor > 0 ? prop.maxSharedMemoryPerMultiProcessor
                                                           : prop.sharedMemPerBlock;
@@ -2424,7 +2441,8 @@ namespace {
 
 // Launches k_speculate; with `aa` the fused form that first accepts and appends.
 sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
-                           const AcceptArgs *aa, hipStream_t st) {
+                           const AcceptArgs *aa, hipStream_t st, int2 *occ = nullptr,
+                           int32_t *unit_sa = nullptr) {
     SpecParams p;
     p.g_text = c->g_text; p.g_sa = c->g_sa; p.g_bucket = c->g_bucket; p.g_tok1 = c->g_tok1; p.g_tok1s = c->g_tok1s;
     p.g_N = (int32_t)c->g_N;
@@ -2433,7 +2451,7 @@ sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, 
     p.D = c->cfg.D; p.P = c->cfg.P; p.max_nodes = c->max_nodes;
     p.alpha = c->cfg.alpha; p.min_score = c->cfg.min_score; p.tau = c->cfg.tau;
     p.den_mode = c->cfg.den_mode; p.linear = c->cfg.linear;
-    p.occ = c->s_occ; p.unit_sa = c->s_unit_sa;
+    p.occ = occ ? occ : c->s_occ; p.unit_sa = unit_sa ? unit_sa : c->s_unit_sa;
     p.err = c->d_err;
     p.counters = c->d_counters;
     p.algo_bytes = c->d_algo_bytes;
@@ -2498,6 +2516,18 @@ sd_status sd_speculate_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch,
                             hipStream_t st) {
     if (batch == 0) return SD_OK;
     return launch_speculate(c, d_slot_ids, batch, out, nullptr, st);
+}
+
+sd_status sd_speculate_static_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
+                                   hipStream_t st) {
+    if (batch == 0) return SD_OK;
+    // rows of max_ctx_tokens entries per request of this call: occurrence records, then lists
+    const int64_t rows = (int64_t)batch * c->cfg.max_ctx_tokens;
+    if (rows * (int64_t)(sizeof(int2) + sizeof(int32_t)) > (int64_t)SD_STATIC_SCRATCH_BYTES)
+        return SD_ERR_CAPACITY;
+    int2 *occ = reinterpret_cast<int2 *>(c->static_scratch);
+    int32_t *unit_sa = reinterpret_cast<int32_t *>(occ + rows);
+    return launch_speculate(c, d_slot_ids, batch, out, nullptr, st, occ, unit_sa);
 }
 
 sd_status sd_accept_append_speculate_impl(sd_ctx *c, sd_trees trees, const int32_t *d_slot_ids,
