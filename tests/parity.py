@@ -51,8 +51,14 @@ def oracle_speculate_batch(tg, contexts, D, P, alpha, min_score, max_nodes, requ
     return out
 
 
+GUARD = 64          # guard elements on either side of every output buffer
+GUARD_VALUE = -1234567
+
+
 class GpuPath:
-    """The HIP library driven through its binding, inputs handed over as numpy arrays."""
+    """The HIP library driven through its binding, inputs handed over as numpy arrays.  Every
+    output buffer the library writes sits between two runs of guard words, which are checked
+    after each call: a store outside the buffer fails the test that made it."""
 
     def __init__(self, vocab, D, P, alpha, min_score, max_slots, max_ctx, max_global, den_mode=0,
                  linear=0, tau=0.0):
@@ -66,6 +72,41 @@ class GpuPath:
 
     def close(self):
         self.sd.sd_destroy(self.ctx)
+
+    def _out(self, shape, dtype, fill):
+        """A poisoned output tensor of the given shape inside a larger buffer whose first and
+        last GUARD elements hold GUARD_VALUE."""
+        torch = self.torch
+        n = int(np.prod(shape))
+        buf = torch.full((n + 2 * GUARD,), GUARD_VALUE, dtype=dtype, device=self.dev)
+        view = buf[GUARD:GUARD + n].view(*shape)
+        view.fill_(fill)
+        self._guarded = getattr(self, "_guarded", [])
+        self._guarded.append(buf)
+        return view
+
+    def check_guards(self):
+        for buf in getattr(self, "_guarded", []):
+            edge = self.torch.cat([buf[:GUARD], buf[-GUARD:]])
+            assert bool((edge == GUARD_VALUE).all().item()), "a store outside an output buffer"
+
+    def _trees(self, B, mn):
+        """sd_trees whose arrays are guarded and poisoned, so that unwritten entries show up."""
+        torch = self.torch
+        tr = self.sd.Trees(B, mn, self.dev)
+        self._guarded = []
+        i32, f64 = torch.int32, torch.float64
+        tr.tokens, tr.parents = self._out((B, mn), i32, -7), self._out((B, mn), i32, -7)
+        tr.scores, tr.tree_score = self._out((B, mn), f64, -7.0), self._out((B,), f64, -7.0)
+        tr.n_nodes, tr.match_len = self._out((B,), i32, -7), self._out((B,), i32, -7)
+        tr.source, tr.use_draft = self._out((B,), i32, -7), self._out((B,), i32, -7)
+        self._tree_guards = self._guarded
+        return tr
+
+    def _accept_outputs(self, B, mn):
+        i32 = self.torch.int32
+        self._guarded = list(getattr(self, "_tree_guards", []))
+        return self._out((B,), i32, -7), self._out((B, mn), i32, -7), self._out((B,), i32, -7)
 
     def _seqs(self, seqs):
         torch = self.torch
@@ -111,14 +152,11 @@ class GpuPath:
         torch = self.torch
         B = len(slots)
         mn = max_nodes or self.max_nodes
-        tr = self.sd.Trees(B, mn, self.dev)
-        # poison the outputs so that unwritten entries show up
-        tr.tokens.fill_(-7); tr.parents.fill_(-7); tr.scores.fill_(-7.0); tr.n_nodes.fill_(-7)
-        tr.match_len.fill_(-7); tr.source.fill_(-7); tr.tree_score.fill_(-7.0)
-        tr.use_draft.fill_(-7)
+        tr = self._trees(B, mn)
         self.sd.sd_speculate(self.ctx, torch.tensor(list(slots), dtype=torch.int32,
                                                     device=self.dev), tr)
         torch.cuda.synchronize()
+        self.check_guards()
         self.trees = tr
         return dict(n_nodes=tr.n_nodes.cpu().numpy(), tokens=tr.tokens.cpu().numpy(),
                     parents=tr.parents.cpu().numpy(), scores=tr.scores.cpu().numpy(),
@@ -130,11 +168,10 @@ class GpuPath:
         tr = self.trees
         B, mn = tr.batch, tr.max_nodes
         d_t = torch.from_numpy(np.ascontiguousarray(target, np.int32)).to(self.dev)
-        al = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
-        ap = torch.full((B, mn), -7, dtype=torch.int32, device=self.dev)
-        bo = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        al, ap, bo = self._accept_outputs(B, mn)
         self.sd.sd_accept(self.ctx, tr, B, d_t, al, ap, bo)
         torch.cuda.synchronize()
+        self.check_guards()
         return al.cpu().numpy(), ap.cpu().numpy(), bo.cpu().numpy()
 
     def accept_append(self, slots, target):
@@ -143,13 +180,12 @@ class GpuPath:
         tr = self.trees
         B, mn = tr.batch, tr.max_nodes
         d_t = torch.from_numpy(np.ascontiguousarray(target, np.int32)).to(self.dev)
-        al = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
-        ap = torch.full((B, mn), -7, dtype=torch.int32, device=self.dev)
-        bo = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        al, ap, bo = self._accept_outputs(B, mn)
         self.sd.sd_accept_append(self.ctx, tr,
                                  torch.tensor(list(slots), dtype=torch.int32, device=self.dev),
                                  d_t, al, ap, bo)
         torch.cuda.synchronize()
+        self.check_guards()
         return al.cpu().numpy(), ap.cpu().numpy(), bo.cpu().numpy()
 
     def accept_append_speculate(self, slots, target):
@@ -159,12 +195,11 @@ class GpuPath:
         tr = self.trees
         B, mn = tr.batch, tr.max_nodes
         d_t = torch.from_numpy(np.ascontiguousarray(target, np.int32)).to(self.dev)
-        al = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
-        ap = torch.full((B, mn), -7, dtype=torch.int32, device=self.dev)
-        bo = torch.full((B,), -7, dtype=torch.int32, device=self.dev)
+        al, ap, bo = self._accept_outputs(B, mn)
         self.sd.sd_accept_append_speculate(
             self.ctx, tr, torch.tensor(list(slots), dtype=torch.int32, device=self.dev), d_t, al, ap, bo)
         torch.cuda.synchronize()
+        self.check_guards()
         trees = dict(n_nodes=tr.n_nodes.cpu().numpy(), tokens=tr.tokens.cpu().numpy(),
                      parents=tr.parents.cpu().numpy(), scores=tr.scores.cpu().numpy(),
                      tree_score=tr.tree_score.cpu().numpy(), match_len=tr.match_len.cpu().numpy(),

@@ -98,7 +98,8 @@ def test_agentic_scaled_parity():
     w = make_workload(scaled("agentic", n_docs=300, batch=32, ctx=2048), seed=0, name="agentic-s")
     got, want = _run_workload(w)
     assert (want["n_nodes"] > 0).sum() >= w.batch // 2
-    assert (want["source"] == 1).any() or True
+    # (which index the winners came from is asserted at full size, through the library's own
+    # counters: tests/test_gpu_full_size.py)
 
 
 def test_large_scaled_parity():

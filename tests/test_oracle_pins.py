@@ -199,18 +199,22 @@ def test_scores_closed_form_structure_and_topk(tiny_workload):
             # top-K property on counts: enumerate all admissible descendants by scanning
             if len(tok) and p >= 2:
                 sel = sorted((tg.lookup(q)[0] for q in paths), reverse=True)
-                cand = []
+                # `sure`: nodes clearly at or above min_score; `maybe`: those plus the ones
+                # within 1e-9 of it, on which rounding may decide either way (fewest
+                # occurrences of all, so they sort last)
+                sure, maybe = [], []
                 stack = [root]
                 while stack:
                     cur = stack.pop()
                     for t_, c_ in brute.children(docs, cur, w.D).items():
-                        if c_ / c_root >= w.min_score * (1 + 1e-9):
-                            cand.append(c_)
+                        if c_ / c_root >= w.min_score * (1 - 1e-9):
+                            maybe.append(c_)
                             stack.append(cur + [t_])
-                cand.sort(reverse=True)
-                # (a candidate within 1e-9 of min_score is left out of `cand`, hence the guard)
-                if len(cand) >= len(sel):
-                    assert sel == cand[:len(sel)]
+                            if c_ / c_root >= w.min_score * (1 + 1e-9):
+                                sure.append(c_)
+                maybe.sort(reverse=True)
+                assert sel == maybe[:len(sel)]
+                assert len(sel) >= min(K, len(sure))
                 n_checked += 1
     assert n_checked > 20
 
