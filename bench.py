@@ -1,13 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the SuffixDecoding draft-generation path on one MI355X.
 
-A step is one decode step over the whole batch: sd_speculate (match, expand, select), the
-simulated greedy verifier, sd_accept, and sd_index_append of the accepted + bonus tokens.
+A step is one decode step over the whole batch: the simulated greedy verifier on the current
+drafts, then sd_accept_append_speculate (acceptance, append of the accepted + bonus tokens,
+the next drafts): one speculation, one verification, one acceptance and one append per step.
 The two index builds (global corpus, request contexts) happen once per run and are timed
 separately in the same run (index_build_tokens_per_s).  Inputs are synthetic, resident in HBM
 before any timed region starts.
 
-Prints ONE JSON line.  `value` = speculation trees per second over K timed steps.
+Prints ONE JSON line.  `value` = speculation trees per second over K timed decode steps of the
+headline workload (large); `other_workloads` holds the same figures for the agentic,
+low-repetition and streaming configurations (streaming: per-step latency over its 64 steps).
 """
 from __future__ import annotations
 
@@ -26,19 +29,45 @@ HBM_PEAK_GBS = 8000.0
 
 
 def _traffic_from_profiles(kernel: str, workload: str):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), if a summary
-    for this kernel and workload has been committed under profiles/."""
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), and the
+    commit the summary says it was measured at, if a summary for this kernel and workload has
+    been committed under profiles/."""
     path = os.path.join(ROOT, "profiles", "%s_%s_pmc.md" % (kernel, workload))
     try:
-        m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
-        return float(m.group(1)) if m else None
+        txt = open(path).read()
     except OSError:
-        return None
+        return None, None
+    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", txt)
+    c = re.search(r"measured_at_commit:\s*([0-9a-f]+)", txt)
+    return (float(m.group(1)) if m else None), (c.group(1) if c else None)
 
 
-def cpu_baseline(w, n_requests: int, build_tokens: int):
-    """The oracle as it stands, single thread, on a bounded sample of the same workload."""
-    import numpy as np
+def _host_threads() -> int:
+    """Threads the oracle's all-cores leg uses: the cores this process may run on, at most 16
+    (the share of a one-GPU job on the benchmark machine)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
+def _cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(w, n_one: int, n_all: int, build_tokens: int):
+    """The oracle as it stands on a bounded sample of the same workload: GenerateCandidateTree
+    for the first requests of the batch against the full corpus, on one thread and, over
+    disjoint requests, on all the host cores this process has (the tries are read-only while
+    drafting, and the C oracle runs outside the interpreter lock)."""
+    import concurrent.futures as cf
     import oracle
     from tests import parity
     docs = w.docs()
@@ -53,33 +82,263 @@ def cpu_baseline(w, n_requests: int, build_tokens: int):
             break
     build_s = time.perf_counter() - t0
     del t
-    # (b) draft generation for the first n_requests requests against the full corpus; the
-    # global trie holds exactly the suffixes those requests can reach
-    contexts = [w.contexts[b] for b in range(n_requests)]
+    # (b) draft generation; the global trie holds exactly the suffixes the sample can reach
+    threads = _host_threads()
+    n_all = max(n_one, min(n_all, w.batch))
+    contexts = [w.contexts[b] for b in range(n_all)]
     tg = parity.oracle_global_trie(docs, w.D, w.vocab, contexts, w.P)
-    tries = []
-    for x in contexts:
+
+    def request_trie(x):
         tr = oracle.Trie(w.D)
         tr.append(x)
-        tries.append(tr)
-    reps = []
-    for _ in range(5):   # median of five passes over the sample
-        t0 = time.perf_counter()
-        drafted = 0
-        for x, tr in zip(contexts, tries):
-            g = oracle.generate(tg, tr, x, w.P, w.alpha, w.min_score)
-            drafted += g["n_nodes"]
-        reps.append(time.perf_counter() - t0)
-    spec_s = sorted(reps)[len(reps) // 2]
+        return tr
+
+    with cf.ThreadPoolExecutor(threads) as ex:
+        tries = list(ex.map(request_trie, contexts))
+
+        def draft(i):
+            return oracle.generate(tg, tries[i], contexts[i], w.P, w.alpha, w.min_score)["n_nodes"]
+
+        reps = []
+        for _ in range(5):   # one thread: median of five passes over the first n_one requests
+            t0 = time.perf_counter()
+            drafted = sum(draft(i) for i in range(n_one))
+            reps.append(time.perf_counter() - t0)
+        one_s = sorted(reps)[len(reps) // 2]
+        reps_all = []
+        for _ in range(5):   # all threads over all n_all requests
+            t0 = time.perf_counter()
+            drafted_all = sum(ex.map(draft, range(n_all)))
+            reps_all.append(time.perf_counter() - t0)
+        all_s = sorted(reps_all)[len(reps_all) // 2]
     return {
-        "value": n_requests / spec_s, "unit": "trees/s", "cores": 1, "kind": "oracle",
-        "sample": "first %d requests of the batch against the full %d-token corpus "
-                  "(GenerateCandidateTree only, tries prebuilt, median of five passes); build leg: plain trie over the "
-                  "first %d corpus tokens" % (n_requests, len(w.corpus), n),
-        "us_per_drafted_token": spec_s / max(drafted, 1) * 1e6,
-        "first_pass_trees_per_s": n_requests / reps[0],   # caches cold: every later pass is faster
+        "value": n_all / all_s, "unit": "trees/s", "cores": threads, "kind": "oracle",
+        "sample": "GenerateCandidateTree for the first %d requests of the batch against the full "
+                  "%d-token corpus on %d threads over disjoint requests (tries prebuilt and "
+                  "read-only, median of five passes); one-thread figures: the first %d requests; "
+                  "build leg: plain trie over the first %d corpus tokens on one thread"
+                  % (n_all, len(w.corpus), threads, n_one, n),
+        "cpu_model": _cpu_model(), "host_cpus_visible": os.cpu_count(),
+        "us_per_drafted_token": all_s / max(drafted_all, 1) * 1e6,
+        "one_thread": {"value": n_one / one_s, "unit": "trees/s", "cores": 1,
+                       "us_per_drafted_token": one_s / max(drafted, 1) * 1e6,
+                       "first_pass_trees_per_s": n_one / reps[0]},
         "index_build_tokens_per_s": n / build_s,
     }
+
+
+class Run:
+    """One workload on the device: inputs uploaded, context created, the decode step in its
+    three forms, and the timing legs every workload gets."""
+
+    def __init__(self, args, name, total_steps):
+        import numpy as np
+        import torch
+        import paper_2411_04975_amd as sd
+        from workloads import CONFIGS, make_workload, verifier
+        self.np, self.torch, self.sd, self.verifier = np, torch, sd, verifier
+        self.args = args
+        cfg = CONFIGS[name]
+        self.cfg = cfg
+        mn = int(np.floor(cfg["alpha"] * cfg["P"]))
+        self.mn = mn
+        self.w = w = make_workload(name, seed=args.seed,
+                                   future_len=(total_steps + 2) * (mn + 1) + mn + 2)
+        self.dev = dev = torch.device("cuda", 0)
+        torch.cuda.set_device(dev)
+        self.B, self.ctx_len = B, ctx_len = w.batch, w.ctx_len
+        self.n_tokens, self.n_docs = int(w.corpus.shape[0]), len(w.doc_offsets) - 1
+        i32 = torch.int32
+        self.d_corpus = torch.from_numpy(w.corpus).to(dev)
+        self.d_doc_off = torch.from_numpy(w.doc_offsets).to(dev)
+        self.d_ctx = torch.from_numpy(w.contexts.reshape(-1)).to(dev)
+        self.d_ctx_off = torch.arange(0, (B + 1) * ctx_len, ctx_len, dtype=torch.int64, device=dev)
+        self.d_future = torch.from_numpy(w.future).to(dev)
+        self.d_slots = torch.arange(B, dtype=i32, device=dev)
+        max_ctx = ctx_len + (total_steps + 1) * (mn + 1)
+        self.ctx = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, B, max_ctx,
+                                self.n_tokens + self.n_docs, 0)
+        self.trees = sd.Trees(B, mn, dev)
+        self.d_target = torch.zeros((B, mn + 1), dtype=i32, device=dev)
+        self.d_alen = torch.full((B,), -1, dtype=i32, device=dev)
+        self.d_apath = torch.zeros((B, mn), dtype=i32, device=dev)
+        self.d_bonus = torch.zeros(B, dtype=i32, device=dev)
+        self.d_new = torch.zeros(B * (mn + 1), dtype=i32, device=dev)
+        self.d_newoff = torch.zeros(B + 1, dtype=i32, device=dev)
+        self.d_pos = torch.zeros(B, dtype=i32, device=dev)
+        self.one_launch = not (args.separate_calls or args.two_launches)
+        self.step = (self.step_separate if args.separate_calls else
+                     self.step_fused if args.two_launches else self.step_next)
+
+    def close(self):
+        self.sd.sd_destroy(self.ctx)
+
+    def ev(self):
+        return self.torch.cuda.Event(enable_timing=True)
+
+    # ---- index builds -----------------------------------------------------------------------
+    def build_global(self):
+        self.sd.sd_index_build(self.ctx, self.sd.SD_SCOPE_GLOBAL, None, self.d_corpus,
+                               self.d_doc_off, self.n_tokens)
+
+    def build_requests(self):
+        self.sd.sd_index_build(self.ctx, self.sd.SD_SCOPE_REQUESTS, self.d_slots, self.d_ctx,
+                               self.d_ctx_off, self.B * self.ctx_len)
+
+    def time_builds(self, reps):
+        """Median of `reps` global builds and one request build, HIP events, inputs in HBM."""
+        torch = self.torch
+        self.build_global()
+        torch.cuda.synchronize()
+        ms = []
+        for _ in range(reps):
+            e0, e1 = self.ev(), self.ev()
+            e0.record()
+            self.build_global()
+            e1.record()
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        ms.sort()
+        e0, e1 = self.ev(), self.ev()
+        e0.record()
+        self.build_requests()
+        e1.record()
+        torch.cuda.synchronize()
+        return ms[len(ms) // 2], e0.elapsed_time(e1)
+
+    # ---- the decode step, three ways --------------------------------------------------------
+    def step_separate(self):
+        sd, v = self.sd, self.verifier
+        sd.sd_speculate(self.ctx, self.d_slots, self.trees)
+        v.targets(self.trees.n_nodes, self.trees.parents, self.d_future, self.d_pos, self.d_target)
+        sd.sd_accept(self.ctx, self.trees, self.B, self.d_target, self.d_alen, self.d_apath, self.d_bonus)
+        v.collect(self.trees.tokens, self.d_alen, self.d_apath, self.d_bonus, self.d_new,
+                  self.d_newoff, self.d_pos)
+        sd.sd_index_append(self.ctx, self.d_slots, self.d_new, self.d_newoff)
+
+    def step_fused(self):
+        # the verifier stand-in moves its positions on by what the previous step produced;
+        # sd_accept_append does sd_accept and sd_index_append of the result in one launch
+        sd, v = self.sd, self.verifier
+        sd.sd_speculate(self.ctx, self.d_slots, self.trees)
+        v.targets(self.trees.n_nodes, self.trees.parents, self.d_future, self.d_pos, self.d_target,
+                  advance=self.d_alen)
+        sd.sd_accept_append(self.ctx, self.trees, self.d_slots, self.d_target, self.d_alen,
+                            self.d_apath, self.d_bonus)
+
+    def step_next(self):
+        # One library launch per step: the trees hold the current drafts; the verifier stand-in
+        # produces their target tokens; sd_accept_append_speculate ends the step (acceptance,
+        # append) and drafts the next trees from the extended contexts.
+        self.verifier.targets(self.trees.n_nodes, self.trees.parents, self.d_future, self.d_pos,
+                              self.d_target, advance=self.d_alen)
+        self.sd.sd_accept_append_speculate(self.ctx, self.trees, self.d_slots, self.d_target,
+                                           self.d_alen, self.d_apath, self.d_bonus)
+
+    def reset(self):
+        self.build_requests()
+        self.d_pos.zero_()
+        self.d_alen.fill_(-1)
+        if self.one_launch:  # the first drafts: every later step leaves the next ones behind
+            self.sd.sd_speculate(self.ctx, self.d_slots, self.trees)
+
+    def warm(self, W):
+        self.reset()
+        for _ in range(W):
+            self.step()
+        self.torch.cuda.synchronize()
+
+    def capture(self, n_steps):
+        g = self.torch.cuda.CUDAGraph()
+        with self.torch.cuda.graph(g):
+            for _ in range(n_steps):
+                self.step()
+        self.torch.cuda.synchronize()
+        return g
+
+    def timed_steps(self, K, W, steps_per_graph):
+        """Wall clock between device synchronisations over K steps that follow W warm-up steps
+        from a fresh state.  The steps are replayed from a HIP graph captured through the same
+        C-ABI calls (steps_per_graph <= 0: all K in one graph, one launch for the timed region;
+        1: one launch per step), or enqueued from the host with --no-graph."""
+        torch = self.torch
+        self.warm(W)                  # also loads every kernel before capture
+        S = 0
+        graphs = None
+        if not self.args.no_graph:
+            S = K if steps_per_graph <= 0 else max(1, min(steps_per_graph, K))
+            graphs = (self.capture(S), self.capture(1) if K % S else None)
+            self.warm(W)              # capture ran no work: start again from a known state
+        t0 = time.perf_counter()
+        if graphs is not None:
+            for _ in range(K // S):
+                graphs[0].replay()
+            for _ in range(K % S):
+                graphs[1].replay()
+        else:
+            for _ in range(K):
+                self.step()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, S
+
+    def step_latency(self, K, W):
+        """Every step its own launch (a one-step graph, or host enqueue), bracketed by events
+        and synchronised: what a serving loop that waits for each step sees."""
+        torch = self.torch
+        self.warm(max(W, 1))
+        run = self.step
+        if not self.args.no_graph:
+            run = self.capture(1).replay
+            self.warm(W)
+        lat = []
+        for _ in range(K):
+            e0, e1 = self.ev(), self.ev()
+            e0.record()
+            run()
+            e1.record()
+            torch.cuda.synchronize()
+            lat.append(e0.elapsed_time(e1))
+        lat.sort()
+        return {"median": lat[len(lat) // 2], "p99": lat[min(len(lat) - 1, int(0.99 * len(lat)))],
+                "max": lat[-1], "steps": K}
+
+    def common_figures(self, K, W, build_reps):
+        """The figures every workload reports."""
+        B = self.B
+        g_build_ms, r_build_ms = self.time_builds(build_reps)
+        elapsed, S = self.timed_steps(K, W, self.args.steps_per_graph)
+        mean_nodes = float(self.trees.n_nodes.float().mean().item())
+        mean_accept = float(self.d_alen.float().mean().item())
+        st = self.sd.sd_get_stats(self.ctx)
+        assert st["err_bad_token"] == 0 and st["err_bad_slot"] == 0 and st["err_ctx_overflow"] == 0, st
+        elapsed1, _ = self.timed_steps(K, W, 1)
+        out = {
+            "batch": B, "ctx_len": self.ctx_len, "corpus_tokens": self.n_tokens,
+            "steps": K, "warmup": W,
+            "ms_per_step": elapsed / K * 1e3, "trees_per_s": B * K / elapsed,
+            "launch": ("hip-graph replay, %d step%s per graph" % (S, "" if S == 1 else "s"))
+                      if S else "host enqueue",
+            "ms_per_step_one_launch_per_step": elapsed1 / K * 1e3,
+            "step_latency_ms": self.step_latency(K, W),
+            "index_build_ms": g_build_ms,
+            "index_build_tokens_per_s": self.n_tokens / (g_build_ms * 1e-3),
+            "request_build_ms": r_build_ms,
+            "request_build_tokens_per_s": B * self.ctx_len / (r_build_ms * 1e-3),
+            "mean_tree_nodes": mean_nodes, "mean_accept_len": mean_accept,
+            "index_bytes": st["index_bytes"], "scratch_bytes": st["scratch_bytes"],
+        }
+        # what the library's own counters say about all drafting calls so far
+        if st["spec_requests"]:
+            out["counters"] = {
+                "requests_with_a_tree": st["spec_trees"] / st["spec_requests"],
+                "mean_winning_p": st["spec_match_len"] / max(st["spec_trees"], 1),
+                "mean_nodes_per_tree": st["spec_nodes"] / max(st["spec_trees"], 1),
+                "trees_from_request_index": st["spec_from_request"] / max(st["spec_trees"], 1),
+                "global_matches_by_per_p_search": st["spec_global_search"] / st["spec_requests"],
+                "requests_with_long_request_lists": st["spec_request_wide"] / st["spec_requests"],
+                "mean_accept_len": st["accept_len"] / max(st["accept_requests"], 1),
+            }
+        return out, elapsed, S
 
 
 def main():
@@ -88,6 +347,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large")
+    ap.add_argument("--others", default="agentic,lowrep,streaming",
+                    help="further workloads whose step time, step latency and build rates go into "
+                         "other_workloads (streaming always runs its 64 decode steps); empty: none")
     ap.add_argument("--build-reps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true",
@@ -116,56 +378,25 @@ def main():
     import numpy as np
     import torch
     import paper_2411_04975_amd as sd
-    from workloads import CONFIGS, make_workload, verifier
+    from workloads import CONFIGS, verifier
     from workloads.synth import extra_contexts
 
     K, W = args.steps, args.warmup
-    cfg = CONFIGS[args.workload]
-    mn = int(np.floor(cfg["alpha"] * cfg["P"]))
-    total_steps = K + W
-    w = make_workload(args.workload, seed=args.seed, future_len=(total_steps + 2) * (mn + 1) + mn + 2)
-    dev = torch.device("cuda", 0)
-    torch.cuda.set_device(dev)
-    B, ctx_len = w.batch, w.ctx_len
-    n_tokens, n_docs = int(w.corpus.shape[0]), len(w.doc_offsets) - 1
-
+    run = Run(args, args.workload, K + W)
+    w, cfg, mn, dev = run.w, run.cfg, run.mn, run.dev
+    B, ctx_len, n_tokens, n_docs = run.B, run.ctx_len, run.n_tokens, run.n_docs
+    ctx, trees, d_slots, d_ctx = run.ctx, run.trees, run.d_slots, run.d_ctx
+    ev, step, reset, one_launch = run.ev, run.step, run.reset, run.one_launch
     i32 = torch.int32
-    d_corpus = torch.from_numpy(w.corpus).to(dev)
-    d_doc_off = torch.from_numpy(w.doc_offsets).to(dev)
-    d_ctx = torch.from_numpy(w.contexts.reshape(-1)).to(dev)
-    d_ctx_off = torch.arange(0, (B + 1) * ctx_len, ctx_len, dtype=torch.int64, device=dev)
-    d_future = torch.from_numpy(w.future).to(dev)
-    d_slots = torch.arange(B, dtype=i32, device=dev)
-    max_ctx = ctx_len + (total_steps + 1) * (mn + 1)
 
-    ctx = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, B, max_ctx, n_tokens + n_docs, 0)
-    trees = sd.Trees(B, mn, dev)
-    d_target = torch.zeros((B, mn + 1), dtype=i32, device=dev)
-    d_alen = torch.full((B,), -1, dtype=i32, device=dev)
-    d_apath = torch.zeros((B, mn), dtype=i32, device=dev)
-    d_bonus = torch.zeros(B, dtype=i32, device=dev)
-    d_new = torch.zeros(B * (mn + 1), dtype=i32, device=dev)
-    d_newoff = torch.zeros(B + 1, dtype=i32, device=dev)
-    d_pos = torch.zeros(B, dtype=i32, device=dev)
-
-    def ev():
-        return torch.cuda.Event(enable_timing=True)
-
-    # ---- index builds (timed separately, inputs already in HBM) -------------------------
-    def build_global():
-        sd.sd_index_build(ctx, sd.SD_SCOPE_GLOBAL, None, d_corpus, d_doc_off, n_tokens)
-
-    def build_requests():
-        sd.sd_index_build(ctx, sd.SD_SCOPE_REQUESTS, d_slots, d_ctx, d_ctx_off, B * ctx_len)
-
-    build_global()
+    run.build_global()
     torch.cuda.synchronize()
     # The hand-written streaming copy of known size (the corpus: 4 B read + 4 B written per
     # token) lets rocprofv3 counter runs of this script calibrate FETCH_SIZE / WRITE_SIZE; the
     # same kernel over 2 x 512 MiB gives the achievable HBM rate of this run.
-    calib = torch.empty_like(d_corpus)
+    calib = torch.empty_like(run.d_corpus)
     if n_tokens % 4 == 0:
-        verifier.stream_copy(d_corpus, calib)
+        verifier.stream_copy(run.d_corpus, calib)
     torch.cuda.synchronize()
     del calib
     big_a = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
@@ -181,144 +412,34 @@ def main():
         copy_ms.append(e0.elapsed_time(e1))
     achievable_gbs = 2.0 * big_a.numel() / (min(copy_ms[1:]) * 1e-3) / 1e9
     del big_a, big_b
-    build_ms = []
-    for _ in range(args.build_reps):
-        e0, e1 = ev(), ev()
-        e0.record()
-        build_global()
-        e1.record()
-        torch.cuda.synchronize()
-        build_ms.append(e0.elapsed_time(e1))
-    build_ms.sort()
-    g_build_ms = build_ms[len(build_ms) // 2]
+
+    head, elapsed, S = run.common_figures(K, W, args.build_reps)
+    mean_nodes, mean_accept = head["mean_tree_nodes"], head["mean_accept_len"]
     sd.sd_debug_profile(ctx, 1)
-    build_global()
+    run.build_global()
     prof_build = sd.sd_debug_profile_read(ctx)
     sd.sd_debug_profile(ctx, 0)
-    e0, e1 = ev(), ev()
-    e0.record()
-    build_requests()
-    e1.record()
-    torch.cuda.synchronize()
-    r_build_ms = e0.elapsed_time(e1)
-
-    # ---- decode steps ---------------------------------------------------------------------
-    def step_separate():
-        sd.sd_speculate(ctx, d_slots, trees)
-        verifier.targets(trees.n_nodes, trees.parents, d_future, d_pos, d_target)
-        sd.sd_accept(ctx, trees, B, d_target, d_alen, d_apath, d_bonus)
-        verifier.collect(trees.tokens, d_alen, d_apath, d_bonus, d_new, d_newoff, d_pos)
-        sd.sd_index_append(ctx, d_slots, d_new, d_newoff)
-
-    def step_fused():
-        # the verifier stand-in moves its positions on by what the previous step produced;
-        # sd_accept_append does sd_accept and sd_index_append of the result in one launch
-        sd.sd_speculate(ctx, d_slots, trees)
-        verifier.targets(trees.n_nodes, trees.parents, d_future, d_pos, d_target, advance=d_alen)
-        sd.sd_accept_append(ctx, trees, d_slots, d_target, d_alen, d_apath, d_bonus)
-
-    def step_next():
-        # One library launch per step: the trees hold the current drafts; the verifier stand-in
-        # produces their target tokens; sd_accept_append_speculate ends the step (acceptance,
-        # append) and drafts the next trees from the extended contexts.  Per step the same
-        # work as above: one speculation, one verification, one acceptance, one append.
-        verifier.targets(trees.n_nodes, trees.parents, d_future, d_pos, d_target, advance=d_alen)
-        sd.sd_accept_append_speculate(ctx, trees, d_slots, d_target, d_alen, d_apath, d_bonus)
-
-    one_launch = not (args.separate_calls or args.two_launches)
-    step = step_separate if args.separate_calls else step_fused if args.two_launches else step_next
-
-    def reset():
-        build_requests()
-        d_pos.zero_()
-        d_alen.fill_(-1)
-        if one_launch:  # the first drafts: every later step leaves the next ones behind
-            sd.sd_speculate(ctx, d_slots, trees)
-
-    # The timed loop replays a HIP graph captured from the steps: the same kernels, enqueued by
-    # the same C-ABI calls, without the host between them (a graph launch costs about 4 us, so
-    # one graph holds all timed steps; --steps-per-graph 1 replays step by step, --no-graph
-    # times host-side enqueueing instead).
-    for _ in range(W):
-        step()
-    torch.cuda.synchronize()
-    graph = None
-    if not args.no_graph:
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph):
-            step()
-        torch.cuda.synchronize()
-        S = K if args.steps_per_graph <= 0 else max(1, min(args.steps_per_graph, K))
-        graph_s = graph
-        if S > 1:
-            graph_s = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(graph_s):
-                for _ in range(S):
-                    step()
-            torch.cuda.synchronize()
-        reset()                       # capture ran no work; start the timed region from a
-        for _ in range(W):            # known state: W eager warm-up steps after a rebuild
-            step()
-        torch.cuda.synchronize()
-    run_step = graph.replay if graph is not None else step
-    t0 = time.perf_counter()
-    if graph is not None:
-        for _ in range(K // S):
-            graph_s.replay()
-        for _ in range(K % S):
-            graph.replay()
-    else:
-        for _ in range(K):
-            step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    mean_nodes = float(trees.n_nodes.float().mean().item())
-    mean_accept = float(d_alen.float().mean().item())
-    stats = sd.sd_get_stats(ctx)
-    assert stats["err_bad_token"] == 0 and stats["err_bad_slot"] == 0 and \
-        stats["err_ctx_overflow"] == 0, stats
-
-    # ---- per-step latency (each step bracketed by events and synchronised) ----------------
-    reset()
-    for _ in range(W):
-        step()
-    torch.cuda.synchronize()
-    lat = []
-    for _ in range(K):
-        e0, e1 = ev(), ev()
-        e0.record()
-        run_step()
-        e1.record()
-        torch.cuda.synchronize()
-        lat.append(e0.elapsed_time(e1))
-    lat.sort()
-    step_latency = {"median": lat[len(lat) // 2], "p99": lat[min(len(lat) - 1, int(0.99 * len(lat)))],
-                    "max": lat[-1]}
 
     # ---- sd_speculate alone: median over 50 calls from one fixed state, and against batch ---
-    reset()
-    for _ in range(W):
-        step()
-    torch.cuda.synchronize()
+    run.warm(W)
 
     def time_speculate(slots_t, reps):
         for _ in range(5):
             sd.sd_speculate(ctx, slots_t, trees)
         torch.cuda.synchronize()
-        run = None
         if not args.no_graph:
             g2 = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g2):
                 sd.sd_speculate(ctx, slots_t, trees)
             torch.cuda.synchronize()
-            run = g2.replay
+            go = g2.replay
         else:
-            run = lambda: sd.sd_speculate(ctx, slots_t, trees)
+            go = lambda: sd.sd_speculate(ctx, slots_t, trees)
         ts = []
         for _ in range(reps):
             e0, e1 = ev(), ev()
             e0.record()
-            run()
+            go()
             e1.record()
             torch.cuda.synchronize()
             ts.append(e0.elapsed_time(e1))
@@ -369,23 +490,17 @@ def main():
             else torch.zeros(B + 1, dtype=torch.int64, device=dev)
         sd.sd_index_build(ctx, sd.SD_SCOPE_REQUESTS, d_slots, cut, off, B * L)
         us_by_context[str(L)] = kernel_us()
-    build_requests()
+    run.build_requests()
 
     # ---- per-kernel durations (HIP events on the launch stream) over the same K steps -----
-    reset()
-    for _ in range(W):
-        step()
-    torch.cuda.synchronize()
+    run.warm(W)
     sd.sd_debug_profile(ctx, 1)
     sd.sd_debug_profile_read(ctx)
     for _ in range(K):
         step()
     prof = sd.sd_debug_profile_read(ctx)
     # ---- algorithmic bytes of the same launches (counting variants, untimed) --------------
-    reset()
-    for _ in range(W):
-        step()
-    torch.cuda.synchronize()
+    run.warm(W)
     sd.sd_debug_profile(ctx, 2)
     sd.sd_debug_profile_read(ctx)
     for _ in range(K):
@@ -394,9 +509,7 @@ def main():
     sd.sd_debug_profile(ctx, 0)
 
     # ---- latency profile of sd_speculate: wall-clock marks inside the timing variant --------
-    reset()
-    for _ in range(W):
-        step()
+    run.warm(W)
     sd.sd_debug_profile(ctx, 3)
     sd.sd_debug_profile_read(ctx)
     for _ in range(3):
@@ -449,20 +562,22 @@ def main():
     if one_launch:
         exp_bytes += B * (8.0 * mean_nodes + 4.0 * (mn + 1) + 4.0 * mn + 8.0 + 4.0 * (mean_accept + 1))
     achieved = exp_bytes / (exp_ms * 1e-3) / 1e9 if exp_ms > 0 else 0.0
+    traffic, traffic_commit = _traffic_from_profiles("k_speculate", w.name)
     roofline = {"bound": "hbm",
                 "kernel": "k_speculate<accept and append first>" if one_launch else "k_speculate",
                 "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": _traffic_from_profiles("k_speculate", w.name),
+                "traffic": traffic, "traffic_measured_at_commit": traffic_commit,
                 "algo_bytes_per_launch": exp_bytes, "avg_launch_ms": exp_ms,
                 "achievable": achievable_gbs, "frac_of_achievable": achieved / achievable_gbs}
     N = n_tokens + n_docs
     sc = prof_build["sort_scatter"]
     sc_ms = sc["ms"] / max(sc["launches"], 1)
     sc_ach = 24.0 * N / (sc_ms * 1e-3) / 1e9 if sc_ms > 0 else 0.0
+    traffic_b, traffic_b_commit = _traffic_from_profiles("k_radix_scatter", w.name)
     roofline_build = {"bound": "hbm", "kernel": "k_radix_scatter", "achieved": sc_ach,
                       "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": sc_ach / HBM_PEAK_GBS,
-                      "traffic": _traffic_from_profiles("k_radix_scatter", w.name),
+                      "traffic": traffic_b, "traffic_measured_at_commit": traffic_b_commit,
                       "algo_bytes_per_launch": 24.0 * N, "avg_launch_ms": sc_ms,
                       "launches_per_build": sc["launches"], "achievable": achievable_gbs,
                       "frac_of_achievable": sc_ach / achievable_gbs}
@@ -474,8 +589,11 @@ def main():
         "value": B * K / elapsed, "unit": "trees/s", "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": elapsed / K * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "int32+f64", "data": "synthetic",
-        "launch": ("hip-graph replay, %d step%s per graph" % (S, "" if S == 1 else "s"))
-                  if graph is not None else "host enqueue",
+        "value_is": "requests drafted for per second of whole decode steps (verifier stand-in, "
+                    "acceptance, append, next drafts), all timed steps in one graph launch; "
+                    "sd_speculate alone: speculate_only_trees_per_s; one launch per step: "
+                    "ms_per_step_one_launch_per_step",
+        "launch": head["launch"],
         "config": {"workload": w.name, "batch": B, "ctx_len": ctx_len, "corpus_tokens": n_tokens,
                    "corpus_docs": n_docs, "vocab": w.vocab, "D": w.D, "P": w.P, "alpha": w.alpha,
                    "min_score": w.min_score, "max_nodes": mn, "seed": args.seed,
@@ -488,19 +606,21 @@ def main():
                             if args.two_launches else
                             "simulated verifier + sd_accept_append_speculate (verification of "
                             "the current drafts, acceptance, append, next drafts)")},
-        "index_build_tokens_per_s": n_tokens / (g_build_ms * 1e-3),
-        "index_build_ms": g_build_ms, "request_build_ms": r_build_ms,
-        "request_build_tokens_per_s": B * ctx_len / (r_build_ms * 1e-3),
-        "step_latency_ms": step_latency,
+        "ms_per_step_one_launch_per_step": head["ms_per_step_one_launch_per_step"],
+        "index_build_tokens_per_s": head["index_build_tokens_per_s"],
+        "index_build_ms": head["index_build_ms"], "request_build_ms": head["request_build_ms"],
+        "request_build_tokens_per_s": head["request_build_tokens_per_s"],
+        "step_latency_ms": head["step_latency_ms"],
         "speculate_only_ms_median": spec_ms, "speculate_only_trees_per_s": B / (spec_ms * 1e-3),
         "speculate_latency_us_by_batch": latency_by_batch,
         "speculate_kernel_us_by_context_tokens": us_by_context,
         "speculate_latency_profile": latency_profile,
         "stream_copy_gbs": achievable_gbs,
         "mean_tree_nodes": mean_nodes, "mean_accept_len": mean_accept,
+        "counters": head.get("counters"),
         "kernel_ms_per_launch": kernels_ms, "build_kernel_ms_total": build_kernels_ms,
         "roofline": roofline, "roofline_build": roofline_build,
-        "index_bytes": stats["index_bytes"], "scratch_bytes": stats["scratch_bytes"],
+        "index_bytes": head["index_bytes"], "scratch_bytes": head["scratch_bytes"],
     }
     # ---- empirical entropy of the global index (the paper's effectiveness predictor) -------
     t0 = time.perf_counter()
@@ -514,6 +634,7 @@ def main():
     # ---- online insertion: the outputs of one batch (B documents of max_nodes + 1 tokens) are
     # added to the global index; done last because it grows the index.  The context was sized
     # for the corpus alone, so a second context with room for the insertions does this leg.
+    d_corpus, d_doc_off, d_future = run.d_corpus, run.d_doc_off, run.d_future
     ins_docs, ins_len, ins_reps = B, mn + 1, 3
     ctx2 = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, 1, 64,
                         n_tokens + n_docs + ins_reps * ins_docs * (ins_len + 1), 0)
@@ -535,7 +656,7 @@ def main():
                            "ms_median": ins_ms[len(ins_ms) // 2],
                            "tokens_per_s": ins_docs * ins_len / (ins_ms[len(ins_ms) // 2] * 1e-3)}
     sd.sd_destroy(ctx2)
-    sd.sd_destroy(ctx)
+    run.close()
 
     # ---- sd_speculate as throughput work: batches of several workgroups per compute unit ----
     # The workload's own batch is one workgroup per compute unit and bound by its slowest
@@ -594,17 +715,42 @@ def main():
             del gw, tr
         st3 = sd.sd_get_stats(ctx3)
         assert st3["err_bad_token"] == 0 and st3["err_bad_slot"] == 0, st3
+        by_batch["scratch_bytes_of_the_%d_slot_context" % nmax] = st3["scratch_bytes"]
         sd.sd_destroy(ctx3)
         out["speculate_throughput_by_batch"] = by_batch
-        # the same kernel with the compute units full: its share of the roofline there
+        # the same kernel with the compute units full: its share of the roofline there (a
+        # batch no configuration names: context, never the headline fraction)
         top_b = str(wide[-1])
         out["roofline"]["sd_speculate_at_batch_%s" % top_b] = {
             "achieved": by_batch[top_b]["achieved_gbs"], "frac": by_batch[top_b]["frac_of_peak"],
             "frac_of_achievable": by_batch[top_b]["frac_of_achievable"],
             "avg_launch_ms": by_batch[top_b]["us_per_launch"] * 1e-3,
             "algo_bytes_per_launch": by_batch[top_b]["algo_bytes_per_launch"]}
+        del d_wctx, d_woff, d_wslots
+    del run, d_corpus, d_doc_off, d_future, d_ctx, trees, d_slots, ctx2d, ev, step, reset, ctx
+    torch.cuda.empty_cache()
+
+    # ---- the other configurations: step time, per-step latency, build rates -----------------
+    others = {}
+    for name in [v.strip() for v in args.others.split(",") if v.strip()]:
+        if name == args.workload or name not in CONFIGS:
+            continue
+        # the streaming configuration is defined as a run of 64 decode steps from the given
+        # contexts: its latency figures are over those 64 steps, no warm-up steps before them
+        Ko, Wo = (CONFIGS[name]["steps"], 0) if name == "streaming" else (K, W)
+        r = Run(args, name, Ko + Wo)
+        fig, _, _ = r.common_figures(Ko, Wo, args.build_reps)
+        fig["config"] = {k: r.cfg[k] for k in ("vocab", "D", "P", "alpha", "min_score")}
+        r.close()
+        del r
+        torch.cuda.empty_cache()
+        others[name] = fig
+    out["other_workloads"] = others
+
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, n_requests=min(32, B), build_tokens=300_000)
+        from workloads import make_workload
+        wl = make_workload(args.workload, seed=args.seed)
+        out["cpu_baseline"] = cpu_baseline(wl, n_one=min(32, B), n_all=min(128, B), build_tokens=300_000)
     print(json.dumps(out))
 
 

@@ -235,7 +235,7 @@ sd_status sd_speculate_static(sd_ctx *ctx, const int32_t *d_slot_ids, int32_t ba
  * d_accept_len[b] = number of accepted nodes, d_accept_path[b*max_nodes ..]
  * their indices in order (rest -1), d_bonus[b] = the target token at the last
  * accepted node (the token the target model contributes itself).
- * trees.max_nodes <= 256. */
+ * trees.max_nodes <= 256, batch <= max_batch_slots. */
 sd_status sd_accept(sd_ctx *ctx, sd_trees trees, int32_t batch, const int32_t *d_target_tokens,
                     int32_t *d_accept_len, int32_t *d_accept_path, int32_t *d_bonus,
                     void *hip_stream);

@@ -33,7 +33,7 @@ void free_all(sd_ctx *c) {
     void *ptrs[] = {c->g_text, c->g_sa, c->g_bucket, c->g_tok1, c->g_tok1s, c->b_keys[0], c->b_keys[1], c->b_vals[0],
                     c->b_vals[1], c->b_rank, c->b_flags, c->b_gid2, c->b_hist, c->b_partials, c->r_text,
                     c->r_len, c->s_occ, c->s_unit_sa, c->d_err, c->s_unit_ticks, c->d_entropy,
-                    c->d_round_flag, c->d_counters};
+                    c->d_round_flag};
     for (void *p : ptrs)
         if (p) (void)hipFree(p);
     if (c->d_algo_bytes) (void)hipFree(c->d_algo_bytes);
@@ -98,14 +98,13 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
          dev_alloc(&c->b_gid2, cap, sb);
     ok = ok && dev_alloc(&c->b_hist, c->b_hist_cap, sb);
     ok = ok && dev_alloc(&c->b_partials, c->b_partials_cap, sb);
-    ok = ok && dev_alloc(&c->r_text, B * c->r_stride, sb) && dev_alloc(&c->r_len, B, sb);
+    ok = ok && dev_alloc(&c->r_text, B * c->r_stride, sb) && dev_alloc(&c->r_len, ((B + 31) / 32) * 32 + B * SD_CTR_STRIDE * 2, sb);
     ok = ok && dev_alloc(&c->s_occ, B * ctx, sb);
     ok = ok && dev_alloc(&c->s_unit_sa, B * ctx, sb);
     ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb) && dev_alloc(&c->d_entropy, 4, sb) &&
          dev_alloc(&c->d_round_flag, 8, sb);
     ok = ok && dev_alloc(&c->s_unit_ticks, B * 2 * P * 4 + B * 16 * 8, sb);
     ok = ok && dev_alloc(&c->d_algo_bytes, SD_K_COUNT, sb);
-    ok = ok && dev_alloc(&c->d_counters, SD_CTR_N, sb);
     if (!ok) {
         free_all(c);
         delete c;
@@ -123,7 +122,10 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     sd_fill_i32(c->r_len, B, 0, nullptr);
     sd_fill_i32(c->d_err, SD_DEVERR_N, 0, nullptr);
     sd_fill_i32((int32_t *)c->d_algo_bytes, 2 * SD_K_COUNT, 0, nullptr);
-    sd_fill_i32((int32_t *)c->d_counters, 2 * SD_CTR_N, 0, nullptr);
+    // the counters live behind the context lengths, in the same allocation: every workgroup
+    // reads its length at its start, so the counters' page is one the compute unit has seen
+    c->d_counters = reinterpret_cast<unsigned long long *>(c->r_len + ((B + 31) / 32) * 32);
+    sd_fill_i32((int32_t *)c->d_counters, 2 * B * SD_CTR_STRIDE, 0, nullptr);
     if (hipDeviceSynchronize() != hipSuccess) {
         free_all(c);
         delete c;
@@ -243,6 +245,8 @@ sd_status sd_accept(sd_ctx *c, sd_trees trees, int32_t batch, const int32_t *d_t
                     void *hip_stream) {
     if (!c) return SD_ERR_INVALID_ARG;
     if (batch < 0) return fail(c, SD_ERR_INVALID_ARG, "negative batch");
+    if (batch > c->cfg.max_batch_slots)
+        return fail(c, SD_ERR_CAPACITY, "batch exceeds max_batch_slots");
     if (batch == 0) return SD_OK;
     if (!trees.d_n_nodes || !trees.d_tokens || !trees.d_parents || trees.max_nodes < 1 ||
         !d_target_tokens || !d_accept_len || !d_accept_path || !d_bonus)
@@ -303,11 +307,20 @@ sd_status sd_get_stats(sd_ctx *c, sd_stats *o) {
     o->reserved = 0;
     o->index_bytes = c->index_bytes;
     o->scratch_bytes = c->scratch_bytes;
-    unsigned long long ctr[SD_CTR_N];
-    if (hipMemcpy(ctr, c->d_counters, sizeof(ctr), hipMemcpyDeviceToHost) != hipSuccess)
+    const size_t rows = (size_t)c->cfg.max_batch_slots;
+    unsigned long long *ctr = new (std::nothrow) unsigned long long[rows * SD_CTR_STRIDE];
+    if (!ctr) return fail(c, SD_ERR_OOM, "host buffer for the counters");
+    if (hipMemcpy(ctr, c->d_counters, rows * SD_CTR_STRIDE * sizeof(*ctr), hipMemcpyDeviceToHost) !=
+        hipSuccess) {
+        delete[] ctr;
         return fail(c, SD_ERR_HIP, "hipMemcpy");
+    }
     int64_t *dst = &o->spec_requests;  // the counter fields follow each other in this order
-    for (int i = 0; i < SD_CTR_N; i++) dst[i] = (int64_t)ctr[i];
+    for (int i = 0; i < SD_CTR_N; i++) {
+        dst[i] = 0;
+        for (size_t r = 0; r < rows; r++) dst[i] += (int64_t)ctr[r * SD_CTR_STRIDE + i];
+    }
+    delete[] ctr;
     return SD_OK;
 }
 

@@ -20,6 +20,14 @@ enum {
     SD_CTR_GLOBAL_LIST, SD_CTR_GLOBAL_SEARCH, SD_CTR_REQUEST_WIDE, SD_CTR_OCC_IN_MEMORY,
     SD_CTR_LIST_ROUNDS, SD_CTR_ACCEPT_REQUESTS, SD_CTR_ACCEPT_LEN, SD_CTR_N
 };
+// Every request index b of a call has a row of its own (SD_CTR_STRIDE words, the first SD_CTR_N
+// in use): the workgroup that serves request b reads the row early, adds its share and stores
+// it with its results, plain loads and stores (calls on one context do not overlap, and a
+// launch has one workgroup per b); sd_get_stats adds the rows up.  The counters of the
+// drafting calls come first, those of acceptance behind them.  (Atomic adds were measured: on
+// a dozen shared addresses they queue up, 15 us per launch at batch 512; spread over 256
+// addresses each they still held the end of every launch up by 0.3 to 1 us.)
+#define SD_CTR_STRIDE 16
 
 struct sd_ctx {
     sd_config cfg;
@@ -64,7 +72,7 @@ struct sd_ctx {
 
     void *static_scratch = nullptr;  // this device's address of the library's static scratch array
     int32_t *d_err = nullptr;        // [SD_DEVERR_N]
-    unsigned long long *d_counters = nullptr;  // [SD_CTR_N]
+    unsigned long long *d_counters = nullptr;  // [max_batch_slots][SD_CTR_STRIDE]
     double *d_entropy = nullptr;     // [3] accumulators of sd_index_entropy
     int32_t *d_round_flag = nullptr; // [8] per doubling round: groups too long for the in-tile sort
 

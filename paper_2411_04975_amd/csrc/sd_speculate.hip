@@ -270,7 +270,7 @@ struct WgShared {
     int gl_pos[64], gl_L[64], gcnt[72];
     int g_mode, g_n2;
     double best_s[16];
-    int best_o[16];
+    int best_o[16], best_n[16];
 };
 
 // MatchPattern on the per-request structure, for all pattern lengths at once, by the whole
@@ -1895,6 +1895,10 @@ __device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_
     int32_t *path = aa.accept_path + (int64_t)b * max_nodes;
     // every load of the tree and the targets is issued before the node count is looked at
     int n = n_nodes[b];
+    // this request's counters of verified requests and accepted nodes (see sd_internal.h)
+    unsigned long long *ctr = aa.counters + (int64_t)b * SD_CTR_STRIDE;
+    unsigned long long c_req = 0, c_len = 0;
+    if (lane == 0) { c_req = ctr[SD_CTR_ACCEPT_REQUESTS]; c_len = ctr[SD_CTR_ACCEPT_LEN]; }
     int32_t mt[4], mp[4];
 #pragma unroll
     for (int r = 0; r < 4; r++) {
@@ -1997,8 +2001,8 @@ __device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_
     if (lane == 0) {
         aa.accept_len[b] = L;
         aa.bonus[b] = bon;
-        atomicAdd(&aa.counters[SD_CTR_ACCEPT_REQUESTS], 1ull);
-        if (L > 0) atomicAdd(&aa.counters[SD_CTR_ACCEPT_LEN], (unsigned long long)L);
+        ctr[SD_CTR_ACCEPT_REQUESTS] = c_req + 1ull;
+        ctr[SD_CTR_ACCEPT_LEN] = c_len + (unsigned long long)L;
         if (APPEND && row) {
             int32_t t = bon;
             if (t < 0 || t >= ap.vocab) {
@@ -2071,6 +2075,15 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
     int2 *const s_sort = reinterpret_cast<int2 *>(smem);
     ScanState scan;
     occ_scan_issue<STATS>(t_old, x, sh, scan, nb);
+    // the request's row of counters (what sd_get_stats reports): read now by the last wave,
+    // behind the scan's loads, and written back by it with this launch's share at the end,
+    // beside the wave that writes the tree (a single wave issues an instruction every few
+    // cycles, so even fifty more of them on the winner's path held every launch up by a
+    // third of a microsecond).  Plain loads and stores: a row belongs to one workgroup per
+    // launch.
+    unsigned long long ctr_old = 0;
+    if (wave == nw - 1 && lane < SD_CTR_ACCEPT_REQUESTS)
+        ctr_old = p.counters[(int64_t)b * SD_CTR_STRIDE + lane];
     int t = t_old;
     // lane k: pattern token k of the wave's first two pattern lengths
     int32_t wkA0 = 0, wkB0 = 0;
@@ -2270,6 +2283,15 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         n_rounds++;
     }
 
+    if (wave == nw - 1) {  // the routes this request takes, into the row of counters (lane k: counter k)
+        const bool two = t >= 2 && P >= 2 && p.g_N > 0;
+        const int add = lane == SD_CTR_GLOBAL_LIST ? (listed && two)
+                        : lane == SD_CTR_GLOBAL_SEARCH ? (!listed && two)
+                        : lane == SD_CTR_REQUEST_WIDE ? (wide_r != 0)
+                        : lane == SD_CTR_OCC_IN_MEMORY ? (uni(sh.m) > p.occ_cap)
+                        : lane == SD_CTR_LIST_ROUNDS ? n_rounds - 1 : 0;
+        ctr_old += (unsigned long long)add;
+    }
     const uint64_t wg2 = TICKS ? wall_clock64() : 0;
     double best_s = 0.0;
     int best_o = -1, best_n = 0, cur = 0;
@@ -2321,7 +2343,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
     }
     for (; my_round < n_rounds - 1; my_round++) __syncthreads();  // the rounds this wave had no run in
     const uint64_t wg3 = TICKS ? wall_clock64() : 0;
-    if (lane == 0) { sh.best_s[wave] = best_s; sh.best_o[wave] = best_o; }
+    if (lane == 0) { sh.best_s[wave] = best_s; sh.best_o[wave] = best_o; sh.best_n[wave] = best_n; }
     __syncthreads();
     if (TICKS && lane == 0 && wave < 16) {
         // per wave: start (absolute, low 32 bits), then ticks since the start at: occurrences
@@ -2350,6 +2372,14 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
             wo = (int)~ox;
         }
     }
+    if (wave == nw - 1 && lane < SD_CTR_ACCEPT_REQUESTS) {  // lane k: counter k of the drafting calls
+        const int n = ww < 0 ? 0 : sh.best_n[ww];
+        const bool tree = n > 0;
+        const int add = lane == SD_CTR_REQUESTS ? 1 : lane == SD_CTR_TREES ? tree : lane == SD_CTR_NODES ? n
+                        : lane == SD_CTR_MATCH_LEN ? (tree ? wo % p.P + 1 : 0)
+                        : lane == SD_CTR_FROM_REQUEST ? (tree && wo >= p.P) : 0;
+        p.counters[(int64_t)b * SD_CTR_STRIDE + lane] = ctr_old + (unsigned long long)add;
+    }
     if (wave == (ww < 0 ? 0 : ww)) {
         const int n = ww < 0 ? 0 : best_n;
         const int kept = cur ^ 1;  // the buffer the wave's best tree was left in
@@ -2370,19 +2400,6 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
             out.d_source[b] = ww >= 0 ? wo / p.P : -1;
             if (out.d_use_draft) out.d_use_draft[b] = (ww >= 0 && ws > p.tau) ? 1 : 0;
             SD_CNT(24);
-            // what sd_get_stats reports about the drafting calls
-            unsigned long long *ctr = p.counters;
-            atomicAdd(&ctr[SD_CTR_REQUESTS], 1ull);
-            if (n > 0) {
-                atomicAdd(&ctr[SD_CTR_TREES], 1ull);
-                atomicAdd(&ctr[SD_CTR_NODES], (unsigned long long)n);
-                atomicAdd(&ctr[SD_CTR_MATCH_LEN], (unsigned long long)(wo % p.P + 1));
-                if (wo >= p.P) atomicAdd(&ctr[SD_CTR_FROM_REQUEST], 1ull);
-            }
-            if (t >= 2 && P >= 2 && p.g_N > 0) atomicAdd(&ctr[listed ? SD_CTR_GLOBAL_LIST : SD_CTR_GLOBAL_SEARCH], 1ull);
-            if (wide_r) atomicAdd(&ctr[SD_CTR_REQUEST_WIDE], 1ull);
-            if (n_rounds > 1) atomicAdd(&ctr[SD_CTR_LIST_ROUNDS], (unsigned long long)(n_rounds - 1));
-            if (uni(sh.m) > p.occ_cap) atomicAdd(&ctr[SD_CTR_OCC_IN_MEMORY], 1ull);
         }
     }
     flush_count<STATS>(nb, p.algo_bytes + SD_K_SPECULATE);
