@@ -155,6 +155,9 @@ class Run:
         self.d_ctx_off = torch.arange(0, (B + 1) * ctx_len, ctx_len, dtype=torch.int64, device=dev)
         self.d_future = torch.from_numpy(w.future).to(dev)
         self.d_slots = torch.arange(B, dtype=i32, device=dev)
+        # request b lives in slot b: the decode step says so by passing no slot ids (which
+        # spares every drafting workgroup one dependent load), unless --explicit-slot-ids
+        self.step_slots = self.d_slots if args.explicit_slot_ids else None
         max_ctx = ctx_len + (total_steps + 1) * (mn + 1)
         self.ctx = sd.sd_create(w.vocab, w.D, w.P, w.alpha, w.min_score, B, max_ctx,
                                 self.n_tokens + self.n_docs, 0)
@@ -209,21 +212,21 @@ class Run:
     # ---- the decode step, three ways --------------------------------------------------------
     def step_separate(self):
         sd, v = self.sd, self.verifier
-        sd.sd_speculate(self.ctx, self.d_slots, self.trees)
+        sd.sd_speculate(self.ctx, self.step_slots, self.trees)
         v.targets(self.trees.n_nodes, self.trees.parents, self.d_future, self.d_pos, self.d_target)
         sd.sd_accept(self.ctx, self.trees, self.B, self.d_target, self.d_alen, self.d_apath, self.d_bonus)
         v.collect(self.trees.tokens, self.d_alen, self.d_apath, self.d_bonus, self.d_new,
                   self.d_newoff, self.d_pos)
-        sd.sd_index_append(self.ctx, self.d_slots, self.d_new, self.d_newoff)
+        sd.sd_index_append(self.ctx, self.step_slots, self.d_new, self.d_newoff)
 
     def step_fused(self):
         # the verifier stand-in moves its positions on by what the previous step produced;
         # sd_accept_append does sd_accept and sd_index_append of the result in one launch
         sd, v = self.sd, self.verifier
-        sd.sd_speculate(self.ctx, self.d_slots, self.trees)
+        sd.sd_speculate(self.ctx, self.step_slots, self.trees)
         v.targets(self.trees.n_nodes, self.trees.parents, self.d_future, self.d_pos, self.d_target,
                   advance=self.d_alen)
-        sd.sd_accept_append(self.ctx, self.trees, self.d_slots, self.d_target, self.d_alen,
+        sd.sd_accept_append(self.ctx, self.trees, self.step_slots, self.d_target, self.d_alen,
                             self.d_apath, self.d_bonus)
 
     def step_next(self):
@@ -232,7 +235,7 @@ class Run:
         # append) and drafts the next trees from the extended contexts.
         self.verifier.targets(self.trees.n_nodes, self.trees.parents, self.d_future, self.d_pos,
                               self.d_target, advance=self.d_alen)
-        self.sd.sd_accept_append_speculate(self.ctx, self.trees, self.d_slots, self.d_target,
+        self.sd.sd_accept_append_speculate(self.ctx, self.trees, self.step_slots, self.d_target,
                                            self.d_alen, self.d_apath, self.d_bonus)
 
     def reset(self):
@@ -240,7 +243,7 @@ class Run:
         self.d_pos.zero_()
         self.d_alen.fill_(-1)
         if self.one_launch:  # the first drafts: every later step leaves the next ones behind
-            self.sd.sd_speculate(self.ctx, self.d_slots, self.trees)
+            self.sd.sd_speculate(self.ctx, self.step_slots, self.trees)
 
     def warm(self, W):
         self.reset()
@@ -364,6 +367,9 @@ def main():
     ap.add_argument("--two-launches", action="store_true",
                     help="sd_speculate and sd_accept_append as two launches per step instead of "
                          "sd_accept_append_speculate (the end of a step and the next draft in one)")
+    ap.add_argument("--explicit-slot-ids", action="store_true",
+                    help="pass an array of slot ids (0, 1, 2, ...) to the calls of the decode step "
+                         "instead of NULL, which stands for the same identity mapping")
     ap.add_argument("--throughput-batches", default="1024,4096,8192",
                     help="batch sizes beyond the workload's own at which sd_speculate is timed as "
                          "throughput work (several workgroups per compute unit); empty: skip")
@@ -412,6 +418,12 @@ def main():
         copy_ms.append(e0.elapsed_time(e1))
     achievable_gbs = 2.0 * big_a.numel() / (min(copy_ms[1:]) * 1e-3) / 1e9
     del big_a, big_b
+
+    # what a load costs whose address comes from the load before it (one lane, random lines):
+    # working sets that fit the L2, the memory-side cache, and neither
+    dep_ns = {name: verifier.dependent_load_ns(lines, 20000, dev)
+              for name, lines in (("2 MB", 1 << 14), ("64 MB", 1 << 19), ("2 GB", 1 << 24))}
+    torch.cuda.empty_cache()
 
     head, elapsed, S = run.common_figures(K, W, args.build_reps)
     mean_nodes, mean_accept = head["mean_tree_nodes"], head["mean_accept_len"]
@@ -605,7 +617,9 @@ def main():
                             "sd_speculate + simulated verifier + sd_accept_append"
                             if args.two_launches else
                             "simulated verifier + sd_accept_append_speculate (verification of "
-                            "the current drafts, acceptance, append, next drafts)")},
+                            "the current drafts, acceptance, append, next drafts)"),
+                   "slot_ids": "explicit array" if args.explicit_slot_ids else
+                               "NULL (request b is slot b)"},
         "ms_per_step_one_launch_per_step": head["ms_per_step_one_launch_per_step"],
         "index_build_tokens_per_s": head["index_build_tokens_per_s"],
         "index_build_ms": head["index_build_ms"], "request_build_ms": head["request_build_ms"],
@@ -615,7 +629,7 @@ def main():
         "speculate_latency_us_by_batch": latency_by_batch,
         "speculate_kernel_us_by_context_tokens": us_by_context,
         "speculate_latency_profile": latency_profile,
-        "stream_copy_gbs": achievable_gbs,
+        "stream_copy_gbs": achievable_gbs, "dependent_load_ns_by_working_set": dep_ns,
         "mean_tree_nodes": mean_nodes, "mean_accept_len": mean_accept,
         "counters": head.get("counters"),
         "kernel_ms_per_launch": kernels_ms, "build_kernel_ms_total": build_kernels_ms,

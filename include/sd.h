@@ -29,6 +29,9 @@
  *  - One sd_ctx belongs to one device; calls on one sd_ctx must not overlap.
  *  - Tokens are int32 in [0, vocab).  Sequence i of a (tokens, offsets) pair
  *    is tokens[offsets[i] .. offsets[i+1]).
+ *  - Wherever a call takes d_slot_ids, NULL stands for the identity: sequence
+ *    or request i is slot i.  A serving loop that keeps request i in slot i
+ *    saves every drafting workgroup one dependent load that way.
  *
  * Readings of points the paper leaves open are part of this contract:
  *  - Depth bound D: the indexes hold every suffix cut to its first D tokens, so
@@ -296,9 +299,10 @@ typedef struct {
 sd_status sd_debug_profile(sd_ctx *ctx, int32_t mode);
 sd_status sd_debug_profile_read(sd_ctx *ctx, sd_profile *host_out);
 
-/* Latency profile: after an sd_speculate call made with profiling mode 3, copies four
- * wall-clock marks per (request, index, p) unit -- ticks since the unit started at the end of
- * its set-up, of reading its match, of the first child enumeration, and of the whole unit; unit
+/* Latency profile: after an sd_speculate call made with profiling mode 3, copies four words
+ * per (request, index, p) unit -- the ticks the unit spent merging tied single-occurrence
+ * chains, then ticks since the unit started at the end of reading its match, of the first child
+ * enumeration, and of the whole unit; unit
  * index = (b * 2 + index) * P + (p - 1), `count` = 4 * units -- and the tick rate in kHz.
  * Only units that were expanded are written (a pattern length whose tree is known from a
  * longer pattern of the same request is not); the others keep what the buffer held.

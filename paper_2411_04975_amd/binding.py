@@ -219,7 +219,8 @@ def sd_index_build(ctx: _Ctx, scope: int, slot_ids: Optional[torch.Tensor], toke
         raise ValueError("seq_offsets needs at least one entry")
     code = _load().sd_index_build(
         ctx.handle, scope,
-        _ptr(slot_ids, torch.int32, ctx, n_seq if scope == SD_SCOPE_REQUESTS else 0, "slot_ids"),
+        _ptr(slot_ids, torch.int32, ctx,
+             n_seq if scope == SD_SCOPE_REQUESTS and slot_ids is not None else 0, "slot_ids"),
         _ptr(tokens, torch.int32, ctx, n_tokens, "tokens"),
         _ptr(seq_offsets, torch.int64, ctx, n_seq + 1, "seq_offsets"), n_seq, n_tokens,
         _stream(stream, ctx))
@@ -248,29 +249,33 @@ def sd_index_entropy(ctx: _Ctx, stream=None):
 
 def sd_index_append(ctx: _Ctx, slot_ids: torch.Tensor, new_tokens: torch.Tensor,
                     new_offsets: torch.Tensor, stream=None) -> None:
-    n = int(slot_ids.numel())
+    n = int(new_offsets.numel()) - 1 if slot_ids is None else int(slot_ids.numel())
     code = _load().sd_index_append(
-        ctx.handle, _ptr(slot_ids, torch.int32, ctx, n, "slot_ids"),
+        ctx.handle, _ptr(slot_ids, torch.int32, ctx, 0 if slot_ids is None else n, "slot_ids"),
         _ptr(new_tokens, torch.int32, ctx, 0 if n == 0 else 1, "new_tokens"),
         _ptr(new_offsets, torch.int32, ctx, n + 1, "new_offsets"), n, _stream(stream, ctx))
     _check(ctx, code)
 
 
-def sd_speculate(ctx: _Ctx, slot_ids: torch.Tensor, trees: Trees, stream=None) -> None:
-    batch = int(slot_ids.numel())
+def _batch_of(slot_ids, trees: "Trees") -> int:
+    """slot_ids None: the identity over the trees' whole batch."""
+    batch = trees.batch if slot_ids is None else int(slot_ids.numel())
     if batch > trees.batch:
         raise ValueError("trees hold %d requests, batch is %d" % (trees.batch, batch))
-    code = _load().sd_speculate(ctx.handle, _ptr(slot_ids, torch.int32, ctx, batch, "slot_ids"),
+    return batch
+
+
+def sd_speculate(ctx: _Ctx, slot_ids: Optional[torch.Tensor], trees: Trees, stream=None) -> None:
+    batch = _batch_of(slot_ids, trees)
+    code = _load().sd_speculate(ctx.handle, _ptr(slot_ids, torch.int32, ctx, 0 if slot_ids is None else batch, "slot_ids"),
                                 batch, trees._struct(ctx, batch), _stream(stream, ctx))
     _check(ctx, code)
 
 
 def sd_speculate_static(ctx: _Ctx, slot_ids: torch.Tensor, trees: Trees, stream=None) -> None:
     """sd_speculate with the library's static device array as working memory."""
-    batch = int(slot_ids.numel())
-    if batch > trees.batch:
-        raise ValueError("trees hold %d requests, batch is %d" % (trees.batch, batch))
-    code = _load().sd_speculate_static(ctx.handle, _ptr(slot_ids, torch.int32, ctx, batch, "slot_ids"),
+    batch = _batch_of(slot_ids, trees)
+    code = _load().sd_speculate_static(ctx.handle, _ptr(slot_ids, torch.int32, ctx, 0 if slot_ids is None else batch, "slot_ids"),
                                        batch, trees._struct(ctx, batch), _stream(stream, ctx))
     _check(ctx, code)
 
@@ -294,9 +299,9 @@ def sd_accept_append(ctx: _Ctx, trees: Trees, slot_ids: torch.Tensor, target_tok
     """sd_accept plus sd_index_append of the accepted tokens and the bonus token, one launch."""
     i32 = torch.int32
     mn = trees.max_nodes
-    batch = int(slot_ids.numel())
+    batch = _batch_of(slot_ids, trees)
     code = _load().sd_accept_append(ctx.handle, trees._struct(ctx, batch),
-                                    _ptr(slot_ids, i32, ctx, batch, "slot_ids"), batch,
+                                    _ptr(slot_ids, i32, ctx, 0 if slot_ids is None else batch, "slot_ids"), batch,
                                     _ptr(target_tokens, i32, ctx, batch * (mn + 1), "target_tokens"),
                                     _ptr(accept_len, i32, ctx, batch, "accept_len"),
                                     _ptr(accept_path, i32, ctx, batch * mn, "accept_path"),
@@ -311,9 +316,10 @@ def sd_accept_append_speculate(ctx: _Ctx, trees: Trees, slot_ids: torch.Tensor,
     `trees`, one launch."""
     i32 = torch.int32
     mn = trees.max_nodes
-    batch = int(slot_ids.numel())
+    batch = _batch_of(slot_ids, trees)
     code = _load().sd_accept_append_speculate(
-        ctx.handle, trees._struct(ctx, batch), _ptr(slot_ids, i32, ctx, batch, "slot_ids"), batch,
+        ctx.handle, trees._struct(ctx, batch),
+        _ptr(slot_ids, i32, ctx, 0 if slot_ids is None else batch, "slot_ids"), batch,
         _ptr(target_tokens, i32, ctx, batch * (mn + 1), "target_tokens"),
         _ptr(accept_len, i32, ctx, batch, "accept_len"),
         _ptr(accept_path, i32, ctx, batch * mn, "accept_path"),

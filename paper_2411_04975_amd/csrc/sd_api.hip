@@ -162,7 +162,6 @@ sd_status sd_index_build(sd_ctx *c, sd_scope scope, const int32_t *d_slot_ids,
         return sd_build_global_impl(c, d_tokens, d_seq_offsets, n_seq, n_tokens, st);
     }
     if (scope == SD_SCOPE_REQUESTS) {
-        if (n_seq > 0 && !d_slot_ids) return fail(c, SD_ERR_INVALID_ARG, "d_slot_ids is null");
         if (n_seq > c->cfg.max_batch_slots)
             return fail(c, SD_ERR_CAPACITY, "more sequences than request slots");
         return sd_build_requests_impl(c, d_slot_ids, d_tokens, d_seq_offsets, n_seq, st);
@@ -197,7 +196,7 @@ sd_status sd_index_append(sd_ctx *c, const int32_t *d_slot_ids, const int32_t *d
     if (n_slots < 0) return fail(c, SD_ERR_INVALID_ARG, "negative size");
     if (n_slots > c->cfg.max_batch_slots)
         return fail(c, SD_ERR_CAPACITY, "more slots than configured");
-    if (n_slots > 0 && (!d_slot_ids || !d_new_offsets || !d_new_tokens))
+    if (n_slots > 0 && (!d_new_offsets || !d_new_tokens))
         return fail(c, SD_ERR_INVALID_ARG, "null pointer");
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
     return sd_append_impl(c, d_slot_ids, d_new_tokens, d_new_offsets, n_slots,
@@ -216,7 +215,7 @@ sd_status sd_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_t
     if (batch > c->cfg.max_batch_slots)
         return fail(c, SD_ERR_CAPACITY, "batch exceeds max_batch_slots");
     if (batch == 0) return SD_OK;
-    if (!d_slot_ids || !trees_ok(out)) return fail(c, SD_ERR_INVALID_ARG, "null pointer");
+    if (!trees_ok(out)) return fail(c, SD_ERR_INVALID_ARG, "null pointer");
     if (out.max_nodes < c->max_nodes)
         return fail(c, SD_ERR_INVALID_ARG, "trees.max_nodes below floor(alpha*P)");
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
@@ -233,7 +232,7 @@ sd_status sd_speculate_static(sd_ctx *c, const int32_t *d_slot_ids, int32_t batc
         return fail(c, SD_ERR_CAPACITY,
                     "batch * max_ctx_tokens * 12 bytes exceeds SD_STATIC_SCRATCH_BYTES");
     if (batch == 0) return SD_OK;
-    if (!d_slot_ids || !trees_ok(out)) return fail(c, SD_ERR_INVALID_ARG, "null pointer");
+    if (!trees_ok(out)) return fail(c, SD_ERR_INVALID_ARG, "null pointer");
     if (out.max_nodes < c->max_nodes)
         return fail(c, SD_ERR_INVALID_ARG, "trees.max_nodes below floor(alpha*P)");
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
@@ -265,7 +264,7 @@ sd_status sd_accept_append(sd_ctx *c, sd_trees trees, const int32_t *d_slot_ids,
     if (batch > c->cfg.max_batch_slots) return fail(c, SD_ERR_CAPACITY, "more slots than configured");
     if (batch == 0) return SD_OK;
     if (!trees.d_n_nodes || !trees.d_tokens || !trees.d_parents || trees.max_nodes < 1 ||
-        !d_slot_ids || !d_target_tokens || !d_accept_len || !d_accept_path || !d_bonus)
+        !d_target_tokens || !d_accept_len || !d_accept_path || !d_bonus)
         return fail(c, SD_ERR_INVALID_ARG, "null pointer");
     if (trees.max_nodes > 256) return fail(c, SD_ERR_INVALID_ARG, "trees.max_nodes above 256");
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
@@ -281,7 +280,7 @@ sd_status sd_accept_append_speculate(sd_ctx *c, sd_trees trees, const int32_t *d
     if (batch < 0) return fail(c, SD_ERR_INVALID_ARG, "negative batch");
     if (batch > c->cfg.max_batch_slots) return fail(c, SD_ERR_CAPACITY, "more slots than configured");
     if (batch == 0) return SD_OK;
-    if (!d_slot_ids || !trees_ok(trees) || !d_target_tokens || !d_accept_len || !d_accept_path ||
+    if (!trees_ok(trees) || !d_target_tokens || !d_accept_len || !d_accept_path ||
         !d_bonus)
         return fail(c, SD_ERR_INVALID_ARG, "null pointer");
     if (trees.max_nodes < c->max_nodes)

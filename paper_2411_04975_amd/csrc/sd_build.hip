@@ -325,7 +325,7 @@ __global__ __launch_bounds__(TB) void k_req_build(const int32_t *__restrict__ sl
                                                   int32_t max_ctx, int32_t max_slots, int32_t vocab,
                                                   int32_t *err) {
     const int s = blockIdx.x;
-    const int32_t slot = slot_ids[s];
+    const int32_t slot = slot_ids ? slot_ids[s] : s;  // no ids given: sequence s is slot s
     if (slot < 0 || slot >= max_slots) {
         if (threadIdx.x == 0) atomicOr(&err[SD_DEVERR_SLOT], 1);
         return;
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(64) void k_req_append(const int32_t *__restrict__ s
                                                    int32_t max_ctx, int32_t max_slots, int32_t vocab,
                                                    int32_t *err) {
     const int s = blockIdx.x;
-    const int32_t slot = slot_ids[s];
+    const int32_t slot = slot_ids ? slot_ids[s] : s;
     if (slot < 0 || slot >= max_slots) {
         if (threadIdx.x == 0) atomicOr(&err[SD_DEVERR_SLOT], 1);
         return;

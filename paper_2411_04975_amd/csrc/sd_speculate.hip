@@ -311,8 +311,8 @@ __device__ __forceinline__ void occ_scan_issue(int t_old, const int32_t *__restr
 template <bool STATS, class Between>
 __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, int t, int t_old,
                                     const int32_t *newtok, const int32_t *__restrict__ x,
-                                    int2 *s_sort, WgShared &sh, ScanState &st, unsigned &nb,
-                                    Between between) {
+                                    int2 *s_sort, WgShared &sh, ScanState &st, int32_t tail,
+                                    unsigned &nb, Between between) {
     const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
     int2 *occ = p.occ + (int64_t)b * p.max_ctx;
     const int4 *x4 = reinterpret_cast<const int4 *>(x);
@@ -395,8 +395,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
         while ((1 << pplog) < p.P) pplog++;
         const int PP = 1 << pplog, G = 64 >> pplog, g = lane >> pplog, k = lane & (PP - 1);
         const uint64_t gmask = PP >= 64 ? ~0ull : ((1ull << PP) - 1ull);
-        int32_t tl = 0;
-        if (k < p.P && k < t) tl = x[t - 1 - k];
+        const int32_t tl = __shfl(tail, k);  // the k-th token from the context's end (0 beyond it)
         constexpr int U = 4;
         for (int i0 = wave * G * U; i0 < m; i0 += nw * G * U) {
             int e[U];
@@ -1695,7 +1694,6 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
     const int K = (int)floor(p.alpha * (double)pl);
     uint32_t tick_setup = 0, tick_match = 0, tick_root = 0;
     sg.lo = 0; sg.m = 0; sg.wlog = 0;
-    if (TICKS) tick_setup = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(t & 0);
 
     const int32_t *sa = nullptr, *text = nullptr;
     int32_t lo = 0, hi = 0;
@@ -1798,10 +1796,13 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
                 }
             }
             const int ntop = tk0.ntop;
-            if (ntop >= 2 && !p.linear &&
-                tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok, t_par, t_score,
-                                   deepest, nb))
-                continue;
+            if (ntop >= 2 && !p.linear) {
+                const uint64_t m0 = TICKS ? wall_clock64() : 0;
+                const bool merged = tied_chains<STATS>(f, sg, text, best.s, K, p.D, n, total, t_tok,
+                                                       t_par, t_score, deepest, nb);
+                if (TICKS) tick_setup += (uint32_t)(wall_clock64() - m0);  // time spent merging
+                if (merged) continue;
+            }
             const int bi = best.idx;
             const int32_t blo = tk0.lo, bhi = tk0.hi;
             int32_t d = tk0.dep;
@@ -1852,7 +1853,7 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
         }
     }
     wsync();
-    if (TICKS && lane == 0) {  // phase marks: set-up, match, root children, whole unit
+    if (TICKS && lane == 0) {  // time spent merging tied chains; marks: match, root children, whole unit
         p.unit_ticks[uidx * 4 + 0] = tick_setup;
         p.unit_ticks[uidx * 4 + 1] = tick_match;
         p.unit_ticks[uidx * 4 + 2] = tick_root;
@@ -1964,7 +1965,7 @@ __device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_
     bool slot_ok = false;
     if (APPEND) {  // L accepted tokens and the bonus token go behind the slot's context
         // (a caller that has looked up the slot and its length already passes them in)
-        const int32_t slot = known_slot != -2 ? known_slot : ap.slot_ids[b];
+        const int32_t slot = known_slot != -2 ? known_slot : (ap.slot_ids ? ap.slot_ids[b] : b);
         if (slot < 0 || slot >= ap.max_slots) {
             if (lane == 0) atomicOr(&ap.err[SD_DEVERR_SLOT], 1);
         } else {
@@ -2058,7 +2059,9 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
     const int lane = threadIdx.x & 63, wave = uni((int32_t)(threadIdx.x >> 6)), nw = blockDim.x >> 6;
     const int b = blockIdx.x;
     unsigned nb = 0;
-    const int32_t slot = uni(slot_ids[b]);
+    // (no slot ids given: request b is slot b, and the chain of dependent loads that every
+    // request starts with is one load shorter)
+    const int32_t slot = slot_ids ? uni(slot_ids[b]) : b;
     const bool slot_ok = slot >= 0 && slot < p.max_slots;
     if (!slot_ok && threadIdx.x == 0) atomicOr(&p.err[SD_DEVERR_SLOT], 1);
     // the context length before this launch appends anything
@@ -2085,14 +2088,18 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
     if (wave == nw - 1 && lane < SD_CTR_ACCEPT_REQUESTS)
         ctr_old = p.counters[(int64_t)b * SD_CTR_STRIDE + lane];
     int t = t_old;
-    // lane k: pattern token k of the wave's first two pattern lengths
+    // lane k < P: the k-th token from the context's end.  Loaded now for the context as it
+    // stands; the fused form puts the tokens it appends in front afterwards, from LDS, so
+    // that nothing has to be read back from the row once the acceptance is settled.
+    int32_t tail = 0;
+    if (lane < P && lane < t_old) tail = x[t_old - 1 - lane];
+    // lane k: pattern token k of the wave's first two pattern lengths (taken from the tail)
     int32_t wkA0 = 0, wkB0 = 0;
-    int32_t tail = 0;  // lane k < P: the k-th token from the context's end
     auto pattern_tokens = [&]() {
         const int plA = 1 + wave, plB = plA + nw;
-        if (plA <= P && plA <= t && p.g_N > 0 && lane < plA) wkA0 = x[t - plA + lane];
-        if (plB <= P && plB <= t && p.g_N > 0 && lane < plB) wkB0 = x[t - plB + lane];
-        if (p.g_N > 0 && lane < P && lane < t) tail = x[t - 1 - lane];
+        const int32_t a = __shfl(tail, (plA - 1 - lane) & 63), bb = __shfl(tail, (plB - 1 - lane) & 63);
+        if (plA <= P && plA <= t && lane < plA) wkA0 = a;
+        if (plB <= P && plB <= t && lane < plB) wkB0 = bb;
     };
     if (ACCEPT) {
         if (wave == 0) {
@@ -2108,12 +2115,17 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         // compute unit and its cache, and only this workgroup touches the row.
         __syncthreads();
         t = slot_ok ? uni(sh.t_new) : 0;
+        {   // the appended tokens come first in the tail, the old tail moves back
+            const int n_new = t - t_old;  // (0 for a bad slot or an append that did not fit)
+            const int32_t moved = __shfl(tail, (lane - n_new) & 63);
+            if (n_new > 0) tail = lane < P && lane < t ? (lane < n_new ? sh.newtok[n_new - 1 - lane] : moved) : 0;
+        }
         pattern_tokens();
     } else {
         pattern_tokens();
         __syncthreads();  // the counters of the occurrence list are set
     }
-    request_occurrences<STATS>(p, b, t, t_old, sh.newtok, x, s_sort, sh, scan, nb, [&]() {
+    request_occurrences<STATS>(p, b, t, t_old, sh.newtok, x, s_sort, sh, scan, tail, nb, [&]() {
         // List form: the suffixes that start with the context's last two tokens are located
         // once (every wave does that for itself: same loads, no barrier).  If there are at
         // most 64 of them, every longer pattern's occurrences are among them: the waves share

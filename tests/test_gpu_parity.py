@@ -122,6 +122,59 @@ def test_non_identity_slots_and_partial_batch(tiny_workload):
 
 
 
+def test_null_slot_ids_mean_the_identity(tiny_workload):
+    """Every call that takes slot ids accepts NULL for "request i is slot i": builds, appends,
+    drafts and fused steps made that way give what the same calls with the ids 0, 1, 2, ...
+    give."""
+    import torch
+    import paper_2411_04975_amd as sd
+    w = tiny_workload
+    docs = w.docs()
+    B, mn = w.batch, w.max_nodes
+    contexts = [w.contexts[b] for b in range(B)]
+    rng = np.random.default_rng(17)
+    results = []
+    for explicit in (True, False):
+        g = parity.GpuPath(w.vocab, w.D, w.P, w.alpha, w.min_score, B, w.ctx_len + 4 * (mn + 1),
+                           len(w.corpus) + len(docs))
+        try:
+            ids = torch.arange(B, dtype=torch.int32, device=g.dev) if explicit else None
+            g.build_global(docs)
+            d_tok, d_off, n = g._seqs(contexts)
+            sd.sd_index_build(g.ctx, sd.SD_SCOPE_REQUESTS, ids, d_tok, d_off, n)
+            new = [w.future[b, :1 + b % 3] for b in range(B)]
+            d_new, d_noff, _ = g._seqs(new)
+            sd.sd_index_append(g.ctx, ids, d_new, d_noff.to(torch.int32))
+            tr = g._trees(B, mn)
+            sd.sd_speculate(g.ctx, ids, tr)
+            torch.cuda.synchronize()
+            first = {k: getattr(tr, k).cpu().numpy().copy() for k in ("n_nodes", "tokens", "parents", "scores")}
+            tgt = parity.targets_from_future(first, w.future[:, 3:], mn)
+            d_t = torch.from_numpy(tgt).to(g.dev)
+            al, ap, bo = g._accept_outputs(B, mn)
+            sd.sd_accept_append_speculate(g.ctx, tr, ids, d_t, al, ap, bo)
+            torch.cuda.synchronize()
+            g.check_guards()
+            al2, ap2, bo2 = g._accept_outputs(B, mn)
+            sd.sd_accept_append(g.ctx, tr, ids, d_t, al2, ap2, bo2)
+            torch.cuda.synchronize()
+            g.check_guards()
+            tr3 = g._trees(B, mn)
+            sd.sd_speculate_static(g.ctx, ids, tr3)
+            torch.cuda.synchronize()
+            st = g.stats()
+            assert st["err_bad_slot"] == 0 and st["err_bad_token"] == 0 and st["err_ctx_overflow"] == 0
+            results.append([first["n_nodes"], first["tokens"], first["parents"], first["scores"],
+                            al.cpu().numpy(), bo.cpu().numpy(), tr.tokens.cpu().numpy(),
+                            tr.n_nodes.cpu().numpy(), al2.cpu().numpy(), tr3.tokens.cpu().numpy(),
+                            tr3.parents.cpu().numpy(), tr3.scores.cpu().numpy()])
+        finally:
+            g.close()
+    for a_, b_ in zip(*results):
+        assert np.array_equal(a_, b_)
+    assert results[0][0].sum() > 0 and results[0][7].sum() > 0
+
+
 def _more_minis():
     """Cases aimed at the chain merge (token ties, more chains than one call merges, chains
     longer than one window), at the depth bound inside runs of equal counts, and at the

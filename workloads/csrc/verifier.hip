@@ -102,9 +102,30 @@ __global__ __launch_bounds__(256) void k_stream_copy(const int4 *__restrict__ sr
         dst[i] = src[i];
 }
 
+// Dependent loads, one after the other, by a single lane: next[i] names the entry to read
+// after entry i (entries 32 words apart: one memory line each).  The time per hop is the latency
+// of a load whose address comes from the load before it, from whatever level of the memory
+// system holds a working set of that size: the cost unit of the drafting kernel's probe chains.
+__global__ __launch_bounds__(64) void k_chase(const uint32_t *__restrict__ next, uint32_t start,
+                                              int hops, uint32_t *__restrict__ out) {
+    if (threadIdx.x != 0) return;
+    uint32_t i = start;
+    for (int h = 0; h < hops; h++) i = __builtin_nontemporal_load(next + (size_t)i * 32);
+    out[0] = i;
+}
+
 }  // namespace
 
 extern "C" {
+
+// follows d_next (uint32, one entry per 32 words, values are entry numbers) for `hops` loads
+// from entry `start` on one lane; *d_out receives the last entry reached
+int wl_chase(const void *d_next, uint32_t start, int hops, void *d_out, void *stream) {
+    if (hops <= 0) return 0;
+    hipLaunchKernelGGL(k_chase, dim3(1), dim3(64), 0, (hipStream_t)stream, (const uint32_t *)d_next,
+                       start, hops, (uint32_t *)d_out);
+    return hipGetLastError() == hipSuccess ? 0 : 1;
+}
 
 // copies n_bytes (a multiple of 16, both pointers 16-byte aligned) from d_src to d_dst
 int wl_stream_copy(const void *d_src, void *d_dst, int64_t n_bytes, void *stream) {

@@ -40,6 +40,8 @@ def _load():
         L.wl_collect.argtypes = [vp, C.c_int, vp, vp, vp, C.c_int, vp, vp, vp, vp]
         L.wl_stream_copy.restype = C.c_int
         L.wl_stream_copy.argtypes = [vp, vp, C.c_int64, vp]
+        L.wl_chase.restype = C.c_int
+        L.wl_chase.argtypes = [vp, C.c_uint32, C.c_int, vp, vp]
         _lib = L
     return _lib
 
@@ -81,3 +83,34 @@ def stream_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
     rc = _load().wl_stream_copy(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), nbytes,
                                 C.c_void_p(st))
     assert rc == 0, rc
+
+
+def dependent_load_ns(n_lines: int, hops: int, device) -> float:
+    """Nanoseconds per load when every load's address comes from the load before it, over a
+    working set of n_lines memory lines (128 bytes apart) visited in a seeded random cyclic
+    order by one lane.  Every timed walk starts where no walk has been before (or, in a
+    working set smaller than the walk, goes round the cycle), so the level of the memory
+    system that answers is the one that holds the whole set.  Measurement glue: nothing of the
+    method is in it."""
+    g = torch.Generator(device="cpu")
+    g.manual_seed(1234)
+    perm = torch.randperm(n_lines, generator=g, dtype=torch.int64)
+    nxt = torch.empty(n_lines, dtype=torch.int64)
+    nxt[perm] = torch.roll(perm, -1)
+    table = torch.zeros(n_lines * 32, dtype=torch.int32, device=device)
+    table[::32] = nxt.to(torch.int32).to(device)
+    out = torch.zeros(1, dtype=torch.int32, device=device)
+    st = torch.cuda.current_stream(device).cuda_stream
+    L = _load()
+    times = []
+    for rep in range(4):                       # the first walk also loads the kernel
+        start = int(perm[(rep * hops) % n_lines])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        rc = L.wl_chase(C.c_void_p(table.data_ptr()), start, hops, C.c_void_p(out.data_ptr()),
+                        C.c_void_p(st))
+        e1.record()
+        torch.cuda.synchronize()
+        assert rc == 0
+        times.append(e0.elapsed_time(e1))
+    return min(times[1:]) * 1e6 / hops
