@@ -39,6 +39,8 @@ struct SpecParams {
     int32_t D, P, max_nodes;
     int32_t den_mode, linear;
     int32_t occ_cap;  // occurrence records (with their keys) that fit the workgroup's LDS
+    int32_t key_bits; // bits of a token code (0 .. vocab) inside an occurrence's sort key
+    int32_t key_toks; // tokens after an occurrence that its sort key holds: 3 if they fit, else 2
     double alpha, min_score, tau;
     int2 *occ;
     int32_t *unit_sa;
@@ -151,48 +153,129 @@ __device__ __forceinline__ void occ_sort(int2 *arr, uint64_t *key, int m, const 
     }
 }
 
-// The same network with one element per thread, held in registers (n2, the list's length rounded
-// up to a power of two, is at most the workgroup's size; elements beyond the list carry the
-// key ~0 and sink to the end).  A step whose partner sits in the same wave is three lane
-// permutes and a compare; only the steps that cross waves (partner distance 64 and up) go
-// through LDS, with two barriers each: ten of the 55 steps for 1024 elements.  Both partners
-// evaluate the same ordered pair (the lower place's element against the upper place's), so
-// they agree on the outcome.  Every thread of the workgroup calls this (barriers inside).
+// Sort key of an occurrence record (end position, left-extension): see request_occurrences.
 template <bool STATS>
-__device__ __forceinline__ int2 occ_sort_regs(int2 rec, uint64_t key, int n2, int2 *s_rec, uint64_t *s_key,
-                                              const int32_t *__restrict__ x, int depth, unsigned &nb) {
-    const int i = threadIdx.x, lane = i & 63;
-    const bool on = i < n2;
-    for (int k = 2; k <= n2; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            const int xr = j == (k >> 1) ? k - 1 : j;  // the partner's place is i ^ xr
-            int2 orec = rec;
-            uint64_t okey = key;
-            if (xr < 64) {
-                const int src = lane ^ xr;
+__device__ __forceinline__ uint64_t occ_key(const SpecParams &p, const int32_t *__restrict__ x, int2 rec,
+                                            int depth, unsigned &nb) {
+    const int kt = p.key_toks < depth ? p.key_toks : depth;  // (a path of D tokens ends the compare)
+    const uint64_t t1 = (uint64_t)(uint32_t)(x[rec.x + 1] + 1);
+    const uint64_t t2 = kt >= 2 ? (uint64_t)(uint32_t)(x[rec.x + 2] + 1) : 0ull;
+    const uint64_t t3 = kt >= 3 ? (uint64_t)(uint32_t)(x[rec.x + 3] + 1) : 0ull;
+    SD_CNT(4 * kt);
+    const uint64_t more = floor(p.alpha * (double)rec.y) > (double)p.key_toks ? 1ull : 0ull;
+    const int kb = p.key_bits;
+    return p.key_toks == 3 ? (t1 << (2 * kb + 1)) | (t2 << (kb + 1)) | (t3 << 1) | more
+                           : (t1 << (kb + 1)) | (t2 << 1) | more;
+}
+
+// Sort of up to one element per thread (m is at most the workgroup's size; threads without an
+// element pass the key ~0).  Every wave first orders its own 64 elements with a bitonic network
+// whose partners are reached by lane permutes, and leaves the keys as a sorted run in LDS; an
+// element's final place is then its place in its own run plus, for every other run, the number
+// of that run's keys that go before it, found by a binary search in the run (among equal keys
+// of different runs the earlier run goes first).  That is some 250 instructions and 50 LDS
+// reads per element, all waves at work, where a network over the whole list takes 55 steps
+// with ten of them across waves (18 us for the 550 occurrences of a frequent token), and
+// counting the keys that go before an element one by one is bound by LDS bandwidth (13 us).
+// Equal keys whose low bit is set must be ordered by the tokens beyond the key: such groups
+// (rare: the key holds three tokens) lie side by side after the placement and are put in order
+// by token-by-token compares in memory.  s_rec receives the sorted records; s_key and *s_flag
+// are scratch.  Every thread of the workgroup calls this (barriers inside).
+template <bool STATS>
+__device__ __forceinline__ void occ_sort_runs(int2 rec, uint64_t key, int m, int2 *s_rec, uint64_t *s_key,
+                                              int *s_flag, const int32_t *__restrict__ x, int depth,
+                                              unsigned &nb) {
+    const int i = threadIdx.x, lane = i & 63, w0 = i & ~63;  // w0: where this wave's run starts
+    const bool busy = w0 < m;                                // (the same for all lanes of a wave)
+    if (m <= 64) {
+        // One run (the usual case where contexts hardly repeat their last token): the first
+        // wave's network is the whole sort, equal keys are settled inside it, and nobody waits
+        // at a barrier.
+        if (busy) {
+            int n2 = 1;  // the network's size: elements beyond the list carry the key ~0
+            while (n2 < m) n2 <<= 1;
+            for (int k = 2; k <= n2; k <<= 1) {
+                for (int j = k >> 1; j > 0; j >>= 1) {
+                    const int src = lane ^ (j == (k >> 1) ? k - 1 : j);
+                    int2 orec;
+                    orec.x = __shfl(rec.x, src);
+                    orec.y = __shfl(rec.y, src);
+                    const uint32_t klo = (uint32_t)__shfl((int)(uint32_t)key, src);
+                    const uint32_t khi = (uint32_t)__shfl((int)(uint32_t)(key >> 32), src);
+                    const uint64_t okey = ((uint64_t)khi << 32) | klo;
+                    const bool lower = src > lane;  // a: the lower place's element
+                    const int2 a = lower ? rec : orec, b = lower ? orec : rec;
+                    const uint64_t ka = lower ? key : okey, kb = lower ? okey : key;
+                    bool swap;
+                    if (ka != kb) swap = kb < ka;
+                    else swap = ((ka & 1) && ka != ~0ull) ? occ_less<STATS>(x, b, a, depth, nb) : false;
+                    if (swap) { rec = orec; key = okey; }
+                }
+            }
+            if (lane < m) s_rec[lane] = rec;
+        }
+        return;
+    }
+    if (busy) {
+        for (int k = 2; k <= 64; k <<= 1) {
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                const int src = lane ^ (j == (k >> 1) ? k - 1 : j);
+                int2 orec;
                 orec.x = __shfl(rec.x, src);
                 orec.y = __shfl(rec.y, src);
                 const uint32_t klo = (uint32_t)__shfl((int)(uint32_t)key, src);
                 const uint32_t khi = (uint32_t)__shfl((int)(uint32_t)(key >> 32), src);
-                okey = ((uint64_t)khi << 32) | klo;
-            } else {
-                if (on) { s_rec[i] = rec; s_key[i] = key; }
-                __syncthreads();
-                if (on) { orec = s_rec[i ^ xr]; okey = s_key[i ^ xr]; }
-                __syncthreads();
-            }
-            if (on) {
-                const bool lower = (i ^ xr) > i;
-                const int2 a = lower ? rec : orec, b = lower ? orec : rec;  // a: lower place
-                const uint64_t ka = lower ? key : okey, kb = lower ? okey : key;
-                bool swap;
-                if (ka != kb) swap = kb < ka;
-                else swap = ((ka & 1) && ka != ~0ull) ? occ_less<STATS>(x, b, a, depth, nb) : false;
-                if (swap) { rec = orec; key = okey; }
+                const uint64_t okey = ((uint64_t)khi << 32) | klo;
+                // both partners look at the same ordered pair: the lower place keeps the lower key
+                const bool take = src > lane ? okey < key : key < okey;
+                if (take) { rec = orec; key = okey; }
             }
         }
+        s_key[i] = key;
     }
-    return rec;
+    if (i == 0) *s_flag = 0;
+    __syncthreads();
+    int place = lane;
+    if (busy) {
+        const int nruns = (m + 63) >> 6;
+#pragma unroll 2
+        for (int r = 0; r < nruns; r++) {
+            if (r * 64 == w0) continue;
+            const uint64_t *run = s_key + r * 64;
+            const bool first = r * 64 < w0;  // an earlier run: its equal keys go before mine
+            int pos = 0;
+#pragma unroll
+            for (int step = 32; step > 0; step >>= 1) {
+                const uint64_t kq = run[pos + step - 1];
+                pos += (first ? kq <= key : kq < key) ? step : 0;
+            }
+            const uint64_t kq = run[pos];
+            place += pos + ((first ? kq <= key : kq < key) ? 1 : 0);
+        }
+    }
+    __syncthreads();  // all keys have been read
+    const bool mine = busy && key != ~0ull;
+    if (mine) { s_rec[place] = rec; s_key[place] = key; }
+    __syncthreads();
+    bool tie = false;
+    if (mine && (key & 1))
+        tie = (place > 0 && s_key[place - 1] == key) || (place + 1 < m && s_key[place + 1] == key);
+    if (tie) *s_flag = 1;
+    __syncthreads();
+    if (*s_flag) {
+        int np = place;
+        if (tie) {
+            int g0 = place, g1 = place + 1;
+            while (g0 > 0 && s_key[g0 - 1] == key) g0--;
+            while (g1 < m && s_key[g1] == key) g1++;
+            np = g0;
+            for (int q = g0; q < g1; q++)
+                if (q != place) np += occ_less<STATS>(x, s_rec[q], rec, depth, nb) ? 1 : 0;
+        }
+        __syncthreads();
+        if (tie) s_rec[np] = rec;
+        __syncthreads();
+    }
 }
 
 // Wave-wide maximum in every lane.  Inside a row of 16 lanes the values meet through four
@@ -259,6 +342,7 @@ __device__ __forceinline__ int32_t wave_inclusive_sum(int32_t v) {
 struct WgShared {
     int m;           // occurrences of the context's last token
     int next;        // head of the unit queue
+    int sort_flag;   // scratch of the occurrence sort
     unsigned long long top_bits;  // highest SCORE of a finished tree so far (bits of the double)
     int t_new;       // context length after the append of the fused form
     int newtok[260]; // fused form: the tokens appended in this launch
@@ -442,39 +526,29 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
         const int depth = p.D - 1;
         if (in_lds) {
             if (m > 1) {
-                // Sort key: the two tokens after the occurrence, end marker lowest (rows are
-                // padded with end markers, and only a pattern's own tail is followed by one), then
-                // one bit that says whether the occurrence can ever be asked for more.  An
-                // occurrence with left-extension L belongs to the lists of the patterns p <= L,
-                // whose trees have at most floor(alpha p) <= floor(alpha L) nodes and therefore
-                // look at no token further than that many places behind it.  Where that is two
-                // or less the key is the whole order; such occurrences come before the others
-                // of the same key, which are ordered among themselves by the tokens beyond.
+                // Sort key: the three tokens after the occurrence (two if three codes do not fit
+                // 63 bits), end marker lowest (rows are padded with end markers, and only a
+                // pattern's own tail is followed by one), then one bit that says whether the
+                // occurrence can ever be asked for more.  An occurrence with left-extension L
+                // belongs to the lists of the patterns p <= L, whose trees have at most
+                // floor(alpha p) <= floor(alpha L) nodes and therefore look at no token further
+                // than that many places behind it.  Where that is no more than the key holds,
+                // the key is the whole order; such occurrences come before the others of the
+                // same key, which are ordered among themselves by the tokens beyond.  (With two
+                // tokens per key the sort of 550 occurrences of a frequent token took 18 us on
+                // the low-repetition workload: every step of the network in which some pair of
+                // a wave has equal keys waits for that pair's token-by-token compare in memory.)
                 uint64_t *key = reinterpret_cast<uint64_t *>(s_sort + occ_cap);
-                int n2 = 1;
-                while (n2 < m) n2 <<= 1;
-                if (n2 <= nthr) {  // one element per thread: sorted in registers
+                if (m <= nthr) {  // one element per thread
                     int2 rec = make_int2(0, 0);
                     uint64_t kk = ~0ull;
                     if (tid < m) {
                         rec = s_sort[tid];
-                        const uint32_t t1 = (uint32_t)(x[rec.x + 1] + 1);
-                        const uint32_t t2 = depth >= 2 ? (uint32_t)(x[rec.x + 2] + 1) : 0u;
-                        const uint64_t more = floor(p.alpha * (double)rec.y) > 2.0 ? 1u : 0u;
-                        kk = ((uint64_t)t1 << 33) | ((uint64_t)t2 << 1) | more;
-                        SD_CNT(8);
+                        kk = occ_key<STATS>(p, x, rec, depth, nb);
                     }
-                    rec = occ_sort_regs<STATS>(rec, kk, n2, s_sort, key, x, depth, nb);
-                    if (tid < m) s_sort[tid] = rec;
+                    occ_sort_runs<STATS>(rec, kk, m, s_sort, key, &sh.sort_flag, x, depth, nb);
                 } else {
-                    for (int i = tid; i < m; i += nthr) {
-                        const int e = s_sort[i].x;
-                        const uint32_t t1 = (uint32_t)(x[e + 1] + 1);
-                        const uint32_t t2 = depth >= 2 ? (uint32_t)(x[e + 2] + 1) : 0u;
-                        const uint64_t more = floor(p.alpha * (double)s_sort[i].y) > 2.0 ? 1u : 0u;
-                        key[i] = ((uint64_t)t1 << 33) | ((uint64_t)t2 << 1) | more;
-                        SD_CNT(8);
-                    }
+                    for (int i = tid; i < m; i += nthr) key[i] = occ_key<STATS>(p, x, s_sort[i], depth, nb);
                     __syncthreads();
                     occ_sort<STATS>(s_sort, key, m, x, depth, nb);
                 }
@@ -2481,6 +2555,8 @@ sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, 
     p.alpha = c->cfg.alpha; p.min_score = c->cfg.min_score; p.tau = c->cfg.tau;
     p.den_mode = c->cfg.den_mode; p.linear = c->cfg.linear;
     p.occ = occ ? occ : c->s_occ; p.unit_sa = unit_sa ? unit_sa : c->s_unit_sa;
+    p.key_bits = sd_bits_for((uint64_t)c->cfg.vocab);  // codes 0 .. vocab
+    p.key_toks = 3 * p.key_bits + 1 <= 64 ? 3 : 2;
     p.err = c->d_err;
     p.counters = c->d_counters;
     p.algo_bytes = c->d_algo_bytes;
