@@ -467,7 +467,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
     const int m = sh.m;
     // A single occurrence is the context's own last token: nothing follows it, so no pattern
     // has a continuation in this index, and the counts stay at zero, which says just that.
-    if (m <= 1) return;
+    if (__builtin_expect(m <= 1, 1)) return;
     const bool in_lds = m <= occ_cap;
     // How far each occurrence extends to the left together with the context's own tail.  An
     // occurrence takes PP lanes (P rounded up to a power of two): lane k of them compares the
@@ -648,7 +648,7 @@ struct Taken {
 __device__ __forceinline__ Taken frontier_take(const Frontier &f) {
     const int lane = threadIdx.x & 63;
     Taken r;
-    if (f.n > 64) {  // more entries than lanes: the parts one by one
+    if (__builtin_expect(f.n > 64, 0)) {  // more entries than lanes: the parts one by one
         r.k = frontier_pick(f, true);
         r.lo = uni(f.lo[r.k.idx]); r.hi = uni(f.hi[r.k.idx]); r.dep = uni(f.dep[r.k.idx]);
         r.ntop = 0;
@@ -716,7 +716,7 @@ __device__ __forceinline__ void frontier_put(Frontier &f, int hole, bool cand, d
     }
     const int nc = __popcll(C);
     const int stay = f.n - (hole >= 0 ? 1 : 0);
-    if (stay + nc <= f.cap) {
+    if (__builtin_expect(stay + nc <= f.cap, 1)) {
         if (cand) {
             int j = __popcll(C & lanemask_lt());
             int s = hole >= 0 ? (j == 0 ? hole : f.n + j - 1) : f.n + j;
@@ -848,7 +848,7 @@ __device__ __forceinline__ void push_children(Frontier &f, int hole, Stage &sg, 
     }
     const int lane = threadIdx.x & 63;
     const int32_t m = hi - lo;
-    if (m <= 64) {
+    if (__builtin_expect(m <= 64, 1)) {
         const bool in = lane < m;
         const int mycb = stage_node(sg, sa, text, lo, m, d);
         int32_t tok = 0x7fffffff;
@@ -2218,7 +2218,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
             const bool reach = hi2 - lo2 <= SAMPLED_MAX;
             if (reach && lo2 < hi2) col_stage<STATS>(p, w_last, lo2, hi2, nb);
             const int n2 = hi2 > lo2 ? hi2 - lo2 : 0;
-            if (reach && n2 <= 64) {
+            if (__builtin_expect(reach && n2 <= 64, 1)) {
                 int pplog = 0;
                 while ((1 << pplog) < P) pplog++;
                 const int PP = 1 << pplog, G = 64 >> pplog, g = lane >> pplog, k = lane & (PP - 1);
@@ -2363,7 +2363,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         off = o;
     };
     int n_rounds = 1, my_round = 0;
-    if (wide_r) {
+    if (__builtin_expect(wide_r != 0, 0)) {
         int off_last;
         place(nruns - ng - 1, n_rounds, off_last);
         n_rounds++;
@@ -2388,7 +2388,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         if (g >= nruns) break;
         const int src = g >= ng ? 1 : 0;
         int usa_off = 0;
-        if (src && wide_r) {
+        if (__builtin_expect(src && wide_r, 0)) {
             int rnd;
             place(g - ng, rnd, usa_off);
             for (; my_round < rnd; my_round++) __syncthreads();
