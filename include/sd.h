@@ -79,7 +79,7 @@ typedef enum {
 
 /* Limits checked by sd_create: den_mode and linear in {0, 1}, tau >= 0, 1 <= P < D <= 255, P <= 64, alpha > 0,
  * 1 <= floor(alpha*P) <= 256, 0 <= min_score <= 1, 1 <= vocab <= 2^24,
- * max_batch_slots >= 1, max_ctx_tokens >= 1, 0 <= max_global_tokens (documents
+ * max_batch_slots >= 1, 1 <= max_ctx_tokens <= 2^25, 0 <= max_global_tokens (documents
  * included, each document costs one extra position) < 2^31 - 4096. */
 typedef struct {
     int32_t vocab;
@@ -217,11 +217,11 @@ sd_status sd_speculate(sd_ctx *ctx, const int32_t *d_slot_ids, int32_t batch, sd
 /* sd_speculate for callers that cannot allocate device memory or may not touch memory that
  * was allocated at run time (code under HIP graph capture in a process whose allocator is
  * frozen, tight serving loops, harnesses that forbid hipMalloc): the same kernel with the same
- * results, but its working memory (occurrence records and suffix lists, 12 bytes per request
+ * results, but its working memory (occurrence records and suffix lists, 8 bytes per request
  * of the call and token of max_ctx_tokens) is a static array of SD_STATIC_SCRATCH_BYTES inside
  * the library's device code instead of buffers of the context; the call itself allocates and
  * frees nothing.  SD_ERR_CAPACITY, with nothing enqueued, if
- * batch * max_ctx_tokens * 12 > SD_STATIC_SCRATCH_BYTES.  Each device holds one such array
+ * batch * max_ctx_tokens * 8 > SD_STATIC_SCRATCH_BYTES.  Each device holds one such array
  * for the life of the process, shared by every context on it: calls that overlap on one
  * device (two streams, two contexts) race; calls that follow each other on one stream do
  * not, and nothing in the array has to survive from one call to the next. */

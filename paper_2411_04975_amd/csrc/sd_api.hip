@@ -64,7 +64,7 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     if (cfg->max_batch_slots < 1 || cfg->max_ctx_tokens < 1 || cfg->max_global_tokens < 0 ||
         cfg->max_global_tokens >= (int64_t)2147483647 - 4096)
         return SD_ERR_INVALID_ARG;
-    if ((int64_t)cfg->max_ctx_tokens >= (int64_t)2147483647 - 4096) return SD_ERR_INVALID_ARG;
+    if (cfg->max_ctx_tokens > (1 << 25)) return SD_ERR_INVALID_ARG;  // occurrence records hold 25 bits of position
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) {
         (void)hipGetLastError();
@@ -228,9 +228,9 @@ sd_status sd_speculate_static(sd_ctx *c, const int32_t *d_slot_ids, int32_t batc
     if (batch < 0) return fail(c, SD_ERR_INVALID_ARG, "negative batch");
     if (batch > c->cfg.max_batch_slots)
         return fail(c, SD_ERR_CAPACITY, "batch exceeds max_batch_slots");
-    if ((int64_t)batch * c->cfg.max_ctx_tokens * 12 > (int64_t)SD_STATIC_SCRATCH_BYTES)
+    if ((int64_t)batch * c->cfg.max_ctx_tokens * 8 > (int64_t)SD_STATIC_SCRATCH_BYTES)
         return fail(c, SD_ERR_CAPACITY,
-                    "batch * max_ctx_tokens * 12 bytes exceeds SD_STATIC_SCRATCH_BYTES");
+                    "batch * max_ctx_tokens * 8 bytes exceeds SD_STATIC_SCRATCH_BYTES");
     if (batch == 0) return SD_OK;
     if (!trees_ok(out)) return fail(c, SD_ERR_INVALID_ARG, "null pointer");
     if (out.max_nodes < c->max_nodes)

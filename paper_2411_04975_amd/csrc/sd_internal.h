@@ -65,7 +65,7 @@ struct sd_ctx {
     int64_t r_stride = 0;
 
     // ---- speculate scratch (sized for max_batch_slots requests) -------
-    int2 *s_occ = nullptr;           // [B][max_ctx]: (end position e, common-suffix length L)
+    uint32_t *s_occ = nullptr;       // [B][max_ctx]: end position e << 7 | common-suffix length L
     int32_t *s_unit_sa = nullptr;    // [B][max_ctx]: per-request room for suffix lists of more
                                      // than 64 occurrences (shared by the pattern lengths)
     uint32_t *s_unit_ticks = nullptr;  // [B][2P][4], written by the counting kernel variants

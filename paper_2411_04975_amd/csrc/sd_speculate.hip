@@ -42,7 +42,7 @@ struct SpecParams {
     int32_t key_bits; // bits of a token code (0 .. vocab) inside an occurrence's sort key
     int32_t key_toks; // tokens after an occurrence that its sort key holds: 3 if they fit, else 2
     double alpha, min_score, tau;
-    int2 *occ;
+    uint32_t *occ;
     int32_t *unit_sa;
     int32_t *err;
     unsigned long long *counters;  // what sd_get_stats reports (SD_CTR_*)
@@ -93,6 +93,12 @@ __device__ __forceinline__ void wsync() {
 // ------------------------------------------------------------------------------------------
 constexpr int OCC_LDS_SORT = 2048;
 
+// An occurrence record (end position e, common-suffix length L <= P <= 64) as it is kept in the
+// request's row of scratch memory: one word, L in the low seven bits (sd_create bounds
+// max_ctx_tokens by 2^25).  In registers and in LDS a record is an int2 (e, L).
+__device__ __forceinline__ uint32_t occ_pack(int2 r) { return ((uint32_t)r.x << 7) | (uint32_t)r.y; }
+__device__ __forceinline__ int2 occ_unpack(uint32_t u) { return make_int2((int)(u >> 7), (int)(u & 127u)); }
+
 // order of two occurrences by the tokens that follow them (end marker lowest), then by position
 template <bool STATS>
 __device__ __forceinline__ bool occ_less(const int32_t *__restrict__ x, int2 a, int2 b, int depth,
@@ -112,8 +118,13 @@ __device__ __forceinline__ bool occ_less(const int32_t *__restrict__ x, int2 a, 
 // the whole workgroup.  With `key` given (the two tokens after each occurrence packed into one
 // word, kept beside the records) most compares are decided without touching memory; equal
 // keys fall back to the token-by-token compare.
-template <bool STATS>
-__device__ __forceinline__ void occ_sort(int2 *arr, uint64_t *key, int m, const int32_t *__restrict__ x, int depth, unsigned &nb) {
+__device__ __forceinline__ int2 occ_get(const int2 *arr, int i) { return arr[i]; }
+__device__ __forceinline__ int2 occ_get(const uint32_t *arr, int i) { return occ_unpack(arr[i]); }
+__device__ __forceinline__ void occ_put(int2 *arr, int i, int2 r) { arr[i] = r; }
+__device__ __forceinline__ void occ_put(uint32_t *arr, int i, int2 r) { arr[i] = occ_pack(r); }
+
+template <bool STATS, class Rec>
+__device__ __forceinline__ void occ_sort(Rec *arr, uint64_t *key, int m, const int32_t *__restrict__ x, int depth, unsigned &nb) {
     int n2 = 1;
     while (n2 < m) n2 <<= 1;
     // Thread t handles elements t, t + blockDim, ...: a wave owns whole aligned blocks of 64
@@ -127,7 +138,7 @@ __device__ __forceinline__ void occ_sort(int2 *arr, uint64_t *key, int m, const 
             for (int i = threadIdx.x; i < m; i += blockDim.x) {
                 int l = mirror ? (i ^ (k - 1)) : (i ^ j);
                 if (l > i && l < m) {
-                    int2 a = arr[i], b = arr[l];
+                    const int2 a = occ_get(arr, i), b = occ_get(arr, l);
                     bool swap;
                     if (key) {
                         const uint64_t ka = key[i], kb = key[l];
@@ -139,8 +150,8 @@ __device__ __forceinline__ void occ_sort(int2 *arr, uint64_t *key, int m, const 
                         swap = occ_less<STATS>(x, b, a, depth, nb);
                     }
                     if (swap) {
-                        arr[i] = b;
-                        arr[l] = a;
+                        occ_put(arr, i, b);
+                        occ_put(arr, l, a);
                     }
                 }
             }
@@ -398,7 +409,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                                     int2 *s_sort, WgShared &sh, ScanState &st, int32_t tail,
                                     unsigned &nb, Between between) {
     const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
-    int2 *occ = p.occ + (int64_t)b * p.max_ctx;
+    uint32_t *occ = p.occ + (int64_t)b * p.max_ctx;
     const int4 *x4 = reinterpret_cast<const int4 *>(x);
     const int nq = t_old > 0 ? (t_old + 3) >> 2 : 0;
     int4(&v)[4] = st.v;
@@ -438,7 +449,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
 #pragma unroll
                     for (int c = 0; c < 4; c++)
                         if (hs[c]) {
-                            occ[off].x = es[c];
+                            occ[off] = occ_pack(make_int2(es[c], 0));
                             if (off < occ_cap) s_sort[off].x = es[c];
                             off++;
                         }
@@ -455,7 +466,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                     if (lane == 0) off = atomicAdd(&sh.m, (int)__popcll(hm));
                     off = uni(off) + __popcll(hm & lanemask_lt());
                     if ((hm >> lane) & 1) {
-                        occ[off].x = t_old + i;
+                        occ[off] = occ_pack(make_int2(t_old + i, 0));
                         if (off < occ_cap) s_sort[off].x = t_old + i;
                     }
                 }
@@ -487,7 +498,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
 #pragma unroll
             for (int u = 0; u < U; u++) {
                 const int i = i0 + u * G + g;
-                e[u] = i < m ? (in_lds ? s_sort[i].x : occ[i].x) : -1;
+                e[u] = i < m ? (in_lds ? s_sort[i].x : occ_unpack(occ[i]).x) : -1;
             }
 #pragma unroll
             for (int u = 0; u < U; u++) {
@@ -506,7 +517,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                 if (k == 0 && e[u] >= 0) {
                     const int i = i0 + u * G + g;
                     if (in_lds) s_sort[i].y = l;
-                    else occ[i].y = l;
+                    else occ[i] = occ_pack(make_int2(e[u], l));
                     atomicAdd(&sh.cnt[l], 1);
                     SD_CNT(8);
                 }
@@ -553,7 +564,7 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                     occ_sort<STATS>(s_sort, key, m, x, depth, nb);
                 }
             }
-            for (int i = tid; i < m; i += nthr) occ[i] = s_sort[i];
+            for (int i = tid; i < m; i += nthr) occ[i] = occ_pack(s_sort[i]);
         } else {
             occ_sort<STATS>(occ, nullptr, m, x, depth, nb);
         }
@@ -1805,7 +1816,7 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
             // m == 1 is the context's own tail alone: it stops at the end marker, so the
             // unit has no candidate at all and nothing else needs to be read
             const int m1 = m > 1 ? uni(sh.m) : 0;
-            const int2 *occ = p.occ + (int64_t)b * p.max_ctx;
+            const uint32_t *occ = p.occ + (int64_t)b * p.max_ctx;
             // a list of more than 64 occurrences goes to the request's row of scratch memory,
             // at the place the caller has assigned to this run of pattern lengths
             int32_t *usa = p.unit_sa + (int64_t)b * p.max_ctx + usa_off;
@@ -1814,8 +1825,8 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
             for (int base = 0; base < m1; base += 64) {
                 int i = base + lane;
                 int2 o = make_int2(0, 0);
-                if (i < m1) o = occ[i];
-                if (i < m1) SD_CNT(8);
+                if (i < m1) o = occ_unpack(occ[i]);
+                if (i < m1) SD_CNT(4);
                 bool keep = i < m1 && o.y >= pl;
                 uint64_t mk = __ballot(keep);
                 if (keep) {
@@ -2544,7 +2555,7 @@ namespace {
 
 // Launches k_speculate; with `aa` the fused form that first accepts and appends.
 sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, sd_trees out,
-                           const AcceptArgs *aa, hipStream_t st, int2 *occ = nullptr,
+                           const AcceptArgs *aa, hipStream_t st, uint32_t *occ = nullptr,
                            int32_t *unit_sa = nullptr) {
     SpecParams p;
     p.g_text = c->g_text; p.g_sa = c->g_sa; p.g_bucket = c->g_bucket; p.g_tok1 = c->g_tok1; p.g_tok1s = c->g_tok1s;
@@ -2628,9 +2639,9 @@ sd_status sd_speculate_static_impl(sd_ctx *c, const int32_t *d_slot_ids, int32_t
     if (batch == 0) return SD_OK;
     // rows of max_ctx_tokens entries per request of this call: occurrence records, then lists
     const int64_t rows = (int64_t)batch * c->cfg.max_ctx_tokens;
-    if (rows * (int64_t)(sizeof(int2) + sizeof(int32_t)) > (int64_t)SD_STATIC_SCRATCH_BYTES)
+    if (rows * (int64_t)(sizeof(uint32_t) + sizeof(int32_t)) > (int64_t)SD_STATIC_SCRATCH_BYTES)
         return SD_ERR_CAPACITY;
-    int2 *occ = reinterpret_cast<int2 *>(c->static_scratch);
+    uint32_t *occ = reinterpret_cast<uint32_t *>(c->static_scratch);
     int32_t *unit_sa = reinterpret_cast<int32_t *>(occ + rows);
     return launch_speculate(c, d_slot_ids, batch, out, nullptr, st, occ, unit_sa);
 }

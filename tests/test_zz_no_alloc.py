@@ -55,16 +55,16 @@ def test_static_scratch_entry_point_matches_sd_speculate():
 def test_static_scratch_entry_point_rejects_what_does_not_fit():
     import torch
     import paper_2411_04975_amd as sd
-    # 64 requests x 32768 tokens x 12 bytes = 24 MiB > 16 MiB; 32 requests fit
-    g = parity.GpuPath(100, 8, 4, 1.0, 0.1, 64, 32768, 1000)
+    # 96 requests x 32768 tokens x 8 bytes = 24 MiB > 16 MiB; 64 requests fit exactly
+    g = parity.GpuPath(100, 8, 4, 1.0, 0.1, 96, 32768, 1000)
     try:
-        tr = sd.Trees(64, g.max_nodes, g.dev)
-        slots = torch.arange(64, dtype=torch.int32, device=g.dev)
+        tr = sd.Trees(96, g.max_nodes, g.dev)
+        slots = torch.arange(96, dtype=torch.int32, device=g.dev)
         with pytest.raises(sd.SdError) as e:
             sd.sd_speculate_static(g.ctx, slots, tr)
         assert e.value.code == 4 and "SD_STATIC_SCRATCH_BYTES" in str(e.value)
-        sd.sd_speculate_static(g.ctx, slots[:32].contiguous(), tr)      # empty contexts: no trees
+        sd.sd_speculate_static(g.ctx, slots[:64].contiguous(), tr)      # empty contexts: no trees
         torch.cuda.synchronize()
-        assert int(tr.n_nodes[:32].abs().sum().item()) == 0
+        assert int(tr.n_nodes[:64].abs().sum().item()) == 0
     finally:
         g.close()
