@@ -961,7 +961,22 @@ __device__ __forceinline__ void push_children(Frontier &f, int hole, Stage &sg, 
     const double den = (double)dn;
     int64_t stride = (int64_t)floor(min_score * den / ps * (1.0 - 1e-9));
     if (stride < 1) stride = 1;
-    const int64_t np = ((int64_t)m + stride - 1) / stride;
+    int64_t np = ((int64_t)m + stride - 1) / stride;
+    // Where the probes a stride apart would leave most of the wave idle, the whole wave probes
+    // at a finer step instead: an admissible run (at least `stride` long) then holds at least
+    // floor(stride / step) probes in a row, which rules out most of the probed tokens at once
+    // (on independent tokens nearly every probe a stride apart shows another token, and the
+    // searches below share the wave: 10 candidates leave 3 probes per search and round, one
+    // candidate 32), and the ends of a run are bracketed that much more narrowly.
+    int need = 1;
+    {
+        const int64_t fine = ((int64_t)m + 63) / 64;
+        if (fine < stride) {
+            need = (int)(stride / fine);
+            stride = fine;
+            np = ((int64_t)m + stride - 1) / stride;  // <= 64: one group of probes
+        }
+    }
     for (int64_t k0 = 0; k0 < np; k0 += 64) {
         const int64_t k = k0 + lane;
         const bool in = k < np;
@@ -973,7 +988,6 @@ __device__ __forceinline__ void push_children(Frontier &f, int hole, Stage &sg, 
         if (lane == 0) prevtok = k == 0 ? (int32_t)0x80000000 : text[(int64_t)sa[q - stride] + d];
         if (lane == 0 && k != 0) SD_CNT(8);
         const bool change = in && tok != prevtok;
-        const bool first = change && tok >= 0;
         // The run of a probed token starts in (q - stride, q] and ends behind the last probe
         // that holds the token: before the next probe if there is one (in this group of 64),
         // else before hi, which is at most a stride away unless further groups follow.
@@ -982,6 +996,8 @@ __device__ __forceinline__ void push_children(Frontier &f, int hole, Stage &sg, 
         const int n_in = np - k0 < 64 ? (int)(np - k0) : 64;  // probes in this group
         int nxt = above ? lane + 1 + (__ffsll((unsigned long long)above) - 1) : 64;
         if (nxt > n_in) nxt = n_in;  // the next probe with another token, or the end of the group
+        // (need > 1 only with a single group, where the probes that hold a token are all in sight)
+        const bool first = change && tok >= 0 && nxt - lane >= need;
         const int32_t q_ls = (int32_t)(q + (int64_t)(nxt - 1 - lane) * stride);
         int32_t lb_lo = q, lb_hi = q, ub_lo = q_ls + 1, ub_hi = hi;  // (hi: the run may go on into the next group)
         if (k > 0) lb_lo = (int32_t)(q - stride + 1);
