@@ -1065,75 +1065,6 @@ __device__ __forceinline__ void push_children(Frontier &f, int hole, Stage &sg, 
     }
 }
 
-// MatchPattern on a sorted suffix array: narrows [lo, hi), the bucket of the pattern's first
-// token, to the suffixes that start with all pl pattern tokens.  Lower and upper bound are
-// searched together: each step loads both probe suffixes at once, and the two halves of the
-// wave compare one probe each against the pattern (lane k of a half holds pattern token k).
-template <bool STATS>
-__device__ __forceinline__ void match_range(const int32_t *__restrict__ sa, const int32_t *__restrict__ text,
-                            int32_t &lo, int32_t &hi, int32_t wk, int pl, unsigned &nb) {
-    const int lane = threadIdx.x & 63;
-    int32_t la = lo, ha = hi, lu = lo, hu = hi;
-    if (pl <= 32) {
-        const int half = lane >> 5, k = lane & 31;
-        const int32_t wq = __shfl(wk, k);
-        const bool act = k < pl;
-        while (la < ha || lu < hu) {
-            const bool doA = la < ha, doB = lu < hu;
-            const int32_t midA = la + ((ha - la) >> 1), midB = lu + ((hu - lu) >> 1);
-            const int64_t posA = doA ? sa[midA] : 0, posB = doB ? sa[midB] : 0;
-            if (lane == 0) SD_CNT(4 * ((int)doA + (int)doB));
-            const bool on = act && (half ? doB : doA);
-            const int32_t tk = on ? text[(half ? posB : posA) + k] : wq;
-            if (on) SD_CNT(4);
-            const uint64_t ne = __ballot(on && tk != wq);
-            const uint32_t neA = (uint32_t)ne, neB = (uint32_t)(ne >> 32);
-            int cA = 0, cB = 0;
-            if (neA) {
-                int fl = __ffs(neA) - 1;
-                cA = __shfl(tk, fl) < __shfl(wq, fl) ? -1 : 1;
-            }
-            if (neB) {
-                int fl = 32 + __ffs(neB) - 1;
-                cB = __shfl(tk, fl) < __shfl(wq, fl) ? -1 : 1;
-            }
-            if (doA) { if (cA < 0) la = midA + 1; else ha = midA; }
-            if (doB) { if (cB <= 0) lu = midB + 1; else hu = midB; }
-        }
-    } else {
-        const bool act = lane < pl;
-        while (la < ha) {  // first suffix whose leading pl tokens are >= the pattern
-            int32_t mid = la + ((ha - la) >> 1);
-            int64_t pos = sa[mid];
-            int32_t tk = act ? text[pos + lane] : 0;
-            SD_CNT(act ? (lane == 0 ? 8 : 4) : 0);
-            uint64_t ne = __ballot(act && tk != wk);
-            bool less = false;
-            if (ne) {
-                int fl = __ffsll((unsigned long long)ne) - 1;
-                less = __shfl(tk, fl) < __shfl(wk, fl);
-            }
-            if (less) la = mid + 1; else ha = mid;
-        }
-        lu = la;
-        while (lu < hu) {  // first suffix whose leading pl tokens are > the pattern
-            int32_t mid = lu + ((hu - lu) >> 1);
-            int64_t pos = sa[mid];
-            int32_t tk = act ? text[pos + lane] : 0;
-            SD_CNT(act ? (lane == 0 ? 8 : 4) : 0);
-            uint64_t ne = __ballot(act && tk != wk);
-            bool greater = false;
-            if (ne) {
-                int fl = __ffsll((unsigned long long)ne) - 1;
-                greater = __shfl(tk, fl) > __shfl(wk, fl);
-            }
-            if (!greater) lu = mid + 1; else hu = mid;
-        }
-    }
-    lo = la;
-    hi = lu;
-}
-
 // Tied single-occurrence chains.  When every frontier entry that shares the top score is a
 // node with one occurrence (at most TIE_MAX of them, all staged), each of them heads a chain
 // whose nodes all keep that score (count ratio 1/1), while everything else in the frontier
@@ -1450,61 +1381,62 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
 // context's last two tokens start too many suffixes for the list form).  The pattern's first
 // token selects a bucket of the suffix array; the second token is located in the bucket's
 // second-token column (sorted, read with coalesced loads: buckets up to SCAN_MAX entries are
-// simply scanned); the few suffixes left are compared with the whole pattern lane-parallel.
-// The dependent chain is bucket -> column -> suffix array -> text, whatever p is.
+// simply scanned, up to SAMPLED_MAX a sample of the column is read first); the few suffixes left
+// are compared with the whole pattern lane-parallel, and a dependent chain of bucket -> column
+// -> suffix array -> text is all there is, whatever p is.  More suffixes than that (frequent
+// tokens, text repeated many times over) are narrowed by a multi-way search that compares
+// several tokens per probe; so is a bucket too wide for the column's short routes, from the
+// pattern's second token on.
 constexpr int SCAN_MAX = 256;
-constexpr int COL_FAN = 8;  // probes per bound and round in a wide bucket (<= 32)
 constexpr int DIRECT_MAX = 8;  // up to this many suffixes are compared with the whole pattern at once
-constexpr int LEVEL_MIN = 256;  // ranges above this are narrowed token by token first
+constexpr int LEVEL_TLOG = 2;  // tokens per level of the search over a long range: 2^LEVEL_TLOG
 
-// Narrows the sorted range [l, h) to the entries whose token (tok_at(i), non-decreasing over
-// the range) is w1.
-template <bool STATS, class TokAt>
-__device__ __forceinline__ void range_fan(TokAt tok_at, int32_t w1, int32_t &l, int32_t &h,
-                                          unsigned &nb) {
-    const int lane = threadIdx.x & 63;
-        // lower and upper bound of the token by COL_FAN-way search, one half
-        // of the wave per bound: every round probes COL_FAN evenly spaced entries per
-        // bound and keeps the gap in which the answer lies.  Every probe moves a whole memory
-        // line for four bytes, so a wide fan trades latency for traffic: 32 probes per bound
-        // were faster for one request and much slower for 256 (the low-repetition workload went
-        // from 100 to 154 us per call); 8 keep the traffic near that of a binary search.
-        int32_t la = l, ha = h, lu = l, hu = h;  // the bounds lie in [la, ha] and [lu, hu]
-        const int half = lane >> 5, k = lane & 31;
-        while (la < ha || lu < hu) {
-            const int32_t lo_ = half ? lu : la, hi_ = half ? hu : ha;
-            const int32_t n = hi_ - lo_;
-            const int32_t step = (n + COL_FAN - 1) / COL_FAN;
-            const int64_t idx = (int64_t)lo_ + (int64_t)k * step;
-            const bool valid = k < COL_FAN && n > 0 && idx < hi_;
-            int32_t v = 0;
-            if (valid) v = tok_at(idx);
-            // probes holding a smaller (lower bound) / not larger (upper bound) token: a prefix
-            const uint64_t pm = __ballot(valid && (half ? v <= w1 : v < w1));
-            const int cA = __popc((uint32_t)pm), cB = __popc((uint32_t)(pm >> 32));
-            if (la < ha) {
-                const int32_t st = (ha - la + COL_FAN - 1) / COL_FAN;
-                if (cA == 0) ha = la;
-                else {
-                    const int64_t q = (int64_t)la + (int64_t)(cA - 1) * st;
-                    const int64_t nh = q + st < ha ? q + st : ha;
-                    la = (int32_t)(q + 1);
-                    ha = (int32_t)(nh > q + 1 ? nh : q + 1);
-                }
-            }
-            if (lu < hu) {
-                const int32_t st = (hu - lu + COL_FAN - 1) / COL_FAN;
-                if (cB == 0) hu = lu;
-                else {
-                    const int64_t q = (int64_t)lu + (int64_t)(cB - 1) * st;
-                    const int64_t nh = q + st < hu ? q + st : hu;
-                    lu = (int32_t)(q + 1);
-                    hu = (int32_t)(nh > q + 1 ? nh : q + 1);
-                }
-            }
+// [lo, hi): the suffixes (a range of the sorted suffix array) that agree with the pattern on its
+// first `depth` tokens (lane k of wk: pattern token k, pl of them).  Narrows the range to the
+// suffixes that also agree on the next T = 2^tlog <= 32 tokens, as far as the pattern goes.  Lower
+// and upper end are searched side by side, one half of the wave per end: a round probes
+// F = 32 / T suffixes per end, evenly spaced over the interval the end is known to lie in, T
+// lanes per probe comparing one token each, and keeps the gap between two probes (an (F + 1)-ary
+// search whose compares span T tokens).  The dependent chain is two loads per round (suffix
+// array, text) and log_(F+1)(hi - lo) rounds, where narrowing token by token costs as many
+// rounds again for every further token that a wide range needs.
+template <bool STATS>
+__device__ __forceinline__ void range_fan_tokens(const int32_t *__restrict__ sa,
+                                                 const int32_t *__restrict__ text, int32_t wk, int pl,
+                                                 int depth, int tlog, int32_t &lo, int32_t &hi,
+                                                 unsigned &nb) {
+    const int lane = threadIdx.x & 63, half = lane >> 5, k = lane & 31;
+    const int T = 1 << tlog, F = 32 >> tlog, j = k >> tlog, tt = k & (T - 1);
+    const uint32_t tmask = T >= 32 ? ~0u : (1u << T) - 1u;
+    const int32_t w = __shfl(wk, (depth + tt) & 63);
+    const bool tok_on = depth + tt < pl;
+    int32_t l = lo, h = hi;  // the interval this lane's end lies in: [l, h]
+    while (__ballot(l < h)) {
+        const bool go = l < h;
+        const int64_t n = (int64_t)h - l;
+        const int32_t pt = (int32_t)(l + n * (j + 1) / (F + 1));
+        int32_t v = w;
+        if (go && tok_on) {
+            v = text[(int64_t)sa[pt] + depth + tt];
+            SD_CNT(tt == 0 ? 8 : 4);
         }
-        l = la;
-        h = lu;
+        // probe against pattern over the T tokens: the first token that differs decides
+        const uint64_t ne = __ballot(v != w), lt = __ballot(v < w);
+        const int sh = k & ~(T - 1);
+        const uint32_t gne = ((uint32_t)(ne >> (half * 32)) >> sh) & tmask;
+        const uint32_t glt = ((uint32_t)(lt >> (half * 32)) >> sh) & tmask;
+        const int cmp = gne == 0 ? 0 : ((glt & (gne & (0u - gne))) ? -1 : 1);
+        // the end is the first suffix that is not below (lower end) / above (upper end) the
+        // pattern: the probes that say "further on" form a prefix
+        const bool further = go && (half ? cmp <= 0 : cmp < 0);
+        const uint64_t fm = __ballot(further && tt == 0);
+        const int cf = __popc((uint32_t)(fm >> (half * 32)));
+        const int32_t nl = cf > 0 ? (int32_t)(l + n * cf / (F + 1)) + 1 : l;
+        const int32_t nh = cf < F ? (int32_t)(l + n * (cf + 1) / (F + 1)) : h;
+        if (go) { l = nl; h = nh; }
+    }
+    lo = __builtin_amdgcn_readlane(l, 0);
+    hi = __builtin_amdgcn_readlane(l, 32);
 }
 
 // Result of an out-of-line second-stage lookup for two patterns.
@@ -1575,34 +1507,25 @@ __device__ __attribute__((noinline)) WideOut col_sampled(const int32_t *__restri
     return WideOut{loA, hiA, loB, hiB, nb};
 }
 
-// last stage for one pattern: [lo, hi) holds the suffixes that start with its first two tokens
+// last stage for one pattern: [lo, hi) holds the suffixes that start with its first `depth` tokens
 template <bool STATS>
 __device__ __forceinline__ void match_rest(const SpecParams &p, int32_t wk, int pl, int32_t &lo,
-                                           int32_t &hi, unsigned &nb) {
+                                           int32_t &hi, int depth, unsigned &nb) {
     const int lane = threadIdx.x & 63;
-    if (pl == 2 || lo >= hi) return;
-    // A long range is first narrowed by the pattern's third token, then its fourth, ... with
-    // the multi-way search (the suffixes of the range agree on everything before, so the token
-    // at that depth is sorted over the range): a level usually shrinks the range by orders of
-    // magnitude.  Once the range is short, or a level hardly shrank it (many suffixes that
-    // share the whole pattern), whole-pattern compares finish the job.
-    int depth = 2;
-    while (hi - lo > LEVEL_MIN && depth < pl) {
-        const int32_t w = __shfl(wk, depth);
-        const int32_t *sa = p.g_sa, *text = p.g_text;
+    // A long range is narrowed by the pattern's next four tokens at a time, which usually
+    // shrinks it by orders of magnitude.  When a level hardly shrank it (many suffixes that
+    // share the whole pattern: text copied from one template), the next level takes all the
+    // tokens that are left, up to 32 per probe.  Once at most DIRECT_MAX suffixes remain they
+    // are compared with the whole pattern in one go.
+    int tlog = LEVEL_TLOG;
+    while (hi - lo > DIRECT_MAX && depth < pl) {
         const int32_t before = hi - lo;
-        range_fan<STATS>([&](int64_t i) {
-            SD_CNT(8);
-            return text[(int64_t)sa[i] + depth];
-        }, w, lo, hi, nb);
-        depth++;
-        if ((int64_t)(hi - lo) * 4 > before) break;
+        range_fan_tokens<STATS>(p.g_sa, p.g_text, wk, pl, depth, tlog, lo, hi, nb);
+        depth += 1 << tlog;
+        if ((int64_t)(hi - lo) * 4 > before)
+            while (tlog < 5 && (1 << tlog) < pl - depth) tlog++;
     }
     if (lo >= hi || depth >= pl) return;
-    if (hi - lo > DIRECT_MAX) {
-        match_range<STATS>(p.g_sa, p.g_text, lo, hi, wk, pl, nb);
-        return;
-    }
     {  // compare every remaining suffix with the whole pattern
         const int32_t cnt = hi - lo;
         const int64_t pos = lane < cnt ? p.g_sa[lo + lane] : 0;
@@ -1647,9 +1570,14 @@ __device__ __forceinline__ void match_global(const SpecParams &p, int32_t wk, in
     lo = __builtin_amdgcn_readlane(bv, 0);
     hi = __builtin_amdgcn_readlane(bv, 1);
     if (pl == 1 || lo >= hi) return;
-    const int32_t w1 = __builtin_amdgcn_readlane(wk, 1);
-    col_stage<STATS>(p, w1, lo, hi, nb);
-    match_rest<STATS>(p, wk, pl, lo, hi, nb);
+    // (a bucket too wide for the second-token column's short routes is searched with several
+    // tokens per probe from the start)
+    const bool wide = hi - lo > SAMPLED_MAX;
+    if (!wide) {
+        const int32_t w1 = __builtin_amdgcn_readlane(wk, 1);
+        col_stage<STATS>(p, w1, lo, hi, nb);
+    }
+    if (wide || pl > 2) match_rest<STATS>(p, wk, pl, lo, hi, wide ? 1 : 2, nb);
 }
 
 // Second stage for one pattern: narrows the first token's bucket [lo, hi) to the suffixes whose
@@ -1664,8 +1592,8 @@ __device__ __forceinline__ void col_stage(const SpecParams &p, int32_t w1, int32
         const WideOut r = col_sampled<STATS>(col, p.g_tok1s, true, w1, l, h, false, 0, 0, 0);
         l = r.loA; h = r.hiA;
         SD_CNT(r.nb);
-    } else if (h - l > SCAN_MAX) {
-        range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1, l, h, nb);
+    } else if (h - l > SCAN_MAX) {  // (callers send such buckets elsewhere; kept for completeness)
+        range_fan_tokens<STATS>(p.g_sa, p.g_text, w1, 2, 1, LEVEL_TLOG, l, h, nb);
     } else {
         int32_t v[SCAN_MAX / 64];
 #pragma unroll
@@ -1733,11 +1661,11 @@ __device__ __forceinline__ void match_global_pair(const SpecParams &p, int32_t w
         loA = r.loA; hiA = r.hiA; loB = r.loB; hiB = r.hiB;
         SD_CNT(r.nb);
     }
-    if (goA && !narrowA && !smpA) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1A, loA, hiA, nb);
-    if (goB && !narrowB && !smpB) range_fan<STATS>([&](int64_t i) { SD_CNT(4); return col[i]; }, w1B, loB, hiB, nb);
+    // (a wider bucket goes to the search with several tokens per probe, from its second token on)
+    const bool wideA = goA && !narrowA && !smpA, wideB = goB && !narrowB && !smpB;
     // last stage: compare the few suffixes left with the whole pattern, A in the lower half of
     // the wave and B in the upper half
-    const bool restA = goA && plA > 2 && loA < hiA, restB = goB && plB > 2 && loB < hiB;
+    const bool restA = goA && (plA > 2 || wideA) && loA < hiA, restB = goB && (plB > 2 || wideB) && loB < hiB;
     const bool dirA = restA && hiA - loA <= DIRECT_MAX, dirB = restB && hiB - loB <= DIRECT_MAX;
     if (dirA || dirB) {
         const int32_t cntA = dirA ? hiA - loA : 0, cntB = dirB ? hiB - loB : 0;
@@ -1775,8 +1703,8 @@ __device__ __forceinline__ void match_global_pair(const SpecParams &p, int32_t w
         if (dirA) { hiA = loA + leA; loA = loA + lsA; }
         if (dirB) { hiB = loB + leB; loB = loB + lsB; }
     }
-    if (restA && !dirA) match_rest<STATS>(p, wkA, plA, loA, hiA, nb);
-    if (restB && !dirB) match_rest<STATS>(p, wkB, plB, loB, hiB, nb);
+    if (restA && !dirA) match_rest<STATS>(p, wkA, plA, loA, hiA, wideA ? 1 : 2, nb);
+    if (restB && !dirB) match_rest<STATS>(p, wkB, plB, loB, hiB, wideB ? 1 : 2, nb);
 }
 
 // One unit (request b, index src: 0 global / 1 request, pattern length pl) on one wavefront:
