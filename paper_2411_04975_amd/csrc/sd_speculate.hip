@@ -1908,12 +1908,40 @@ struct AcceptArgs {
 
 // Acceptance for request b on one wavefront (max_nodes <= 256): node j is accepted iff its
 // token equals the target token at its parent's position and its parent is accepted, which
-// pointer jumping over the parent links settles in at most eight rounds.  s_tgt[257], s_anc[256]
-// and s_ok[256] are LDS of the calling wave.  With APPEND the accepted tokens and the bonus
+// pointer jumping over the parent links settles in at most eight rounds (trees of up to 64
+// nodes: one node per lane, links and flags in registers; larger ones in LDS).  s_tgt[257],
+// s_anc[256] and s_ok[256] are LDS of the calling wave.  With APPEND the accepted tokens and the bonus
 // token go behind the slot's context (and into s_new in LDS if that is given).  Returns the
 // slot's context length afterwards (0 for a bad slot), which only the APPEND form looks up.
+// What the acceptance reads first, for lane l: the node count, node l and target position l
+// (and position 64, which a tree of 64 nodes has), and the request's two counters.  Kept apart
+// from accept_wave so that a caller with other loads to wait for can issue these first.
+struct AcceptIn {
+    int32_t n, tok0, par0, tgt0, tgt64;
+    unsigned long long c_req, c_len;
+};
+
+__device__ __forceinline__ AcceptIn accept_fetch(int b, const int32_t *__restrict__ n_nodes,
+                                                 const int32_t *__restrict__ tokens,
+                                                 const int32_t *__restrict__ parents, int max_nodes,
+                                                 const AcceptArgs &aa) {
+    const int lane = threadIdx.x & 63;
+    const int32_t *tgt = aa.target + (int64_t)b * (max_nodes + 1);
+    AcceptIn in;
+    in.n = n_nodes[b];
+    in.tok0 = lane < max_nodes ? tokens[(int64_t)b * max_nodes + lane] : -1;
+    in.par0 = lane < max_nodes ? parents[(int64_t)b * max_nodes + lane] : -1;
+    in.tgt0 = lane <= max_nodes ? tgt[lane] : 0;
+    in.tgt64 = max_nodes >= 64 ? tgt[64] : 0;
+    // this request's counters of verified requests and accepted nodes (see sd_internal.h)
+    const unsigned long long *ctr = aa.counters + (int64_t)b * SD_CTR_STRIDE;
+    in.c_req = 0; in.c_len = 0;
+    if (lane == 0) { in.c_req = ctr[SD_CTR_ACCEPT_REQUESTS]; in.c_len = ctr[SD_CTR_ACCEPT_LEN]; }
+    return in;
+}
+
 template <bool APPEND>
-__device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_nodes,
+__device__ __forceinline__ int accept_wave(int b, const AcceptIn &in,
                                            const int32_t *__restrict__ tokens,
                                            const int32_t *__restrict__ parents, int max_nodes,
                                            const AcceptArgs &aa, const AppendArgs &ap, int32_t *s_tgt,
@@ -1923,25 +1951,48 @@ __device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_
     const int32_t *tok = tokens + (int64_t)b * max_nodes, *par = parents + (int64_t)b * max_nodes;
     const int32_t *tgt = aa.target + (int64_t)b * (max_nodes + 1);
     int32_t *path = aa.accept_path + (int64_t)b * max_nodes;
-    // every load of the tree and the targets is issued before the node count is looked at
-    int n = n_nodes[b];
-    // this request's counters of verified requests and accepted nodes (see sd_internal.h)
+    int n = in.n;
     unsigned long long *ctr = aa.counters + (int64_t)b * SD_CTR_STRIDE;
-    unsigned long long c_req = 0, c_len = 0;
-    if (lane == 0) { c_req = ctr[SD_CTR_ACCEPT_REQUESTS]; c_len = ctr[SD_CTR_ACCEPT_LEN]; }
+    const unsigned long long c_req = in.c_req, c_len = in.c_len;
+    const bool small = max_nodes <= 64;  // one node per lane: settled in registers, below
     int32_t mt[4], mp[4];
+    mt[0] = in.tok0; mp[0] = in.par0;
 #pragma unroll
-    for (int r = 0; r < 4; r++) {
+    for (int r = 1; r < 4; r++) {
         int j = lane + 64 * r;
         mt[r] = j < max_nodes ? tok[j] : -1;
         mp[r] = j < max_nodes ? par[j] : -1;
     }
-    for (int i = lane; i <= max_nodes; i += 64) s_tgt[i] = tgt[i];
+    if (!small) {
+        s_tgt[lane] = in.tgt0;
+        for (int i = 64 + lane; i <= max_nodes; i += 64) s_tgt[i] = tgt[i];
+    }
     if (n > max_nodes) n = max_nodes;
     if (n < 0) n = 0;
 #pragma unroll
     for (int r = 0; r < 4; r++)
         if (lane + 64 * r >= n) { mt[r] = -1; mp[r] = -1; }
+    uint64_t am[4] = {0ull, 0ull, 0ull, 0ull};
+    int L = 0, last = -1;
+    int32_t bon;
+    if (small) {
+        // the same pointer jumping with the links and flags in registers, passed between
+        // lanes by permutes: no LDS round trip and no wave barrier per round
+        const bool wf = lane < n && mp[0] >= -1 && mp[0] < lane;
+        const int32_t want = __shfl(in.tgt0, wf ? mp[0] + 1 : 0);  // (mp[0] + 1 <= lane <= 63)
+        int32_t ok = wf && mt[0] == want, anc = wf ? mp[0] : -1;
+        for (int round = 0; round < 6; round++) {  // 2^6 >= the deepest possible path
+            const bool open = anc >= 0;
+            if (!__ballot(open)) break;
+            const int src = open ? anc : lane;
+            const int32_t o2 = __shfl(ok, src), a2 = __shfl(anc, src);
+            if (open) { ok &= o2; anc = a2; }
+        }
+        am[0] = __ballot(lane < n && ok);
+        if (am[0]) last = 63 - __clzll((unsigned long long)am[0]);
+        L = __popcll(am[0]);
+        bon = last + 1 < 64 ? __builtin_amdgcn_readlane(in.tgt0, (last + 1) & 63) : in.tgt64;
+    } else {
     wsync();
 #pragma unroll
     for (int r = 0; r < 4; r++) {
@@ -1979,8 +2030,6 @@ __device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_
         }
         wsync();
     }
-    uint64_t am[4];
-    int L = 0, last = -1;
 #pragma unroll
     for (int r = 0; r < 4; r++) {
         int j = lane + 64 * r;
@@ -1988,7 +2037,8 @@ __device__ __forceinline__ int accept_wave(int b, const int32_t *__restrict__ n_
         if (am[r]) last = 64 * r + 63 - __clzll((unsigned long long)am[r]);
         L += __popcll(am[r]);
     }
-    const int32_t bon = s_tgt[last + 1];
+    bon = s_tgt[last + 1];
+    }
     int32_t *row = nullptr;
     int32_t old = 0, slot_of_b = 0;
     bool slot_ok = false;
@@ -2055,7 +2105,8 @@ __global__ __launch_bounds__(64) void k_accept(const int32_t *__restrict__ n_nod
     __shared__ int32_t s_tgt[257];
     __shared__ int32_t s_anc[256];
     __shared__ int32_t s_ok[256];
-    accept_wave<APPEND>(blockIdx.x, n_nodes, tokens, parents, max_nodes, aa, ap, s_tgt, s_anc, s_ok,
+    const AcceptIn in = accept_fetch(blockIdx.x, n_nodes, tokens, parents, max_nodes, aa);
+    accept_wave<APPEND>(blockIdx.x, in, tokens, parents, max_nodes, aa, ap, s_tgt, s_anc, s_ok,
                         nullptr);
 }
 
@@ -2093,6 +2144,9 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
     const int32_t slot = slot_ids ? uni(slot_ids[b]) : b;
     const bool slot_ok = slot >= 0 && slot < p.max_slots;
     if (!slot_ok && threadIdx.x == 0) atomicOr(&p.err[SD_DEVERR_SLOT], 1);
+    // (fused form: what the acceptance reads is asked for before anything waits for memory)
+    AcceptIn ain = {};
+    if (ACCEPT && wave == 0) ain = accept_fetch(b, out.d_n_nodes, out.d_tokens, out.d_parents, out.max_nodes, aa);
     // the context length before this launch appends anything
     const int t_old = slot_ok ? uni(p.r_len[slot]) : 0;
     const int32_t *x = p.r_text + (int64_t)(slot_ok ? slot : 0) * p.r_stride;
@@ -2134,7 +2188,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         if (wave == 0) {
             // LDS that the occurrence sort takes over afterwards
             int32_t *s_tgt = reinterpret_cast<int32_t *>(smem), *s_anc = s_tgt + 260, *s_ok = s_anc + 256;
-            const int nl = accept_wave<true>(b, out.d_n_nodes, out.d_tokens, out.d_parents,
+            const int nl = accept_wave<true>(b, ain, out.d_tokens, out.d_parents,
                                              out.max_nodes, aa, ap, s_tgt, s_anc, s_ok, sh.newtok,
                                              slot, t_old);
             if (lane == 0) sh.t_new = nl;
