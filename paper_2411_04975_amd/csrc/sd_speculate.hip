@@ -354,6 +354,7 @@ struct WgShared {
     int m;           // occurrences of the context's last token
     int next;        // head of the unit queue
     int sort_flag;   // scratch of the occurrence sort
+    int n_surv;      // occurrences whose left-extension the one-token check did not settle
     unsigned long long top_bits;  // highest SCORE of a finished tree so far (bits of the double)
     int t_new;       // context length after the append of the fused form
     int newtok[260]; // fused form: the tokens appended in this launch
@@ -388,7 +389,7 @@ template <bool STATS>
 __device__ __forceinline__ void occ_scan_issue(int t_old, const int32_t *__restrict__ x, WgShared &sh,
                                                ScanState &st, unsigned &nb) {
     const int tid = threadIdx.x, nthr = blockDim.x;
-    if (tid == 0) { sh.m = 0; sh.next = 0; sh.top_bits = 0; }
+    if (tid == 0) { sh.m = 0; sh.next = 0; sh.top_bits = 0; sh.n_surv = 0; }
     if (tid < 72) { sh.cnt[tid] = 0; sh.gcnt[tid] = 0; }
     // Coalesced scan, 16 bytes per load, four loads in flight per thread; rows start 256-byte
     // aligned.
@@ -401,6 +402,67 @@ __device__ __forceinline__ void occ_scan_issue(int t_old, const int32_t *__restr
         if (q < nq) SD_CNT(16);
     }
     st.last_old = t_old > 0 ? x[t_old - 1] : 0;
+}
+
+// Left-extensions when the last token has more occurrences than one trip of the workgroup
+// takes (a frequent token; records in LDS): most occurrences differ from the context's tail
+// in the very next token to the left.  One load per occurrence, an occurrence per thread,
+// settles those; the rest is listed (in `lst`) and compared token by token as in the caller's
+// loop, PP lanes per occurrence.  Out of line: the route is rare and is kept from weighing on
+// the registers and the code layout of the usual one.  Called by every thread (barrier inside).
+template <bool STATS>
+__device__ __attribute__((noinline)) unsigned left_extensions_many(int m, int t, int P, int32_t tail,
+                                                                    const int32_t *__restrict__ x,
+                                                                    int2 *s_sort, int32_t *lst,
+                                                                    WgShared &sh) {
+    unsigned nb = 0;
+    const int tid = threadIdx.x, lane = tid & 63, nthr = blockDim.x;
+    const int wave = uni((int32_t)(tid >> 6)), nw = nthr >> 6;
+    const int32_t tl1 = __builtin_amdgcn_readlane(tail, 1);
+    for (int i = tid; i < ((m + 63) & ~63); i += nthr) {
+        const bool on = i < m;
+        const int e = on ? s_sort[i].x : -1;
+        const int lim = e + 1 < P ? e + 1 : P;
+        const bool rd = on && e != t - 1 && lim > 1;
+        const int32_t vv = rd ? x[e - 1] : tl1;
+        if (rd) SD_CNT(8);
+        const bool one = on && (lim <= 1 || (rd && vv != tl1));  // left-extension 1
+        const bool surv = on && !one;
+        if (one) s_sort[i].y = 1;
+        const uint64_t om = __ballot(one), sm = __ballot(surv);
+        if (lane == 0 && om) atomicAdd(&sh.cnt[1], (int)__popcll(om));
+        if (sm) {
+            int base = 0;
+            if (lane == 0) base = atomicAdd(&sh.n_surv, (int)__popcll(sm));
+            base = uni(base);
+            if (surv) lst[base + __popcll(sm & lanemask_lt())] = i;
+        }
+    }
+    __syncthreads();
+    const int n_items = sh.n_surv;
+    int pplog = 0;
+    while ((1 << pplog) < P) pplog++;
+    const int PP = 1 << pplog, G = 64 >> pplog, g = lane >> pplog, k = lane & (PP - 1);
+    const uint64_t gmask = PP >= 64 ? ~0ull : ((1ull << PP) - 1ull);
+    const int32_t tl = __shfl(tail, k);
+    for (int j0 = wave * G; j0 < n_items; j0 += nw * G) {
+        const int j = j0 + g;
+        const int i = j < n_items ? lst[j] : -1;
+        const int e = i >= 0 ? s_sort[i].x : -1;
+        const int lim = e + 1 < P ? e + 1 : P;  // (0 for an empty place)
+        const bool rd = e >= 0 && e != t - 1 && k < lim;
+        const int32_t v = rd ? x[e - k] : tl;
+        if (rd) SD_CNT(8);
+        const uint64_t mis = __ballot(k >= 1 && k < lim && v != tl);
+        const uint64_t gm = (mis >> (g << pplog)) & gmask;
+        const int l = gm ? __ffsll((unsigned long long)gm) - 1 : lim;
+        if (k == 0 && e >= 0) {
+            s_sort[i].y = l;
+            atomicAdd(&sh.cnt[l], 1);
+            SD_CNT(8);
+        }
+    }
+    return nb;
 }
 
 template <bool STATS, class Between>
@@ -492,6 +554,12 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
         const uint64_t gmask = PP >= 64 ? ~0ull : ((1ull << PP) - 1ull);
         const int32_t tl = __shfl(tail, k);  // the k-th token from the context's end (0 beyond it)
         constexpr int U = 4;
+        if (__builtin_expect(in_lds && m > nw * G * U, 0)) {
+            // (the room of the sort keys, free until the sort, takes the list)
+            const unsigned cnt_many = left_extensions_many<STATS>(
+                m, t, p.P, tail, x, s_sort, reinterpret_cast<int32_t *>(s_sort + occ_cap), sh);
+            SD_CNT(cnt_many);
+        } else
         for (int i0 = wave * G * U; i0 < m; i0 += nw * G * U) {
             int e[U];
             int32_t v[U];
