@@ -17,7 +17,13 @@
  *  - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).
  *    sd_index_build, sd_index_append, sd_speculate and sd_accept only ENQUEUE
  *    work; they do not synchronise the device.  sd_create, sd_destroy and
- *    sd_get_stats synchronise.
+ *    sd_get_stats synchronise.  sd_index_build of the global index and
+ *    sd_index_insert wait for `hip_stream` while they enqueue (once for
+ *    ordinary text, a few times for text with long repeats of frequent tokens:
+ *    the host looks at what the first sorting rounds found to leave out device-wide
+ *    sorts that are not needed), unless the stream is being captured into a
+ *    graph: then they only enqueue.  Their last kernels are still in flight
+ *    when they return.
  *  - Errors the host can see (bad arguments, sizes beyond the configured
  *    capacity) return a code at once and enqueue nothing.  Conditions only the
  *    device can see raise a sticky device flag that sd_get_stats reports: a

@@ -386,11 +386,32 @@ inline unsigned nblk(int64_t n) { return (unsigned)((n + TB - 1) / TB); }
 
 }  // namespace
 
+// A stream that is being captured into a graph cannot be waited for.
+static bool stream_can_wait(hipStream_t st) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return cs == hipStreamCaptureStatusNone;
+}
+
 // Sorts the N positions of `text` (documents with an end marker after each, padding behind)
 // by their suffixes, compared on at least D tokens.  Returns which of b_vals[0/1] holds the
-// sorted positions.
+// sorted positions (-1: a HIP call failed).
+// A round's device-wide fall-back is some twenty launches that return at once when the in-tile
+// kernel has done the round: about 2 us each, a tenth of the build of a 10M-token corpus.
+// Groups only ever split, so once a round's in-tile kernel has coped, those of all later rounds
+// will: the host waits for the stream after a round's in-tile kernel and reads its flag, until
+// the first round that needs no fall-back; from there on the rounds are enqueued without
+// fall-backs and without waiting (one wait for text without long repeats; text whose frequent
+// tokens make the first rounds fall back pays a wait for each of those rounds and gets them
+// back from the launches it no longer makes afterwards).  On a stream that cannot be waited
+// for, every round is enqueued with its fall-back, switched by the flag on the device.
 static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, int32_t *tok1_out,
                                   hipStream_t st) {
+    const bool can_wait = stream_can_wait(st);
+    bool settled = false;  // no later round can need its fall-back
     const int tok_bits = sd_bits_for((uint64_t)c->cfg.vocab);  // codes 0..vocab
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_init_keys, dim3(nblk(N)), dim3(TB), 0, text, N, tok_bits, c->b_keys[0], c->b_vals[0]);
     int cur = sd_sort_pairs(c, N, 2 * tok_bits, 0, st);
@@ -413,9 +434,22 @@ static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, int
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_small,
                   dim3((unsigned)((N + SMALL_TILE - 1) / SMALL_TILE)), dim3(SMALL_THREADS), 0,
                   c->b_vals[cur], gid, c->b_rank, N, h, gid_next, c->b_vals[cur ^ 1], flag);
-        if (h * 2 < c->cfg.D)  // (the last round's numbers are not needed by anyone)
+        if (can_wait && !settled) {
+            int32_t too_long = 0;
+            if (hipStreamSynchronize(st) != hipSuccess ||
+                hipMemcpy(&too_long, flag, sizeof(too_long), hipMemcpyDeviceToHost) != hipSuccess)
+                return -1;
+            settled = too_long == 0;
+        }
+        // (after a round that fell back, the device-wide sort brings the ranks up to date)
+        if (h * 2 < c->cfg.D && (settled || !can_wait))  // (the last round's numbers are not needed by anyone)
             SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_rank_update, dim3(nblk(N) < 8192u ? nblk(N) : 8192u),
                       dim3(TB), 0, c->b_vals[cur ^ 1], gid_next, gid, N, c->b_rank, flag);
+        if (settled) {
+            cur ^= 1;
+            uint32_t *t = gid; gid = gid_next; gid_next = t;
+            continue;
+        }
         const int start = (passes & 1) ? cur : cur ^ 1;
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_round_keys, dim3(nblk(N) < 4096u ? nblk(N) : 4096u), dim3(TB), 0, c->b_rank, N, h, rank_bits, c->b_keys[start], c->b_vals[start], flag);
         (void)sd_sort_pairs(c, N, 2 * rank_bits, start, st, flag);
@@ -442,6 +476,7 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
     }
     if (N > 0) {
         const int cur = build_sorted_positions(c, c->g_text, N, c->g_tok1, st);
+        if (cur < 0) return SD_ERR_HIP;
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_finish_sa, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], N,
                   c->g_sa);
     }
@@ -465,6 +500,7 @@ sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_
         SD_LAUNCH(c, SD_K_INSERT, st, k_layout_marks, dim3(nblk(m)), dim3(TB), 0, d_offsets, n_seq, M, ntext);
     }
     const int cur = build_sorted_positions(c, ntext, M, nullptr, st);
+    if (cur < 0) return SD_ERR_HIP;
     // b_vals[cur]: new positions in order; b_flags: their ranks in the old array; merged arrays
     // go to b_vals[1 - cur] and b_rank, which then change places with g_sa and g_tok1
     uint32_t *dsa = c->b_vals[cur], *rank = c->b_flags;
