@@ -347,7 +347,10 @@ class Run:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=64,
+                    help="timed decode steps (default: as many as the streaming configuration "
+                         "runs; the one graph launch and the closing synchronisation of the timed "
+                         "region, some 50 us together, are spread over them)")
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="large")
     ap.add_argument("--others", default="agentic,lowrep,streaming",

@@ -354,6 +354,7 @@ struct WgShared {
     int m;           // occurrences of the context's last token
     int next;        // head of the unit queue
     int sort_flag;   // scratch of the occurrence sort
+    unsigned long long ctr[SD_CTR_ACCEPT_REQUESTS];  // the request's drafting counters, on their way through the launch
     int n_surv;      // occurrences whose left-extension the one-token check did not settle
     unsigned long long top_bits;  // highest SCORE of a finished tree so far (bits of the double)
     int t_new;       // context length after the append of the fused form
@@ -2276,6 +2277,9 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         pattern_tokens();
         __syncthreads();  // the counters of the occurrence list are set
     }
+    // (the counters wait in LDS for the end of the launch: two registers less to carry through
+    // matching and expansion; the load is older than the tail's, which has just been waited for)
+    if (wave == nw - 1 && lane < SD_CTR_ACCEPT_REQUESTS) sh.ctr[lane] = ctr_old;
     request_occurrences<STATS>(p, b, t, t_old, sh.newtok, x, s_sort, sh, scan, tail, nb, [&]() {
         // List form: the suffixes that start with the context's last two tokens are located
         // once (every wave does that for itself: same loads, no barrier).  If there are at
@@ -2453,7 +2457,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
                         : lane == SD_CTR_REQUEST_WIDE ? (wide_r != 0)
                         : lane == SD_CTR_OCC_IN_MEMORY ? (uni(sh.m) > p.occ_cap)
                         : lane == SD_CTR_LIST_ROUNDS ? n_rounds - 1 : 0;
-        ctr_old += (unsigned long long)add;
+        if (lane < SD_CTR_ACCEPT_REQUESTS) sh.ctr[lane] += (unsigned long long)add;
     }
     const uint64_t wg2 = TICKS ? wall_clock64() : 0;
     double best_s = 0.0;
@@ -2541,7 +2545,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         const int add = lane == SD_CTR_REQUESTS ? 1 : lane == SD_CTR_TREES ? tree : lane == SD_CTR_NODES ? n
                         : lane == SD_CTR_MATCH_LEN ? (tree ? wo % p.P + 1 : 0)
                         : lane == SD_CTR_FROM_REQUEST ? (tree && wo >= p.P) : 0;
-        p.counters[(int64_t)b * SD_CTR_STRIDE + lane] = ctr_old + (unsigned long long)add;
+        p.counters[(int64_t)b * SD_CTR_STRIDE + lane] = sh.ctr[lane] + (unsigned long long)add;
     }
     if (wave == (ww < 0 ? 0 : ww)) {
         const int n = ww < 0 ? 0 : best_n;
