@@ -1479,11 +1479,17 @@ __device__ __forceinline__ void range_fan_tokens(const int32_t *__restrict__ sa,
     const uint32_t tmask = T >= 32 ? ~0u : (1u << T) - 1u;
     const int32_t w = __shfl(wk, (depth + tt) & 63);
     const bool tok_on = depth + tt < pl;
+    // probe j of an interval of n places sits at floor(n * frac / 2^32) with frac about
+    // 2^32 (j + 1) / (F + 1): increasing in j and below n, which is all the search needs (one
+    // multiply, no 64-bit division: F + 1 is one of 2, 3, 5, 9, 17, 33)
+    const uint32_t recip = tlog >= 5 ? 2147483648u : tlog == 4 ? 1431655765u : tlog == 3 ? 858993459u
+                           : tlog == 2 ? 477218588u : tlog == 1 ? 252645135u : 130150524u;
+    const uint32_t frac = recip * (uint32_t)(j + 1);
     int32_t l = lo, h = hi;  // the interval this lane's end lies in: [l, h]
     while (__ballot(l < h)) {
         const bool go = l < h;
-        const int64_t n = (int64_t)h - l;
-        const int32_t pt = (int32_t)(l + n * (j + 1) / (F + 1));
+        const uint32_t n = (uint32_t)(h - l);
+        const int32_t pt = l + (int32_t)__umulhi(n, frac);
         int32_t v = w;
         if (go && tok_on) {
             v = text[(int64_t)sa[pt] + depth + tt];
@@ -1499,9 +1505,16 @@ __device__ __forceinline__ void range_fan_tokens(const int32_t *__restrict__ sa,
         // pattern: the probes that say "further on" form a prefix
         const bool further = go && (half ? cmp <= 0 : cmp < 0);
         const uint64_t fm = __ballot(further && tt == 0);
-        const int cf = __popc((uint32_t)(fm >> (half * 32)));
-        const int32_t nl = cf > 0 ? (int32_t)(l + n * cf / (F + 1)) + 1 : l;
-        const int32_t nh = cf < F ? (int32_t)(l + n * (cf + 1) / (F + 1)) : h;
+        const int cfa = __popc((uint32_t)fm), cfb = __popc((uint32_t)(fm >> 32));
+        const int cf = half ? cfb : cfa;
+        // the end lies behind the last probe that says "further on" and at or before the next
+        // one: their places are read from the lanes that made them (scalar lane indices)
+        const int32_t la_ = __builtin_amdgcn_readlane(pt, (cfa > 0 ? cfa - 1 : 0) << tlog);
+        const int32_t na_ = __builtin_amdgcn_readlane(pt, (cfa < F ? cfa : 0) << tlog);
+        const int32_t lb_ = __builtin_amdgcn_readlane(pt, 32 + ((cfb > 0 ? cfb - 1 : 0) << tlog));
+        const int32_t nb_ = __builtin_amdgcn_readlane(pt, 32 + ((cfb < F ? cfb : 0) << tlog));
+        const int32_t nl = cf > 0 ? (half ? lb_ : la_) + 1 : l;
+        const int32_t nh = cf < F ? (half ? nb_ : na_) : h;
         if (go) { l = nl; h = nh; }
     }
     lo = __builtin_amdgcn_readlane(l, 0);
@@ -2300,6 +2313,8 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
             if (reach && lo2 < hi2) col_stage<STATS>(p, w_last, lo2, hi2, nb);
             const int n2 = hi2 > lo2 ? hi2 - lo2 : 0;
             if (__builtin_expect(reach && n2 <= 64, 1)) {
+                // (stored at once: two values less to keep through the loop)
+                if (threadIdx.x == 0) { sh.g_lo[1] = lo1; sh.g_hi[1] = hi1; }
                 int pplog = 0;
                 while ((1 << pplog) < P) pplog++;
                 const int PP = 1 << pplog, G = 64 >> pplog, g = lane >> pplog, k = lane & (PP - 1);
@@ -2337,10 +2352,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
                         }
                     }
                 }
-                if (threadIdx.x == 0) {
-                    sh.g_lo[1] = lo1; sh.g_hi[1] = hi1;
-                    sh.g_mode = 1; sh.g_n2 = n2;
-                }
+                if (threadIdx.x == 0) { sh.g_mode = 1; sh.g_n2 = n2; }
                 return;
             }
         }
@@ -2521,13 +2533,16 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         wt[3] = (uint32_t)(wg3 - wg0); wt[4] = (uint32_t)(wall_clock64() - wg0);
         wt[5] = (uint32_t)nruns; wt[6] = (uint32_t)sh.m; wt[7] = (uint32_t)nw;
     }
+    // (the lane number is taken afresh here: keeping it in a register from the kernel's start
+    // to its end costs a register that the expansion needs)
+    const int lane_e = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
     // the winning wave: top SCORE, then the earliest unit in scan order (lane w looks at wave w;
     // units are distinct, so the second criterion leaves one wave)
     double ws = 0.0;
     int wo = -1, ww = -1;
     {
-        const double s = lane < nw ? sh.best_s[lane] : 0.0;
-        const int o = lane < nw ? sh.best_o[lane] : -1;
+        const double s = lane_e < nw ? sh.best_s[lane_e] : 0.0;
+        const int o = lane_e < nw ? sh.best_o[lane_e] : -1;
         const bool valid = o >= 0;
         const double sx = wave_max_f64(valid ? s : -__longlong_as_double(0x7ff0000000000000ll));
         const bool top = valid && s == sx;
@@ -2539,13 +2554,13 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
             wo = (int)~ox;
         }
     }
-    if (wave == nw - 1 && lane < SD_CTR_ACCEPT_REQUESTS) {  // lane k: counter k of the drafting calls
+    if (wave == nw - 1 && lane_e < SD_CTR_ACCEPT_REQUESTS) {  // lane k: counter k of the drafting calls
         const int n = ww < 0 ? 0 : sh.best_n[ww];
         const bool tree = n > 0;
-        const int add = lane == SD_CTR_REQUESTS ? 1 : lane == SD_CTR_TREES ? tree : lane == SD_CTR_NODES ? n
-                        : lane == SD_CTR_MATCH_LEN ? (tree ? wo % p.P + 1 : 0)
-                        : lane == SD_CTR_FROM_REQUEST ? (tree && wo >= p.P) : 0;
-        p.counters[(int64_t)b * SD_CTR_STRIDE + lane] = sh.ctr[lane] + (unsigned long long)add;
+        const int add = lane_e == SD_CTR_REQUESTS ? 1 : lane_e == SD_CTR_TREES ? tree : lane_e == SD_CTR_NODES ? n
+                        : lane_e == SD_CTR_MATCH_LEN ? (tree ? wo % p.P + 1 : 0)
+                        : lane_e == SD_CTR_FROM_REQUEST ? (tree && wo >= p.P) : 0;
+        p.counters[(int64_t)b * SD_CTR_STRIDE + lane_e] = sh.ctr[lane_e] + (unsigned long long)add;
     }
     if (wave == (ww < 0 ? 0 : ww)) {
         const int n = ww < 0 ? 0 : best_n;
@@ -2553,14 +2568,14 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
         const int32_t *btk = kept ? ttk1 : ttk0, *bpr = kept ? tpr1 : tpr0;
         const double *bsc = kept ? tsc1 : tsc0;
         const int64_t ob = (int64_t)b * out.max_nodes;
-        for (int i = lane; i < out.max_nodes; i += 64) {
+        for (int i = lane_e; i < out.max_nodes; i += 64) {
             const bool live = i < n;
             out.d_tokens[ob + i] = live ? btk[i] : -1;
             out.d_parents[ob + i] = live ? bpr[i] : -1;
             out.d_scores[ob + i] = live ? bsc[i] : 0.0;
             SD_CNT(16);
         }
-        if (lane == 0) {
+        if (lane_e == 0) {
             out.d_n_nodes[b] = n;
             out.d_tree_score[b] = ww >= 0 ? ws : 0.0;
             out.d_match_len[b] = ww >= 0 ? wo % p.P + 1 : 0;
