@@ -288,7 +288,8 @@ sd_status sd_get_stats(sd_ctx *ctx, sd_stats *host_out);
  * which adds up the bytes the algorithm asks for (context tokens scanned,
  * suffix-array words, text tokens, occurrence records, emitted nodes),
  * 3 = time kernels and run the timing variant of the speculation kernel,
- * which leaves wall-clock marks for the two sd_debug_read_*_ticks calls.  sd_debug_profile_read
+ * which leaves wall-clock marks for the two sd_debug_read_*_ticks calls (calls of up to
+ * SD_TICK_SLOTS requests: larger ones run the ordinary kernel).  sd_debug_profile_read
  * synchronises, reports per-kernel launch counts, total milliseconds and
  * counted bytes since the previous read, and clears them. */
 enum {
@@ -297,6 +298,7 @@ enum {
     SD_K_ACCEPT_SPECULATE = 9, SD_K_COUNT = 10
 };
 #define SD_PROF_MAX_SPANS 8192
+#define SD_TICK_SLOTS 1024
 typedef struct {
     int64_t launches[SD_K_COUNT];
     double ms[SD_K_COUNT];

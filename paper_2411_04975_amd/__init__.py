@@ -5,7 +5,7 @@ include/sd.h; this package is a thin ctypes binding with the same call names.
 There is no CPU fallback: importing the binding without the built shared
 object raises.
 """
-from .binding import (SD_SCOPE_GLOBAL, SD_SCOPE_REQUESTS, SD_STATIC_SCRATCH_BYTES,  # noqa: F401
+from .binding import (SD_SCOPE_GLOBAL, SD_SCOPE_REQUESTS, SD_STATIC_SCRATCH_BYTES, SD_TICK_SLOTS,  # noqa: F401
                       SdError, Trees, lib_path, sd_accept, sd_accept_append,
                       sd_accept_append_speculate, sd_create, sd_debug_profile,
                       sd_debug_profile_read, sd_debug_read_global, sd_debug_read_request_ticks,

@@ -55,6 +55,7 @@ class _Stats(C.Structure):
             "spec_list_rounds", "accept_requests", "accept_len")]
 
 SD_STATIC_SCRATCH_BYTES = 16 << 20
+SD_TICK_SLOTS = 1024   # requests the timing variant of sd_speculate keeps marks for
 
 
 KERNEL_NAMES = ["speculate", "accept", "append", "req_build", "sort_hist", "sort_scan",

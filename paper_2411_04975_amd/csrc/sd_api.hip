@@ -103,7 +103,8 @@ sd_status sd_create(const sd_config *cfg, sd_ctx **out) {
     ok = ok && dev_alloc(&c->s_unit_sa, B * ctx, sb);
     ok = ok && dev_alloc(&c->d_err, SD_DEVERR_N, sb) && dev_alloc(&c->d_entropy, 4, sb) &&
          dev_alloc(&c->d_round_flag, 8, sb);
-    ok = ok && dev_alloc(&c->s_unit_ticks, B * 2 * P * 4 + B * 16 * 8, sb);
+    c->tick_slots = (int32_t)(B < SD_TICK_SLOTS ? B : SD_TICK_SLOTS);
+    ok = ok && dev_alloc(&c->s_unit_ticks, (int64_t)c->tick_slots * (2 * P * 4 + 16 * 8), sb);
     ok = ok && dev_alloc(&c->d_algo_bytes, SD_K_COUNT, sb);
     if (!ok) {
         free_all(c);
@@ -359,8 +360,8 @@ sd_status sd_debug_profile_read(sd_ctx *c, sd_profile *o) {
 
 sd_status sd_debug_read_unit_ticks(sd_ctx *c, uint32_t *h_ticks, int64_t count, int32_t *khz) {
     if (!c || !h_ticks || !khz || count < 0) return SD_ERR_INVALID_ARG;
-    if (count > (int64_t)c->cfg.max_batch_slots * 2 * c->cfg.P * 4)
-        return fail(c, SD_ERR_CAPACITY, "more units than the context holds");
+    if (count > (int64_t)c->tick_slots * 2 * c->cfg.P * 4)
+        return fail(c, SD_ERR_CAPACITY, "more units than the tick buffers hold (SD_TICK_SLOTS requests)");
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
     if (hipDeviceSynchronize() != hipSuccess) return fail(c, SD_ERR_HIP, "device synchronize failed");
     int rate = 0;
@@ -375,15 +376,15 @@ sd_status sd_debug_read_unit_ticks(sd_ctx *c, uint32_t *h_ticks, int64_t count, 
 
 sd_status sd_debug_read_request_ticks(sd_ctx *c, uint32_t *h_ticks, int32_t batch, int32_t *khz) {
     if (!c || !h_ticks || !khz || batch < 0) return SD_ERR_INVALID_ARG;
-    if (batch > c->cfg.max_batch_slots)
-        return fail(c, SD_ERR_CAPACITY, "more requests than the context holds");
+    if (batch > c->tick_slots)
+        return fail(c, SD_ERR_CAPACITY, "more requests than the tick buffers hold (SD_TICK_SLOTS)");
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, SD_ERR_HIP, "hipSetDevice");
     if (hipDeviceSynchronize() != hipSuccess) return fail(c, SD_ERR_HIP, "device synchronize failed");
     int rate = 0;
     if (hipDeviceGetAttribute(&rate, hipDeviceAttributeWallClockRate, c->cfg.device) != hipSuccess)
         return fail(c, SD_ERR_HIP, "hipDeviceGetAttribute");
     *khz = rate;
-    const uint32_t *src = c->s_unit_ticks + (int64_t)c->cfg.max_batch_slots * 2 * c->cfg.P * 4;
+    const uint32_t *src = c->s_unit_ticks + (int64_t)c->tick_slots * 2 * c->cfg.P * 4;
     if (batch && hipMemcpy(h_ticks, src, (size_t)batch * 16 * 8 * sizeof(uint32_t),
                            hipMemcpyDeviceToHost) != hipSuccess)
         return fail(c, SD_ERR_HIP, "hipMemcpy");

@@ -68,6 +68,7 @@ struct sd_ctx {
     uint32_t *s_occ = nullptr;       // [B][max_ctx]: end position e << 7 | common-suffix length L
     int32_t *s_unit_sa = nullptr;    // [B][max_ctx]: per-request room for suffix lists of more
                                      // than 64 occurrences (shared by the pattern lengths)
+    int32_t tick_slots = 0;            // requests the tick buffers have room for: min(max_batch_slots, SD_TICK_SLOTS)
     uint32_t *s_unit_ticks = nullptr;  // [B][2P][4], written by the counting kernel variants
 
     void *static_scratch = nullptr;  // this device's address of the library's static scratch array

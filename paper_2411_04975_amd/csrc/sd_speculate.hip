@@ -2657,8 +2657,9 @@ sd_status launch_speculate(sd_ctx *c, const int32_t *d_slot_ids, int32_t batch, 
     p.counters = c->d_counters;
     p.algo_bytes = c->d_algo_bytes;
     p.unit_ticks = c->s_unit_ticks;
-    p.wg_ticks = c->s_unit_ticks + (int64_t)c->cfg.max_batch_slots * 2 * c->cfg.P * 4;
-    const bool stats = c->prof_mode == 2, ticks = c->prof_mode == 3;
+    p.wg_ticks = c->s_unit_ticks + (int64_t)c->tick_slots * 2 * c->cfg.P * 4;
+    // (the timing variant indexes its marks by request: only calls that the buffers have room for)
+    const bool stats = c->prof_mode == 2, ticks = c->prof_mode == 3 && batch <= c->tick_slots;
     // per wave: frontier 6 arrays, two trees of 3 arrays, staging
     size_t lds_wave = (size_t)c->max_nodes * (3 * sizeof(double) + 9 * sizeof(int32_t)) +
                       (64 + 64 + TC_TOKENS + 128) * sizeof(int32_t);

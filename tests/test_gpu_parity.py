@@ -1163,6 +1163,8 @@ def test_wide_batches_on_thinner_workgroups():
             got = g.speculate(range(nb))
             bad = parity.compare_trees(got, rows(want_v, nb), "batch %d" % nb)
             assert not bad, "\n".join(bad)
+            if nb > sd.SD_TICK_SLOTS:      # the timing variant keeps marks for that many requests
+                continue
             sd.sd_debug_profile(g.ctx, 3)
             timed = g.speculate(range(nb))
             rt, _ = sd.sd_debug_read_request_ticks(g.ctx, nb)
