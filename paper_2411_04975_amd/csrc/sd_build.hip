@@ -26,6 +26,7 @@
 namespace {
 
 constexpr int TB = 256;
+constexpr int LAYOUT_ITEMS = 16;  // tokens per thread of k_layout_text
 
 // text[i + doc(i)] = tokens[i]: document j is shifted right by j to make room for one end
 // marker after each earlier document.
@@ -33,11 +34,13 @@ __global__ __launch_bounds__(TB) void k_layout_text(const int32_t *__restrict__ 
                                                     const int64_t *__restrict__ offs, int32_t n_seq,
                                                     int64_t n_tokens, int32_t *__restrict__ text,
                                                     int32_t vocab, int32_t *err) {
-    // The tokens of a workgroup lie in a few neighbouring documents: two threads find the
-    // documents of its first and last token among all of them, everyone else searches between.
+    // The tokens of a workgroup (LAYOUT_ITEMS per thread) lie in a few neighbouring documents:
+    // two threads find the documents of its first and last token among all of them (a chain of
+    // dependent loads that the whole workgroup waits for: hence the long tiles), everyone else
+    // searches between.
     __shared__ int32_t s_doc[2];
-    const int64_t i0 = (int64_t)blockIdx.x * TB;
-    const int64_t i1 = i0 + TB - 1 < n_tokens - 1 ? i0 + TB - 1 : n_tokens - 1;
+    const int64_t i0 = (int64_t)blockIdx.x * (TB * LAYOUT_ITEMS);
+    const int64_t i1 = i0 + TB * LAYOUT_ITEMS - 1 < n_tokens - 1 ? i0 + TB * LAYOUT_ITEMS - 1 : n_tokens - 1;
     if (threadIdx.x < 2) {
         const int64_t q = threadIdx.x ? i1 : i0;
         int32_t lo = 0, hi = n_seq;  // largest j with offs[j] <= q, in [lo, hi)
@@ -48,20 +51,24 @@ __global__ __launch_bounds__(TB) void k_layout_text(const int32_t *__restrict__ 
         s_doc[threadIdx.x] = lo;
     }
     __syncthreads();
-    int64_t i = i0 + threadIdx.x;
-    if (i >= n_tokens) return;
-    // largest j with offs[j] <= i
-    int32_t lo = s_doc[0], hi = s_doc[1] + 1;  // answer in [lo, hi)
-    while (hi - lo > 1) {
-        int32_t mid = (lo + hi) >> 1;
-        if (offs[mid] <= i) lo = mid; else hi = mid;
+    const int32_t d0 = s_doc[0], d1 = s_doc[1];
+#pragma unroll 4
+    for (int k = 0; k < LAYOUT_ITEMS; k++) {
+        const int64_t i = i0 + (int64_t)k * TB + threadIdx.x;
+        if (i >= n_tokens) break;
+        // largest j with offs[j] <= i
+        int32_t lo = d0, hi = d1 + 1;  // answer in [lo, hi)
+        while (hi - lo > 1) {
+            int32_t mid = (lo + hi) >> 1;
+            if (offs[mid] <= i) lo = mid; else hi = mid;
+        }
+        int32_t t = tokens[i];
+        if (t < 0 || t >= vocab) {
+            atomicOr(&err[SD_DEVERR_TOKEN], 1);
+            t = 0;
+        }
+        text[i + lo] = t;
     }
-    int32_t t = tokens[i];
-    if (t < 0 || t >= vocab) {
-        atomicOr(&err[SD_DEVERR_TOKEN], 1);
-        t = 0;
-    }
-    text[i + lo] = t;
 }
 
 __global__ __launch_bounds__(TB) void k_layout_marks(const int64_t *__restrict__ offs, int32_t n_seq,
@@ -469,7 +476,7 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
     c->g_tokens = n_tokens;
     c->g_docs = n_seq;
     if (n_tokens > 0)
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_layout_text, dim3(nblk(n_tokens)), dim3(TB), 0, d_tokens, d_offsets, n_seq, n_tokens, c->g_text, vocab, c->d_err);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_layout_text, dim3(nblk((n_tokens + LAYOUT_ITEMS - 1) / LAYOUT_ITEMS)), dim3(TB), 0, d_tokens, d_offsets, n_seq, n_tokens, c->g_text, vocab, c->d_err);
     {
         int64_t m = n_seq > SD_TEXT_PAD ? n_seq : SD_TEXT_PAD;
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_layout_marks, dim3(nblk(m)), dim3(TB), 0, d_offsets, n_seq, N, c->g_text);
@@ -494,7 +501,7 @@ sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_
     if (M == 0) return SD_OK;
     int32_t *ntext = c->g_text + N;
     if (n_tokens > 0)
-        SD_LAUNCH(c, SD_K_INSERT, st, k_layout_text, dim3(nblk(n_tokens)), dim3(TB), 0, d_tokens, d_offsets, n_seq, n_tokens, ntext, vocab, c->d_err);
+        SD_LAUNCH(c, SD_K_INSERT, st, k_layout_text, dim3(nblk((n_tokens + LAYOUT_ITEMS - 1) / LAYOUT_ITEMS)), dim3(TB), 0, d_tokens, d_offsets, n_seq, n_tokens, ntext, vocab, c->d_err);
     {
         int64_t m = n_seq > SD_TEXT_PAD ? n_seq : SD_TEXT_PAD;
         SD_LAUNCH(c, SD_K_INSERT, st, k_layout_marks, dim3(nblk(m)), dim3(TB), 0, d_offsets, n_seq, M, ntext);
