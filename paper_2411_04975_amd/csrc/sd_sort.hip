@@ -290,6 +290,10 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_tile_last(const uint64_t *_
     }
 }
 
+// (Entry k * SC_THREADS + t of the tile belongs to thread t: every load and store of a wave
+// covers neighbouring words.  With SC_ITEMS consecutive entries per thread each load
+// instruction touched 64 lines, and the kernel took 311 us for 10M entries, most of it for
+// that and not for the scatter.)
 __global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__restrict__ keys,
                                                            const uint32_t *__restrict__ vals,
                                                            int64_t n,
@@ -298,30 +302,62 @@ __global__ __launch_bounds__(SC_THREADS) void k_rank_apply(const uint64_t *__res
                                                            uint32_t *__restrict__ gid,
                                                            const uint32_t *__restrict__ gid_old,
                                                            const int32_t *__restrict__ run_if) {
-    __shared__ uint32_t s_wave[SC_THREADS / 64];
+    constexpr int NW = SC_THREADS / 64;
+    static_assert(SC_ITEMS * NW == 64, "one wave scans the parts of a tile");
+    __shared__ uint64_t s_edge[SC_ITEMS][NW];  // key of the last lane of (row k, wave w)
+    __shared__ uint32_t s_tot[SC_ITEMS * NW];  // group starts: maximum over (row k, wave w), then
+                                               // over everything before it in the tile
     if (run_if && *run_if == 0) return;
-    const int64_t base = (int64_t)blockIdx.x * SC_TILE + (int64_t)threadIdx.x * SC_ITEMS;
-    uint32_t f[SC_ITEMS];
-    uint32_t s = 0;
-    uint64_t prev = base > 0 && base - 1 < n ? keys[base - 1] : 0ull;
+    const int t = threadIdx.x, lane = t & 63, w = t >> 6;
+    const int64_t base = (int64_t)blockIdx.x * SC_TILE;
+    uint64_t key[SC_ITEMS];
 #pragma unroll
     for (int k = 0; k < SC_ITEMS; k++) {
-        int64_t i = base + k;
-        uint64_t key = i < n ? keys[i] : 0ull;
-        f[k] = i < n && (i == 0 || key != prev) ? (uint32_t)(i + 1) : 0u;
-        prev = key;
-        s = f[k] > s ? f[k] : s;
+        const int64_t i = base + (int64_t)k * SC_THREADS + t;
+        key[k] = i < n ? keys[i] : 0ull;
     }
-    uint32_t ex = block_excl_scanmax_256(s, s_wave, nullptr);
-    const uint32_t before = partials[blockIdx.x];
-    ex = before > ex ? before : ex;
+    const uint64_t before_tile = base > 0 ? keys[base - 1] : 0ull;
+#pragma unroll
+    for (int k = 0; k < SC_ITEMS; k++)
+        if (lane == 63) s_edge[k][w] = key[k];
+    __syncthreads();
+    uint32_t inc[SC_ITEMS];  // running maximum of the group starts inside (row k, wave w)
 #pragma unroll
     for (int k = 0; k < SC_ITEMS; k++) {
-        int64_t i = base + k;
-        ex = f[k] > ex ? f[k] : ex;
+        const int64_t i = base + (int64_t)k * SC_THREADS + t;
+        uint64_t prev = __shfl_up(key[k], 1);
+        if (lane == 0) prev = w > 0 ? s_edge[k][w - 1] : (k > 0 ? s_edge[k > 0 ? k - 1 : 0][NW - 1] : before_tile);
+        uint32_t v = i < n && (i == 0 || key[k] != prev) ? (uint32_t)(i + 1) : 0u;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t u = __shfl_up(v, o);
+            if (lane >= o) v = u > v ? u : v;
+        }
+        inc[k] = v;
+        if (lane == 63) s_tot[k * NW + w] = v;
+    }
+    __syncthreads();
+    if (t < 64) {  // exclusive running maximum over the SC_ITEMS * NW = 64 parts, in array order
+        uint32_t v = s_tot[t];
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t u = __shfl_up(v, o);
+            if (lane >= o) v = u > v ? u : v;
+        }
+        uint32_t ex = __shfl_up(v, 1);
+        if (lane == 0) ex = 0;
+        const uint32_t before = partials[blockIdx.x];
+        s_tot[t] = before > ex ? before : ex;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < SC_ITEMS; k++) {
+        const int64_t i = base + (int64_t)k * SC_THREADS + t;
+        const uint32_t carry = s_tot[k * NW + w];
+        const uint32_t g = inc[k] > carry ? inc[k] : carry;
         if (i < n) {
-            if (!gid_old || gid_old[i] != ex) rank[vals[i]] = ex;
-            gid[i] = ex;
+            if (!gid_old || gid_old[i] != g) rank[vals[i]] = g;
+            gid[i] = g;
         }
     }
 }
