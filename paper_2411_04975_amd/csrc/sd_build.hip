@@ -26,21 +26,25 @@
 namespace {
 
 constexpr int TB = 256;
-constexpr int LAYOUT_ITEMS = 16;  // tokens per thread of k_layout_text
+// tokens per thread of k_layout_text
+inline int layout_items(int64_t n_tokens) { return n_tokens >= (1 << 20) ? 16 : 1; }
 
 // text[i + doc(i)] = tokens[i]: document j is shifted right by j to make room for one end
 // marker after each earlier document.
 __global__ __launch_bounds__(TB) void k_layout_text(const int32_t *__restrict__ tokens,
                                                     const int64_t *__restrict__ offs, int32_t n_seq,
                                                     int64_t n_tokens, int32_t *__restrict__ text,
-                                                    int32_t vocab, int32_t *err) {
-    // The tokens of a workgroup (LAYOUT_ITEMS per thread) lie in a few neighbouring documents:
-    // two threads find the documents of its first and last token among all of them (a chain of
-    // dependent loads that the whole workgroup waits for: hence the long tiles), everyone else
-    // searches between.
+                                                    int32_t vocab, int32_t *err, int items) {
+    // The tokens of a workgroup (`items` per thread: many for a corpus, one for the few
+    // documents of an insertion) lie in a few neighbouring documents: two threads find the
+    // documents of its first and last token among all of them (a chain of dependent loads that
+    // the whole workgroup waits for: hence long tiles for long inputs); the offsets of the
+    // documents between go to LDS, where everyone else searches.
+    constexpr int LDS_DOCS = 128;
     __shared__ int32_t s_doc[2];
-    const int64_t i0 = (int64_t)blockIdx.x * (TB * LAYOUT_ITEMS);
-    const int64_t i1 = i0 + TB * LAYOUT_ITEMS - 1 < n_tokens - 1 ? i0 + TB * LAYOUT_ITEMS - 1 : n_tokens - 1;
+    __shared__ int64_t s_offs[LDS_DOCS];
+    const int64_t i0 = (int64_t)blockIdx.x * TB * items;
+    const int64_t i1 = i0 + (int64_t)TB * items - 1 < n_tokens - 1 ? i0 + (int64_t)TB * items - 1 : n_tokens - 1;
     if (threadIdx.x < 2) {
         const int64_t q = threadIdx.x ? i1 : i0;
         int32_t lo = 0, hi = n_seq;  // largest j with offs[j] <= q, in [lo, hi)
@@ -52,15 +56,17 @@ __global__ __launch_bounds__(TB) void k_layout_text(const int32_t *__restrict__ 
     }
     __syncthreads();
     const int32_t d0 = s_doc[0], d1 = s_doc[1];
-#pragma unroll 4
-    for (int k = 0; k < LAYOUT_ITEMS; k++) {
+    const bool in_lds = d1 - d0 < LDS_DOCS;
+    if (in_lds && (int)threadIdx.x <= d1 - d0) s_offs[threadIdx.x] = offs[d0 + threadIdx.x];
+    __syncthreads();
+    for (int k = 0; k < items; k++) {
         const int64_t i = i0 + (int64_t)k * TB + threadIdx.x;
         if (i >= n_tokens) break;
         // largest j with offs[j] <= i
         int32_t lo = d0, hi = d1 + 1;  // answer in [lo, hi)
         while (hi - lo > 1) {
             int32_t mid = (lo + hi) >> 1;
-            if (offs[mid] <= i) lo = mid; else hi = mid;
+            if ((in_lds ? s_offs[mid - d0] : offs[mid]) <= i) lo = mid; else hi = mid;
         }
         int32_t t = tokens[i];
         if (t < 0 || t >= vocab) {
@@ -476,7 +482,7 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
     c->g_tokens = n_tokens;
     c->g_docs = n_seq;
     if (n_tokens > 0)
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_layout_text, dim3(nblk((n_tokens + LAYOUT_ITEMS - 1) / LAYOUT_ITEMS)), dim3(TB), 0, d_tokens, d_offsets, n_seq, n_tokens, c->g_text, vocab, c->d_err);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_layout_text, dim3(nblk((n_tokens + layout_items(n_tokens) - 1) / layout_items(n_tokens))), dim3(TB), 0, d_tokens, d_offsets, n_seq, n_tokens, c->g_text, vocab, c->d_err, layout_items(n_tokens));
     {
         int64_t m = n_seq > SD_TEXT_PAD ? n_seq : SD_TEXT_PAD;
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_layout_marks, dim3(nblk(m)), dim3(TB), 0, d_offsets, n_seq, N, c->g_text);
@@ -501,7 +507,7 @@ sd_status sd_insert_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_
     if (M == 0) return SD_OK;
     int32_t *ntext = c->g_text + N;
     if (n_tokens > 0)
-        SD_LAUNCH(c, SD_K_INSERT, st, k_layout_text, dim3(nblk((n_tokens + LAYOUT_ITEMS - 1) / LAYOUT_ITEMS)), dim3(TB), 0, d_tokens, d_offsets, n_seq, n_tokens, ntext, vocab, c->d_err);
+        SD_LAUNCH(c, SD_K_INSERT, st, k_layout_text, dim3(nblk((n_tokens + layout_items(n_tokens) - 1) / layout_items(n_tokens))), dim3(TB), 0, d_tokens, d_offsets, n_seq, n_tokens, ntext, vocab, c->d_err, layout_items(n_tokens));
     {
         int64_t m = n_seq > SD_TEXT_PAD ? n_seq : SD_TEXT_PAD;
         SD_LAUNCH(c, SD_K_INSERT, st, k_layout_marks, dim3(nblk(m)), dim3(TB), 0, d_offsets, n_seq, M, ntext);
