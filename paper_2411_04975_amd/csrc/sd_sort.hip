@@ -2,10 +2,10 @@
 // sorted key array (a device-wide prefix maximum), both hand-written for 64-wide wavefronts.
 // Used by the suffix-array construction in sd_build.hip.
 //
-// One pass = three launches: per-tile digit histogram, per-digit prefix sums along the tiles,
-// stable scatter.  Inside a tile the stable rank of a key among keys with the same
-// digit comes from wave-wide ballots (all lanes holding the same digit find each other with
-// one ballot per digit bit), so no shared-memory atomics are contended.  The scatter first
+// One pass = three launches: per-tile digit histogram (one LDS add per key into the wave's own
+// counters), per-digit prefix sums along the tiles, stable scatter.  Inside a tile the stable
+// rank of a key among keys with the same digit comes from wave-wide ballots (all lanes holding
+// the same digit find each other with one ballot per digit bit).  The scatter first
 // orders the tile by digit in LDS, so that global writes go out as runs of neighbouring lanes.
 #include "sd_internal.h"
 
@@ -63,20 +63,24 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_hist(const uint64_t *__res
                                                            uint32_t *__restrict__ tile_hist,
                                                            int64_t ntiles,
                                                            const int32_t *__restrict__ run_if) {
-    __shared__ volatile uint32_t s_cnt[RS_WAVES][RS_BINS];
+    __shared__ uint32_t s_cnt[RS_WAVES][RS_BINS];
     if (run_if && *run_if == 0) return;  // same for the whole grid: the pass is not needed
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, w = tid >> 6;
     for (int i = tid; i < RS_WAVES * RS_BINS; i += RS_THREADS) (&s_cnt[0][0])[i] = 0;
     __syncthreads();
     const int64_t base = (int64_t)blockIdx.x * RS_TILE;
-    const uint64_t lt = lanemask_lt();
-#pragma unroll 4
+    // all loads of the tile first, then one LDS add per key into the wave's own counters (the
+    // counts need no order, unlike the ranks of the scatter)
+    uint64_t key[RS_ITEMS];
+#pragma unroll
     for (int k = 0; k < RS_ITEMS; k++) {
         int64_t idx = base + (int64_t)k * RS_THREADS + tid;
-        bool valid = idx < n;
-        uint32_t d = valid ? (uint32_t)((keys[idx] >> shift) & (RS_BINS - 1)) : 0u;
-        uint64_t peers = match_digit(d, valid);
-        if (valid && (peers & lt) == 0) s_cnt[w][d] = s_cnt[w][d] + (uint32_t)__popcll(peers);
+        key[k] = idx < n ? keys[idx] : 0ull;
+    }
+#pragma unroll
+    for (int k = 0; k < RS_ITEMS; k++) {
+        int64_t idx = base + (int64_t)k * RS_THREADS + tid;
+        if (idx < n) atomicAdd(&s_cnt[w][(uint32_t)((key[k] >> shift) & (RS_BINS - 1))], 1u);
     }
     __syncthreads();
     uint32_t tot = 0;
