@@ -216,17 +216,6 @@ __global__ __launch_bounds__(TB) void k_rank_update(const uint32_t *__restrict__
     }
 }
 
-// final suffix array (the second-token column, tok1[i] = second token of suffix i, is written
-// after the first sort: inside the bucket of a first token the column is sorted, so the second
-// pattern token is located by a coalesced scan of the column instead of dependent
-// (suffix array -> text) probes)
-__global__ __launch_bounds__(TB) void k_finish_sa(const uint32_t *__restrict__ vals, int64_t N,
-                                                  int32_t *__restrict__ sa) {
-    int64_t i = (int64_t)blockIdx.x * TB + threadIdx.x;
-    if (i >= N) return;
-    sa[i] = (int32_t)vals[i];
-}
-
 // bucket[c] = first index whose suffix starts with token code (token + 1) >= c
 __global__ __launch_bounds__(TB) void k_bucket(const int32_t *__restrict__ text,
                                                const int32_t *__restrict__ sa, int64_t N,
@@ -490,8 +479,14 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
     if (N > 0) {
         const int cur = build_sorted_positions(c, c->g_text, N, c->g_tok1, st);
         if (cur < 0) return SD_ERR_HIP;
-        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_finish_sa, dim3(nblk(N)), dim3(TB), 0, c->b_vals[cur], N,
-                  c->g_sa);
+        // The sorted positions are the suffix array: the buffer they are in becomes g_sa and the
+        // old g_sa a scratch buffer (same sizes; a copy took 17 us for 10M positions).  The
+        // second-token column was written after the first sort: inside the bucket of a first
+        // token it is sorted, so the second pattern token is located by a coalesced scan of the
+        // column instead of dependent (suffix array -> text) probes.
+        int32_t *old_sa = c->g_sa;
+        c->g_sa = reinterpret_cast<int32_t *>(c->b_vals[cur]);
+        c->b_vals[cur] = reinterpret_cast<uint32_t *>(old_sa);
     }
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, N, vocab, c->g_bucket);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
