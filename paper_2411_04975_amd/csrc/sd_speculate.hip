@@ -1012,7 +1012,7 @@ __device__ __forceinline__ void push_children(Frontier &f, int hole, Stage &sg, 
     }
     // Wide node: a child that can still reach min_score has at least c_min occurrences, so its
     // run contains one of the positions lo, lo + c_min, lo + 2 c_min, ...  Probe those, then
-    // bracket the run of each distinct probed token by binary search.  The bound is taken a
+    // bracket the run of each distinct probed token by a multi-way search.  The bound is taken a
     // little low (factor 1 - 1e-9) so that rounding can never hide an admissible child; the
     // exact binary64 test below decides.
     frontier_close(f, hole);
@@ -2598,7 +2598,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
 }  // namespace
 
 // Scratch memory of sd_speculate_static: the occurrence records and suffix-list rows of its
-// requests (12 bytes per request and context token), in place of the buffers a context
+// requests (8 bytes per request and context token), in place of the buffers a context
 // allocates.  Every device the library runs on holds its own copy of the array at its own
 // address; host code reaches it only through the address that hipGetSymbolAddress reports for
 // the device that is current (kept per device in scratch_ptr, and per context).
