@@ -129,18 +129,22 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
     const uint64_t *__restrict__ kin, const uint32_t *__restrict__ vin, uint64_t *__restrict__ kout,
     uint32_t *__restrict__ vout, int64_t n, int shift, const uint32_t *__restrict__ row_excl,
     const uint32_t *__restrict__ row_total, int64_t ntiles, const int32_t *__restrict__ run_if) {
+    // 52 KB of LDS, so that three workgroups share a compute unit (with 54 KB two did): the
+    // per-wave digit counts are 16-bit (a tile has 4096 keys), and the block scans' partial
+    // sums sit where the keys go afterwards
     __shared__ uint64_t s_keys[RS_TILE];
     __shared__ uint32_t s_vals[RS_TILE];
-    __shared__ volatile uint32_t s_wcnt[RS_WAVES][RS_BINS];
+    __shared__ volatile uint16_t s_wcnt[RS_WAVES][RS_BINS];
     __shared__ uint32_t s_excl[RS_BINS];
     __shared__ uint32_t s_gbase[RS_BINS];
-    __shared__ uint32_t s_wave[RS_WAVES];
+    uint32_t *s_wave = reinterpret_cast<uint32_t *>(s_keys);  // (the keys arrive later)
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     if (run_if && *run_if == 0) return;
     for (int i = tid; i < RS_WAVES * RS_BINS; i += RS_THREADS) (&s_wcnt[0][0])[i] = 0;
     __syncthreads();
     const int64_t base = (int64_t)blockIdx.x * RS_TILE;
     const int cnt = (int)((n - base) < RS_TILE ? (n - base) : RS_TILE);
+    static_assert(RS_TILE <= 65535, "16-bit digit counts");
     const uint64_t lt = lanemask_lt();
 
     uint64_t key[RS_ITEMS];
@@ -163,7 +167,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
         uint64_t peers = match_digit(d, valid);
         uint32_t pre = s_wcnt[w][d];
         uint32_t below = (uint32_t)__popcll(peers & lt);
-        if (valid && below == 0) s_wcnt[w][d] = pre + (uint32_t)__popcll(peers);
+        if (valid && below == 0) s_wcnt[w][d] = (uint16_t)(pre + (uint32_t)__popcll(peers));
         rnk[k] = pre + below;
     }
     __syncthreads();
@@ -173,7 +177,7 @@ __global__ __launch_bounds__(RS_THREADS) void k_radix_scatter(
 #pragma unroll
         for (int i = 0; i < RS_WAVES; i++) {
             uint32_t c = s_wcnt[i][d];
-            s_wcnt[i][d] = acc;  // keys of digit d held by earlier waves of this tile
+            s_wcnt[i][d] = (uint16_t)acc;  // keys of digit d held by earlier waves of this tile
             acc += c;
         }
         uint32_t ex = block_excl_scan_256(acc, s_wave, nullptr);
