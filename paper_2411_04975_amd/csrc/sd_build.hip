@@ -216,6 +216,23 @@ __global__ __launch_bounds__(TB) void k_rank_update(const uint32_t *__restrict__
     }
 }
 
+// bucket[c] = first place whose key starts with a token code >= c, from the keys of the first
+// sort (leading token code in the bits from tok_bits up): what k_bucket finds through suffix
+// array and text, with one load per step of the search instead of two dependent ones.  No later
+// step moves an entry out of its first token's bucket.
+__global__ __launch_bounds__(TB) void k_bucket_keys(const uint64_t *__restrict__ keys, int64_t N,
+                                                    int tok_bits, int32_t vocab,
+                                                    int32_t *__restrict__ bucket) {
+    int64_t c = (int64_t)blockIdx.x * TB + threadIdx.x;
+    if (c > (int64_t)vocab + 1) return;
+    int64_t lo = 0, hi = N;
+    while (lo < hi) {
+        int64_t mid = (lo + hi) >> 1;
+        if ((int64_t)(keys[mid] >> tok_bits) < c) lo = mid + 1; else hi = mid;
+    }
+    bucket[c] = (int32_t)lo;
+}
+
 // bucket[c] = first index whose suffix starts with token code (token + 1) >= c
 __global__ __launch_bounds__(TB) void k_bucket(const int32_t *__restrict__ text,
                                                const int32_t *__restrict__ sa, int64_t N,
@@ -417,8 +434,10 @@ static int build_sorted_positions(sd_ctx *c, const int32_t *text, int64_t N, int
     const int tok_bits = sd_bits_for((uint64_t)c->cfg.vocab);  // codes 0..vocab
     SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_init_keys, dim3(nblk(N)), dim3(TB), 0, text, N, tok_bits, c->b_keys[0], c->b_vals[0]);
     int cur = sd_sort_pairs(c, N, 2 * tok_bits, 0, st);
-    if (tok1_out)
+    if (tok1_out) {  // (the global build: second-token column and bucket table come from these keys)
         SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_tok1_from_keys, dim3(nblk(N)), dim3(TB), 0, c->b_keys[cur], N, tok_bits, tok1_out, c->g_tok1s);
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_bucket_keys, dim3(nblk((int64_t)c->cfg.vocab + 2)), dim3(TB), 0, c->b_keys[cur], N, tok_bits, c->cfg.vocab, c->g_bucket);
+    }
     const int rank_bits = sd_bits_for((uint64_t)N);  // ranks 0..N
     // So far the positions are ordered by their first h = 2 tokens.  Each round first tries the
     // in-tile reordering (enough once no group is longer than its halo, which stays true for
@@ -488,7 +507,8 @@ sd_status sd_build_global_impl(sd_ctx *c, const int32_t *d_tokens, const int64_t
         c->g_sa = reinterpret_cast<int32_t *>(c->b_vals[cur]);
         c->b_vals[cur] = reinterpret_cast<uint32_t *>(old_sa);
     }
-    SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, N, vocab, c->g_bucket);
+    if (N == 0)  // (an empty index: every bucket is empty)
+        SD_LAUNCH(c, SD_K_BUILD_OTHER, st, k_bucket, dim3(nblk((int64_t)vocab + 2)), dim3(TB), 0, c->g_text, c->g_sa, N, vocab, c->g_bucket);
     return hipGetLastError() == hipSuccess ? SD_OK : SD_ERR_HIP;
 }
 
