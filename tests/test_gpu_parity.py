@@ -399,18 +399,21 @@ def test_fused_step_end_and_next_draft_in_one_launch():
         g.close()
 
 
-def test_accept_on_synthetic_trees():
+@pytest.mark.parametrize("mn", [256, 64, 16])
+def test_accept_on_synthetic_trees(mn):
     """sd_accept against the oracle's walk on trees that sd_speculate would not produce by
-    itself: chains of every length up to the largest tree (short accepted paths are walked,
-    long ones settled by pointer jumping), bushy random trees, targets that stop the walk
-    anywhere, empty trees."""
+    itself: chains of every length up to the largest tree, bushy random trees, targets that
+    stop the walk anywhere, empty trees; for trees of up to 256 nodes (pointer jumping in LDS)
+    and of up to 64 and 16 (one node per lane, in registers; a chain of 64 accepted to the
+    end takes its bonus token from target position 64)."""
     import torch
     import paper_2411_04975_amd as sd
-    rng = np.random.default_rng(17)
-    mn = 256
+    rng = np.random.default_rng(17 + mn)
     cases = []
-    for L in (0, 1, 2, 7, 8, 9, 10, 63, 64, 65, 200, 256):       # a chain accepted up to node L
-        n = 256
+    for L in (0, 1, 2, 7, 8, 9, 10, 15, 16, 63, 64, 65, 200, 256):  # a chain accepted up to node L
+        if L > mn:
+            continue
+        n = mn
         tok = rng.integers(0, 50, n).astype(np.int32)
         par = np.arange(-1, n - 1, dtype=np.int32)
         tgt = np.empty(n + 1, np.int32)
@@ -440,7 +443,7 @@ def test_accept_on_synthetic_trees():
         cases.append((n, tok, par, tgt))
     B = len(cases)
     dev = torch.device("cuda", 0)
-    ctx = sd.sd_create(1000, 8, 4, 64.0, 0.1, B, 16, 16, 0)        # floor(alpha P) = 256
+    ctx = sd.sd_create(1000, 8, 4, mn / 4.0, 0.1, B, 16, 16, 0)    # floor(alpha P) = mn
     try:
         tr = sd.Trees(B, mn, dev)
         toks = np.full((B, mn), -1, np.int32)
@@ -1071,6 +1074,53 @@ def test_first_token_buckets_around_the_scan_limits(n):
         bad = parity.compare_trees(got, want, "bucket of %d" % n)
         assert not bad, "\n".join(bad)
         assert int((want["source"] == 0).sum()) >= B // 2
+    finally:
+        g.close()
+
+
+@pytest.mark.parametrize("copies,alphabet", [(3, 50), (90, 50), (90, 3), (6000, 3)])
+def test_longest_patterns(copies, alphabet):
+    """P = 64, the largest pattern length the library takes, with D = 140 and alpha 1.5 (trees
+    of up to 96 nodes): contexts end inside text that the corpus holds `copies` times, so that
+    patterns of every length up to 64 match, at once from the suffixes that start with the last
+    two tokens (few copies) or one pattern length at a time, singly above length 32 (many
+    copies; a three-letter alphabet makes the first tokens' buckets wide and the ranges long),
+    and the request's own index sees left-extensions of up to 64 tokens."""
+    rng = np.random.default_rng(64000 + copies + alphabet)
+    vocab, D, P, alpha, ms = 60, 140, 64, 1.5, 0.02
+    piece = rng.integers(0, alphabet, 200).astype(np.int32)
+    docs = []
+    for i in range(copies):
+        a = int(rng.integers(0, 60))
+        d = piece[a:a + int(rng.integers(100, 140))].copy()
+        if i % 3 == 0:
+            d[int(rng.integers(0, len(d)))] = int(rng.integers(0, alphabet))    # a mutation
+        docs.append(np.concatenate([rng.integers(0, alphabet, int(rng.integers(0, 9))).astype(np.int32), d]))
+    docs.append(rng.integers(0, alphabet, 300).astype(np.int32))
+    ctxs = []
+    for i in range(12):
+        e = int(rng.integers(70, 190))
+        x = piece[max(0, e - int(rng.integers(1, 150))):e].copy()
+        if i % 4 == 1:                                   # the context repeats its own tail further up
+            x = np.concatenate([x, rng.integers(0, alphabet, 5).astype(np.int32), x[-70:]])
+        if i % 4 == 2 and len(x) > 40:                   # a break 40 tokens before the end
+            x[-40] = (int(x[-40]) + 1) % alphabet
+        ctxs.append(x.astype(np.int32))
+    B = len(ctxs)
+    n_pos = sum(len(d) for d in docs) + len(docs)
+    g = parity.GpuPath(vocab, D, P, alpha, ms, B, 400, n_pos)
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), ctxs)
+        got = g.speculate(range(B))
+        tg = oracle.Trie(D)
+        for d in docs:
+            tg.add_doc(d)
+        want = parity.oracle_speculate_batch(tg, ctxs, D, P, alpha, ms, g.max_nodes)
+        bad = parity.compare_trees(got, want, "P = 64, %d copies, alphabet %d" % (copies, alphabet))
+        assert not bad, "\n".join(bad)
+        assert int(want["match_len"].max()) > 32, "a pattern longer than 32 tokens wins somewhere"
+        assert int((want["n_nodes"] > 0).sum()) >= B // 2
     finally:
         g.close()
 
