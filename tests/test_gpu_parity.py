@@ -11,6 +11,11 @@ from workloads import make_workload, scaled
 pytestmark = pytest.mark.gpu
 
 
+def sd_read_global(g):
+    import paper_2411_04975_amd as sd
+    return sd.sd_debug_read_global(g.ctx)
+
+
 def _run_workload(w, check_accept=True, slots=None):
     docs = w.docs()
     contexts = [w.contexts[b] for b in range(w.batch)]
@@ -1074,6 +1079,48 @@ def test_first_token_buckets_around_the_scan_limits(n):
         bad = parity.compare_trees(got, want, "bucket of %d" % n)
         assert not bad, "\n".join(bad)
         assert int((want["source"] == 0).sum()) >= B // 2
+    finally:
+        g.close()
+
+
+def test_largest_vocabulary_and_depth():
+    """vocab = 2^24 and D = 255, the largest the library takes: token codes of 25 bits (the
+    first sort's keys hold two of them; the occurrence sort's keys then hold two tokens instead
+    of three), suffixes compared on 255 tokens.  A handful of token ids from the top of the
+    range, in contexts whose last token occurs a few hundred times (several sorted runs that
+    are merged; equal keys that the tokens beyond the key must order) and a corpus that repeats
+    a long piece, so that matches and chains run deep."""
+    rng = np.random.default_rng(224)
+    vocab, D, P, alpha, ms = 1 << 24, 255, 8, 2.0, 0.02
+    ids = np.array([vocab - 1, vocab - 2, vocab - 77, 1 << 23, (1 << 23) + 1, 3, 0], np.int32)
+    piece = ids[rng.integers(0, len(ids), 400)]
+    docs = [piece[a:a + 300].copy() for a in (0, 20, 50, 90)]
+    docs.append(ids[rng.integers(0, 3, 500)])
+    ctxs = []
+    for i in range(10):
+        body = ids[rng.integers(0, 3 if i % 2 else len(ids), int(rng.integers(150, 900)))]
+        e = int(rng.integers(100, 390))
+        if i % 3 == 0:      # a context that repeats a piece of its own, which the corpus does not hold
+            unit = ids[rng.integers(0, len(ids), 37)]
+            ctxs.append(np.concatenate([body, np.tile(unit, 9)[:-int(rng.integers(1, 30))]]).astype(np.int32))
+        else:
+            ctxs.append(np.concatenate([body, piece[e - 60:e]]).astype(np.int32))
+    B = len(ctxs)
+    n_pos = sum(len(d) for d in docs) + len(docs)
+    g = parity.GpuPath(vocab, D, P, alpha, ms, B, 1400, n_pos)
+    try:
+        g.build_global(docs)
+        text, sa = sd_read_global(g)
+        assert _sorted_on_D(text, sa, D)[0]
+        g.build_requests(range(B), ctxs)
+        got = g.speculate(range(B))
+        tg = oracle.Trie(D)
+        for d in docs:
+            tg.add_doc(d)
+        want = parity.oracle_speculate_batch(tg, ctxs, D, P, alpha, ms, g.max_nodes)
+        bad = parity.compare_trees(got, want, "vocab 2^24, D 255")
+        assert not bad, "\n".join(bad)
+        assert int((want["source"] == 1).sum()) >= 1 and int((want["source"] == 0).sum()) >= 1
     finally:
         g.close()
 
