@@ -1125,16 +1125,18 @@ def test_largest_vocabulary_and_depth():
         g.close()
 
 
-@pytest.mark.parametrize("copies,alphabet", [(3, 50), (90, 50), (90, 3), (6000, 3)])
-def test_longest_patterns(copies, alphabet):
+@pytest.mark.parametrize("copies,alphabet,alpha", [(3, 50, 1.5), (90, 50, 1.5), (90, 3, 1.5), (6000, 3, 1.5),
+                                                   (90, 50, 4.0), (6000, 3, 4.0)])
+def test_longest_patterns(copies, alphabet, alpha):
     """P = 64, the largest pattern length the library takes, with D = 140 and alpha 1.5 (trees
-    of up to 96 nodes): contexts end inside text that the corpus holds `copies` times, so that
+    of up to 96 nodes) or 4 (256 nodes, the largest tree; fewer waves per workgroup then, for
+    the LDS their frontiers take): contexts end inside text that the corpus holds `copies` times, so that
     patterns of every length up to 64 match, at once from the suffixes that start with the last
     two tokens (few copies) or one pattern length at a time, singly above length 32 (many
     copies; a three-letter alphabet makes the first tokens' buckets wide and the ranges long),
     and the request's own index sees left-extensions of up to 64 tokens."""
     rng = np.random.default_rng(64000 + copies + alphabet)
-    vocab, D, P, alpha, ms = 60, 140, 64, 1.5, 0.02
+    vocab, D, P, ms = 60, 140, 64, 0.02
     piece = rng.integers(0, alphabet, 200).astype(np.int32)
     docs = []
     for i in range(copies):
