@@ -1170,6 +1170,35 @@ def test_longest_patterns(copies, alphabet, alpha):
         assert not bad, "\n".join(bad)
         assert int(want["match_len"].max()) > 32, "a pattern longer than 32 tokens wins somewhere"
         assert int((want["n_nodes"] > 0).sum()) >= B // 2
+        # a fused step on these trees (more than 64 nodes: the acceptance settles them in LDS):
+        # the targets follow each draft's first-child chain for some nodes, then differ
+        mn = g.max_nodes
+        tgt = np.full((B, mn + 1), vocab - 1, np.int32)
+        tries, ctx2, exp = [], [], []
+        for b in range(B):
+            n = int(want["n_nodes"][b])
+            v = -1
+            for _ in range(int(rng.integers(0, 90))):
+                kids = [j for j in range(n) if want["parents"][b, j] == v]
+                if not kids:
+                    break
+                tgt[b, v + 1] = want["tokens"][b, kids[0]]
+                v = kids[0]
+            L, path, bonus = oracle.accept(want["tokens"][b, :n], want["parents"][b, :n], tgt[b])
+            new = np.array([int(want["tokens"][b, j]) for j in path] + [int(bonus)], np.int32)
+            exp.append((L, list(path), bonus))
+            ctx2.append(np.concatenate([ctxs[b], new]))
+            tr = oracle.Trie(D)
+            tr.append(ctx2[b])
+            tries.append(tr)
+        al, ap, bo, got2 = g.accept_append_speculate(range(B), tgt)
+        for b in range(B):
+            L, path, bonus = exp[b]
+            assert al[b] == L and bo[b] == bonus and list(ap[b, :L]) == path, b
+        assert max(e[0] for e in exp) > 40
+        want2 = parity.oracle_speculate_batch(tg, ctx2, D, P, alpha, ms, mn, request_tries=tries)
+        bad = parity.compare_trees(got2, want2, "fused step at P = 64")
+        assert not bad, "\n".join(bad)
     finally:
         g.close()
 
