@@ -1039,6 +1039,47 @@ def test_suffix_array_with_long_and_short_groups(D):
         g.close()
 
 
+def test_global_build_captured_into_a_graph():
+    """A build enqueued on a stream that is being captured cannot wait for the stream to see
+    which sorting rounds need their device-wide fall-back: it enqueues every round with its
+    fall-back behind a device-side switch.  The corpus has runs of one token (rounds that fall
+    back) next to random text; the graph is replayed twice, with other work in between, and the
+    index must be sorted on D tokens and draft like the oracle each time."""
+    import torch
+    import paper_2411_04975_amd as sd
+    rng = np.random.default_rng(78)
+    D, P, alpha, ms, vocab = 16, 6, 2.0, 0.05, 64
+    docs = [np.full(300, 7, np.int32), rng.integers(0, 50, 3000).astype(np.int32),
+            np.tile(np.array([1, 2, 3], np.int32), 400), np.zeros(0, np.int32),
+            np.array([9], np.int32), rng.integers(0, 3, 2500).astype(np.int32)]
+    ctxs = [np.concatenate([rng.integers(0, 50, 20), d[5:5 + 12]]).astype(np.int32)
+            for d in (docs[1], docs[2], docs[5], docs[0])]
+    N = sum(len(d) for d in docs) + len(docs)
+    g = parity.GpuPath(vocab, D, P, alpha, ms, len(ctxs), 64, N)
+    try:
+        d_tok, d_off, n = g._seqs(docs)
+        g.build_global([np.array([5, 5, 5], np.int32)])       # something else first
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            sd.sd_index_build(g.ctx, sd.SD_SCOPE_GLOBAL, None, d_tok, d_off, n)
+        tg = oracle.Trie(D)
+        for d in docs:
+            tg.add_doc(d)
+        want = parity.oracle_speculate_batch(tg, ctxs, D, P, alpha, ms, g.max_nodes)
+        g.build_requests(range(len(ctxs)), ctxs)
+        for rep in range(2):
+            gr.replay()
+            torch.cuda.synchronize()
+            text, sa = sd.sd_debug_read_global(g.ctx)
+            assert len(sa) == N and np.array_equal(np.sort(sa), np.arange(N))
+            assert _sorted_on_D(text, sa, D)[0]
+            bad = parity.compare_trees(g.speculate(range(len(ctxs))), want, "replay %d" % rep)
+            assert not bad, "\n".join(bad)
+            _ = (torch.arange(1000, device=g.dev) * 2).sum().item()
+    finally:
+        g.close()
+
+
 @pytest.mark.parametrize("n", [255, 256, 257, 640, 1023, 1024, 1025, 2500, 4095, 4096, 4097, 6000])
 def test_first_token_buckets_around_the_scan_limits(n):
     """The second pattern token is located inside the first token's bucket by one of three
