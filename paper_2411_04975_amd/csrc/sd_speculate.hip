@@ -835,6 +835,7 @@ __device__ __forceinline__ void frontier_put(Frontier &f, int hole, bool cand, d
 // ever asked for deeper tokens, so each slot's window moves forward only.  With W tokens per
 // slot one coalesced fill serves W levels of the tree: expansion then runs out of LDS.
 constexpr int TC_TOKENS = 512;
+constexpr int FILL_U = TC_TOKENS / 64;  // loads per lane that fill all the windows of a wave
 constexpr int CB_NONE = -(1 << 30);
 constexpr int CHAIN_MAX_M = 8;  // widest node the unary-run shortcut looks at
 constexpr int MED_MAX = 256;  // widest node whose suffixes are all read (a multiple of 64)
@@ -877,10 +878,21 @@ __device__ __forceinline__ int stage_node(Stage &sg, const int32_t *__restrict__
     if (__ballot(miss)) {  // move the windows of this node's suffixes to depth d
         wsync();
         if (in) sg.cb[slot] = d;
+        // (at most TC_TOKENS tokens, FILL_U loads per lane, all of them in flight together: a
+        // loop of load, wait, store took a memory round trip per 64 tokens)
         const int total = m << sg.wlog;
-        for (int idx = lane; idx < total; idx += 64) {
-            int ii = slot0 + (idx >> sg.wlog), k = idx & (W - 1);
-            sg.tc[(ii << sg.wlog) + k] = text[(int64_t)sg.pos[ii] + d + k];
+        int32_t v[FILL_U];
+#pragma unroll
+        for (int u = 0; u < FILL_U; u++) {
+            const int idx = u * 64 + lane;
+            v[u] = 0;
+            if (u * 64 < total && idx < total)
+                v[u] = text[(int64_t)sg.pos[slot0 + (idx >> sg.wlog)] + d + (idx & (W - 1))];
+        }
+#pragma unroll
+        for (int u = 0; u < FILL_U; u++) {
+            const int idx = u * 64 + lane;
+            if (u * 64 < total && idx < total) sg.tc[(slot0 << sg.wlog) + idx] = v[u];
         }
         wsync();
         mycb = d;
@@ -1239,17 +1251,32 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         int32_t abase = 0;
         uint32_t nexttok = DEAD, n2 = DEAD, cand = DEAD;
         // token windows: W tokens per chain from the element after its head on
-        auto fill = [&]() {
+        // (`need` <= W tokens per chain are fetched, rounded up to a power of two; all loads in
+        // flight together)
+        auto fill = [&](int need) {
             wsync();
-            const int total = j << wlog;
+            int flog = 3;
+            while ((1 << flog) < need) flog++;
+            const int total = j << flog;  // <= TC_TOKENS
             const int32_t adv = hdep - cdepv;  // elements of the chain taken so far
-            for (int b0 = 0; b0 < total; b0 += 64) {
-                const int idx = b0 + lane, q = (idx >> wlog) & 63;
-                const int32_t pq = __shfl(pos0, q), aq = __shfl(adv, q);  // all lanes take part
-                if (idx < total) {
-                    sg.tc[idx] = text[(int64_t)pq + aq + (idx & (W - 1))];
-                    SD_CNT(4);
+            int32_t v[FILL_U];
+#pragma unroll
+            for (int u = 0; u < FILL_U; u++) {
+                const int idx = u * 64 + lane, q = (idx >> flog) & 63;
+                v[u] = 0;
+                if (u * 64 < total) {
+                    const int32_t pq = __shfl(pos0, q), aq = __shfl(adv, q);  // all lanes take part
+                    if (idx < total) {
+                        v[u] = text[(int64_t)pq + aq + (idx & ((1 << flog) - 1))];
+                        SD_CNT(4);
+                    }
                 }
+            }
+#pragma unroll
+            for (int u = 0; u < FILL_U; u++) {
+                const int idx = u * 64 + lane;
+                if (u * 64 < total && idx < total)
+                    sg.tc[((idx >> flog) << wlog) + (idx & ((1 << flog) - 1))] = v[u];
             }
             wsync();
             abase = base + 1 - hdep;
@@ -1272,8 +1299,8 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         // a chain moves by at most one element per step and looks two elements ahead
         const int burst = W - 2 < 64 ? W - 2 : 64;
         while (nn < KK && !done) {
-            fill();
             const int lim = KK - nn < burst ? KK - nn : burst;
+            fill(lim + 2);
             int32_t otok = 0, opar = 0;  // lane k: the node taken in step k of this burst
             int k = 0;
             for (; k < lim; k++) {
