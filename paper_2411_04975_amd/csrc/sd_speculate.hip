@@ -1155,19 +1155,23 @@ __device__ __forceinline__ void push_children(Frontier &f, int hole, Stage &sg, 
 //
 // Few chains are merged as whole sequences, one after the other (taking the best head among k
 // chains equals merging them pairwise, because (token, parent) keys are distinct).  Merging a
-// sequence X with a chain Y under "take the head with the lower (token, parent)": element x_t
-// leaves after exactly r(t) elements of Y, where r(t) is the first j >= r(t-1) at which y_j
-// does not beat x_t.  y_j beats x_t if its token is lower, or equal with the lower parent
-// index; parents are the chain predecessors, so on equal tokens y_j wins iff y_(j-1) left
-// before x_t's own predecessor x_t', i.e. iff j <= r(t') (for chain heads the given parent
-// indices decide).  One pair of ballots per x_t gives {j : y_j < x_t} and {j : y_j == x_t} as
-// lane masks and r(t) follows with a few scalar bit operations.  x_t lands at t + r(t); the
-// elements of Y fill the positions left over, in order.  At most 63 nodes are taken per call
-// (one 64-token window per chain: its head plus 63 tokens), the caller comes back for more.
-// Per-chain state lives in the lanes of vector registers (lane q: chain q).
+// chain X into the sequence Y merged so far under "take the head with the lower (token,
+// parent)": element x_t leaves after exactly r(t) elements of Y, where r(t) is the first
+// j >= r(t-1) at which y_j does not beat x_t.  y_j beats x_t if its token is lower, or equal
+// with the lower parent index; parents are the predecessors within a chain, x_t's is x_(t-1),
+// which left after r(t-1) elements of Y, so on equal tokens y_j wins iff its predecessor's
+// place in Y is below r(t-1) (the given parents of chain heads are older than every new node
+// and decide among themselves).  Three ballots per x_t give {j : y_j < x_t}, {j : y_j == x_t}
+// and the predecessors below r(t-1) as lane masks, and r(t) follows with a few scalar bit
+// operations.  The loop runs over the elements of the chain that is added, never over the
+// sequence merged so far (which is as long as all chains before together: with the roles the
+// other way round the third chain of a merge cost as much as the rest of the expansion).
+// x_t lands at t + r(t); the elements of Y fill the positions left over, in order.  At most 63
+// nodes are taken per call (one 64-token window per chain: its head plus 63 tokens), the caller
+// comes back for more.  Per-chain state lives in the lanes of vector registers (lane q: chain q).
 constexpr int TIE_MAX = 64;
 // From this many chains on the merge goes step by step over all chains at once (below); fewer
-// chains are merged as whole sequences.  4 measured best on the synthetic workloads (2, 3, 6, 10 tried).
+// chains are merged as whole sequences.  4 measured best on the synthetic workloads (2, 3, 8, 16 tried).
 constexpr int KWAY_MIN = 4;
 
 // total + s + s + ... (n times), added one by one in that order like the sequential sum of node
@@ -1373,56 +1377,39 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         const int a = bad ? __ffsll((unsigned long long)bad) - 1 : 64;
         alenv = set_lane(a, q, alenv);
         const int ly = a < room ? a : room;
-        const uint64_t ymask = ly >= 64 ? ~0ull : ((1ull << ly) - 1ull);
         const int32_t yinit = __builtin_amdgcn_readlane(cparv, q);
-        // x_t lands at t + r(t) and r never decreases: once that reaches `room` neither x_t nor
-        // anything after it is kept, and every y_j still unplaced lands at j + t >= room as
-        // well.  Lanes the loop never reached keep myr = 64 (dropped).
+        // The loop goes over the new chain X (plain: x_t's predecessor is x_(t-1)), the
+        // sequence merged so far is Y.  x_t lands at t + r(t) and r never decreases: once that
+        // reaches `room` neither x_t nor anything after it is kept, and every y_j still
+        // unplaced lands at j + t >= room as well.  Lanes the loop never reached keep myr = 64
+        // (dropped).  Equal tokens: y_j wins iff its predecessor left before x_(t-1), which
+        // left after r(t-1) elements of Y, i.e. iff that predecessor's place in Y is below
+        // r(t-1) (a head's given parent is older than every new node); for x_0 the given
+        // parents decide, and only heads of Y can win.
+        const uint64_t zmask = lz >= 64 ? ~0ull : ((1ull << lz) - 1ull);
+        const uint64_t tie0 = ballot64(zprev < 0 && zinit < yinit);
         int r = 0;
         int32_t myr = 64;
-        if (q == 1) {
-            // X is still a plain chain: x_t's predecessor is x_(t-1), which left after r(t-1)
-            // elements of Y, so among the j >= r(t-1) still in question an equal token wins
-            // only at j = r(t-1); for x_0 the given parents decide, and only y_0 can win
-            const uint64_t tie0 = yinit < __builtin_amdgcn_readlane(zinit, 0) ? 1ull : 0ull;
-            for (int t = 0; t < lz && t + r < room; t++) {  // r < 63 inside the loop
-                const int32_t xt = __builtin_amdgcn_readlane(zt, t);
-                const uint64_t lt = ballot64(yt < xt), eq = ballot64(yt == xt);
-                const uint64_t wins = (lt | (eq & (t ? 1ull << r : tie0))) & ymask;
-                const uint64_t rest = ~(wins >> r);
-                r = rest ? r + __ffsll((unsigned long long)rest) - 1 : 64;
-                myr = set_lane(r, t, myr);
-            }
-        } else
-        for (int t = 0; t < lz && t + r < room; t++) {
-            const int32_t xt = __builtin_amdgcn_readlane(zt, t);
-            uint64_t lt = ballot64(yt < xt) & ymask;
-            const uint64_t eq = ballot64(yt == xt) & ymask;
-            if (eq) {  // ties: y_j wins for j <= R
-                const int32_t tp = __builtin_amdgcn_readlane(zprev, t);
-                int R;
-                if (tp >= 0) R = __builtin_amdgcn_readlane(myr, tp);
-                else R = yinit < __builtin_amdgcn_readlane(zinit, t) ? 0 : -1;
-                const uint64_t le = R < 0 ? 0ull : (R >= 63 ? ~0ull : ((2ull << R) - 1ull));
-                lt |= eq & le;
-            }
-            if (r < 64) {
-                const uint64_t rest = ~(lt >> r);
-                r = rest ? r + __ffsll((unsigned long long)rest) - 1 : 64;
-            }
+        for (int t = 0; t < ly && t + r < room; t++) {  // r < 63 inside the loop
+            const int32_t xt = __builtin_amdgcn_readlane(yt, t);
+            const uint64_t lt = ballot64(zt < xt), eq = ballot64(zt == xt);
+            const uint64_t tie = t ? ballot64(zprev < r) : tie0;
+            const uint64_t wins = (lt | (eq & tie)) & zmask;
+            const uint64_t rest = ~(wins >> r);  // (never empty: wins has no bit from 63 on)
+            r += __ffsll((unsigned long long)rest) - 1;
             myr = set_lane(r, t, myr);
         }
         wsync();
         MM[lane] = -1;
         wsync();
-        if (lane < lz && lane + myr < 64) { TT[lane + myr] = zt; MM[lane + myr] = zm; }
+        if (lane < ly && lane + myr < 64) { TT[lane + myr] = yt; MM[lane + myr] = (q << 8) | lane; }
         wsync();
         const int32_t mt = TT[lane], mm = MM[lane];
         const bool hole = mm == -1;  // not taken by X: the holes take Y's elements in order
         const int h = __popcll(ballot64(hole) & lanemask_lt());
-        const int32_t yv = __shfl(yt, h);
-        zt = hole ? yv : mt;
-        zm = hole ? ((q << 8) | h) : mm;
+        const int32_t zv = __shfl(zt, h), zmv = __shfl(zm, h);
+        zt = hole ? zv : mt;
+        zm = hole ? zmv : mm;
         lz = lz + ly < room ? lz + ly : room;
         // predecessor links and given parents of the new sequence
         zprev = -1;
