@@ -1217,6 +1217,10 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
     const int32_t ctokv = __shfl(etok, srcl), cparv = __shfl(epar, srcl), cdepv = __shfl(edep, srcl),
                   cslotv = __shfl(mylo, srcl) - sg.lo;
     const int32_t cposv = lane < j ? sg.pos[cslotv] : 0;
+    // Where the staged windows of all these suffixes reach from their heads down to depth D,
+    // every token the merge can ask for is in LDS already and nothing is loaded.
+    const int32_t ccbv = lane < j ? sg.cb[cslotv] : 0;
+    const bool covered = !ballot64(lane < j && !(ccbv <= cdepv && ccbv + (1 << sg.wlog) >= D));
     // take the tied entries out of the frontier (the others keep their relative order)
     {
         const bool keep = have && !tie;
@@ -1251,13 +1255,21 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         uint32_t htok = chain ? (uint32_t)ctokv : DEAD;
         int32_t hpar = cparv, hdep = chain ? cdepv : 0;
         const int32_t pos0 = cposv + cdepv;  // text index of the token of the chain's element 1
-        const int base = (chain ? lane : 0) << wlog;
+        // (covered: the chain's staged window, whose token i stands at child index ccb + i)
+        const int base = covered ? (chain ? (cslotv << sg.wlog) - ccbv : 0) : (chain ? lane : 0) << wlog;
         int32_t abase = 0;
         uint32_t nexttok = DEAD, n2 = DEAD, cand = DEAD;
         // token windows: W tokens per chain from the element after its head on
         // (`need` <= W tokens per chain are fetched, rounded up to a power of two; all loads in
         // flight together)
         auto fill = [&](int need) {
+            if (covered) {  // tokens hdep, hdep + 1, ... of the staged window
+                abase = base + 1;
+                nexttok = chain ? (uint32_t)sg.tc[base + hdep] : DEAD;
+                n2 = (uint32_t)sg.tc[abase + hdep];
+                cand = hdep < D ? nexttok : DEAD;
+                return;
+            }
             wsync();
             int flog = 3;
             while ((1 << flog) < need) flog++;
@@ -1301,7 +1313,7 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         double tot = total;
         bool done = false;
         // a chain moves by at most one element per step and looks two elements ahead
-        const int burst = W - 2 < 64 ? W - 2 : 64;
+        const int burst = covered ? 64 : W - 2 < 64 ? W - 2 : 64;
         while (nn < KK && !done) {
             const int lim = KK - nn < burst ? KK - nn : burst;
             fill(lim + 2);
@@ -1340,7 +1352,7 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         // a head of depth D that was taken left its chain at depth D + 1
         if (ballot64(chain && hdep > D)) deepest = true;
         wsync();
-        if (lane < 64) sg.cb[lane] = CB_NONE;  // the staged token windows were overwritten
+        if (!covered) sg.cb[lane] = CB_NONE;  // the staged token windows were overwritten
         wsync();
         n = nn;
         total = tot;
@@ -1352,12 +1364,26 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
     int32_t alenv = 0;
     int32_t zt, zm = lane, zprev = lane - 1, zinit;
     int lz;
-    int32_t wnext = text[(int64_t)__builtin_amdgcn_readlane(cposv, 0) + __builtin_amdgcn_readlane(cdepv, 0) + lane];
-    {
+    // lane l >= 1: the token of chain q's element l (child index cdep + l - 1), from the staged
+    // window or from memory (the load for the next chain is issued before this one is used)
+    int32_t wnext = 0;
+    if (!covered)
+        wnext = text[(int64_t)__builtin_amdgcn_readlane(cposv, 0) + __builtin_amdgcn_readlane(cdepv, 0) + lane];
+    auto chain_tokens = [&](int q) -> int32_t {
+        if (covered) {
+            const int at = (__builtin_amdgcn_readlane(cslotv, q) << sg.wlog) +
+                           __builtin_amdgcn_readlane(cdepv, q) - __builtin_amdgcn_readlane(ccbv, q);
+            return sg.tc[at + (lane >= 1 ? lane - 1 : 0)];
+        }
         const int32_t w = wnext;
-        wnext = text[(int64_t)__builtin_amdgcn_readlane(cposv, 1) + __builtin_amdgcn_readlane(cdepv, 1) + lane];
+        if (q + 1 < j)
+            wnext = text[(int64_t)__builtin_amdgcn_readlane(cposv, q + 1) +
+                         __builtin_amdgcn_readlane(cdepv, q + 1) + lane];
+        return __shfl_up(w, 1);
+    };
+    {
         const int cd = __builtin_amdgcn_readlane(cdepv, 0);
-        const int32_t up = __shfl_up(w, 1);
+        const int32_t up = chain_tokens(0);
         zt = lane == 0 ? __builtin_amdgcn_readlane(ctokv, 0) : up;
         const uint64_t bad = ballot64(lane >= 1 && (up < 0 || cd + lane - 1 >= D));
         const int a = bad ? __ffsll((unsigned long long)bad) - 1 : 64;
@@ -1366,12 +1392,8 @@ __device__ __forceinline__ bool tied_chains(Frontier &f, Stage &sg, const int32_
         zinit = __builtin_amdgcn_readlane(cparv, 0);
     }
     for (int q = 1; q < j; q++) {
-        const int32_t w = wnext;
-        if (q + 1 < j)
-            wnext = text[(int64_t)__builtin_amdgcn_readlane(cposv, q + 1) +
-                         __builtin_amdgcn_readlane(cdepv, q + 1) + lane];
         const int cd = __builtin_amdgcn_readlane(cdepv, q);
-        const int32_t up = __shfl_up(w, 1);
+        const int32_t up = chain_tokens(q);
         const int32_t yt = lane == 0 ? __builtin_amdgcn_readlane(ctokv, q) : up;
         const uint64_t bad = ballot64(lane >= 1 && (up < 0 || cd + lane - 1 >= D));
         const int a = bad ? __ffsll((unsigned long long)bad) - 1 : 64;
