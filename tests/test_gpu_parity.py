@@ -1461,6 +1461,59 @@ def test_fuzz_small_configurations(chunk):
             g.close()
 
 
+@pytest.mark.parametrize("vocab,D,P,alpha,copies", [
+    (50000, 64, 32, 2.0, 3), (50000, 64, 32, 2.0, 4), (50000, 64, 32, 2.0, 6),
+    (3, 64, 32, 2.0, 3), (3, 64, 24, 2.0, 5), (7, 48, 16, 4.0, 3),
+    (50000, 200, 32, 2.0, 3), (5, 200, 32, 2.0, 4), (50000, 255, 60, 1.0, 9),
+])
+def test_tied_chain_merges(vocab, D, P, alpha, copies):
+    """Trees whose top scores tie between several single-occurrence chains: a template occurs
+    `copies` times, every copy with one token of its own a few places behind the pattern, and
+    goes on alike afterwards (equal tokens at equal offsets: the tie rule decides all along).
+    Large and tiny vocabularies, depth bounds that the staged windows reach (64) and do not
+    reach (200, 255), two to nine chains, trees cut by K and trees that end by themselves."""
+    rng = np.random.default_rng(vocab * 1000 + D + copies)
+    docs, ctxs = [], []
+    for case in range(6):
+        L = int(rng.integers(P + 8, P + 140))
+        tmpl = rng.integers(0, vocab, L).astype(np.int32)
+        head = int(rng.integers(P, P + 6))          # the pattern and a few tokens all copies share
+        for c in range(copies):
+            d = tmpl.copy()
+            at = head + int(rng.integers(0, 4)) + (c % 2)
+            if at < L:
+                d[at] = (d[at] + 1 + c) % vocab       # this copy's own token (may tie with another's)
+            cut = L if rng.random() < 0.6 else int(rng.integers(head + 1, L + 1))
+            docs.append(d[:cut])
+        pre = rng.integers(0, vocab, int(rng.integers(0, 20))).astype(np.int32)
+        ctxs.append(np.concatenate([pre, tmpl[:head - int(rng.integers(0, 5))]]).astype(np.int32))
+    B = len(ctxs)
+    N = sum(len(d) for d in docs) + len(docs)
+    g = parity.GpuPath(vocab, D, P, alpha, 0.01, B, 512, N + 4)
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), ctxs)
+        tg = oracle.Trie(D)
+        for d in docs:
+            tg.add_doc(d)
+        got = g.speculate(range(B))
+        want = parity.oracle_speculate_batch(tg, ctxs, D, P, alpha, 0.01, g.max_nodes)
+        bad = parity.compare_trees(got, want, "tied chains vocab %d D %d copies %d" % (vocab, D, copies))
+        assert not bad, "\n".join(bad)
+        # the case is what it claims to be: trees that branch into several chains
+        branching = 0
+        for b in range(B):
+            n = int(want["n_nodes"][b])
+            par = [int(v) for v in want["parents"][b, :n]]
+            kids = {}
+            for v in par:
+                kids[v] = kids.get(v, 0) + 1
+            branching += any(k >= 2 for k in kids.values())
+        assert branching >= 3, branching
+    finally:
+        g.close()
+
+
 @pytest.mark.parametrize("chunk", [0, 1, 2, 3, 460])
 def test_fuzz_fused_decode_loops(chunk):
     """50 random small configurations (10 per test), four decode steps each, every step ended by
