@@ -1919,8 +1919,45 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
     if (hi > lo) {
         f.n = 0;
         f.cap = K;
-        push_children<STATS>(f, -1, sg, sa, text, lo, hi, pl, -1, 1.0, p.min_score, p.D, p.den_mode,
-                             nb);
+        // Unary run below the node [blo, blo + m) of depth d, whose score is sc and whose place
+        // in the tree is cur (-1: the matched node itself): while all suffixes of the node agree
+        // on the next token and none has ended, the node has exactly one child, with the node's
+        // own score (count ratio 1).  Where nothing else in the frontier shares that score the
+        // greedy rule must take that child next, and so on down the run: the run is taken at
+        // once.
+        auto unary_run = [&](int32_t blo, int32_t m, int32_t &d, int &cur, double sc) {
+            const int32_t mycb = stage_node(sg, sa, text, blo, m, d);
+            const int slot0 = blo - sg.lo, W = 1 << sg.wlog;
+            const int32_t tk = m <= CHAIN_MAX_M / 2
+                                   ? common_token<CHAIN_MAX_M / 2>(sg, slot0, m, d, W, mycb)
+                                   : common_token<CHAIN_MAX_M>(sg, slot0, m, d, W, mycb);
+            int lim = K - n < p.D - d ? K - n : p.D - d;
+            uint64_t ok = __ballot(tk >= 0 && lane < lim);
+            int L = ~ok ? __ffsll((unsigned long long)~ok) - 1 : 64;
+            if (L > 0) {
+                if (lane < L) {
+                    t_tok[n + lane] = tk; t_par[n + lane] = cur + lane;
+                    t_score[n + lane] = sc;
+                    SD_CNT(8 * m);
+                }
+                total = add_times(total, sc, L);
+                cur += L;
+                n += L;
+                d += L;
+                if (d >= p.D) deepest = true;
+            }
+        };
+        // The matched node first: a narrow one whose suffixes all go on alike (the usual case: a
+        // pattern seen once or a few times) has one child of score 1, which is taken with its
+        // run without going through the frontier.
+        {
+            int32_t d = pl;
+            int cur = -1;
+            if (d < p.D && hi - lo <= CHAIN_MAX_M) unary_run(lo, hi - lo, d, cur, 1.0);
+            if (n < K)
+                push_children<STATS>(f, -1, sg, sa, text, lo, hi, d, cur, 1.0, p.min_score, p.D,
+                                     p.den_mode, nb);
+        }
         if (TICKS) tick_root = (uint32_t)(wall_clock64() - tick0) + (uint32_t)(f.n & 0);
         while (n < K && f.n > 0) {
             const Taken tk0 = frontier_take(f);
@@ -1964,34 +2001,10 @@ __device__ __forceinline__ int run_unit(const SpecParams &p, const WgShared &sh,
                 f.n = 0;
                 hole = -1;
             }
-            // Unary run: while all suffixes of the node agree on the next token and none has
-            // ended, the node has exactly one child, with the node's own score (count ratio 1).
-            // If that score is strictly above everything else in the frontier (no other entry
-            // shares the top score), the greedy rule must take that child next, and so on down
-            // the run: take the run at once.
+            // (the unary run below the node, if no other entry shares the top score)
             const int32_t m = bhi - blo;
-            if (n < K && d < p.D && m <= CHAIN_MAX_M && (ntop == 1 || p.linear)) {
-                const int32_t mycb = stage_node(sg, sa, text, blo, m, d);
-                const int slot0 = blo - sg.lo, W = 1 << sg.wlog;
-                const int32_t tk = m <= CHAIN_MAX_M / 2
-                                       ? common_token<CHAIN_MAX_M / 2>(sg, slot0, m, d, W, mycb)
-                                       : common_token<CHAIN_MAX_M>(sg, slot0, m, d, W, mycb);
-                int lim = K - n < p.D - d ? K - n : p.D - d;
-                uint64_t ok = __ballot(tk >= 0 && lane < lim);
-                int L = ~ok ? __ffsll((unsigned long long)~ok) - 1 : 64;
-                if (L > 0) {
-                    if (lane < L) {
-                        t_tok[n + lane] = tk; t_par[n + lane] = cur + lane;
-                        t_score[n + lane] = best.s;
-                        SD_CNT(8 * m);
-                    }
-                    total = add_times(total, best.s, L);
-                    cur += L;
-                    n += L;
-                    d += L;
-                    if (d >= p.D) deepest = true;
-                }
-            }
+            if (n < K && d < p.D && m <= CHAIN_MAX_M && (ntop == 1 || p.linear))
+                unary_run(blo, m, d, cur, best.s);
             if (n < K)
                 push_children<STATS>(f, hole, sg, sa, text, blo, bhi, d, cur, best.s, p.min_score,
                                      p.D, p.den_mode, nb);
