@@ -19,14 +19,33 @@ __global__ __launch_bounds__(64) void k_targets(const int32_t *__restrict__ n_no
                                                 int32_t *__restrict__ target) {
     __shared__ int32_t s_anc[256], s_dep[256];
     const int b = blockIdx.x, lane = threadIdx.x;
-    int n = n_nodes[b];
-    if (n > 256) n = 256;
     const int32_t *par = parents + (int64_t)b * max_nodes;
-    const int32_t p0 = pos[b] + (advance ? advance[b] + 1 : 0);
+    // everything that does not depend on another load is asked for at once
+    int n = n_nodes[b];
+    const int32_t pos0 = pos[b], adv = advance ? advance[b] + 1 : 0;
+    const int32_t mypar = lane < max_nodes ? par[lane] : -1;
+    if (n > 256) n = 256;
+    const int32_t p0 = pos0 + adv;
     if (advance && lane == 0) pos[b] = p0;
     const int32_t *fut = future + (int64_t)b * future_stride + p0;
     int32_t *tgt = target + (int64_t)b * (max_nodes + 1);
     const int32_t f0 = fut[0];
+    if (n <= 64) {
+        // one node per lane: depth by pointer jumping over the parent links (a link must lead
+        // to a lower index), links and depths in registers, log2(depth) rounds
+        int32_t anc = (lane < n && mypar >= 0 && mypar < lane) ? mypar : -1, dep = lane < n ? 1 : 0;
+        for (int round = 0; round < 6; round++) {
+            if (!__ballot(anc >= 0)) break;
+            const int src = anc >= 0 ? anc : lane;
+            const int32_t da = __shfl(dep, src), aa = __shfl(anc, src);
+            if (anc >= 0) { dep += da; anc = aa; }
+        }
+        const int32_t v = lane < n ? fut[dep] : f0;
+        if (lane == 0) tgt[0] = f0;
+        if (lane < max_nodes) tgt[1 + lane] = v;
+        for (int j = 64 + lane; j < max_nodes; j += 64) tgt[1 + j] = f0;
+        return;
+    }
     // depth of every node by pointer jumping over the parent links (a link must lead to a
     // lower index): log2(depth) rounds instead of a walk of `depth` dependent steps
     for (int j = lane; j < n; j += 64) {
