@@ -195,7 +195,7 @@ __device__ __forceinline__ uint64_t occ_key(const SpecParams &p, const int32_t *
 template <bool STATS>
 __device__ __forceinline__ void occ_sort_runs(int2 rec, uint64_t key, int m, int2 *s_rec, uint64_t *s_key,
                                               int *s_flag, const int32_t *__restrict__ x, int depth,
-                                              unsigned &nb) {
+                                              unsigned &nb, bool presorted = false) {
     const int i = threadIdx.x, lane = i & 63, w0 = i & ~63;  // w0: where this wave's run starts
     const bool busy = w0 < m;                                // (the same for all lanes of a wave)
     if (m <= 64) {
@@ -227,7 +227,7 @@ __device__ __forceinline__ void occ_sort_runs(int2 rec, uint64_t key, int m, int
         }
         return;
     }
-    if (busy) {
+    if (busy && !presorted) {
         for (int k = 2; k <= 64; k <<= 1) {
             for (int j = k >> 1; j > 0; j >>= 1) {
                 const int src = lane ^ (j == (k >> 1) ? k - 1 : j);
@@ -356,6 +356,9 @@ struct WgShared {
     int sort_flag;   // scratch of the occurrence sort
     unsigned long long ctr[SD_CTR_ACCEPT_REQUESTS];  // the request's drafting counters, on their way through the launch
     int n_surv;      // occurrences whose left-extension the one-token check did not settle
+    int scan_done;   // waves that have put down the hits of their part of the context scan
+    int chunk_next;  // frequent last token: the next 64 occurrences nobody has taken yet
+    int early;       // the occurrences were dealt with in such parts before the barrier
     unsigned long long top_bits;  // highest SCORE of a finished tree so far (bits of the double)
     int t_new;       // context length after the append of the fused form
     int newtok[260]; // fused form: the tokens appended in this launch
@@ -390,7 +393,7 @@ template <bool STATS>
 __device__ __forceinline__ void occ_scan_issue(int t_old, const int32_t *__restrict__ x, WgShared &sh,
                                                ScanState &st, unsigned &nb) {
     const int tid = threadIdx.x, nthr = blockDim.x;
-    if (tid == 0) { sh.m = 0; sh.next = 0; sh.top_bits = 0; sh.n_surv = 0; }
+    if (tid == 0) { sh.m = 0; sh.next = 0; sh.top_bits = 0; sh.n_surv = 0; sh.scan_done = 0; sh.chunk_next = 0; sh.early = 0; }
     if (tid < 72) { sh.cnt[tid] = 0; sh.gcnt[tid] = 0; }
     // Coalesced scan, 16 bytes per load, four loads in flight per thread; rows start 256-byte
     // aligned.
@@ -466,7 +469,126 @@ __device__ __attribute__((noinline)) unsigned left_extensions_many(int m, int t,
     return nb;
 }
 
-template <bool STATS, class Between>
+// Frequent last token, occurrences [64 c, 64 c + 64) of the list in LDS on one wave: their
+// left-extensions (most differ from the context's tail in the very next token to the left,
+// which one load per occurrence settles; the rest is compared token by token, PP lanes per
+// occurrence), their sort keys, and the wave's 64-element network, which leaves records and
+// keys as a sorted run in place.  No barrier: a wave takes such a part whenever it is free,
+// while others are still searching the global index.
+template <bool STATS>
+__device__ __forceinline__ unsigned occ_chunk(int c, int m, int t, int P, int depth,
+                                                         int key_toks, int key_bits, double alpha,
+                                                         int32_t tail, const int32_t *__restrict__ x,
+                                                         int2 *s_sort, uint64_t *s_key, WgShared &sh) {
+    unsigned nb = 0;
+    const int lane = threadIdx.x & 63;
+    const int i = c * 64 + lane;
+    const bool on = i < m;
+    const int e = on ? s_sort[i].x : -1;
+    const int lim = e + 1 < P ? e + 1 : P;
+    const int32_t tl1 = __builtin_amdgcn_readlane(tail, 1);
+    const bool rd = on && e != t - 1 && lim > 1;
+    const int32_t vv = rd ? x[e - 1] : tl1;
+    if (rd) SD_CNT(8);
+    // the tokens behind the occurrence, for its key (rows are padded with end markers)
+    const int kt = key_toks < depth ? key_toks : depth;
+    const uint64_t t1 = on ? (uint64_t)(uint32_t)(x[e + 1] + 1) : 0ull;
+    const uint64_t t2 = on && kt >= 2 ? (uint64_t)(uint32_t)(x[e + 2] + 1) : 0ull;
+    const uint64_t t3 = on && kt >= 3 ? (uint64_t)(uint32_t)(x[e + 3] + 1) : 0ull;
+    if (on) SD_CNT(4 * kt);
+    const bool one = on && (lim <= 1 || (rd && vv != tl1));  // left-extension 1
+    uint64_t sm = __ballot(on && !one);
+    int pplog = 0;
+    while ((1 << pplog) < P) pplog++;
+    const int PP = 1 << pplog, G = 64 >> pplog, g = lane >> pplog, k = lane & (PP - 1);
+    const uint64_t gmask = PP >= 64 ? ~0ull : ((1ull << PP) - 1ull);
+    const int32_t tl = __shfl(tail, k);
+    while (sm) {  // G of the others per trip, PP lanes each
+        int src = -1;
+        for (int q = 0; q < G && sm; q++) {
+            const int l = __ffsll((unsigned long long)sm) - 1;
+            sm &= sm - 1;
+            if (g == q) src = l;
+        }
+        const int es = __shfl(e, src >= 0 ? src : lane);
+        const int ee = src >= 0 ? es : -1;
+        const int lims = ee + 1 < P ? ee + 1 : P;  // (0 for an empty place)
+        const bool rdk = ee >= 0 && ee != t - 1 && k < lims;
+        const int32_t v = rdk ? x[ee - k] : tl;
+        if (rdk) SD_CNT(8);
+        const uint64_t mis = __ballot(k >= 1 && k < lims && v != tl);
+        const uint64_t gm = (mis >> (g << pplog)) & gmask;
+        const int l = gm ? __ffsll((unsigned long long)gm) - 1 : lims;
+        if (k == 0 && ee >= 0) {
+            s_sort[c * 64 + src].y = l;
+            SD_CNT(8);
+        }
+    }
+    wsync();
+    const int L = one ? 1 : (on ? s_sort[i].y : 0);
+    if (on) atomicAdd(&sh.cnt[L], 1);
+    int2 rec = make_int2(e, L);
+    uint64_t key = ~0ull;
+    if (on) {
+        const uint64_t more = floor(alpha * (double)L) > (double)key_toks ? 1ull : 0ull;
+        key = key_toks == 3 ? (t1 << (2 * key_bits + 1)) | (t2 << (key_bits + 1)) | (t3 << 1) | more
+                            : (t1 << (key_bits + 1)) | (t2 << 1) | more;
+    }
+    for (int kk = 2; kk <= 64; kk <<= 1) {
+        for (int j = kk >> 1; j > 0; j >>= 1) {
+            const int src = lane ^ (j == (kk >> 1) ? kk - 1 : j);
+            int2 orec;
+            orec.x = __shfl(rec.x, src);
+            orec.y = __shfl(rec.y, src);
+            const uint32_t klo = (uint32_t)__shfl((int)(uint32_t)key, src);
+            const uint32_t khi = (uint32_t)__shfl((int)(uint32_t)(key >> 32), src);
+            const uint64_t okey = ((uint64_t)khi << 32) | klo;
+            // both partners look at the same ordered pair: the lower place keeps the lower key
+            const bool take = src > lane ? okey < key : key < okey;
+            if (take) { rec = orec; key = okey; }
+        }
+    }
+    wsync();
+    s_sort[i] = rec;  // (within the room of the list's 64-entry parts: the LDS holds whole parts)
+    s_key[i] = key;
+    return nb;
+}
+
+// What a wave does with a frequent last token once its own search in the global index is over
+// (per-pattern route only, where the waves' searches take unequal times): it waits until every
+// wave's hits are down (each wave has counted itself in before it waits for anything, so the
+// wait ends; it is over long before a wave gets here), and if the list is of the kind that
+// request_occurrences sorts with one element per thread, it takes parts of 64 occurrences
+// until none is left: left-extensions, keys and the per-wave part of the sort then do not wait
+// behind the workgroup's barrier for the slowest search.  Out of line: the route is rare and is
+// kept from weighing on the registers and the code layout of the usual one.
+template <bool STATS>
+__device__ __attribute__((noinline)) unsigned occ_take_chunks(int nw, int t, int P, int depth, int occ_cap,
+                                                               int key_toks, int key_bits, double alpha,
+                                                               int32_t tail, const int32_t *__restrict__ x,
+                                                               int2 *s_sort, WgShared &sh) {
+    unsigned nb = 0;
+    const int lane = threadIdx.x & 63;
+    while (__hip_atomic_load(&sh.scan_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < nw)
+        __builtin_amdgcn_s_sleep(1);
+    wsync();
+    const int m_all = __hip_atomic_load(&sh.m, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    int pplog = 0;
+    while ((1 << pplog) < P) pplog++;
+    if (!(m_all > nw * (64 >> pplog) * 4 && m_all <= occ_cap && m_all <= nw * 64)) return 0;
+    uint64_t *s_key = reinterpret_cast<uint64_t *>(s_sort + occ_cap);
+    if (lane == 0) sh.early = 1;  // (every wave that gets here writes the same)
+    for (;;) {
+        int c = 0;
+        if (lane == 0) c = atomicAdd(&sh.chunk_next, 1);
+        c = uni(c);
+        if (c * 64 >= m_all) break;
+        nb += occ_chunk<STATS>(c, m_all, t, P, depth, key_toks, key_bits, alpha, tail, x, s_sort, s_key, sh);
+    }
+    return nb;
+}
+
+template <bool STATS, bool EARLY, class Between>
 __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, int t, int t_old,
                                     const int32_t *newtok, const int32_t *__restrict__ x,
                                     int2 *s_sort, WgShared &sh, ScanState &st, int32_t tail,
@@ -536,9 +658,19 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
             }
         }
     }
+    // (this wave's hits are down: the count below says when every wave's are.  The hits and
+    // the count are LDS operations of one wave, which the LDS takes in the order they were
+    // issued: the compiler must keep that order, nothing has to be waited for.)
+    if (EARLY) {
+        wsync();
+        if (lane == 0) atomicAdd(&sh.scan_done, 1);
+    }
     between();
     __syncthreads();
     const int m = sh.m;
+    // (a frequent last token's occurrences may have been dealt with already, in parts of 64 by
+    // the waves that came out of the caller's work early: see occ_take_chunks)
+    const bool early = EARLY && uni(sh.early) != 0;
     // A single occurrence is the context's own last token: nothing follows it, so no pattern
     // has a continuation in this index, and the counts stay at zero, which says just that.
     if (__builtin_expect(m <= 1, 1)) return;
@@ -555,7 +687,9 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
         const uint64_t gmask = PP >= 64 ? ~0ull : ((1ull << PP) - 1ull);
         const int32_t tl = __shfl(tail, k);  // the k-th token from the context's end (0 beyond it)
         constexpr int U = 4;
-        if (__builtin_expect(in_lds && m > nw * G * U, 0)) {
+        if (early) {
+            // (done already, see above)
+        } else if (__builtin_expect(in_lds && m > nw * G * U, 0)) {
             // (the room of the sort keys, free until the sort, takes the list)
             const unsigned cnt_many = left_extensions_many<STATS>(
                 m, t, p.P, tail, x, s_sort, reinterpret_cast<int32_t *>(s_sort + occ_cap), sh);
@@ -622,11 +756,13 @@ __device__ __forceinline__ void request_occurrences(const SpecParams &p, int b, 
                 if (m <= nthr) {  // one element per thread
                     int2 rec = make_int2(0, 0);
                     uint64_t kk = ~0ull;
-                    if (tid < m) {
+                    if (early) {  // the runs of 64 are sorted already, keys beside them
+                        if ((tid & ~63) < m) { rec = s_sort[tid]; kk = key[tid]; }
+                    } else if (tid < m) {
                         rec = s_sort[tid];
                         kk = occ_key<STATS>(p, x, rec, depth, nb);
                     }
-                    occ_sort_runs<STATS>(rec, kk, m, s_sort, key, &sh.sort_flag, x, depth, nb);
+                    occ_sort_runs<STATS>(rec, kk, m, s_sort, key, &sh.sort_flag, x, depth, nb, early);
                 } else {
                     for (int i = tid; i < m; i += nthr) key[i] = occ_key<STATS>(p, x, s_sort[i], depth, nb);
                     __syncthreads();
@@ -2342,7 +2478,7 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
     // (the counters wait in LDS for the end of the launch: two registers less to carry through
     // matching and expansion; the load is older than the tail's, which has just been waited for)
     if (wave == nw - 1 && lane < SD_CTR_ACCEPT_REQUESTS) sh.ctr[lane] = ctr_old;
-    request_occurrences<STATS>(p, b, t, t_old, sh.newtok, x, s_sort, sh, scan, tail, nb, [&]() {
+    request_occurrences<STATS, ACCEPT>(p, b, t, t_old, sh.newtok, x, s_sort, sh, scan, tail, nb, [&]() {
         // List form: the suffixes that start with the context's last two tokens are located
         // once (every wave does that for itself: same loads, no barrier).  If there are at
         // most 64 of them, every longer pattern's occurrences are among them: the waves share
@@ -2428,6 +2564,15 @@ __global__ __launch_bounds__(1024) __attribute__((amdgpu_waves_per_eu(6))) void 
                 sh.g_lo[plA] = loA; sh.g_hi[plA] = hiA;
                 if (plB <= P) { sh.g_lo[plB] = loB; sh.g_hi[plB] = hiB; }
             }
+        }
+        // (a frequent last token: the waves that are done with their searches early take the
+        // left-extensions and the per-wave part of the occurrence sort meanwhile)
+        // (in the decode step's form of the kernel; the form without the acceptance has no
+        // register left for the call)
+        if (ACCEPT) {
+            const unsigned cnt_chunks = occ_take_chunks<STATS>(nw, t, P, p.D - 1, p.occ_cap, p.key_toks,
+                                                               p.key_bits, p.alpha, tail, x, s_sort, sh);
+            SD_CNT(cnt_chunks);
         }
     });
     const uint64_t wg1 = TICKS ? wall_clock64() : 0;
