@@ -133,3 +133,64 @@ def test_long_lists_on_thin_workgroups():
         assert st["spec_list_rounds"] >= 1
     finally:
         g.close()
+
+
+@pytest.mark.parametrize("B", [5, 700, 2600])
+def test_frequent_last_token_in_the_fused_step(B):
+    """The decode step's kernel with last tokens that occur some hundred times in their contexts
+    and a global index that sends every pattern length on a search of its own: the waves that
+    are done with their searches first take the occurrences in parts of 64 before the barrier.
+    One workgroup per compute unit (16 waves) and several (8 to 4 waves), where a part of the
+    lists is too long for that route and takes the other one."""
+    rng = np.random.default_rng(43 + B)
+    vocab, D, P, alpha, ms = 6, 20, 8, 2.0, 0.02
+    docs = [rng.integers(0, vocab, 4000).astype(np.int32) for _ in range(3)]
+    lens = (70, 300, 700, 1200, 2000)
+    distinct = [rng.integers(0, vocab, n).astype(np.int32) for n in lens]
+    contexts = [distinct[b % len(distinct)] for b in range(B)]
+    mn = int(np.floor(alpha * P))
+    g = parity.GpuPath(vocab, D, P, alpha, ms, B, max(lens) + mn + 1,
+                       sum(len(d) for d in docs) + len(docs))
+    try:
+        g.build_global(docs)
+        g.build_requests(range(B), contexts)
+        st0 = g.stats()
+        got = g.speculate(range(B))
+        tg = parity.oracle_global_trie(docs, D, vocab)
+        tries = []
+        for x in distinct:
+            tr = oracle.Trie(D)
+            tr.append(x)
+            tries.append(tr)
+        want_d = parity.oracle_speculate_batch(tg, distinct, D, P, alpha, ms, mn, request_tries=tries)
+        pick = np.arange(B) % len(distinct)
+        want = {k: v[pick] for k, v in want_d.items()}
+        bad = parity.compare_trees(got, want, "frequent last token, first drafts")
+        assert not bad, "\n".join(bad)
+        st1 = g.stats()
+        assert st1["spec_global_search"] - st0["spec_global_search"] == B   # no list form here
+        fut = rng.integers(0, vocab, (len(distinct), mn + 2)).astype(np.int32)
+        for d in range(0, len(distinct), 2):     # the verifier agrees with some first draft tokens
+            if want_d["n_nodes"][d] > 0:
+                fut[d, 0] = want_d["tokens"][d, 0]
+        tgt_d = parity.targets_from_future(want_d, fut, mn)
+        al, ap, bo, nxt = g.accept_append_speculate(range(B), tgt_d[pick])
+        ext = []
+        for d in range(len(distinct)):
+            k = int(want_d["n_nodes"][d])
+            L, path, bonus = oracle.accept(want_d["tokens"][d, :k], want_d["parents"][d, :k], tgt_d[d])
+            assert np.all(al[pick == d] == L) and np.all(bo[pick == d] == bonus)
+            new = np.array([int(want_d["tokens"][d, j]) for j in path] + [int(bonus)], np.int32)
+            tries[d].append(new)
+            ext.append(np.concatenate([distinct[d], new]))
+        want2_d = parity.oracle_speculate_batch(tg, ext, D, P, alpha, ms, mn, request_tries=tries)
+        want2 = {k: v[pick] for k, v in want2_d.items()}
+        bad = parity.compare_trees(nxt, want2, "frequent last token, next drafts")
+        assert not bad, "\n".join(bad)
+        # the lists are of the lengths meant: from a dozen to some hundred occurrences
+        occ = [int(np.sum(x == x[-1])) for x in ext]
+        assert min(occ) < 64 and max(occ) > 256, occ
+        st = g.stats()
+        assert st["err_bad_token"] == 0 and st["err_bad_slot"] == 0 and st["err_ctx_overflow"] == 0
+    finally:
+        g.close()
