@@ -384,6 +384,9 @@ struct WgShared {
 // of which those from t_old on (appended meanwhile by the first wave) are taken from `newtok`
 // in LDS.  `between` is independent work of the caller (the global matches), run after this
 // wave has dealt with its part of the scan, while other waves may still be at it.
+// With EARLY every wave counts itself in (scan_done) once its hits are down, and `between` may
+// call occ_take_chunks, which then deals with a frequent last token's occurrences before the
+// barrier and says so in `early`.
 struct ScanState {
     int4 v[4];         // the first round of scan loads
     int32_t last_old;  // token t_old - 1
