@@ -46,6 +46,8 @@ __global__ __launch_bounds__(TB) void k_len_pos(const int32_t *__restrict__ text
     if (base + lane < N) lenpos[base + lane] = (uint8_t)k;
 }
 
+typedef int32_t tok4 __attribute__((ext_vector_type(4), aligned(4)));
+
 __global__ __launch_bounds__(TB) void k_lcp_len(const int32_t *__restrict__ text,
                                                 const int32_t *__restrict__ sa,
                                                 const uint8_t *__restrict__ lenpos, int64_t N,
@@ -57,8 +59,26 @@ __global__ __launch_bounds__(TB) void k_lcp_len(const int32_t *__restrict__ text
     int k = 0;
     if (i > 0) {
         // the neighbour's end marker differs from every token of w: no bound of its own needed
+        // (four tokens of either suffix per step, loaded as one 16-byte word at 4-byte
+        // alignment; what lies behind a suffix's end is text or padding and is not looked at)
         const int32_t *w = text + p, *v = text + sa[i - 1];
-        while (k < L && w[k] == v[k]) k++;
+        while (k < L) {
+            const tok4 a = *reinterpret_cast<const tok4 *>(w + k), b = *reinterpret_cast<const tok4 *>(v + k);
+            const int left = L - k;
+            int same = 0;
+            if (a.x == b.x) {
+                same = 1;
+                if (left > 1 && a.y == b.y) {
+                    same = 2;
+                    if (left > 2 && a.z == b.z) {
+                        same = 3;
+                        if (left > 3 && a.w == b.w) same = 4;
+                    }
+                }
+            }
+            k += same;
+            if (same < 4) break;
+        }
     }
     lcp[i] = (uint8_t)k;
     len[i] = (uint8_t)L;
